@@ -1,0 +1,288 @@
+"""ctypes/numpy access to the CPU oracle (oracle/q8t_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests, the smoke check and the benchmark's
+cpu-baseline leg.  The product package never imports this module and this module
+never imports the product package.  It holds argument marshalling only; every
+piece of arithmetic lives in the C file.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "q8t_oracle.c")
+_LIB = os.path.join(_HERE, "libq8t_oracle.so")
+
+
+class QParams(C.Structure):
+    _fields_ = [("vmin", C.c_float), ("vmax", C.c_float), ("scale", C.c_float),
+                ("inv_scale", C.c_float), ("zero_point", C.c_int32), ("bits", C.c_int32)]
+
+    def as_tuple(self):
+        return (self.vmin, self.vmax, self.scale, self.inv_scale, self.zero_point, self.bits)
+
+    def __repr__(self):
+        return "QParams(vmin=%r, vmax=%r, scale=%r, inv_scale=%r, zp=%d, bits=%d)" % self.as_tuple()
+
+
+class ConvDesc(C.Structure):
+    _fields_ = [(k, C.c_int) for k in ("N", "C", "H", "W", "K", "R", "S", "stride", "pad")]
+
+    @property
+    def P(self):
+        return (self.H + 2 * self.pad - self.R) // self.stride + 1
+
+    @property
+    def Q(self):
+        return (self.W + 2 * self.pad - self.S) // self.stride + 1
+
+
+def build(force=False):
+    """Compile the oracle with gcc (plain C, OpenMP on outer loops, no FMA contraction)."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    cmd = ["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared", "-fPIC",
+           "-o", _LIB, _SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB)
+        _lib.orc_range_bn_scale.restype = C.c_double
+        _lib.orc_range_bn_scale.argtypes = [C.c_int64]
+        _lib.orc_r16.restype = C.c_uint32
+        _lib.orc_r16.argtypes = [C.c_uint64, C.c_uint64]
+        _lib.orc_rng_words.argtypes = [C.c_uint64, C.c_uint64, C.POINTER(C.c_uint32),
+                                       C.POINTER(C.c_uint32)]
+        _lib.orc_num_threads.restype = C.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def num_threads():
+    return int(lib().orc_num_threads())
+
+
+def range_bn_scale(n):
+    return float(lib().orc_range_bn_scale(int(n)))
+
+
+def r16(i, seed):
+    return int(lib().orc_r16(C.c_uint64(int(i)), C.c_uint64(int(seed))))
+
+
+def rng_words(g, seed):
+    w0, w1 = C.c_uint32(), C.c_uint32()
+    lib().orc_rng_words(C.c_uint64(int(g)), C.c_uint64(int(seed)), C.byref(w0), C.byref(w1))
+    return w0.value, w1.value
+
+
+def minmax(x):
+    x = _f32(x).ravel()
+    mn, mx = C.c_float(), C.c_float()
+    lib().orc_minmax(_p(x), C.c_int64(x.size), C.byref(mn), C.byref(mx))
+    return np.float32(mn.value), np.float32(mx.value)
+
+
+def qparams_from_range(vmin, vmax, bits):
+    qp = QParams()
+    lib().orc_qparams_from_range(C.c_float(vmin), C.c_float(vmax), C.c_int(bits), C.byref(qp))
+    return qp
+
+
+def _stored_dtype(bits):
+    return np.int8 if bits <= 8 else np.int16
+
+
+def quantize(x, bits=8, stochastic=False, seed=0, vrange=None):
+    """Returns (stored codes, levels int32, QParams), shaped like x."""
+    x = _f32(x)
+    n = x.size
+    levels = np.empty(x.shape, dtype=np.int32)
+    stored = np.empty(x.shape, dtype=_stored_dtype(bits))
+    qp = QParams()
+    if vrange is None:
+        lib().orc_quantize(_p(x), C.c_int64(n), C.c_int(bits), C.c_int(int(stochastic)),
+                           C.c_uint64(int(seed)), _p(levels), _p(stored), C.byref(qp))
+    else:
+        lib().orc_quantize_with_range(_p(x), C.c_int64(n), C.c_int(bits), C.c_int(int(stochastic)),
+                                      C.c_uint64(int(seed)), C.c_float(vrange[0]),
+                                      C.c_float(vrange[1]), _p(levels), _p(stored), C.byref(qp))
+    return stored, levels, qp
+
+
+def dequantize(stored, qp):
+    stored = np.ascontiguousarray(stored, dtype=_stored_dtype(qp.bits))
+    out = np.empty(stored.shape, dtype=np.float32)
+    lib().orc_dequantize(_p(stored), C.byref(qp), C.c_int64(stored.size), _p(out))
+    return out
+
+
+def _i8(a):
+    return np.ascontiguousarray(a, dtype=np.int8)
+
+
+def _i16(a):
+    return np.ascontiguousarray(a, dtype=np.int16)
+
+
+def qgemm_fwd(qx, px, qw, pw):
+    qx, qw = _i8(qx), _i8(qw)
+    M, K = qx.shape
+    K2, N = qw.shape
+    assert K == K2
+    y = np.empty((M, N), np.float32)
+    acc = np.empty((M, N), np.int64)
+    lib().orc_qgemm_fwd(_p(qx), C.byref(px), _p(qw), C.byref(pw), M, N, K, _p(y), _p(acc))
+    return y, acc
+
+
+def qgemm_dgrad(qdy, pg, qw, pw):
+    qdy, qw = _i8(qdy), _i8(qw)
+    M, N = qdy.shape
+    K, N2 = qw.shape
+    assert N == N2
+    dx = np.empty((M, K), np.float32)
+    acc = np.empty((M, K), np.int64)
+    lib().orc_qgemm_dgrad(_p(qdy), C.byref(pg), _p(qw), C.byref(pw), M, N, K, _p(dx), _p(acc))
+    return dx, acc
+
+
+def qgemm_wgrad(qx, px, qdy16, pg):
+    qx, qdy16 = _i8(qx), _i16(qdy16)
+    M, K = qx.shape
+    M2, N = qdy16.shape
+    assert M == M2
+    dw = np.empty((K, N), np.float32)
+    acc = np.empty((K, N), np.int64)
+    lib().orc_qgemm_wgrad(_p(qx), C.byref(px), _p(qdy16), C.byref(pg), M, N, K, _p(dw), _p(acc))
+    return dw, acc
+
+
+def conv_desc(N, Cin, H, W, K, R, S, stride, pad):
+    return ConvDesc(N, Cin, H, W, K, R, S, stride, pad)
+
+
+def qconv_fwd(d, qx, px, qw, pw):
+    qx, qw = _i8(qx), _i8(qw)
+    assert qx.shape == (d.N, d.C, d.H, d.W) and qw.shape == (d.K, d.C, d.R, d.S)
+    shape = (d.N, d.K, d.P, d.Q)
+    y = np.empty(shape, np.float32)
+    acc = np.empty(shape, np.int64)
+    lib().orc_qconv_fwd(C.byref(d), _p(qx), C.byref(px), _p(qw), C.byref(pw), _p(y), _p(acc))
+    return y, acc
+
+
+def qconv_dgrad(d, qdy, pg, qw, pw):
+    qdy, qw = _i8(qdy), _i8(qw)
+    assert qdy.shape == (d.N, d.K, d.P, d.Q) and qw.shape == (d.K, d.C, d.R, d.S)
+    shape = (d.N, d.C, d.H, d.W)
+    dx = np.empty(shape, np.float32)
+    acc = np.empty(shape, np.int64)
+    lib().orc_qconv_dgrad(C.byref(d), _p(qdy), C.byref(pg), _p(qw), C.byref(pw), _p(dx), _p(acc))
+    return dx, acc
+
+
+def qconv_wgrad(d, qx, px, qdy16, pg):
+    qx, qdy16 = _i8(qx), _i16(qdy16)
+    assert qx.shape == (d.N, d.C, d.H, d.W) and qdy16.shape == (d.N, d.K, d.P, d.Q)
+    shape = (d.K, d.C, d.R, d.S)
+    dw = np.empty(shape, np.float32)
+    acc = np.empty(shape, np.int64)
+    lib().orc_qconv_wgrad(C.byref(d), _p(qx), C.byref(px), _p(qdy16), C.byref(pg), _p(dw), _p(acc))
+    return dw, acc
+
+
+def _opt_f32(a):
+    return None if a is None else _f32(a)
+
+
+def range_bn_stats(x):
+    x = _f32(x)
+    N, Cc, H, W = x.shape
+    stats = np.empty((3, Cc), np.float32)
+    lib().orc_range_bn_stats(_p(x), N, Cc, H, W, _p(stats))
+    return stats
+
+
+def range_bn_fwd(x, gamma=None, beta=None, eps=0.0, stats=None, quantized=False):
+    """Returns (y, stats[3,C], q_stored or None, QParams or None).
+    With `stats` given, only the elementwise stage runs (on those statistics)."""
+    x = _f32(x)
+    N, Cc, H, W = x.shape
+    gamma, beta = _opt_f32(gamma), _opt_f32(beta)
+    y = np.empty(x.shape, np.float32)
+    q = np.empty(x.shape, np.int8) if quantized else None
+    qp = QParams()
+    if stats is None:
+        stats = np.empty((3, Cc), np.float32)
+        lib().orc_range_bn_fwd(_p(x), N, Cc, H, W, _p(gamma), _p(beta), C.c_float(eps), _p(y),
+                               _p(stats), _p(q), C.byref(qp))
+    else:
+        stats = _f32(stats)
+        lib().orc_range_bn_fwd_apply(_p(x), N, Cc, H, W, _p(gamma), _p(beta), C.c_float(eps),
+                                     _p(stats), _p(y), _p(q), C.byref(qp))
+    return y, stats, q, (qp if quantized else None)
+
+
+def range_bn_bwd_sums(x, dy, stats, eps=0.0):
+    x, dy, stats = _f32(x), _f32(dy), _f32(stats)
+    N, Cc, H, W = x.shape
+    sums = np.empty((2, Cc), np.float64)
+    lib().orc_range_bn_bwd_sums(_p(x), _p(dy), _p(stats), N, Cc, H, W, C.c_float(eps), _p(sums))
+    return sums
+
+
+def range_bn_bwd(x, dy, stats, gamma=None, eps=0.0, sums=None):
+    """Returns (dx, dgamma, dbeta).  With `sums` given ([2,C] float64: sum dy,
+    sum dy*xhat) only the elementwise stage runs."""
+    x, dy, stats = _f32(x), _f32(dy), _f32(stats)
+    N, Cc, H, W = x.shape
+    gamma = _opt_f32(gamma)
+    dx = np.empty(x.shape, np.float32)
+    dgamma = np.empty(Cc, np.float32)
+    dbeta = np.empty(Cc, np.float32)
+    if sums is None:
+        lib().orc_range_bn_bwd(_p(x), _p(dy), _p(stats), N, Cc, H, W, _p(gamma), C.c_float(eps),
+                               _p(dx), _p(dgamma), _p(dbeta))
+    else:
+        sums = np.ascontiguousarray(sums, dtype=np.float64)
+        lib().orc_range_bn_bwd_apply(_p(x), _p(dy), _p(stats), _p(sums), N, Cc, H, W, _p(gamma),
+                                     C.c_float(eps), _p(dx), _p(dgamma), _p(dbeta))
+    return dx, dgamma, dbeta
+
+
+def range_bn_fwd_f64(x, gamma=None, beta=None, eps=0.0):
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    N, Cc, H, W = x.shape
+    g = None if gamma is None else np.ascontiguousarray(gamma, dtype=np.float64)
+    b = None if beta is None else np.ascontiguousarray(beta, dtype=np.float64)
+    y = np.empty(x.shape, np.float64)
+    lib().orc_range_bn_fwd_f64(_p(x), N, Cc, H, W, _p(g), _p(b), C.c_double(eps), _p(y))
+    return y
+
+
+def standard_bn_f64(x):
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    N, Cc, H, W = x.shape
+    y = np.empty(x.shape, np.float64)
+    lib().orc_standard_bn_f64(_p(x), N, Cc, H, W, _p(y))
+    return y
