@@ -1,0 +1,167 @@
+/*
+ * q8t.h -- C ABI of libq8t: the quantized back-propagation step of a conv/FC layer plus
+ * Range Batch-Norm, as hand-written HIP kernels for gfx950 (MI355X).
+ *
+ * Method: "Scalable Methods for 8-bit Training of Neural Networks" (Banner, Hubara, Hoffer,
+ * Soudry).  Each entry point cites the passage that defines its operation.
+ *
+ * Conventions (all entry points)
+ *  - Every pointer is a DEVICE pointer unless the comment says "host".  The caller owns every
+ *    buffer, including the workspace `ws` (size from the matching *_workspace_size query, 256-byte
+ *    aligned; contents on entry are irrelevant, contents on return are unspecified).
+ *  - The library allocates nothing, keeps no global state and never synchronizes the host: all
+ *    work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *  - Float tensors are contiguous NCHW (conv / Range BN) or row-major (FC).
+ *  - Quantized payloads are SIGNED: an M-bit level q in [0, 2^M-1] is stored as q - 2^(M-1),
+ *    int8 for M <= 8 and int16 for 8 < M <= 16, in the same logical layout as the float source.
+ *  - Return value: Q8T_OK or a negative error code.  Shapes, bit widths and pointers are checked
+ *    on the host before anything is launched; on error nothing has been enqueued.
+ */
+#ifndef Q8T_H
+#define Q8T_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    Q8T_OK = 0,
+    Q8T_ERR_NULL = -1,      /* a required pointer is NULL */
+    Q8T_ERR_SHAPE = -2,     /* a dimension is <= 0 or beyond what index arithmetic supports */
+    Q8T_ERR_BITS = -3,      /* bit width outside [2,16] (or not 8 / 16 where fixed) */
+    Q8T_ERR_OVERFLOW = -4,  /* reduction length too large for the 32-bit accumulator contract */
+    Q8T_ERR_WORKSPACE = -5, /* ws is NULL or misaligned although the call needs one */
+    Q8T_ERR_HIP = -6        /* a launch was rejected by the runtime */
+};
+
+/* Affine quantization parameters (Appendix B).  Device-resident: written by the quantize calls,
+ * read by the product calls, never touched by the host inside the library.
+ *   real value = scale * (level - zero_point),  level = stored + 2^(bits-1).                  */
+typedef struct {
+    float vmin, vmax;      /* clamping range after it was widened to contain 0 */
+    float scale;           /* (vmax - vmin) / (2^bits - 1); 1 for an all-zero tensor */
+    float inv_scale;       /* fl32(1 / scale) */
+    int32_t zero_point;    /* level of the real value 0, in [0, 2^bits - 1] */
+    int32_t bits;
+} q8t_qparams;
+
+/* Convolution geometry: input [N,C,H,W], filter [K,C,R,S], output [N,K,P,Q] with
+ * P = (H + 2*pad - R)/stride + 1 (Q likewise); zero padding, no bias, no dilation, no groups. */
+typedef struct {
+    int N, C, H, W, K, R, S, stride, pad;
+} q8t_conv_desc;
+
+/* ---------------------------------------------------------------------------------------------
+ * Quantization (Appendix B; Section 4 "Quantization methods").
+ *
+ *   vmin = min(min_i x_i, 0), vmax = max(max_i x_i, 0)
+ *   scale = (vmax - vmin)/(2^M - 1), zero_point = round(-vmin/scale) clamped to [0, 2^M - 1]
+ *   level_i = clamp(round(x_i * inv_scale + zero_point), 0, 2^M - 1)
+ * evaluated in fp32 with one rounding per operation (no fused multiply-add); round is
+ * round-half-to-even.  With stochastic != 0 (Section 4: required for gradients) the level is
+ * floor(t) + [frac(t)*65536 > r + 0.5] where r are 16 bits of a stateless counter-based generator
+ * keyed by (seed, flat element index).
+ *
+ * x: n floats.  q_out: n int8 (bits <= 8) or n int16.  qp_out: one q8t_qparams.  n may be 0
+ * (then qp_out describes the range [0,0]).  n <= 2^34.
+ */
+size_t q8t_quantize_workspace_size(int64_t n);
+int q8t_quantize(const float *x, int64_t n, int bits, int stochastic, uint64_t seed, void *q_out,
+                 q8t_qparams *qp_out, void *ws, void *stream);
+
+/* Same, with the range supplied instead of searched: vmin_vmax points to 2 device floats
+ * (Section 4: the range of an activation is already known to the preceding Range BN).  Values
+ * outside the range saturate.  Needs no workspace. */
+int q8t_quantize_with_range(const float *x, int64_t n, int bits, int stochastic, uint64_t seed,
+                            const float *vmin_vmax, void *q_out, q8t_qparams *qp_out, void *stream);
+
+/* Gradient bifurcation (Section 1; Section 7): one pass over g yields the 8-bit copy that feeds
+ * the layer gradient and the 16-bit copy that feeds the weight gradient.  Both share g's min/max
+ * and use stochastic rounding with their own seeds.  ws: q8t_quantize_workspace_size(n). */
+int q8t_quantize_bifurcate(const float *g, int64_t n, uint64_t seed8, uint64_t seed16, int8_t *q8_out,
+                           q8t_qparams *qp8_out, int16_t *q16_out, q8t_qparams *qp16_out, void *ws,
+                           void *stream);
+
+/* out_i = scale * (level_i - zero_point).  q holds int8 or int16 according to qp->bits. */
+int q8t_dequantize(const void *q, const q8t_qparams *qp, int64_t n, float *out, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Fully connected layer, row-major (Section 4, eqs. (grad_layer) and (grad_weight)).
+ *   fwd  : Y [M,N] = X[M,K]  * W[K,N]
+ *   dgrad: dX[M,K] = dY[M,N] * W[K,N]^T           (8-bit copy of dY, stochastic)
+ *   wgrad: dW[K,N] = X[M,K]^T * dY16[M,N]         (16-bit copy of dY, 8-bit layer input)
+ * Operands are stored codes with their device-resident parameters.  The integer accumulator is
+ *   acc = sum_k (level_a - zero_a) * (level_b - zero_b)
+ * exact, and the float result is fl32(scale_a*scale_b) * (float)acc for fwd/dgrad and
+ * (float)((double)acc * (double)fl32(scale_a*scale_b)) for wgrad.  `acc_out` (nullable) receives
+ * the accumulator itself: int32 for fwd/dgrad, int64 for wgrad.  The float output is nullable too.
+ * fwd/dgrad require a reduction length <= 33025 (so that |acc| < 2^31), else Q8T_ERR_OVERFLOW;
+ * wgrad accepts any M (partial sums are reduced in 64 bits).
+ * which: 0 fwd, 1 dgrad, 2 wgrad.
+ */
+size_t q8t_qgemm_workspace_size(int M, int N, int K, int which);
+int q8t_qgemm_fwd(const int8_t *qx, const q8t_qparams *px, const int8_t *qw, const q8t_qparams *pw,
+                  int M, int N, int K, float *y, int32_t *acc_out, void *ws, void *stream);
+int q8t_qgemm_dgrad(const int8_t *qdy, const q8t_qparams *pg, const int8_t *qw, const q8t_qparams *pw,
+                    int M, int N, int K, float *dx, int32_t *acc_out, void *ws, void *stream);
+int q8t_qgemm_wgrad(const int8_t *qx, const q8t_qparams *px, const int16_t *qdy16,
+                    const q8t_qparams *pg16, int M, int N, int K, float *dw, int64_t *acc_out,
+                    void *ws, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Convolution layer, NCHW (same three products, Section 4).  A padded tap contributes nothing.
+ *   fwd  : Y [n,k,p,q] = sum_{c,r,s} X[n,c,p*st+r-pad,q*st+s-pad] * W[k,c,r,s]
+ *   dgrad: dX[n,c,h,w] = sum_{k,r,s} dY[n,k,p,q] * W[k,c,r,s]   over p*st+r-pad = h, q*st+s-pad = w
+ *   wgrad: dW[k,c,r,s] = sum_{n,p,q} dY16[n,k,p,q] * X[n,c,p*st+r-pad,q*st+s-pad]
+ * Same accumulator / scaling / acc_out contract as the FC calls (reduction lengths C*R*S, K*R*S
+ * and N*P*Q respectively).
+ */
+size_t q8t_qconv_workspace_size(const q8t_conv_desc *desc /* host */, int which);
+int q8t_qconv_fwd(const q8t_conv_desc *desc /* host */, const int8_t *qx, const q8t_qparams *px,
+                  const int8_t *qw, const q8t_qparams *pw, float *y, int32_t *acc_out, void *ws,
+                  void *stream);
+int q8t_qconv_dgrad(const q8t_conv_desc *desc /* host */, const int8_t *qdy, const q8t_qparams *pg,
+                    const int8_t *qw, const q8t_qparams *pw, float *dx, int32_t *acc_out, void *ws,
+                    void *stream);
+int q8t_qconv_wgrad(const q8t_conv_desc *desc /* host */, const int8_t *qx, const q8t_qparams *px,
+                    const int16_t *qdy16, const q8t_qparams *pg16, float *dw, int64_t *acc_out,
+                    void *ws, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Range Batch-Norm over NCHW (Section 3, eq. (range); FC activations: H = W = 1).
+ * Per channel c over its n = N*H*W values:
+ *   mu = mean(x), range = max(x) - min(x), C(n) = 1/sqrt(2 ln n)
+ *   y = gamma_c * (x - mu) / (C(n)*range + eps) + beta_c
+ * fp32 elementwise arithmetic, one rounding per operation; the mean is accumulated in fp64.
+ * gamma / beta nullable (1 / 0).  stats_out: [3][C] floats = mean, min, max (kept for backward).
+ * y is nullable.  If q_out != NULL the output is also emitted as 8-bit codes quantized per tensor,
+ * the range taken from the images of each channel's min and max (Section 4: no extra pass over the
+ * data), with parameters in qp_out.  Requires n >= 2.
+ */
+size_t q8t_range_bn_workspace_size(int N, int C, int H, int W);
+int q8t_range_bn_fwd(const float *x, int N, int C, int H, int W, const float *gamma,
+                     const float *beta, float eps, float *y, float *stats_out, int8_t *q_out,
+                     q8t_qparams *qp_out, void *ws, void *stream);
+
+/* Backward of the above (Section 7: the derivative of max / min is one at every coordinate that
+ * attains it and zero elsewhere).  With g_j = gamma*dy_j, s = C(n)*range + eps:
+ *   dbeta = sum dy,  dgamma = sum dy * xhat
+ *   dx_j = (g_j - mean(g))/s - C(n)*(sum_i g_i*xhat_i)/s * ([x_j == max] - [x_j == min])
+ * stats: the [3][C] array written by the forward call.  dx, dgamma, dbeta are each nullable. */
+int q8t_range_bn_bwd(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
+                     const float *gamma, float eps, float *dx, float *dgamma, float *dbeta, void *ws,
+                     void *stream);
+
+/* C(n) = 1/sqrt(2 ln n) (Section 3), host arithmetic in double.  n >= 2. */
+double q8t_range_bn_scale(int64_t n);
+
+/* Library version string (host pointer, static storage). */
+const char *q8t_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* Q8T_H */

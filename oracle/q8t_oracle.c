@@ -137,23 +137,25 @@ uint32_t orc_r16(uint64_t i, uint64_t seed)
  */
 static int32_t orc_level(float x, const orc_qparams *qp, int stochastic, uint64_t i, uint64_t seed)
 {
-    int32_t qmax = (1 << qp->bits) - 1;
+    float qmax = (float)((1 << qp->bits) - 1);
     float u = x * qp->inv_scale;
     float t = u + (float)qp->zero_point;
-    int32_t q;
+    float q;
     if (!stochastic) {
-        q = (int32_t)rintf(t);
+        q = rintf(t);
     } else {
         float f = floorf(t);
         float frac = t - f;
         uint32_t r = orc_r16(i, seed);
         float lhs = frac * 65536.0f;
         float rhs = (float)r + 0.5f;
-        q = (int32_t)f + (lhs > rhs ? 1 : 0);
+        q = (lhs > rhs) ? f + 1.0f : f;
     }
-    if (q < 0) q = 0;
+    /* saturate while still in float: a value far outside a supplied range must land on the
+       nearest end level, whatever an out-of-range float-to-int conversion would do */
+    if (q < 0.0f) q = 0.0f;
     if (q > qmax) q = qmax;
-    return q;
+    return (int32_t)q;
 }
 
 /*

@@ -1,0 +1,284 @@
+"""Thin ctypes binding over libq8t.so (the C ABI declared in include/q8t.h).
+
+Argument marshalling only: torch supplies device memory and the current stream, every step of
+the method runs in the library's HIP kernels.  There is no CPU fallback: if the library is not
+built the import fails.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libq8t.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        "libq8t.so is not built (%s): run `python -c 'import __graft_entry__ as g; g.build()'` "
+        "or `python paper_1805_11046_amd/build.py`" % LIB_PATH)
+
+_lib = C.CDLL(LIB_PATH)
+
+ERRORS = {-1: "Q8T_ERR_NULL", -2: "Q8T_ERR_SHAPE", -3: "Q8T_ERR_BITS", -4: "Q8T_ERR_OVERFLOW",
+          -5: "Q8T_ERR_WORKSPACE", -6: "Q8T_ERR_HIP"}
+
+
+class Q8TError(RuntimeError):
+    def __init__(self, code, where):
+        super().__init__("%s failed: %s (%d)" % (where, ERRORS.get(code, "?"), code))
+        self.code = code
+
+
+class ConvDesc(C.Structure):
+    """q8t_conv_desc: input [N,C,H,W], filter [K,C,R,S]."""
+    _fields_ = [(k, C.c_int) for k in ("N", "C", "H", "W", "K", "R", "S", "stride", "pad")]
+
+    @property
+    def P(self):
+        return (self.H + 2 * self.pad - self.R) // self.stride + 1
+
+    @property
+    def Q(self):
+        return (self.W + 2 * self.pad - self.S) // self.stride + 1
+
+
+QPARAMS_BYTES = 24
+_vp, _i, _i64, _u64, _f, _sz = C.c_void_p, C.c_int, C.c_int64, C.c_uint64, C.c_float, C.c_size_t
+
+_SIGS = {
+    "q8t_quantize_workspace_size": (_sz, [_i64]),
+    "q8t_quantize": (_i, [_vp, _i64, _i, _i, _u64, _vp, _vp, _vp, _vp]),
+    "q8t_quantize_with_range": (_i, [_vp, _i64, _i, _i, _u64, _vp, _vp, _vp, _vp]),
+    "q8t_quantize_bifurcate": (_i, [_vp, _i64, _u64, _u64, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_dequantize": (_i, [_vp, _vp, _i64, _vp, _vp]),
+    "q8t_qgemm_workspace_size": (_sz, [_i, _i, _i, _i]),
+    "q8t_qgemm_fwd": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp]),
+    "q8t_qgemm_dgrad": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp]),
+    "q8t_qgemm_wgrad": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp]),
+    "q8t_qconv_workspace_size": (_sz, [C.POINTER(ConvDesc), _i]),
+    "q8t_qconv_fwd": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_qconv_dgrad": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_qconv_wgrad": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_range_bn_workspace_size": (_sz, [_i, _i, _i, _i]),
+    "q8t_range_bn_fwd": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_range_bn_bwd": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _f, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_range_bn_scale": (C.c_double, [_i64]),
+    "q8t_version": (C.c_char_p, []),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _fn = getattr(_lib, _name)  # AttributeError here = the library does not export the symbol
+    _fn.restype = _res
+    _fn.argtypes = _args
+
+EXPORTED = tuple(sorted(_SIGS))
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc, where):
+    if rc != 0:
+        raise Q8TError(rc, where)
+
+
+def _dev(t):
+    if not t.is_cuda:
+        raise ValueError("q8t works on device tensors only (got a CPU tensor)")
+    if not t.is_contiguous():
+        raise ValueError("q8t needs contiguous tensors")
+    return t
+
+
+_ws_cache = {}
+
+
+def workspace(nbytes, device):
+    """A reusable device scratch buffer of at least nbytes (grown on demand, one per device)."""
+    key = (device.type, device.index)
+    buf = _ws_cache.get(key)
+    need = max(int(nbytes), 256)
+    if buf is None or buf.numel() < need:
+        buf = torch.empty(need, dtype=torch.uint8, device=device)
+        _ws_cache[key] = buf
+    return buf
+
+
+def new_qparams(device):
+    """Device-resident q8t_qparams (24 bytes) as an int32[6] tensor."""
+    return torch.empty(6, dtype=torch.int32, device=device)
+
+
+def qparams_to_host(qp):
+    """(vmin, vmax, scale, inv_scale, zero_point, bits) read back from the device."""
+    h = qp.cpu()
+    f = h[:4].view(torch.float32)
+    return (float(f[0]), float(f[1]), float(f[2]), float(f[3]), int(h[4]), int(h[5]))
+
+
+def version():
+    return _lib.q8t_version().decode()
+
+
+def range_bn_scale(n):
+    return float(_lib.q8t_range_bn_scale(int(n)))
+
+
+# ------------------------------------------------------------------ quantization
+def quantize(x, bits=8, stochastic=False, seed=0, q_out=None, qp_out=None, ws=None):
+    _dev(x)
+    n = x.numel()
+    q = q_out if q_out is not None else torch.empty(x.shape, dtype=torch.int8 if bits <= 8 else torch.int16,
+                                                     device=x.device)
+    qp = qp_out if qp_out is not None else new_qparams(x.device)
+    ws = ws if ws is not None else workspace(_lib.q8t_quantize_workspace_size(n), x.device)
+    _check(_lib.q8t_quantize(_ptr(x), n, bits, int(bool(stochastic)), int(seed) & (2 ** 64 - 1), _ptr(q),
+                             _ptr(qp), _ptr(ws), _stream()), "q8t_quantize")
+    return q, qp
+
+
+def quantize_with_range(x, vmin_vmax, bits=8, stochastic=False, seed=0, q_out=None, qp_out=None):
+    _dev(x)
+    _dev(vmin_vmax)
+    n = x.numel()
+    q = q_out if q_out is not None else torch.empty(x.shape, dtype=torch.int8 if bits <= 8 else torch.int16,
+                                                     device=x.device)
+    qp = qp_out if qp_out is not None else new_qparams(x.device)
+    _check(_lib.q8t_quantize_with_range(_ptr(x), n, bits, int(bool(stochastic)), int(seed) & (2 ** 64 - 1),
+                                        _ptr(vmin_vmax), _ptr(q), _ptr(qp), _stream()),
+           "q8t_quantize_with_range")
+    return q, qp
+
+
+def quantize_bifurcate(g, seed8=0, seed16=1, q8_out=None, qp8_out=None, q16_out=None, qp16_out=None, ws=None):
+    _dev(g)
+    n = g.numel()
+    q8 = q8_out if q8_out is not None else torch.empty(g.shape, dtype=torch.int8, device=g.device)
+    q16 = q16_out if q16_out is not None else torch.empty(g.shape, dtype=torch.int16, device=g.device)
+    qp8 = qp8_out if qp8_out is not None else new_qparams(g.device)
+    qp16 = qp16_out if qp16_out is not None else new_qparams(g.device)
+    ws = ws if ws is not None else workspace(_lib.q8t_quantize_workspace_size(n), g.device)
+    _check(_lib.q8t_quantize_bifurcate(_ptr(g), n, int(seed8) & (2 ** 64 - 1), int(seed16) & (2 ** 64 - 1),
+                                       _ptr(q8), _ptr(qp8), _ptr(q16), _ptr(qp16), _ptr(ws), _stream()),
+           "q8t_quantize_bifurcate")
+    return q8, qp8, q16, qp16
+
+
+def dequantize(q, qp, out=None):
+    _dev(q)
+    out = out if out is not None else torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    _check(_lib.q8t_dequantize(_ptr(q), _ptr(qp), q.numel(), _ptr(out), _stream()), "q8t_dequantize")
+    return out
+
+
+# ------------------------------------------------------------------ FC products
+def _fc(fn, name, a, pa, b, pb, M, N, K, out_shape, which, acc_dtype, want_acc, out, ws):
+    dev = a.device
+    y = out if out is not None else torch.empty(out_shape, dtype=torch.float32, device=dev)
+    acc = torch.empty(out_shape, dtype=acc_dtype, device=dev) if want_acc else None
+    ws = ws if ws is not None else workspace(_lib.q8t_qgemm_workspace_size(M, N, K, which), dev)
+    _check(fn(_ptr(a), _ptr(pa), _ptr(b), _ptr(pb), M, N, K, _ptr(y), _ptr(acc), _ptr(ws), _stream()), name)
+    return y, acc
+
+
+def qgemm_fwd(qx, px, qw, pw, want_acc=False, out=None, ws=None):
+    """Y[M,N] = X[M,K] W[K,N]"""
+    _dev(qx), _dev(qw)
+    M, K = qx.shape
+    K2, N = qw.shape
+    assert K == K2
+    return _fc(_lib.q8t_qgemm_fwd, "q8t_qgemm_fwd", qx, px, qw, pw, M, N, K, (M, N), 0, torch.int32, want_acc,
+               out, ws)
+
+
+def qgemm_dgrad(qdy, pg, qw, pw, want_acc=False, out=None, ws=None):
+    """dX[M,K] = dY[M,N] W[K,N]^T"""
+    _dev(qdy), _dev(qw)
+    M, N = qdy.shape
+    K, N2 = qw.shape
+    assert N == N2
+    return _fc(_lib.q8t_qgemm_dgrad, "q8t_qgemm_dgrad", qdy, pg, qw, pw, M, N, K, (M, K), 1, torch.int32,
+               want_acc, out, ws)
+
+
+def qgemm_wgrad(qx, px, qdy16, pg16, want_acc=False, out=None, ws=None):
+    """dW[K,N] = X[M,K]^T dY16[M,N]"""
+    _dev(qx), _dev(qdy16)
+    M, K = qx.shape
+    M2, N = qdy16.shape
+    assert M == M2 and qdy16.dtype == torch.int16
+    return _fc(_lib.q8t_qgemm_wgrad, "q8t_qgemm_wgrad", qx, px, qdy16, pg16, M, N, K, (K, N), 2, torch.int64,
+               want_acc, out, ws)
+
+
+# ------------------------------------------------------------------ convolution products
+def conv_desc(N, Cin, H, W, K, R, S, stride, pad):
+    return ConvDesc(N, Cin, H, W, K, R, S, stride, pad)
+
+
+def _conv(fn, name, d, a, pa, b, pb, out_shape, which, acc_dtype, want_acc, out, ws):
+    dev = a.device
+    y = out if out is not None else torch.empty(out_shape, dtype=torch.float32, device=dev)
+    acc = torch.empty(out_shape, dtype=acc_dtype, device=dev) if want_acc else None
+    ws = ws if ws is not None else workspace(_lib.q8t_qconv_workspace_size(C.byref(d), which), dev)
+    _check(fn(C.byref(d), _ptr(a), _ptr(pa), _ptr(b), _ptr(pb), _ptr(y), _ptr(acc), _ptr(ws), _stream()), name)
+    return y, acc
+
+
+def qconv_fwd(d, qx, px, qw, pw, want_acc=False, out=None, ws=None):
+    _dev(qx), _dev(qw)
+    assert tuple(qx.shape) == (d.N, d.C, d.H, d.W) and tuple(qw.shape) == (d.K, d.C, d.R, d.S)
+    return _conv(_lib.q8t_qconv_fwd, "q8t_qconv_fwd", d, qx, px, qw, pw, (d.N, d.K, d.P, d.Q), 0, torch.int32,
+                 want_acc, out, ws)
+
+
+def qconv_dgrad(d, qdy, pg, qw, pw, want_acc=False, out=None, ws=None):
+    _dev(qdy), _dev(qw)
+    assert tuple(qdy.shape) == (d.N, d.K, d.P, d.Q) and tuple(qw.shape) == (d.K, d.C, d.R, d.S)
+    return _conv(_lib.q8t_qconv_dgrad, "q8t_qconv_dgrad", d, qdy, pg, qw, pw, (d.N, d.C, d.H, d.W), 1,
+                 torch.int32, want_acc, out, ws)
+
+
+def qconv_wgrad(d, qx, px, qdy16, pg16, want_acc=False, out=None, ws=None):
+    _dev(qx), _dev(qdy16)
+    assert tuple(qx.shape) == (d.N, d.C, d.H, d.W) and tuple(qdy16.shape) == (d.N, d.K, d.P, d.Q)
+    assert qdy16.dtype == torch.int16
+    return _conv(_lib.q8t_qconv_wgrad, "q8t_qconv_wgrad", d, qx, px, qdy16, pg16, (d.K, d.C, d.R, d.S), 2,
+                 torch.int64, want_acc, out, ws)
+
+
+# ------------------------------------------------------------------ Range BN
+def range_bn_fwd(x, gamma=None, beta=None, eps=0.0, quantized=False, want_y=True, y_out=None, stats_out=None,
+                 q_out=None, qp_out=None, ws=None):
+    """Returns (y or None, stats[3,C], q or None, qp or None)."""
+    _dev(x)
+    N, Cc, H, W = x.shape
+    dev = x.device
+    y = y_out if y_out is not None else (torch.empty_like(x) if want_y else None)
+    stats = stats_out if stats_out is not None else torch.empty((3, Cc), dtype=torch.float32, device=dev)
+    q = qp = None
+    if quantized:
+        q = q_out if q_out is not None else torch.empty(x.shape, dtype=torch.int8, device=dev)
+        qp = qp_out if qp_out is not None else new_qparams(dev)
+    ws = ws if ws is not None else workspace(_lib.q8t_range_bn_workspace_size(N, Cc, H, W), dev)
+    _check(_lib.q8t_range_bn_fwd(_ptr(x), N, Cc, H, W, _ptr(gamma), _ptr(beta), float(eps), _ptr(y), _ptr(stats),
+                                 _ptr(q), _ptr(qp), _ptr(ws), _stream()), "q8t_range_bn_fwd")
+    return y, stats, q, qp
+
+
+def range_bn_bwd(x, dy, stats, gamma=None, eps=0.0, dx_out=None, ws=None):
+    """Returns (dx, dgamma, dbeta)."""
+    _dev(x), _dev(dy), _dev(stats)
+    N, Cc, H, W = x.shape
+    dev = x.device
+    dx = dx_out if dx_out is not None else torch.empty_like(x)
+    dgamma = torch.empty(Cc, dtype=torch.float32, device=dev)
+    dbeta = torch.empty(Cc, dtype=torch.float32, device=dev)
+    ws = ws if ws is not None else workspace(_lib.q8t_range_bn_workspace_size(N, Cc, H, W), dev)
+    _check(_lib.q8t_range_bn_bwd(_ptr(x), _ptr(dy), _ptr(stats), N, Cc, H, W, _ptr(gamma), float(eps), _ptr(dx),
+                                 _ptr(dgamma), _ptr(dbeta), _ptr(ws), _stream()), "q8t_range_bn_bwd")
+    return dx, dgamma, dbeta

@@ -1,0 +1,100 @@
+// C-ABI entry points of the product calls: argument checks on the host, then dispatch to the
+// specialised kernel for the shape if there is one, else to the general kernel.
+#include "q8t_common.h"
+#include "q8t_internal.h"
+
+namespace {
+
+constexpr int kMaxRed32 = 33025;  // 255*255*K < 2^31  (32-bit accumulator contract of fwd / dgrad)
+
+int fc_check(int M, int N, int K, const void *a, const void *qa, const void *b, const void *qb, const void *o1,
+             const void *o2)
+{
+    if (M <= 0 || N <= 0 || K <= 0) return Q8T_ERR_SHAPE;
+    if ((int64_t)M * N >= ((int64_t)1 << 31) || (int64_t)M * K >= ((int64_t)1 << 31) ||
+        (int64_t)K * N >= ((int64_t)1 << 31))
+        return Q8T_ERR_SHAPE;
+    if (!a || !qa || !b || !qb || (!o1 && !o2)) return Q8T_ERR_NULL;
+    return Q8T_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *q8t_version(void) { return "q8t 0.1 (gfx950)"; }
+
+size_t q8t_qgemm_workspace_size(int M, int N, int K, int which)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || which < 0 || which > 2) return 0;
+    return q8t_generic_fc_ws(which, M, N, K);
+}
+
+int q8t_qgemm_fwd(const int8_t *qx, const q8t_qparams *px, const int8_t *qw, const q8t_qparams *pw, int M, int N,
+                  int K, float *y, int32_t *acc_out, void *ws, void *stream)
+{
+    const int rc = fc_check(M, N, K, qx, px, qw, pw, y, acc_out);
+    if (rc) return rc;
+    if (K > kMaxRed32) return Q8T_ERR_OVERFLOW;
+    return q8t_generic_fc(0, qx, px, qw, pw, M, N, K, y, acc_out, ws, (hipStream_t)stream);
+}
+
+int q8t_qgemm_dgrad(const int8_t *qdy, const q8t_qparams *pg, const int8_t *qw, const q8t_qparams *pw, int M,
+                    int N, int K, float *dx, int32_t *acc_out, void *ws, void *stream)
+{
+    const int rc = fc_check(M, N, K, qdy, pg, qw, pw, dx, acc_out);
+    if (rc) return rc;
+    if (N > kMaxRed32) return Q8T_ERR_OVERFLOW;
+    return q8t_generic_fc(1, qdy, pg, qw, pw, M, N, K, dx, acc_out, ws, (hipStream_t)stream);
+}
+
+int q8t_qgemm_wgrad(const int8_t *qx, const q8t_qparams *px, const int16_t *qdy16, const q8t_qparams *pg16, int M,
+                    int N, int K, float *dw, int64_t *acc_out, void *ws, void *stream)
+{
+    const int rc = fc_check(M, N, K, qx, px, qdy16, pg16, dw, acc_out);
+    if (rc) return rc;
+    return q8t_generic_fc(2, qdy16, pg16, qx, px, M, N, K, dw, acc_out, ws, (hipStream_t)stream);
+}
+
+size_t q8t_qconv_workspace_size(const q8t_conv_desc *desc, int which)
+{
+    if (!desc || which < 0 || which > 2) return 0;
+    size_t g = q8t_generic_conv_ws(which, desc);
+    size_t f = q8t_fast_conv_ws(which, desc);
+    return g > f ? g : f;
+}
+
+int q8t_qconv_fwd(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams *px, const int8_t *qw,
+                  const q8t_qparams *pw, float *y, int32_t *acc_out, void *ws, void *stream)
+{
+    if (!desc || !qx || !px || !qw || !pw || (!y && !acc_out)) return Q8T_ERR_NULL;
+    const int rc = q8t_conv_reduction_check(0, desc);
+    if (rc) return rc;
+    if (q8t_fast_conv_supported(0, desc, qx, qw, y, acc_out))
+        return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
+    return q8t_generic_conv(0, desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
+}
+
+int q8t_qconv_dgrad(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qparams *pg, const int8_t *qw,
+                    const q8t_qparams *pw, float *dx, int32_t *acc_out, void *ws, void *stream)
+{
+    if (!desc || !qdy || !pg || !qw || !pw || (!dx && !acc_out)) return Q8T_ERR_NULL;
+    const int rc = q8t_conv_reduction_check(1, desc);
+    if (rc) return rc;
+    if (q8t_fast_conv_supported(1, desc, qdy, qw, dx, acc_out))
+        return q8t_fast_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, ws, (hipStream_t)stream);
+    return q8t_generic_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, ws, (hipStream_t)stream);
+}
+
+int q8t_qconv_wgrad(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams *px, const int16_t *qdy16,
+                    const q8t_qparams *pg16, float *dw, int64_t *acc_out, void *ws, void *stream)
+{
+    if (!desc || !qx || !px || !qdy16 || !pg16 || (!dw && !acc_out)) return Q8T_ERR_NULL;
+    const int rc = q8t_conv_reduction_check(2, desc);
+    if (rc) return rc;
+    if (q8t_fast_conv_supported(2, desc, qdy16, qx, dw, acc_out))
+        return q8t_fast_conv(2, desc, qdy16, pg16, qx, px, dw, acc_out, ws, (hipStream_t)stream);
+    return q8t_generic_conv(2, desc, qdy16, pg16, qx, px, dw, acc_out, ws, (hipStream_t)stream);
+}
+
+}  // extern "C"

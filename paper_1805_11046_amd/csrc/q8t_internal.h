@@ -1,0 +1,22 @@
+// Internal (non-exported) interfaces between the translation units of libq8t.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "q8t.h"
+
+// general kernel (igemm_generic.hip).  which: 0 fwd, 1 dgrad, 2 wgrad.  For wgrad the 16-bit
+// operand is passed first (a, qa).
+int q8t_generic_fc(int which, const void *a, const q8t_qparams *qa, const void *b, const q8t_qparams *qb, int M,
+                   int N, int K, float *out_f, void *out_acc, void *ws, hipStream_t st);
+size_t q8t_generic_fc_ws(int which, int M, int N, int K);
+int q8t_generic_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
+                     const q8t_qparams *qb, float *out_f, void *out_acc, void *ws, hipStream_t st);
+size_t q8t_generic_conv_ws(int which, const q8t_conv_desc *d);
+int q8t_conv_reduction_check(int which, const q8t_conv_desc *d);
+
+// specialised convolution kernels (conv_fast.hip)
+bool q8t_fast_conv_supported(int which, const q8t_conv_desc *d, const void *a, const void *b, const void *out_f,
+                             const void *out_acc);
+size_t q8t_fast_conv_ws(int which, const q8t_conv_desc *d);
+int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
+                  const q8t_qparams *qb, float *out_f, void *out_acc, void *ws, hipStream_t st);

@@ -1,0 +1,386 @@
+// Per-tensor min/max affine quantization (Appendix B), nearest or stochastic rounding
+// (Section 4), and the fused 8+16-bit "gradient bifurcation" pass (Sections 1 and 7).
+//
+// Two launches per call, no host synchronization in between:
+//   1. minmax_partials : grid-stride pass, float4 loads, wavefront-shuffle reductions, one
+//                        (min,max) pair per workgroup into the workspace.
+//   2. quantize_apply  : every workgroup folds the <=1024 pairs itself (identical fp32 sequence in
+//                        every workgroup, so they all agree bit for bit), derives scale and zero
+//                        point, then quantizes its share: 4 elements -> one packed store.
+// HBM-bound: 9 algorithmic bytes per element for 8-bit output (4 read + 4 re-read + 1 written).
+#include "q8t_common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxPartials = 1024;
+
+__device__ __forceinline__ float block_reduce_min(float v, float *smem)
+{
+    v = wave_reduce(v, OpMin());
+    if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = smem[0];
+    for (int w = 1; w < kThreads / 64; ++w) r = fminf(r, smem[w]);
+    __syncthreads();
+    return r;
+}
+__device__ __forceinline__ float block_reduce_max(float v, float *smem)
+{
+    v = wave_reduce(v, OpMax());
+    if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = smem[0];
+    for (int w = 1; w < kThreads / 64; ++w) r = fmaxf(r, smem[w]);
+    __syncthreads();
+    return r;
+}
+
+__device__ __forceinline__ void mm4(float &mn, float &mx, const float4 v)
+{
+    mn = fminf(fminf(mn, v.x), fminf(v.y, fminf(v.z, v.w)));
+    mx = fmaxf(fmaxf(mx, v.x), fmaxf(v.y, fmaxf(v.z, v.w)));
+}
+
+// pass 1: one (min,max) pair per workgroup
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void minmax_partials(const float *__restrict__ x, int64_t n,
+                                                            float2 *__restrict__ partials)
+{
+    __shared__ float smem[kThreads / 64];
+    float mn = INFINITY, mx = -INFINITY;
+    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    if (VEC) {
+        const int64_t n4 = n >> 2;
+        const float4 *x4 = reinterpret_cast<const float4 *>(x);
+        int64_t i = gid;
+        for (; i + 3 * stride < n4; i += 4 * stride) {
+            const float4 a = x4[i], b = x4[i + stride], c = x4[i + 2 * stride], d = x4[i + 3 * stride];
+            mm4(mn, mx, a);
+            mm4(mn, mx, b);
+            mm4(mn, mx, c);
+            mm4(mn, mx, d);
+        }
+        for (; i < n4; i += stride) mm4(mn, mx, x4[i]);
+        const int64_t tail = (n4 << 2) + gid;  // the n % 4 leftover elements
+        if (tail < n) {
+            mn = fminf(mn, x[tail]);
+            mx = fmaxf(mx, x[tail]);
+        }
+    } else {
+        for (int64_t i = gid; i < n; i += stride) {
+            mn = fminf(mn, x[i]);
+            mx = fmaxf(mx, x[i]);
+        }
+    }
+    mn = block_reduce_min(mn, smem);
+    mx = block_reduce_max(mx, smem);
+    if (threadIdx.x == 0) partials[blockIdx.x] = make_float2(mn, mx);
+}
+
+// ---- counter-based generator: 3 hashes serve the 4 elements of one group ----------------------
+__device__ __forceinline__ uint32_t mix32(uint32_t x)
+{
+    x ^= x >> 16;
+    x *= 0x6A09E667u;
+    x ^= x >> 15;
+    x *= 0xBB67AE85u;
+    x ^= x >> 16;
+    return x;
+}
+__device__ __forceinline__ void rng_group(uint32_t group, uint32_t seed_lo, uint32_t seed_hi,
+                                          uint32_t &w0, uint32_t &w1)
+{
+    const uint32_t phi = 0x9E3779B9u;
+    const uint32_t h = mix32(group * phi + seed_lo) ^ seed_hi;
+    w0 = mix32(h + phi);
+    w1 = mix32(h + 2u * phi);
+}
+__device__ __forceinline__ uint32_t rng_r16(int64_t i, uint32_t seed_lo, uint32_t seed_hi)
+{
+    uint32_t w0, w1;
+    rng_group((uint32_t)(i >> 2), seed_lo, seed_hi, w0, w1);
+    const uint32_t w = (i & 2) ? w1 : w0;
+    return (w >> (16 * (uint32_t)(i & 1))) & 0xFFFFu;
+}
+
+template <typename OUT>
+struct Pack4;
+template <>
+struct Pack4<int8_t> {
+    typedef uint32_t type;
+    static __device__ __forceinline__ uint32_t pack(int a, int b, int c, int d)
+    {
+        return (uint32_t)(a & 255) | ((uint32_t)(b & 255) << 8) | ((uint32_t)(c & 255) << 16) |
+               ((uint32_t)(d & 255) << 24);
+    }
+};
+template <>
+struct Pack4<int16_t> {
+    typedef uint2 type;
+    static __device__ __forceinline__ uint2 pack(int a, int b, int c, int d)
+    {
+        return make_uint2((uint32_t)(a & 65535) | ((uint32_t)(b & 65535) << 16),
+                          (uint32_t)(c & 65535) | ((uint32_t)(d & 65535) << 16));
+    }
+};
+
+template <typename OUT, bool STOCH>
+__device__ __forceinline__ typename Pack4<OUT>::type quant4(const float4 v, const Affine &a,
+                                                           uint32_t group, uint32_t seed_lo,
+                                                           uint32_t seed_hi)
+{
+    uint32_t w0 = 0, w1 = 0;
+    if (STOCH) rng_group(group, seed_lo, seed_hi, w0, w1);
+    const int q0 = level_of<STOCH>(v.x, a, w0 & 0xFFFFu) - a.half;
+    const int q1 = level_of<STOCH>(v.y, a, w0 >> 16) - a.half;
+    const int q2 = level_of<STOCH>(v.z, a, w1 & 0xFFFFu) - a.half;
+    const int q3 = level_of<STOCH>(v.w, a, w1 >> 16) - a.half;
+    return Pack4<OUT>::pack(q0, q1, q2, q3);
+}
+
+// every workgroup folds the partial pairs in the same order -> identical range everywhere
+__device__ __forceinline__ void fold_partials(const float2 *__restrict__ partials, int npartials,
+                                              float *smem, float &vmin, float &vmax)
+{
+    float mn = INFINITY, mx = -INFINITY;
+    for (int i = threadIdx.x; i < npartials; i += kThreads) {
+        const float2 p = partials[i];
+        mn = fminf(mn, p.x);
+        mx = fmaxf(mx, p.y);
+    }
+    vmin = block_reduce_min(mn, smem);
+    vmax = block_reduce_max(mx, smem);
+}
+
+// pass 2, single output
+template <typename OUT, bool STOCH, bool VEC>
+__global__ __launch_bounds__(kThreads) void quantize_apply(
+    const float *__restrict__ x, int64_t n, int bits, uint32_t seed_lo, uint32_t seed_hi,
+    const float2 *__restrict__ partials, int npartials, OUT *__restrict__ q_out,
+    q8t_qparams *__restrict__ qp_out)
+{
+    __shared__ float smem[kThreads / 64];
+    float vmin, vmax;
+    fold_partials(partials, npartials, smem, vmin, vmax);
+    const q8t_qparams qp = make_qparams(vmin, vmax, bits);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *qp_out = qp;
+    const Affine a = affine_of(qp);
+
+    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    if (VEC) {
+        typedef typename Pack4<OUT>::type P;
+        const int64_t n4 = n >> 2;
+        const float4 *x4 = reinterpret_cast<const float4 *>(x);
+        P *q4 = reinterpret_cast<P *>(q_out);
+        int64_t i = gid;
+        for (; i + 3 * stride < n4; i += 4 * stride) {
+            const float4 v0 = x4[i], v1 = x4[i + stride], v2 = x4[i + 2 * stride],
+                         v3 = x4[i + 3 * stride];
+            q4[i] = quant4<OUT, STOCH>(v0, a, (uint32_t)i, seed_lo, seed_hi);
+            q4[i + stride] = quant4<OUT, STOCH>(v1, a, (uint32_t)(i + stride), seed_lo, seed_hi);
+            q4[i + 2 * stride] = quant4<OUT, STOCH>(v2, a, (uint32_t)(i + 2 * stride), seed_lo, seed_hi);
+            q4[i + 3 * stride] = quant4<OUT, STOCH>(v3, a, (uint32_t)(i + 3 * stride), seed_lo, seed_hi);
+        }
+        for (; i < n4; i += stride) q4[i] = quant4<OUT, STOCH>(x4[i], a, (uint32_t)i, seed_lo, seed_hi);
+        const int64_t tail = (n4 << 2) + gid;
+        if (tail < n) {
+            const uint32_t r = STOCH ? rng_r16(tail, seed_lo, seed_hi) : 0u;
+            q_out[tail] = (OUT)(level_of<STOCH>(x[tail], a, r) - a.half);
+        }
+    } else {
+        for (int64_t i = gid; i < n; i += stride) {
+            const uint32_t r = STOCH ? rng_r16(i, seed_lo, seed_hi) : 0u;
+            q_out[i] = (OUT)(level_of<STOCH>(x[i], a, r) - a.half);
+        }
+    }
+}
+
+// pass 2, bifurcated: 8-bit and 16-bit stochastic copies from one read of g
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void quantize_bifurcate_apply(
+    const float *__restrict__ x, int64_t n, uint32_t s8_lo, uint32_t s8_hi, uint32_t s16_lo,
+    uint32_t s16_hi, const float2 *__restrict__ partials, int npartials, int8_t *__restrict__ q8,
+    q8t_qparams *__restrict__ qp8_out, int16_t *__restrict__ q16, q8t_qparams *__restrict__ qp16_out)
+{
+    __shared__ float smem[kThreads / 64];
+    float vmin, vmax;
+    fold_partials(partials, npartials, smem, vmin, vmax);
+    const q8t_qparams qp8 = make_qparams(vmin, vmax, 8);
+    const q8t_qparams qp16 = make_qparams(vmin, vmax, 16);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *qp8_out = qp8;
+        *qp16_out = qp16;
+    }
+    const Affine a8 = affine_of(qp8), a16 = affine_of(qp16);
+    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    if (VEC) {
+        const int64_t n4 = n >> 2;
+        const float4 *x4 = reinterpret_cast<const float4 *>(x);
+        uint32_t *o8 = reinterpret_cast<uint32_t *>(q8);
+        uint2 *o16 = reinterpret_cast<uint2 *>(q16);
+        int64_t i = gid;
+        for (; i + stride < n4; i += 2 * stride) {
+            const float4 v0 = x4[i], v1 = x4[i + stride];
+            o8[i] = quant4<int8_t, true>(v0, a8, (uint32_t)i, s8_lo, s8_hi);
+            o16[i] = quant4<int16_t, true>(v0, a16, (uint32_t)i, s16_lo, s16_hi);
+            o8[i + stride] = quant4<int8_t, true>(v1, a8, (uint32_t)(i + stride), s8_lo, s8_hi);
+            o16[i + stride] = quant4<int16_t, true>(v1, a16, (uint32_t)(i + stride), s16_lo, s16_hi);
+        }
+        for (; i < n4; i += stride) {
+            const float4 v0 = x4[i];
+            o8[i] = quant4<int8_t, true>(v0, a8, (uint32_t)i, s8_lo, s8_hi);
+            o16[i] = quant4<int16_t, true>(v0, a16, (uint32_t)i, s16_lo, s16_hi);
+        }
+        const int64_t tail = (n4 << 2) + gid;
+        if (tail < n) {
+            q8[tail] = (int8_t)(level_of<true>(x[tail], a8, rng_r16(tail, s8_lo, s8_hi)) - a8.half);
+            q16[tail] = (int16_t)(level_of<true>(x[tail], a16, rng_r16(tail, s16_lo, s16_hi)) - a16.half);
+        }
+    } else {
+        for (int64_t i = gid; i < n; i += stride) {
+            q8[i] = (int8_t)(level_of<true>(x[i], a8, rng_r16(i, s8_lo, s8_hi)) - a8.half);
+            q16[i] = (int16_t)(level_of<true>(x[i], a16, rng_r16(i, s16_lo, s16_hi)) - a16.half);
+        }
+    }
+}
+
+// the element width follows qp->bits, which only the device knows
+__global__ __launch_bounds__(kThreads) void dequantize_kernel(const void *__restrict__ q,
+                                                              const q8t_qparams *__restrict__ qp,
+                                                              int64_t n, float *__restrict__ out)
+{
+    const float scale = qp->scale;
+    const int bits = qp->bits;
+    const int shift = (1 << (bits - 1)) - qp->zero_point;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    const int8_t *q8 = (const int8_t *)q;
+    const int16_t *q16 = (const int16_t *)q;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+        const int s = (bits <= 8) ? (int)q8[i] : (int)q16[i];
+        out[i] = scale * (float)(s + shift);
+    }
+}
+
+int grid_for(int64_t work_items, int per_thread, int cap)
+{
+    int64_t g = (work_items + (int64_t)kThreads * per_thread - 1) / ((int64_t)kThreads * per_thread);
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+constexpr int64_t kMaxElements = (int64_t)1 << 34;
+
+template <typename OUT>
+int launch_apply(const float *x, int64_t n, int bits, int stochastic, uint64_t seed,
+                 const float2 *partials, int npartials, OUT *q, q8t_qparams *qp, hipStream_t st)
+{
+    const bool vec = q8t_aligned(x, 16) && q8t_aligned(q, 4 * sizeof(OUT));
+    const int grid = grid_for(vec ? (n >> 2) : n, 4, 8192);
+    const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
+#define Q8T_GO(S, V) \
+    hipLaunchKernelGGL((quantize_apply<OUT, S, V>), dim3(grid), dim3(kThreads), 0, st, x, n, bits, lo, hi, partials, npartials, q, qp)
+    if (stochastic) {
+        if (vec) Q8T_GO(true, true); else Q8T_GO(true, false);
+    } else {
+        if (vec) Q8T_GO(false, true); else Q8T_GO(false, false);
+    }
+#undef Q8T_GO
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
+
+int launch_minmax(const float *x, int64_t n, float2 *partials, hipStream_t st)
+{
+    if (n == 0) return 0;
+    const bool vec = q8t_aligned(x, 16);
+    const int grid = grid_for(vec ? (n >> 2) : n, 8, kMaxPartials);
+    if (vec)
+        hipLaunchKernelGGL(minmax_partials<true>, dim3(grid), dim3(kThreads), 0, st, x, n, partials);
+    else
+        hipLaunchKernelGGL(minmax_partials<false>, dim3(grid), dim3(kThreads), 0, st, x, n, partials);
+    return grid;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t q8t_quantize_workspace_size(int64_t n)
+{
+    (void)n;
+    return sizeof(float2) * kMaxPartials;
+}
+
+int q8t_quantize(const float *x, int64_t n, int bits, int stochastic, uint64_t seed, void *q_out,
+                 q8t_qparams *qp_out, void *ws, void *stream)
+{
+    if (n < 0 || n > kMaxElements) return Q8T_ERR_SHAPE;
+    if (bits < 2 || bits > 16) return Q8T_ERR_BITS;
+    if (!qp_out || (n > 0 && (!x || !q_out))) return Q8T_ERR_NULL;
+    if (!ws || !q8t_aligned(ws, 8)) return Q8T_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    float2 *partials = (float2 *)ws;
+    const int np = launch_minmax(x, n, partials, st);
+    Q8T_LAUNCH_CHECK();
+    if (bits <= 8)
+        return launch_apply<int8_t>(x, n, bits, stochastic, seed, partials, np, (int8_t *)q_out, qp_out, st);
+    return launch_apply<int16_t>(x, n, bits, stochastic, seed, partials, np, (int16_t *)q_out, qp_out, st);
+}
+
+int q8t_quantize_with_range(const float *x, int64_t n, int bits, int stochastic, uint64_t seed,
+                            const float *vmin_vmax, void *q_out, q8t_qparams *qp_out, void *stream)
+{
+    if (n < 0 || n > kMaxElements) return Q8T_ERR_SHAPE;
+    if (bits < 2 || bits > 16) return Q8T_ERR_BITS;
+    if (!qp_out || !vmin_vmax || (n > 0 && (!x || !q_out))) return Q8T_ERR_NULL;
+    if (!q8t_aligned(vmin_vmax, 8)) return Q8T_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    // the supplied pair plays the role of a single partial result
+    const float2 *partials = (const float2 *)vmin_vmax;
+    if (bits <= 8)
+        return launch_apply<int8_t>(x, n, bits, stochastic, seed, partials, 1, (int8_t *)q_out, qp_out, st);
+    return launch_apply<int16_t>(x, n, bits, stochastic, seed, partials, 1, (int16_t *)q_out, qp_out, st);
+}
+
+int q8t_quantize_bifurcate(const float *g, int64_t n, uint64_t seed8, uint64_t seed16, int8_t *q8_out,
+                           q8t_qparams *qp8_out, int16_t *q16_out, q8t_qparams *qp16_out, void *ws,
+                           void *stream)
+{
+    if (n < 0 || n > kMaxElements) return Q8T_ERR_SHAPE;
+    if (!qp8_out || !qp16_out || (n > 0 && (!g || !q8_out || !q16_out))) return Q8T_ERR_NULL;
+    if (!ws || !q8t_aligned(ws, 8)) return Q8T_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    float2 *partials = (float2 *)ws;
+    const int np = launch_minmax(g, n, partials, st);
+    Q8T_LAUNCH_CHECK();
+    const bool vec = q8t_aligned(g, 16) && q8t_aligned(q8_out, 4) && q8t_aligned(q16_out, 8);
+    const int grid = grid_for(vec ? (n >> 2) : n, 2, 8192);
+    if (vec)
+        hipLaunchKernelGGL(quantize_bifurcate_apply<true>, dim3(grid), dim3(kThreads), 0, st, g, n,
+                           (uint32_t)seed8, (uint32_t)(seed8 >> 32), (uint32_t)seed16,
+                           (uint32_t)(seed16 >> 32), partials, np, q8_out, qp8_out, q16_out, qp16_out);
+    else
+        hipLaunchKernelGGL(quantize_bifurcate_apply<false>, dim3(grid), dim3(kThreads), 0, st, g, n,
+                           (uint32_t)seed8, (uint32_t)(seed8 >> 32), (uint32_t)seed16,
+                           (uint32_t)(seed16 >> 32), partials, np, q8_out, qp8_out, q16_out, qp16_out);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
+
+int q8t_dequantize(const void *q, const q8t_qparams *qp, int64_t n, float *out, void *stream)
+{
+    if (n < 0 || n > kMaxElements) return Q8T_ERR_SHAPE;
+    if (!qp || (n > 0 && (!q || !out))) return Q8T_ERR_NULL;
+    if (n == 0) return Q8T_OK;
+    hipLaunchKernelGGL(dequantize_kernel, dim3(grid_for(n, 4, 8192)), dim3(kThreads), 0,
+                       (hipStream_t)stream, q, qp, n, out);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
+
+}  // extern "C"

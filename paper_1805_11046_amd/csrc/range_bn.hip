@@ -1,0 +1,497 @@
+// Range Batch-Norm forward / backward over NCHW (Section 3, eq. (range); Section 7 for the
+// derivative of max and min).  HBM-bound streaming kernels.
+//
+// forward : stats_partial (one coalesced pass: fp64 sum, min, max per channel slice)
+//           -> finalize (per channel mean/min/max; optional per-tensor output range)
+//           -> apply (normalize, optional fused 8-bit output)          12 B/element (9 with int8 out)
+// backward: bwd_partial (fp64 sums of dy and dy*xhat) -> finalize (dgamma, dbeta, per-channel
+//           constants) -> apply (dx)                                    20 B/element
+#include "q8t_common.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxSplit = 64;
+
+struct FwdPartial {
+    double sum;
+    float mn, mx;
+};
+
+__device__ __forceinline__ double block_sum_d(double v, double *smem)
+{
+    v = wave_reduce(v, OpAddD());
+    if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double r = smem[0];
+    for (int w = 1; w < kThreads / 64; ++w) r += smem[w];
+    __syncthreads();
+    return r;
+}
+__device__ __forceinline__ float block_min_f(float v, float *smem)
+{
+    v = wave_reduce(v, OpMin());
+    if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = smem[0];
+    for (int w = 1; w < kThreads / 64; ++w) r = fminf(r, smem[w]);
+    __syncthreads();
+    return r;
+}
+__device__ __forceinline__ float block_max_f(float v, float *smem)
+{
+    v = wave_reduce(v, OpMax());
+    if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = smem[0];
+    for (int w = 1; w < kThreads / 64; ++w) r = fmaxf(r, smem[w]);
+    __syncthreads();
+    return r;
+}
+
+// 1 / (C(n)*(max-min) + eps): one fp32 rounding per operation
+__device__ __forceinline__ float bn_inv(float mn, float mx, float cn, float eps)
+{
+    const float range = mx - mn;
+    const float scaled = cn * range;
+    const float denom = scaled + eps;
+    return 1.0f / denom;
+}
+// gamma * ((x - mu) * inv) + beta, no fused operations
+__device__ __forceinline__ float bn_map(float x, float mu, float inv, float g, float b)
+{
+    const float cen = x - mu;
+    const float xh = cen * inv;
+    const float sc = xh * g;
+    return sc + b;
+}
+
+// ---- forward, pass 1 --------------------------------------------------------------------------
+// workgroup (c, sp) reduces images [sp*NB, (sp+1)*NB) of channel c
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void bn_stats_partial(const float *__restrict__ x, int N, int C,
+                                                             int HW, int NB,
+                                                             FwdPartial *__restrict__ parts)
+{
+    __shared__ double smd[kThreads / 64];
+    __shared__ float smf[kThreads / 64];
+    const int c = blockIdx.x, sp = blockIdx.y;
+    const int b0 = sp * NB, b1 = min(N, b0 + NB);
+    double sum = 0.0;
+    float mn = INFINITY, mx = -INFINITY;
+    if (VEC) {
+        const int hw4 = HW >> 2;
+        for (int b = b0; b < b1; ++b) {
+            const float4 *p = reinterpret_cast<const float4 *>(x + ((int64_t)b * C + c) * HW);
+#pragma unroll 4
+            for (int i = threadIdx.x; i < hw4; i += kThreads) {
+                const float4 v = p[i];
+                sum += (double)v.x;
+                sum += (double)v.y;
+                sum += (double)v.z;
+                sum += (double)v.w;
+                mn = fminf(fminf(mn, v.x), fminf(v.y, fminf(v.z, v.w)));
+                mx = fmaxf(fmaxf(mx, v.x), fmaxf(v.y, fmaxf(v.z, v.w)));
+            }
+        }
+    } else {
+        const int cnt = (b1 - b0) * HW;
+        for (int idx = threadIdx.x; idx < cnt; idx += kThreads) {
+            const int b = b0 + idx / HW, i = idx % HW;
+            const float v = x[((int64_t)b * C + c) * HW + i];
+            sum += (double)v;
+            mn = fminf(mn, v);
+            mx = fmaxf(mx, v);
+        }
+    }
+    sum = block_sum_d(sum, smd);
+    mn = block_min_f(mn, smf);
+    mx = block_max_f(mx, smf);
+    if (threadIdx.x == 0) {
+        FwdPartial r;
+        r.sum = sum;
+        r.mn = mn;
+        r.mx = mx;
+        parts[(int64_t)c * gridDim.y + sp] = r;
+    }
+}
+
+// ---- forward, finalize (one workgroup) ----------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void bn_fwd_finalize(const FwdPartial *__restrict__ parts, int C,
+                                                            int split, double n, float cn, float eps,
+                                                            const float *__restrict__ gamma,
+                                                            const float *__restrict__ beta,
+                                                            float *__restrict__ stats,
+                                                            q8t_qparams *__restrict__ qp_out)
+{
+    __shared__ float smf[kThreads / 64];
+    float lo = INFINITY, hi = -INFINITY;
+    for (int c = threadIdx.x; c < C; c += kThreads) {
+        double s = 0.0;
+        float mn = INFINITY, mx = -INFINITY;
+        for (int k = 0; k < split; ++k) {
+            const FwdPartial p = parts[(int64_t)c * split + k];
+            s += p.sum;
+            mn = fminf(mn, p.mn);
+            mx = fmaxf(mx, p.mx);
+        }
+        const float mu = (float)(s / n);
+        stats[c] = mu;
+        stats[C + c] = mn;
+        stats[2 * C + c] = mx;
+        if (qp_out) {
+            // images of the channel's extrema under the output map (monotone in x)
+            const float g = gamma ? gamma[c] : 1.0f, b = beta ? beta[c] : 0.0f;
+            const float inv = bn_inv(mn, mx, cn, eps);
+            const float a = bn_map(mn, mu, inv, g, b), z = bn_map(mx, mu, inv, g, b);
+            lo = fminf(lo, fminf(a, z));
+            hi = fmaxf(hi, fmaxf(a, z));
+        }
+    }
+    if (qp_out) {
+        lo = block_min_f(lo, smf);
+        hi = block_max_f(hi, smf);
+        if (threadIdx.x == 0) *qp_out = make_qparams(lo, hi, 8);
+    }
+}
+
+// ---- forward, pass 2 ----------------------------------------------------------------------------
+// one (image, channel) plane per workgroup iteration
+template <bool VEC, bool QOUT>
+__global__ __launch_bounds__(kThreads) void bn_fwd_apply(const float *__restrict__ x, int64_t planes,
+                                                         int C, int HW, const float *__restrict__ stats,
+                                                         const float *__restrict__ gamma,
+                                                         const float *__restrict__ beta, float cn,
+                                                         float eps, float *__restrict__ y,
+                                                         int8_t *__restrict__ q,
+                                                         const q8t_qparams *__restrict__ qp)
+{
+    Affine a;
+    if (QOUT) a = affine_of(*qp);
+    for (int64_t pl = blockIdx.x; pl < planes; pl += gridDim.x) {
+        const int c = (int)(pl % C);
+        const float mu = stats[c];
+        const float inv = bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
+        const float g = gamma ? gamma[c] : 1.0f, b = beta ? beta[c] : 0.0f;
+        const int64_t base = pl * HW;
+        if (VEC) {
+            const float4 *p = reinterpret_cast<const float4 *>(x + base);
+            float4 *o = reinterpret_cast<float4 *>(y + base);
+            uint32_t *oq = reinterpret_cast<uint32_t *>(q + base);
+            const int hw4 = HW >> 2;
+#pragma unroll 4
+            for (int i = threadIdx.x; i < hw4; i += kThreads) {
+                const float4 v = p[i];
+                float4 r;
+                r.x = bn_map(v.x, mu, inv, g, b);
+                r.y = bn_map(v.y, mu, inv, g, b);
+                r.z = bn_map(v.z, mu, inv, g, b);
+                r.w = bn_map(v.w, mu, inv, g, b);
+                if (y) o[i] = r;
+                if (QOUT) {
+                    const int q0 = level_of<false>(r.x, a, 0) - 128, q1 = level_of<false>(r.y, a, 0) - 128,
+                              q2 = level_of<false>(r.z, a, 0) - 128, q3 = level_of<false>(r.w, a, 0) - 128;
+                    oq[i] = (uint32_t)(q0 & 255) | ((uint32_t)(q1 & 255) << 8) |
+                            ((uint32_t)(q2 & 255) << 16) | ((uint32_t)(q3 & 255) << 24);
+                }
+            }
+        } else {
+            for (int i = threadIdx.x; i < HW; i += kThreads) {
+                const float r = bn_map(x[base + i], mu, inv, g, b);
+                if (y) y[base + i] = r;
+                if (QOUT) q[base + i] = (int8_t)(level_of<false>(r, a, 0) - 128);
+            }
+        }
+    }
+}
+
+// small planes: one thread per element
+template <bool QOUT>
+__global__ __launch_bounds__(kThreads) void bn_fwd_apply_flat(const float *__restrict__ x, int64_t total,
+                                                              int C, int HW,
+                                                              const float *__restrict__ stats,
+                                                              const float *__restrict__ gamma,
+                                                              const float *__restrict__ beta, float cn,
+                                                              float eps, float *__restrict__ y,
+                                                              int8_t *__restrict__ q,
+                                                              const q8t_qparams *__restrict__ qp)
+{
+    Affine a;
+    if (QOUT) a = affine_of(*qp);
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+        const int c = (int)((i / HW) % C);
+        const float inv = bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
+        const float r = bn_map(x[i], stats[c], inv, gamma ? gamma[c] : 1.0f, beta ? beta[c] : 0.0f);
+        if (y) y[i] = r;
+        if (QOUT) q[i] = (int8_t)(level_of<false>(r, a, 0) - 128);
+    }
+}
+
+// ---- backward, pass 1 ---------------------------------------------------------------------------
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void bn_bwd_partial(const float *__restrict__ x,
+                                                           const float *__restrict__ dy,
+                                                           const float *__restrict__ stats, int N, int C,
+                                                           int HW, int NB, float cn, float eps,
+                                                           double2 *__restrict__ parts)
+{
+    __shared__ double smd[kThreads / 64];
+    const int c = blockIdx.x, sp = blockIdx.y;
+    const int b0 = sp * NB, b1 = min(N, b0 + NB);
+    const float mu = stats[c];
+    const float inv = bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
+    double s0 = 0.0, s1 = 0.0;
+    if (VEC) {
+        const int hw4 = HW >> 2;
+        for (int b = b0; b < b1; ++b) {
+            const int64_t base = ((int64_t)b * C + c) * HW;
+            const float4 *px = reinterpret_cast<const float4 *>(x + base);
+            const float4 *pg = reinterpret_cast<const float4 *>(dy + base);
+#pragma unroll 2
+            for (int i = threadIdx.x; i < hw4; i += kThreads) {
+                const float4 v = px[i], g = pg[i];
+                const float h0 = (v.x - mu) * inv, h1 = (v.y - mu) * inv, h2 = (v.z - mu) * inv,
+                            h3 = (v.w - mu) * inv;
+                s0 += (double)g.x;
+                s0 += (double)g.y;
+                s0 += (double)g.z;
+                s0 += (double)g.w;
+                s1 += (double)g.x * (double)h0;
+                s1 += (double)g.y * (double)h1;
+                s1 += (double)g.z * (double)h2;
+                s1 += (double)g.w * (double)h3;
+            }
+        }
+    } else {
+        const int cnt = (b1 - b0) * HW;
+        for (int idx = threadIdx.x; idx < cnt; idx += kThreads) {
+            const int b = b0 + idx / HW, i = idx % HW;
+            const int64_t j = ((int64_t)b * C + c) * HW + i;
+            const float h = (x[j] - mu) * inv;
+            s0 += (double)dy[j];
+            s1 += (double)dy[j] * (double)h;
+        }
+    }
+    s0 = block_sum_d(s0, smd);
+    s1 = block_sum_d(s1, smd);
+    if (threadIdx.x == 0) parts[(int64_t)c * gridDim.y + sp] = make_double2(s0, s1);
+}
+
+__global__ __launch_bounds__(kThreads) void bn_bwd_finalize(const double2 *__restrict__ parts, int C,
+                                                            int split, double n, float cn, float eps,
+                                                            const float *__restrict__ stats,
+                                                            const float *__restrict__ gamma,
+                                                            float *__restrict__ dgamma,
+                                                            float *__restrict__ dbeta,
+                                                            float2 *__restrict__ consts)
+{
+    const int c = blockIdx.x * kThreads + threadIdx.x;
+    if (c >= C) return;
+    double s0 = 0.0, s1 = 0.0;
+    for (int k = 0; k < split; ++k) {
+        const double2 p = parts[(int64_t)c * split + k];
+        s0 += p.x;
+        s1 += p.y;
+    }
+    if (dbeta) dbeta[c] = (float)s0;
+    if (dgamma) dgamma[c] = (float)s1;
+    const float g = gamma ? gamma[c] : 1.0f;
+    const float inv = bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
+    const double A = (double)g * s0, B = (double)g * s1;
+    const float mean_g = (float)(A / n);
+    const float kb = (float)((double)inv * (double)cn * B);
+    consts[c] = make_float2(mean_g, kb);
+}
+
+// dx_j = inv*(gamma*dy_j - mean_g) -/+ kb at the coordinates that attain max / min
+__device__ __forceinline__ float bn_dx(float xv, float dyv, float g, float mean_g, float inv, float kb,
+                                       float mn, float mx)
+{
+    const float gh = g * dyv;
+    const float t = gh - mean_g;
+    float v = inv * t;
+    if (xv == mx) v = v - kb;
+    if (xv == mn) v = v + kb;
+    return v;
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void bn_bwd_apply(const float *__restrict__ x,
+                                                         const float *__restrict__ dy, int64_t planes,
+                                                         int C, int HW, const float *__restrict__ stats,
+                                                         const float *__restrict__ gamma,
+                                                         const float2 *__restrict__ consts, float cn,
+                                                         float eps, float *__restrict__ dx)
+{
+    for (int64_t pl = blockIdx.x; pl < planes; pl += gridDim.x) {
+        const int c = (int)(pl % C);
+        const float mn = stats[C + c], mx = stats[2 * C + c];
+        const float inv = bn_inv(mn, mx, cn, eps);
+        const float g = gamma ? gamma[c] : 1.0f;
+        const float2 k = consts[c];
+        const int64_t base = pl * HW;
+        if (VEC) {
+            const float4 *px = reinterpret_cast<const float4 *>(x + base);
+            const float4 *pg = reinterpret_cast<const float4 *>(dy + base);
+            float4 *o = reinterpret_cast<float4 *>(dx + base);
+            const int hw4 = HW >> 2;
+#pragma unroll 2
+            for (int i = threadIdx.x; i < hw4; i += kThreads) {
+                const float4 v = px[i], d = pg[i];
+                float4 r;
+                r.x = bn_dx(v.x, d.x, g, k.x, inv, k.y, mn, mx);
+                r.y = bn_dx(v.y, d.y, g, k.x, inv, k.y, mn, mx);
+                r.z = bn_dx(v.z, d.z, g, k.x, inv, k.y, mn, mx);
+                r.w = bn_dx(v.w, d.w, g, k.x, inv, k.y, mn, mx);
+                o[i] = r;
+            }
+        } else {
+            for (int i = threadIdx.x; i < HW; i += kThreads)
+                dx[base + i] = bn_dx(x[base + i], dy[base + i], g, k.x, inv, k.y, mn, mx);
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void bn_bwd_apply_flat(const float *__restrict__ x,
+                                                              const float *__restrict__ dy, int64_t total,
+                                                              int C, int HW,
+                                                              const float *__restrict__ stats,
+                                                              const float *__restrict__ gamma,
+                                                              const float2 *__restrict__ consts, float cn,
+                                                              float eps, float *__restrict__ dx)
+{
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+        const int c = (int)((i / HW) % C);
+        const float mn = stats[C + c], mx = stats[2 * C + c];
+        const float2 k = consts[c];
+        dx[i] = bn_dx(x[i], dy[i], gamma ? gamma[c] : 1.0f, k.x, bn_inv(mn, mx, cn, eps), k.y, mn, mx);
+    }
+}
+
+// ---- host side ------------------------------------------------------------------------------------
+int split_for(int N, int C)
+{
+    int s = (2048 + C - 1) / C;
+    if (s > kMaxSplit) s = kMaxSplit;
+    if (s > N) s = N;
+    if (s < 1) s = 1;
+    return s;
+}
+
+size_t ws_parts_bytes(int C) { return (size_t)C * kMaxSplit * sizeof(FwdPartial); }
+
+int check_shape(int N, int C, int H, int W)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return Q8T_ERR_SHAPE;
+    const int64_t hw = (int64_t)H * W;
+    if (hw > (1 << 30) || (int64_t)N * hw < 2 || (int64_t)N * hw > ((int64_t)1 << 40)) return Q8T_ERR_SHAPE;
+    if (C > 65535 * 16) return Q8T_ERR_SHAPE;
+    return Q8T_OK;
+}
+
+int planes_grid(int64_t planes) { return (int)(planes < 65536 * 16 ? planes : 65536 * 16); }
+
+}  // namespace
+
+extern "C" {
+
+double q8t_range_bn_scale(int64_t n) { return 1.0 / sqrt(2.0 * log((double)n)); }
+
+size_t q8t_range_bn_workspace_size(int N, int C, int H, int W)
+{
+    (void)N; (void)H; (void)W;
+    if (C <= 0) return 0;
+    return ws_parts_bytes(C) + (size_t)C * sizeof(float2);
+}
+
+int q8t_range_bn_fwd(const float *x, int N, int C, int H, int W, const float *gamma,
+                     const float *beta, float eps, float *y, float *stats_out, int8_t *q_out,
+                     q8t_qparams *qp_out, void *ws, void *stream)
+{
+    const int rc = check_shape(N, C, H, W);
+    if (rc) return rc;
+    if (!x || !stats_out || (q_out && !qp_out)) return Q8T_ERR_NULL;
+    if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const int HW = H * W;
+    const double n = (double)N * HW;
+    const float cn = (float)q8t_range_bn_scale((int64_t)N * HW);
+    FwdPartial *parts = (FwdPartial *)ws;
+    const int split = split_for(N, C), NB = (N + split - 1) / split;
+    const int nsplit = (N + NB - 1) / NB;
+    const bool vec = (HW % 4 == 0) && q8t_aligned(x, 16) && (!y || q8t_aligned(y, 16)) &&
+                     (!q_out || q8t_aligned(q_out, 4));
+    if (vec)
+        hipLaunchKernelGGL(bn_stats_partial<true>, dim3(C, nsplit), dim3(kThreads), 0, st, x, N, C, HW, NB, parts);
+    else
+        hipLaunchKernelGGL(bn_stats_partial<false>, dim3(C, nsplit), dim3(kThreads), 0, st, x, N, C, HW, NB, parts);
+    Q8T_LAUNCH_CHECK();
+    hipLaunchKernelGGL(bn_fwd_finalize, dim3(1), dim3(kThreads), 0, st, parts, C, nsplit, n, cn, eps, gamma,
+                       beta, stats_out, q_out ? qp_out : (q8t_qparams *)nullptr);
+    Q8T_LAUNCH_CHECK();
+    if (!y && !q_out) return Q8T_OK;
+    const int64_t planes = (int64_t)N * C;
+    if (HW >= 256) {
+        const dim3 grid(planes_grid(planes));
+#define Q8T_GO(V, Q) \
+    hipLaunchKernelGGL((bn_fwd_apply<V, Q>), grid, dim3(kThreads), 0, st, x, planes, C, HW, stats_out, gamma, beta, cn, eps, y, q_out, qp_out)
+        if (vec) { if (q_out) Q8T_GO(true, true); else Q8T_GO(true, false); }
+        else     { if (q_out) Q8T_GO(false, true); else Q8T_GO(false, false); }
+#undef Q8T_GO
+    } else {
+        const int64_t total = planes * HW;
+        const dim3 grid((unsigned)((total + kThreads - 1) / kThreads < 65536 * 16 ? (total + kThreads - 1) / kThreads : 65536 * 16));
+        if (q_out)
+            hipLaunchKernelGGL(bn_fwd_apply_flat<true>, grid, dim3(kThreads), 0, st, x, total, C, HW, stats_out, gamma, beta, cn, eps, y, q_out, qp_out);
+        else
+            hipLaunchKernelGGL(bn_fwd_apply_flat<false>, grid, dim3(kThreads), 0, st, x, total, C, HW, stats_out, gamma, beta, cn, eps, y, q_out, qp_out);
+    }
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
+
+int q8t_range_bn_bwd(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
+                     const float *gamma, float eps, float *dx, float *dgamma, float *dbeta, void *ws,
+                     void *stream)
+{
+    const int rc = check_shape(N, C, H, W);
+    if (rc) return rc;
+    if (!x || !dy || !stats) return Q8T_ERR_NULL;
+    if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const int HW = H * W;
+    const double n = (double)N * HW;
+    const float cn = (float)q8t_range_bn_scale((int64_t)N * HW);
+    double2 *parts = (double2 *)ws;
+    float2 *consts = (float2 *)((char *)ws + ws_parts_bytes(C));
+    const int split = split_for(N, C), NB = (N + split - 1) / split;
+    const int nsplit = (N + NB - 1) / NB;
+    const bool vec = (HW % 4 == 0) && q8t_aligned(x, 16) && q8t_aligned(dy, 16) && (!dx || q8t_aligned(dx, 16));
+    if (vec)
+        hipLaunchKernelGGL(bn_bwd_partial<true>, dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn, eps, parts);
+    else
+        hipLaunchKernelGGL(bn_bwd_partial<false>, dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn, eps, parts);
+    Q8T_LAUNCH_CHECK();
+    hipLaunchKernelGGL(bn_bwd_finalize, dim3((C + kThreads - 1) / kThreads), dim3(kThreads), 0, st, parts, C,
+                       nsplit, n, cn, eps, stats, gamma, dgamma, dbeta, consts);
+    Q8T_LAUNCH_CHECK();
+    if (!dx) return Q8T_OK;
+    const int64_t planes = (int64_t)N * C;
+    if (HW >= 256) {
+        const dim3 grid(planes_grid(planes));
+        if (vec)
+            hipLaunchKernelGGL(bn_bwd_apply<true>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, cn, eps, dx);
+        else
+            hipLaunchKernelGGL(bn_bwd_apply<false>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, cn, eps, dx);
+    } else {
+        const int64_t total = planes * HW;
+        const dim3 grid((unsigned)((total + kThreads - 1) / kThreads < 65536 * 16 ? (total + kThreads - 1) / kThreads : 65536 * 16));
+        hipLaunchKernelGGL(bn_bwd_apply_flat, grid, dim3(kThreads), 0, st, x, dy, total, C, HW, stats, gamma, consts, cn, eps, dx);
+    }
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,65 @@
+"""The C-ABI library loads without a GPU and exports every symbol the public header declares."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "q8t.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(q8t_[a-z0-9_]+)\s*\(", text)))
+
+
+def _lib_path():
+    path = os.path.join(ROOT, "paper_1805_11046_amd", "libq8t.so")
+    if not os.path.exists(path):
+        import __graft_entry__
+        __graft_entry__.build()
+    return path
+
+
+def test_header_declares_the_expected_calls():
+    names = _declared_functions()
+    for must in ("q8t_quantize", "q8t_quantize_with_range", "q8t_quantize_bifurcate", "q8t_dequantize",
+                 "q8t_qgemm_fwd", "q8t_qgemm_dgrad", "q8t_qgemm_wgrad", "q8t_qconv_fwd", "q8t_qconv_dgrad",
+                 "q8t_qconv_wgrad", "q8t_range_bn_fwd", "q8t_range_bn_bwd", "q8t_range_bn_scale"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(_lib_path())
+    for name in _declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_binding_covers_every_declared_symbol():
+    _lib_path()
+    from paper_1805_11046_amd import binding
+    assert sorted(binding.EXPORTED) == _declared_functions()
+
+
+def test_host_only_calls():
+    # these entry points do no GPU work: the closed form of Section 3 and size queries
+    _lib_path()
+    from paper_1805_11046_amd import binding
+    import math
+    assert binding.range_bn_scale(401408) == (2 * math.log(401408)) ** -0.5
+    assert binding._lib.q8t_quantize_workspace_size(1 << 20) >= 8
+    d = binding.conv_desc(128, 64, 56, 56, 64, 3, 3, 1, 1)
+    assert (d.P, d.Q) == (56, 56)
+    for which in (0, 1, 2):
+        assert binding._lib.q8t_qconv_workspace_size(ctypes.byref(d), which) >= 0
+    assert "gfx950" in binding.version()
+
+
+def test_argument_errors_are_reported_before_any_launch():
+    _lib_path()
+    from paper_1805_11046_amd import binding
+    L = binding._lib
+    assert L.q8t_quantize(None, 16, 8, 0, 0, None, None, None, None) == -1      # NULL
+    assert L.q8t_quantize(None, -1, 8, 0, 0, None, None, None, None) == -2      # shape
+    assert L.q8t_quantize(None, 16, 17, 0, 0, None, None, None, None) == -3     # bits
+    assert L.q8t_qgemm_fwd(None, None, None, None, 0, 1, 1, None, None, None, None) == -2
+    assert L.q8t_range_bn_fwd(None, 1, 1, 1, 1, None, None, 0.0, None, None, None, None, None, None) == -2

@@ -1,0 +1,148 @@
+"""GPU parity: FC and convolution products (forward, layer gradient, 16x8-bit weight gradient)
+vs the oracle.  Integer accumulators bit-exact, float outputs within 1e-5 / 1e-6."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_util import close, dev, host, qp_dev_from, require_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand_q(g, shape, bits=8, zp=None):
+    half = 2 ** (bits - 1)
+    lv = g.integers(0, 2 ** bits, size=shape)
+    zp = int(g.integers(0, 2 ** bits)) if zp is None else zp
+    dt = np.int8 if bits <= 8 else np.int16
+    qp = oracle.QParams(0.0, 0.0, float(np.float32(g.uniform(0.01, 0.1))), 1.0, zp, bits)
+    return (lv - half).astype(dt), qp
+
+
+FC_SHAPES = [(64, 128, 256), (1, 1, 1), (70, 50, 130), (5, 200, 64), (130, 65, 1000), (256, 1000, 512)]
+
+
+@pytest.mark.parametrize("M,N,K", FC_SHAPES)
+def test_fc_products(M, N, K):
+    q8t = require_gpu()
+    g = synth.rng(M * 1000 + N + K)
+    sx, px = _rand_q(g, (M, K))
+    sw, pw = _rand_q(g, (K, N))
+    sg, pg = _rand_q(g, (M, N))
+    sg16, pg16 = _rand_q(g, (M, N), bits=16)
+    dpx, dpw, dpg, dpg16 = (qp_dev_from(p) for p in (px, pw, pg, pg16))
+    y, acc = q8t.qgemm_fwd(dev(sx), dpx, dev(sw), dpw, want_acc=True)
+    oy, oacc = oracle.qgemm_fwd(sx, px, sw, pw)
+    assert np.array_equal(host(acc).astype(np.int64), oacc)
+    close(host(y), oy)
+    dx, acc = q8t.qgemm_dgrad(dev(sg), dpg, dev(sw), dpw, want_acc=True)
+    odx, oacc = oracle.qgemm_dgrad(sg, pg, sw, pw)
+    assert np.array_equal(host(acc).astype(np.int64), oacc)
+    close(host(dx), odx)
+    dw, acc = q8t.qgemm_wgrad(dev(sx), dpx, dev(sg16), dpg16, want_acc=True)
+    odw, oacc = oracle.qgemm_wgrad(sx, px, sg16, pg16)
+    assert np.array_equal(host(acc), oacc)
+    close(host(dw), odw)
+
+
+def test_fc_extreme_codes_do_not_overflow():
+    # all codes at the far end from the zero point, reduction length at the contract's limit
+    q8t = require_gpu()
+    M, N, K = 16, 16, 33025
+    sx = np.full((M, K), 127, np.int8)
+    sw = np.full((K, N), 127, np.int8)
+    px = oracle.QParams(0, 0, 1.0, 1.0, 0, 8)
+    pw = oracle.QParams(0, 0, 1.0, 1.0, 0, 8)
+    y, acc = q8t.qgemm_fwd(dev(sx), qp_dev_from(px), dev(sw), qp_dev_from(pw), want_acc=True)
+    assert (host(acc) == 255 * 255 * K).all()
+    with pytest.raises(q8t.binding.Q8TError) as e:
+        q8t.qgemm_fwd(dev(np.zeros((2, K + 1), np.int8)), qp_dev_from(px), dev(np.zeros((K + 1, 2), np.int8)),
+                      qp_dev_from(pw))
+    assert e.value.code == -4
+
+
+def test_config0_layer_step():
+    # FC 64x256x128: quantize -> forward; bifurcated dY -> dgrad, wgrad; all through the C ABI
+    q8t = require_gpu()
+    x, w, dy = synth.fc_layer(seed=0)
+    qx, px = q8t.quantize(dev(x), 8)
+    qw, pw = q8t.quantize(dev(w), 8)
+    g8, pg8, g16, pg16 = q8t.quantize_bifurcate(dev(dy), seed8=11, seed16=12)
+    y, acc = q8t.qgemm_fwd(qx, px, qw, pw, want_acc=True)
+    dx, accd = q8t.qgemm_dgrad(g8, pg8, qw, pw, want_acc=True)
+    dw, accw = q8t.qgemm_wgrad(qx, px, g16, pg16, want_acc=True)
+    sx, _, opx = oracle.quantize(x, 8)
+    sw, _, opw = oracle.quantize(w, 8)
+    s8, _, o8 = oracle.quantize(dy, 8, True, seed=11)
+    s16, _, o16 = oracle.quantize(dy, 16, True, seed=12)
+    oy, oacc = oracle.qgemm_fwd(sx, opx, sw, opw)
+    odx, oaccd = oracle.qgemm_dgrad(s8, o8, sw, opw)
+    odw, oaccw = oracle.qgemm_wgrad(sx, opx, s16, o16)
+    assert np.array_equal(host(acc).astype(np.int64), oacc)
+    assert np.array_equal(host(accd).astype(np.int64), oaccd)
+    assert np.array_equal(host(accw), oaccw)
+    close(host(y), oy)
+    close(host(dx), odx)
+    close(host(dw), odw)
+
+
+CONV_CASES = [
+    # N, C, H, W, K, R, S, stride, pad
+    (2, 3, 7, 6, 4, 3, 3, 1, 1),
+    (1, 2, 9, 9, 3, 3, 3, 2, 1),
+    (2, 4, 5, 5, 3, 1, 1, 1, 0),
+    (1, 3, 8, 8, 2, 1, 1, 2, 0),
+    (1, 3, 23, 22, 5, 7, 7, 2, 3),
+    (2, 64, 14, 14, 64, 3, 3, 1, 1),     # specialised-kernel shape, small
+    (3, 64, 56, 56, 64, 3, 3, 1, 1),     # config-2 layer at batch 3
+    (2, 128, 12, 12, 64, 3, 3, 1, 1),
+    (2, 256, 10, 10, 64, 1, 1, 1, 0),    # bottleneck 1x1 reduce
+    (2, 64, 10, 10, 256, 1, 1, 1, 0),    # bottleneck 1x1 expand
+    (2, 64, 16, 16, 128, 3, 3, 2, 1),    # stride-2 3x3
+    (2, 64, 16, 16, 128, 1, 1, 2, 0),    # stride-2 1x1 downsample
+    (2, 16, 9, 9, 24, 3, 3, 1, 1),
+    (1, 80, 7, 7, 72, 3, 3, 1, 1),       # channels not a multiple of 64
+]
+
+
+def _conv_operands(g, case):
+    N, C, H, W, K, R, S, st, pad = case
+    od = oracle.conv_desc(*case)
+    sx, px = _rand_q(g, (N, C, H, W))
+    sw, pw = _rand_q(g, (K, C, R, S))
+    sg, pg = _rand_q(g, (N, K, od.P, od.Q))
+    sg16, pg16 = _rand_q(g, (N, K, od.P, od.Q), bits=16)
+    return od, (sx, px), (sw, pw), (sg, pg), (sg16, pg16)
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_products(case):
+    q8t = require_gpu()
+    g = synth.rng(sum(case))
+    od, (sx, px), (sw, pw), (sg, pg), (sg16, pg16) = _conv_operands(g, case)
+    d = q8t.conv_desc(*case)
+    dpx, dpw, dpg, dpg16 = (qp_dev_from(p) for p in (px, pw, pg, pg16))
+    y, acc = q8t.qconv_fwd(d, dev(sx), dpx, dev(sw), dpw, want_acc=True)
+    oy, oacc = oracle.qconv_fwd(od, sx, px, sw, pw)
+    assert np.array_equal(host(acc).astype(np.int64), oacc)
+    close(host(y), oy)
+    dx, acc = q8t.qconv_dgrad(d, dev(sg), dpg, dev(sw), dpw, want_acc=True)
+    odx, oacc = oracle.qconv_dgrad(od, sg, pg, sw, pw)
+    assert np.array_equal(host(acc).astype(np.int64), oacc)
+    close(host(dx), odx)
+    dw, acc = q8t.qconv_wgrad(d, dev(sx), dpx, dev(sg16), dpg16, want_acc=True)
+    odw, oacc = oracle.qconv_wgrad(od, sx, px, sg16, pg16)
+    assert np.array_equal(host(acc), oacc)
+    close(host(dw), odw)
+
+
+def test_conv_float_only_and_acc_only_outputs_agree():
+    q8t = require_gpu()
+    case = (2, 64, 14, 14, 64, 3, 3, 1, 1)
+    g = synth.rng(5)
+    od, (sx, px), (sw, pw), _, _ = _conv_operands(g, case)
+    d = q8t.conv_desc(*case)
+    dpx, dpw = qp_dev_from(px), qp_dev_from(pw)
+    y1, acc1 = q8t.qconv_fwd(d, dev(sx), dpx, dev(sw), dpw, want_acc=True)
+    y2, _ = q8t.qconv_fwd(d, dev(sx), dpx, dev(sw), dpw, want_acc=False)
+    assert np.array_equal(host(y1), host(y2))

@@ -1,0 +1,122 @@
+"""GPU parity: Range BN forward/backward vs the oracle.
+
+min/max are order-independent and must be bit-equal; the mean and the backward sums are long
+float sums (fp64 on both sides, different order), compared within tolerance.  Everything
+elementwise is then checked bit for bit by re-running the oracle's elementwise stage on the
+GPU's own statistics."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_util import close, dev, host, require_gpu, same_qparams
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [(8, 5, 6, 7),      # ragged, scalar path
+          (4, 3, 8, 8),      # small planes
+          (6, 7, 16, 16),    # vector path
+          (3, 2, 40, 36),    # several sweeps per plane, ragged tail inside a plane
+          (64, 128, 1, 1),   # FC activations (config 0)
+          (2, 1, 1, 1),      # smallest legal n
+          (5, 70, 20, 20)]
+
+
+def _inputs(shape, seed):
+    g = synth.rng(seed)
+    N, C, H, W = shape
+    x = (g.standard_normal(shape) * g.uniform(0.1, 3, (1, C, 1, 1)) + g.uniform(-2, 2, (1, C, 1, 1))).astype(np.float32)
+    dy = synth.normal(g, shape, std=1e-2)
+    gamma = g.uniform(-2, 2, C).astype(np.float32)
+    beta = g.uniform(-1, 1, C).astype(np.float32)
+    return x, dy, gamma, beta
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("affine", [False, True])
+@pytest.mark.parametrize("eps", [0.0, 1e-5])
+def test_forward(shape, affine, eps):
+    q8t = require_gpu()
+    x, _, gamma, beta = _inputs(shape, 1)
+    if not affine:
+        gamma = beta = None
+    y, stats, q, qp = q8t.range_bn_fwd(dev(x), None if gamma is None else dev(gamma),
+                                       None if beta is None else dev(beta), eps, quantized=True)
+    oy, ostats, _, _ = oracle.range_bn_fwd(x, gamma, beta, eps)
+    st = host(stats)
+    assert np.array_equal(st[1:], ostats[1:])          # min, max: exact
+    close(st[0], ostats[0])                            # mean: fp64 sums in a different order
+    close(host(y), oy)
+    # elementwise stage, bit for bit, on the GPU's statistics
+    fy, _, fq, fqp = oracle.range_bn_fwd(x, gamma, beta, eps, stats=st, quantized=True)
+    assert np.array_equal(host(y), fy)
+    same_qparams(q8t, qp, fqp)
+    assert np.array_equal(host(q), fq)
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("affine", [False, True])
+def test_backward(shape, affine):
+    q8t = require_gpu()
+    x, dy, gamma, _ = _inputs(shape, 2)
+    if not affine:
+        gamma = None
+    eps = 1e-5
+    ostats = oracle.range_bn_stats(x)
+    dx, dgamma, dbeta = q8t.range_bn_bwd(dev(x), dev(dy), dev(ostats), None if gamma is None else dev(gamma), eps)
+    odx, odg, odb = oracle.range_bn_bwd(x, dy, ostats, gamma, eps)
+    close(host(dgamma), odg)
+    close(host(dbeta), odb)
+    close(host(dx), odx)
+
+
+def test_ties_at_the_extrema():
+    q8t = require_gpu()
+    g = synth.rng(9)
+    x = g.standard_normal((4, 2, 8, 8)).astype(np.float32)
+    x[0, 0, 0, 0] = x[3, 0, 5, 5] = 9.0
+    x[1, 0, 2, 2] = x[2, 0, 7, 1] = -9.0
+    x[:, 1] = 1.25  # constant channel: max == min everywhere
+    dy = g.standard_normal(x.shape).astype(np.float32)
+    stats = oracle.range_bn_stats(x)
+    dx, _, _ = q8t.range_bn_bwd(dev(x), dev(dy), dev(stats), None, 1e-3)
+    odx, _, _ = oracle.range_bn_bwd(x, dy, stats, None, 1e-3)
+    close(host(dx), odx)
+    y, st, _, _ = q8t.range_bn_fwd(dev(x), eps=1e-3)
+    oy, _, _, _ = oracle.range_bn_fwd(x, eps=1e-3, stats=host(st))
+    assert np.array_equal(host(y), oy)
+
+
+def test_config1_full_size():
+    # 128x64x56x56, half Gaussian / half Laplace channels, 8-bit per-tensor output, eps 1e-5
+    q8t = require_gpu()
+    x, dy = synth.range_bn_input(seed=0)
+    xd, dyd = dev(x), dev(dy)
+    y, stats, q, qp = q8t.range_bn_fwd(xd, eps=1e-5, quantized=True)
+    oy, ostats, _, _ = oracle.range_bn_fwd(x, eps=1e-5)
+    st = host(stats)
+    assert np.array_equal(st[1:], ostats[1:])
+    close(st[0], ostats[0])
+    close(host(y), oy)
+    fy, _, fq, fqp = oracle.range_bn_fwd(x, eps=1e-5, stats=st, quantized=True)
+    assert np.array_equal(host(y), fy)
+    same_qparams(q8t, qp, fqp)
+    assert np.array_equal(host(q), fq)
+    n_unforced = int((host(q) != oracle.range_bn_fwd(x, eps=1e-5, quantized=True)[2]).sum())
+    print("int8 codes differing from the un-forced oracle run:", n_unforced, "of", x.size)
+    assert n_unforced <= x.size * 1e-5
+    dx, dgamma, dbeta = q8t.range_bn_bwd(xd, dyd, stats, None, 1e-5)
+    odx, odg, odb = oracle.range_bn_bwd(x, dy, st, None, 1e-5)
+    close(host(dbeta), odb)
+    close(host(dgamma), odg)
+    close(host(dx), odx)
+    # int8-only output (no fp32 y written) gives the same codes
+    _, _, q2, _ = q8t.range_bn_fwd(xd, eps=1e-5, quantized=True, want_y=False)
+    assert np.array_equal(host(q2), host(q))
+
+
+def test_rejects_degenerate_batch():
+    q8t = require_gpu()
+    with pytest.raises(q8t.binding.Q8TError) as e:
+        q8t.range_bn_fwd(dev(np.ones((1, 3, 1, 1), np.float32)))
+    assert e.value.code == -2

@@ -229,3 +229,12 @@ def test_matches_numpy_float32_sequence():
     ref = np.clip(np.rint(t), 0, 255).astype(np.int32)
     assert (qp.scale, qp.inv_scale, qp.zero_point) == (scale, inv, zp)
     assert np.array_equal(lv, ref)
+
+
+def test_values_outside_a_supplied_range_saturate():
+    # range [-1, 2]: scale 3/255, zero point 85, both ends on the grid
+    x = np.array([-1e30, -5.0, -1.0, 0.0, 2.0, 5.0, 1e30, 3e9], np.float32)
+    for stochastic in (False, True):
+        _, lv, qp = oracle.quantize(x, 8, stochastic=stochastic, seed=3, vrange=(-1.0, 2.0))
+        assert qp.zero_point == 85
+        assert list(lv) == [0, 0, 0, 85, 255, 255, 255, 255]
