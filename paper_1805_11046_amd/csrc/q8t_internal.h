@@ -20,3 +20,10 @@ bool q8t_fast_conv_supported(int which, const q8t_conv_desc *d, const void *a, c
 size_t q8t_fast_conv_ws(int which, const q8t_conv_desc *d);
 int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
                   const q8t_qparams *qb, float *out_f, void *out_acc, void *ws, hipStream_t st);
+
+// specialised 3x3 weight-gradient kernel (wgrad_fast.hip)
+bool q8t_fast_wgrad_supported(const q8t_conv_desc *d, const void *g16, const void *x, const void *dw,
+                              const void *acc);
+size_t q8t_fast_wgrad_ws(const q8t_conv_desc *d);
+int q8t_fast_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams *qg, const int8_t *x,
+                   const q8t_qparams *qx, float *dw, int64_t *acc_out, void *ws, hipStream_t st);

@@ -1,0 +1,343 @@
+// Specialised weight-gradient kernel for stride-1 3x3 (pad 1) convolutions:
+//   dW[k,c,r,s] = sum_{n,p,q} g16[n,k,p,q] * x8[n,c,p+r-1,q+s-1]        (Section 4, eq. (grad_weight))
+// with the 16-bit copy of the gradient (Sections 1, 7) and the 8-bit layer input, exact in integers.
+//
+// GEMM view: rows = output channel k, cols = (input channel c, tap), reduction = (image, position).
+// Both operands are contiguous along the reduction in NCHW, so nothing is transposed.  The 16-bit
+// operand is split into two signed bytes (s = 256*hi + lo + 128) and run as two int8 MFMA products.
+//
+// Padding without masks: inside LDS every image row is given a pitch of W+4 bytes; the 4 spare
+// bytes hold the operand's zero point.  In that "padded-pitch" index space a tap is a pure byte
+// offset ((r-1)*pitch + (s-1)), a pad column serves as right border of one row and left border
+// of the next, and positions before/after the image are zero-point rows.  The gradient operand is
+// staged with the same pitch (zero code in the pad columns), so pad positions contribute nothing.
+// The three horizontal taps of a row come from one 24-byte aligned read, shifted with
+// v_alignbyte.
+//
+// Work split: the output is tiny (K*C*9) and the reduction huge (N*H*W), so the reduction is split
+// three ways: across workgroups (k-ranges of whole images), across the 4 wavefront pairs of a
+// workgroup (interleaved 64-position K-steps, summed through LDS at the end) and in time.  A
+// workgroup owns 64 rows x 16 channels x 9 taps x 2 byte planes = 72 MFMA tiles; wavefront
+// (plane, lane-of-K) holds 36 of them.  Per-slice int32 partials (each slice is far below the
+// 32-bit bound) are combined in int64 by wgrad_reduce, which also applies the zero-point
+// correction from the row / column sums gathered with v_dot4 beside the MFMAs.
+#include "q8t_common.h"
+#include "q8t_internal.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 512;
+constexpr int KC = 256;               // padded positions per staged chunk (4 K-steps of 64)
+constexpr int APITCH = KC + 16;       // LDS bytes per gradient row and byte plane
+constexpr int HALO = 64;              // staged halo on either side of the input chunk (>= pitch+1, mult. of 4)
+constexpr int BROW = KC + 2 * HALO;   // staged input bytes per channel
+constexpr int BPITCH = BROW + 20;     // 404 bytes = 101 dwords: at most 2-way bank conflicts for the
+                                      // (16 channels x 4 k-blocks) dword reads of one wavefront
+constexpr int A_BYTES = 2 * 64 * APITCH;
+constexpr int B_BYTES = 16 * BPITCH;
+constexpr int TILE_INTS = 2 * 4 * 9 * 4 * 64;          // [plane][mt][tap][j][lane]
+constexpr int PART_INTS = TILE_INTS + 9 * 16 + 2 * 64; // + column sums [tap][ch] + row sums [plane][row]
+constexpr int SLOT_INTS = 36 * 4 * 64 + 16 * 64;       // one wavefront's accumulators + its sums
+constexpr int SMEM_BYTES = 2 * SLOT_INTS * 4;          // reduction slots (larger than the staging area)
+
+struct WGeom {
+    int N, C, K, H, W, PQ;
+    int pitch, Lp;        // padded row pitch, padded positions per image (H*pitch)
+    int chunks;           // chunks per image
+    int ncg, nrg;         // channel groups (C/16), row groups (K/64)
+    int S, ipr;           // k-ranges, images per k-range
+};
+
+__device__ __forceinline__ int dot4_ones(int v, int acc) { return __builtin_amdgcn_sdot4(v, 0x01010101, acc, false); }
+
+__global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restrict__ g16,
+                                                          const int8_t *__restrict__ x,
+                                                          const q8t_qparams *__restrict__ qpg,
+                                                          const q8t_qparams *__restrict__ qpx, WGeom g,
+                                                          int *__restrict__ partial)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    uint8_t *As = smem;              // [plane][row][APITCH]
+    uint8_t *Bs = smem + A_BYTES;    // [channel][BPITCH]
+
+    // XCD-aware decode: workgroups that share a k-range (same gradient rows) sit on one XCD
+    const int bid = blockIdx.x;
+    const int xcd = bid & 7, jj = bid >> 3;
+    const int per = g.ncg * g.nrg;
+    const int sub = jj % per, kr = (jj / per) * 8 + xcd;
+    if (kr >= g.S) return;
+    const int cg = sub % g.ncg, rg = sub / g.ncg;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int plane = wave & 1, kl = wave >> 1;
+    const int l16 = lane & 15, kb = lane >> 4;
+
+    const int zsg = qpg->zero_point - 32768, zsx = qpx->zero_point - 128;
+    const uint32_t a_pad = (uint32_t)(zsg & 0xFFFF) * 0x00010001u;   // two zero codes
+    const uint32_t b_pad = (uint32_t)(zsx & 255) * 0x01010101u;
+
+    const int img0 = kr * g.ipr, img1 = min(g.N, img0 + g.ipr);
+    const int units = (img1 - img0) * g.chunks;
+
+    v4i acc[4][9];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int t = 0; t < 9; ++t) acc[i][t] = (v4i){0, 0, 0, 0};
+    int cs[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    int rs[4] = {0, 0, 0, 0};
+
+    uint2 regA[8];
+    uint32_t regB[3];
+
+    auto load_regs = [&](int u) {
+        const int b = img0 + u / g.chunks, kp0 = (u % g.chunks) * KC;
+        {   // gradient rows: wavefront w stages rows w, w+8, ...; lane = group of 4 positions
+            const int kp = kp0 + 4 * lane;
+            const int p = kp / g.pitch, qq = kp - p * g.pitch;
+            const bool valid = kp < g.Lp && qq < g.W;
+            const int16_t *src = g16 + ((int64_t)b * g.K + rg * 64 + wave) * g.PQ + p * g.W + qq;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                regA[i] = make_uint2(a_pad, a_pad);
+                if (valid) regA[i] = *reinterpret_cast<const uint2 *>(src + (int64_t)i * 8 * g.PQ);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {   // input: 16 channels x 96 groups of 4 positions
+            const int idx = tid + kThreads * i;
+            const int c = idx / 96, gi = idx - c * 96;
+            const int kp = kp0 - HALO + 4 * gi;
+            bool valid = kp >= 0 && kp < g.Lp;
+            const int kpc = valid ? kp : 0;
+            const int p = kpc / g.pitch, qq = kpc - p * g.pitch;
+            valid = valid && qq < g.W;
+            regB[i] = b_pad;
+            if (valid)
+                regB[i] = *reinterpret_cast<const uint32_t *>(x + ((int64_t)b * g.C + cg * 16 + c) * g.PQ + p * g.W + qq);
+        }
+    };
+    auto write_lds = [&]() {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = wave + 8 * i;
+            const uint32_t hi = __builtin_amdgcn_perm(regA[i].y, regA[i].x, 0x07050301);
+            const uint32_t lo = __builtin_amdgcn_perm(regA[i].y, regA[i].x, 0x06040200) ^ 0x80808080u;
+            *reinterpret_cast<uint32_t *>(&As[row * APITCH + 4 * lane]) = hi;
+            *reinterpret_cast<uint32_t *>(&As[64 * APITCH + row * APITCH + 4 * lane]) = lo;
+        }
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const int idx = tid + kThreads * i;
+            const int c = idx / 96, gi = idx - c * 96;
+            *reinterpret_cast<uint32_t *>(&Bs[c * BPITCH + 4 * gi]) = regB[i];
+        }
+    };
+
+    if (units > 0) load_regs(0);
+    for (int u = 0; u < units; ++u) {
+        __syncthreads();
+        write_lds();
+        __syncthreads();
+        if (u + 1 < units) load_regs(u + 1);
+        const int kstart = (u % g.chunks) * KC + kl * 64;
+        if (kstart < g.Lp) {
+            v4i a[4];
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+                a[mt] = *reinterpret_cast<const v4i *>(&As[plane * 64 * APITCH + (mt * 16 + l16) * APITCH + kl * 64 + kb * 16]);
+                rs[mt] = dot4_ones(a[mt][0], dot4_ones(a[mt][1], dot4_ones(a[mt][2], dot4_ones(a[mt][3], rs[mt]))));
+            }
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                const int base = HALO + kl * 64 + kb * 16 + (r - 1) * g.pitch - 4;
+                uint32_t d[6];
+#pragma unroll
+                for (int i = 0; i < 6; ++i) d[i] = *reinterpret_cast<const uint32_t *>(&Bs[l16 * BPITCH + base + 4 * i]);
+                v4i f[3];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    f[0][i] = (int)__builtin_amdgcn_alignbyte(d[i + 1], d[i], 3);
+                    f[1][i] = (int)d[i + 1];
+                    f[2][i] = (int)__builtin_amdgcn_alignbyte(d[i + 2], d[i + 1], 1);
+                }
+#pragma unroll
+                for (int s = 0; s < 3; ++s) {
+                    const int tap = r * 3 + s;
+                    cs[tap] = dot4_ones(f[s][0], dot4_ones(f[s][1], dot4_ones(f[s][2], dot4_ones(f[s][3], cs[tap]))));
+#pragma unroll
+                    for (int mt = 0; mt < 4; ++mt)
+                        acc[mt][tap] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mt], f[s], acc[mt][tap], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // fold the 4 k-blocks of the row / column sums
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        cs[t] += __shfl_xor(cs[t], 16, 64);
+        cs[t] += __shfl_xor(cs[t], 32, 64);
+    }
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+        rs[mt] += __shfl_xor(rs[mt], 16, 64);
+        rs[mt] += __shfl_xor(rs[mt], 32, 64);
+    }
+
+    // ---- sum the 4 K-lanes of each plane through LDS: (1 -> 0), (3 -> 2), then (2 -> 0) ----
+    int *slots = reinterpret_cast<int *>(smem);
+    for (int round = 0; round < 3; ++round) {
+        const int src = round == 0 ? 1 : (round == 1 ? 3 : 2);
+        const int dst = round == 0 ? 0 : (round == 1 ? 2 : 0);
+        int *slot = slots + plane * SLOT_INTS;
+        __syncthreads();
+        if (kl == src) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int t = 0; t < 9; ++t)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) slot[((mt * 9 + t) * 4 + j) * 64 + lane] = acc[mt][t][j];
+#pragma unroll
+            for (int t = 0; t < 9; ++t) slot[36 * 4 * 64 + t * 64 + lane] = cs[t];
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) slot[36 * 4 * 64 + (9 + mt) * 64 + lane] = rs[mt];
+        }
+        __syncthreads();
+        if (kl == dst) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int t = 0; t < 9; ++t)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[mt][t][j] += slot[((mt * 9 + t) * 4 + j) * 64 + lane];
+#pragma unroll
+            for (int t = 0; t < 9; ++t) cs[t] += slot[36 * 4 * 64 + t * 64 + lane];
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) rs[mt] += slot[36 * 4 * 64 + (9 + mt) * 64 + lane];
+        }
+    }
+
+    // ---- K-lane 0 of each plane writes the workgroup's partial, in register-tile order ----
+    if (kl == 0) {
+        int *out = partial + ((int64_t)(kr * g.nrg + rg) * g.ncg + cg) * PART_INTS;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int t = 0; t < 9; ++t)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    out[(((plane * 4 + mt) * 9 + t) * 4 + j) * 64 + lane] = acc[mt][t][j];
+        if (kb == 0) {
+            if (plane == 0) {
+#pragma unroll
+                for (int t = 0; t < 9; ++t) out[TILE_INTS + t * 16 + l16] = cs[t];
+            }
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) out[TILE_INTS + 144 + plane * 64 + mt * 16 + l16] = rs[mt];
+        }
+    }
+}
+
+// int64 reduction over the k-ranges + zero-point correction + dequantization
+__global__ __launch_bounds__(256) void wgrad_reduce(const int *__restrict__ partial, WGeom g,
+                                                    const q8t_qparams *__restrict__ qpg,
+                                                    const q8t_qparams *__restrict__ qpx, float *__restrict__ dw,
+                                                    int64_t *__restrict__ acc_out)
+{
+    const int sub = blockIdx.y;               // (rg, cg)
+    const int cg = sub % g.ncg, rg = sub / g.ncg;
+    const int idx = blockIdx.x * 256 + threadIdx.x;   // ((mt*9 + tap)*4 + j)*64 + lane, < 9216
+    const int lane = idx & 63, j = (idx >> 6) & 3, mt_tap = idx >> 8;
+    const int tap = mt_tap % 9, mt = mt_tap / 9;
+    const int row_l = mt * 16 + (lane >> 4) * 4 + j, ch_l = lane & 15;
+
+    const int zsg = qpg->zero_point - 32768, zsx = qpx->zero_point - 128;
+    const double sc = (double)(qpg->scale * qpx->scale);
+    const int64_t ca = 128 - zsg;
+    const int ksteps_img = (g.Lp + 63) / 64;
+    int64_t v = 0;
+    for (int kr = 0; kr < g.S; ++kr) {
+        const int *p = partial + ((int64_t)(kr * g.nrg + rg) * g.ncg + cg) * PART_INTS;
+        const int nimg = min(g.N, (kr + 1) * g.ipr) - kr * g.ipr;
+        const int64_t Kp = (int64_t)nimg * ksteps_img * 64;
+        const int64_t hi = p[idx], lo = p[TILE_INTS / 2 + idx];
+        const int64_t csv = p[TILE_INTS + tap * 16 + ch_l];
+        const int64_t rsh = p[TILE_INTS + 144 + row_l], rsl = p[TILE_INTS + 144 + 64 + row_l];
+        v += 256 * hi + lo + ca * csv - (int64_t)zsx * (256 * rsh + rsl + ca * Kp);
+    }
+    const int64_t o = ((int64_t)(rg * 64 + row_l) * g.C + cg * 16 + ch_l) * 9 + tap;
+    if (acc_out) acc_out[o] = v;
+    if (dw) dw[o] = (float)((double)v * sc);
+}
+
+bool wgrad_shape_ok(const q8t_conv_desc *d)
+{
+    if (d->stride != 1 || d->R != 3 || d->S != 3 || d->pad != 1) return false;
+    if (d->K % 64 || d->C % 16 || d->W % 4) return false;
+    if (d->W + 4 + 1 > HALO || d->H < 1) return false;
+    // every k-range stays far below the 32-bit partial bound: 2^14 * positions < 2^31
+    return true;
+}
+
+WGeom wgrad_geom(const q8t_conv_desc *d)
+{
+    WGeom g;
+    g.N = d->N; g.C = d->C; g.K = d->K; g.H = d->H; g.W = d->W; g.PQ = d->H * d->W;
+    g.pitch = d->W + 4;
+    g.Lp = d->H * g.pitch;
+    g.chunks = (g.Lp + KC - 1) / KC;
+    g.ncg = d->C / 16;
+    g.nrg = d->K / 64;
+    int want = 256 / (g.ncg * g.nrg);        // one workgroup per compute unit
+    if (want < 1) want = 1;
+    if (want > d->N) want = d->N;
+    g.ipr = (d->N + want - 1) / want;
+    // bound the positions per k-range so that 2^14 * padded positions stays below 2^31
+    const int max_ipr = (int)(((int64_t)1 << 16) / (g.Lp + 64));
+    if (g.ipr > max_ipr) g.ipr = max_ipr > 0 ? max_ipr : 1;
+    g.S = (d->N + g.ipr - 1) / g.ipr;
+    return g;
+}
+
+}  // namespace
+
+bool q8t_fast_wgrad_supported(const q8t_conv_desc *d, const void *g16, const void *x, const void *dw,
+                              const void *acc)
+{
+    if (!wgrad_shape_ok(d)) return false;
+    if ((int64_t)d->H * (d->W + 4) + 64 > ((int64_t)1 << 16)) return false;
+    return q8t_aligned(g16, 8) && q8t_aligned(x, 4) && q8t_aligned(dw, 4) && q8t_aligned(acc, 8);
+}
+
+size_t q8t_fast_wgrad_ws(const q8t_conv_desc *d)
+{
+    if (!wgrad_shape_ok(d)) return 0;
+    const WGeom g = wgrad_geom(d);
+    return (size_t)g.S * g.nrg * g.ncg * PART_INTS * sizeof(int);
+}
+
+int q8t_fast_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams *qg, const int8_t *x,
+                   const q8t_qparams *qx, float *dw, int64_t *acc_out, void *ws, hipStream_t st)
+{
+    if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    const WGeom g = wgrad_geom(d);
+    static bool attr = false;
+    if (!attr) {
+        if (hipFuncSetAttribute((const void *)wgrad_s1_3x3, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                SMEM_BYTES) != hipSuccess)
+            return Q8T_ERR_HIP;
+        attr = true;
+    }
+    const int per = g.ncg * g.nrg;
+    const int blocks = ((g.S + 7) / 8) * 8 * per;
+    hipLaunchKernelGGL(wgrad_s1_3x3, dim3(blocks), dim3(kThreads), SMEM_BYTES, st, g16, x, qg, qx, g, (int *)ws);
+    Q8T_LAUNCH_CHECK();
+    hipLaunchKernelGGL(wgrad_reduce, dim3(9216 / 256, per), dim3(256), 0, st, (const int *)ws, g, qg, qx, dw,
+                       acc_out);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}

@@ -102,6 +102,11 @@ CONV_CASES = [
     (2, 64, 16, 16, 128, 1, 1, 2, 0),    # stride-2 1x1 downsample
     (2, 16, 9, 9, 24, 3, 3, 1, 1),
     (1, 80, 7, 7, 72, 3, 3, 1, 1),       # channels not a multiple of 64
+    (5, 32, 8, 8, 128, 3, 3, 1, 1),      # specialised weight gradient: 2 row groups, short images
+    (3, 64, 28, 28, 64, 3, 3, 1, 1),
+    (20, 16, 4, 8, 64, 3, 3, 1, 1),      # more images than one per workgroup, non-square
+    (2, 192, 8, 12, 192, 3, 3, 1, 1),
+    (1, 64, 60, 56, 64, 3, 3, 1, 1),     # last chunk of the image is ragged
 ]
 
 
