@@ -28,18 +28,41 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
-constexpr int BM = 256;          // rows per workgroup
+constexpr int BM = 256;          // rows per sub-tile
 constexpr int CH = 64;           // channels per reduction chunk / output channels per workgroup
-constexpr int ROWB = 80;         // LDS bytes per staged row
-constexpr int MAX_W = 64;        // widest image row the 3x3 variant stages
-constexpr int MAX_STAGE_ROWS = BM + 2 * (MAX_W + 1) + 8;
+constexpr int ROWB = 80;         // LDS bytes per staged activation row (64 + 16: conflict-free b128 reads)
+constexpr int MAXR9 = 464;       // staged rows (padded coordinates) of the 3x3 variant
+constexpr int MAXR1 = BM;        // 1x1 variant: no halo, no padding
+constexpr int MAX_SLABS = 7;     // staging iterations per wavefront
+constexpr int kSkip = -1000000;  // marks a staging slot with nothing to store
+
+struct FastDiv {
+    uint32_t d;
+    float r;
+};
 
 struct FastGeom {
     int N, C, K;      // images, reduction channels, output channels
     int H, W, PQ;     // plane
-    int64_t M;        // N * PQ
-    int tiles;        // ceil(M / BM)
+    int M;            // N * PQ (< 2^31)
+    FastDiv dPQ, dW, dIMG, dW1;
 };
+
+// quotient of n / d for quotients below 2^16 (image index, row index): float estimate + fix-up
+__device__ __forceinline__ uint32_t fdiv(uint32_t n, const FastDiv fd)
+{
+    uint32_t q = (uint32_t)((float)n * fd.r);
+    const int32_t rem = (int32_t)(n - q * fd.d);
+    if (rem < 0) --q;
+    else if ((uint32_t)rem >= fd.d) ++q;
+    return q;
+}
+template <int D>
+__device__ __forceinline__ uint32_t divc(uint32_t n, const FastDiv fd)
+{
+    if (D > 0) return n / (uint32_t)(D > 0 ? D : 1);
+    return fdiv(n, fd);
+}
 
 // ---- weight pre-pass: repack + per-output-channel sums -----------------------------------------
 // out[(oc/64)][cc][tap][oc%64][ch%64] = W'(oc, ch, tap);  forward: W'(oc,ch,r,s) = W[oc][ch][r][s];
@@ -88,31 +111,47 @@ __device__ __forceinline__ void transpose4x4(const uint32_t in[4], uint32_t out[
 
 __device__ __forceinline__ int dot4_ones(int v, int acc) { return __builtin_amdgcn_sdot4(v, 0x01010101, acc, false); }
 
-// XCD-aware order: consecutive workgroup ids go round-robin over the 8 XCDs; give each XCD one
-// contiguous run of tiles so that neighbouring tiles (which share halo rows) share an L2.
-__device__ __forceinline__ int xcd_tile(int bid, int tiles)
-{
-    const int per = (tiles + 7) / 8;
-    const int t = (bid & 7) * per + (bid >> 3);
-    return t;
-}
+// Persistent workgroups: each owns one contiguous range of output rows (a multiple of 16) and walks
+// it in sub-tiles of 256 rows.  Consecutive workgroup ids go round-robin over the 8 XCDs, so the
+// ranges are dealt out such that each XCD works on one contiguous stretch of the tensor
+// (neighbouring ranges share halo rows, and then an L2).
+struct Sched {
+    int nbx;          // workgroups along the rows (multiple of 8)
+    int rpb;          // rows per workgroup (multiple of 16)
+    int halo_al;      // real positions staged on either side of a sub-tile (multiple of 4)
+    int pg_blocks;    // ceil((BM + 2*halo_al)/4 / 16)
+    int maxr;         // LDS rows a sub-tile can touch (padded coordinates)
+};
 
-template <int TAPS>
+// Padded coordinates (3x3 only).  Inside LDS the staged positions are laid out with one extra
+// row after every image row and one extra image row between images, all holding the operand's
+// zero point:  A(b,p,q) = b*(H+1)*(W+1) + (p+1)*(W+1) + q.  A filter tap is then the constant
+// row offset dr*(W+1) + ds for every output position, borders included -- no per-lane masks.
+// WC > 0 fixes a square image size at compile time (cheap index arithmetic, immediate offsets).
+template <int TAPS, int WC>
 __global__ __launch_bounds__(kThreads, 2) void conv_s1_kernel(const int8_t *__restrict__ x,
                                                               const int8_t *__restrict__ wpk,
                                                               const int *__restrict__ colsum,
                                                               const q8t_qparams *__restrict__ qpa,
-                                                              const q8t_qparams *__restrict__ qpb, FastGeom g,
+                                                              const q8t_qparams *__restrict__ qpb,
+                                                              const FastGeom g, const Sched sch,
                                                               float *__restrict__ y, int32_t *__restrict__ acc_out)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    constexpr int A_BYTES = (TAPS == 9 ? MAX_STAGE_ROWS : BM + 8) * ROWB;
+    constexpr int A_BYTES = (TAPS == 9 ? MAXR9 : MAXR1) * ROWB;
+    constexpr int B_VEC = TAPS * CH * 4 / kThreads;   // 16-byte pieces of the weight chunk per thread
+    constexpr int PQC = WC * WC, W1C = (TAPS == 9 && WC) ? WC + 1 : WC, IMGC = (TAPS == 9 && WC) ? (WC + 1) * (WC + 1) : PQC;
     uint8_t *As = smem;
     uint8_t *Bs = smem + A_BYTES;
-    int *rs = reinterpret_cast<int *>(smem + A_BYTES + TAPS * CH * ROWB);
 
-    const int tile = xcd_tile(blockIdx.x, g.tiles);
-    if (tile >= g.tiles) return;
+    const int W = WC ? WC : g.W, PQ = WC ? PQC : g.PQ;
+    const int W1 = (TAPS == 9) ? W + 1 : W;
+    const int IMG = WC ? IMGC : (int)g.dIMG.d;
+
+    const int bidx = (blockIdx.x & 7) * (sch.nbx >> 3) + (blockIdx.x >> 3);
+    const int row_begin = bidx * sch.rpb;
+    const int row_end = min(g.M, row_begin + sch.rpb);
+    if (row_begin >= row_end) return;
     const int occ = blockIdx.y;  // output-channel chunk
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, kb = lane >> 4;
@@ -121,138 +160,190 @@ __global__ __launch_bounds__(kThreads, 2) void conv_s1_kernel(const int8_t *__re
     const float sc = qpa->scale * qpb->scale;
     const uint32_t zavec = (uint32_t)(za & 255) * 0x01010101u;
 
-    const int64_t g0 = (int64_t)tile * BM;
-    const int halo = (TAPS == 9) ? g.W + 1 : 0;
-    const int64_t stage_start = (g0 - halo) & ~(int64_t)3;  // arithmetic: also right for negatives
-    const int stage_rows = (int)(((g0 + BM + halo + 3) & ~(int64_t)3) - stage_start);
-    const int row_base = (int)(g0 - stage_start) + wave * 64;  // LDS row of this wave's first output row
-
-    // border predicates of this lane's A rows (one row per m-tile: row l16 of the 16)
-    bool ok_up[4], ok_dn[4], ok_lf[4], ok_rt[4];
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
-        const int64_t gr = g0 + wave * 64 + mt * 16 + l16;
-        const int pos = (int)(gr % g.PQ);
-        const int p = pos / g.W, q = pos - p * g.W;
-        ok_up[mt] = p > 0;
-        ok_dn[mt] = p < g.H - 1;
-        ok_lf[mt] = q > 0;
-        ok_rt[mt] = q < g.W - 1;
-    }
-
-    v4i acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = (v4i){0, 0, 0, 0};
-    int rsum[4] = {0, 0, 0, 0};
+    // padded coordinate of a real row index
+    auto apad = [&](uint32_t gr) -> int {
+        if (TAPS != 9) return (int)gr;
+        const uint32_t b = divc<PQC>(gr, g.dPQ);
+        const uint32_t pos = gr - b * PQ;
+        const uint32_t p = divc<WC>(pos, g.dW);
+        return (int)(b * IMG + pos + p + W1);
+    };
 
     const int CC = g.C / CH;
-    for (int cc = 0; cc < CC; ++cc) {
-        __syncthreads();
-        // ---- stage A: [position][64 channels], transposing 4x4 bytes per lane ----
-        {
-            const int npg = stage_rows >> 2;        // groups of 4 positions
-            const int pg_blocks = (npg + 15) >> 4;  // blocks of 16 position groups
+    const int nsub = (row_end - row_begin + BM - 1) / BM;
+    const int nsteps = nsub * CC;
+    const int npg = (BM + 2 * sch.halo_al) >> 2;
+
+    // ---- register prefetch of the next step's operands ----
+    uint32_t pa[MAX_SLABS][4];
+    int prow[MAX_SLABS], pthr[MAX_SLABS];   // LDS row of the group's first position (kSkip: nothing), straddle point
+    uint4 pb[B_VEC];
+    auto prefetch = [&](int step, bool with_b) {
+        const int sub = step / CC, cc = step - sub * CC;
+        const int g0 = row_begin + sub * BM;
+        const int a0 = apad((uint32_t)g0) - ((TAPS == 9) ? W1 + 1 : 0);   // padded coordinate of LDS row 0
+#pragma unroll
+        for (int it = 0; it < MAX_SLABS; ++it) {
             // one wavefront instruction = 16 position groups x 4 channel groups: 64-byte global
-            // segments per channel, 16 distinct LDS banks per store
-            for (int slab = wave; slab < pg_blocks * 4; slab += kThreads / 64) {
-                const int pgb = slab % pg_blocks, cgb = slab / pg_blocks;
-                const int pg = pgb * 16 + (lane & 15), cg = cgb * 4 + (lane >> 4);
-                if (pg < npg) {
-                    const int64_t gr = stage_start + (int64_t)pg * 4;
-                    uint32_t in[4] = {0, 0, 0, 0}, out[4];
-                    if (gr >= 0 && gr < g.M) {
-                        const int b = (int)(gr / g.PQ);
-                        const int pos = (int)(gr - (int64_t)b * g.PQ);
-                        const int8_t *src = x + ((int64_t)b * g.C + cc * CH + cg * 4) * g.PQ + pos;
+            // segments per channel, 16 distinct LDS banks per transposed store
+            const int slab = wave + it * (kThreads / 64);
+            const int pgb = slab % sch.pg_blocks, cgb = slab / sch.pg_blocks;
+            const int pg = pgb * 16 + l16, cg = cgb * 4 + kb;
+            const int gr = g0 - sch.halo_al + pg * 4;
+            prow[it] = kSkip;
+            pthr[it] = 4;
+            if (cgb < 4 && pg < npg && gr >= 0 && gr < g.M) {
+                const uint32_t b = divc<PQC>((uint32_t)gr, g.dPQ);
+                const uint32_t pos = (uint32_t)gr - b * PQ;
+                int r = gr - g0;
+                if (TAPS == 9) {
+                    const uint32_t p = divc<WC>(pos, g.dW);
+                    r = (int)(b * IMG + pos + p + W1) - a0;
+                    pthr[it] = W - 1 - (int)(pos - p * W);   // positions after this one sit one row further
+                }
+                if (r > -4 && r < sch.maxr) {   // rows outside [0, maxr) are dropped at the store
+                    prow[it] = r;
+                    const int8_t *src = x + ((size_t)(b * g.C + cc * CH + cg * 4) * PQ + pos);
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) in[j] = *reinterpret_cast<const uint32_t *>(src + (int64_t)j * g.PQ);
-                    }
-                    transpose4x4(in, out);
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        *reinterpret_cast<uint32_t *>(&As[(pg * 4 + i) * ROWB + cg * 4]) = out[i];
+                    for (int j = 0; j < 4; ++j) pa[it][j] = *reinterpret_cast<const uint32_t *>(src + (size_t)j * PQ);
                 }
             }
         }
-        // ---- stage B: packed weights of (occ, cc): [tap][64 oc][64 ch] -> rows of 80 bytes ----
-        {
-            const int8_t *src = wpk + ((int64_t)occ * CC + cc) * TAPS * CH * CH;
-            for (int e = tid; e < TAPS * CH * 4; e += kThreads) {
-                const int row = e >> 2, part = e & 3;
-                const uint4 v = *reinterpret_cast<const uint4 *>(src + (int64_t)row * CH + part * 16);
-                *reinterpret_cast<uint4 *>(&Bs[row * ROWB + part * 16]) = v;
+        if (with_b) {
+            const int8_t *src = wpk + (size_t)(occ * CC + cc) * TAPS * CH * CH;
+#pragma unroll
+            for (int i = 0; i < B_VEC; ++i) pb[i] = *reinterpret_cast<const uint4 *>(src + (size_t)(tid + i * kThreads) * 16);
+        }
+    };
+    auto commit = [&](int step, bool with_b) {
+#pragma unroll
+        for (int it = 0; it < MAX_SLABS; ++it) {
+            if (prow[it] != kSkip) {
+                const int cg = ((wave + it * (kThreads / 64)) / sch.pg_blocks) * 4 + kb;
+                uint32_t out[4];
+                transpose4x4(pa[it], out);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int row = prow[it] + i + ((TAPS == 9 && i > pthr[it]) ? 1 : 0);
+                    if (row >= 0 && row < sch.maxr) *reinterpret_cast<uint32_t *>(&As[row * ROWB + cg * 4]) = out[i];
+                }
             }
         }
+        if (TAPS == 9) {
+            // zero-point rows: the pad column after every image row and the pad row between images
+            const int sub = step / CC;
+            const int g0 = row_begin + sub * BM;
+            const int a0 = apad((uint32_t)g0) - (W1 + 1);
+            for (int rr = tid; rr < sch.maxr; rr += kThreads) {
+                const int ac = a0 + rr;
+                bool pad = ac < 0;
+                if (!pad) {
+                    const uint32_t bi = divc<IMGC>((uint32_t)ac, g.dIMG);
+                    const uint32_t rem = (uint32_t)ac - bi * IMG;
+                    const uint32_t ri = divc<W1C>(rem, g.dW1);
+                    pad = (ri == 0) || (rem - ri * W1 == (uint32_t)W);
+                }
+                if (pad) {
+                    const uint4 z = make_uint4(zavec, zavec, zavec, zavec);
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4 *>(&As[rr * ROWB + i * 16]) = z;
+                }
+            }
+        }
+        if (with_b) {
+#pragma unroll
+            for (int i = 0; i < B_VEC; ++i) {
+                // 16-byte piece: row e/4 of [tap][oc], part e%4; parts are XOR-swizzled by the row
+                // so that the b128 fragment reads of 16 consecutive rows are conflict-free
+                const int e = tid + i * kThreads, row = e >> 2, part = e & 3;
+                *reinterpret_cast<uint4 *>(&Bs[row * CH + ((part ^ ((row >> 2) & 3)) << 4)]) = pb[i];
+            }
+        }
+    };
+
+    v4i acc[4][4], accrs[4];
+    int abase[4];
+    const v4i ones = (v4i){0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    const int bbase = l16 * CH + ((kb ^ (l16 >> 2)) << 4);
+
+    prefetch(0, true);
+    for (int step = 0; step < nsteps; ++step) {
+        const int sub = step / CC, cc = step - sub * CC;
+        const int g0 = row_begin + sub * BM;
+        const bool with_b = (CC > 1) || (step == 0);
         __syncthreads();
-        // ---- MFMA: one K-step per tap ----
+        commit(step, with_b);
+        __syncthreads();
+        if (step + 1 < nsteps) prefetch(step + 1, CC > 1);
+
+        if (cc == 0) {
+            const int ag0 = apad((uint32_t)g0);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = (v4i){0, 0, 0, 0};
+                accrs[mt] = (v4i){0, 0, 0, 0};
+                // LDS address of this lane's A row in m-tile (mt*4 + wave), before the tap offset
+                int gr = g0 + (mt * 4 + wave) * 16 + l16;
+                if (gr >= g.M) gr = g0;
+                abase[mt] = (apad((uint32_t)gr) - ag0) * ROWB + kb * 16;
+            }
+        }
+        // ---- MFMA: one K-step per tap, plus an all-ones column tile that yields the row sums of A
+        // in the accumulator layout.  M-tiles are interleaved over the wavefronts so that a ragged
+        // last sub-tile stays balanced ----
 #pragma unroll
         for (int tap = 0; tap < TAPS; ++tap) {
-            const int dr = (TAPS == 9) ? tap / 3 - 1 : 0, ds = (TAPS == 9) ? tap % 3 - 1 : 0;
-            const int off = dr * g.W + ds;
+            const int toff = (TAPS == 9) ? ((tap / 3) * W1 + (tap % 3)) * ROWB : 0;
             v4i bf[4];
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt)
-                bf[nt] = *reinterpret_cast<const v4i *>(&Bs[(tap * CH + nt * 16 + l16) * ROWB + kb * 16]);
+                bf[nt] = *reinterpret_cast<const v4i *>(&Bs[bbase + (tap * CH + nt * 16) * CH]);
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt) {
-                v4i a = *reinterpret_cast<const v4i *>(&As[(row_base + mt * 16 + l16 + off) * ROWB + kb * 16]);
-                if (TAPS == 9) {
-                    bool ok = true;
-                    if (dr < 0) ok = ok && ok_up[mt];
-                    if (dr > 0) ok = ok && ok_dn[mt];
-                    if (ds < 0) ok = ok && ok_lf[mt];
-                    if (ds > 0) ok = ok && ok_rt[mt];
-                    if (!ok) a = (v4i){(int)zavec, (int)zavec, (int)zavec, (int)zavec};
-                }
-                rsum[mt] = dot4_ones(a[0], dot4_ones(a[1], dot4_ones(a[2], dot4_ones(a[3], rsum[mt]))));
+                if (g0 + (mt * 4 + wave) * 16 >= row_end) continue;   // wavefront-uniform
+                const v4i a = *reinterpret_cast<const v4i *>(&As[abase[mt] + toff]);
 #pragma unroll
                 for (int nt = 0; nt < 4; ++nt)
                     acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bf[nt], acc[mt][nt], 0, 0, 0);
+                accrs[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, ones, accrs[mt], 0, 0, 0);
             }
         }
-    }
+        if (cc != CC - 1) continue;
 
-    // ---- row sums: fold the 4 k-blocks, hand them to the lanes that own the rows in the C layout ----
+        // ---- epilogue: zero-point correction (wrapping 32-bit arithmetic: the corrected value fits
+        // by contract), dequantization, 4 consecutive positions of one output channel per lane ----
+        const uint32_t Kp = (uint32_t)(g.C * TAPS);
+        const uint32_t kzz = Kp * (uint32_t)za * (uint32_t)zb;
+        uint32_t csn[4];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
-        int v = rsum[mt];
-        v += __shfl_xor(v, 16, 64);
-        v += __shfl_xor(v, 32, 64);
-        if (kb == 0) rs[wave * 64 + mt * 16 + l16] = v;
-    }
-    __syncthreads();
-
-    // zero-point correction in wrapping 32-bit arithmetic: the corrected value fits by contract
-    const uint32_t Kp = (uint32_t)(g.C * TAPS);
-    const uint32_t kzz = Kp * (uint32_t)za * (uint32_t)zb;
-    const uint32_t uzb = (uint32_t)zb;
+        for (int nt = 0; nt < 4; ++nt) csn[nt] = (uint32_t)za * (uint32_t)colsum[occ * CH + nt * 16 + l16];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
-        const int lr = wave * 64 + mt * 16 + kb * 4;
-        const int64_t gr = g0 + lr;
-        if (gr >= g.M) continue;
-        const int b = (int)(gr / g.PQ);
-        const int pos = (int)(gr - (int64_t)b * g.PQ);
-        const int4 r4 = *reinterpret_cast<const int4 *>(&rs[lr]);
+        for (int mt = 0; mt < 4; ++mt) {
+            const int gr = g0 + (mt * 4 + wave) * 16 + kb * 4;
+            if (gr >= row_end) continue;
+            const uint32_t b = divc<PQC>((uint32_t)gr, g.dPQ);
+            const uint32_t pos = (uint32_t)gr - b * PQ;
+            uint32_t t[4];
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-            const int oc = occ * CH + nt * 16 + l16;
-            const uint32_t cs = (uint32_t)za * (uint32_t)colsum[oc];
-            const int64_t o = ((int64_t)b * g.K + oc) * g.PQ + pos;
-            const int c0 = (int)((uint32_t)acc[mt][nt][0] - uzb * (uint32_t)r4.x - cs + kzz);
-            const int c1 = (int)((uint32_t)acc[mt][nt][1] - uzb * (uint32_t)r4.y - cs + kzz);
-            const int c2 = (int)((uint32_t)acc[mt][nt][2] - uzb * (uint32_t)r4.z - cs + kzz);
-            const int c3 = (int)((uint32_t)acc[mt][nt][3] - uzb * (uint32_t)r4.w - cs + kzz);
-            if (acc_out) *reinterpret_cast<int4 *>(acc_out + o) = make_int4(c0, c1, c2, c3);
-            if (y) {
-                float4 f;
-                f.x = sc * (float)c0;
-                f.y = sc * (float)c1;
-                f.z = sc * (float)c2;
-                f.w = sc * (float)c3;
-                *reinterpret_cast<float4 *>(y + o) = f;
+            for (int j = 0; j < 4; ++j) t[j] = kzz - (uint32_t)zb * (uint32_t)accrs[mt][j];
+            const size_t o0 = (size_t)(b * g.K + occ * CH + l16) * PQ + pos;
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) {
+                const size_t o = o0 + (size_t)(nt * 16) * PQ;
+                const int c0 = (int)((uint32_t)acc[mt][nt][0] + t[0] - csn[nt]);
+                const int c1 = (int)((uint32_t)acc[mt][nt][1] + t[1] - csn[nt]);
+                const int c2 = (int)((uint32_t)acc[mt][nt][2] + t[2] - csn[nt]);
+                const int c3 = (int)((uint32_t)acc[mt][nt][3] + t[3] - csn[nt]);
+                if (acc_out) *reinterpret_cast<int4 *>(acc_out + o) = make_int4(c0, c1, c2, c3);
+                if (y) {
+                    float4 f;
+                    f.x = sc * (float)c0;
+                    f.y = sc * (float)c1;
+                    f.z = sc * (float)c2;
+                    f.w = sc * (float)c3;
+                    *reinterpret_cast<float4 *>(y + o) = f;
+                }
             }
         }
     }
@@ -261,7 +352,15 @@ __global__ __launch_bounds__(kThreads, 2) void conv_s1_kernel(const int8_t *__re
 template <int TAPS>
 constexpr size_t smem_bytes()
 {
-    return (size_t)(TAPS == 9 ? MAX_STAGE_ROWS : BM + 8) * ROWB + (size_t)TAPS * CH * ROWB + BM * sizeof(int);
+    return (size_t)(TAPS == 9 ? MAXR9 : MAXR1) * ROWB + (size_t)TAPS * CH * CH;
+}
+
+// LDS rows (padded coordinates) one sub-tile can touch
+int rows_needed(int taps, int W, int PQ)
+{
+    if (taps != 9) return BM;
+    const int W1 = W + 1;
+    return (BM - 1) + (BM + W - 1) / W + W1 * (BM / PQ + 1) + 2 * W1 + 8;
 }
 
 bool shape_ok(int which, const q8t_conv_desc *d)
@@ -271,9 +370,18 @@ bool shape_ok(int which, const q8t_conv_desc *d)
     if (!((d->R == 3 && d->pad == 1) || (d->R == 1 && d->pad == 0))) return false;
     if (d->C % CH || d->K % CH) return false;
     if ((d->H * d->W) % 4) return false;
-    if (d->R == 3 && d->W > MAX_W) return false;
-    if (d->H < 2 || d->W < 2) return false;
+    if (d->H < 2 || d->W < 2 || d->N > 32768 || d->H > 32768) return false;   // quotient range of fdiv
+    if (d->R == 3 && (rows_needed(9, d->W, d->H * d->W) > MAXR9 || ((d->W + 1 + 3) & ~3) * 2 + BM > MAX_SLABS * 64))
+        return false;
     return true;
+}
+
+FastDiv mkdiv(int d)
+{
+    FastDiv f;
+    f.d = (uint32_t)d;
+    f.r = 1.0f / (float)d;
+    return f;
 }
 
 }  // namespace
@@ -294,6 +402,24 @@ size_t q8t_fast_conv_ws(int which, const q8t_conv_desc *d)
     return ((wbytes + 255) & ~(size_t)255) + (size_t)oc * sizeof(int);
 }
 
+template <int TAPS, int WC>
+int launch_conv(dim3 grid, hipStream_t st, const int8_t *a, const int8_t *wpk, const int *colsum,
+                const q8t_qparams *qa, const q8t_qparams *qb, const FastGeom &g, const Sched &sch, float *out_f,
+                int32_t *out_acc)
+{
+    static bool attr = false;
+    if (!attr && smem_bytes<TAPS>() > 65536) {
+        if (hipFuncSetAttribute((const void *)conv_s1_kernel<TAPS, WC>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)smem_bytes<TAPS>()) != hipSuccess)
+            return Q8T_ERR_HIP;
+        attr = true;
+    }
+    hipLaunchKernelGGL((conv_s1_kernel<TAPS, WC>), grid, dim3(kThreads), smem_bytes<TAPS>(), st, a, wpk, colsum, qa,
+                       qb, g, sch, out_f, out_acc);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
+
 int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
                   const q8t_qparams *qb, float *out_f, void *out_acc, void *ws, hipStream_t st)
 {
@@ -309,26 +435,36 @@ int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
     g.PQ = d->H * d->W;
     g.C = which == 0 ? d->C : d->K;   // reduction channels
     g.K = which == 0 ? d->K : d->C;   // output channels
-    g.M = (int64_t)g.N * g.PQ;
-    g.tiles = (int)((g.M + BM - 1) / BM);
+    g.M = g.N * g.PQ;
+    const int W1 = taps == 9 ? d->W + 1 : d->W;
+    g.dPQ = mkdiv(g.PQ);
+    g.dW = mkdiv(g.W);
+    g.dW1 = mkdiv(W1);
+    g.dIMG = mkdiv(taps == 9 ? (d->H + 1) * W1 : g.PQ);
     hipLaunchKernelGGL(repack_weights, dim3(g.K), dim3(kThreads), 0, st, (const int8_t *)b, d->K, d->C, d->R, d->S,
                        which, wpk, colsum);
     Q8T_LAUNCH_CHECK();
-    const dim3 grid((unsigned)(((g.tiles + 7) / 8) * 8), (unsigned)(g.K / CH));
+    Sched sch;
+    const int occs = g.K / CH;
+    int nbx = 512 / occs;                       // two workgroups per compute unit in total
+    const int max_useful = (g.M + 63) / 64;     // no point in ranges shorter than 64 rows
+    if (nbx > max_useful) nbx = max_useful;
+    nbx = ((nbx + 7) / 8) * 8;
+    sch.nbx = nbx;
+    sch.rpb = ((g.M + nbx - 1) / nbx + 15) / 16 * 16;
+    sch.halo_al = taps == 9 ? ((g.W + 1 + 3) & ~3) : 0;
+    sch.pg_blocks = (((BM + 2 * sch.halo_al) >> 2) + 15) / 16;
+    sch.maxr = rows_needed(taps, g.W, g.PQ);
+    const dim3 grid((unsigned)nbx, (unsigned)occs);
+    const int8_t *pa = (const int8_t *)a;
+    int32_t *pacc = (int32_t *)out_acc;
+    const bool sq = d->H == d->W;
     if (taps == 9) {
-        static bool attr9 = false;
-        if (!attr9) {
-            if (hipFuncSetAttribute((const void *)conv_s1_kernel<9>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)smem_bytes<9>()) != hipSuccess)
-                return Q8T_ERR_HIP;
-            attr9 = true;
-        }
-        hipLaunchKernelGGL(conv_s1_kernel<9>, grid, dim3(kThreads), smem_bytes<9>(), st, (const int8_t *)a, wpk,
-                           colsum, qa, qb, g, out_f, (int32_t *)out_acc);
-    } else {
-        hipLaunchKernelGGL(conv_s1_kernel<1>, grid, dim3(kThreads), smem_bytes<1>(), st, (const int8_t *)a, wpk,
-                           colsum, qa, qb, g, out_f, (int32_t *)out_acc);
+        if (sq && d->W == 56) return launch_conv<9, 56>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc);
+        if (sq && d->W == 28) return launch_conv<9, 28>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc);
+        if (sq && d->W == 14) return launch_conv<9, 14>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc);
+        return launch_conv<9, 0>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc);
     }
-    Q8T_LAUNCH_CHECK();
-    return Q8T_OK;
+    if (sq && d->W == 56) return launch_conv<1, 56>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc);
+    return launch_conv<1, 0>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc);
 }

@@ -39,3 +39,15 @@ def close(a, b):
     b = np.asarray(b, np.float64)
     bad = np.abs(a - b) > ATOL + RTOL * np.abs(b)
     assert not bad.any(), "%d of %d outside tolerance, max abs diff %g" % (bad.sum(), bad.size, np.abs(a - b).max())
+
+
+def same_ints(got, exp):
+    """bit-exact comparison with a short failure message"""
+    got = np.asarray(got)
+    exp = np.asarray(exp)
+    assert got.shape == exp.shape, (got.shape, exp.shape)
+    bad = got != exp   # exact comparison (integers; floats value by value)
+    if bad.any():
+        idx = tuple(int(v) for v in np.argwhere(bad)[0])
+        raise AssertionError("%d of %d values differ; first at %s: got %r, expected %r"
+                             % (bad.sum(), bad.size, idx, got[idx], exp[idx]))

@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 import synth
-from gpu_util import close, dev, host, qp_dev_from, require_gpu
+from gpu_util import same_ints, close, dev, host, qp_dev_from, require_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -33,15 +33,15 @@ def test_fc_products(M, N, K):
     dpx, dpw, dpg, dpg16 = (qp_dev_from(p) for p in (px, pw, pg, pg16))
     y, acc = q8t.qgemm_fwd(dev(sx), dpx, dev(sw), dpw, want_acc=True)
     oy, oacc = oracle.qgemm_fwd(sx, px, sw, pw)
-    assert np.array_equal(host(acc).astype(np.int64), oacc)
+    same_ints(host(acc), oacc)
     close(host(y), oy)
     dx, acc = q8t.qgemm_dgrad(dev(sg), dpg, dev(sw), dpw, want_acc=True)
     odx, oacc = oracle.qgemm_dgrad(sg, pg, sw, pw)
-    assert np.array_equal(host(acc).astype(np.int64), oacc)
+    same_ints(host(acc), oacc)
     close(host(dx), odx)
     dw, acc = q8t.qgemm_wgrad(dev(sx), dpx, dev(sg16), dpg16, want_acc=True)
     odw, oacc = oracle.qgemm_wgrad(sx, px, sg16, pg16)
-    assert np.array_equal(host(acc), oacc)
+    same_ints(host(acc), oacc)
     close(host(dw), odw)
 
 
@@ -78,9 +78,9 @@ def test_config0_layer_step():
     oy, oacc = oracle.qgemm_fwd(sx, opx, sw, opw)
     odx, oaccd = oracle.qgemm_dgrad(s8, o8, sw, opw)
     odw, oaccw = oracle.qgemm_wgrad(sx, opx, s16, o16)
-    assert np.array_equal(host(acc).astype(np.int64), oacc)
-    assert np.array_equal(host(accd).astype(np.int64), oaccd)
-    assert np.array_equal(host(accw), oaccw)
+    same_ints(host(acc), oacc)
+    same_ints(host(accd), oaccd)
+    same_ints(host(accw), oaccw)
     close(host(y), oy)
     close(host(dx), odx)
     close(host(dw), odw)
@@ -107,6 +107,11 @@ CONV_CASES = [
     (20, 16, 4, 8, 64, 3, 3, 1, 1),      # more images than one per workgroup, non-square
     (2, 192, 8, 12, 192, 3, 3, 1, 1),
     (1, 64, 60, 56, 64, 3, 3, 1, 1),     # last chunk of the image is ragged
+    (2, 64, 56, 56, 256, 1, 1, 1, 0),    # 1x1 at the full plane size
+    (40, 64, 6, 6, 64, 3, 3, 1, 1),      # one 256-row tile spans several small images
+    (9, 64, 14, 14, 128, 3, 3, 1, 1),
+    (3, 128, 28, 28, 128, 3, 3, 1, 1),
+    (2, 64, 10, 18, 64, 3, 3, 1, 1),     # width not a multiple of 4
 ]
 
 
@@ -129,15 +134,15 @@ def test_conv_products(case):
     dpx, dpw, dpg, dpg16 = (qp_dev_from(p) for p in (px, pw, pg, pg16))
     y, acc = q8t.qconv_fwd(d, dev(sx), dpx, dev(sw), dpw, want_acc=True)
     oy, oacc = oracle.qconv_fwd(od, sx, px, sw, pw)
-    assert np.array_equal(host(acc).astype(np.int64), oacc)
+    same_ints(host(acc), oacc)
     close(host(y), oy)
     dx, acc = q8t.qconv_dgrad(d, dev(sg), dpg, dev(sw), dpw, want_acc=True)
     odx, oacc = oracle.qconv_dgrad(od, sg, pg, sw, pw)
-    assert np.array_equal(host(acc).astype(np.int64), oacc)
+    same_ints(host(acc), oacc)
     close(host(dx), odx)
     dw, acc = q8t.qconv_wgrad(d, dev(sx), dpx, dev(sg16), dpg16, want_acc=True)
     odw, oacc = oracle.qconv_wgrad(od, sx, px, sg16, pg16)
-    assert np.array_equal(host(acc), oacc)
+    same_ints(host(acc), oacc)
     close(host(dw), odw)
 
 

@@ -5,7 +5,7 @@ import torch
 
 import oracle
 import synth
-from gpu_util import close, dev, host, require_gpu, same_qparams
+from gpu_util import same_ints, close, dev, host, require_gpu, same_qparams
 
 pytestmark = pytest.mark.gpu
 
@@ -19,7 +19,7 @@ def test_quantize_matches_oracle(n, bits, stochastic):
     q, qp = q8t.quantize(dev(x), bits, stochastic, seed=77 + n)
     s, _, oqp = oracle.quantize(x, bits, stochastic, seed=77 + n)
     same_qparams(q8t, qp, oqp)
-    assert np.array_equal(host(q), s)
+    same_ints(host(q), s)
 
 
 @pytest.mark.parametrize("bits", [4, 8, 12, 16])
@@ -33,7 +33,7 @@ def test_quantize_unaligned_pointer_and_seeds(bits):
             q, qp = q8t.quantize(xs, bits, True, seed=seed)
             s, _, oqp = oracle.quantize(xh, bits, True, seed=seed)
             same_qparams(q8t, qp, oqp)
-            assert np.array_equal(host(q), s)
+            same_ints(host(q), s)
 
 
 def test_quantize_special_ranges():
@@ -46,7 +46,7 @@ def test_quantize_special_ranges():
             q, qp = q8t.quantize(dev(x), 8, stochastic, seed=5)
             s, _, oqp = oracle.quantize(x, 8, stochastic, seed=5)
             same_qparams(q8t, qp, oqp)
-            assert np.array_equal(host(q), s)
+            same_ints(host(q), s)
 
 
 @pytest.mark.parametrize("bits", [8, 16])
@@ -59,7 +59,7 @@ def test_quantize_with_supplied_range_saturates(bits):
         q, qp = q8t.quantize_with_range(dev(x), dev(rng), bits, stochastic, seed=8)
         s, _, oqp = oracle.quantize(x, bits, stochastic, seed=8, vrange=(-1.0, 2.0))
         same_qparams(q8t, qp, oqp)
-        assert np.array_equal(host(q), s)
+        same_ints(host(q), s)
 
 
 @pytest.mark.parametrize("n", [6, 4096 + 3, 1 << 21])
@@ -71,8 +71,8 @@ def test_bifurcated_gradient_copies(n):
     s16, _, o16 = oracle.quantize(g, 16, True, seed=2 ** 33 + 456)
     same_qparams(q8t, qp8, o8)
     same_qparams(q8t, qp16, o16)
-    assert np.array_equal(host(q8), s8)
-    assert np.array_equal(host(q16), s16)
+    same_ints(host(q8), s8)
+    same_ints(host(q16), s16)
     # both copies dequantize back to g within one step of their own grid
     close(host(q8t.dequantize(q16, qp16)), oracle.dequantize(s16, o16))
     close(host(q8t.dequantize(q8, qp8)), oracle.dequantize(s8, o8))
@@ -85,14 +85,14 @@ def test_full_size_activation_tensor():
     q, qp = q8t.quantize(dev(x), 8)
     s, _, oqp = oracle.quantize(x, 8)
     same_qparams(q8t, qp, oqp)
-    assert np.array_equal(host(q), s)
+    same_ints(host(q), s)
     q8, qp8, q16, qp16 = q8t.quantize_bifurcate(dev(dy), seed8=1, seed16=2)
     s8, _, o8 = oracle.quantize(dy, 8, True, seed=1)
     s16, _, o16 = oracle.quantize(dy, 16, True, seed=2)
     same_qparams(q8t, qp8, o8)
     same_qparams(q8t, qp16, o16)
-    assert np.array_equal(host(q8), s8)
-    assert np.array_equal(host(q16), s16)
+    same_ints(host(q8), s8)
+    same_ints(host(q16), s16)
 
 
 def test_error_codes_on_device_arguments():

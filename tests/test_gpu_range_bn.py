@@ -9,7 +9,7 @@ import pytest
 
 import oracle
 import synth
-from gpu_util import close, dev, host, require_gpu, same_qparams
+from gpu_util import same_ints, close, dev, host, require_gpu, same_qparams
 
 pytestmark = pytest.mark.gpu
 
@@ -49,9 +49,9 @@ def test_forward(shape, affine, eps):
     close(host(y), oy)
     # elementwise stage, bit for bit, on the GPU's statistics
     fy, _, fq, fqp = oracle.range_bn_fwd(x, gamma, beta, eps, stats=st, quantized=True)
-    assert np.array_equal(host(y), fy)
+    same_ints(host(y), fy)
     same_qparams(q8t, qp, fqp)
-    assert np.array_equal(host(q), fq)
+    same_ints(host(q), fq)
 
 
 @pytest.mark.parametrize("shape", SHAPES)
@@ -84,7 +84,7 @@ def test_ties_at_the_extrema():
     close(host(dx), odx)
     y, st, _, _ = q8t.range_bn_fwd(dev(x), eps=1e-3)
     oy, _, _, _ = oracle.range_bn_fwd(x, eps=1e-3, stats=host(st))
-    assert np.array_equal(host(y), oy)
+    same_ints(host(y), oy)
 
 
 def test_config1_full_size():
@@ -99,9 +99,9 @@ def test_config1_full_size():
     close(st[0], ostats[0])
     close(host(y), oy)
     fy, _, fq, fqp = oracle.range_bn_fwd(x, eps=1e-5, stats=st, quantized=True)
-    assert np.array_equal(host(y), fy)
+    same_ints(host(y), fy)
     same_qparams(q8t, qp, fqp)
-    assert np.array_equal(host(q), fq)
+    same_ints(host(q), fq)
     n_unforced = int((host(q) != oracle.range_bn_fwd(x, eps=1e-5, quantized=True)[2]).sum())
     print("int8 codes differing from the un-forced oracle run:", n_unforced, "of", x.size)
     assert n_unforced <= x.size * 1e-5
