@@ -25,15 +25,19 @@
 
 namespace {
 
+constexpr int BM_ROWS = 256;
+
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
-constexpr int BM = 256;          // rows per sub-tile
+constexpr int kThreads = 512;     // 8 wavefronts: two 16-row m-tiles each per sub-tile
+constexpr int kWaves = kThreads / 64;
+constexpr int MT = BM_ROWS / 16 / kWaves;   // m-tiles per wavefront
+constexpr int BM = BM_ROWS;          // rows per sub-tile
 constexpr int CH = 64;           // channels per reduction chunk / output channels per workgroup
 constexpr int ROWB = 80;         // LDS bytes per staged activation row (64 + 16: conflict-free b128 reads)
 constexpr int MAXR9 = 464;       // staged rows (padded coordinates) of the 3x3 variant
 constexpr int MAXR1 = BM;        // 1x1 variant: no halo, no padding
-constexpr int MAX_SLABS = 7;     // staging iterations per wavefront
+constexpr int MAX_SLABS = 4;     // staging iterations per wavefront (28 slabs of 64 lanes at most)
 constexpr int kSkip = -1000000;  // marks a staging slot with nothing to store
 
 struct FastDiv {
@@ -67,16 +71,17 @@ __device__ __forceinline__ uint32_t divc(uint32_t n, const FastDiv fd)
 // ---- weight pre-pass: repack + per-output-channel sums -----------------------------------------
 // out[(oc/64)][cc][tap][oc%64][ch%64] = W'(oc, ch, tap);  forward: W'(oc,ch,r,s) = W[oc][ch][r][s];
 // layer gradient: W'(oc,ch,r,s) = W[ch][oc][R-1-r][S-1-s]  (oc = input channel of the layer).
-__global__ __launch_bounds__(kThreads) void repack_weights(const int8_t *__restrict__ w, int Kf, int Cf, int R,
+constexpr int kRepackThreads = 256;
+__global__ __launch_bounds__(kRepackThreads) void repack_weights(const int8_t *__restrict__ w, int Kf, int Cf, int R,
                                                            int S, int dgrad, int8_t *__restrict__ out,
                                                            int *__restrict__ colsum)
 {
-    __shared__ int red[kThreads / 64];
+    __shared__ int red[kRepackThreads / 64];
     const int OC = dgrad ? Cf : Kf, CHN = dgrad ? Kf : Cf;
     const int oc = blockIdx.x;
     const int taps = R * S, CC = CHN / CH;
     int sum = 0;
-    for (int e = threadIdx.x; e < taps * CHN; e += kThreads) {
+    for (int e = threadIdx.x; e < taps * CHN; e += kRepackThreads) {
         const int tap = e / CHN, ch = e - tap * CHN;
         const int r = tap / S, s = tap - r * S;
         int v;
@@ -128,8 +133,8 @@ struct Sched {
 // zero point:  A(b,p,q) = b*(H+1)*(W+1) + (p+1)*(W+1) + q.  A filter tap is then the constant
 // row offset dr*(W+1) + ds for every output position, borders included -- no per-lane masks.
 // WC > 0 fixes a square image size at compile time (cheap index arithmetic, immediate offsets).
-template <int TAPS, int WC>
-__global__ __launch_bounds__(kThreads, 2) void conv_s1_kernel(const int8_t *__restrict__ x,
+template <int TAPS, int WC, bool V16>
+__global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__restrict__ x,
                                                               const int8_t *__restrict__ wpk,
                                                               const int *__restrict__ colsum,
                                                               const q8t_qparams *__restrict__ qpa,
@@ -139,7 +144,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_s1_kernel(const int8_t *__re
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     constexpr int A_BYTES = (TAPS == 9 ? MAXR9 : MAXR1) * ROWB;
-    constexpr int B_VEC = TAPS * CH * 4 / kThreads;   // 16-byte pieces of the weight chunk per thread
+    constexpr int B_PIECES = TAPS * CH * 4;            // 16-byte pieces of the weight chunk
+    constexpr int B_VEC = (B_PIECES + kThreads - 1) / kThreads;
     constexpr int PQC = WC * WC, W1C = (TAPS == 9 && WC) ? WC + 1 : WC, IMGC = (TAPS == 9 && WC) ? (WC + 1) * (WC + 1) : PQC;
     uint8_t *As = smem;
     uint8_t *Bs = smem + A_BYTES;
@@ -170,18 +176,52 @@ __global__ __launch_bounds__(kThreads, 2) void conv_s1_kernel(const int8_t *__re
     };
 
     const int CC = g.C / CH;
-    const int nsub = (row_end - row_begin + BM - 1) / BM;
+    // The first sub-tile is shorter by a workgroup-dependent amount, so that the workgroups of a
+    // compute unit (and of the chip) are in different phases (load / MFMA / store) at any moment
+    // instead of marching in lock-step and using the memory system in bursts.
+    const int stag = ((blockIdx.x >> 3) + (blockIdx.x >> 8)) & 3;
+    const int len0 = min(row_end - row_begin, 64 * (1 + stag));
+    const int nsub = 1 + (row_end - row_begin - len0 + BM - 1) / BM;
     const int nsteps = nsub * CC;
+    auto tile_begin = [&](int sub) { return row_begin + (sub == 0 ? 0 : len0 + (sub - 1) * BM); };
+    auto tile_end = [&](int sub) { return sub == 0 ? row_begin + len0 : min(row_end, tile_begin(sub) + BM); };
     const int npg = (BM + 2 * sch.halo_al) >> 2;
 
     // ---- register prefetch of the next step's operands ----
     uint32_t pa[MAX_SLABS][4];
     int prow[MAX_SLABS], pthr[MAX_SLABS];   // LDS row of the group's first position (kSkip: nothing), straddle point
-    uint4 pb[B_VEC];
-    auto prefetch = [&](int step, bool with_b) {
+    uint4 pq[4];                            // wide staging variant: 4 channels x 16 positions
+    auto prefetch = [&](int step) {
         const int sub = step / CC, cc = step - sub * CC;
-        const int g0 = row_begin + sub * BM;
+        const int g0 = tile_begin(sub);
         const int a0 = apad((uint32_t)g0) - ((TAPS == 9) ? W1 + 1 : 0);   // padded coordinate of LDS row 0
+        const int stage = tile_end(sub) - g0 + 2 * sch.halo_al;           // real positions to stage
+        if (V16) {
+            // wide variant: one lane = 16 positions x 4 channels, four 16-byte loads.  The vector
+            // memory pipeline takes about as long for a 4-byte as for a 16-byte access per lane,
+            // so this issues a quarter of the load instructions.  lane -> channel group (l16),
+            // (wavefront, kb) -> group of 16 positions: 64-byte segments per channel plane.
+            const int pg16 = wave * 4 + kb, cg = l16;
+            const int gr = g0 - sch.halo_al + pg16 * 16;
+            prow[0] = kSkip;
+            if (pg16 * 16 < stage && gr >= 0 && gr < g.M) {
+                const uint32_t b = divc<PQC>((uint32_t)gr, g.dPQ);
+                const uint32_t pos = (uint32_t)gr - b * PQ;
+                int r = gr - g0;
+                pthr[0] = 0;
+                if (TAPS == 9) {
+                    const uint32_t p = divc<WC>(pos, g.dW);
+                    r = (int)(b * IMG + pos + p + W1) - a0;
+                    pthr[0] = (int)(pos - p * W);   // column of the first position
+                }
+                if (r > -20 && r < sch.maxr) {
+                    prow[0] = r;
+                    const int8_t *src = x + ((size_t)(b * g.C + cc * CH + cg * 4) * PQ + pos);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) pq[j] = *reinterpret_cast<const uint4 *>(src + (size_t)j * PQ);
+                }
+            }
+        } else
 #pragma unroll
         for (int it = 0; it < MAX_SLABS; ++it) {
             // one wavefront instruction = 16 position groups x 4 channel groups: 64-byte global
@@ -192,7 +232,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_s1_kernel(const int8_t *__re
             const int gr = g0 - sch.halo_al + pg * 4;
             prow[it] = kSkip;
             pthr[it] = 4;
-            if (cgb < 4 && pg < npg && gr >= 0 && gr < g.M) {
+            if (cgb < 4 && pg * 4 < stage && gr >= 0 && gr < g.M) {
                 const uint32_t b = divc<PQC>((uint32_t)gr, g.dPQ);
                 const uint32_t pos = (uint32_t)gr - b * PQ;
                 int r = gr - g0;
@@ -209,13 +249,34 @@ __global__ __launch_bounds__(kThreads, 2) void conv_s1_kernel(const int8_t *__re
                 }
             }
         }
-        if (with_b) {
-            const int8_t *src = wpk + (size_t)(occ * CC + cc) * TAPS * CH * CH;
-#pragma unroll
-            for (int i = 0; i < B_VEC; ++i) pb[i] = *reinterpret_cast<const uint4 *>(src + (size_t)(tid + i * kThreads) * 16);
-        }
     };
-    auto commit = [&](int step, bool with_b) {
+    auto commit = [&](int step) {
+        if (V16) {
+            if (prow[0] != kSkip) {
+                const int cg = l16;
+#pragma unroll
+                for (int j4 = 0; j4 < 4; ++j4) {
+                    const uint32_t in[4] = {j4 == 0 ? pq[0].x : j4 == 1 ? pq[0].y : j4 == 2 ? pq[0].z : pq[0].w,
+                                            j4 == 0 ? pq[1].x : j4 == 1 ? pq[1].y : j4 == 2 ? pq[1].z : pq[1].w,
+                                            j4 == 0 ? pq[2].x : j4 == 1 ? pq[2].y : j4 == 2 ? pq[2].z : pq[2].w,
+                                            j4 == 0 ? pq[3].x : j4 == 1 ? pq[3].y : j4 == 2 ? pq[3].z : pq[3].w};
+                    uint32_t out[4];
+                    transpose4x4(in, out);
+                    // positions 4*j4 .. 4*j4+3 lie in one image row (W % 4 == 0); every row end
+                    // passed since the first position shifts the LDS row by one (the pad row)
+                    int bump = 0;
+                    if (TAPS == 9) {
+                        const int col = pthr[0] + 4 * j4;
+                        bump = (col >= W) + (col >= 2 * W) + (col >= 3 * W) + (col >= 4 * W);
+                    }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int row = prow[0] + 4 * j4 + i + bump;
+                        if (row >= 0 && row < sch.maxr) *reinterpret_cast<uint32_t *>(&As[row * ROWB + cg * 4]) = out[i];
+                    }
+                }
+            }
+        } else
 #pragma unroll
         for (int it = 0; it < MAX_SLABS; ++it) {
             if (prow[it] != kSkip) {
@@ -232,7 +293,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_s1_kernel(const int8_t *__re
         if (TAPS == 9) {
             // zero-point rows: the pad column after every image row and the pad row between images
             const int sub = step / CC;
-            const int g0 = row_begin + sub * BM;
+            const int g0 = tile_begin(sub);
             const int a0 = apad((uint32_t)g0) - (W1 + 1);
             for (int rr = tid; rr < sch.maxr; rr += kThreads) {
                 const int ac = a0 + rr;
@@ -250,41 +311,46 @@ __global__ __launch_bounds__(kThreads, 2) void conv_s1_kernel(const int8_t *__re
                 }
             }
         }
-        if (with_b) {
+    };
+    // weights of (occ, cc): [tap][64 oc][64 ch] from the packed copy (L2-resident) into LDS.
+    // 16-byte pieces; the 4 pieces of a row are XOR-swizzled by the row so that the b128
+    // fragment reads of 16 consecutive rows are conflict-free
+    auto stage_b = [&](int cc) {
+        const int8_t *src = wpk + (size_t)(occ * CC + cc) * TAPS * CH * CH;
 #pragma unroll
-            for (int i = 0; i < B_VEC; ++i) {
-                // 16-byte piece: row e/4 of [tap][oc], part e%4; parts are XOR-swizzled by the row
-                // so that the b128 fragment reads of 16 consecutive rows are conflict-free
-                const int e = tid + i * kThreads, row = e >> 2, part = e & 3;
-                *reinterpret_cast<uint4 *>(&Bs[row * CH + ((part ^ ((row >> 2) & 3)) << 4)]) = pb[i];
-            }
+        for (int i = 0; i < B_VEC; ++i) {
+            const int e = tid + i * kThreads, row = e >> 2, part = e & 3;
+            if (e < B_PIECES)
+                *reinterpret_cast<uint4 *>(&Bs[row * CH + ((part ^ ((row >> 2) & 3)) << 4)]) =
+                    *reinterpret_cast<const uint4 *>(src + (size_t)e * 16);
         }
     };
 
-    v4i acc[4][4], accrs[4];
-    int abase[4];
+    v4i acc[MT][4], accrs[MT];
+    int abase[MT];
     const v4i ones = (v4i){0x01010101, 0x01010101, 0x01010101, 0x01010101};
     const int bbase = l16 * CH + ((kb ^ (l16 >> 2)) << 4);
 
-    prefetch(0, true);
+    prefetch(0);
     for (int step = 0; step < nsteps; ++step) {
         const int sub = step / CC, cc = step - sub * CC;
-        const int g0 = row_begin + sub * BM;
+        const int g0 = tile_begin(sub), g1 = tile_end(sub);
         const bool with_b = (CC > 1) || (step == 0);
         __syncthreads();
-        commit(step, with_b);
+        commit(step);
+        if (with_b) stage_b(cc);
         __syncthreads();
-        if (step + 1 < nsteps) prefetch(step + 1, CC > 1);
+        if (step + 1 < nsteps) prefetch(step + 1);
 
         if (cc == 0) {
             const int ag0 = apad((uint32_t)g0);
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
+            for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
                 for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = (v4i){0, 0, 0, 0};
                 accrs[mt] = (v4i){0, 0, 0, 0};
                 // LDS address of this lane's A row in m-tile (mt*4 + wave), before the tap offset
-                int gr = g0 + (mt * 4 + wave) * 16 + l16;
+                int gr = g0 + (mt * kWaves + wave) * 16 + l16;
                 if (gr >= g.M) gr = g0;
                 abase[mt] = (apad((uint32_t)gr) - ag0) * ROWB + kb * 16;
             }
@@ -300,8 +366,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_s1_kernel(const int8_t *__re
             for (int nt = 0; nt < 4; ++nt)
                 bf[nt] = *reinterpret_cast<const v4i *>(&Bs[bbase + (tap * CH + nt * 16) * CH]);
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
-                if (g0 + (mt * 4 + wave) * 16 >= row_end) continue;   // wavefront-uniform
+            for (int mt = 0; mt < MT; ++mt) {
+                if (g0 + (mt * kWaves + wave) * 16 >= g1) continue;   // wavefront-uniform
                 const v4i a = *reinterpret_cast<const v4i *>(&As[abase[mt] + toff]);
 #pragma unroll
                 for (int nt = 0; nt < 4; ++nt)
@@ -319,9 +385,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv_s1_kernel(const int8_t *__re
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) csn[nt] = (uint32_t)za * (uint32_t)colsum[occ * CH + nt * 16 + l16];
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-            const int gr = g0 + (mt * 4 + wave) * 16 + kb * 4;
-            if (gr >= row_end) continue;
+        for (int mt = 0; mt < MT; ++mt) {
+            const int gr = g0 + (mt * kWaves + wave) * 16 + kb * 4;
+            if (gr >= g1) continue;
             const uint32_t b = divc<PQC>((uint32_t)gr, g.dPQ);
             const uint32_t pos = (uint32_t)gr - b * PQ;
             uint32_t t[4];
@@ -371,7 +437,7 @@ bool shape_ok(int which, const q8t_conv_desc *d)
     if (d->C % CH || d->K % CH) return false;
     if ((d->H * d->W) % 4) return false;
     if (d->H < 2 || d->W < 2 || d->N > 32768 || d->H > 32768) return false;   // quotient range of fdiv
-    if (d->R == 3 && (rows_needed(9, d->W, d->H * d->W) > MAXR9 || ((d->W + 1 + 3) & ~3) * 2 + BM > MAX_SLABS * 64))
+    if (d->R == 3 && (rows_needed(9, d->W, d->H * d->W) > MAXR9 || ((d->W + 1 + 3) & ~3) * 2 + BM > MAX_SLABS * kWaves / 4 * 64))
         return false;
     return true;
 }
@@ -402,19 +468,19 @@ size_t q8t_fast_conv_ws(int which, const q8t_conv_desc *d)
     return ((wbytes + 255) & ~(size_t)255) + (size_t)oc * sizeof(int);
 }
 
-template <int TAPS, int WC>
+template <int TAPS, int WC, bool V16>
 int launch_conv(dim3 grid, hipStream_t st, const int8_t *a, const int8_t *wpk, const int *colsum,
                 const q8t_qparams *qa, const q8t_qparams *qb, const FastGeom &g, const Sched &sch, float *out_f,
                 int32_t *out_acc)
 {
     static bool attr = false;
     if (!attr && smem_bytes<TAPS>() > 65536) {
-        if (hipFuncSetAttribute((const void *)conv_s1_kernel<TAPS, WC>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute((const void *)conv_s1_kernel<TAPS, WC, V16>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)smem_bytes<TAPS>()) != hipSuccess)
             return Q8T_ERR_HIP;
         attr = true;
     }
-    hipLaunchKernelGGL((conv_s1_kernel<TAPS, WC>), grid, dim3(kThreads), smem_bytes<TAPS>(), st, a, wpk, colsum, qa,
+    hipLaunchKernelGGL((conv_s1_kernel<TAPS, WC, V16>), grid, dim3(kThreads), smem_bytes<TAPS>(), st, a, wpk, colsum, qa,
                        qb, g, sch, out_f, out_acc);
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
@@ -441,30 +507,37 @@ int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
     g.dW = mkdiv(g.W);
     g.dW1 = mkdiv(W1);
     g.dIMG = mkdiv(taps == 9 ? (d->H + 1) * W1 : g.PQ);
-    hipLaunchKernelGGL(repack_weights, dim3(g.K), dim3(kThreads), 0, st, (const int8_t *)b, d->K, d->C, d->R, d->S,
+    hipLaunchKernelGGL(repack_weights, dim3(g.K), dim3(kRepackThreads), 0, st, (const int8_t *)b, d->K, d->C, d->R, d->S,
                        which, wpk, colsum);
     Q8T_LAUNCH_CHECK();
     Sched sch;
     const int occs = g.K / CH;
-    int nbx = 512 / occs;                       // two workgroups per compute unit in total
+    int nbx = 512 / occs;                       // two workgroups (16 wavefronts) per compute unit in total
     const int max_useful = (g.M + 63) / 64;     // no point in ranges shorter than 64 rows
     if (nbx > max_useful) nbx = max_useful;
     nbx = ((nbx + 7) / 8) * 8;
     sch.nbx = nbx;
     sch.rpb = ((g.M + nbx - 1) / nbx + 15) / 16 * 16;
-    sch.halo_al = taps == 9 ? ((g.W + 1 + 3) & ~3) : 0;
+    // wide staging needs 16-position groups that never straddle an image or start mid-row group
+    const bool v16 = (g.PQ % 16 == 0) && (g.W % 4 == 0) && g.W >= 4 && q8t_aligned(a, 16);
+    sch.halo_al = taps == 9 ? (v16 ? ((g.W + 1 + 15) & ~15) : ((g.W + 1 + 3) & ~3)) : 0;
     sch.pg_blocks = (((BM + 2 * sch.halo_al) >> 2) + 15) / 16;
     sch.maxr = rows_needed(taps, g.W, g.PQ);
     const dim3 grid((unsigned)nbx, (unsigned)occs);
     const int8_t *pa = (const int8_t *)a;
     int32_t *pacc = (int32_t *)out_acc;
     const bool sq = d->H == d->W;
+#define Q8T_CONV(T, WCV, V) return launch_conv<T, WCV, V>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc)
     if (taps == 9) {
-        if (sq && d->W == 56) return launch_conv<9, 56>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc);
-        if (sq && d->W == 28) return launch_conv<9, 28>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc);
-        if (sq && d->W == 14) return launch_conv<9, 14>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc);
-        return launch_conv<9, 0>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc);
+        if (sq && d->W == 56 && v16) Q8T_CONV(9, 56, true);
+        if (sq && d->W == 28 && v16) Q8T_CONV(9, 28, true);
+        if (sq && d->W == 14) Q8T_CONV(9, 14, false);
+        if (v16) Q8T_CONV(9, 0, true);
+        Q8T_CONV(9, 0, false);
     }
-    if (sq && d->W == 56) return launch_conv<1, 56>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc);
-    return launch_conv<1, 0>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc);
+    if (sq && d->W == 56 && v16) Q8T_CONV(1, 56, true);
+    if (v16) Q8T_CONV(1, 0, true);
+    Q8T_CONV(1, 0, false);
+#undef Q8T_CONV
 }
+

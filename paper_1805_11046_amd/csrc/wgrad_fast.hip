@@ -45,6 +45,7 @@ constexpr int SMEM_BYTES = 2 * SLOT_INTS * 4;          // reduction slots (large
 struct WGeom {
     int N, C, K, H, W, PQ;
     int pitch, Lp;        // padded row pitch, padded positions per image (H*pitch)
+    float rpitch;         // 1/pitch
     int chunks;           // chunks per image
     int ncg, nrg;         // channel groups (C/16), row groups (K/64)
     int S, ipr;           // k-ranges, images per k-range
@@ -52,6 +53,8 @@ struct WGeom {
 
 __device__ __forceinline__ int dot4_ones(int v, int acc) { return __builtin_amdgcn_sdot4(v, 0x01010101, acc, false); }
 
+// WC > 0 fixes the image width at compile time (constant-divisor index arithmetic)
+template <int WC>
 __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restrict__ g16,
                                                           const int8_t *__restrict__ x,
                                                           const q8t_qparams *__restrict__ qpg,
@@ -59,6 +62,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
                                                           int *__restrict__ partial)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    const int Wd = WC ? WC : g.W, pitch = WC ? WC + 4 : g.pitch;
     uint8_t *As = smem;              // [plane][row][APITCH]
     uint8_t *Bs = smem + A_BYTES;    // [channel][BPITCH]
 
@@ -91,14 +95,23 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
 
     uint2 regA[8];
     uint32_t regB[3];
+    // position / pitch: quotients are image rows (< 2^15), a float estimate with fix-up is exact
+    auto pdiv = [&](uint32_t n) -> uint32_t {
+        if (WC) return n / (uint32_t)(WC ? WC + 4 : 1);
+        uint32_t q = (uint32_t)((float)n * g.rpitch);
+        const int rem = (int)(n - q * (uint32_t)pitch);
+        if (rem < 0) --q;
+        else if (rem >= pitch) ++q;
+        return q;
+    };
 
     auto load_regs = [&](int u) {
         const int b = img0 + u / g.chunks, kp0 = (u % g.chunks) * KC;
         {   // gradient rows: wavefront w stages rows w, w+8, ...; lane = group of 4 positions
             const int kp = kp0 + 4 * lane;
-            const int p = kp / g.pitch, qq = kp - p * g.pitch;
-            const bool valid = kp < g.Lp && qq < g.W;
-            const int16_t *src = g16 + ((int64_t)b * g.K + rg * 64 + wave) * g.PQ + p * g.W + qq;
+            const int p = (int)pdiv((uint32_t)kp), qq = kp - p * pitch;
+            const bool valid = kp < g.Lp && qq < Wd;
+            const int16_t *src = g16 + ((int64_t)b * g.K + rg * 64 + wave) * g.PQ + p * Wd + qq;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 regA[i] = make_uint2(a_pad, a_pad);
@@ -112,11 +125,11 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
             const int kp = kp0 - HALO + 4 * gi;
             bool valid = kp >= 0 && kp < g.Lp;
             const int kpc = valid ? kp : 0;
-            const int p = kpc / g.pitch, qq = kpc - p * g.pitch;
-            valid = valid && qq < g.W;
+            const int p = (int)pdiv((uint32_t)kpc), qq = kpc - p * pitch;
+            valid = valid && qq < Wd;
             regB[i] = b_pad;
             if (valid)
-                regB[i] = *reinterpret_cast<const uint32_t *>(x + ((int64_t)b * g.C + cg * 16 + c) * g.PQ + p * g.W + qq);
+                regB[i] = *reinterpret_cast<const uint32_t *>(x + ((int64_t)b * g.C + cg * 16 + c) * g.PQ + p * Wd + qq);
         }
     };
     auto write_lds = [&]() {
@@ -152,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
             }
 #pragma unroll
             for (int r = 0; r < 3; ++r) {
-                const int base = HALO + kl * 64 + kb * 16 + (r - 1) * g.pitch - 4;
+                const int base = HALO + kl * 64 + kb * 16 + (r - 1) * pitch - 4;
                 uint32_t d[6];
 #pragma unroll
                 for (int i = 0; i < 6; ++i) d[i] = *reinterpret_cast<const uint32_t *>(&Bs[l16 * BPITCH + base + 4 * i]);
@@ -166,7 +179,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
 #pragma unroll
                 for (int s = 0; s < 3; ++s) {
                     const int tap = r * 3 + s;
-                    cs[tap] = dot4_ones(f[s][0], dot4_ones(f[s][1], dot4_ones(f[s][2], dot4_ones(f[s][3], cs[tap]))));
+                    if (plane == 0)   // wavefront-uniform: one plane gathers the column sums
+                        cs[tap] = dot4_ones(f[s][0], dot4_ones(f[s][1], dot4_ones(f[s][2], dot4_ones(f[s][3], cs[tap]))));
 #pragma unroll
                     for (int mt = 0; mt < 4; ++mt)
                         acc[mt][tap] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mt], f[s], acc[mt][tap], 0, 0, 0);
@@ -242,25 +256,27 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
     }
 }
 
-// int64 reduction over the k-ranges + zero-point correction + dequantization
+// int64 reduction over the k-ranges + zero-point correction + dequantization.
+// Workgroup = 64 accumulator slots x 4 quarters of the k-ranges, folded through LDS.
 __global__ __launch_bounds__(256) void wgrad_reduce(const int *__restrict__ partial, WGeom g,
                                                     const q8t_qparams *__restrict__ qpg,
                                                     const q8t_qparams *__restrict__ qpx, float *__restrict__ dw,
                                                     int64_t *__restrict__ acc_out)
 {
+    __shared__ int64_t fold[4][64];
     const int sub = blockIdx.y;               // (rg, cg)
     const int cg = sub % g.ncg, rg = sub / g.ncg;
-    const int idx = blockIdx.x * 256 + threadIdx.x;   // ((mt*9 + tap)*4 + j)*64 + lane, < 9216
-    const int lane = idx & 63, j = (idx >> 6) & 3, mt_tap = idx >> 8;
+    const int lane = threadIdx.x & 63, quarter = threadIdx.x >> 6;
+    const int idx = blockIdx.x * 64 + lane;   // ((mt*9 + tap)*4 + j)*64 + lane, < 9216
+    const int j = (idx >> 6) & 3, mt_tap = idx >> 8;
     const int tap = mt_tap % 9, mt = mt_tap / 9;
     const int row_l = mt * 16 + (lane >> 4) * 4 + j, ch_l = lane & 15;
 
     const int zsg = qpg->zero_point - 32768, zsx = qpx->zero_point - 128;
-    const double sc = (double)(qpg->scale * qpx->scale);
     const int64_t ca = 128 - zsg;
     const int ksteps_img = (g.Lp + 63) / 64;
     int64_t v = 0;
-    for (int kr = 0; kr < g.S; ++kr) {
+    for (int kr = quarter; kr < g.S; kr += 4) {
         const int *p = partial + ((int64_t)(kr * g.nrg + rg) * g.ncg + cg) * PART_INTS;
         const int nimg = min(g.N, (kr + 1) * g.ipr) - kr * g.ipr;
         const int64_t Kp = (int64_t)nimg * ksteps_img * 64;
@@ -269,9 +285,15 @@ __global__ __launch_bounds__(256) void wgrad_reduce(const int *__restrict__ part
         const int64_t rsh = p[TILE_INTS + 144 + row_l], rsl = p[TILE_INTS + 144 + 64 + row_l];
         v += 256 * hi + lo + ca * csv - (int64_t)zsx * (256 * rsh + rsl + ca * Kp);
     }
-    const int64_t o = ((int64_t)(rg * 64 + row_l) * g.C + cg * 16 + ch_l) * 9 + tap;
-    if (acc_out) acc_out[o] = v;
-    if (dw) dw[o] = (float)((double)v * sc);
+    fold[quarter][lane] = v;
+    __syncthreads();
+    if (quarter == 0) {
+        v = fold[0][lane] + fold[1][lane] + fold[2][lane] + fold[3][lane];
+        const double sc = (double)(qpg->scale * qpx->scale);
+        const int64_t o = ((int64_t)(rg * 64 + row_l) * g.C + cg * 16 + ch_l) * 9 + tap;
+        if (acc_out) acc_out[o] = v;
+        if (dw) dw[o] = (float)((double)v * sc);
+    }
 }
 
 bool wgrad_shape_ok(const q8t_conv_desc *d)
@@ -289,6 +311,7 @@ WGeom wgrad_geom(const q8t_conv_desc *d)
     g.N = d->N; g.C = d->C; g.K = d->K; g.H = d->H; g.W = d->W; g.PQ = d->H * d->W;
     g.pitch = d->W + 4;
     g.Lp = d->H * g.pitch;
+    g.rpitch = 1.0f / (float)g.pitch;
     g.chunks = (g.Lp + KC - 1) / KC;
     g.ncg = d->C / 16;
     g.nrg = d->K / 64;
@@ -301,6 +324,22 @@ WGeom wgrad_geom(const q8t_conv_desc *d)
     if (g.ipr > max_ipr) g.ipr = max_ipr > 0 ? max_ipr : 1;
     g.S = (d->N + g.ipr - 1) / g.ipr;
     return g;
+}
+
+template <int WC>
+int launch_wgrad(int blocks, hipStream_t st, const int16_t *g16, const int8_t *x, const q8t_qparams *qg,
+                 const q8t_qparams *qx, const WGeom &g, int *ws)
+{
+    static bool attr = false;
+    if (!attr) {
+        if (hipFuncSetAttribute((const void *)wgrad_s1_3x3<WC>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                SMEM_BYTES) != hipSuccess)
+            return Q8T_ERR_HIP;
+        attr = true;
+    }
+    hipLaunchKernelGGL(wgrad_s1_3x3<WC>, dim3(blocks), dim3(kThreads), SMEM_BYTES, st, g16, x, qg, qx, g, ws);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
 }
 
 }  // namespace
@@ -325,18 +364,13 @@ int q8t_fast_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams
 {
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
     const WGeom g = wgrad_geom(d);
-    static bool attr = false;
-    if (!attr) {
-        if (hipFuncSetAttribute((const void *)wgrad_s1_3x3, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                SMEM_BYTES) != hipSuccess)
-            return Q8T_ERR_HIP;
-        attr = true;
-    }
     const int per = g.ncg * g.nrg;
     const int blocks = ((g.S + 7) / 8) * 8 * per;
-    hipLaunchKernelGGL(wgrad_s1_3x3, dim3(blocks), dim3(kThreads), SMEM_BYTES, st, g16, x, qg, qx, g, (int *)ws);
-    Q8T_LAUNCH_CHECK();
-    hipLaunchKernelGGL(wgrad_reduce, dim3(9216 / 256, per), dim3(256), 0, st, (const int *)ws, g, qg, qx, dw,
+    const int rc = d->W == 56   ? launch_wgrad<56>(blocks, st, g16, x, qg, qx, g, (int *)ws)
+                   : d->W == 28 ? launch_wgrad<28>(blocks, st, g16, x, qg, qx, g, (int *)ws)
+                                : launch_wgrad<0>(blocks, st, g16, x, qg, qx, g, (int *)ws);
+    if (rc) return rc;
+    hipLaunchKernelGGL(wgrad_reduce, dim3(9216 / 64, per), dim3(256), 0, st, (const int *)ws, g, qg, qx, dw,
                        acc_out);
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
