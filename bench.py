@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--batch", type=int, default=128)
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-batch", type=int, default=32)
+    ap.add_argument("--cpu-batch", type=int, default=128)
     return ap.parse_args()
 
 
@@ -189,6 +189,11 @@ def main():
         ach = dom_bytes / dom_us / 1e3
         roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
+    try:   # HBM bytes per call measured with rocprofv3 --pmc (profiles/), if recorded for this call
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic_layer_step.json")) as f:
+            roofline["traffic"] = json.load(f).get(dominant) if args.batch == 128 else None
+    except OSError:
+        pass
     roofline["kernel"] = dominant
     roofline["us_per_launch"] = round(dom_us, 2)
 
