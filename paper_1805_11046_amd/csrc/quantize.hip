@@ -52,17 +52,21 @@ __global__ __launch_bounds__(kThreads) void minmax_partials(const float *__restr
     const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     if (VEC) {
+        // each workgroup streams one contiguous slice (better DRAM channel spread than a
+        // grid-wide stride), 4 independent 16-byte loads in flight per lane
         const int64_t n4 = n >> 2;
         const float4 *x4 = reinterpret_cast<const float4 *>(x);
-        int64_t i = gid;
-        for (; i + 3 * stride < n4; i += 4 * stride) {
-            const float4 a = x4[i], b = x4[i + stride], c = x4[i + 2 * stride], d = x4[i + 3 * stride];
+        const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
+        const int64_t lo = (int64_t)blockIdx.x * per, hi = min(n4, lo + per);
+        int64_t i = lo + threadIdx.x;
+        for (; i + 3 * kThreads < hi; i += 4 * kThreads) {
+            const float4 a = x4[i], b = x4[i + kThreads], c = x4[i + 2 * kThreads], d = x4[i + 3 * kThreads];
             mm4(mn, mx, a);
             mm4(mn, mx, b);
             mm4(mn, mx, c);
             mm4(mn, mx, d);
         }
-        for (; i < n4; i += stride) mm4(mn, mx, x4[i]);
+        for (; i < hi; i += kThreads) mm4(mn, mx, x4[i]);
         const int64_t tail = (n4 << 2) + gid;  // the n % 4 leftover elements
         if (tail < n) {
             mn = fminf(mn, x[tail]);
@@ -175,16 +179,17 @@ __global__ __launch_bounds__(kThreads) void quantize_apply(
         const int64_t n4 = n >> 2;
         const float4 *x4 = reinterpret_cast<const float4 *>(x);
         P *q4 = reinterpret_cast<P *>(q_out);
-        int64_t i = gid;
-        for (; i + 3 * stride < n4; i += 4 * stride) {
-            const float4 v0 = x4[i], v1 = x4[i + stride], v2 = x4[i + 2 * stride],
-                         v3 = x4[i + 3 * stride];
+        const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
+        const int64_t lo = (int64_t)blockIdx.x * per, hi = min(n4, lo + per);
+        int64_t i = lo + threadIdx.x;
+        for (; i + 3 * kThreads < hi; i += 4 * kThreads) {
+            const float4 v0 = x4[i], v1 = x4[i + kThreads], v2 = x4[i + 2 * kThreads], v3 = x4[i + 3 * kThreads];
             q4[i] = quant4<OUT, STOCH>(v0, a, (uint32_t)i, seed_lo, seed_hi);
-            q4[i + stride] = quant4<OUT, STOCH>(v1, a, (uint32_t)(i + stride), seed_lo, seed_hi);
-            q4[i + 2 * stride] = quant4<OUT, STOCH>(v2, a, (uint32_t)(i + 2 * stride), seed_lo, seed_hi);
-            q4[i + 3 * stride] = quant4<OUT, STOCH>(v3, a, (uint32_t)(i + 3 * stride), seed_lo, seed_hi);
+            q4[i + kThreads] = quant4<OUT, STOCH>(v1, a, (uint32_t)(i + kThreads), seed_lo, seed_hi);
+            q4[i + 2 * kThreads] = quant4<OUT, STOCH>(v2, a, (uint32_t)(i + 2 * kThreads), seed_lo, seed_hi);
+            q4[i + 3 * kThreads] = quant4<OUT, STOCH>(v3, a, (uint32_t)(i + 3 * kThreads), seed_lo, seed_hi);
         }
-        for (; i < n4; i += stride) q4[i] = quant4<OUT, STOCH>(x4[i], a, (uint32_t)i, seed_lo, seed_hi);
+        for (; i < hi; i += kThreads) q4[i] = quant4<OUT, STOCH>(x4[i], a, (uint32_t)i, seed_lo, seed_hi);
         const int64_t tail = (n4 << 2) + gid;
         if (tail < n) {
             const uint32_t r = STOCH ? rng_r16(tail, seed_lo, seed_hi) : 0u;
@@ -222,15 +227,17 @@ __global__ __launch_bounds__(kThreads) void quantize_bifurcate_apply(
         const float4 *x4 = reinterpret_cast<const float4 *>(x);
         uint32_t *o8 = reinterpret_cast<uint32_t *>(q8);
         uint2 *o16 = reinterpret_cast<uint2 *>(q16);
-        int64_t i = gid;
-        for (; i + stride < n4; i += 2 * stride) {
-            const float4 v0 = x4[i], v1 = x4[i + stride];
+        const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
+        const int64_t lo = (int64_t)blockIdx.x * per, hi = min(n4, lo + per);
+        int64_t i = lo + threadIdx.x;
+        for (; i + kThreads < hi; i += 2 * kThreads) {
+            const float4 v0 = x4[i], v1 = x4[i + kThreads];
             o8[i] = quant4<int8_t, true>(v0, a8, (uint32_t)i, s8_lo, s8_hi);
             o16[i] = quant4<int16_t, true>(v0, a16, (uint32_t)i, s16_lo, s16_hi);
-            o8[i + stride] = quant4<int8_t, true>(v1, a8, (uint32_t)(i + stride), s8_lo, s8_hi);
-            o16[i + stride] = quant4<int16_t, true>(v1, a16, (uint32_t)(i + stride), s16_lo, s16_hi);
+            o8[i + kThreads] = quant4<int8_t, true>(v1, a8, (uint32_t)(i + kThreads), s8_lo, s8_hi);
+            o16[i + kThreads] = quant4<int16_t, true>(v1, a16, (uint32_t)(i + kThreads), s16_lo, s16_hi);
         }
-        for (; i < n4; i += stride) {
+        for (; i < hi; i += kThreads) {
             const float4 v0 = x4[i];
             o8[i] = quant4<int8_t, true>(v0, a8, (uint32_t)i, s8_lo, s8_hi);
             o16[i] = quant4<int16_t, true>(v0, a16, (uint32_t)i, s16_lo, s16_hi);
@@ -280,7 +287,7 @@ int launch_apply(const float *x, int64_t n, int bits, int stochastic, uint64_t s
                  const float2 *partials, int npartials, OUT *q, q8t_qparams *qp, hipStream_t st)
 {
     const bool vec = q8t_aligned(x, 16) && q8t_aligned(q, 4 * sizeof(OUT));
-    const int grid = grid_for(vec ? (n >> 2) : n, 4, 8192);
+    const int grid = grid_for(vec ? (n >> 2) : n, 4, 2048);
     const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
 #define Q8T_GO(S, V) \
     hipLaunchKernelGGL((quantize_apply<OUT, S, V>), dim3(grid), dim3(kThreads), 0, st, x, n, bits, lo, hi, partials, npartials, q, qp)
@@ -298,7 +305,7 @@ int launch_minmax(const float *x, int64_t n, float2 *partials, hipStream_t st)
 {
     if (n == 0) return 0;
     const bool vec = q8t_aligned(x, 16);
-    const int grid = grid_for(vec ? (n >> 2) : n, 8, kMaxPartials);
+    const int grid = grid_for(vec ? (n >> 2) : n, 8, 1024);
     if (vec)
         hipLaunchKernelGGL(minmax_partials<true>, dim3(grid), dim3(kThreads), 0, st, x, n, partials);
     else
@@ -359,7 +366,7 @@ int q8t_quantize_bifurcate(const float *g, int64_t n, uint64_t seed8, uint64_t s
     const int np = launch_minmax(g, n, partials, st);
     Q8T_LAUNCH_CHECK();
     const bool vec = q8t_aligned(g, 16) && q8t_aligned(q8_out, 4) && q8t_aligned(q16_out, 8);
-    const int grid = grid_for(vec ? (n >> 2) : n, 2, 8192);
+    const int grid = grid_for(vec ? (n >> 2) : n, 2, 2048);
     if (vec)
         hipLaunchKernelGGL(quantize_bifurcate_apply<true>, dim3(grid), dim3(kThreads), 0, st, g, n,
                            (uint32_t)seed8, (uint32_t)(seed8 >> 32), (uint32_t)seed16,

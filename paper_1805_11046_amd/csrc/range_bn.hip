@@ -157,9 +157,33 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_finalize(const FwdPartial *__
 
 // ---- forward, pass 2 ----------------------------------------------------------------------------
 // one (image, channel) plane per workgroup iteration
+// fold the slices of one channel inside a wavefront (lane k holds slice k; fixed butterfly order,
+// so every workgroup of the channel obtains bit-identical statistics)
+__device__ __forceinline__ void fold_fwd_parts(const FwdPartial *__restrict__ parts, int c, int split, double n,
+                                               float &mu, float &mn, float &mx)
+{
+    const int lane = threadIdx.x & 63;
+    double s = 0.0;
+    float a = INFINITY, b = -INFINITY;
+    if (lane < split) {
+        const FwdPartial p = parts[(int64_t)c * split + lane];
+        s = p.sum;
+        a = p.mn;
+        b = p.mx;
+    }
+    s = wave_reduce(s, OpAddD());
+    mn = wave_reduce(a, OpMin());
+    mx = wave_reduce(b, OpMax());
+    mu = (float)(s / n);
+}
+
+// With `parts` != NULL the statistics are folded here from the slices of pass 1 (and written to
+// `stats` by the workgroups of image 0), which saves the separate finalize launch.
 template <bool VEC, bool QOUT>
 __global__ __launch_bounds__(kThreads) void bn_fwd_apply(const float *__restrict__ x, int64_t planes,
-                                                         int C, int HW, const float *__restrict__ stats,
+                                                         int C, int HW, float *__restrict__ stats,
+                                                         const FwdPartial *__restrict__ parts, int split,
+                                                         double n,
                                                          const float *__restrict__ gamma,
                                                          const float *__restrict__ beta, float cn,
                                                          float eps, float *__restrict__ y,
@@ -170,8 +194,20 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_apply(const float *__restrict
     if (QOUT) a = affine_of(*qp);
     for (int64_t pl = blockIdx.x; pl < planes; pl += gridDim.x) {
         const int c = (int)(pl % C);
-        const float mu = stats[c];
-        const float inv = bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
+        float mu, cmn, cmx;
+        if (parts) {
+            fold_fwd_parts(parts, c, split, n, mu, cmn, cmx);   // every wavefront folds the same slices
+            if (pl < C && threadIdx.x == 0) {
+                stats[c] = mu;
+                stats[C + c] = cmn;
+                stats[2 * C + c] = cmx;
+            }
+        } else {
+            mu = stats[c];
+            cmn = stats[C + c];
+            cmx = stats[2 * C + c];
+        }
+        const float inv = bn_inv(cmn, cmx, cn, eps);
         const float g = gamma ? gamma[c] : 1.0f, b = beta ? beta[c] : 0.0f;
         const int64_t base = pl * HW;
         if (VEC) {
@@ -316,20 +352,43 @@ __device__ __forceinline__ float bn_dx(float xv, float dyv, float g, float mean_
     return v;
 }
 
+// With `parts` != NULL the per-channel sums are folded here (fixed butterfly order inside a
+// wavefront) and dgamma / dbeta are written by the workgroups of image 0: no finalize launch.
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void bn_bwd_apply(const float *__restrict__ x,
                                                          const float *__restrict__ dy, int64_t planes,
                                                          int C, int HW, const float *__restrict__ stats,
                                                          const float *__restrict__ gamma,
-                                                         const float2 *__restrict__ consts, float cn,
-                                                         float eps, float *__restrict__ dx)
+                                                         const float2 *__restrict__ consts,
+                                                         const double2 *__restrict__ parts, int split, double n,
+                                                         float *__restrict__ dgamma, float *__restrict__ dbeta,
+                                                         float cn, float eps, float *__restrict__ dx)
 {
     for (int64_t pl = blockIdx.x; pl < planes; pl += gridDim.x) {
         const int c = (int)(pl % C);
         const float mn = stats[C + c], mx = stats[2 * C + c];
         const float inv = bn_inv(mn, mx, cn, eps);
         const float g = gamma ? gamma[c] : 1.0f;
-        const float2 k = consts[c];
+        float2 k;
+        if (parts) {
+            const int lane = threadIdx.x & 63;
+            double s0 = 0.0, s1 = 0.0;
+            if (lane < split) {
+                const double2 p = parts[(int64_t)c * split + lane];
+                s0 = p.x;
+                s1 = p.y;
+            }
+            s0 = wave_reduce(s0, OpAddD());
+            s1 = wave_reduce(s1, OpAddD());
+            if (pl < C && threadIdx.x == 0) {
+                if (dbeta) dbeta[c] = (float)s0;
+                if (dgamma) dgamma[c] = (float)s1;
+            }
+            const double A = (double)g * s0, B = (double)g * s1;
+            k = make_float2((float)(A / n), (float)((double)inv * (double)cn * B));
+        } else {
+            k = consts[c];
+        }
         const int64_t base = pl * HW;
         if (VEC) {
             const float4 *px = reinterpret_cast<const float4 *>(x + base);
@@ -428,15 +487,21 @@ int q8t_range_bn_fwd(const float *x, int N, int C, int H, int W, const float *ga
     else
         hipLaunchKernelGGL(bn_stats_partial<false>, dim3(C, nsplit), dim3(kThreads), 0, st, x, N, C, HW, NB, parts);
     Q8T_LAUNCH_CHECK();
-    hipLaunchKernelGGL(bn_fwd_finalize, dim3(1), dim3(kThreads), 0, st, parts, C, nsplit, n, cn, eps, gamma,
-                       beta, stats_out, q_out ? qp_out : (q8t_qparams *)nullptr);
-    Q8T_LAUNCH_CHECK();
+    // the per-tensor range of the fused 8-bit output needs all channels: separate finalize then.
+    // Otherwise the plane kernel folds the slices itself (one launch less).
+    const bool fused = !q_out && y && HW >= 256;
+    if (!fused) {
+        hipLaunchKernelGGL(bn_fwd_finalize, dim3(1), dim3(kThreads), 0, st, parts, C, nsplit, n, cn, eps, gamma,
+                           beta, stats_out, q_out ? qp_out : (q8t_qparams *)nullptr);
+        Q8T_LAUNCH_CHECK();
+    }
     if (!y && !q_out) return Q8T_OK;
     const int64_t planes = (int64_t)N * C;
+    const FwdPartial *fparts = fused ? parts : (const FwdPartial *)nullptr;
     if (HW >= 256) {
         const dim3 grid(planes_grid(planes));
 #define Q8T_GO(V, Q) \
-    hipLaunchKernelGGL((bn_fwd_apply<V, Q>), grid, dim3(kThreads), 0, st, x, planes, C, HW, stats_out, gamma, beta, cn, eps, y, q_out, qp_out)
+    hipLaunchKernelGGL((bn_fwd_apply<V, Q>), grid, dim3(kThreads), 0, st, x, planes, C, HW, stats_out, fparts, nsplit, n, gamma, beta, cn, eps, y, q_out, qp_out)
         if (vec) { if (q_out) Q8T_GO(true, true); else Q8T_GO(true, false); }
         else     { if (q_out) Q8T_GO(false, true); else Q8T_GO(false, false); }
 #undef Q8T_GO
@@ -474,17 +539,20 @@ int q8t_range_bn_bwd(const float *x, const float *dy, const float *stats, int N,
     else
         hipLaunchKernelGGL(bn_bwd_partial<false>, dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn, eps, parts);
     Q8T_LAUNCH_CHECK();
-    hipLaunchKernelGGL(bn_bwd_finalize, dim3((C + kThreads - 1) / kThreads), dim3(kThreads), 0, st, parts, C,
-                       nsplit, n, cn, eps, stats, gamma, dgamma, dbeta, consts);
-    Q8T_LAUNCH_CHECK();
+    const bool fused = dx && HW >= 256;
+    if (!fused) {
+        hipLaunchKernelGGL(bn_bwd_finalize, dim3((C + kThreads - 1) / kThreads), dim3(kThreads), 0, st, parts, C,
+                           nsplit, n, cn, eps, stats, gamma, dgamma, dbeta, consts);
+        Q8T_LAUNCH_CHECK();
+    }
     if (!dx) return Q8T_OK;
     const int64_t planes = (int64_t)N * C;
     if (HW >= 256) {
         const dim3 grid(planes_grid(planes));
         if (vec)
-            hipLaunchKernelGGL(bn_bwd_apply<true>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, cn, eps, dx);
+            hipLaunchKernelGGL(bn_bwd_apply<true>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx);
         else
-            hipLaunchKernelGGL(bn_bwd_apply<false>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, cn, eps, dx);
+            hipLaunchKernelGGL(bn_bwd_apply<false>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx);
     } else {
         const int64_t total = planes * HW;
         const dim3 grid((unsigned)((total + kThreads - 1) / kThreads < 65536 * 16 ? (total + kThreads - 1) / kThreads : 65536 * 16));
