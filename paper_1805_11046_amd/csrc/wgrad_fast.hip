@@ -31,16 +31,17 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int kThreads = 512;
 constexpr int KC = 256;               // padded positions per staged chunk (4 K-steps of 64)
 constexpr int APITCH = KC + 16;       // LDS bytes per gradient row and byte plane
-constexpr int HALO = 64;              // staged halo on either side of the input chunk (>= pitch+1, mult. of 4)
+constexpr int HALO = 72;              // staged halo on either side of the input chunk (>= pitch+1, mult. of 8)
 constexpr int BROW = KC + 2 * HALO;   // staged input bytes per channel
-constexpr int BPITCH = BROW + 20;     // 404 bytes = 101 dwords: at most 2-way bank conflicts for the
+constexpr int BPITCH = BROW + 4;      // 404 bytes = 101 dwords: at most 2-way bank conflicts for the
                                       // (16 channels x 4 k-blocks) dword reads of one wavefront
 constexpr int A_BYTES = 2 * 64 * APITCH;
 constexpr int B_BYTES = 16 * BPITCH;
 constexpr int TILE_INTS = 2 * 4 * 9 * 4 * 64;          // [plane][mt][tap][j][lane]
 constexpr int PART_INTS = TILE_INTS + 9 * 16 + 2 * 64; // + column sums [tap][ch] + row sums [plane][row]
 constexpr int SLOT_INTS = 36 * 4 * 64 + 16 * 64;       // one wavefront's accumulators + its sums
-constexpr int SMEM_BYTES = 2 * SLOT_INTS * 4;          // reduction slots (larger than the staging area)
+constexpr int BUF_BYTES = A_BYTES + B_BYTES;           // one staging buffer (two are used)
+constexpr int SMEM_BYTES = 2 * BUF_BYTES > 2 * SLOT_INTS * 4 ? 2 * BUF_BYTES : 2 * SLOT_INTS * 4;
 
 struct WGeom {
     int N, C, K, H, W, PQ;
@@ -62,9 +63,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
                                                           int *__restrict__ partial)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    const int Wd = WC ? WC : g.W, pitch = WC ? WC + 4 : g.pitch;
-    uint8_t *As = smem;              // [plane][row][APITCH]
-    uint8_t *Bs = smem + A_BYTES;    // [channel][BPITCH]
+    constexpr bool WIDE = WC > 0 && WC % 8 == 0;          // rows are 16-byte aligned: wide staging
+    constexpr int PITCHC = WIDE ? WC + 8 : WC + 4;
+    const int Wd = WC ? WC : g.W, pitch = WC ? PITCHC : g.pitch;
 
     // XCD-aware decode: workgroups that share a k-range (same gradient rows) sit on one XCD
     const int bid = blockIdx.x;
@@ -93,11 +94,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
     int cs[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
     int rs[4] = {0, 0, 0, 0};
 
-    uint2 regA[8];
-    uint32_t regB[3];
+    // staging registers: one chunk (64 gradient rows x 256 positions, 16 input channels x BROW)
+    uint4 regA[4];
+    uint2 regB[WIDE ? 2 : 4];
     // position / pitch: quotients are image rows (< 2^15), a float estimate with fix-up is exact
     auto pdiv = [&](uint32_t n) -> uint32_t {
-        if (WC) return n / (uint32_t)(WC ? WC + 4 : 1);
+        if (WC) return n / (uint32_t)(WC ? PITCHC : 1);
         uint32_t q = (uint32_t)((float)n * g.rpitch);
         const int rem = (int)(n - q * (uint32_t)pitch);
         if (rem < 0) --q;
@@ -107,86 +109,151 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
 
     auto load_regs = [&](int u) {
         const int b = img0 + u / g.chunks, kp0 = (u % g.chunks) * KC;
-        {   // gradient rows: wavefront w stages rows w, w+8, ...; lane = group of 4 positions
+        if (WIDE) {
+            // pieces of 8 positions: 16-byte gradient loads, 8-byte input loads (the vector memory
+            // pipeline is paid per instruction, not per byte)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = tid + kThreads * i, row = e >> 5, pi = e & 31;
+                const int kp = kp0 + 8 * pi;
+                const int p = (int)pdiv((uint32_t)kp), qq = kp - p * pitch;
+                regA[i] = make_uint4(a_pad, a_pad, a_pad, a_pad);
+                if (kp < g.Lp && qq < Wd)
+                    regA[i] = *reinterpret_cast<const uint4 *>(g16 + ((int64_t)b * g.K + rg * 64 + row) * g.PQ + p * Wd + qq);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int e = tid + kThreads * i, c = e / (BROW / 8), pi = e - c * (BROW / 8);
+                const int kp = kp0 - HALO + 8 * pi;
+                bool valid = e < 16 * (BROW / 8) && kp >= 0 && kp < g.Lp;
+                const int kpc = valid ? kp : 0;
+                const int p = (int)pdiv((uint32_t)kpc), qq = kpc - p * pitch;
+                valid = valid && qq < Wd;
+                regB[i] = make_uint2(b_pad, b_pad);
+                if (valid)
+                    regB[i] = *reinterpret_cast<const uint2 *>(x + ((int64_t)b * g.C + cg * 16 + c) * g.PQ + p * Wd + qq);
+            }
+        } else {
+            // pieces of 4 positions; wavefront w stages gradient rows w, w+8, ..., lane = piece
             const int kp = kp0 + 4 * lane;
             const int p = (int)pdiv((uint32_t)kp), qq = kp - p * pitch;
             const bool valid = kp < g.Lp && qq < Wd;
             const int16_t *src = g16 + ((int64_t)b * g.K + rg * 64 + wave) * g.PQ + p * Wd + qq;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                regA[i] = make_uint2(a_pad, a_pad);
-                if (valid) regA[i] = *reinterpret_cast<const uint2 *>(src + (int64_t)i * 8 * g.PQ);
+            for (int i = 0; i < 4; ++i) {
+                uint2 v0 = make_uint2(a_pad, a_pad), v1 = v0;
+                if (valid) {
+                    v0 = *reinterpret_cast<const uint2 *>(src + (int64_t)(2 * i) * 8 * g.PQ);
+                    v1 = *reinterpret_cast<const uint2 *>(src + (int64_t)(2 * i + 1) * 8 * g.PQ);
+                }
+                regA[i] = make_uint4(v0.x, v0.y, v1.x, v1.y);   // rows wave+16i and wave+16i+8
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = tid + kThreads * i, c = e / (BROW / 4), gi = e - c * (BROW / 4);
+                const int kp = kp0 - HALO + 4 * gi;
+                bool valid = e < 16 * (BROW / 4) && kp >= 0 && kp < g.Lp;
+                const int kpc = valid ? kp : 0;
+                const int p = (int)pdiv((uint32_t)kpc), qq = kpc - p * pitch;
+                valid = valid && qq < Wd;
+                regB[i].x = b_pad;
+                if (valid)
+                    regB[i].x = *reinterpret_cast<const uint32_t *>(x + ((int64_t)b * g.C + cg * 16 + c) * g.PQ + p * Wd + qq);
             }
         }
+    };
+    auto write_lds = [&](int buf) {
+        uint8_t *A = smem + buf * BUF_BYTES, *B = A + A_BYTES;
+        if (WIDE) {
 #pragma unroll
-        for (int i = 0; i < 3; ++i) {   // input: 16 channels x 96 groups of 4 positions
-            const int idx = tid + kThreads * i;
-            const int c = idx / 96, gi = idx - c * 96;
-            const int kp = kp0 - HALO + 4 * gi;
-            bool valid = kp >= 0 && kp < g.Lp;
-            const int kpc = valid ? kp : 0;
-            const int p = (int)pdiv((uint32_t)kpc), qq = kpc - p * pitch;
-            valid = valid && qq < Wd;
-            regB[i] = b_pad;
-            if (valid)
-                regB[i] = *reinterpret_cast<const uint32_t *>(x + ((int64_t)b * g.C + cg * 16 + c) * g.PQ + p * Wd + qq);
+            for (int i = 0; i < 4; ++i) {
+                const int e = tid + kThreads * i, row = e >> 5, pi = e & 31;
+                const uint32_t h0 = __builtin_amdgcn_perm(regA[i].y, regA[i].x, 0x07050301);
+                const uint32_t h1 = __builtin_amdgcn_perm(regA[i].w, regA[i].z, 0x07050301);
+                const uint32_t l0 = __builtin_amdgcn_perm(regA[i].y, regA[i].x, 0x06040200) ^ 0x80808080u;
+                const uint32_t l1 = __builtin_amdgcn_perm(regA[i].w, regA[i].z, 0x06040200) ^ 0x80808080u;
+                *reinterpret_cast<uint2 *>(&A[row * APITCH + 8 * pi]) = make_uint2(h0, h1);
+                *reinterpret_cast<uint2 *>(&A[(64 + row) * APITCH + 8 * pi]) = make_uint2(l0, l1);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int e = tid + kThreads * i, c = e / (BROW / 8), pi = e - c * (BROW / 8);
+                if (e < 16 * (BROW / 8)) *reinterpret_cast<uint2 *>(&B[c * BPITCH + 8 * pi]) = regB[i];
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+#pragma unroll
+                for (int hsel = 0; hsel < 2; ++hsel) {
+                    const int row = wave + 16 * i + 8 * hsel;
+                    const uint32_t lo32 = hsel ? regA[i].z : regA[i].x, hi32 = hsel ? regA[i].w : regA[i].y;
+                    const uint32_t hi = __builtin_amdgcn_perm(hi32, lo32, 0x07050301);
+                    const uint32_t lo = __builtin_amdgcn_perm(hi32, lo32, 0x06040200) ^ 0x80808080u;
+                    *reinterpret_cast<uint32_t *>(&A[row * APITCH + 4 * lane]) = hi;
+                    *reinterpret_cast<uint32_t *>(&A[(64 + row) * APITCH + 4 * lane]) = lo;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = tid + kThreads * i, c = e / (BROW / 4), gi = e - c * (BROW / 4);
+                if (e < 16 * (BROW / 4)) *reinterpret_cast<uint32_t *>(&B[c * BPITCH + 4 * gi]) = regB[i].x;
+            }
         }
     };
-    auto write_lds = [&]() {
+    auto compute = [&](int u, int buf) {
+        const uint8_t *A = smem + buf * BUF_BYTES, *B = A + A_BYTES;
+        const int kstart = (u % g.chunks) * KC + kl * 64;
+        if (kstart >= g.Lp) return;   // wavefront-uniform: ragged last chunk of an image
+        v4i a[4];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = wave + 8 * i;
-            const uint32_t hi = __builtin_amdgcn_perm(regA[i].y, regA[i].x, 0x07050301);
-            const uint32_t lo = __builtin_amdgcn_perm(regA[i].y, regA[i].x, 0x06040200) ^ 0x80808080u;
-            *reinterpret_cast<uint32_t *>(&As[row * APITCH + 4 * lane]) = hi;
-            *reinterpret_cast<uint32_t *>(&As[64 * APITCH + row * APITCH + 4 * lane]) = lo;
+        for (int mt = 0; mt < 4; ++mt) {
+            a[mt] = *reinterpret_cast<const v4i *>(&A[(plane * 64 + mt * 16 + l16) * APITCH + kl * 64 + kb * 16]);
+            rs[mt] = dot4_ones(a[mt][0], dot4_ones(a[mt][1], dot4_ones(a[mt][2], dot4_ones(a[mt][3], rs[mt]))));
         }
 #pragma unroll
-        for (int i = 0; i < 3; ++i) {
-            const int idx = tid + kThreads * i;
-            const int c = idx / 96, gi = idx - c * 96;
-            *reinterpret_cast<uint32_t *>(&Bs[c * BPITCH + 4 * gi]) = regB[i];
+        for (int r = 0; r < 3; ++r) {
+            const int base = HALO + kl * 64 + kb * 16 + (r - 1) * pitch - 4;
+            uint32_t d[6];
+#pragma unroll
+            for (int i = 0; i < 6; ++i) d[i] = *reinterpret_cast<const uint32_t *>(&B[l16 * BPITCH + base + 4 * i]);
+            v4i f[3];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                f[0][i] = (int)__builtin_amdgcn_alignbyte(d[i + 1], d[i], 3);
+                f[1][i] = (int)d[i + 1];
+                f[2][i] = (int)__builtin_amdgcn_alignbyte(d[i + 2], d[i + 1], 1);
+            }
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+                const int tap = r * 3 + s;
+                if (plane == 0)   // wavefront-uniform: one plane gathers the column sums
+                    cs[tap] = dot4_ones(f[s][0], dot4_ones(f[s][1], dot4_ones(f[s][2], dot4_ones(f[s][3], cs[tap]))));
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt)
+                    acc[mt][tap] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mt], f[s], acc[mt][tap], 0, 0, 0);
+            }
         }
     };
 
-    if (units > 0) load_regs(0);
+    // Double-buffered LDS, one barrier per chunk.  The two wavefronts that share a SIMD run the
+    // phases of an iteration in opposite order (MFMA first / staging first), so that one issues
+    // matrix instructions while the other occupies the vector-memory and LDS pipes.
+    const bool late = wave >= 4;
+    if (units > 0) {
+        load_regs(0);
+        write_lds(0);
+        if (units > 1) load_regs(1);
+    }
+    __syncthreads();
     for (int u = 0; u < units; ++u) {
-        __syncthreads();
-        write_lds();
-        __syncthreads();
-        if (u + 1 < units) load_regs(u + 1);
-        const int kstart = (u % g.chunks) * KC + kl * 64;
-        if (kstart < g.Lp) {
-            v4i a[4];
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
-                a[mt] = *reinterpret_cast<const v4i *>(&As[plane * 64 * APITCH + (mt * 16 + l16) * APITCH + kl * 64 + kb * 16]);
-                rs[mt] = dot4_ones(a[mt][0], dot4_ones(a[mt][1], dot4_ones(a[mt][2], dot4_ones(a[mt][3], rs[mt]))));
-            }
-#pragma unroll
-            for (int r = 0; r < 3; ++r) {
-                const int base = HALO + kl * 64 + kb * 16 + (r - 1) * pitch - 4;
-                uint32_t d[6];
-#pragma unroll
-                for (int i = 0; i < 6; ++i) d[i] = *reinterpret_cast<const uint32_t *>(&Bs[l16 * BPITCH + base + 4 * i]);
-                v4i f[3];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    f[0][i] = (int)__builtin_amdgcn_alignbyte(d[i + 1], d[i], 3);
-                    f[1][i] = (int)d[i + 1];
-                    f[2][i] = (int)__builtin_amdgcn_alignbyte(d[i + 2], d[i + 1], 1);
-                }
-#pragma unroll
-                for (int s = 0; s < 3; ++s) {
-                    const int tap = r * 3 + s;
-                    if (plane == 0)   // wavefront-uniform: one plane gathers the column sums
-                        cs[tap] = dot4_ones(f[s][0], dot4_ones(f[s][1], dot4_ones(f[s][2], dot4_ones(f[s][3], cs[tap]))));
-#pragma unroll
-                    for (int mt = 0; mt < 4; ++mt)
-                        acc[mt][tap] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mt], f[s], acc[mt][tap], 0, 0, 0);
-                }
-            }
+        const int cur = u & 1;
+        if (!late) compute(u, cur);
+        if (u + 1 < units) {
+            write_lds(cur ^ 1);
+            if (u + 2 < units) load_regs(u + 2);
         }
+        if (late) compute(u, cur);
+        __syncthreads();
     }
 
     // fold the 4 k-blocks of the row / column sums
@@ -300,7 +367,7 @@ bool wgrad_shape_ok(const q8t_conv_desc *d)
 {
     if (d->stride != 1 || d->R != 3 || d->S != 3 || d->pad != 1) return false;
     if (d->K % 64 || d->C % 16 || d->W % 4) return false;
-    if (d->W + 4 + 1 > HALO || d->H < 1) return false;
+    if (d->W + 8 + 1 > HALO || d->H < 1) return false;
     // every k-range stays far below the 32-bit partial bound: 2^14 * positions < 2^31
     return true;
 }
@@ -309,7 +376,7 @@ WGeom wgrad_geom(const q8t_conv_desc *d)
 {
     WGeom g;
     g.N = d->N; g.C = d->C; g.K = d->K; g.H = d->H; g.W = d->W; g.PQ = d->H * d->W;
-    g.pitch = d->W + 4;
+    g.pitch = (d->W == 56) ? d->W + 8 : d->W + 4;   // must match the kernel variant chosen for this width
     g.Lp = d->H * g.pitch;
     g.rpitch = 1.0f / (float)g.pitch;
     g.chunks = (g.Lp + KC - 1) / KC;
@@ -349,7 +416,7 @@ bool q8t_fast_wgrad_supported(const q8t_conv_desc *d, const void *g16, const voi
 {
     if (!wgrad_shape_ok(d)) return false;
     if ((int64_t)d->H * (d->W + 4) + 64 > ((int64_t)1 << 16)) return false;
-    return q8t_aligned(g16, 8) && q8t_aligned(x, 4) && q8t_aligned(dw, 4) && q8t_aligned(acc, 8);
+    return q8t_aligned(g16, 16) && q8t_aligned(x, 8) && q8t_aligned(dw, 4) && q8t_aligned(acc, 8);
 }
 
 size_t q8t_fast_wgrad_ws(const q8t_conv_desc *d)
