@@ -1,0 +1,131 @@
+"""GPU parity at the full sizes of the workloads, in the launch configuration the benchmark times.
+
+Forward and layer-gradient outputs of image n depend on image n only, so the oracle computes a
+sample of images one by one; the weight gradient reduces over the whole batch and is compared in
+full.  A second test chains the calls of one layer step and checks every stage against the oracle
+run on the GPU's own intermediates (bit-exact integers stage by stage)."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_util import close, dev, host, require_gpu, same_ints, same_qparams
+
+pytestmark = pytest.mark.gpu
+
+
+def _sub_desc(case, n):
+    c = list(case)
+    c[0] = n
+    return oracle.conv_desc(*c)
+
+
+def _check_conv_layer(q8t, case, seed, sample, check_wgrad=True):
+    N, C, H, W, K, R, S, st, pad = case
+    x, w, dy = synth.conv_layer(seed=seed, N=N, C=C, H=H, W=W, K=K, R=R, S=S, stride=st, pad=pad)
+    d = q8t.conv_desc(*case)
+    qx, px = q8t.quantize(dev(x), 8)
+    qw, pw = q8t.quantize(dev(w), 8)
+    g8, pg8, g16, pg16 = q8t.quantize_bifurcate(dev(dy), seed8=21, seed16=22)
+    sx, _, opx = oracle.quantize(x, 8)
+    sw, _, opw = oracle.quantize(w, 8)
+    s8, _, o8 = oracle.quantize(dy, 8, True, seed=21)
+    s16, _, o16 = oracle.quantize(dy, 16, True, seed=22)
+    same_qparams(q8t, px, opx)
+    same_qparams(q8t, pw, opw)
+    same_qparams(q8t, pg8, o8)
+    same_qparams(q8t, pg16, o16)
+    same_ints(host(qx), sx)
+    same_ints(host(g8), s8)
+    same_ints(host(g16), s16)
+    y, acc = q8t.qconv_fwd(d, qx, px, qw, pw, want_acc=True)
+    dx, accd = q8t.qconv_dgrad(d, g8, pg8, qw, pw, want_acc=True)
+    y, acc, dx, accd = host(y), host(acc), host(dx), host(accd)
+    d1 = _sub_desc(case, 1)
+    for n in sample:
+        oy, oacc = oracle.qconv_fwd(d1, sx[n:n + 1], opx, sw, opw)
+        same_ints(acc[n:n + 1], oacc)
+        close(y[n:n + 1], oy)
+        odx, oaccd = oracle.qconv_dgrad(d1, s8[n:n + 1], o8, sw, opw)
+        same_ints(accd[n:n + 1], oaccd)
+        close(dx[n:n + 1], odx)
+    if check_wgrad:
+        dw, accw = q8t.qconv_wgrad(d, qx, px, g16, pg16, want_acc=True)
+        odw, oaccw = oracle.qconv_wgrad(oracle.conv_desc(*case), sx, opx, s16, o16)
+        same_ints(host(accw), oaccw)
+        close(host(dw), odw)
+
+
+def test_config2_conv3x3_full_size():
+    q8t = require_gpu()
+    _check_conv_layer(q8t, (128, 64, 56, 56, 64, 3, 3, 1, 1), seed=0, sample=(0, 77, 127))
+
+
+def test_config3_bottleneck_convs_full_size():
+    q8t = require_gpu()
+    _check_conv_layer(q8t, (128, 256, 56, 56, 64, 1, 1, 1, 0), seed=1, sample=(0, 127))
+    _check_conv_layer(q8t, (128, 64, 56, 56, 256, 1, 1, 1, 0), seed=2, sample=(5, 126))
+
+
+@pytest.mark.parametrize("case", [(256, 128, 28, 28, 128, 3, 3, 1, 1), (256, 256, 14, 14, 256, 3, 3, 1, 1),
+                                  (64, 64, 56, 56, 128, 3, 3, 2, 1), (16, 3, 224, 224, 64, 7, 7, 2, 3)])
+def test_config4_layer_shapes(case):
+    # ResNet-18 layers at (or, for the slow general kernel, near) their batch-256 sizes
+    q8t = require_gpu()
+    _check_conv_layer(q8t, case, seed=3, sample=(0, case[0] - 1), check_wgrad=case[0] * case[2] * case[3] < 4e5)
+
+
+def test_layer_step_chain_stage_by_stage():
+    # quantize -> conv fwd -> Range BN fwd -> Range BN bwd -> bifurcated quantization -> dgrad, wgrad.
+    # Every stage is checked against the oracle fed with the GPU's output of the stage before.
+    q8t = require_gpu()
+    case = (4, 64, 56, 56, 64, 3, 3, 1, 1)
+    x, w, _ = synth.conv_layer(seed=5, N=4)
+    dout = synth.normal(synth.rng(6), (4, 64, 56, 56), std=1e-2)
+    d, od = q8t.conv_desc(*case), oracle.conv_desc(*case)
+    qx, px = q8t.quantize(dev(x), 8)
+    qw, pw = q8t.quantize(dev(w), 8)
+    y, acc = q8t.qconv_fwd(d, qx, px, qw, pw, want_acc=True)
+    bn, stats, _, _ = q8t.range_bn_fwd(y, eps=1e-5)
+    g, dgam, dbet = q8t.range_bn_bwd(y, dev(dout), stats, None, 1e-5)
+    g8, pg8, g16, pg16 = q8t.quantize_bifurcate(g, seed8=31, seed16=32)
+    dx, accd = q8t.qconv_dgrad(d, g8, pg8, qw, pw, want_acc=True)
+    dw, accw = q8t.qconv_wgrad(d, qx, px, g16, pg16, want_acc=True)
+
+    sx, _, opx = oracle.quantize(x, 8)
+    sw, _, opw = oracle.quantize(w, 8)
+    same_ints(host(qx), sx)
+    same_ints(host(qw), sw)
+    oy, oacc = oracle.qconv_fwd(od, sx, opx, sw, opw)
+    same_ints(host(acc), oacc)
+    close(host(y), oy)
+    yh, sth = host(y), host(stats)
+    obn, ost, _, _ = oracle.range_bn_fwd(yh, eps=1e-5)
+    assert np.array_equal(sth[1:], ost[1:])
+    close(sth[0], ost[0])
+    fbn, _, _, _ = oracle.range_bn_fwd(yh, eps=1e-5, stats=sth)
+    same_ints(host(bn), fbn)
+    og, odg, odb = oracle.range_bn_bwd(yh, dout, sth, None, 1e-5)
+    close(host(g), og)
+    close(host(dgam), odg)
+    close(host(dbet), odb)
+    gh = host(g)
+    s8, _, o8 = oracle.quantize(gh, 8, True, seed=31)
+    s16, _, o16 = oracle.quantize(gh, 16, True, seed=32)
+    same_qparams(q8t, pg8, o8)
+    same_qparams(q8t, pg16, o16)
+    same_ints(host(g8), s8)
+    same_ints(host(g16), s16)
+    odx, oaccd = oracle.qconv_dgrad(od, s8, o8, sw, opw)
+    same_ints(host(accd), oaccd)
+    close(host(dx), odx)
+    odw, oaccw = oracle.qconv_wgrad(od, sx, opx, s16, o16)
+    same_ints(host(accw), oaccw)
+    close(host(dw), odw)
+    # un-forced end-to-end run of the oracle from the same inputs: the 8-bit gradient codes may
+    # differ in a handful of places (the fp64 sums of the BN backward are taken in another order)
+    g_or, _, _ = oracle.range_bn_bwd(oy, dout, oracle.range_bn_stats(oy), None, 1e-5)
+    s8_free, _, _ = oracle.quantize(g_or, 8, True, seed=31)
+    diff = int((s8_free != host(g8)).sum())
+    print("8-bit gradient codes differing from the un-forced oracle chain:", diff, "of", s8_free.size)
+    assert diff <= 1e-4 * s8_free.size
