@@ -14,6 +14,8 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kMaxPartials = 1024;
+constexpr int kSmallThreads = 1024;
+constexpr int64_t kSmallN = 1 << 16;   // below this, one workgroup does both passes
 
 __device__ __forceinline__ float block_reduce_min(float v, float *smem)
 {
@@ -203,6 +205,41 @@ __global__ __launch_bounds__(kThreads) void quantize_apply(
     }
 }
 
+// small tensors (weights of a layer): both passes in one workgroup, one launch
+template <typename OUT, bool STOCH>
+__global__ __launch_bounds__(kSmallThreads) void quantize_small(const float *__restrict__ x, int n, int bits,
+                                                                uint32_t seed_lo, uint32_t seed_hi,
+                                                                OUT *__restrict__ q_out,
+                                                                q8t_qparams *__restrict__ qp_out)
+{
+    __shared__ float smn[kSmallThreads / 64], smx[kSmallThreads / 64];
+    float mn = INFINITY, mx = -INFINITY;
+    for (int i = threadIdx.x; i < n; i += kSmallThreads) {
+        mn = fminf(mn, x[i]);
+        mx = fmaxf(mx, x[i]);
+    }
+    mn = wave_reduce(mn, OpMin());
+    mx = wave_reduce(mx, OpMax());
+    if ((threadIdx.x & 63) == 0) {
+        smn[threadIdx.x >> 6] = mn;
+        smx[threadIdx.x >> 6] = mx;
+    }
+    __syncthreads();
+    mn = smn[0];
+    mx = smx[0];
+    for (int w = 1; w < kSmallThreads / 64; ++w) {
+        mn = fminf(mn, smn[w]);
+        mx = fmaxf(mx, smx[w]);
+    }
+    const q8t_qparams qp = make_qparams(mn, mx, bits);
+    if (threadIdx.x == 0) *qp_out = qp;
+    const Affine a = affine_of(qp);
+    for (int i = threadIdx.x; i < n; i += kSmallThreads) {
+        const uint32_t r = STOCH ? rng_r16(i, seed_lo, seed_hi) : 0u;
+        q_out[i] = (OUT)(level_of<STOCH>(x[i], a, r) - a.half);
+    }
+}
+
 // pass 2, bifurcated: 8-bit and 16-bit stochastic copies from one read of g
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void quantize_bifurcate_apply(
@@ -331,6 +368,15 @@ int q8t_quantize(const float *x, int64_t n, int bits, int stochastic, uint64_t s
     if (!qp_out || (n > 0 && (!x || !q_out))) return Q8T_ERR_NULL;
     if (!ws || !q8t_aligned(ws, 8)) return Q8T_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
+    if (n > 0 && n <= kSmallN) {
+        const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
+#define Q8T_SMALL(T, S) hipLaunchKernelGGL((quantize_small<T, S>), dim3(1), dim3(kSmallThreads), 0, st, x, (int)n, bits, lo, hi, (T *)q_out, qp_out)
+        if (bits <= 8) { if (stochastic) Q8T_SMALL(int8_t, true); else Q8T_SMALL(int8_t, false); }
+        else           { if (stochastic) Q8T_SMALL(int16_t, true); else Q8T_SMALL(int16_t, false); }
+#undef Q8T_SMALL
+        Q8T_LAUNCH_CHECK();
+        return Q8T_OK;
+    }
     float2 *partials = (float2 *)ws;
     const int np = launch_minmax(x, n, partials, st);
     Q8T_LAUNCH_CHECK();
