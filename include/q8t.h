@@ -155,6 +155,19 @@ int q8t_range_bn_bwd(const float *x, const float *dy, const float *stats, int N,
                      const float *gamma, float eps, float *dx, float *dgamma, float *dbeta, void *ws,
                      void *stream);
 
+/* Range BN backward fused with the bifurcated quantization of its result (Section 7 for the
+ * backward rule; Sections 1 and 4 for the 8-bit / 16-bit stochastic copies of the layer gradient).
+ * dx is written as fp32 and its min/max is taken in the same pass, so the quantizer needs no range
+ * search of its own: one pass over dx less than q8t_range_bn_bwd followed by
+ * q8t_quantize_bifurcate(dx, ...), with bit-identical results.  dx, q8_out, q16_out and both
+ * parameter blocks are required; dgamma / dbeta stay nullable.  Requires H*W >= 256 (else
+ * Q8T_ERR_SHAPE: use the two separate calls).  ws: q8t_range_bn_bwd_bifurcate_workspace_size. */
+size_t q8t_range_bn_bwd_bifurcate_workspace_size(int N, int C, int H, int W);
+int q8t_range_bn_bwd_bifurcate(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
+                               const float *gamma, float eps, float *dx, float *dgamma, float *dbeta,
+                               uint64_t seed8, uint64_t seed16, int8_t *q8_out, q8t_qparams *qp8_out,
+                               int16_t *q16_out, q8t_qparams *qp16_out, void *ws, void *stream);
+
 /* C(n) = 1/sqrt(2 ln n) (Section 3), host arithmetic in double.  n >= 2. */
 double q8t_range_bn_scale(int64_t n);
 

@@ -62,6 +62,9 @@ _SIGS = {
     "q8t_range_bn_workspace_size": (_sz, [_i, _i, _i, _i]),
     "q8t_range_bn_fwd": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _vp]),
     "q8t_range_bn_bwd": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _f, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_range_bn_bwd_bifurcate_workspace_size": (_sz, [_i, _i, _i, _i]),
+    "q8t_range_bn_bwd_bifurcate": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _f, _vp, _vp, _vp, _u64, _u64, _vp, _vp,
+                                        _vp, _vp, _vp, _vp]),
     "q8t_range_bn_scale": (C.c_double, [_i64]),
     "q8t_version": (C.c_char_p, []),
 }
@@ -282,3 +285,25 @@ def range_bn_bwd(x, dy, stats, gamma=None, eps=0.0, dx_out=None, ws=None):
     _check(_lib.q8t_range_bn_bwd(_ptr(x), _ptr(dy), _ptr(stats), N, Cc, H, W, _ptr(gamma), float(eps), _ptr(dx),
                                  _ptr(dgamma), _ptr(dbeta), _ptr(ws), _stream()), "q8t_range_bn_bwd")
     return dx, dgamma, dbeta
+
+
+def range_bn_bwd_bifurcate(x, dy, stats, gamma=None, eps=0.0, seed8=0, seed16=1, dx_out=None, q8_out=None,
+                           qp8_out=None, q16_out=None, qp16_out=None, ws=None):
+    """Range BN backward + bifurcated quantization of dx in one call.
+    Returns (dx, dgamma, dbeta, q8, qp8, q16, qp16)."""
+    _dev(x), _dev(dy), _dev(stats)
+    N, Cc, H, W = x.shape
+    dev = x.device
+    dx = dx_out if dx_out is not None else torch.empty_like(x)
+    dgamma = torch.empty(Cc, dtype=torch.float32, device=dev)
+    dbeta = torch.empty(Cc, dtype=torch.float32, device=dev)
+    q8 = q8_out if q8_out is not None else torch.empty(x.shape, dtype=torch.int8, device=dev)
+    q16 = q16_out if q16_out is not None else torch.empty(x.shape, dtype=torch.int16, device=dev)
+    qp8 = qp8_out if qp8_out is not None else new_qparams(dev)
+    qp16 = qp16_out if qp16_out is not None else new_qparams(dev)
+    ws = ws if ws is not None else workspace(_lib.q8t_range_bn_bwd_bifurcate_workspace_size(N, Cc, H, W), dev)
+    _check(_lib.q8t_range_bn_bwd_bifurcate(_ptr(x), _ptr(dy), _ptr(stats), N, Cc, H, W, _ptr(gamma), float(eps),
+                                           _ptr(dx), _ptr(dgamma), _ptr(dbeta), int(seed8) & (2 ** 64 - 1),
+                                           int(seed16) & (2 ** 64 - 1), _ptr(q8), _ptr(qp8), _ptr(q16), _ptr(qp16),
+                                           _ptr(ws), _stream()), "q8t_range_bn_bwd_bifurcate")
+    return dx, dgamma, dbeta, q8, qp8, q16, qp16

@@ -9,6 +9,7 @@
 //                        point, then quantizes its share: 4 elements -> one packed store.
 // HBM-bound: 9 algorithmic bytes per element for 8-bit output (4 read + 4 re-read + 1 written).
 #include "q8t_common.h"
+#include "q8t_internal.h"
 
 namespace {
 
@@ -165,7 +166,7 @@ template <typename OUT, bool STOCH, bool VEC>
 __global__ __launch_bounds__(kThreads) void quantize_apply(
     const float *__restrict__ x, int64_t n, int bits, uint32_t seed_lo, uint32_t seed_hi,
     const float2 *__restrict__ partials, int npartials, OUT *__restrict__ q_out,
-    q8t_qparams *__restrict__ qp_out)
+    q8t_qparams *__restrict__ qp_out, int rev)
 {
     __shared__ float smem[kThreads / 64];
     float vmin, vmax;
@@ -182,7 +183,7 @@ __global__ __launch_bounds__(kThreads) void quantize_apply(
         const float4 *x4 = reinterpret_cast<const float4 *>(x);
         P *q4 = reinterpret_cast<P *>(q_out);
         const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
-        const int64_t lo = (int64_t)blockIdx.x * per, hi = min(n4, lo + per);
+        const int64_t lo = (int64_t)(rev ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * per, hi = min(n4, lo + per);
         int64_t i = lo + threadIdx.x;
         for (; i + 3 * kThreads < hi; i += 4 * kThreads) {
             const float4 v0 = x4[i], v1 = x4[i + kThreads], v2 = x4[i + 2 * kThreads], v3 = x4[i + 3 * kThreads];
@@ -327,7 +328,7 @@ int launch_apply(const float *x, int64_t n, int bits, int stochastic, uint64_t s
     const int grid = grid_for(vec ? (n >> 2) : n, 4, 2048);
     const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
 #define Q8T_GO(S, V) \
-    hipLaunchKernelGGL((quantize_apply<OUT, S, V>), dim3(grid), dim3(kThreads), 0, st, x, n, bits, lo, hi, partials, npartials, q, qp)
+    hipLaunchKernelGGL((quantize_apply<OUT, S, V>), dim3(grid), dim3(kThreads), 0, st, x, n, bits, lo, hi, partials, npartials, q, qp, getenv("Q8T_DBG_REV") ? 1 : 0)
     if (stochastic) {
         if (vec) Q8T_GO(true, true); else Q8T_GO(true, false);
     } else {
@@ -424,6 +425,30 @@ int q8t_quantize_bifurcate(const float *g, int64_t n, uint64_t seed8, uint64_t s
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
 }
+
+}  // extern "C"
+
+// internal: bifurcated quantization when (min,max) pairs of g already exist (produced by the
+// kernel that wrote g).  `partials` holds np <= 2048 float2 pairs.
+int q8t_bifurcate_from_partials(const float *g, int64_t n, const void *partials, int np, uint64_t seed8,
+                                uint64_t seed16, int8_t *q8_out, q8t_qparams *qp8_out, int16_t *q16_out,
+                                q8t_qparams *qp16_out, hipStream_t st)
+{
+    const bool vec = q8t_aligned(g, 16) && q8t_aligned(q8_out, 4) && q8t_aligned(q16_out, 8);
+    const int grid = grid_for(vec ? (n >> 2) : n, 2, 2048);
+    if (vec)
+        hipLaunchKernelGGL(quantize_bifurcate_apply<true>, dim3(grid), dim3(kThreads), 0, st, g, n,
+                           (uint32_t)seed8, (uint32_t)(seed8 >> 32), (uint32_t)seed16,
+                           (uint32_t)(seed16 >> 32), (const float2 *)partials, np, q8_out, qp8_out, q16_out, qp16_out);
+    else
+        hipLaunchKernelGGL(quantize_bifurcate_apply<false>, dim3(grid), dim3(kThreads), 0, st, g, n,
+                           (uint32_t)seed8, (uint32_t)(seed8 >> 32), (uint32_t)seed16,
+                           (uint32_t)(seed16 >> 32), (const float2 *)partials, np, q8_out, qp8_out, q16_out, qp16_out);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
+
+extern "C" {
 
 int q8t_dequantize(const void *q, const q8t_qparams *qp, int64_t n, float *out, void *stream)
 {

@@ -7,6 +7,7 @@
 // backward: bwd_partial (fp64 sums of dy and dy*xhat) -> finalize (dgamma, dbeta, per-channel
 //           constants) -> apply (dx)                                    20 B/element
 #include "q8t_common.h"
+#include "q8t_internal.h"
 
 namespace {
 
@@ -362,9 +363,13 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply(const float *__restrict
                                                          const float2 *__restrict__ consts,
                                                          const double2 *__restrict__ parts, int split, double n,
                                                          float *__restrict__ dgamma, float *__restrict__ dbeta,
-                                                         float cn, float eps, float *__restrict__ dx)
+                                                         float cn, float eps, float *__restrict__ dx,
+                                                         float2 *__restrict__ mm_out, int rev)
 {
-    for (int64_t pl = blockIdx.x; pl < planes; pl += gridDim.x) {
+    __shared__ float smf[kThreads / 64];
+    float dmn = INFINITY, dmx = -INFINITY;   // range of the dx values this workgroup writes (if asked for)
+    for (int64_t pl0 = blockIdx.x; pl0 < planes; pl0 += gridDim.x) {
+        const int64_t pl = rev ? planes - 1 - pl0 : pl0;
         const int c = (int)(pl % C);
         const float mn = stats[C + c], mx = stats[2 * C + c];
         const float inv = bn_inv(mn, mx, cn, eps);
@@ -404,11 +409,24 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply(const float *__restrict
                 r.z = bn_dx(v.z, d.z, g, k.x, inv, k.y, mn, mx);
                 r.w = bn_dx(v.w, d.w, g, k.x, inv, k.y, mn, mx);
                 o[i] = r;
+                if (mm_out) {
+                    dmn = fminf(fminf(dmn, r.x), fminf(r.y, fminf(r.z, r.w)));
+                    dmx = fmaxf(fmaxf(dmx, r.x), fmaxf(r.y, fmaxf(r.z, r.w)));
+                }
             }
         } else {
-            for (int i = threadIdx.x; i < HW; i += kThreads)
-                dx[base + i] = bn_dx(x[base + i], dy[base + i], g, k.x, inv, k.y, mn, mx);
+            for (int i = threadIdx.x; i < HW; i += kThreads) {
+                const float r = bn_dx(x[base + i], dy[base + i], g, k.x, inv, k.y, mn, mx);
+                dx[base + i] = r;
+                dmn = fminf(dmn, r);
+                dmx = fmaxf(dmx, r);
+            }
         }
+    }
+    if (mm_out) {
+        dmn = block_min_f(dmn, smf);
+        dmx = block_max_f(dmx, smf);
+        if (threadIdx.x == 0) mm_out[blockIdx.x] = make_float2(dmn, dmx);
     }
 }
 
@@ -517,9 +535,9 @@ int q8t_range_bn_fwd(const float *x, int N, int C, int H, int W, const float *ga
     return Q8T_OK;
 }
 
-int q8t_range_bn_bwd(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
-                     const float *gamma, float eps, float *dx, float *dgamma, float *dbeta, void *ws,
-                     void *stream)
+static int range_bn_bwd_impl(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
+                             const float *gamma, float eps, float *dx, float *dgamma, float *dbeta, void *ws,
+                             void *stream, float2 *mm_out, int *mm_count)
 {
     const int rc = check_shape(N, C, H, W);
     if (rc) return rc;
@@ -540,6 +558,7 @@ int q8t_range_bn_bwd(const float *x, const float *dy, const float *stats, int N,
         hipLaunchKernelGGL(bn_bwd_partial<false>, dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn, eps, parts);
     Q8T_LAUNCH_CHECK();
     const bool fused = dx && HW >= 256;
+    if (mm_out && !fused) return Q8T_ERR_SHAPE;   // the fused range output exists for the plane kernel only
     if (!fused) {
         hipLaunchKernelGGL(bn_bwd_finalize, dim3((C + kThreads - 1) / kThreads), dim3(kThreads), 0, st, parts, C,
                            nsplit, n, cn, eps, stats, gamma, dgamma, dbeta, consts);
@@ -548,11 +567,15 @@ int q8t_range_bn_bwd(const float *x, const float *dy, const float *stats, int N,
     if (!dx) return Q8T_OK;
     const int64_t planes = (int64_t)N * C;
     if (HW >= 256) {
-        const dim3 grid(planes_grid(planes));
+        // with a range output, one (min,max) pair per workgroup: keep the grid at 2048 workgroups
+        int64_t cap = 2048; if (getenv("Q8T_DBG_MMCAP")) cap = atoi(getenv("Q8T_DBG_MMCAP"));
+        const dim3 grid(mm_out ? (unsigned)(planes < cap ? planes : cap) : (unsigned)planes_grid(planes));
+        if (mm_count) *mm_count = (int)grid.x;
+        if (getenv("Q8T_DBG_NOMM")) mm_out = nullptr;
         if (vec)
-            hipLaunchKernelGGL(bn_bwd_apply<true>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx);
+            hipLaunchKernelGGL(bn_bwd_apply<true>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx, mm_out, getenv("Q8T_DBG_REV") ? 1 : 0);
         else
-            hipLaunchKernelGGL(bn_bwd_apply<false>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx);
+            hipLaunchKernelGGL(bn_bwd_apply<false>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx, mm_out, getenv("Q8T_DBG_REV") ? 1 : 0);
     } else {
         const int64_t total = planes * HW;
         const dim3 grid((unsigned)((total + kThreads - 1) / kThreads < 65536 * 16 ? (total + kThreads - 1) / kThreads : 65536 * 16));
@@ -560,6 +583,35 @@ int q8t_range_bn_bwd(const float *x, const float *dy, const float *stats, int N,
     }
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
+}
+
+int q8t_range_bn_bwd(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
+                     const float *gamma, float eps, float *dx, float *dgamma, float *dbeta, void *ws,
+                     void *stream)
+{
+    return range_bn_bwd_impl(x, dy, stats, N, C, H, W, gamma, eps, dx, dgamma, dbeta, ws, stream, nullptr, nullptr);
+}
+
+size_t q8t_range_bn_bwd_bifurcate_workspace_size(int N, int C, int H, int W)
+{
+    return q8t_range_bn_workspace_size(N, C, H, W) + 256 + 16384 * sizeof(float2);
+}
+
+int q8t_range_bn_bwd_bifurcate(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
+                               const float *gamma, float eps, float *dx, float *dgamma, float *dbeta,
+                               uint64_t seed8, uint64_t seed16, int8_t *q8_out, q8t_qparams *qp8_out,
+                               int16_t *q16_out, q8t_qparams *qp16_out, void *ws, void *stream)
+{
+    if (!dx || !q8_out || !qp8_out || !q16_out || !qp16_out) return Q8T_ERR_NULL;
+    if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    if ((int64_t)H * W < 256) return Q8T_ERR_SHAPE;   // planes this small: use the two separate calls
+    const size_t off = (q8t_range_bn_workspace_size(N, C, H, W) + 255) & ~(size_t)255;
+    float2 *mm = (float2 *)((char *)ws + off);
+    int np = 0;
+    const int rc = range_bn_bwd_impl(x, dy, stats, N, C, H, W, gamma, eps, dx, dgamma, dbeta, ws, stream, mm, &np);
+    if (rc) return rc;
+    return q8t_bifurcate_from_partials(dx, (int64_t)N * C * H * W, mm, np, seed8, seed16, q8_out, qp8_out, q16_out,
+                                       qp16_out, (hipStream_t)stream);
 }
 
 }  // extern "C"

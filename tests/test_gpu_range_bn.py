@@ -120,3 +120,33 @@ def test_rejects_degenerate_batch():
     with pytest.raises(q8t.binding.Q8TError) as e:
         q8t.range_bn_fwd(dev(np.ones((1, 3, 1, 1), np.float32)))
     assert e.value.code == -2
+
+
+@pytest.mark.parametrize("shape", [(6, 7, 16, 16), (3, 2, 40, 36), (128, 64, 56, 56)])
+def test_backward_fused_with_bifurcated_quantization(shape):
+    # same results as the two separate calls; the codes are checked against the oracle's quantizer
+    # run on the GPU's own dx (bit-exact), dx itself against the oracle within tolerance
+    q8t = require_gpu()
+    x, dy, gamma, _ = _inputs(shape, 4) if shape[0] < 100 else (*synth.range_bn_input(seed=1), None, None)
+    eps = 1e-5
+    stats = oracle.range_bn_stats(x)
+    xd, dyd, sd = dev(x), dev(dy), dev(stats)
+    gd = None if gamma is None else dev(gamma)
+    dx, dgamma, dbeta, q8, qp8, q16, qp16 = q8t.range_bn_bwd_bifurcate(xd, dyd, sd, gd, eps, seed8=41, seed16=42)
+    dx2, dgamma2, dbeta2 = q8t.range_bn_bwd(xd, dyd, sd, gd, eps)
+    r8, rp8, r16, rp16 = q8t.quantize_bifurcate(dx2, seed8=41, seed16=42)
+    assert np.array_equal(host(dx), host(dx2))
+    assert np.array_equal(host(dgamma), host(dgamma2)) and np.array_equal(host(dbeta), host(dbeta2))
+    assert q8t.qparams_to_host(qp8) == q8t.qparams_to_host(rp8)
+    assert q8t.qparams_to_host(qp16) == q8t.qparams_to_host(rp16)
+    same_ints(host(q8), host(r8))
+    same_ints(host(q16), host(r16))
+    dxh = host(dx)
+    odx, _, _ = oracle.range_bn_bwd(x, dy, stats, gamma, eps)
+    close(dxh, odx)
+    s8, _, o8 = oracle.quantize(dxh, 8, True, seed=41)
+    s16, _, o16 = oracle.quantize(dxh, 16, True, seed=42)
+    same_qparams(q8t, qp8, o8)
+    same_qparams(q8t, qp16, o16)
+    same_ints(host(q8), s8)
+    same_ints(host(q16), s16)
