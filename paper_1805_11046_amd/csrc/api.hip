@@ -18,6 +18,14 @@ int fc_check(int M, int N, int K, const void *a, const void *qa, const void *b, 
     return Q8T_OK;
 }
 
+// the GEMM form of the weight gradient pays off once the product is not tiny
+bool wgrad_wants_gemm(const q8t_conv_desc *d)
+{
+    if (!q8t_gemm_wgrad_supported(d)) return false;
+    const int P = (d->H + 2 * d->pad - d->R) / d->stride + 1, Q = (d->W + 2 * d->pad - d->S) / d->stride + 1;
+    return (double)d->K * d->C * d->R * d->S * d->N * P * Q >= 4194304.0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -62,6 +70,8 @@ size_t q8t_qconv_workspace_size(const q8t_conv_desc *desc, int which)
     size_t g = q8t_generic_conv_ws(which, desc);
     size_t f = q8t_fast_conv_ws(which, desc);
     if (which == 2) f = q8t_fast_wgrad_ws(desc);
+    const size_t h = which < 2 ? q8t_nhwc_conv_ws(which, desc) : (wgrad_wants_gemm(desc) ? q8t_gemm_wgrad_ws(desc) : 0);
+    if (h > g) g = h;
     return g > f ? g : f;
 }
 
@@ -73,6 +83,8 @@ int q8t_qconv_fwd(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams
     if (rc) return rc;
     if (q8t_fast_conv_supported(0, desc, qx, qw, y, acc_out))
         return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
+    if (q8t_nhwc_conv_supported(0, desc))
+        return q8t_nhwc_conv(0, desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
     return q8t_generic_conv(0, desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
 }
 
@@ -84,6 +96,8 @@ int q8t_qconv_dgrad(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qpar
     if (rc) return rc;
     if (q8t_fast_conv_supported(1, desc, qdy, qw, dx, acc_out))
         return q8t_fast_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, ws, (hipStream_t)stream);
+    if (q8t_nhwc_conv_supported(1, desc))
+        return q8t_nhwc_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, ws, (hipStream_t)stream);
     return q8t_generic_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, ws, (hipStream_t)stream);
 }
 
@@ -95,6 +109,8 @@ int q8t_qconv_wgrad(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qpara
     if (rc) return rc;
     if (q8t_fast_wgrad_supported(desc, qdy16, qx, dw, acc_out))
         return q8t_fast_wgrad(desc, qdy16, pg16, qx, px, dw, acc_out, ws, (hipStream_t)stream);
+    if (wgrad_wants_gemm(desc))
+        return q8t_gemm_wgrad(desc, qdy16, pg16, qx, px, dw, acc_out, ws, (hipStream_t)stream);
     return q8t_generic_conv(2, desc, qdy16, pg16, qx, px, dw, acc_out, ws, (hipStream_t)stream);
 }
 

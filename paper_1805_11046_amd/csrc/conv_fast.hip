@@ -162,7 +162,7 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, kb = lane >> 4;
 
-    const int za = qpa->zero_point - 128, zb = qpb->zero_point - 128;
+    const int za = qpa->zero_point - (1 << (qpa->bits - 1)), zb = qpb->zero_point - (1 << (qpb->bits - 1));
     const float sc = qpa->scale * qpb->scale;
     const uint32_t zavec = (uint32_t)(za & 255) * 0x01010101u;
 

@@ -1,0 +1,463 @@
+// General MFMA path for the forward and layer-gradient convolutions (Section 4: both products
+// take 8-bit operands and accumulate in 32 bits): any filter size, stride and padding, for
+// channel counts that are multiples of 64.  Three launches per call (plus one per extra stride
+// class of a layer gradient):
+//
+//  1. to_nhwc      the NCHW int8 operand is rewritten channel-contiguous ([N][H][W][C]) into the
+//                  workspace, so that the 64 reduction channels of one filter tap are 64
+//                  consecutive bytes; the same pass emits the per-position channel sum that the
+//                  zero-point correction needs.
+//  2. repack_taps  filter -> [tap][output channel][reduction channel] and the per-output-channel
+//                  sums (per stride class).
+//  3. igemm_nhwc   implicit GEMM, rows = output positions (128 per workgroup), columns = output
+//                  channels (128 or 64), K = taps x channels in steps of 64.  Global loads of step
+//                  s+1 are in flight while the MFMAs of step s run; LDS is double-buffered with one
+//                  barrier per step; rows of 64 bytes sit 80 bytes apart so that the 16-byte
+//                  operand reads of a wavefront are conflict-free.
+//
+// Padded taps are staged as the stored zero point, which makes their corrected contribution
+// exactly zero; with a = stored code, za/zb = stored zero points:
+//    sum (a-za)(b-zb) = sum ab - zb*sum a - za*sum b + Kp*za*zb.
+//
+// The layer gradient of a strided convolution is split into stride x stride classes of input
+// positions (same residue of (h, w) modulo the stride).  Inside a class every position sees the
+// same subset of filter taps at stride 1, so each class is one dense launch and no multiply is
+// spent on taps that cannot contribute.
+#include "q8t_common.h"
+#include "q8t_internal.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int BM = 128;      // output positions per workgroup
+constexpr int PITCH = 80;    // LDS bytes between rows of 64
+constexpr int MAXT = 49;     // taps (7x7)
+constexpr int MAXCLS = 16;   // stride classes (stride <= 4)
+
+struct TapList {             // per tap: two small signed numbers
+    int8_t a[MAXT + 3], b[MAXT + 3];
+};
+struct ClassOffsets {
+    int off[MAXCLS + 1];     // taps of class z are [off[z], off[z+1]) of the TapList
+};
+
+struct Geo {
+    int N, IH, IW, Cp;       // staged operand: [N][IH][IW][Cp]
+    int OH, OW;              // output positions enumerated by this launch (rows m = (n, oh, ow))
+    int ish, isw;            // operand step per output step
+    int OC, OHf, OWf;        // NCHW result: channels, full height and width
+    int osh, osw, oph, opw;  // result position = (oh*osh + oph, ow*osw + opw)
+    int M;                   // N*OH*OW
+    int T;                   // taps of this launch
+    int vec;                 // result pointers are 16-byte aligned
+};
+
+__device__ __forceinline__ int bytesum4(uint32_t v) { return __builtin_amdgcn_sdot4((int)v, 0x01010101, 0, false); }
+
+// ---- 1. NCHW -> NHWC with channel sums --------------------------------------------------------
+template <int VB>   // bytes per global load: 4 needs HW % 4 == 0 and a 4-byte aligned source
+__global__ __launch_bounds__(kThreads) void to_nhwc(const int8_t *__restrict__ src, int C, int HW,
+                                                    int8_t *__restrict__ dst, int *__restrict__ chansum)
+{
+    __shared__ __align__(16) int8_t tile[64 * PITCH];
+    const int n = blockIdx.y, p0 = blockIdx.x * 64;
+    const int tid = threadIdx.x;
+    const int rp = tid >> 2, rq = tid & 3;   // read-out role: position rp, 16-byte chunk rq
+    int sum = 0;
+    for (int c0 = 0; c0 < C; c0 += 64) {
+        if (VB == 4) {
+            const int ch = tid >> 4, d = tid & 15;
+#pragma unroll
+            for (int pass = 0; pass < 4; ++pass) {
+                const int c = ch + pass * 16, p = p0 + d * 4;
+                uint32_t v = 0;
+                if (p < HW) v = *reinterpret_cast<const uint32_t *>(src + (size_t)(n * C + c0 + c) * HW + p);
+                tile[(d * 4 + 0) * PITCH + c] = (int8_t)(v & 255);
+                tile[(d * 4 + 1) * PITCH + c] = (int8_t)((v >> 8) & 255);
+                tile[(d * 4 + 2) * PITCH + c] = (int8_t)((v >> 16) & 255);
+                tile[(d * 4 + 3) * PITCH + c] = (int8_t)(v >> 24);
+            }
+        } else {
+            const int ch = tid >> 6, d = tid & 63;
+#pragma unroll 4
+            for (int pass = 0; pass < 16; ++pass) {
+                const int c = ch + pass * 4, p = p0 + d;
+                tile[d * PITCH + c] = p < HW ? src[(size_t)(n * C + c0 + c) * HW + p] : (int8_t)0;
+            }
+        }
+        __syncthreads();
+        if (p0 + rp < HW) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(tile + rp * PITCH + rq * 16);
+            *reinterpret_cast<uint4 *>(dst + ((size_t)n * HW + p0 + rp) * C + c0 + rq * 16) = v;
+            sum += bytesum4(v.x) + bytesum4(v.y) + bytesum4(v.z) + bytesum4(v.w);
+        }
+        __syncthreads();
+    }
+    sum += __shfl_xor(sum, 1, Q8T_WAVE);
+    sum += __shfl_xor(sum, 2, Q8T_WAVE);
+    if (rq == 0 && p0 + rp < HW) chansum[(size_t)n * HW + p0 + rp] = sum;
+}
+
+// ---- 2. filter -> [tap][output channel][reduction channel], sums per output channel ------------
+// grid (OC, classes).  which 0: out = k, reduction = c;  which 1: out = c, reduction = k.
+__global__ __launch_bounds__(kThreads) void repack_taps(const int8_t *__restrict__ w, int Kf, int Cf, int R, int S,
+                                                        int which, TapList taps, TapList offs, ClassOffsets co,
+                                                        int8_t *__restrict__ wt, int *__restrict__ colsum,
+                                                        int *__restrict__ tapoff)
+{
+    __shared__ int part[kThreads / 64];
+    const int j = blockIdx.x, z = blockIdx.y;
+    // operand offsets of the taps, packed (dh in the low half), for the main kernel
+    if (j == 0 && z == 0 && threadIdx.x == 0)
+        for (int tt = 0; tt < co.off[MAXCLS]; ++tt)
+            tapoff[tt] = (int)((uint32_t)(uint16_t)(int16_t)offs.a[tt] | ((uint32_t)(uint16_t)(int16_t)offs.b[tt] << 16));
+    const int OC = which == 0 ? Kf : Cf, Cp = which == 0 ? Cf : Kf;
+    const int RS = R * S;
+    int sum = 0;
+    for (int tt = co.off[z]; tt < co.off[z + 1]; ++tt) {
+        const int rs = taps.a[tt] * S + taps.b[tt];
+        for (int c = threadIdx.x; c < Cp; c += kThreads) {
+            const size_t src = which == 0 ? ((size_t)j * Cf + c) * RS + rs : ((size_t)c * Cf + j) * RS + rs;
+            const int8_t v = w[src];
+            wt[((size_t)tt * OC + j) * Cp + c] = v;
+            sum += v;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, Q8T_WAVE);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) colsum[z * OC + j] = part[0] + part[1] + part[2] + part[3];
+}
+
+// ---- 3. implicit GEMM ---------------------------------------------------------------------------
+template <int BN>
+__global__ __launch_bounds__(kThreads) void igemm_nhwc(const int8_t *__restrict__ xin, const int *__restrict__ chansum,
+                                                       const int8_t *__restrict__ wt, const int *__restrict__ colsum,
+                                                       const q8t_qparams *__restrict__ qpa,
+                                                       const q8t_qparams *__restrict__ qpb, Geo g,
+                                                       const int *__restrict__ tapoff,
+                                                       float *__restrict__ out_f, int32_t *__restrict__ out_acc)
+{
+    constexpr int WM = BN == 128 ? 2 : 4;   // wavefronts along the rows
+    constexpr int MT = BM / WM / 16;        // 16-row MFMA tiles per wavefront
+    constexpr int NT = 4;                   // 16-column MFMA tiles per wavefront
+    constexpr int NB = BN / 64;             // 16-byte filter loads per thread and step
+
+    __shared__ __align__(16) int8_t sA[2][BM * PITCH];
+    __shared__ __align__(16) int8_t sB[2][BN * PITCH];
+    __shared__ int rs[BM];
+    __shared__ long long roff[BM];
+    __shared__ int stap[MAXT + 3];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, kb = lane >> 4;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const int za = qpa->zero_point - (1 << (qpa->bits - 1)), zb = qpb->zero_point - (1 << (qpb->bits - 1));
+    const float sc = qpa->scale * qpb->scale;
+    const uint32_t padw = (uint32_t)(za & 255) * 0x01010101u;
+    const int OHW = g.OH * g.OW;
+
+    if (tid < g.T) stap[tid] = tapoff[tid];
+    __syncthreads();
+    // per-row bookkeeping: operand sum over the taps (padded taps count Cp zero codes) and the
+    // offset of the row's position inside one output channel plane
+    if (tid < BM) {
+        const int m = m0 + tid;
+        int sum = 0;
+        long long off = -1;
+        if (m < g.M) {
+            const int n = m / OHW, rem = m - n * OHW;
+            const int oh = rem / g.OW, ow = rem - oh * g.OW;
+            for (int t = 0; t < g.T; ++t) {
+                const int to = stap[t];
+                const int ih = oh * g.ish + (int)(int16_t)(to & 0xFFFF), iw = ow * g.isw + (to >> 16);
+                if ((unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW)
+                    sum += chansum[(n * g.IH + ih) * g.IW + iw];
+                else
+                    sum += g.Cp * za;
+            }
+            off = (long long)n * g.OC * g.OHf * g.OWf + (long long)(oh * g.osh + g.oph) * g.OWf + ow * g.osw + g.opw;
+        }
+        rs[tid] = sum;
+        roff[tid] = off;
+    }
+
+    // staging roles
+    const int ar = tid >> 1, ah = tid & 1;   // operand: row ar, 32-byte half ah
+    const int am = m0 + ar;
+    const bool av = am < g.M;
+    int an = 0, ih0 = 0, iw0 = 0;
+    if (av) {
+        an = am / OHW;
+        const int rem = am - an * OHW;
+        const int oh = rem / g.OW;
+        ih0 = oh * g.ish;
+        iw0 = (rem - oh * g.OW) * g.isw;
+    }
+    const int br = NB == 2 ? tid >> 1 : tid >> 2;          // filter: row br
+    const int bo = NB == 2 ? (tid & 1) * 32 : (tid & 3) * 16;
+
+    const int CC = g.Cp >> 6;
+    const int steps = g.T * CC;
+    uint4 pa0, pa1, pb0, pb1;
+    pa0 = pa1 = pb0 = pb1 = make_uint4(0, 0, 0, 0);
+    int lt = 0, lc = 0;   // tap and channel chunk of the next load
+
+    auto load = [&]() {
+        const int to = stap[lt];
+        const int ih = ih0 + (int)(int16_t)(to & 0xFFFF), iw = iw0 + (to >> 16);
+        if (av && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW) {
+            const int8_t *p = xin + (size_t)((an * g.IH + ih) * g.IW + iw) * g.Cp + lc * 64 + ah * 32;
+            pa0 = *reinterpret_cast<const uint4 *>(p);
+            pa1 = *reinterpret_cast<const uint4 *>(p + 16);
+        } else {
+            pa0 = make_uint4(padw, padw, padw, padw);
+            pa1 = pa0;
+        }
+        const int8_t *q = wt + ((size_t)lt * g.OC + n0 + br) * g.Cp + lc * 64 + bo;
+        pb0 = *reinterpret_cast<const uint4 *>(q);
+        if (NB == 2) pb1 = *reinterpret_cast<const uint4 *>(q + 16);
+        if (++lc == CC) {
+            lc = 0;
+            ++lt;
+        }
+    };
+    auto store = [&](int buf) {
+        *reinterpret_cast<uint4 *>(&sA[buf][ar * PITCH + ah * 32]) = pa0;
+        *reinterpret_cast<uint4 *>(&sA[buf][ar * PITCH + ah * 32 + 16]) = pa1;
+        *reinterpret_cast<uint4 *>(&sB[buf][br * PITCH + bo]) = pb0;
+        if (NB == 2) *reinterpret_cast<uint4 *>(&sB[buf][br * PITCH + bo + 16]) = pb1;
+    };
+
+    const int rowbase = BN == 128 ? (wave & 1) * 64 : wave * 32;
+    const int colbase = BN == 128 ? (wave >> 1) * 64 : 0;
+
+    v4i acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (v4i){0, 0, 0, 0};
+
+    if (steps > 0) {
+        load();
+        store(0);
+    }
+    __syncthreads();
+    for (int s = 0; s < steps; ++s) {
+        const int buf = s & 1;
+        if (s + 1 < steps) load();
+        v4i bf[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            bf[nt] = *reinterpret_cast<const v4i *>(&sB[buf][(colbase + nt * 16 + l16) * PITCH + kb * 16]);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const v4i a = *reinterpret_cast<const v4i *>(&sA[buf][(rowbase + mt * 16 + l16) * PITCH + kb * 16]);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bf[nt], acc[mt][nt], 0, 0, 0);
+        }
+        if (s + 1 < steps) store(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: zero-point correction in wrapping 32-bit arithmetic (the corrected value fits
+    // by contract), dequantization; a lane holds 4 consecutive rows of one output channel ----
+    const uint32_t kzz = (uint32_t)(g.T * g.Cp) * (uint32_t)za * (uint32_t)zb;
+    const long long plane = (long long)g.OHf * g.OWf;
+    uint32_t csn[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) csn[nt] = (uint32_t)za * (uint32_t)colsum[n0 + colbase + nt * 16 + l16];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int r0 = rowbase + mt * 16 + kb * 4;
+        long long o[4];
+        uint32_t t[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            o[j] = roff[r0 + j];
+            t[j] = kzz - (uint32_t)zb * (uint32_t)rs[r0 + j];
+        }
+        const bool contig = g.vec && o[0] >= 0 && o[1] == o[0] + 1 && o[2] == o[0] + 2 && o[3] == o[0] + 3;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const long long cb = (long long)(n0 + colbase + nt * 16 + l16) * plane;
+            int c[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) c[j] = (int)((uint32_t)acc[mt][nt][j] + t[j] - csn[nt]);
+            if (contig && (((o[0] + cb) & 3) == 0)) {
+                if (out_acc) *reinterpret_cast<int4 *>(out_acc + o[0] + cb) = make_int4(c[0], c[1], c[2], c[3]);
+                if (out_f) {
+                    float4 f;
+                    f.x = sc * (float)c[0];
+                    f.y = sc * (float)c[1];
+                    f.z = sc * (float)c[2];
+                    f.w = sc * (float)c[3];
+                    *reinterpret_cast<float4 *>(out_f + o[0] + cb) = f;
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (o[j] < 0) continue;
+                    if (out_acc) out_acc[o[j] + cb] = c[j];
+                    if (out_f) out_f[o[j] + cb] = sc * (float)c[j];
+                }
+            }
+        }
+    }
+}
+
+struct Plan {
+    int red, oc;          // reduction and output channels
+    int IH, IW;           // operand spatial size
+    int OHf, OWf;         // result spatial size
+    int ncls;             // launches of the main kernel
+    size_t o_chansum, o_wt, o_colsum, o_tapoff, total;
+};
+
+inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+bool make_plan(int which, const q8t_conv_desc *d, Plan *p)
+{
+    if (which < 0 || which > 1) return false;
+    if (d->N <= 0 || d->C <= 0 || d->K <= 0 || d->H <= 0 || d->W <= 0 || d->R <= 0 || d->S <= 0) return false;
+    if (d->stride < 1 || d->stride > 4 || d->pad < 0 || d->pad > 100) return false;
+    if (d->R * d->S > MAXT || d->R > 100 || d->S > 100) return false;
+    if (d->H + 2 * d->pad < d->R || d->W + 2 * d->pad < d->S) return false;
+    const int P = (d->H + 2 * d->pad - d->R) / d->stride + 1, Q = (d->W + 2 * d->pad - d->S) / d->stride + 1;
+    p->red = which == 0 ? d->C : d->K;
+    p->oc = which == 0 ? d->K : d->C;
+    if (p->red % 64 || p->oc % 64) return false;
+    p->IH = which == 0 ? d->H : P;
+    p->IW = which == 0 ? d->W : Q;
+    p->OHf = which == 0 ? P : d->H;
+    p->OWf = which == 0 ? Q : d->W;
+    p->ncls = which == 0 ? 1 : d->stride * d->stride;
+    const int64_t ipos = (int64_t)d->N * p->IH * p->IW, opos = (int64_t)d->N * p->OHf * p->OWf;
+    if (ipos >= ((int64_t)1 << 31) || opos >= ((int64_t)1 << 31)) return false;
+    if ((int64_t)d->N * (which == 0 ? d->C : d->K) >= ((int64_t)1 << 31)) return false;
+    const size_t xn = up256((size_t)ipos * p->red);
+    p->o_chansum = xn;
+    p->o_wt = p->o_chansum + up256((size_t)ipos * sizeof(int));
+    p->o_colsum = p->o_wt + up256((size_t)d->K * d->C * d->R * d->S);
+    p->o_tapoff = p->o_colsum + up256((size_t)p->ncls * p->oc * sizeof(int));
+    p->total = p->o_tapoff + up256((MAXT + 3) * sizeof(int));
+    return true;
+}
+
+}  // namespace
+
+bool q8t_nhwc_conv_supported(int which, const q8t_conv_desc *d)
+{
+    Plan p;
+    return make_plan(which, d, &p);
+}
+
+size_t q8t_nhwc_conv_ws(int which, const q8t_conv_desc *d)
+{
+    Plan p;
+    return make_plan(which, d, &p) ? p.total : 0;
+}
+
+int q8t_nhwc_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
+                  const q8t_qparams *qb, float *out_f, void *out_acc, void *ws, hipStream_t st)
+{
+    Plan p;
+    if (!make_plan(which, d, &p)) return Q8T_ERR_SHAPE;
+    if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    int8_t *xn = (int8_t *)ws;
+    int *chansum = (int *)((char *)ws + p.o_chansum);
+    int8_t *wt = (int8_t *)ws + p.o_wt;
+    int *colsum = (int *)((char *)ws + p.o_colsum);
+    int *tapoff = (int *)((char *)ws + p.o_tapoff);
+
+    // 1. operand relayout
+    {
+        const int HW = p.IH * p.IW;
+        const dim3 grid((unsigned)((HW + 63) / 64), (unsigned)d->N);
+        if (HW % 4 == 0 && q8t_aligned(a, 4))
+            hipLaunchKernelGGL(to_nhwc<4>, grid, dim3(kThreads), 0, st, (const int8_t *)a, p.red, HW, xn, chansum);
+        else
+            hipLaunchKernelGGL(to_nhwc<1>, grid, dim3(kThreads), 0, st, (const int8_t *)a, p.red, HW, xn, chansum);
+        Q8T_LAUNCH_CHECK();
+    }
+
+    // 2. taps of every class.  forward: one class with all taps, operand offset (r - pad, s - pad).
+    // layer gradient: class (ph, pw) keeps the taps with (ph + pad - r) and (pw + pad - s) divisible
+    // by the stride; the operand (output-gradient) offset is that quotient.
+    TapList rs_list = {}, off_list = {};
+    ClassOffsets co = {};
+    const int stv = d->stride;
+    int nt = 0;
+    for (int z = 0; z < p.ncls; ++z) {
+        co.off[z] = nt;
+        const int ph = z / stv, pw = z % stv;
+        for (int r = 0; r < d->R; ++r)
+            for (int s = 0; s < d->S; ++s) {
+                int dh, dw;
+                if (which == 0) {
+                    dh = r - d->pad;
+                    dw = s - d->pad;
+                } else {
+                    const int eh = ph + d->pad - r, ew = pw + d->pad - s;
+                    if (eh % stv || ew % stv) continue;
+                    dh = eh / stv;
+                    dw = ew / stv;
+                }
+                rs_list.a[nt] = (int8_t)r;
+                rs_list.b[nt] = (int8_t)s;
+                off_list.a[nt] = (int8_t)dh;
+                off_list.b[nt] = (int8_t)dw;
+                ++nt;
+            }
+    }
+    for (int z = p.ncls; z <= MAXCLS; ++z) co.off[z] = nt;
+    hipLaunchKernelGGL(repack_taps, dim3((unsigned)p.oc, (unsigned)p.ncls), dim3(kThreads), 0, st, (const int8_t *)b,
+                       d->K, d->C, d->R, d->S, which, rs_list, off_list, co, wt, colsum, tapoff);
+    Q8T_LAUNCH_CHECK();
+
+    // 3. one launch per class
+    for (int z = 0; z < p.ncls; ++z) {
+        Geo g;
+        g.N = d->N;
+        g.IH = p.IH;
+        g.IW = p.IW;
+        g.Cp = p.red;
+        g.OC = p.oc;
+        g.OHf = p.OHf;
+        g.OWf = p.OWf;
+        if (which == 0) {
+            g.OH = p.OHf;
+            g.OW = p.OWf;
+            g.ish = g.isw = stv;
+            g.osh = g.osw = 1;
+            g.oph = g.opw = 0;
+        } else {
+            const int ph = z / stv, pw = z % stv;
+            g.OH = (p.OHf - ph + stv - 1) / stv;
+            g.OW = (p.OWf - pw + stv - 1) / stv;
+            g.ish = g.isw = 1;
+            g.osh = g.osw = stv;
+            g.oph = ph;
+            g.opw = pw;
+        }
+        if (g.OH <= 0 || g.OW <= 0) continue;
+        g.M = d->N * g.OH * g.OW;
+        g.T = co.off[z + 1] - co.off[z];
+        g.vec = q8t_aligned(out_f, 16) && q8t_aligned(out_acc, 16);
+        const int8_t *wz = wt + (size_t)co.off[z] * p.oc * p.red;
+        const int *cz = colsum + (size_t)z * p.oc;
+        const unsigned mt = (unsigned)((g.M + BM - 1) / BM);
+        if (p.oc % 128 == 0)
+            hipLaunchKernelGGL(igemm_nhwc<128>, dim3(mt, (unsigned)(p.oc / 128)), dim3(kThreads), 0, st, xn, chansum,
+                               wz, cz, qa, qb, g, tapoff + co.off[z], out_f, (int32_t *)out_acc);
+        else
+            hipLaunchKernelGGL(igemm_nhwc<64>, dim3(mt, (unsigned)(p.oc / 64)), dim3(kThreads), 0, st, xn, chansum, wz,
+                               cz, qa, qb, g, tapoff + co.off[z], out_f, (int32_t *)out_acc);
+        Q8T_LAUNCH_CHECK();
+    }
+    return Q8T_OK;
+}

@@ -21,11 +21,25 @@ size_t q8t_fast_conv_ws(int which, const q8t_conv_desc *d);
 int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
                   const q8t_qparams *qb, float *out_f, void *out_acc, void *ws, hipStream_t st);
 
+// general MFMA path over a channel-contiguous copy of the operand (conv_nhwc.hip): forward and
+// layer gradient, channel counts that are multiples of 64
+bool q8t_nhwc_conv_supported(int which, const q8t_conv_desc *d);
+size_t q8t_nhwc_conv_ws(int which, const q8t_conv_desc *d);
+int q8t_nhwc_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
+                  const q8t_qparams *qb, float *out_f, void *out_acc, void *ws, hipStream_t st);
+
 // specialised 3x3 weight-gradient kernel (wgrad_fast.hip)
 bool q8t_fast_wgrad_supported(const q8t_conv_desc *d, const void *g16, const void *x, const void *dw,
                               const void *acc);
 size_t q8t_fast_wgrad_ws(const q8t_conv_desc *d);
 int q8t_fast_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams *qg, const int8_t *x,
+                   const q8t_qparams *qx, float *dw, int64_t *acc_out, void *ws, hipStream_t st);
+
+// general weight-gradient path: byte planes of the gradient x im2col rows of the input as one
+// int8 MFMA GEMM with the reduction split into overflow-free slices (wgrad_gemm.hip)
+bool q8t_gemm_wgrad_supported(const q8t_conv_desc *d);
+size_t q8t_gemm_wgrad_ws(const q8t_conv_desc *d);
+int q8t_gemm_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams *qg, const int8_t *x,
                    const q8t_qparams *qx, float *dw, int64_t *acc_out, void *ws, hipStream_t st);
 
 // bifurcated quantization from ready-made (min,max) pairs (quantize.hip)

@@ -79,7 +79,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
     const int plane = wave & 1, kl = wave >> 1;
     const int l16 = lane & 15, kb = lane >> 4;
 
-    const int zsg = qpg->zero_point - 32768, zsx = qpx->zero_point - 128;
+    const int zsg = qpg->zero_point - (1 << (qpg->bits - 1)), zsx = qpx->zero_point - (1 << (qpx->bits - 1));
     const uint32_t a_pad = (uint32_t)(zsg & 0xFFFF) * 0x00010001u;   // two zero codes
     const uint32_t b_pad = (uint32_t)(zsx & 255) * 0x01010101u;
 
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(256) void wgrad_reduce(const int *__restrict__ part
     const int tap = mt_tap % 9, mt = mt_tap / 9;
     const int row_l = mt * 16 + (lane >> 4) * 4 + j, ch_l = lane & 15;
 
-    const int zsg = qpg->zero_point - 32768, zsx = qpx->zero_point - 128;
+    const int zsg = qpg->zero_point - (1 << (qpg->bits - 1)), zsx = qpx->zero_point - (1 << (qpx->bits - 1));
     const int64_t ca = 128 - zsg;
     const int ksteps_img = (g.Lp + 63) / 64;
     int64_t v = 0;

@@ -112,6 +112,21 @@ CONV_CASES = [
     (9, 64, 14, 14, 128, 3, 3, 1, 1),
     (3, 128, 28, 28, 128, 3, 3, 1, 1),
     (2, 64, 10, 18, 64, 3, 3, 1, 1),     # width not a multiple of 4
+    # channel-contiguous general MFMA path (channels multiples of 64, shape not covered by the 3x3 / 1x1 kernels)
+    (3, 128, 7, 7, 64, 3, 3, 1, 1),      # 49-position planes: byte relayout, unaligned result rows
+    (2, 64, 9, 11, 128, 3, 3, 2, 1),     # odd sizes at stride 2: uneven stride classes in the layer gradient
+    (2, 64, 13, 13, 64, 5, 5, 3, 2),     # stride 3, 5x5
+    (1, 64, 20, 20, 64, 7, 7, 2, 3),     # 49 taps
+    (2, 128, 7, 7, 128, 1, 1, 1, 0),
+    (2, 64, 8, 8, 64, 2, 2, 2, 0),       # even filter size, no padding
+    (130, 64, 3, 3, 64, 3, 3, 1, 1),     # many tiny images, ragged last tile
+    (2, 64, 11, 9, 64, 3, 3, 2, 0),      # input rows and columns no output touches (zero layer gradient there)
+    # GEMM form of the weight gradient (byte planes x im2col rows)
+    (16, 3, 32, 32, 64, 7, 7, 2, 3),     # first-layer shape: 3 input channels, 147 columns
+    (8, 256, 14, 14, 256, 3, 3, 1, 1),   # 14x14 planes, 256 channels
+    (16, 512, 7, 7, 512, 3, 3, 1, 1),    # 7x7 planes, 512 channels
+    (24, 64, 56, 56, 64, 1, 1, 1, 0),    # reduction longer than one overflow-free slice
+    (5, 24, 17, 13, 40, 3, 2, 2, 1),     # nothing a multiple of anything
 ]
 
 
@@ -130,6 +145,35 @@ def test_conv_products(case):
     q8t = require_gpu()
     g = synth.rng(sum(case))
     od, (sx, px), (sw, pw), (sg, pg), (sg16, pg16) = _conv_operands(g, case)
+    d = q8t.conv_desc(*case)
+    dpx, dpw, dpg, dpg16 = (qp_dev_from(p) for p in (px, pw, pg, pg16))
+    y, acc = q8t.qconv_fwd(d, dev(sx), dpx, dev(sw), dpw, want_acc=True)
+    oy, oacc = oracle.qconv_fwd(od, sx, px, sw, pw)
+    same_ints(host(acc), oacc)
+    close(host(y), oy)
+    dx, acc = q8t.qconv_dgrad(d, dev(sg), dpg, dev(sw), dpw, want_acc=True)
+    odx, oacc = oracle.qconv_dgrad(od, sg, pg, sw, pw)
+    same_ints(host(acc), oacc)
+    close(host(dx), odx)
+    dw, acc = q8t.qconv_wgrad(d, dev(sx), dpx, dev(sg16), dpg16, want_acc=True)
+    odw, oacc = oracle.qconv_wgrad(od, sx, px, sg16, pg16)
+    same_ints(host(acc), oacc)
+    close(host(dw), odw)
+
+
+@pytest.mark.parametrize("case", [(2, 64, 14, 14, 64, 3, 3, 1, 1), (2, 64, 9, 11, 128, 3, 3, 2, 1),
+                                  (2, 16, 9, 9, 24, 3, 3, 1, 1), (2, 64, 10, 10, 128, 1, 1, 1, 0)])
+def test_conv_products_below_8_and_16_bits(case):
+    # widths M < 8 (and < 16 for the weight-gradient operand) are stored as level - 2^(M-1) in the
+    # same containers; every kernel family has to take the stored zero point from the width
+    q8t = require_gpu()
+    g = synth.rng(77 + sum(case))
+    N, C, H, W, K, R, S, st, pad = case
+    od = oracle.conv_desc(*case)
+    sx, px = _rand_q(g, (N, C, H, W), bits=5)
+    sw, pw = _rand_q(g, (K, C, R, S), bits=4)
+    sg, pg = _rand_q(g, (N, K, od.P, od.Q), bits=6)
+    sg16, pg16 = _rand_q(g, (N, K, od.P, od.Q), bits=12)
     d = q8t.conv_desc(*case)
     dpx, dpw, dpg, dpg16 = (qp_dev_from(p) for p in (px, pw, pg, pg16))
     y, acc = q8t.qconv_fwd(d, dev(sx), dpx, dev(sw), dpw, want_acc=True)
