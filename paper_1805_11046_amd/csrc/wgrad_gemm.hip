@@ -33,7 +33,20 @@ __device__ __forceinline__ int bytesum16(const uint4 &v)
     return bytesum4(v.x) + bytesum4(v.y) + bytesum4(v.z) + bytesum4(v.w);
 }
 
+// quotient x / d for 0 <= x < 2^24 through the float reciprocal, corrected by at most one
+__device__ __forceinline__ int fdiv(int x, int d, float rd)
+{
+    int q = (int)((float)x * rd);
+    const int r = x - q * d;
+    if (r < 0) --q;
+    else if (r >= d) ++q;
+    return q;
+}
+
 // ---- A': byte planes of the 16-bit gradient, [2K][Mp] -----------------------------------------
+// G = codes per global load: 16 (planes of a multiple of 16 positions, 32-byte aligned rows),
+// 4 (multiple of 4, 8-byte aligned) or 1.  A group of G positions never straddles two images.
+template <int G>
 __global__ __launch_bounds__(kThreads) void split16(const int16_t *__restrict__ g16, int K, int PQ, int64_t Mtot,
                                                     int64_t Mp, const q8t_qparams *__restrict__ qpg,
                                                     int8_t *__restrict__ A)
@@ -44,18 +57,50 @@ __global__ __launch_bounds__(kThreads) void split16(const int16_t *__restrict__ 
     const int k = (int)(id / chunks);
     const int64_t m0 = (id - (int64_t)k * chunks) << 4;
     const int zsg = qpg->zero_point - (1 << (qpg->bits - 1));
+    const uint32_t zz = (uint32_t)(zsg & 0xFFFF) * 0x00010001u;
     int n = (int)(m0 / PQ), pq = (int)(m0 - (int64_t)n * PQ);
-    uint32_t hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
+    uint32_t d[8];   // 16 codes, two per dword
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        int s = zsg;
-        if (m0 + i < Mtot) s = g16[((size_t)n * K + k) * PQ + pq];
-        hi[i >> 2] |= (uint32_t)((s >> 8) & 255) << (8 * (i & 3));
-        lo[i >> 2] |= (uint32_t)(((s & 255) - 128) & 255) << (8 * (i & 3));
-        if (++pq == PQ) {
-            pq = 0;
-            ++n;
+    for (int i = 0; i < 8; ++i) d[i] = zz;
+    if (G == 16) {
+        if (m0 < Mtot) {
+            const uint4 *src = reinterpret_cast<const uint4 *>(g16 + ((size_t)n * K + k) * PQ + pq);
+            const uint4 u = src[0], v = src[1];
+            d[0] = u.x; d[1] = u.y; d[2] = u.z; d[3] = u.w;
+            d[4] = v.x; d[5] = v.y; d[6] = v.z; d[7] = v.w;
         }
+    } else if (G == 4) {
+#pragma unroll
+        for (int grp = 0; grp < 4; ++grp) {
+            if (m0 + grp * 4 < Mtot) {
+                const uint2 u = *reinterpret_cast<const uint2 *>(g16 + ((size_t)n * K + k) * PQ + pq);
+                d[grp * 2] = u.x;
+                d[grp * 2 + 1] = u.y;
+            }
+            pq += 4;
+            if (pq == PQ) {
+                pq = 0;
+                ++n;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if (m0 + i < Mtot) {
+                const uint32_t s = (uint16_t)g16[((size_t)n * K + k) * PQ + pq];
+                d[i >> 1] = (i & 1) ? (d[i >> 1] & 0x0000FFFFu) | (s << 16) : (d[i >> 1] & 0xFFFF0000u) | s;
+            }
+            if (++pq == PQ) {
+                pq = 0;
+                ++n;
+            }
+        }
+    }
+    uint32_t hi[4], lo[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        hi[i] = __builtin_amdgcn_perm(d[2 * i + 1], d[2 * i], 0x07050301u);
+        lo[i] = __builtin_amdgcn_perm(d[2 * i + 1], d[2 * i], 0x06040200u) ^ 0x80808080u;
     }
     *reinterpret_cast<uint4 *>(A + (size_t)k * Mp + m0) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
     *reinterpret_cast<uint4 *>(A + (size_t)(K + k) * Mp + m0) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
@@ -101,6 +146,61 @@ __global__ __launch_bounds__(kThreads) void im2col_rows(const int8_t *__restrict
         }
     }
     *reinterpret_cast<uint4 *>(B + (size_t)col * Mp + m0) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// Same result through LDS: a workgroup stages the zero-padded planes of one channel for a group of
+// NI images (NI*P*Q a multiple of 4, so that its stretch of every row starts on a dword), then
+// every thread builds one dword (4 consecutive positions) for each of the R*S taps.  The input is
+// read once instead of R*S times and every store is a full dword.
+__global__ __launch_bounds__(kThreads) void im2col_planes(const int8_t *__restrict__ x, ConvG g, int NI, int64_t Mtot,
+                                                          int64_t Mp, const q8t_qparams *__restrict__ qpx,
+                                                          int8_t *__restrict__ B)
+{
+    extern __shared__ __align__(16) int8_t planes[];
+    const int c = blockIdx.y, n0 = blockIdx.x * NI;
+    const int ni = min(NI, g.N - n0);
+    const int Hp = g.H + 2 * g.pad, Wp = g.W + 2 * g.pad, PB = Hp * Wp;
+    const int PQ = g.P * g.Q, HW = g.H * g.W;
+    const int zsx = qpx->zero_point - (1 << (qpx->bits - 1));
+    for (int i = threadIdx.x; i < ni * PB; i += kThreads) planes[i] = (int8_t)zsx;
+    __syncthreads();
+    const float rHW = 1.0f / (float)HW, rW = 1.0f / (float)g.W, rPQ = 1.0f / (float)PQ, rQ = 1.0f / (float)g.Q;
+    for (int i = threadIdx.x; i < ni * HW; i += kThreads) {
+        const int nl = fdiv(i, HW, rHW), t = i - nl * HW, h = fdiv(t, g.W, rW), w = t - h * g.W;
+        planes[nl * PB + (h + g.pad) * Wp + w + g.pad] = x[((size_t)(n0 + nl) * g.C + c) * HW + t];
+    }
+    __syncthreads();
+    const int64_t mbase = (int64_t)n0 * PQ;
+    const bool last = n0 + NI >= g.N;
+    const int64_t mend = last ? Mp : mbase + (int64_t)NI * PQ;   // the last group also writes the padding
+    const int ndw = (int)((mend - mbase) >> 2);
+    const int RS = g.R * g.S;
+    const uint32_t zb = (uint32_t)(zsx & 255);
+    for (int dp = threadIdx.x; dp < ndw; dp += kThreads) {
+        int off[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = dp * 4 + j;
+            off[j] = -1;
+            if (mbase + e < Mtot) {
+                const int nl = fdiv(e, PQ, rPQ), t = e - nl * PQ, pp = fdiv(t, g.Q, rQ), qq = t - pp * g.Q;
+                off[j] = nl * PB + pp * g.stride * Wp + qq * g.stride;
+            }
+        }
+        int8_t *dst = B + ((size_t)c * RS) * Mp + mbase + (int64_t)dp * 4;
+        for (int r = 0; r < g.R; ++r)
+            for (int s = 0; s < g.S; ++s) {
+                const int o = r * Wp + s;
+                uint32_t v = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t b = off[j] >= 0 ? (uint32_t)(uint8_t)planes[off[j] + o] : zb;
+                    v |= b << (8 * j);
+                }
+                *reinterpret_cast<uint32_t *>(dst) = v;
+                dst += Mp;
+            }
+    }
 }
 
 // ---- C[z][i][j] = sum over slice z of A'[i][m] * B'[j][m] ---------------------------------------
@@ -200,35 +300,183 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const int8_t *__restrict__ A
                 dst[(size_t)(r0 + rowbase + mt * 16 + kb * 4 + j) * Rbp + c0 + colbase + nt * 16 + l16] = acc[mt][nt][j];
 }
 
+// ---- 1x1, stride 1, no padding, planes of a multiple of 64 positions ---------------------------
+// Both operands are read in place: a step is 64 consecutive positions of one image, where row k
+// of the gradient and row c of the input are contiguous in NCHW.  The 16-bit codes are split into
+// their byte planes in registers.  A row tile holds 64 output channels: rows 0..63 the high
+// bytes, rows 64..127 the low bytes, and the slice results keep that tiled row order.
+template <int BN>
+__global__ __launch_bounds__(kThreads) void gemm_direct(const int16_t *__restrict__ g16, const int8_t *__restrict__ x, int K,
+                                                        int C, int PQ, int steps_total, int steps_slice, int Rap, int Rbp,
+                                                        int32_t *__restrict__ part, int *__restrict__ rsum,
+                                                        int *__restrict__ csum)
+{
+    constexpr int WM = BN == 128 ? 2 : 4;
+    constexpr int MT = BM / WM / 16;
+    constexpr int NT = 4;
+    constexpr int NB = BN / 64;
+
+    __shared__ __align__(16) int8_t sA[2][BM * PITCH];
+    __shared__ __align__(16) int8_t sB[2][BN * PITCH];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, kb = lane >> 4;
+    const int k0 = blockIdx.x * 64, c0 = blockIdx.y * BN, z = blockIdx.z;
+    const int r0 = blockIdx.x * BM;
+    const int t0 = z * steps_slice;
+    const int steps = min(steps_slice, steps_total - t0);
+    const int cpi = PQ >> 6;   // steps per image
+
+    const int kr = tid >> 2, kq = tid & 3;                 // gradient row, 16-code quarter
+    const int br = NB == 2 ? tid >> 1 : tid >> 2;
+    const int bo = NB == 2 ? (tid & 1) * 32 : (tid & 3) * 16;
+    int n = t0 / cpi, ch = t0 - n * cpi;
+
+    uint4 a0, a1, b0, b1;
+    a0 = a1 = b0 = b1 = make_uint4(0, 0, 0, 0);
+    int shi = 0, slo = 0, sb = 0;
+    auto load = [&]() {
+        const int16_t *pa = g16 + ((size_t)n * K + k0 + kr) * PQ + ch * 64 + kq * 16;
+        const int8_t *pb = x + ((size_t)n * C + c0 + br) * PQ + ch * 64 + bo;
+        a0 = *reinterpret_cast<const uint4 *>(pa);
+        a1 = *reinterpret_cast<const uint4 *>(pa + 8);
+        b0 = *reinterpret_cast<const uint4 *>(pb);
+        if (NB == 2) b1 = *reinterpret_cast<const uint4 *>(pb + 16);
+        if (++ch == cpi) {
+            ch = 0;
+            ++n;
+        }
+    };
+    auto store = [&](int buf) {
+        uint4 hi, lo;
+        hi.x = __builtin_amdgcn_perm(a0.y, a0.x, 0x07050301u);
+        hi.y = __builtin_amdgcn_perm(a0.w, a0.z, 0x07050301u);
+        hi.z = __builtin_amdgcn_perm(a1.y, a1.x, 0x07050301u);
+        hi.w = __builtin_amdgcn_perm(a1.w, a1.z, 0x07050301u);
+        lo.x = __builtin_amdgcn_perm(a0.y, a0.x, 0x06040200u) ^ 0x80808080u;
+        lo.y = __builtin_amdgcn_perm(a0.w, a0.z, 0x06040200u) ^ 0x80808080u;
+        lo.z = __builtin_amdgcn_perm(a1.y, a1.x, 0x06040200u) ^ 0x80808080u;
+        lo.w = __builtin_amdgcn_perm(a1.w, a1.z, 0x06040200u) ^ 0x80808080u;
+        *reinterpret_cast<uint4 *>(&sA[buf][kr * PITCH + kq * 16]) = hi;
+        *reinterpret_cast<uint4 *>(&sA[buf][(64 + kr) * PITCH + kq * 16]) = lo;
+        *reinterpret_cast<uint4 *>(&sB[buf][br * PITCH + bo]) = b0;
+        if (NB == 2) *reinterpret_cast<uint4 *>(&sB[buf][br * PITCH + bo + 16]) = b1;
+        shi += bytesum16(hi);
+        slo += bytesum16(lo);
+        sb += bytesum16(b0);
+        if (NB == 2) sb += bytesum16(b1);
+    };
+
+    const int rowbase = BN == 128 ? (wave & 1) * 64 : wave * 32;
+    const int colbase = BN == 128 ? (wave >> 1) * 64 : 0;
+    v4i acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (v4i){0, 0, 0, 0};
+
+    if (steps > 0) {
+        load();
+        store(0);
+    }
+    __syncthreads();
+    for (int s = 0; s < steps; ++s) {
+        const int buf = s & 1;
+        if (s + 1 < steps) load();
+        v4i bf[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            bf[nt] = *reinterpret_cast<const v4i *>(&sB[buf][(colbase + nt * 16 + l16) * PITCH + kb * 16]);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const v4i a = *reinterpret_cast<const v4i *>(&sA[buf][(rowbase + mt * 16 + l16) * PITCH + kb * 16]);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bf[nt], acc[mt][nt], 0, 0, 0);
+        }
+        if (s + 1 < steps) store(buf ^ 1);
+        __syncthreads();
+    }
+
+    shi += __shfl_xor(shi, 1, Q8T_WAVE);
+    shi += __shfl_xor(shi, 2, Q8T_WAVE);
+    slo += __shfl_xor(slo, 1, Q8T_WAVE);
+    slo += __shfl_xor(slo, 2, Q8T_WAVE);
+    sb += __shfl_xor(sb, 1, Q8T_WAVE);
+    if (NB == 1) sb += __shfl_xor(sb, 2, Q8T_WAVE);
+    if (blockIdx.y == 0 && kq == 0) {
+        rsum[(size_t)z * Rap + r0 + kr] = shi;
+        rsum[(size_t)z * Rap + r0 + 64 + kr] = slo;
+    }
+    if (blockIdx.x == 0 && (NB == 2 ? (tid & 1) == 0 : (tid & 3) == 0)) csum[(size_t)z * Rbp + c0 + br] = sb;
+
+    int32_t *dst = part + (size_t)z * Rap * Rbp;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                dst[(size_t)(r0 + rowbase + mt * 16 + kb * 4 + j) * Rbp + c0 + colbase + nt * 16 + l16] = acc[mt][nt][j];
+}
+
 // ---- slices -> exact 64-bit sums -> outputs ------------------------------------------------------
 // acc(k,col) = sum (g - zg)(x - zx),  g = 256*hi + lo + 128 :
 //   256*S_hi + S_lo + (128 - zg)*colsum - zx*(256*rowsum_hi + rowsum_lo + (128 - zg)*Mp)
+// A workgroup owns 256/zgn consecutive outputs; its zgn groups of lanes share the slices.
 __global__ __launch_bounds__(kThreads) void wgrad_finish(const int32_t *__restrict__ part, const int *__restrict__ rsum,
                                                          const int *__restrict__ csum, int nz, int K, int CRS, int Rap,
                                                          int Rbp, int64_t Mp, const q8t_qparams *__restrict__ qpg,
                                                          const q8t_qparams *__restrict__ qpx, float *__restrict__ dw,
-                                                         int64_t *__restrict__ acc_out)
+                                                         int64_t *__restrict__ acc_out, int zgn, int tiled)
 {
-    const int64_t id = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (id >= (int64_t)K * CRS) return;
-    const int k = (int)(id / CRS), col = (int)(id - (int64_t)k * CRS);
-    const int zg = qpg->zero_point - (1 << (qpg->bits - 1)), zx = qpx->zero_point - (1 << (qpx->bits - 1));
-    int64_t shi = 0, slo = 0, rhi = 0, rlo = 0, cs = 0;
-    for (int z = 0; z < nz; ++z) {
-        shi += part[((size_t)z * Rap + k) * Rbp + col];
-        slo += part[((size_t)z * Rap + K + k) * Rbp + col];
-        rhi += rsum[(size_t)z * Rap + k];
-        rlo += rsum[(size_t)z * Rap + K + k];
-        cs += csum[(size_t)z * Rbp + col];
+    __shared__ long long red[5][kThreads];
+    const int per = kThreads / zgn;
+    const int o = threadIdx.x % per, zg = threadIdx.x / per;
+    const int64_t id = (int64_t)blockIdx.x * per + o;
+    const bool ok = id < (int64_t)K * CRS;
+    long long shi = 0, slo = 0, rhi = 0, rlo = 0, cs = 0;
+    int k = 0, col = 0;
+    if (ok) {
+        k = (int)(id / CRS);
+        col = (int)(id - (int64_t)k * CRS);
+        // rows of the two byte planes: [all high | all low], or per 64 channels [64 high | 64 low]
+        const int rh = tiled ? (k >> 6) * 128 + (k & 63) : k, rl = tiled ? rh + 64 : K + k;
+        for (int z = zg; z < nz; z += zgn) {
+            shi += part[((size_t)z * Rap + rh) * Rbp + col];
+            slo += part[((size_t)z * Rap + rl) * Rbp + col];
+            rhi += rsum[(size_t)z * Rap + rh];
+            rlo += rsum[(size_t)z * Rap + rl];
+            cs += csum[(size_t)z * Rbp + col];
+        }
     }
-    const int64_t ca = 128 - zg;
-    const int64_t v = 256 * shi + slo + ca * cs - (int64_t)zx * (256 * rhi + rlo + ca * Mp);
+    if (zgn > 1) {
+        red[0][threadIdx.x] = shi;
+        red[1][threadIdx.x] = slo;
+        red[2][threadIdx.x] = rhi;
+        red[3][threadIdx.x] = rlo;
+        red[4][threadIdx.x] = cs;
+        __syncthreads();
+        if (zg != 0 || !ok) return;
+        shi = slo = rhi = rlo = cs = 0;
+        for (int g = 0; g < zgn; ++g) {
+            shi += red[0][g * per + o];
+            slo += red[1][g * per + o];
+            rhi += red[2][g * per + o];
+            rlo += red[3][g * per + o];
+            cs += red[4][g * per + o];
+        }
+    }
+    if (!ok) return;
+    const int zsg = qpg->zero_point - (1 << (qpg->bits - 1)), zsx = qpx->zero_point - (1 << (qpx->bits - 1));
+    const int64_t ca = 128 - zsg;
+    const int64_t v = 256 * shi + slo + ca * cs - (int64_t)zsx * (256 * rhi + rlo + ca * Mp);
     if (acc_out) acc_out[id] = v;
     if (dw) dw[id] = (float)((double)v * (double)(qpg->scale * qpx->scale));
 }
 
 struct Plan {
-    int P, Q, CRS, Rap, Rbp, nz, slice;
+    int P, Q, CRS, Rap, Rbp, nz, slice, direct;
     int64_t Mtot, Mp;
     size_t o_B, o_part, o_rsum, o_csum, total;
 };
@@ -254,7 +502,7 @@ bool make_plan(const q8t_conv_desc *d, Plan *p)
     p->Rap = (2 * d->K + BM - 1) / BM * BM;
     p->Rbp = (p->CRS + 63) / 64 * 64;
     const int64_t tiles = (int64_t)(p->Rap / BM) * (p->Rbp % 128 == 0 ? p->Rbp / 128 : p->Rbp / 64);
-    int64_t nz = (1024 + tiles - 1) / tiles;                 // enough workgroups to fill the chip
+    int64_t nz = (768 + tiles - 1) / tiles;                  // enough workgroups to fill the chip
     const int64_t most = (p->Mp + 1023) / 1024;              // but at least 16 steps per slice
     if (nz > most) nz = most;
     const int64_t ovf = (p->Mp + kMaxSlice - 1) / kMaxSlice;  // 32-bit accumulator bound
@@ -265,6 +513,9 @@ bool make_plan(const q8t_conv_desc *d, Plan *p)
     if (nz > 65535) return false;
     p->nz = (int)nz;
     p->slice = (int)slice;
+    // 1x1 / stride 1 / no padding on planes of a multiple of 64 positions: operands are used in place
+    p->direct = d->R == 1 && d->S == 1 && d->stride == 1 && d->pad == 0 && (p->P * p->Q) % 64 == 0 && d->K % 64 == 0 &&
+                d->C % 64 == 0;
     const size_t a_bytes = up256((size_t)p->Rap * p->Mp);
     p->o_B = a_bytes;
     p->o_part = p->o_B + up256((size_t)p->Rbp * p->Mp);
@@ -300,15 +551,41 @@ int q8t_gemm_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams
     int *rsum = (int *)((char *)ws + p.o_rsum);
     int *csum = (int *)((char *)ws + p.o_csum);
     const int64_t chunks = p.Mp >> 4;
+    const int direct = p.direct && q8t_aligned(g16, 16) && q8t_aligned(x, 16);
+    if (direct) {
+        const int steps_total = (int)(p.Mtot >> 6), steps_slice = p.slice >> 6;
+        if (p.Rbp % 128 == 0)
+            hipLaunchKernelGGL(gemm_direct<128>, dim3((unsigned)(d->K / 64), (unsigned)(p.Rbp / 128), (unsigned)p.nz),
+                               dim3(kThreads), 0, st, g16, x, d->K, d->C, p.P * p.Q, steps_total, steps_slice, p.Rap,
+                               p.Rbp, part, rsum, csum);
+        else
+            hipLaunchKernelGGL(gemm_direct<64>, dim3((unsigned)(d->K / 64), (unsigned)(p.Rbp / 64), (unsigned)p.nz),
+                               dim3(kThreads), 0, st, g16, x, d->K, d->C, p.P * p.Q, steps_total, steps_slice, p.Rap,
+                               p.Rbp, part, rsum, csum);
+        Q8T_LAUNCH_CHECK();
+    } else {
     {
         const int64_t blocks = (chunks * d->K + kThreads - 1) / kThreads;
-        hipLaunchKernelGGL(split16, dim3((unsigned)blocks), dim3(kThreads), 0, st, g16, d->K, p.P * p.Q, p.Mtot, p.Mp, qg, A);
+        const int PQ = p.P * p.Q;
+        if (PQ % 16 == 0 && q8t_aligned(g16, 16))
+            hipLaunchKernelGGL(split16<16>, dim3((unsigned)blocks), dim3(kThreads), 0, st, g16, d->K, PQ, p.Mtot, p.Mp, qg, A);
+        else if (PQ % 4 == 0 && q8t_aligned(g16, 8))
+            hipLaunchKernelGGL(split16<4>, dim3((unsigned)blocks), dim3(kThreads), 0, st, g16, d->K, PQ, p.Mtot, p.Mp, qg, A);
+        else
+            hipLaunchKernelGGL(split16<1>, dim3((unsigned)blocks), dim3(kThreads), 0, st, g16, d->K, PQ, p.Mtot, p.Mp, qg, A);
         Q8T_LAUNCH_CHECK();
     }
     {
         ConvG g = {d->N, d->C, d->H, d->W, d->K, d->R, d->S, d->stride, d->pad, p.P, p.Q};
         const int64_t blocks = (chunks * p.CRS + kThreads - 1) / kThreads;
-        hipLaunchKernelGGL(im2col_rows, dim3((unsigned)blocks), dim3(kThreads), 0, st, x, g, p.Mtot, p.Mp, qx, B);
+        const int PQ = p.P * p.Q;
+        const int NI = PQ % 4 == 0 ? 1 : (PQ % 2 == 0 ? 2 : 4);
+        const size_t lds = (size_t)NI * (d->H + 2 * d->pad) * (d->W + 2 * d->pad);
+        if (lds <= 65536 && (int64_t)NI * PQ + 64 < (1 << 24) && (int64_t)NI * d->H * d->W < (1 << 24) && d->C <= 65535)
+            hipLaunchKernelGGL(im2col_planes, dim3((unsigned)((d->N + NI - 1) / NI), (unsigned)d->C), dim3(kThreads), lds,
+                               st, x, g, NI, p.Mtot, p.Mp, qx, B);
+        else
+            hipLaunchKernelGGL(im2col_rows, dim3((unsigned)blocks), dim3(kThreads), 0, st, x, g, p.Mtot, p.Mp, qx, B);
         Q8T_LAUNCH_CHECK();
     }
     if (p.Rbp % 128 == 0)
@@ -318,10 +595,13 @@ int q8t_gemm_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams
         hipLaunchKernelGGL(gemm_nt<64>, dim3((unsigned)(p.Rap / BM), (unsigned)(p.Rbp / 64), (unsigned)p.nz),
                            dim3(kThreads), 0, st, A, B, p.Mp, p.slice, p.Rap, p.Rbp, part, rsum, csum);
     Q8T_LAUNCH_CHECK();
+    }
     {
         const int64_t count = (int64_t)d->K * p.CRS;
-        hipLaunchKernelGGL(wgrad_finish, dim3((unsigned)((count + kThreads - 1) / kThreads)), dim3(kThreads), 0, st,
-                           part, rsum, csum, p.nz, d->K, p.CRS, p.Rap, p.Rbp, p.Mp, qg, qx, dw, acc_out);
+        const int zgn = p.nz >= 64 ? 16 : (p.nz >= 8 ? 4 : 1);   // lanes sharing the slices of one output
+        const int per = kThreads / zgn;
+        hipLaunchKernelGGL(wgrad_finish, dim3((unsigned)((count + per - 1) / per)), dim3(kThreads), 0, st,
+                           part, rsum, csum, p.nz, d->K, p.CRS, p.Rap, p.Rbp, p.Mp, qg, qx, dw, acc_out, zgn, direct);
         Q8T_LAUNCH_CHECK();
     }
     return Q8T_OK;
