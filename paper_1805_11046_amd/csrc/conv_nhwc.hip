@@ -25,10 +25,11 @@
 // spent on taps that cannot contribute.
 #include "q8t_common.h"
 #include "q8t_internal.h"
+#include "gemm_core.h"
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
+using q8t_gemm::v4i;
 
 constexpr int kThreads = 256;
 constexpr int BM = 128;      // output positions per workgroup
@@ -133,6 +134,50 @@ __global__ __launch_bounds__(kThreads) void repack_taps(const int8_t *__restrict
 }
 
 // ---- 3. implicit GEMM ---------------------------------------------------------------------------
+// operand staging of one thread: row `ar` of the tile (one output position), 32-byte half `ah`;
+// filter row `br`, byte offset `bo`
+template <int NB>
+struct ConvOps {
+    const int8_t *xin, *wt;
+    const __attribute__((address_space(3))) int *stap;   // tap offsets, in LDS
+    int8_t *sA, *sB;
+    int IH, IW, Cp, OC, CC;
+    int an, ih0, iw0, ar, ah, n0br, bo, br;
+    bool av;
+    uint32_t padw;
+    int lt, lc;   // tap and channel chunk of the next load
+
+    __device__ __forceinline__ void load(q8t_gemm::Regs &r)
+    {
+        const int to = stap[lt];
+        const int ih = ih0 + (int)(int16_t)(to & 0xFFFF), iw = iw0 + (to >> 16);
+        uint4 t0 = make_uint4(padw, padw, padw, padw), t1 = t0;
+        if (av && (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW) {
+            const int8_t *p = xin + (size_t)((an * IH + ih) * IW + iw) * Cp + lc * 64 + ah * 32;
+            t0 = *reinterpret_cast<const uint4 *>(p);
+            t1 = *reinterpret_cast<const uint4 *>(p + 16);
+        }
+        r.a0 = t0;
+        r.a1 = t1;
+        const int8_t *q = wt + ((size_t)lt * OC + n0br) * Cp + lc * 64 + bo;
+        r.b0 = *reinterpret_cast<const uint4 *>(q);
+        if (NB == 2) r.b1 = *reinterpret_cast<const uint4 *>(q + 16);
+        if (++lc == CC) {
+            lc = 0;
+            ++lt;
+        }
+    }
+    __device__ __forceinline__ void store(const q8t_gemm::Regs &r, int buf)
+    {
+        int8_t *a = sA + buf * q8t_gemm::BM * PITCH + ar * PITCH + ah * 32;
+        *reinterpret_cast<uint4 *>(a) = r.a0;
+        *reinterpret_cast<uint4 *>(a + 16) = r.a1;
+        int8_t *b = sB + buf * (NB * 64) * PITCH + br * PITCH + bo;
+        *reinterpret_cast<uint4 *>(b) = r.b0;
+        if (NB == 2) *reinterpret_cast<uint4 *>(b + 16) = r.b1;
+    }
+};
+
 template <int BN>
 __global__ __launch_bounds__(kThreads) void igemm_nhwc(const int8_t *__restrict__ xin, const int *__restrict__ chansum,
                                                        const int8_t *__restrict__ wt, const int *__restrict__ colsum,
@@ -141,13 +186,11 @@ __global__ __launch_bounds__(kThreads) void igemm_nhwc(const int8_t *__restrict_
                                                        const int *__restrict__ tapoff,
                                                        float *__restrict__ out_f, int32_t *__restrict__ out_acc)
 {
-    constexpr int WM = BN == 128 ? 2 : 4;   // wavefronts along the rows
-    constexpr int MT = BM / WM / 16;        // 16-row MFMA tiles per wavefront
-    constexpr int NT = 4;                   // 16-column MFMA tiles per wavefront
+    constexpr int MT = q8t_gemm::Tile<BN>::MT, NT = q8t_gemm::Tile<BN>::NT;
     constexpr int NB = BN / 64;             // 16-byte filter loads per thread and step
 
-    __shared__ __align__(16) int8_t sA[2][BM * PITCH];
-    __shared__ __align__(16) int8_t sB[2][BN * PITCH];
+    __shared__ __align__(16) int8_t sA[2 * BM * PITCH];
+    __shared__ __align__(16) int8_t sB[2 * BN * PITCH];
     __shared__ int rs[BM];
     __shared__ long long roff[BM];
     __shared__ int stap[MAXT + 3];
@@ -157,7 +200,6 @@ __global__ __launch_bounds__(kThreads) void igemm_nhwc(const int8_t *__restrict_
     const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
     const int za = qpa->zero_point - (1 << (qpa->bits - 1)), zb = qpb->zero_point - (1 << (qpb->bits - 1));
     const float sc = qpa->scale * qpb->scale;
-    const uint32_t padw = (uint32_t)(za & 255) * 0x01010101u;
     const int OHW = g.OH * g.OW;
 
     if (tid < g.T) stap[tid] = tapoff[tid];
@@ -185,84 +227,47 @@ __global__ __launch_bounds__(kThreads) void igemm_nhwc(const int8_t *__restrict_
         roff[tid] = off;
     }
 
-    // staging roles
-    const int ar = tid >> 1, ah = tid & 1;   // operand: row ar, 32-byte half ah
-    const int am = m0 + ar;
-    const bool av = am < g.M;
-    int an = 0, ih0 = 0, iw0 = 0;
-    if (av) {
-        an = am / OHW;
-        const int rem = am - an * OHW;
-        const int oh = rem / g.OW;
-        ih0 = oh * g.ish;
-        iw0 = (rem - oh * g.OW) * g.isw;
+    ConvOps<NB> ops;
+    ops.xin = xin;
+    ops.wt = wt;
+    ops.stap = (const __attribute__((address_space(3))) int *)stap;
+    ops.sA = sA;
+    ops.sB = sB;
+    ops.IH = g.IH;
+    ops.IW = g.IW;
+    ops.Cp = g.Cp;
+    ops.OC = g.OC;
+    ops.CC = g.Cp >> 6;
+    ops.ar = tid >> 1;
+    ops.ah = tid & 1;
+    ops.br = NB == 2 ? tid >> 1 : tid >> 2;
+    ops.bo = NB == 2 ? (tid & 1) * 32 : (tid & 3) * 16;
+    ops.n0br = n0 + ops.br;
+    ops.padw = (uint32_t)(za & 255) * 0x01010101u;
+    ops.lt = ops.lc = 0;
+    {
+        const int am = m0 + ops.ar;
+        ops.av = am < g.M;
+        ops.an = ops.ih0 = ops.iw0 = 0;
+        if (ops.av) {
+            ops.an = am / OHW;
+            const int rem = am - ops.an * OHW;
+            const int oh = rem / g.OW;
+            ops.ih0 = oh * g.ish;
+            ops.iw0 = (rem - oh * g.OW) * g.isw;
+        }
     }
-    const int br = NB == 2 ? tid >> 1 : tid >> 2;          // filter: row br
-    const int bo = NB == 2 ? (tid & 1) * 32 : (tid & 3) * 16;
-
-    const int CC = g.Cp >> 6;
-    const int steps = g.T * CC;
-    uint4 pa0, pa1, pb0, pb1;
-    pa0 = pa1 = pb0 = pb1 = make_uint4(0, 0, 0, 0);
-    int lt = 0, lc = 0;   // tap and channel chunk of the next load
-
-    auto load = [&]() {
-        const int to = stap[lt];
-        const int ih = ih0 + (int)(int16_t)(to & 0xFFFF), iw = iw0 + (to >> 16);
-        if (av && (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW) {
-            const int8_t *p = xin + (size_t)((an * g.IH + ih) * g.IW + iw) * g.Cp + lc * 64 + ah * 32;
-            pa0 = *reinterpret_cast<const uint4 *>(p);
-            pa1 = *reinterpret_cast<const uint4 *>(p + 16);
-        } else {
-            pa0 = make_uint4(padw, padw, padw, padw);
-            pa1 = pa0;
-        }
-        const int8_t *q = wt + ((size_t)lt * g.OC + n0 + br) * g.Cp + lc * 64 + bo;
-        pb0 = *reinterpret_cast<const uint4 *>(q);
-        if (NB == 2) pb1 = *reinterpret_cast<const uint4 *>(q + 16);
-        if (++lc == CC) {
-            lc = 0;
-            ++lt;
-        }
-    };
-    auto store = [&](int buf) {
-        *reinterpret_cast<uint4 *>(&sA[buf][ar * PITCH + ah * 32]) = pa0;
-        *reinterpret_cast<uint4 *>(&sA[buf][ar * PITCH + ah * 32 + 16]) = pa1;
-        *reinterpret_cast<uint4 *>(&sB[buf][br * PITCH + bo]) = pb0;
-        if (NB == 2) *reinterpret_cast<uint4 *>(&sB[buf][br * PITCH + bo + 16]) = pb1;
-    };
 
     const int rowbase = BN == 128 ? (wave & 1) * 64 : wave * 32;
     const int colbase = BN == 128 ? (wave >> 1) * 64 : 0;
-
     v4i acc[MT][NT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (v4i){0, 0, 0, 0};
 
-    if (steps > 0) {
-        load();
-        store(0);
-    }
-    __syncthreads();
-    for (int s = 0; s < steps; ++s) {
-        const int buf = s & 1;
-        if (s + 1 < steps) load();
-        v4i bf[NT];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            bf[nt] = *reinterpret_cast<const v4i *>(&sB[buf][(colbase + nt * 16 + l16) * PITCH + kb * 16]);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const v4i a = *reinterpret_cast<const v4i *>(&sA[buf][(rowbase + mt * 16 + l16) * PITCH + kb * 16]);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bf[nt], acc[mt][nt], 0, 0, 0);
-        }
-        if (s + 1 < steps) store(buf ^ 1);
-        __syncthreads();
-    }
+    q8t_gemm::pipeline<BN>(ops, g.T * ops.CC, sA, sB, acc);
+    if (g.T == 0) __syncthreads();   // rs / roff of the other threads
 
     // ---- epilogue: zero-point correction in wrapping 32-bit arithmetic (the corrected value fits
     // by contract), dequantization; a lane holds 4 consecutive rows of one output channel ----

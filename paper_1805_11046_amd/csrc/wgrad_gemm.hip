@@ -17,10 +17,11 @@
 // length: every partial sum is an integer below 2^31 and the recombination is done in int64.
 #include "q8t_common.h"
 #include "q8t_internal.h"
+#include "gemm_core.h"
 
 namespace {
 
-typedef int v4i __attribute__((ext_vector_type(4)));
+using q8t_gemm::v4i;
 
 constexpr int kThreads = 256;
 constexpr int BM = 128;
@@ -205,99 +206,94 @@ __global__ __launch_bounds__(kThreads) void im2col_planes(const int8_t *__restri
 
 // ---- C[z][i][j] = sum over slice z of A'[i][m] * B'[j][m] ---------------------------------------
 // Also leaves the sums of the staged bytes per row (of A') and per column (row of B') and slice.
+template <int NB>
+struct NtOps {
+    const int8_t *pa, *pb;
+    int8_t *sA, *sB;
+    int ar, ao, br, bo;
+    int sa, sb;
+    __device__ __forceinline__ void load(q8t_gemm::Regs &r)
+    {
+        r.a0 = *reinterpret_cast<const uint4 *>(pa);
+        r.a1 = *reinterpret_cast<const uint4 *>(pa + 16);
+        r.b0 = *reinterpret_cast<const uint4 *>(pb);
+        if (NB == 2) r.b1 = *reinterpret_cast<const uint4 *>(pb + 16);
+        pa += 64;
+        pb += 64;
+    }
+    __device__ __forceinline__ void store(const q8t_gemm::Regs &r, int buf)
+    {
+        int8_t *a = sA + buf * BM * PITCH + ar * PITCH + ao;
+        *reinterpret_cast<uint4 *>(a) = r.a0;
+        *reinterpret_cast<uint4 *>(a + 16) = r.a1;
+        int8_t *b = sB + buf * (NB * 64) * PITCH + br * PITCH + bo;
+        *reinterpret_cast<uint4 *>(b) = r.b0;
+        if (NB == 2) *reinterpret_cast<uint4 *>(b + 16) = r.b1;
+        sa += bytesum16(r.a0) + bytesum16(r.a1);
+        sb += bytesum16(r.b0);
+        if (NB == 2) sb += bytesum16(r.b1);
+    }
+};
+
+template <int BN>
+__device__ __forceinline__ void write_partials(int32_t *__restrict__ dst, int Rbp, int r0, int c0,
+                                               const v4i (&acc)[q8t_gemm::Tile<BN>::MT][q8t_gemm::Tile<BN>::NT])
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l16 = lane & 15, kb = lane >> 4;
+    const int rowbase = BN == 128 ? (wave & 1) * 64 : wave * 32;
+    const int colbase = BN == 128 ? (wave >> 1) * 64 : 0;
+#pragma unroll
+    for (int mt = 0; mt < q8t_gemm::Tile<BN>::MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < q8t_gemm::Tile<BN>::NT; ++nt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                dst[(size_t)(r0 + rowbase + mt * 16 + kb * 4 + j) * Rbp + c0 + colbase + nt * 16 + l16] = acc[mt][nt][j];
+}
+
 template <int BN>
 __global__ __launch_bounds__(kThreads) void gemm_nt(const int8_t *__restrict__ A, const int8_t *__restrict__ B, int64_t Mp,
                                                     int slice, int Rap, int Rbp, int32_t *__restrict__ part,
                                                     int *__restrict__ rsum, int *__restrict__ csum)
 {
-    constexpr int WM = BN == 128 ? 2 : 4;
-    constexpr int MT = BM / WM / 16;
-    constexpr int NT = 4;
+    constexpr int MT = q8t_gemm::Tile<BN>::MT, NT = q8t_gemm::Tile<BN>::NT;
     constexpr int NB = BN / 64;
+    __shared__ __align__(16) int8_t sA[2 * BM * PITCH];
+    __shared__ __align__(16) int8_t sB[2 * BN * PITCH];
 
-    __shared__ __align__(16) int8_t sA[2][BM * PITCH];
-    __shared__ __align__(16) int8_t sB[2][BN * PITCH];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l16 = lane & 15, kb = lane >> 4;
+    const int tid = threadIdx.x;
     const int r0 = blockIdx.x * BM, c0 = blockIdx.y * BN, z = blockIdx.z;
     const int64_t mb = (int64_t)z * slice;
     const int64_t me = mb + slice < Mp ? mb + slice : Mp;
     const int steps = (int)((me - mb) >> 6);
 
-    const int ar = tid >> 1, ao = (tid & 1) * 32;
-    const int br = NB == 2 ? tid >> 1 : tid >> 2;
-    const int bo = NB == 2 ? (tid & 1) * 32 : (tid & 3) * 16;
-    const int8_t *pa = A + (size_t)(r0 + ar) * Mp + mb + ao;
-    const int8_t *pb = B + (size_t)(c0 + br) * Mp + mb + bo;
+    NtOps<NB> ops;
+    ops.sA = sA;
+    ops.sB = sB;
+    ops.ar = tid >> 1;
+    ops.ao = (tid & 1) * 32;
+    ops.br = NB == 2 ? tid >> 1 : tid >> 2;
+    ops.bo = NB == 2 ? (tid & 1) * 32 : (tid & 3) * 16;
+    ops.pa = A + (size_t)(r0 + ops.ar) * Mp + mb + ops.ao;
+    ops.pb = B + (size_t)(c0 + ops.br) * Mp + mb + ops.bo;
+    ops.sa = ops.sb = 0;
 
-    uint4 a0, a1, b0, b1;
-    a0 = a1 = b0 = b1 = make_uint4(0, 0, 0, 0);
-    int sa = 0, sb = 0;
-    auto load = [&]() {
-        a0 = *reinterpret_cast<const uint4 *>(pa);
-        a1 = *reinterpret_cast<const uint4 *>(pa + 16);
-        b0 = *reinterpret_cast<const uint4 *>(pb);
-        if (NB == 2) b1 = *reinterpret_cast<const uint4 *>(pb + 16);
-        pa += 64;
-        pb += 64;
-    };
-    auto store = [&](int buf) {
-        *reinterpret_cast<uint4 *>(&sA[buf][ar * PITCH + ao]) = a0;
-        *reinterpret_cast<uint4 *>(&sA[buf][ar * PITCH + ao + 16]) = a1;
-        *reinterpret_cast<uint4 *>(&sB[buf][br * PITCH + bo]) = b0;
-        if (NB == 2) *reinterpret_cast<uint4 *>(&sB[buf][br * PITCH + bo + 16]) = b1;
-        sa += bytesum16(a0) + bytesum16(a1);
-        sb += bytesum16(b0);
-        if (NB == 2) sb += bytesum16(b1);
-    };
-
-    const int rowbase = BN == 128 ? (wave & 1) * 64 : wave * 32;
-    const int colbase = BN == 128 ? (wave >> 1) * 64 : 0;
     v4i acc[MT][NT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (v4i){0, 0, 0, 0};
-
-    if (steps > 0) {
-        load();
-        store(0);
-    }
-    __syncthreads();
-    for (int s = 0; s < steps; ++s) {
-        const int buf = s & 1;
-        if (s + 1 < steps) load();
-        v4i bf[NT];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            bf[nt] = *reinterpret_cast<const v4i *>(&sB[buf][(colbase + nt * 16 + l16) * PITCH + kb * 16]);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const v4i a = *reinterpret_cast<const v4i *>(&sA[buf][(rowbase + mt * 16 + l16) * PITCH + kb * 16]);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bf[nt], acc[mt][nt], 0, 0, 0);
-        }
-        if (s + 1 < steps) store(buf ^ 1);
-        __syncthreads();
-    }
+    q8t_gemm::pipeline<BN>(ops, steps, sA, sB, acc);
 
     // byte sums of this slice: the two (or four) threads of a row hold its pieces
+    int sa = ops.sa, sb = ops.sb;
     sa += __shfl_xor(sa, 1, Q8T_WAVE);
     sb += __shfl_xor(sb, 1, Q8T_WAVE);
     if (NB == 1) sb += __shfl_xor(sb, 2, Q8T_WAVE);
-    if (blockIdx.y == 0 && (tid & 1) == 0) rsum[(size_t)z * Rap + r0 + ar] = sa;
-    if (blockIdx.x == 0 && (NB == 2 ? (tid & 1) == 0 : (tid & 3) == 0)) csum[(size_t)z * Rbp + c0 + br] = sb;
-
-    int32_t *dst = part + (size_t)z * Rap * Rbp;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                dst[(size_t)(r0 + rowbase + mt * 16 + kb * 4 + j) * Rbp + c0 + colbase + nt * 16 + l16] = acc[mt][nt][j];
+    if (blockIdx.y == 0 && (tid & 1) == 0) rsum[(size_t)z * Rap + r0 + ops.ar] = sa;
+    if (blockIdx.x == 0 && (NB == 2 ? (tid & 1) == 0 : (tid & 3) == 0)) csum[(size_t)z * Rbp + c0 + ops.br] = sb;
+    write_partials<BN>(part + (size_t)z * Rap * Rbp, Rbp, r0, c0, acc);
 }
 
 // ---- 1x1, stride 1, no padding, planes of a multiple of 64 positions ---------------------------
@@ -305,119 +301,107 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const int8_t *__restrict__ A
 // of the gradient and row c of the input are contiguous in NCHW.  The 16-bit codes are split into
 // their byte planes in registers.  A row tile holds 64 output channels: rows 0..63 the high
 // bytes, rows 64..127 the low bytes, and the slice results keep that tiled row order.
+template <int NB>
+struct DirectOps {
+    const int16_t *g16;
+    const int8_t *x;
+    int8_t *sA, *sB;
+    int K, C, PQ, cpi, k0kr, c0br, kr, kq, br, bo;
+    int n, ch;
+    int shi, slo, sb;
+    __device__ __forceinline__ void load(q8t_gemm::Regs &r)
+    {
+        const int16_t *pa = g16 + ((size_t)n * K + k0kr) * PQ + ch * 64 + kq * 16;
+        const int8_t *pb = x + ((size_t)n * C + c0br) * PQ + ch * 64 + bo;
+        r.a0 = *reinterpret_cast<const uint4 *>(pa);
+        r.a1 = *reinterpret_cast<const uint4 *>(pa + 8);
+        r.b0 = *reinterpret_cast<const uint4 *>(pb);
+        if (NB == 2) r.b1 = *reinterpret_cast<const uint4 *>(pb + 16);
+        if (++ch == cpi) {
+            ch = 0;
+            ++n;
+        }
+    }
+    __device__ __forceinline__ void store(const q8t_gemm::Regs &r, int buf)
+    {
+        uint4 hi, lo;
+        hi.x = __builtin_amdgcn_perm(r.a0.y, r.a0.x, 0x07050301u);
+        hi.y = __builtin_amdgcn_perm(r.a0.w, r.a0.z, 0x07050301u);
+        hi.z = __builtin_amdgcn_perm(r.a1.y, r.a1.x, 0x07050301u);
+        hi.w = __builtin_amdgcn_perm(r.a1.w, r.a1.z, 0x07050301u);
+        lo.x = __builtin_amdgcn_perm(r.a0.y, r.a0.x, 0x06040200u) ^ 0x80808080u;
+        lo.y = __builtin_amdgcn_perm(r.a0.w, r.a0.z, 0x06040200u) ^ 0x80808080u;
+        lo.z = __builtin_amdgcn_perm(r.a1.y, r.a1.x, 0x06040200u) ^ 0x80808080u;
+        lo.w = __builtin_amdgcn_perm(r.a1.w, r.a1.z, 0x06040200u) ^ 0x80808080u;
+        int8_t *a = sA + buf * BM * PITCH + kr * PITCH + kq * 16;
+        *reinterpret_cast<uint4 *>(a) = hi;
+        *reinterpret_cast<uint4 *>(a + 64 * PITCH) = lo;
+        int8_t *b = sB + buf * (NB * 64) * PITCH + br * PITCH + bo;
+        *reinterpret_cast<uint4 *>(b) = r.b0;
+        if (NB == 2) *reinterpret_cast<uint4 *>(b + 16) = r.b1;
+        shi += bytesum16(hi);
+        slo += bytesum16(lo);
+        sb += bytesum16(r.b0);
+        if (NB == 2) sb += bytesum16(r.b1);
+    }
+};
+
 template <int BN>
 __global__ __launch_bounds__(kThreads) void gemm_direct(const int16_t *__restrict__ g16, const int8_t *__restrict__ x, int K,
                                                         int C, int PQ, int steps_total, int steps_slice, int Rap, int Rbp,
                                                         int32_t *__restrict__ part, int *__restrict__ rsum,
                                                         int *__restrict__ csum)
 {
-    constexpr int WM = BN == 128 ? 2 : 4;
-    constexpr int MT = BM / WM / 16;
-    constexpr int NT = 4;
+    constexpr int MT = q8t_gemm::Tile<BN>::MT, NT = q8t_gemm::Tile<BN>::NT;
     constexpr int NB = BN / 64;
+    __shared__ __align__(16) int8_t sA[2 * BM * PITCH];
+    __shared__ __align__(16) int8_t sB[2 * BN * PITCH];
 
-    __shared__ __align__(16) int8_t sA[2][BM * PITCH];
-    __shared__ __align__(16) int8_t sB[2][BN * PITCH];
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l16 = lane & 15, kb = lane >> 4;
+    const int tid = threadIdx.x;
     const int k0 = blockIdx.x * 64, c0 = blockIdx.y * BN, z = blockIdx.z;
     const int r0 = blockIdx.x * BM;
     const int t0 = z * steps_slice;
     const int steps = min(steps_slice, steps_total - t0);
-    const int cpi = PQ >> 6;   // steps per image
 
-    const int kr = tid >> 2, kq = tid & 3;                 // gradient row, 16-code quarter
-    const int br = NB == 2 ? tid >> 1 : tid >> 2;
-    const int bo = NB == 2 ? (tid & 1) * 32 : (tid & 3) * 16;
-    int n = t0 / cpi, ch = t0 - n * cpi;
+    DirectOps<NB> ops;
+    ops.g16 = g16;
+    ops.x = x;
+    ops.sA = sA;
+    ops.sB = sB;
+    ops.K = K;
+    ops.C = C;
+    ops.PQ = PQ;
+    ops.cpi = PQ >> 6;   // steps per image
+    ops.kr = tid >> 2;   // gradient row, 16-code quarter
+    ops.kq = tid & 3;
+    ops.br = NB == 2 ? tid >> 1 : tid >> 2;
+    ops.bo = NB == 2 ? (tid & 1) * 32 : (tid & 3) * 16;
+    ops.k0kr = k0 + ops.kr;
+    ops.c0br = c0 + ops.br;
+    ops.n = t0 / ops.cpi;
+    ops.ch = t0 - ops.n * ops.cpi;
+    ops.shi = ops.slo = ops.sb = 0;
 
-    uint4 a0, a1, b0, b1;
-    a0 = a1 = b0 = b1 = make_uint4(0, 0, 0, 0);
-    int shi = 0, slo = 0, sb = 0;
-    auto load = [&]() {
-        const int16_t *pa = g16 + ((size_t)n * K + k0 + kr) * PQ + ch * 64 + kq * 16;
-        const int8_t *pb = x + ((size_t)n * C + c0 + br) * PQ + ch * 64 + bo;
-        a0 = *reinterpret_cast<const uint4 *>(pa);
-        a1 = *reinterpret_cast<const uint4 *>(pa + 8);
-        b0 = *reinterpret_cast<const uint4 *>(pb);
-        if (NB == 2) b1 = *reinterpret_cast<const uint4 *>(pb + 16);
-        if (++ch == cpi) {
-            ch = 0;
-            ++n;
-        }
-    };
-    auto store = [&](int buf) {
-        uint4 hi, lo;
-        hi.x = __builtin_amdgcn_perm(a0.y, a0.x, 0x07050301u);
-        hi.y = __builtin_amdgcn_perm(a0.w, a0.z, 0x07050301u);
-        hi.z = __builtin_amdgcn_perm(a1.y, a1.x, 0x07050301u);
-        hi.w = __builtin_amdgcn_perm(a1.w, a1.z, 0x07050301u);
-        lo.x = __builtin_amdgcn_perm(a0.y, a0.x, 0x06040200u) ^ 0x80808080u;
-        lo.y = __builtin_amdgcn_perm(a0.w, a0.z, 0x06040200u) ^ 0x80808080u;
-        lo.z = __builtin_amdgcn_perm(a1.y, a1.x, 0x06040200u) ^ 0x80808080u;
-        lo.w = __builtin_amdgcn_perm(a1.w, a1.z, 0x06040200u) ^ 0x80808080u;
-        *reinterpret_cast<uint4 *>(&sA[buf][kr * PITCH + kq * 16]) = hi;
-        *reinterpret_cast<uint4 *>(&sA[buf][(64 + kr) * PITCH + kq * 16]) = lo;
-        *reinterpret_cast<uint4 *>(&sB[buf][br * PITCH + bo]) = b0;
-        if (NB == 2) *reinterpret_cast<uint4 *>(&sB[buf][br * PITCH + bo + 16]) = b1;
-        shi += bytesum16(hi);
-        slo += bytesum16(lo);
-        sb += bytesum16(b0);
-        if (NB == 2) sb += bytesum16(b1);
-    };
-
-    const int rowbase = BN == 128 ? (wave & 1) * 64 : wave * 32;
-    const int colbase = BN == 128 ? (wave >> 1) * 64 : 0;
     v4i acc[MT][NT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (v4i){0, 0, 0, 0};
+    q8t_gemm::pipeline<BN>(ops, steps, sA, sB, acc);
 
-    if (steps > 0) {
-        load();
-        store(0);
-    }
-    __syncthreads();
-    for (int s = 0; s < steps; ++s) {
-        const int buf = s & 1;
-        if (s + 1 < steps) load();
-        v4i bf[NT];
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            bf[nt] = *reinterpret_cast<const v4i *>(&sB[buf][(colbase + nt * 16 + l16) * PITCH + kb * 16]);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const v4i a = *reinterpret_cast<const v4i *>(&sA[buf][(rowbase + mt * 16 + l16) * PITCH + kb * 16]);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bf[nt], acc[mt][nt], 0, 0, 0);
-        }
-        if (s + 1 < steps) store(buf ^ 1);
-        __syncthreads();
-    }
-
+    int shi = ops.shi, slo = ops.slo, sb = ops.sb;
     shi += __shfl_xor(shi, 1, Q8T_WAVE);
     shi += __shfl_xor(shi, 2, Q8T_WAVE);
     slo += __shfl_xor(slo, 1, Q8T_WAVE);
     slo += __shfl_xor(slo, 2, Q8T_WAVE);
     sb += __shfl_xor(sb, 1, Q8T_WAVE);
     if (NB == 1) sb += __shfl_xor(sb, 2, Q8T_WAVE);
-    if (blockIdx.y == 0 && kq == 0) {
-        rsum[(size_t)z * Rap + r0 + kr] = shi;
-        rsum[(size_t)z * Rap + r0 + 64 + kr] = slo;
+    if (blockIdx.y == 0 && ops.kq == 0) {
+        rsum[(size_t)z * Rap + r0 + ops.kr] = shi;
+        rsum[(size_t)z * Rap + r0 + 64 + ops.kr] = slo;
     }
-    if (blockIdx.x == 0 && (NB == 2 ? (tid & 1) == 0 : (tid & 3) == 0)) csum[(size_t)z * Rbp + c0 + br] = sb;
-
-    int32_t *dst = part + (size_t)z * Rap * Rbp;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                dst[(size_t)(r0 + rowbase + mt * 16 + kb * 4 + j) * Rbp + c0 + colbase + nt * 16 + l16] = acc[mt][nt][j];
+    if (blockIdx.x == 0 && (NB == 2 ? (tid & 1) == 0 : (tid & 3) == 0)) csum[(size_t)z * Rbp + c0 + ops.br] = sb;
+    write_partials<BN>(part + (size_t)z * Rap * Rbp, Rbp, r0, c0, acc);
 }
 
 // ---- slices -> exact 64-bit sums -> outputs ------------------------------------------------------
