@@ -9,11 +9,9 @@
 //                  zero-point correction needs.
 //  2. repack_taps  filter -> [tap][output channel][reduction channel] and the per-output-channel
 //                  sums (per stride class).
-//  3. igemm_nhwc   implicit GEMM, rows = output positions (128 per workgroup), columns = output
-//                  channels (128 or 64), K = taps x channels in steps of 64.  Global loads of step
-//                  s+1 are in flight while the MFMAs of step s run; LDS is double-buffered with one
-//                  barrier per step; rows of 64 bytes sit 80 bytes apart so that the 16-byte
-//                  operand reads of a wavefront are conflict-free.
+//  3. igemm_nhwc   implicit GEMM, rows = output positions, columns = output channels, K = taps x
+//                  channels in steps of 64, on the shared software-pipelined main loop
+//                  (gemm_core.h; 256x256, 128x128 or 128x64 tiles).
 //
 // Padded taps are staged as the stored zero point, which makes their corrected contribution
 // exactly zero; with a = stored code, za/zb = stored zero points:
@@ -32,7 +30,6 @@ namespace {
 using q8t_gemm::v4i;
 
 constexpr int kThreads = 256;
-constexpr int BM = 128;      // output positions per workgroup
 constexpr int PITCH = 80;    // LDS bytes between rows of 64
 constexpr int MAXT = 49;     // taps (7x7)
 constexpr int MAXCLS = 16;   // stride classes (stride <= 4)
@@ -134,70 +131,77 @@ __global__ __launch_bounds__(kThreads) void repack_taps(const int8_t *__restrict
 }
 
 // ---- 3. implicit GEMM ---------------------------------------------------------------------------
-// operand staging of one thread: row `ar` of the tile (one output position), 32-byte half `ah`;
-// filter row `br`, byte offset `bo`
-template <int NB>
+// Staging role of a thread (see gemm_core.h): the 16-byte channel chunk q = tid & 3 of the output
+// positions (tile rows) ar = tid >> 2 and ar + RP, and of the filter rows ar and ar + RP.
+template <class C>
 struct ConvOps {
     const int8_t *xin, *wt;
     const __attribute__((address_space(3))) int *stap;   // tap offsets, in LDS
-    int8_t *sA, *sB;
-    int IH, IW, Cp, OC, CC;
-    int an, ih0, iw0, ar, ah, n0br, bo, br;
-    bool av;
+    int IH, IW, Cp, OC, CC, q, wrow;
+    int an0, ih0, iw0, an1, ih1, iw1;   // image and top-left operand position of the two rows
+    bool av0, av1;
     uint32_t padw;
     int lt, lc;   // tap and channel chunk of the next load
 
-    __device__ __forceinline__ void load(q8t_gemm::Regs &r)
+    __device__ __forceinline__ uint4 row(bool av, int an, int ihb, int iwb, int to, int c) const
     {
-        const int to = stap[lt];
-        const int ih = ih0 + (int)(int16_t)(to & 0xFFFF), iw = iw0 + (to >> 16);
-        uint4 t0 = make_uint4(padw, padw, padw, padw), t1 = t0;
-        if (av && (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW) {
-            const int8_t *p = xin + (size_t)((an * IH + ih) * IW + iw) * Cp + lc * 64 + ah * 32;
-            t0 = *reinterpret_cast<const uint4 *>(p);
-            t1 = *reinterpret_cast<const uint4 *>(p + 16);
-        }
-        r.a0 = t0;
-        r.a1 = t1;
-        const int8_t *q = wt + ((size_t)lt * OC + n0br) * Cp + lc * 64 + bo;
-        r.b0 = *reinterpret_cast<const uint4 *>(q);
-        if (NB == 2) r.b1 = *reinterpret_cast<const uint4 *>(q + 16);
-        if (++lc == CC) {
-            lc = 0;
-            ++lt;
-        }
+        const int ih = ihb + (int)(int16_t)(to & 0xFFFF), iw = iwb + (to >> 16);
+        uint4 v = make_uint4(padw, padw, padw, padw);
+        if (av && (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW)
+            v = *reinterpret_cast<const uint4 *>(xin + (size_t)((an * IH + ih) * IW + iw) * Cp + c * 64 + q * 16);
+        return v;
     }
-    __device__ __forceinline__ void store(const q8t_gemm::Regs &r, int buf)
+    __device__ __forceinline__ void load(q8t_gemm::Regs &r, bool valid)
     {
-        int8_t *a = sA + buf * q8t_gemm::BM * PITCH + ar * PITCH + ah * 32;
-        *reinterpret_cast<uint4 *>(a) = r.a0;
-        *reinterpret_cast<uint4 *>(a + 16) = r.a1;
-        int8_t *b = sB + buf * (NB * 64) * PITCH + br * PITCH + bo;
-        *reinterpret_cast<uint4 *>(b) = r.b0;
-        if (NB == 2) *reinterpret_cast<uint4 *>(b + 16) = r.b1;
+        const int t = valid ? lt : 0, c = valid ? lc : 0;
+        const int to = stap[t];
+        r.a0 = row(av0, an0, ih0, iw0, to, c);
+        r.a1 = row(av1, an1, ih1, iw1, to, c);
+        const int8_t *w = wt + ((size_t)t * OC + wrow) * Cp + c * 64 + q * 16;
+        r.b0 = *reinterpret_cast<const uint4 *>(w);
+        r.b1 = C::NB == 2 ? *reinterpret_cast<const uint4 *>(w + (size_t)C::RP * Cp) : r.b0;
+        const bool wrap = lc + 1 == CC;
+        lc = wrap ? 0 : lc + 1;
+        lt += wrap ? 1 : 0;
+    }
+    // a surplus step stages zero filter rows: whatever the operand rows hold, it adds nothing
+    __device__ __forceinline__ void prepare(q8t_gemm::Regs &r, bool valid)
+    {
+        r.b0 = q8t_gemm::sel16(valid, r.b0);
+        r.b1 = q8t_gemm::sel16(valid, r.b1);
     }
 };
 
-template <int BN>
-__global__ __launch_bounds__(kThreads) void igemm_nhwc(const int8_t *__restrict__ xin, const int *__restrict__ chansum,
-                                                       const int8_t *__restrict__ wt, const int *__restrict__ colsum,
-                                                       const q8t_qparams *__restrict__ qpa,
-                                                       const q8t_qparams *__restrict__ qpb, Geo g,
-                                                       const int *__restrict__ tapoff,
-                                                       float *__restrict__ out_f, int32_t *__restrict__ out_acc)
+template <class C>
+constexpr size_t conv_lds_bytes()
 {
-    constexpr int MT = q8t_gemm::Tile<BN>::MT, NT = q8t_gemm::Tile<BN>::NT;
-    constexpr int NB = BN / 64;             // 16-byte filter loads per thread and step
+    return (size_t)C::LDS_BYTES + C::BM * (sizeof(long long) + sizeof(int)) + (MAXT + 3) * sizeof(int);
+}
 
-    __shared__ __align__(16) int8_t sA[2 * BM * PITCH];
-    __shared__ __align__(16) int8_t sB[2 * BN * PITCH];
-    __shared__ int rs[BM];
-    __shared__ long long roff[BM];
-    __shared__ int stap[MAXT + 3];
+template <class C>
+__global__ __launch_bounds__(C::THREADS, C::MINB) void igemm_nhwc(const int8_t *__restrict__ xin,
+                                                                   const int *__restrict__ chansum,
+                                                                   const int8_t *__restrict__ wt,
+                                                                   const int *__restrict__ colsum,
+                                                                   const q8t_qparams *__restrict__ qpa,
+                                                                   const q8t_qparams *__restrict__ qpb, Geo g,
+                                                                   const int *__restrict__ tapoff,
+                                                                   float *__restrict__ out_f, int32_t *__restrict__ out_acc)
+{
+    constexpr int MT = C::MT, NT = C::NT, BM = C::BM, BN = C::BN;
+    extern __shared__ __align__(16) int8_t smem[];
+    int8_t *sA = smem, *sB = smem + 2 * BM * 64;
+    long long *roff = reinterpret_cast<long long *>(smem + C::LDS_BYTES);
+    int *rs = reinterpret_cast<int *>(roff + BM);
+    int *stap = rs + BM;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, kb = lane >> 4;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    // logical tile order: output-channel tiles fastest (they share the operand rows)
+    const int ny = g.OC / BN, total = ((g.M + BM - 1) / BM) * ny;
+    const int lg = q8t_gemm::xcd_logical(blockIdx.x, total);
+    if (lg >= total) return;
+    const int m0 = (lg / ny) * BM, n0 = (lg % ny) * BN;
     const int za = qpa->zero_point - (1 << (qpa->bits - 1)), zb = qpb->zero_point - (1 << (qpb->bits - 1));
     const float sc = qpa->scale * qpb->scale;
     const int OHW = g.OH * g.OW;
@@ -227,46 +231,50 @@ __global__ __launch_bounds__(kThreads) void igemm_nhwc(const int8_t *__restrict_
         roff[tid] = off;
     }
 
-    ConvOps<NB> ops;
+    ConvOps<C> ops;
     ops.xin = xin;
     ops.wt = wt;
     ops.stap = (const __attribute__((address_space(3))) int *)stap;
-    ops.sA = sA;
-    ops.sB = sB;
     ops.IH = g.IH;
     ops.IW = g.IW;
     ops.Cp = g.Cp;
     ops.OC = g.OC;
     ops.CC = g.Cp >> 6;
-    ops.ar = tid >> 1;
-    ops.ah = tid & 1;
-    ops.br = NB == 2 ? tid >> 1 : tid >> 2;
-    ops.bo = NB == 2 ? (tid & 1) * 32 : (tid & 3) * 16;
-    ops.n0br = n0 + ops.br;
+    ops.q = tid & 3;
+    ops.wrow = n0 + (tid >> 2);
     ops.padw = (uint32_t)(za & 255) * 0x01010101u;
     ops.lt = ops.lc = 0;
     {
-        const int am = m0 + ops.ar;
-        ops.av = am < g.M;
-        ops.an = ops.ih0 = ops.iw0 = 0;
-        if (ops.av) {
-            ops.an = am / OHW;
-            const int rem = am - ops.an * OHW;
+        const int am = m0 + (tid >> 2);
+        ops.av0 = am < g.M;
+        ops.an0 = ops.ih0 = ops.iw0 = 0;
+        if (ops.av0) {
+            ops.an0 = am / OHW;
+            const int rem = am - ops.an0 * OHW;
             const int oh = rem / g.OW;
             ops.ih0 = oh * g.ish;
             ops.iw0 = (rem - oh * g.OW) * g.isw;
         }
+        const int bm = am + C::RP;
+        ops.av1 = bm < g.M;
+        ops.an1 = ops.ih1 = ops.iw1 = 0;
+        if (ops.av1) {
+            ops.an1 = bm / OHW;
+            const int rem = bm - ops.an1 * OHW;
+            const int oh = rem / g.OW;
+            ops.ih1 = oh * g.ish;
+            ops.iw1 = (rem - oh * g.OW) * g.isw;
+        }
     }
 
-    const int rowbase = BN == 128 ? (wave & 1) * 64 : wave * 32;
-    const int colbase = BN == 128 ? (wave >> 1) * 64 : 0;
+    const int rowbase = C::rowbase(wave), colbase = C::colbase(wave);
     v4i acc[MT][NT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (v4i){0, 0, 0, 0};
 
-    q8t_gemm::pipeline<BN>(ops, g.T * ops.CC, sA, sB, acc);
+    q8t_gemm::pipeline<C>(ops, g.T * ops.CC, sA, sB, acc);
     if (g.T == 0) __syncthreads();   // rs / roff of the other threads
 
     // ---- epilogue: zero-point correction in wrapping 32-bit arithmetic (the corrected value fits
@@ -455,13 +463,25 @@ int q8t_nhwc_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
         g.vec = q8t_aligned(out_f, 16) && q8t_aligned(out_acc, 16);
         const int8_t *wz = wt + (size_t)co.off[z] * p.oc * p.red;
         const int *cz = colsum + (size_t)z * p.oc;
-        const unsigned mt = (unsigned)((g.M + BM - 1) / BM);
-        if (p.oc % 128 == 0)
-            hipLaunchKernelGGL(igemm_nhwc<128>, dim3(mt, (unsigned)(p.oc / 128)), dim3(kThreads), 0, st, xn, chansum,
-                               wz, cz, qa, qb, g, tapoff + co.off[z], out_f, (int32_t *)out_acc);
-        else
-            hipLaunchKernelGGL(igemm_nhwc<64>, dim3(mt, (unsigned)(p.oc / 64)), dim3(kThreads), 0, st, xn, chansum, wz,
-                               cz, qa, qb, g, tapoff + co.off[z], out_f, (int32_t *)out_acc);
+        // tile: 256 x 256 where the output channels allow it and the launch still fills the chip,
+        // else 128 x 128, else 128 x 64
+#define Q8T_GO(CFG)                                                                                                  \
+    {                                                                                                                \
+        static bool attr = false;                                                                                    \
+        if (!attr && conv_lds_bytes<CFG>() > 65536) {                                                                \
+            if (hipFuncSetAttribute((const void *)igemm_nhwc<CFG>, hipFuncAttributeMaxDynamicSharedMemorySize,       \
+                                    (int)conv_lds_bytes<CFG>()) != hipSuccess)                                       \
+                return Q8T_ERR_HIP;                                                                                  \
+            attr = true;                                                                                             \
+        }                                                                                                            \
+        const int64_t tiles = (int64_t)((g.M + CFG::BM - 1) / CFG::BM) * (p.oc / CFG::BN);                           \
+        hipLaunchKernelGGL(igemm_nhwc<CFG>, dim3(q8t_gemm::xcd_grid(tiles)), dim3(CFG::THREADS), conv_lds_bytes<CFG>(), \
+                           st, xn, chansum, wz, cz, qa, qb, g, tapoff + co.off[z], out_f, (int32_t *)out_acc);       \
+    }
+        if (p.oc % 256 == 0 && (int64_t)((g.M + 255) / 256) * (p.oc / 256) >= 128) Q8T_GO(q8t_gemm::Big)
+        else if (p.oc % 128 == 0) Q8T_GO(q8t_gemm::Mid)
+        else Q8T_GO(q8t_gemm::Small)
+#undef Q8T_GO
         Q8T_LAUNCH_CHECK();
     }
     return Q8T_OK;

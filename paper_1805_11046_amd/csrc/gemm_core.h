@@ -1,83 +1,149 @@
 // Shared main loop of the int8 MFMA GEMM kernels (conv_nhwc.hip, wgrad_gemm.hip).
 //
-// Workgroup tile 128 x BN (BN = 128 or 64), K-step 64, 4 wavefronts.  Operand rows of 64 bytes
-// sit 80 bytes apart in LDS (conflict-free 16-byte reads).  LDS is double-buffered with one
-// barrier per step; global loads run three steps ahead through three named register sets, so
-// that a wavefront waits only for the oldest of the loads it has in flight.
+// Three tile configurations (rows x columns of the workgroup tile, K-step 64):
+//   Big    256 x 256, 8 wavefronts of 128 x 64   (one workgroup per compute unit)
+//   Mid    128 x 128, 4 wavefronts of  64 x 64   (three workgroups per compute unit)
+//   Small  128 x  64, 4 wavefronts of  32 x 64
+// Per K-step a wavefront of the Big tile reads 12 operand fragments from LDS for 32 MFMAs, of the
+// Mid tile 8 for 16: the Big tile halves the LDS and global traffic per MFMA and is what the
+// MFMA-bound shapes use.
+//
+// LDS holds rows of 64 bytes without padding; the 16-byte chunk q of row r sits at chunk
+// q ^ swz(r), which keeps both the row-wise staging stores and the column-wise fragment reads
+// spread over the banks.  LDS is double-buffered with one barrier per step.  The barrier orders
+// LDS traffic only (q8t_lds_barrier), so the global loads of the next steps stay in flight across
+// it: two named register sets hold the tiles of steps s+1 and s+2 while step s is multiplied.
+// The loop body is straight-line code (no branch around a load or a store), which lets the
+// compiler's wait-count bookkeeping keep the younger loads in flight; the step count is rounded
+// up to an even number and the surplus step multiplies staged zeros.
 //
 // The kernel supplies an `Ops` object:
-//   void load(Regs &r)                  issue the global loads of the next K-step into r
-//   void store(const Regs &r, int buf)  write r into LDS buffer buf (and keep byte sums if wanted)
+//   void load(Regs &r, bool valid)     issue the global loads of the next K-step: a0 / a1 = chunk q of
+//                                      tile rows ar and ar + RP, b0 / b1 likewise for the columns
+//                                      (valid == false: any readable address, no advance)
+//   void prepare(Regs &r, bool valid)  called right before the registers go to LDS: transform them
+//                                      in place (byte-plane split, byte sums); with !valid the B
+//                                      registers must become zero (and A too if sums are kept)
+// with ar = tid >> 2, q = tid & 3, RP = threads / 4.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include "q8t_common.h"
 
 namespace q8t_gemm {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int BM = 128;
-constexpr int PITCH = 80;
+// Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by linear index.  The
+// kernels are launched on a 1-D grid of 8*ceil(total/8) workgroups and run logical tile
+// xcd_logical(blockIdx.x, total): consecutive logical tiles, which share an operand tile, then
+// execute back to back on one XCD and find it in that XCD's L2.  A result >= total means "exit".
+__device__ __forceinline__ int xcd_logical(int linear, int total)
+{
+    const int per = (total + 7) >> 3;
+    return (linear & 7) * per + (linear >> 3);
+}
+inline unsigned xcd_grid(int64_t total) { return (unsigned)(((total + 7) >> 3) << 3); }
 
 struct Regs {
     uint4 a0, a1, b0, b1;
 };
 
-template <int BN>
-struct Tile {
-    static constexpr int WM = BN == 128 ? 2 : 4;   // wavefronts along the rows
-    static constexpr int MT = BM / WM / 16;        // 16-row MFMA tiles per wavefront
-    static constexpr int NT = 4;                   // 16-column MFMA tiles per wavefront
-};
-
-template <int BN>
-__device__ __forceinline__ void compute_step(const int8_t *__restrict__ sa, const int8_t *__restrict__ sb, int rowbase,
-                                             int colbase, int l16, int kb, v4i (&acc)[Tile<BN>::MT][Tile<BN>::NT])
+__device__ __forceinline__ uint4 sel16(bool c, const uint4 &v)
 {
-    constexpr int MT = Tile<BN>::MT, NT = Tile<BN>::NT;
-    v4i bf[NT];
+    return make_uint4(c ? v.x : 0u, c ? v.y : 0u, c ? v.z : 0u, c ? v.w : 0u);
+}
+
+// chunk permutation of an LDS row; depends on bits 1..4 of the row only, so rows 64 or 128 apart
+// share it
+__device__ __forceinline__ int swz(int r) { return ((r >> 1) ^ (r >> 3)) & 3; }
+
+template <int BM_, int BN_>
+struct Cfg {
+    static constexpr int BM = BM_, BN = BN_;
+    static constexpr int THREADS = BM == 256 ? 512 : 256;
+    static constexpr int RP = THREADS / 4;                      // rows staged per pass
+    static constexpr int MT = BM == 256 ? 8 : (BN == 128 ? 4 : 2);
+    static constexpr int NT = 4;
+    static constexpr int NB = BN / RP;                          // column passes (1 or 2)
+    static constexpr int LDS_BYTES = 2 * (BM + BN) * 64;
+    static constexpr int MINB = BM == 256 ? 1 : 3;              // workgroups per compute unit aimed at
+    __device__ static __forceinline__ int rowbase(int wave)
+    {
+        return BM == 256 ? (wave & 1) * 128 : (BN == 128 ? (wave & 1) * 64 : wave * 32);
+    }
+    __device__ static __forceinline__ int colbase(int wave) { return BN == 64 ? 0 : (wave >> 1) * 64; }
+};
+typedef Cfg<256, 256> Big;
+typedef Cfg<128, 128> Mid;
+typedef Cfg<128, 64> Small;
+
+template <class C>
+__device__ __forceinline__ void compute_step(const int8_t *__restrict__ sa, const int8_t *__restrict__ sb, int rowbase,
+                                             int colbase, int l16, int kb, v4i (&acc)[C::MT][C::NT])
+{
+    v4i bf[C::NT];
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-        bf[nt] = *reinterpret_cast<const v4i *>(sb + (colbase + nt * 16 + l16) * PITCH + kb * 16);
+    for (int nt = 0; nt < C::NT; ++nt) {
+        const int row = colbase + nt * 16 + l16;
+        bf[nt] = *reinterpret_cast<const v4i *>(sb + row * 64 + ((kb ^ swz(row)) * 16));
+    }
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const v4i a = *reinterpret_cast<const v4i *>(sa + (rowbase + mt * 16 + l16) * PITCH + kb * 16);
+    for (int mt = 0; mt < C::MT; ++mt) {
+        const int row = rowbase + mt * 16 + l16;
+        const v4i af = *reinterpret_cast<const v4i *>(sa + row * 64 + ((kb ^ swz(row)) * 16));
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-            acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bf[nt], acc[mt][nt], 0, 0, 0);
+        for (int nt = 0; nt < C::NT; ++nt)
+            acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af, bf[nt], acc[mt][nt], 0, 0, 0);
     }
 }
 
-// sA: 2 * BM * PITCH bytes, sB: 2 * BN * PITCH bytes
-template <int BN, class Ops>
+// sA: 2 * BM * 64 bytes, sB: 2 * BN * 64 bytes
+template <class C, class Ops>
 __device__ __forceinline__ void pipeline(Ops &ops, int steps, int8_t *__restrict__ sA, int8_t *__restrict__ sB,
-                                         v4i (&acc)[Tile<BN>::MT][Tile<BN>::NT])
+                                         v4i (&acc)[C::MT][C::NT])
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, kb = lane >> 4;
-    const int rowbase = BN == 128 ? (wave & 1) * 64 : wave * 32;
-    const int colbase = BN == 128 ? (wave >> 1) * 64 : 0;
-    Regs r0, r1, r2;
-    r0.a0 = r0.a1 = r0.b0 = r0.b1 = make_uint4(0, 0, 0, 0);
-    r1 = r0;
-    r2 = r0;
-    if (steps > 0) ops.load(r0);
-    if (steps > 1) ops.load(r1);
-    if (steps > 2) ops.load(r2);
-#define Q8T_GEMM_STEP(R, S)                                                          \
-    {                                                                                \
-        const int buf = (S)&1;                                                       \
-        ops.store(R, buf);                                                           \
-        if ((S) + 3 < steps) ops.load(R);                                            \
-        __syncthreads();                                                             \
-        compute_step<BN>(sA + buf * BM * PITCH, sB + buf * BN * PITCH, rowbase, colbase, l16, kb, acc); \
+    const int rowbase = C::rowbase(wave), colbase = C::colbase(wave);
+    const int ar = tid >> 2;
+    const int so = ar * 64 + (((tid & 3) ^ swz(ar)) * 16);   // LDS offset of the thread's chunk in row ar
+    if (steps <= 0) return;
+    Regs q0, q1;
+    q0.a0 = q0.a1 = q0.b0 = q0.b1 = make_uint4(0, 0, 0, 0);
+    q1 = q0;
+#define Q8T_GEMM_STORE(R, BUF, VALID)                                                   \
+    {                                                                                   \
+        Regs t_ = R;                                                                    \
+        ops.prepare(t_, VALID);                                                         \
+        int8_t *a_ = sA + (BUF)*C::BM * 64 + so, *b_ = sB + (BUF)*C::BN * 64 + so;      \
+        *reinterpret_cast<uint4 *>(a_) = t_.a0;                                         \
+        *reinterpret_cast<uint4 *>(a_ + C::RP * 64) = t_.a1;                            \
+        *reinterpret_cast<uint4 *>(b_) = t_.b0;                                         \
+        if (C::NB == 2) *reinterpret_cast<uint4 *>(b_ + C::RP * 64) = t_.b1;            \
     }
-    for (int s = 0; s < steps; s += 3) {
-        Q8T_GEMM_STEP(r0, s)
-        if (s + 1 < steps) Q8T_GEMM_STEP(r1, s + 1)
-        if (s + 2 < steps) Q8T_GEMM_STEP(r2, s + 2)
+    // one step: MFMAs on buffer S&1 while tile S+1 goes from registers to the other buffer and the
+    // loads of tile S+3 are issued; everything between two barriers is one scheduling region
+#define Q8T_GEMM_STEP(R, S)                                                             \
+    {                                                                                   \
+        const int buf = (S)&1;                                                          \
+        compute_step<C>(sA + buf * C::BM * 64, sB + buf * C::BN * 64, rowbase, colbase, l16, kb, acc); \
+        Q8T_GEMM_STORE(R, buf ^ 1, (S) + 1 < steps)                                     \
+        ops.load(R, (S) + 3 < steps);                                                   \
+        q8t_lds_barrier();                                                              \
+    }
+    ops.load(q0, true);
+    ops.load(q1, 1 < steps);
+    Q8T_GEMM_STORE(q0, 0, true)
+    ops.load(q0, 2 < steps);
+    q8t_lds_barrier();
+    for (int s = 0; s < steps; s += 2) {
+        Q8T_GEMM_STEP(q1, s)
+        Q8T_GEMM_STEP(q0, s + 1)
     }
 #undef Q8T_GEMM_STEP
+#undef Q8T_GEMM_STORE
 }
 
 }  // namespace q8t_gemm

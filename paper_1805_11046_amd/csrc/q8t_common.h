@@ -14,6 +14,17 @@
 
 static inline bool q8t_aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every global load
+// in flight (s_waitcnt vmcnt(0)), which serialises a software pipeline that prefetches the next
+// tiles into registers; here the wavefront waits for its LDS operations, and the registers that
+// global loads are still filling are guarded by the compiler's own wait counts at their first use.
+__device__ __forceinline__ void q8t_lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // ---- wavefront (64 lanes) and workgroup reductions ------------------------------------------
 template <typename T, typename Op>
 __device__ __forceinline__ T wave_reduce(T v, Op op)

@@ -25,7 +25,6 @@ using q8t_gemm::v4i;
 
 constexpr int kThreads = 256;
 constexpr int BM = 128;
-constexpr int PITCH = 80;
 constexpr int kMaxSlice = 65536;
 
 __device__ __forceinline__ int bytesum4(uint32_t v) { return __builtin_amdgcn_sdot4((int)v, 0x01010101, 0, false); }
@@ -206,123 +205,130 @@ __global__ __launch_bounds__(kThreads) void im2col_planes(const int8_t *__restri
 
 // ---- C[z][i][j] = sum over slice z of A'[i][m] * B'[j][m] ---------------------------------------
 // Also leaves the sums of the staged bytes per row (of A') and per column (row of B') and slice.
-template <int NB>
+// Staging role of a thread (see gemm_core.h): chunk q = tid & 3 of tile rows ar = tid >> 2 and ar + RP.
+template <class C>
 struct NtOps {
-    const int8_t *pa, *pb;
-    int8_t *sA, *sB;
-    int ar, ao, br, bo;
-    int sa, sb;
-    __device__ __forceinline__ void load(q8t_gemm::Regs &r)
+    const int8_t *pa, *pb, *pa0, *pb0;   // next chunk; first chunk (always readable)
+    size_t skip;                         // RP rows further
+    int sa0, sa1, sb0, sb1;
+    __device__ __forceinline__ void load(q8t_gemm::Regs &r, bool valid)
     {
-        r.a0 = *reinterpret_cast<const uint4 *>(pa);
-        r.a1 = *reinterpret_cast<const uint4 *>(pa + 16);
-        r.b0 = *reinterpret_cast<const uint4 *>(pb);
-        if (NB == 2) r.b1 = *reinterpret_cast<const uint4 *>(pb + 16);
+        const int8_t *qa = valid ? pa : pa0, *qb = valid ? pb : pb0;
+        r.a0 = *reinterpret_cast<const uint4 *>(qa);
+        r.a1 = *reinterpret_cast<const uint4 *>(qa + skip);
+        r.b0 = *reinterpret_cast<const uint4 *>(qb);
+        r.b1 = C::NB == 2 ? *reinterpret_cast<const uint4 *>(qb + skip) : r.b0;
         pa += 64;
         pb += 64;
     }
-    __device__ __forceinline__ void store(const q8t_gemm::Regs &r, int buf)
+    __device__ __forceinline__ void prepare(q8t_gemm::Regs &r, bool valid)
     {
-        int8_t *a = sA + buf * BM * PITCH + ar * PITCH + ao;
-        *reinterpret_cast<uint4 *>(a) = r.a0;
-        *reinterpret_cast<uint4 *>(a + 16) = r.a1;
-        int8_t *b = sB + buf * (NB * 64) * PITCH + br * PITCH + bo;
-        *reinterpret_cast<uint4 *>(b) = r.b0;
-        if (NB == 2) *reinterpret_cast<uint4 *>(b + 16) = r.b1;
-        sa += bytesum16(r.a0) + bytesum16(r.a1);
-        sb += bytesum16(r.b0);
-        if (NB == 2) sb += bytesum16(r.b1);
+        r.a0 = q8t_gemm::sel16(valid, r.a0);
+        r.a1 = q8t_gemm::sel16(valid, r.a1);
+        r.b0 = q8t_gemm::sel16(valid, r.b0);
+        r.b1 = q8t_gemm::sel16(valid, r.b1);
+        sa0 += bytesum16(r.a0);
+        sa1 += bytesum16(r.a1);
+        sb0 += bytesum16(r.b0);
+        if (C::NB == 2) sb1 += bytesum16(r.b1);
     }
 };
 
-template <int BN>
+__device__ __forceinline__ int quad_sum(int v)
+{
+    v += __shfl_xor(v, 1, Q8T_WAVE);
+    v += __shfl_xor(v, 2, Q8T_WAVE);
+    return v;
+}
+
+template <class C>
 __device__ __forceinline__ void write_partials(int32_t *__restrict__ dst, int Rbp, int r0, int c0,
-                                               const v4i (&acc)[q8t_gemm::Tile<BN>::MT][q8t_gemm::Tile<BN>::NT])
+                                               const v4i (&acc)[C::MT][C::NT])
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, kb = lane >> 4;
-    const int rowbase = BN == 128 ? (wave & 1) * 64 : wave * 32;
-    const int colbase = BN == 128 ? (wave >> 1) * 64 : 0;
+    const int rowbase = C::rowbase(wave), colbase = C::colbase(wave);
 #pragma unroll
-    for (int mt = 0; mt < q8t_gemm::Tile<BN>::MT; ++mt)
+    for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < q8t_gemm::Tile<BN>::NT; ++nt)
+        for (int nt = 0; nt < C::NT; ++nt)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 dst[(size_t)(r0 + rowbase + mt * 16 + kb * 4 + j) * Rbp + c0 + colbase + nt * 16 + l16] = acc[mt][nt][j];
 }
 
-template <int BN>
-__global__ __launch_bounds__(kThreads) void gemm_nt(const int8_t *__restrict__ A, const int8_t *__restrict__ B, int64_t Mp,
-                                                    int slice, int Rap, int Rbp, int32_t *__restrict__ part,
-                                                    int *__restrict__ rsum, int *__restrict__ csum)
+template <class C>
+__global__ __launch_bounds__(C::THREADS, C::MINB) void gemm_nt(const int8_t *__restrict__ A, const int8_t *__restrict__ B,
+                                                                int64_t Mp, int slice, int Rap, int Rbp, int nz,
+                                                                int32_t *__restrict__ part, int *__restrict__ rsum,
+                                                                int *__restrict__ csum)
 {
-    constexpr int MT = q8t_gemm::Tile<BN>::MT, NT = q8t_gemm::Tile<BN>::NT;
-    constexpr int NB = BN / 64;
-    __shared__ __align__(16) int8_t sA[2 * BM * PITCH];
-    __shared__ __align__(16) int8_t sB[2 * BN * PITCH];
+    __shared__ __align__(16) int8_t sA[2 * C::BM * 64];
+    __shared__ __align__(16) int8_t sB[2 * C::BN * 64];
 
-    const int tid = threadIdx.x;
-    const int r0 = blockIdx.x * BM, c0 = blockIdx.y * BN, z = blockIdx.z;
+    // logical tile order: row tiles fastest (they share the B' tile), then column tiles (same A' slice)
+    const int nx = Rap / C::BM, ny = Rbp / C::BN;
+    const int lg = q8t_gemm::xcd_logical(blockIdx.x, nx * ny * nz);
+    if (lg >= nx * ny * nz) return;
+    const int bx = lg % nx, by = (lg / nx) % ny, z = lg / (nx * ny);
+    const int tid = threadIdx.x, ar = tid >> 2, q = tid & 3;
+    const int r0 = bx * C::BM, c0 = by * C::BN;
     const int64_t mb = (int64_t)z * slice;
     const int64_t me = mb + slice < Mp ? mb + slice : Mp;
     const int steps = (int)((me - mb) >> 6);
 
-    NtOps<NB> ops;
-    ops.sA = sA;
-    ops.sB = sB;
-    ops.ar = tid >> 1;
-    ops.ao = (tid & 1) * 32;
-    ops.br = NB == 2 ? tid >> 1 : tid >> 2;
-    ops.bo = NB == 2 ? (tid & 1) * 32 : (tid & 3) * 16;
-    ops.pa = A + (size_t)(r0 + ops.ar) * Mp + mb + ops.ao;
-    ops.pb = B + (size_t)(c0 + ops.br) * Mp + mb + ops.bo;
-    ops.sa = ops.sb = 0;
+    NtOps<C> ops;
+    ops.pa = ops.pa0 = A + (size_t)(r0 + ar) * Mp + mb + q * 16;
+    ops.pb = ops.pb0 = B + (size_t)(c0 + ar) * Mp + mb + q * 16;
+    ops.skip = (size_t)C::RP * Mp;
+    ops.sa0 = ops.sa1 = ops.sb0 = ops.sb1 = 0;
 
-    v4i acc[MT][NT];
+    v4i acc[C::MT][C::NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (v4i){0, 0, 0, 0};
-    q8t_gemm::pipeline<BN>(ops, steps, sA, sB, acc);
+        for (int nt = 0; nt < C::NT; ++nt) acc[mt][nt] = (v4i){0, 0, 0, 0};
+    q8t_gemm::pipeline<C>(ops, steps, sA, sB, acc);
 
-    // byte sums of this slice: the two (or four) threads of a row hold its pieces
-    int sa = ops.sa, sb = ops.sb;
-    sa += __shfl_xor(sa, 1, Q8T_WAVE);
-    sb += __shfl_xor(sb, 1, Q8T_WAVE);
-    if (NB == 1) sb += __shfl_xor(sb, 2, Q8T_WAVE);
-    if (blockIdx.y == 0 && (tid & 1) == 0) rsum[(size_t)z * Rap + r0 + ops.ar] = sa;
-    if (blockIdx.x == 0 && (NB == 2 ? (tid & 1) == 0 : (tid & 3) == 0)) csum[(size_t)z * Rbp + c0 + ops.br] = sb;
-    write_partials<BN>(part + (size_t)z * Rap * Rbp, Rbp, r0, c0, acc);
+    // byte sums of this slice: the four threads of a row hold its pieces
+    const int sa0 = quad_sum(ops.sa0), sa1 = quad_sum(ops.sa1), sb0 = quad_sum(ops.sb0), sb1 = quad_sum(ops.sb1);
+    if (by == 0 && q == 0) {
+        rsum[(size_t)z * Rap + r0 + ar] = sa0;
+        rsum[(size_t)z * Rap + r0 + ar + C::RP] = sa1;
+    }
+    if (bx == 0 && q == 0) {
+        csum[(size_t)z * Rbp + c0 + ar] = sb0;
+        if (C::NB == 2) csum[(size_t)z * Rbp + c0 + ar + C::RP] = sb1;
+    }
+    write_partials<C>(part + (size_t)z * Rap * Rbp, Rbp, r0, c0, acc);
 }
 
 // ---- 1x1, stride 1, no padding, planes of a multiple of 64 positions ---------------------------
 // Both operands are read in place: a step is 64 consecutive positions of one image, where row k
 // of the gradient and row c of the input are contiguous in NCHW.  The 16-bit codes are split into
-// their byte planes in registers.  A row tile holds 64 output channels: rows 0..63 the high
-// bytes, rows 64..127 the low bytes, and the slice results keep that tiled row order.
-template <int NB>
+// their byte planes in registers.  A row tile holds RP output channels: its first RP rows are the
+// high bytes, the next RP rows the low bytes, and the slice results keep that tiled row order.
+template <class C>
 struct DirectOps {
     const int16_t *g16;
     const int8_t *x;
-    int8_t *sA, *sB;
-    int K, C, PQ, cpi, k0kr, c0br, kr, kq, br, bo;
-    int n, ch;
-    int shi, slo, sb;
-    __device__ __forceinline__ void load(q8t_gemm::Regs &r)
+    int K, Cin, PQ, cpi, krow, crow, q;
+    int n, ch, n_first, ch_first;
+    int shi, slo, sb0, sb1;
+    __device__ __forceinline__ void load(q8t_gemm::Regs &r, bool valid)
     {
-        const int16_t *pa = g16 + ((size_t)n * K + k0kr) * PQ + ch * 64 + kq * 16;
-        const int8_t *pb = x + ((size_t)n * C + c0br) * PQ + ch * 64 + bo;
+        const int nn = valid ? n : n_first, cc = valid ? ch : ch_first;
+        const int16_t *pa = g16 + ((size_t)nn * K + krow) * PQ + cc * 64 + q * 16;
+        const int8_t *pb = x + ((size_t)nn * Cin + crow) * PQ + cc * 64 + q * 16;
         r.a0 = *reinterpret_cast<const uint4 *>(pa);
         r.a1 = *reinterpret_cast<const uint4 *>(pa + 8);
         r.b0 = *reinterpret_cast<const uint4 *>(pb);
-        if (NB == 2) r.b1 = *reinterpret_cast<const uint4 *>(pb + 16);
-        if (++ch == cpi) {
-            ch = 0;
-            ++n;
-        }
+        r.b1 = C::NB == 2 ? *reinterpret_cast<const uint4 *>(pb + (size_t)C::RP * PQ) : r.b0;
+        const bool wrap = ch + 1 == cpi;
+        ch = wrap ? 0 : ch + 1;
+        n += wrap ? 1 : 0;
     }
-    __device__ __forceinline__ void store(const q8t_gemm::Regs &r, int buf)
+    __device__ __forceinline__ void prepare(q8t_gemm::Regs &r, bool valid)
     {
         uint4 hi, lo;
         hi.x = __builtin_amdgcn_perm(r.a0.y, r.a0.x, 0x07050301u);
@@ -333,75 +339,66 @@ struct DirectOps {
         lo.y = __builtin_amdgcn_perm(r.a0.w, r.a0.z, 0x06040200u) ^ 0x80808080u;
         lo.z = __builtin_amdgcn_perm(r.a1.y, r.a1.x, 0x06040200u) ^ 0x80808080u;
         lo.w = __builtin_amdgcn_perm(r.a1.w, r.a1.z, 0x06040200u) ^ 0x80808080u;
-        int8_t *a = sA + buf * BM * PITCH + kr * PITCH + kq * 16;
-        *reinterpret_cast<uint4 *>(a) = hi;
-        *reinterpret_cast<uint4 *>(a + 64 * PITCH) = lo;
-        int8_t *b = sB + buf * (NB * 64) * PITCH + br * PITCH + bo;
-        *reinterpret_cast<uint4 *>(b) = r.b0;
-        if (NB == 2) *reinterpret_cast<uint4 *>(b + 16) = r.b1;
-        shi += bytesum16(hi);
-        slo += bytesum16(lo);
-        sb += bytesum16(r.b0);
-        if (NB == 2) sb += bytesum16(r.b1);
+        r.a0 = q8t_gemm::sel16(valid, hi);   // a surplus step stages zeros in every plane
+        r.a1 = q8t_gemm::sel16(valid, lo);
+        r.b0 = q8t_gemm::sel16(valid, r.b0);
+        r.b1 = q8t_gemm::sel16(valid, r.b1);
+        shi += bytesum16(r.a0);
+        slo += bytesum16(r.a1);
+        sb0 += bytesum16(r.b0);
+        if (C::NB == 2) sb1 += bytesum16(r.b1);
     }
 };
 
-template <int BN>
-__global__ __launch_bounds__(kThreads) void gemm_direct(const int16_t *__restrict__ g16, const int8_t *__restrict__ x, int K,
-                                                        int C, int PQ, int steps_total, int steps_slice, int Rap, int Rbp,
-                                                        int32_t *__restrict__ part, int *__restrict__ rsum,
-                                                        int *__restrict__ csum)
+template <class C>
+__global__ __launch_bounds__(C::THREADS, C::MINB) void gemm_direct(const int16_t *__restrict__ g16, const int8_t *__restrict__ x,
+                                                                    int K, int Cin, int PQ, int steps_total, int steps_slice,
+                                                                    int Rap, int Rbp, int nz, int32_t *__restrict__ part,
+                                                                    int *__restrict__ rsum, int *__restrict__ csum)
 {
-    constexpr int MT = q8t_gemm::Tile<BN>::MT, NT = q8t_gemm::Tile<BN>::NT;
-    constexpr int NB = BN / 64;
-    __shared__ __align__(16) int8_t sA[2 * BM * PITCH];
-    __shared__ __align__(16) int8_t sB[2 * BN * PITCH];
+    __shared__ __align__(16) int8_t sA[2 * C::BM * 64];
+    __shared__ __align__(16) int8_t sB[2 * C::BN * 64];
 
-    const int tid = threadIdx.x;
-    const int k0 = blockIdx.x * 64, c0 = blockIdx.y * BN, z = blockIdx.z;
-    const int r0 = blockIdx.x * BM;
+    const int nx = K / C::RP, ny = Rbp / C::BN;
+    const int lg = q8t_gemm::xcd_logical(blockIdx.x, nx * ny * nz);
+    if (lg >= nx * ny * nz) return;
+    const int bx = lg % nx, by = (lg / nx) % ny, z = lg / (nx * ny);
+    const int tid = threadIdx.x, ar = tid >> 2, q = tid & 3;
+    const int r0 = bx * C::BM, c0 = by * C::BN;
     const int t0 = z * steps_slice;
     const int steps = min(steps_slice, steps_total - t0);
 
-    DirectOps<NB> ops;
+    DirectOps<C> ops;
     ops.g16 = g16;
     ops.x = x;
-    ops.sA = sA;
-    ops.sB = sB;
     ops.K = K;
-    ops.C = C;
+    ops.Cin = Cin;
     ops.PQ = PQ;
     ops.cpi = PQ >> 6;   // steps per image
-    ops.kr = tid >> 2;   // gradient row, 16-code quarter
-    ops.kq = tid & 3;
-    ops.br = NB == 2 ? tid >> 1 : tid >> 2;
-    ops.bo = NB == 2 ? (tid & 1) * 32 : (tid & 3) * 16;
-    ops.k0kr = k0 + ops.kr;
-    ops.c0br = c0 + ops.br;
-    ops.n = t0 / ops.cpi;
-    ops.ch = t0 - ops.n * ops.cpi;
-    ops.shi = ops.slo = ops.sb = 0;
+    ops.q = q;
+    ops.krow = bx * C::RP + ar;
+    ops.crow = c0 + ar;
+    ops.n = ops.n_first = t0 / ops.cpi;
+    ops.ch = ops.ch_first = t0 - ops.n * ops.cpi;
+    ops.shi = ops.slo = ops.sb0 = ops.sb1 = 0;
 
-    v4i acc[MT][NT];
+    v4i acc[C::MT][C::NT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (v4i){0, 0, 0, 0};
-    q8t_gemm::pipeline<BN>(ops, steps, sA, sB, acc);
+        for (int nt = 0; nt < C::NT; ++nt) acc[mt][nt] = (v4i){0, 0, 0, 0};
+    q8t_gemm::pipeline<C>(ops, steps, sA, sB, acc);
 
-    int shi = ops.shi, slo = ops.slo, sb = ops.sb;
-    shi += __shfl_xor(shi, 1, Q8T_WAVE);
-    shi += __shfl_xor(shi, 2, Q8T_WAVE);
-    slo += __shfl_xor(slo, 1, Q8T_WAVE);
-    slo += __shfl_xor(slo, 2, Q8T_WAVE);
-    sb += __shfl_xor(sb, 1, Q8T_WAVE);
-    if (NB == 1) sb += __shfl_xor(sb, 2, Q8T_WAVE);
-    if (blockIdx.y == 0 && ops.kq == 0) {
-        rsum[(size_t)z * Rap + r0 + ops.kr] = shi;
-        rsum[(size_t)z * Rap + r0 + 64 + ops.kr] = slo;
+    const int shi = quad_sum(ops.shi), slo = quad_sum(ops.slo), sb0 = quad_sum(ops.sb0), sb1 = quad_sum(ops.sb1);
+    if (by == 0 && q == 0) {
+        rsum[(size_t)z * Rap + r0 + ar] = shi;
+        rsum[(size_t)z * Rap + r0 + C::RP + ar] = slo;
     }
-    if (blockIdx.x == 0 && (NB == 2 ? (tid & 1) == 0 : (tid & 3) == 0)) csum[(size_t)z * Rbp + c0 + ops.br] = sb;
-    write_partials<BN>(part + (size_t)z * Rap * Rbp, Rbp, r0, c0, acc);
+    if (bx == 0 && q == 0) {
+        csum[(size_t)z * Rbp + c0 + ar] = sb0;
+        if (C::NB == 2) csum[(size_t)z * Rbp + c0 + ar + C::RP] = sb1;
+    }
+    write_partials<C>(part + (size_t)z * Rap * Rbp, Rbp, r0, c0, acc);
 }
 
 // ---- slices -> exact 64-bit sums -> outputs ------------------------------------------------------
@@ -424,8 +421,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_finish(const int32_t *__restri
     if (ok) {
         k = (int)(id / CRS);
         col = (int)(id - (int64_t)k * CRS);
-        // rows of the two byte planes: [all high | all low], or per 64 channels [64 high | 64 low]
-        const int rh = tiled ? (k >> 6) * 128 + (k & 63) : k, rl = tiled ? rh + 64 : K + k;
+        // rows of the two byte planes: [all high | all low], or per `tiled` channels [high | low]
+        const int rh = tiled ? (k / tiled) * 2 * tiled + (k % tiled) : k, rl = tiled ? rh + tiled : K + k;
         for (int z = zg; z < nz; z += zgn) {
             shi += part[((size_t)z * Rap + rh) * Rbp + col];
             slo += part[((size_t)z * Rap + rl) * Rbp + col];
@@ -461,6 +458,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_finish(const int32_t *__restri
 
 struct Plan {
     int P, Q, CRS, Rap, Rbp, nz, slice, direct;
+    int cfg;   // 2: 256x256 tiles, 1: 128x128, 0: 128x64
     int64_t Mtot, Mp;
     size_t o_B, o_part, o_rsum, o_csum, total;
 };
@@ -485,8 +483,15 @@ bool make_plan(const q8t_conv_desc *d, Plan *p)
     if ((p->Mp >> 4) * widest / kThreads >= ((int64_t)1 << 31)) return false;   // grid of the relayout kernels
     p->Rap = (2 * d->K + BM - 1) / BM * BM;
     p->Rbp = (p->CRS + 63) / 64 * 64;
-    const int64_t tiles = (int64_t)(p->Rap / BM) * (p->Rbp % 128 == 0 ? p->Rbp / 128 : p->Rbp / 64);
-    int64_t nz = (768 + tiles - 1) / tiles;                  // enough workgroups to fill the chip
+    // 1x1 / stride 1 / no padding on planes of a multiple of 64 positions: operands are used in place
+    p->direct = d->R == 1 && d->S == 1 && d->stride == 1 && d->pad == 0 && (p->P * p->Q) % 64 == 0 && d->K % 64 == 0 &&
+                d->C % 64 == 0;
+    p->cfg = (p->Rap % 256 == 0 && p->Rbp % 256 == 0 && (!p->direct || d->K % 128 == 0)) ? 2 : (p->Rbp % 128 == 0 ? 1 : 0);
+    const int bm = p->cfg == 2 ? 256 : 128, bn = p->cfg == 2 ? 256 : (p->cfg == 1 ? 128 : 64);
+    const int64_t tiles = (int64_t)(p->Rap / bm) * (p->Rbp / bn);
+    // slices: the big tile runs one workgroup per compute unit, so aim at (just under) a multiple of
+    // 256 workgroups; the small tiles at three per compute unit
+    int64_t nz = p->cfg == 2 ? (tiles >= 256 ? 1 : 256 / tiles) : (768 + tiles - 1) / tiles;
     const int64_t most = (p->Mp + 1023) / 1024;              // but at least 16 steps per slice
     if (nz > most) nz = most;
     const int64_t ovf = (p->Mp + kMaxSlice - 1) / kMaxSlice;  // 32-bit accumulator bound
@@ -494,12 +499,9 @@ bool make_plan(const q8t_conv_desc *d, Plan *p)
     int64_t slice = ((p->Mp + nz - 1) / nz + 63) & ~(int64_t)63;
     if (slice > kMaxSlice) slice = kMaxSlice;
     nz = (p->Mp + slice - 1) / slice;
-    if (nz > 65535) return false;
+    if (nz > 65535 || tiles * nz >= ((int64_t)1 << 30)) return false;
     p->nz = (int)nz;
     p->slice = (int)slice;
-    // 1x1 / stride 1 / no padding on planes of a multiple of 64 positions: operands are used in place
-    p->direct = d->R == 1 && d->S == 1 && d->stride == 1 && d->pad == 0 && (p->P * p->Q) % 64 == 0 && d->K % 64 == 0 &&
-                d->C % 64 == 0;
     const size_t a_bytes = up256((size_t)p->Rap * p->Mp);
     p->o_B = a_bytes;
     p->o_part = p->o_B + up256((size_t)p->Rbp * p->Mp);
@@ -538,14 +540,14 @@ int q8t_gemm_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams
     const int direct = p.direct && q8t_aligned(g16, 16) && q8t_aligned(x, 16);
     if (direct) {
         const int steps_total = (int)(p.Mtot >> 6), steps_slice = p.slice >> 6;
-        if (p.Rbp % 128 == 0)
-            hipLaunchKernelGGL(gemm_direct<128>, dim3((unsigned)(d->K / 64), (unsigned)(p.Rbp / 128), (unsigned)p.nz),
-                               dim3(kThreads), 0, st, g16, x, d->K, d->C, p.P * p.Q, steps_total, steps_slice, p.Rap,
-                               p.Rbp, part, rsum, csum);
-        else
-            hipLaunchKernelGGL(gemm_direct<64>, dim3((unsigned)(d->K / 64), (unsigned)(p.Rbp / 64), (unsigned)p.nz),
-                               dim3(kThreads), 0, st, g16, x, d->K, d->C, p.P * p.Q, steps_total, steps_slice, p.Rap,
-                               p.Rbp, part, rsum, csum);
+#define Q8T_GO(CFG)                                                                                                       \
+    hipLaunchKernelGGL(gemm_direct<CFG>, dim3(q8t_gemm::xcd_grid((int64_t)(d->K / CFG::RP) * (p.Rbp / CFG::BN) * p.nz)), \
+                       dim3(CFG::THREADS), 0, st, g16, x, d->K, d->C, p.P * p.Q, steps_total, steps_slice, p.Rap, p.Rbp, \
+                       p.nz, part, rsum, csum)
+        if (p.cfg == 2) Q8T_GO(q8t_gemm::Big);
+        else if (p.cfg == 1) Q8T_GO(q8t_gemm::Mid);
+        else Q8T_GO(q8t_gemm::Small);
+#undef Q8T_GO
         Q8T_LAUNCH_CHECK();
     } else {
     {
@@ -572,12 +574,13 @@ int q8t_gemm_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams
             hipLaunchKernelGGL(im2col_rows, dim3((unsigned)blocks), dim3(kThreads), 0, st, x, g, p.Mtot, p.Mp, qx, B);
         Q8T_LAUNCH_CHECK();
     }
-    if (p.Rbp % 128 == 0)
-        hipLaunchKernelGGL(gemm_nt<128>, dim3((unsigned)(p.Rap / BM), (unsigned)(p.Rbp / 128), (unsigned)p.nz),
-                           dim3(kThreads), 0, st, A, B, p.Mp, p.slice, p.Rap, p.Rbp, part, rsum, csum);
-    else
-        hipLaunchKernelGGL(gemm_nt<64>, dim3((unsigned)(p.Rap / BM), (unsigned)(p.Rbp / 64), (unsigned)p.nz),
-                           dim3(kThreads), 0, st, A, B, p.Mp, p.slice, p.Rap, p.Rbp, part, rsum, csum);
+#define Q8T_GO(CFG)                                                                                                   \
+    hipLaunchKernelGGL(gemm_nt<CFG>, dim3(q8t_gemm::xcd_grid((int64_t)(p.Rap / CFG::BM) * (p.Rbp / CFG::BN) * p.nz)), \
+                       dim3(CFG::THREADS), 0, st, A, B, p.Mp, p.slice, p.Rap, p.Rbp, p.nz, part, rsum, csum)
+    if (p.cfg == 2) Q8T_GO(q8t_gemm::Big);
+    else if (p.cfg == 1) Q8T_GO(q8t_gemm::Mid);
+    else Q8T_GO(q8t_gemm::Small);
+#undef Q8T_GO
     Q8T_LAUNCH_CHECK();
     }
     {
@@ -585,7 +588,8 @@ int q8t_gemm_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams
         const int zgn = p.nz >= 64 ? 16 : (p.nz >= 8 ? 4 : 1);   // lanes sharing the slices of one output
         const int per = kThreads / zgn;
         hipLaunchKernelGGL(wgrad_finish, dim3((unsigned)((count + per - 1) / per)), dim3(kThreads), 0, st,
-                           part, rsum, csum, p.nz, d->K, p.CRS, p.Rap, p.Rbp, p.Mp, qg, qx, dw, acc_out, zgn, direct);
+                           part, rsum, csum, p.nz, d->K, p.CRS, p.Rap, p.Rbp, p.Mp, qg, qx, dw, acc_out, zgn,
+                           direct ? (p.cfg == 2 ? 128 : 64) : 0);
         Q8T_LAUNCH_CHECK();
     }
     return Q8T_OK;
