@@ -148,35 +148,39 @@ __global__ __launch_bounds__(kThreads) void im2col_rows(const int8_t *__restrict
     *reinterpret_cast<uint4 *>(B + (size_t)col * Mp + m0) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
-// Same result through LDS: a workgroup stages the zero-padded planes of one channel for a group of
+// Same result through LDS: a workgroup stages the zero-padded planes of CG channels for a group of
 // NI images (NI*P*Q a multiple of 4, so that its stretch of every row starts on a dword), then
-// every thread builds one dword (4 consecutive positions) for each of the R*S taps.  The input is
-// read once instead of R*S times and every store is a full dword.
-__global__ __launch_bounds__(kThreads) void im2col_planes(const int8_t *__restrict__ x, ConvG g, int NI, int64_t Mtot,
+// every thread builds, for one channel, one dword (4 consecutive positions) for each of the R*S
+// taps.  The input is read once instead of R*S times and every store is a full dword.
+__global__ __launch_bounds__(kThreads) void im2col_planes(const int8_t *__restrict__ x, ConvG g, int NI, int CG, int64_t Mtot,
                                                           int64_t Mp, const q8t_qparams *__restrict__ qpx,
                                                           int8_t *__restrict__ B)
 {
     extern __shared__ __align__(16) int8_t planes[];
-    const int c = blockIdx.y, n0 = blockIdx.x * NI;
-    const int ni = min(NI, g.N - n0);
+    const int c0 = blockIdx.y * CG, n0 = blockIdx.x * NI;
+    const int ni = min(NI, g.N - n0), cg = min(CG, g.C - c0);
     const int Hp = g.H + 2 * g.pad, Wp = g.W + 2 * g.pad, PB = Hp * Wp;
     const int PQ = g.P * g.Q, HW = g.H * g.W;
     const int zsx = qpx->zero_point - (1 << (qpx->bits - 1));
-    for (int i = threadIdx.x; i < ni * PB; i += kThreads) planes[i] = (int8_t)zsx;
+    for (int i = threadIdx.x; i < cg * NI * PB; i += kThreads) planes[i] = (int8_t)zsx;
     __syncthreads();
     const float rHW = 1.0f / (float)HW, rW = 1.0f / (float)g.W, rPQ = 1.0f / (float)PQ, rQ = 1.0f / (float)g.Q;
-    for (int i = threadIdx.x; i < ni * HW; i += kThreads) {
-        const int nl = fdiv(i, HW, rHW), t = i - nl * HW, h = fdiv(t, g.W, rW), w = t - h * g.W;
-        planes[nl * PB + (h + g.pad) * Wp + w + g.pad] = x[((size_t)(n0 + nl) * g.C + c) * HW + t];
+    // plane (cl, nl) sits at (cl*NI + nl)*PB
+    for (int i = threadIdx.x; i < cg * ni * HW; i += kThreads) {
+        const int pl = fdiv(i, HW, rHW), t = i - pl * HW, h = fdiv(t, g.W, rW), w = t - h * g.W;
+        const int cl = pl / ni, nl = pl - cl * ni;
+        planes[(cl * NI + nl) * PB + (h + g.pad) * Wp + w + g.pad] = x[((size_t)(n0 + nl) * g.C + c0 + cl) * HW + t];
     }
     __syncthreads();
     const int64_t mbase = (int64_t)n0 * PQ;
     const bool last = n0 + NI >= g.N;
     const int64_t mend = last ? Mp : mbase + (int64_t)NI * PQ;   // the last group also writes the padding
     const int ndw = (int)((mend - mbase) >> 2);
+    const float rndw = 1.0f / (float)ndw;
     const int RS = g.R * g.S;
     const uint32_t zb = (uint32_t)(zsx & 255);
-    for (int dp = threadIdx.x; dp < ndw; dp += kThreads) {
+    for (int it = threadIdx.x; it < cg * ndw; it += kThreads) {
+        const int cl = fdiv(it, ndw, rndw), dp = it - cl * ndw;
         int off[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -184,10 +188,10 @@ __global__ __launch_bounds__(kThreads) void im2col_planes(const int8_t *__restri
             off[j] = -1;
             if (mbase + e < Mtot) {
                 const int nl = fdiv(e, PQ, rPQ), t = e - nl * PQ, pp = fdiv(t, g.Q, rQ), qq = t - pp * g.Q;
-                off[j] = nl * PB + pp * g.stride * Wp + qq * g.stride;
+                off[j] = (cl * NI + nl) * PB + pp * g.stride * Wp + qq * g.stride;
             }
         }
-        int8_t *dst = B + ((size_t)c * RS) * Mp + mbase + (int64_t)dp * 4;
+        int8_t *dst = B + ((size_t)(c0 + cl) * RS) * Mp + mbase + (int64_t)dp * 4;
         for (int r = 0; r < g.R; ++r)
             for (int s = 0; s < g.S; ++s) {
                 const int o = r * Wp + s;
@@ -210,6 +214,7 @@ template <class C>
 struct NtOps {
     const int8_t *pa, *pb, *pa0, *pb0;   // next chunk; first chunk (always readable)
     size_t skip;                         // RP rows further
+    bool need_a, need_b;                 // this workgroup reports the row / column sums of its tiles
     int sa0, sa1, sb0, sb1;
     __device__ __forceinline__ void load(q8t_gemm::Regs &r, bool valid)
     {
@@ -223,14 +228,17 @@ struct NtOps {
     }
     __device__ __forceinline__ void prepare(q8t_gemm::Regs &r, bool valid)
     {
-        r.a0 = q8t_gemm::sel16(valid, r.a0);
-        r.a1 = q8t_gemm::sel16(valid, r.a1);
+        // a surplus step stages zero B' rows, so whatever A' holds adds nothing to the products
         r.b0 = q8t_gemm::sel16(valid, r.b0);
         r.b1 = q8t_gemm::sel16(valid, r.b1);
-        sa0 += bytesum16(r.a0);
-        sa1 += bytesum16(r.a1);
-        sb0 += bytesum16(r.b0);
-        if (C::NB == 2) sb1 += bytesum16(r.b1);
+        if (need_a) {   // uniform over the workgroup
+            sa0 += valid ? bytesum16(r.a0) : 0;
+            sa1 += valid ? bytesum16(r.a1) : 0;
+        }
+        if (need_b) {
+            sb0 += bytesum16(r.b0);
+            if (C::NB == 2) sb1 += bytesum16(r.b1);
+        }
     }
 };
 
@@ -281,6 +289,8 @@ __global__ __launch_bounds__(C::THREADS, C::MINB) void gemm_nt(const int8_t *__r
     ops.pa = ops.pa0 = A + (size_t)(r0 + ar) * Mp + mb + q * 16;
     ops.pb = ops.pb0 = B + (size_t)(c0 + ar) * Mp + mb + q * 16;
     ops.skip = (size_t)C::RP * Mp;
+    ops.need_a = by == 0;
+    ops.need_b = bx == 0;
     ops.sa0 = ops.sa1 = ops.sb0 = ops.sb1 = 0;
 
     v4i acc[C::MT][C::NT];
@@ -314,6 +324,7 @@ struct DirectOps {
     const int8_t *x;
     int K, Cin, PQ, cpi, krow, crow, q;
     int n, ch, n_first, ch_first;
+    bool need_a, need_b;
     int shi, slo, sb0, sb1;
     __device__ __forceinline__ void load(q8t_gemm::Regs &r, bool valid)
     {
@@ -339,14 +350,18 @@ struct DirectOps {
         lo.y = __builtin_amdgcn_perm(r.a0.w, r.a0.z, 0x06040200u) ^ 0x80808080u;
         lo.z = __builtin_amdgcn_perm(r.a1.y, r.a1.x, 0x06040200u) ^ 0x80808080u;
         lo.w = __builtin_amdgcn_perm(r.a1.w, r.a1.z, 0x06040200u) ^ 0x80808080u;
-        r.a0 = q8t_gemm::sel16(valid, hi);   // a surplus step stages zeros in every plane
-        r.a1 = q8t_gemm::sel16(valid, lo);
-        r.b0 = q8t_gemm::sel16(valid, r.b0);
+        r.a0 = hi;
+        r.a1 = lo;
+        r.b0 = q8t_gemm::sel16(valid, r.b0);   // a surplus step stages zero input rows
         r.b1 = q8t_gemm::sel16(valid, r.b1);
-        shi += bytesum16(r.a0);
-        slo += bytesum16(r.a1);
-        sb0 += bytesum16(r.b0);
-        if (C::NB == 2) sb1 += bytesum16(r.b1);
+        if (need_a) {   // uniform over the workgroup
+            shi += valid ? bytesum16(hi) : 0;
+            slo += valid ? bytesum16(lo) : 0;
+        }
+        if (need_b) {
+            sb0 += bytesum16(r.b0);
+            if (C::NB == 2) sb1 += bytesum16(r.b1);
+        }
     }
 };
 
@@ -380,6 +395,8 @@ __global__ __launch_bounds__(C::THREADS, C::MINB) void gemm_direct(const int16_t
     ops.crow = c0 + ar;
     ops.n = ops.n_first = t0 / ops.cpi;
     ops.ch = ops.ch_first = t0 - ops.n * ops.cpi;
+    ops.need_a = by == 0;
+    ops.need_b = bx == 0;
     ops.shi = ops.slo = ops.sb0 = ops.sb1 = 0;
 
     v4i acc[C::MT][C::NT];
@@ -566,10 +583,16 @@ int q8t_gemm_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams
         const int64_t blocks = (chunks * p.CRS + kThreads - 1) / kThreads;
         const int PQ = p.P * p.Q;
         const int NI = PQ % 4 == 0 ? 1 : (PQ % 2 == 0 ? 2 : 4);
-        const size_t lds = (size_t)NI * (d->H + 2 * d->pad) * (d->W + 2 * d->pad);
-        if (lds <= 65536 && (int64_t)NI * PQ + 64 < (1 << 24) && (int64_t)NI * d->H * d->W < (1 << 24) && d->C <= 65535)
-            hipLaunchKernelGGL(im2col_planes, dim3((unsigned)((d->N + NI - 1) / NI), (unsigned)d->C), dim3(kThreads), lds,
-                               st, x, g, NI, p.Mtot, p.Mp, qx, B);
+        const size_t lds1 = (size_t)NI * (d->H + 2 * d->pad) * (d->W + 2 * d->pad);
+        // channels per workgroup: about 1024 dwords of work per tap, within 32 KB of LDS
+        int CG = (int)(4096 / ((int64_t)NI * PQ) > 0 ? 4096 / ((int64_t)NI * PQ) : 1);
+        if (lds1 * CG > 32768) CG = (int)(32768 / lds1 > 0 ? 32768 / lds1 : 1);
+        if (CG > d->C) CG = d->C;
+        const size_t lds = lds1 * CG;
+        if (lds <= 65536 && (int64_t)CG * (NI * (int64_t)PQ + 64) < (1 << 24) && (int64_t)CG * NI * d->H * d->W < (1 << 24) &&
+            (d->C + CG - 1) / CG <= 65535)
+            hipLaunchKernelGGL(im2col_planes, dim3((unsigned)((d->N + NI - 1) / NI), (unsigned)((d->C + CG - 1) / CG)),
+                               dim3(kThreads), lds, st, x, g, NI, CG, p.Mtot, p.Mp, qx, B);
         else
             hipLaunchKernelGGL(im2col_rows, dim3((unsigned)blocks), dim3(kThreads), 0, st, x, g, p.Mtot, p.Mp, qx, B);
         Q8T_LAUNCH_CHECK();
