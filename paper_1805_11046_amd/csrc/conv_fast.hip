@@ -336,10 +336,10 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
         const int sub = step / CC, cc = step - sub * CC;
         const int g0 = tile_begin(sub), g1 = tile_end(sub);
         const bool with_b = (CC > 1) || (step == 0);
-        __syncthreads();
+        q8t_lds_barrier();
         commit(step);
         if (with_b) stage_b(cc);
-        __syncthreads();
+        q8t_lds_barrier();
         if (step + 1 < nsteps) prefetch(step + 1);
 
         if (cc == 0) {

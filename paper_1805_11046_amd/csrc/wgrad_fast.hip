@@ -253,7 +253,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
             if (u + 2 < units) load_regs(u + 2);
         }
         if (late) compute(u, cur);
-        __syncthreads();
+        q8t_lds_barrier();
     }
 
     // fold the 4 k-blocks of the row / column sums
@@ -274,7 +274,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
         const int src = round == 0 ? 1 : (round == 1 ? 3 : 2);
         const int dst = round == 0 ? 0 : (round == 1 ? 2 : 0);
         int *slot = slots + plane * SLOT_INTS;
-        __syncthreads();
+        q8t_lds_barrier();
         if (kl == src) {
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt)
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt) slot[36 * 4 * 64 + (9 + mt) * 64 + lane] = rs[mt];
         }
-        __syncthreads();
+        q8t_lds_barrier();
         if (kl == dst) {
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt)
