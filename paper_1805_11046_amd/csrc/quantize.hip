@@ -206,18 +206,50 @@ __global__ __launch_bounds__(kThreads) void quantize_apply(
     }
 }
 
-// small tensors (weights of a layer): both passes in one workgroup, one launch
-template <typename OUT, bool STOCH>
+// small tensors (weights of a layer): both passes in one workgroup, one launch.  The tensor is
+// read once, with every load of a thread in flight at the same time (one memory latency instead
+// of one per element), and quantized out of registers.
+template <typename OUT, bool STOCH, bool VEC>
 __global__ __launch_bounds__(kSmallThreads) void quantize_small(const float *__restrict__ x, int n, int bits,
                                                                 uint32_t seed_lo, uint32_t seed_hi,
                                                                 OUT *__restrict__ q_out,
                                                                 q8t_qparams *__restrict__ qp_out)
 {
+    constexpr int PER = kSmallN / kSmallThreads;   // elements per thread
     __shared__ float smn[kSmallThreads / 64], smx[kSmallThreads / 64];
     float mn = INFINITY, mx = -INFINITY;
-    for (int i = threadIdx.x; i < n; i += kSmallThreads) {
-        mn = fminf(mn, x[i]);
-        mx = fmaxf(mx, x[i]);
+    float v[PER];
+    if (VEC) {
+        const float4 *x4 = reinterpret_cast<const float4 *>(x);
+        const int n4 = n >> 2;
+#pragma unroll
+        for (int k = 0; k < PER / 4; ++k) {
+            const int i = threadIdx.x + k * kSmallThreads;
+            float4 t = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (i < n4) t = x4[i];
+            v[4 * k] = t.x;
+            v[4 * k + 1] = t.y;
+            v[4 * k + 2] = t.z;
+            v[4 * k + 3] = t.w;
+        }
+#pragma unroll
+        for (int k = 0; k < PER / 4; ++k)
+            if (threadIdx.x + k * kSmallThreads < n4) {
+                mn = fminf(fminf(mn, v[4 * k]), fminf(v[4 * k + 1], fminf(v[4 * k + 2], v[4 * k + 3])));
+                mx = fmaxf(fmaxf(mx, v[4 * k]), fmaxf(v[4 * k + 1], fmaxf(v[4 * k + 2], v[4 * k + 3])));
+            }
+    } else {
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int i = threadIdx.x + k * kSmallThreads;
+            v[k] = i < n ? x[i] : 0.0f;
+        }
+#pragma unroll
+        for (int k = 0; k < PER; ++k)
+            if (threadIdx.x + k * kSmallThreads < n) {
+                mn = fminf(mn, v[k]);
+                mx = fmaxf(mx, v[k]);
+            }
     }
     mn = wave_reduce(mn, OpMin());
     mx = wave_reduce(mx, OpMax());
@@ -235,9 +267,26 @@ __global__ __launch_bounds__(kSmallThreads) void quantize_small(const float *__r
     const q8t_qparams qp = make_qparams(mn, mx, bits);
     if (threadIdx.x == 0) *qp_out = qp;
     const Affine a = affine_of(qp);
-    for (int i = threadIdx.x; i < n; i += kSmallThreads) {
-        const uint32_t r = STOCH ? rng_r16(i, seed_lo, seed_hi) : 0u;
-        q_out[i] = (OUT)(level_of<STOCH>(x[i], a, r) - a.half);
+    if (VEC) {
+        typedef typename Pack4<OUT>::type P;
+        P *q4 = reinterpret_cast<P *>(q_out);
+        const int n4 = n >> 2;
+#pragma unroll
+        for (int k = 0; k < PER / 4; ++k) {
+            const int i = threadIdx.x + k * kSmallThreads;
+            if (i < n4)
+                q4[i] = quant4<OUT, STOCH>(make_float4(v[4 * k], v[4 * k + 1], v[4 * k + 2], v[4 * k + 3]), a, (uint32_t)i,
+                                           seed_lo, seed_hi);
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+            const int i = threadIdx.x + k * kSmallThreads;
+            if (i < n) {
+                const uint32_t r = STOCH ? rng_r16(i, seed_lo, seed_hi) : 0u;
+                q_out[i] = (OUT)(level_of<STOCH>(v[k], a, r) - a.half);
+            }
+        }
     }
 }
 
@@ -371,9 +420,15 @@ int q8t_quantize(const float *x, int64_t n, int bits, int stochastic, uint64_t s
     hipStream_t st = (hipStream_t)stream;
     if (n > 0 && n <= kSmallN) {
         const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
-#define Q8T_SMALL(T, S) hipLaunchKernelGGL((quantize_small<T, S>), dim3(1), dim3(kSmallThreads), 0, st, x, (int)n, bits, lo, hi, (T *)q_out, qp_out)
-        if (bits <= 8) { if (stochastic) Q8T_SMALL(int8_t, true); else Q8T_SMALL(int8_t, false); }
-        else           { if (stochastic) Q8T_SMALL(int16_t, true); else Q8T_SMALL(int16_t, false); }
+#define Q8T_SMALL(T, S, V) hipLaunchKernelGGL((quantize_small<T, S, V>), dim3(1), dim3(kSmallThreads), 0, st, x, (int)n, bits, lo, hi, (T *)q_out, qp_out)
+        const bool vec = n % 4 == 0 && q8t_aligned(x, 16) && q8t_aligned(q_out, bits <= 8 ? 4 : 8);
+        if (bits <= 8) {
+            if (stochastic) { if (vec) Q8T_SMALL(int8_t, true, true); else Q8T_SMALL(int8_t, true, false); }
+            else            { if (vec) Q8T_SMALL(int8_t, false, true); else Q8T_SMALL(int8_t, false, false); }
+        } else {
+            if (stochastic) { if (vec) Q8T_SMALL(int16_t, true, true); else Q8T_SMALL(int16_t, true, false); }
+            else            { if (vec) Q8T_SMALL(int16_t, false, true); else Q8T_SMALL(int16_t, false, false); }
+        }
 #undef Q8T_SMALL
         Q8T_LAUNCH_CHECK();
         return Q8T_OK;
