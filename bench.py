@@ -4,7 +4,8 @@ One "step" = one pass of the whole hot path over one batch of synthetic input, f
 ResNet-18 3x3 conv layer 64->64 @56x56, batch 128 (the conv of config 2 followed by the Range BN
 of config 1's shape, 128x64x56x56):
 
-  forward : quantize X and W (min/max, nearest) -> int8 conv forward -> Range BN forward
+  forward : quantize X and W (min/max, nearest) -> int8 conv forward, whose epilogue also gathers the
+            Range BN statistics -> Range BN normalization to an 8-bit per-tensor output (config 1)
   backward: Range BN backward fused with the bifurcated stochastic quantization of the gradient
             (8-bit and 16-bit copies) -> int8 layer-gradient conv -> 16x8-bit weight-gradient conv
 
@@ -59,7 +60,8 @@ class LayerStep:
         self.qx, self.px = e((N, C, H, W), torch.int8), q8t.new_qparams(dev)
         self.qw, self.pw = e((K, C, 3, 3), torch.int8), q8t.new_qparams(dev)
         self.y = e((N, K, H, W), torch.float32)
-        self.bn = e((N, K, H, W), torch.float32)
+        self.bnq = e((N, K, H, W), torch.int8)   # Range BN output, 8-bit per tensor (what the next layer's product reads)
+        self.pbn = q8t.new_qparams(dev)
         self.stats = e((3, K), torch.float32)
         self.g = e((N, K, H, W), torch.float32)
         self.g8, self.pg8 = e((N, K, H, W), torch.int8), q8t.new_qparams(dev)
@@ -73,10 +75,16 @@ class LayerStep:
             ("quantize_x", lambda s: q8t.quantize(self.x, 8, False, 0, q_out=self.qx, qp_out=self.px), 9.0 * n, 0),
             ("quantize_w", lambda s: q8t.quantize(self.w, 8, False, 0, q_out=self.qw, qp_out=self.pw),
              9.0 * self.w.numel(), 0),
-            ("qconv_fwd", lambda s: q8t.qconv_fwd(self.desc, self.qx, self.px, self.qw, self.pw, out=self.y),
+            # the conv epilogue also gathers the Range BN statistics of its result (mean, min, max per
+            # channel), so the normalization needs no pass of its own over y for them
+            ("qconv_fwd_bn_stats", lambda s: q8t.qconv_fwd_bn_stats(self.desc, self.qx, self.px, self.qw, self.pw,
+                                                                    out=self.y, stats_out=self.stats),
              1.0 * n + 4.0 * n, ops),
-            ("range_bn_fwd", lambda s: q8t.range_bn_fwd(self.y, None, None, 1e-5, y_out=self.bn,
-                                                        stats_out=self.stats), 12.0 * n, 0),
+            # config 1: the normalized output leaves as 8-bit codes with the analytic range
+            # (4 read + 1 written per element)
+            ("range_bn_fwd_apply", lambda s: q8t.range_bn_fwd_apply(self.y, self.stats, None, None, 1e-5,
+                                                                    quantized=True, want_y=False, q_out=self.bnq,
+                                                                    qp_out=self.pbn), 5.0 * n, 0),
             # Range BN backward with the bifurcated quantization of its result: 20 B/element for the
             # backward pass + 7 B/element (4 re-read, 1 + 2 written) for the two copies; the min/max
             # of the gradient is taken while it is written
@@ -128,7 +136,7 @@ def cpu_baseline(batch, seed):
     sx, _, px = oracle.quantize(x, 8)
     sw, _, pw = oracle.quantize(w, 8)
     y, _ = oracle.qconv_fwd(d, sx, px, sw, pw)
-    bn, stats, _, _ = oracle.range_bn_fwd(y, eps=1e-5)
+    _, stats, _, _ = oracle.range_bn_fwd(y, eps=1e-5, quantized=True)
     g, _, _ = oracle.range_bn_bwd(y, dout, stats, None, 1e-5)
     s8, _, p8 = oracle.quantize(g, 8, True, 1)
     s16, _, p16 = oracle.quantize(g, 16, True, 2)

@@ -111,6 +111,17 @@ int q8t_qgemm_wgrad(const int8_t *qx, const q8t_qparams *px, const int16_t *qdy1
                     const q8t_qparams *pg16, int M, int N, int K, float *dw, int64_t *acc_out,
                     void *ws, void *stream);
 
+/* Forward convolution that also returns the Range BN statistics of its result (Sec. 3: mean, min
+ * and max per output channel; Sec. 4: the range is known to the normalizer, no extra pass).
+ * Same arguments as q8t_qconv_fwd, y required; stats_out: device, [3][K] floats = mean, min, max
+ * over the N*P*Q values of each output channel -- what q8t_range_bn_fwd would write into its
+ * stats_out for y.  min/max are exact; the mean is taken from the exact integer sum of the
+ * accumulators (differs from a float scan of y by rounding only).  Workspace: device,
+ * q8t_qconv_fwd_bn_stats_workspace_size(desc) bytes, 16-byte aligned.  Errors as q8t_qconv_fwd. */
+size_t q8t_qconv_fwd_bn_stats_workspace_size(const q8t_conv_desc *desc);
+int q8t_qconv_fwd_bn_stats(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams *px, const int8_t *qw,
+                           const q8t_qparams *pw, float *y, int32_t *acc_out, float *stats_out, void *ws, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Convolution layer, NCHW (same three products, Section 4).  A padded tap contributes nothing.
  *   fwd  : Y [n,k,p,q] = sum_{c,r,s} X[n,c,p*st+r-pad,q*st+s-pad] * W[k,c,r,s]
@@ -145,6 +156,13 @@ size_t q8t_range_bn_workspace_size(int N, int C, int H, int W);
 int q8t_range_bn_fwd(const float *x, int N, int C, int H, int W, const float *gamma,
                      const float *beta, float eps, float *y, float *stats_out, int8_t *q_out,
                      q8t_qparams *qp_out, void *ws, void *stream);
+
+/* Range BN forward with ready-made statistics (Sec. 3, eq. (range)): the normalization pass of
+ * q8t_range_bn_fwd alone.  stats: device, [3][C] = mean, min, max (e.g. from
+ * q8t_qconv_fwd_bn_stats); y and / or q_out + qp_out as in q8t_range_bn_fwd (at least one output).
+ * No workspace.  Errors: Q8T_ERR_SHAPE, Q8T_ERR_NULL, Q8T_ERR_HIP. */
+int q8t_range_bn_fwd_apply(const float *x, int N, int C, int H, int W, const float *gamma, const float *beta, float eps,
+                           const float *stats, float *y, int8_t *q_out, q8t_qparams *qp_out, void *stream);
 
 /* Backward of the above (Section 7: the derivative of max / min is one at every coordinate that
  * attains it and zero elsewhere).  With g_j = gamma*dy_j, s = C(n)*range + eps:

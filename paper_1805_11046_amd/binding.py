@@ -62,6 +62,9 @@ _SIGS = {
     "q8t_range_bn_workspace_size": (_sz, [_i, _i, _i, _i]),
     "q8t_range_bn_fwd": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _vp]),
     "q8t_range_bn_bwd": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _f, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_qconv_fwd_bn_stats_workspace_size": (_sz, [C.POINTER(ConvDesc)]),
+    "q8t_qconv_fwd_bn_stats": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_range_bn_fwd_apply": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp]),
     "q8t_range_bn_bwd_bifurcate_workspace_size": (_sz, [_i, _i, _i, _i]),
     "q8t_range_bn_bwd_bifurcate": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _f, _vp, _vp, _vp, _u64, _u64, _vp, _vp,
                                         _vp, _vp, _vp, _vp]),
@@ -239,6 +242,21 @@ def qconv_fwd(d, qx, px, qw, pw, want_acc=False, out=None, ws=None):
                  want_acc, out, ws)
 
 
+def qconv_fwd_bn_stats(d, qx, px, qw, pw, want_acc=False, out=None, stats_out=None, ws=None):
+    """Forward convolution + Range BN statistics of its result.  Returns (y, acc or None, stats[3,K])."""
+    _dev(qx), _dev(qw)
+    assert tuple(qx.shape) == (d.N, d.C, d.H, d.W) and tuple(qw.shape) == (d.K, d.C, d.R, d.S)
+    dev = qx.device
+    shape = (d.N, d.K, d.P, d.Q)
+    y = out if out is not None else torch.empty(shape, dtype=torch.float32, device=dev)
+    acc = torch.empty(shape, dtype=torch.int32, device=dev) if want_acc else None
+    stats = stats_out if stats_out is not None else torch.empty((3, d.K), dtype=torch.float32, device=dev)
+    ws = ws if ws is not None else workspace(_lib.q8t_qconv_fwd_bn_stats_workspace_size(C.byref(d)), dev)
+    _check(_lib.q8t_qconv_fwd_bn_stats(C.byref(d), _ptr(qx), _ptr(px), _ptr(qw), _ptr(pw), _ptr(y), _ptr(acc),
+                                       _ptr(stats), _ptr(ws), _stream()), "q8t_qconv_fwd_bn_stats")
+    return y, acc, stats
+
+
 def qconv_dgrad(d, qdy, pg, qw, pw, want_acc=False, out=None, ws=None):
     _dev(qdy), _dev(qw)
     assert tuple(qdy.shape) == (d.N, d.K, d.P, d.Q) and tuple(qw.shape) == (d.K, d.C, d.R, d.S)
@@ -271,6 +289,22 @@ def range_bn_fwd(x, gamma=None, beta=None, eps=0.0, quantized=False, want_y=True
     _check(_lib.q8t_range_bn_fwd(_ptr(x), N, Cc, H, W, _ptr(gamma), _ptr(beta), float(eps), _ptr(y), _ptr(stats),
                                  _ptr(q), _ptr(qp), _ptr(ws), _stream()), "q8t_range_bn_fwd")
     return y, stats, q, qp
+
+
+def range_bn_fwd_apply(x, stats, gamma=None, beta=None, eps=0.0, quantized=False, want_y=True, y_out=None, q_out=None,
+                       qp_out=None):
+    """Range BN forward from given statistics.  Returns (y or None, q or None, qp or None)."""
+    _dev(x), _dev(stats)
+    N, Cc, H, W = x.shape
+    dev = x.device
+    y = y_out if y_out is not None else (torch.empty_like(x) if want_y else None)
+    q = qp = None
+    if quantized:
+        q = q_out if q_out is not None else torch.empty(x.shape, dtype=torch.int8, device=dev)
+        qp = qp_out if qp_out is not None else new_qparams(dev)
+    _check(_lib.q8t_range_bn_fwd_apply(_ptr(x), N, Cc, H, W, _ptr(gamma), _ptr(beta), float(eps), _ptr(stats), _ptr(y),
+                                       _ptr(q), _ptr(qp), _stream()), "q8t_range_bn_fwd_apply")
+    return y, q, qp
 
 
 def range_bn_bwd(x, dy, stats, gamma=None, eps=0.0, dx_out=None, ws=None):

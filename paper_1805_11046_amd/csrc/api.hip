@@ -82,10 +82,36 @@ int q8t_qconv_fwd(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams
     const int rc = q8t_conv_reduction_check(0, desc);
     if (rc) return rc;
     if (q8t_fast_conv_supported(0, desc, qx, qw, y, acc_out))
-        return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
+        return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, nullptr, ws, (hipStream_t)stream);
     if (q8t_nhwc_conv_supported(0, desc))
         return q8t_nhwc_conv(0, desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
     return q8t_generic_conv(0, desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
+}
+
+size_t q8t_qconv_fwd_bn_stats_workspace_size(const q8t_conv_desc *desc)
+{
+    if (!desc || desc->stride < 1) return 0;
+    const int P = (desc->H + 2 * desc->pad - desc->R) / desc->stride + 1, Q = (desc->W + 2 * desc->pad - desc->S) / desc->stride + 1;
+    const size_t c = (q8t_qconv_workspace_size(desc, 0) + 255) & ~(size_t)255;
+    return c + q8t_range_bn_workspace_size(desc->N, desc->K, P, Q);
+}
+
+int q8t_qconv_fwd_bn_stats(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams *px, const int8_t *qw,
+                           const q8t_qparams *pw, float *y, int32_t *acc_out, float *stats_out, void *ws, void *stream)
+{
+    if (!desc || !qx || !px || !qw || !pw || !y || !stats_out) return Q8T_ERR_NULL;
+    const int rc = q8t_conv_reduction_check(0, desc);
+    if (rc) return rc;
+    if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    // the specialised kernel gathers the statistics in its epilogue; other shapes run the product
+    // and then the statistics pass of the Range BN over its result
+    if (q8t_fast_conv_supported(0, desc, qx, qw, y, acc_out))
+        return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, stats_out, ws, (hipStream_t)stream);
+    const int rc2 = q8t_qconv_fwd(desc, qx, px, qw, pw, y, acc_out, ws, stream);
+    if (rc2) return rc2;
+    const int P = (desc->H + 2 * desc->pad - desc->R) / desc->stride + 1, Q = (desc->W + 2 * desc->pad - desc->S) / desc->stride + 1;
+    void *bnws = (char *)ws + ((q8t_qconv_workspace_size(desc, 0) + 255) & ~(size_t)255);
+    return q8t_range_bn_stats(y, desc->N, desc->K, P, Q, stats_out, bnws, (hipStream_t)stream);
 }
 
 int q8t_qconv_dgrad(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qparams *pg, const int8_t *qw,
@@ -95,7 +121,7 @@ int q8t_qconv_dgrad(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qpar
     const int rc = q8t_conv_reduction_check(1, desc);
     if (rc) return rc;
     if (q8t_fast_conv_supported(1, desc, qdy, qw, dx, acc_out))
-        return q8t_fast_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, ws, (hipStream_t)stream);
+        return q8t_fast_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, nullptr, ws, (hipStream_t)stream);
     if (q8t_nhwc_conv_supported(1, desc))
         return q8t_nhwc_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, ws, (hipStream_t)stream);
     return q8t_generic_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, ws, (hipStream_t)stream);

@@ -120,6 +120,14 @@ __device__ __forceinline__ int dot4_ones(int v, int acc) { return __builtin_amdg
 // it in sub-tiles of 256 rows.  Consecutive workgroup ids go round-robin over the 8 XCDs, so the
 // ranges are dealt out such that each XCD works on one contiguous stretch of the tensor
 // (neighbouring ranges share halo rows, and then an L2).
+// Per-workgroup statistics of the corrected integer outputs of one output channel, for the Range
+// BN that follows the convolution (Sec. 3; Sec. 4 notes that the normalizer already knows the
+// range).  y = scale*acc is monotone in acc, so min/max of y are the images of these.
+struct ConvStat {
+    long long sum;
+    int mn, mx;
+};
+
 struct Sched {
     int nbx;          // workgroups along the rows (multiple of 8)
     int rpb;          // rows per workgroup (multiple of 16)
@@ -133,16 +141,20 @@ struct Sched {
 // zero point:  A(b,p,q) = b*(H+1)*(W+1) + (p+1)*(W+1) + q.  A filter tap is then the constant
 // row offset dr*(W+1) + ds for every output position, borders included -- no per-lane masks.
 // WC > 0 fixes a square image size at compile time (cheap index arithmetic, immediate offsets).
-template <int TAPS, int WC, bool V16>
+template <int TAPS, int WC, bool V16, bool STATS>
 __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__restrict__ x,
                                                               const int8_t *__restrict__ wpk,
                                                               const int *__restrict__ colsum,
                                                               const q8t_qparams *__restrict__ qpa,
                                                               const q8t_qparams *__restrict__ qpb,
                                                               const FastGeom g, const Sched sch,
-                                                              float *__restrict__ y, int32_t *__restrict__ acc_out)
+                                                              float *__restrict__ y, int32_t *__restrict__ acc_out,
+                                                              ConvStat *__restrict__ bnpart)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    // per-channel statistics of this workgroup's outputs (integer accumulators: exact, order-free)
+    __shared__ unsigned long long st_sum[STATS ? CH : 1];
+    __shared__ int st_min[STATS ? CH : 1], st_max[STATS ? CH : 1];
     constexpr int A_BYTES = (TAPS == 9 ? MAXR9 : MAXR1) * ROWB;
     constexpr int B_PIECES = TAPS * CH * 4;            // 16-byte pieces of the weight chunk
     constexpr int B_VEC = (B_PIECES + kThreads - 1) / kThreads;
@@ -160,6 +172,11 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
     if (row_begin >= row_end) return;
     const int occ = blockIdx.y;  // output-channel chunk
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (STATS && tid < CH) {
+        st_sum[tid] = 0ull;
+        st_min[tid] = 2147483647;
+        st_max[tid] = -2147483647 - 1;
+    }
     const int l16 = lane & 15, kb = lane >> 4;
 
     const int za = qpa->zero_point - (1 << (qpa->bits - 1)), zb = qpb->zero_point - (1 << (qpb->bits - 1));
@@ -387,7 +404,8 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             const int gr = g0 + (mt * kWaves + wave) * 16 + kb * 4;
-            if (gr >= g1) continue;
+            const bool ok = gr < g1;
+            if (!STATS && !ok) continue;   // with statistics every lane stays for the wavefront shuffles
             const uint32_t b = divc<PQC>((uint32_t)gr, g.dPQ);
             const uint32_t pos = (uint32_t)gr - b * PQ;
             uint32_t t[4];
@@ -401,6 +419,25 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
                 const int c1 = (int)((uint32_t)acc[mt][nt][1] + t[1] - csn[nt]);
                 const int c2 = (int)((uint32_t)acc[mt][nt][2] + t[2] - csn[nt]);
                 const int c3 = (int)((uint32_t)acc[mt][nt][3] + t[3] - csn[nt]);
+                if (STATS) {
+                    // fold the 4 row groups (lanes 16 apart) inside the wavefront, then one LDS atomic per
+                    // channel; row groups past the end of the tile contribute neutral values
+                    long long sv = ok ? (long long)c0 + c1 + c2 + c3 : 0ll;
+                    int a = ok ? min(min(c0, c1), min(c2, c3)) : 2147483647;
+                    int bq = ok ? max(max(c0, c1), max(c2, c3)) : -2147483647 - 1;
+                    sv += __shfl_xor(sv, 16, 64);
+                    a = min(a, __shfl_xor(a, 16, 64));
+                    bq = max(bq, __shfl_xor(bq, 16, 64));
+                    sv += __shfl_xor(sv, 32, 64);
+                    a = min(a, __shfl_xor(a, 32, 64));
+                    bq = max(bq, __shfl_xor(bq, 32, 64));
+                    if (kb == 0) {
+                        atomicAdd(&st_sum[nt * 16 + l16], (unsigned long long)sv);
+                        atomicMin(&st_min[nt * 16 + l16], a);
+                        atomicMax(&st_max[nt * 16 + l16], bq);
+                    }
+                }
+                if (STATS && !ok) continue;
                 if (acc_out) *reinterpret_cast<int4 *>(acc_out + o) = make_int4(c0, c1, c2, c3);
                 if (y) {
                     float4 f;
@@ -412,6 +449,58 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
                 }
             }
         }
+    }
+    if (STATS) {
+        __syncthreads();
+        if (tid < CH) {
+            ConvStat r;
+            r.sum = (long long)st_sum[tid];
+            r.mn = st_min[tid];
+            r.mx = st_max[tid];
+            bnpart[((size_t)occ * sch.nbx + bidx) * CH + tid] = r;
+        }
+    }
+}
+
+// statistics of the float outputs from the integer partials: stats[0][k] = mean, [1] = min, [2] = max
+// with y = scale * (float)acc as in the epilogue above (so min / max are bit-identical to a scan of y)
+__global__ __launch_bounds__(256) void conv_stats_finalize(const ConvStat *__restrict__ bnpart, int K, int nbx, int nact,
+                                                           double n, const q8t_qparams *__restrict__ qpa,
+                                                           const q8t_qparams *__restrict__ qpb, float *__restrict__ stats)
+{
+    // one workgroup per output channel; its threads share the workgroups of the convolution
+    __shared__ long long ssum[4];
+    __shared__ int smn[4], smx[4];
+    const int k = blockIdx.x;
+    const int occ = k / CH, ch = k - occ * CH;
+    long long s = 0;
+    int mn = 2147483647, mx = -2147483647 - 1;
+    for (int b = threadIdx.x; b < nact; b += 256) {
+        const ConvStat r = bnpart[((size_t)occ * nbx + b) * CH + ch];
+        s += r.sum;
+        mn = min(mn, r.mn);
+        mx = max(mx, r.mx);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        s += __shfl_xor(s, off, 64);
+        mn = min(mn, __shfl_xor(mn, off, 64));
+        mx = max(mx, __shfl_xor(mx, off, 64));
+    }
+    if ((threadIdx.x & 63) == 0) {
+        ssum[threadIdx.x >> 6] = s;
+        smn[threadIdx.x >> 6] = mn;
+        smx[threadIdx.x >> 6] = mx;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        s = ssum[0] + ssum[1] + ssum[2] + ssum[3];
+        mn = min(min(smn[0], smn[1]), min(smn[2], smn[3]));
+        mx = max(max(smx[0], smx[1]), max(smx[2], smx[3]));
+        const float sc = qpa->scale * qpb->scale;
+        stats[k] = (float)((double)sc * (double)s / n);
+        stats[K + k] = sc * (float)mn;
+        stats[2 * K + k] = sc * (float)mx;
     }
 }
 
@@ -465,35 +554,41 @@ size_t q8t_fast_conv_ws(int which, const q8t_conv_desc *d)
     if (!shape_ok(which, d)) return 0;
     const size_t wbytes = (size_t)d->K * d->C * d->R * d->S;
     const int oc = which == 0 ? d->K : d->C;
-    return ((wbytes + 255) & ~(size_t)255) + (size_t)oc * sizeof(int);
+    // packed filter, column sums, per-workgroup statistics (at most 512 workgroups per channel chunk)
+    return ((wbytes + 255) & ~(size_t)255) + (((size_t)oc * sizeof(int) + 255) & ~(size_t)255) +
+           (size_t)oc * 512 * sizeof(ConvStat);
 }
 
-template <int TAPS, int WC, bool V16>
+template <int TAPS, int WC, bool V16, bool STATS>
 int launch_conv(dim3 grid, hipStream_t st, const int8_t *a, const int8_t *wpk, const int *colsum,
                 const q8t_qparams *qa, const q8t_qparams *qb, const FastGeom &g, const Sched &sch, float *out_f,
-                int32_t *out_acc)
+                int32_t *out_acc, ConvStat *bnpart)
 {
     static bool attr = false;
     if (!attr && smem_bytes<TAPS>() > 65536) {
-        if (hipFuncSetAttribute((const void *)conv_s1_kernel<TAPS, WC, V16>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute((const void *)conv_s1_kernel<TAPS, WC, V16, STATS>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)smem_bytes<TAPS>()) != hipSuccess)
             return Q8T_ERR_HIP;
         attr = true;
     }
-    hipLaunchKernelGGL((conv_s1_kernel<TAPS, WC, V16>), grid, dim3(kThreads), smem_bytes<TAPS>(), st, a, wpk, colsum, qa,
-                       qb, g, sch, out_f, out_acc);
+    hipLaunchKernelGGL((conv_s1_kernel<TAPS, WC, V16, STATS>), grid, dim3(kThreads), smem_bytes<TAPS>(), st, a, wpk, colsum, qa,
+                       qb, g, sch, out_f, out_acc, bnpart);
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
 }
 
 int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
-                  const q8t_qparams *qb, float *out_f, void *out_acc, void *ws, hipStream_t st)
+                  const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *ws, hipStream_t st)
 {
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
     const int taps = d->R * d->S;
     const size_t wbytes = (size_t)d->K * d->C * taps;
+    const int oc_all = which == 0 ? d->K : d->C;
     int8_t *wpk = (int8_t *)ws;
     int *colsum = (int *)((char *)ws + ((wbytes + 255) & ~(size_t)255));
+    ConvStat *bnpart = bn_stats ? (ConvStat *)((char *)colsum + (((size_t)oc_all * sizeof(int) + 255) & ~(size_t)255))
+                                : (ConvStat *)nullptr;
+    int rc = 0;
     FastGeom g;
     g.N = d->N;
     g.H = d->H;
@@ -527,7 +622,12 @@ int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
     const int8_t *pa = (const int8_t *)a;
     int32_t *pacc = (int32_t *)out_acc;
     const bool sq = d->H == d->W;
-#define Q8T_CONV(T, WCV, V) return launch_conv<T, WCV, V>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc)
+#define Q8T_CONV(T, WCV, V)                                                                                          \
+    {                                                                                                                \
+        rc = bnpart ? launch_conv<T, WCV, V, true>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc, bnpart)   \
+                    : launch_conv<T, WCV, V, false>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc, bnpart); \
+        goto launched;                                                                                               \
+    }
     if (taps == 9) {
         if (sq && d->W == 56 && v16) Q8T_CONV(9, 56, true);
         if (sq && d->W == 28 && v16) Q8T_CONV(9, 28, true);
@@ -539,5 +639,14 @@ int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
     if (v16) Q8T_CONV(1, 0, true);
     Q8T_CONV(1, 0, false);
 #undef Q8T_CONV
+launched:
+    if (rc) return rc;
+    if (bn_stats) {
+        const int nact = (g.M + sch.rpb - 1) / sch.rpb;
+        hipLaunchKernelGGL(conv_stats_finalize, dim3((unsigned)g.K), dim3(256), 0, st, bnpart, g.K, nbx, nact,
+                           (double)g.M, qa, qb, bn_stats);
+        Q8T_LAUNCH_CHECK();
+    }
+    return Q8T_OK;
 }
 

@@ -18,8 +18,12 @@ int q8t_conv_reduction_check(int which, const q8t_conv_desc *d);
 bool q8t_fast_conv_supported(int which, const q8t_conv_desc *d, const void *a, const void *b, const void *out_f,
                              const void *out_acc);
 size_t q8t_fast_conv_ws(int which, const q8t_conv_desc *d);
+// bn_stats (nullable, forward only): [3][K] mean / min / max of the float result per output channel
 int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
-                  const q8t_qparams *qb, float *out_f, void *out_acc, void *ws, hipStream_t st);
+                  const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *ws, hipStream_t st);
+
+// Range BN statistics of an NCHW tensor alone (range_bn.hip); ws as for q8t_range_bn_fwd
+int q8t_range_bn_stats(const float *x, int N, int C, int H, int W, float *stats_out, void *ws, hipStream_t st);
 
 // general MFMA path over a channel-contiguous copy of the operand (conv_nhwc.hip): forward and
 // layer gradient, channel counts that are multiples of 64

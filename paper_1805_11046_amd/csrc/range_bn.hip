@@ -156,6 +156,27 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_finalize(const FwdPartial *__
     }
 }
 
+// per-tensor range of the 8-bit output from ready-made statistics (one workgroup)
+__global__ __launch_bounds__(kThreads) void bn_qrange_from_stats(const float *__restrict__ stats, int C, float cn, float eps,
+                                                                 const float *__restrict__ gamma,
+                                                                 const float *__restrict__ beta,
+                                                                 q8t_qparams *__restrict__ qp_out)
+{
+    __shared__ float smf[kThreads / 64];
+    float lo = INFINITY, hi = -INFINITY;
+    for (int c = threadIdx.x; c < C; c += kThreads) {
+        const float mu = stats[c], mn = stats[C + c], mx = stats[2 * C + c];
+        const float g = gamma ? gamma[c] : 1.0f, b = beta ? beta[c] : 0.0f;
+        const float inv = bn_inv(mn, mx, cn, eps);
+        const float a = bn_map(mn, mu, inv, g, b), z = bn_map(mx, mu, inv, g, b);
+        lo = fminf(lo, fminf(a, z));
+        hi = fmaxf(hi, fmaxf(a, z));
+    }
+    lo = block_min_f(lo, smf);
+    hi = block_max_f(hi, smf);
+    if (threadIdx.x == 0) *qp_out = make_qparams(lo, hi, 8);
+}
+
 // ---- forward, pass 2 ----------------------------------------------------------------------------
 // one (image, channel) plane per workgroup iteration
 // fold the slices of one channel inside a wavefront (lane k holds slice k; fixed butterfly order,
@@ -535,6 +556,46 @@ int q8t_range_bn_fwd(const float *x, int N, int C, int H, int W, const float *ga
     return Q8T_OK;
 }
 
+// Forward with statistics that something else already produced (the convolution epilogue):
+// normalization (and 8-bit output) only, one pass over x.
+int q8t_range_bn_fwd_apply(const float *x, int N, int C, int H, int W, const float *gamma, const float *beta, float eps,
+                           const float *stats, float *y, int8_t *q_out, q8t_qparams *qp_out, void *stream)
+{
+    const int rc = check_shape(N, C, H, W);
+    if (rc) return rc;
+    if (!x || !stats || (!y && !q_out) || (q_out && !qp_out)) return Q8T_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    const int HW = H * W;
+    const double n = (double)N * HW;
+    const float cn = (float)q8t_range_bn_scale((int64_t)N * HW);
+    const bool vec = (HW % 4 == 0) && q8t_aligned(x, 16) && (!y || q8t_aligned(y, 16)) &&
+                     (!q_out || q8t_aligned(q_out, 4));
+    if (q_out) {
+        hipLaunchKernelGGL(bn_qrange_from_stats, dim3(1), dim3(kThreads), 0, st, stats, C, cn, eps, gamma, beta, qp_out);
+        Q8T_LAUNCH_CHECK();
+    }
+    float *stats_rw = const_cast<float *>(stats);   // only read when no partial sums are passed
+    const FwdPartial *fparts = nullptr;
+    const int64_t planes = (int64_t)N * C;
+    if (HW >= 256) {
+        const dim3 grid(planes_grid(planes));
+#define Q8T_GO(V, Q) \
+    hipLaunchKernelGGL((bn_fwd_apply<V, Q>), grid, dim3(kThreads), 0, st, x, planes, C, HW, stats_rw, fparts, 1, n, gamma, beta, cn, eps, y, q_out, qp_out)
+        if (vec) { if (q_out) Q8T_GO(true, true); else Q8T_GO(true, false); }
+        else     { if (q_out) Q8T_GO(false, true); else Q8T_GO(false, false); }
+#undef Q8T_GO
+    } else {
+        const int64_t total = planes * HW;
+        const dim3 grid((unsigned)((total + kThreads - 1) / kThreads < 65536 * 16 ? (total + kThreads - 1) / kThreads : 65536 * 16));
+        if (q_out)
+            hipLaunchKernelGGL(bn_fwd_apply_flat<true>, grid, dim3(kThreads), 0, st, x, total, C, HW, stats_rw, gamma, beta, cn, eps, y, q_out, qp_out);
+        else
+            hipLaunchKernelGGL(bn_fwd_apply_flat<false>, grid, dim3(kThreads), 0, st, x, total, C, HW, stats_rw, gamma, beta, cn, eps, y, q_out, qp_out);
+    }
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
+
 static int range_bn_bwd_impl(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
                              const float *gamma, float eps, float *dx, float *dgamma, float *dbeta, void *ws,
                              void *stream, float2 *mm_out, int *mm_count)
@@ -615,3 +676,8 @@ int q8t_range_bn_bwd_bifurcate(const float *x, const float *dy, const float *sta
 }
 
 }  // extern "C"
+
+int q8t_range_bn_stats(const float *x, int N, int C, int H, int W, float *stats_out, void *ws, hipStream_t st)
+{
+    return q8t_range_bn_fwd(x, N, C, H, W, nullptr, nullptr, 0.0f, nullptr, stats_out, nullptr, nullptr, ws, (void *)st);
+}

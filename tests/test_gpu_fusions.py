@@ -1,0 +1,82 @@
+"""GPU parity of the fused calls: convolution forward that also returns the Range BN statistics
+of its result, and Range BN forward from given statistics (normalization pass only)."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_util import close, dev, host, qp_dev_from, require_gpu, same_ints, same_qparams
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    (3, 64, 56, 56, 64, 3, 3, 1, 1),     # specialised kernel, statistics from its epilogue
+    (2, 64, 14, 14, 64, 3, 3, 1, 1),
+    (9, 64, 14, 14, 128, 3, 3, 1, 1),    # two output-channel chunks
+    (2, 256, 10, 10, 64, 1, 1, 1, 0),
+    (40, 64, 6, 6, 64, 3, 3, 1, 1),      # more workgroups than rows to give them: inactive ones must not count
+    (2, 64, 16, 16, 128, 3, 3, 2, 1),    # other shapes: product, then the statistics pass
+    (2, 3, 7, 6, 4, 3, 3, 1, 1),
+]
+
+
+def _rand_q(g, shape, bits=8):
+    half = 2 ** (bits - 1)
+    lv = g.integers(0, 2 ** bits, size=shape)
+    qp = oracle.QParams(0.0, 0.0, float(np.float32(g.uniform(0.01, 0.1))), 1.0, int(g.integers(0, 2 ** bits)), bits)
+    return (lv - half).astype(np.int8), qp
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_conv_forward_with_range_bn_statistics(case):
+    q8t = require_gpu()
+    g = synth.rng(1000 + sum(case))
+    N, C, H, W, K, R, S, st, pad = case
+    sx, px = _rand_q(g, (N, C, H, W))
+    sw, pw = _rand_q(g, (K, C, R, S))
+    d, od = q8t.conv_desc(*case), oracle.conv_desc(*case)
+    y, acc, stats = q8t.qconv_fwd_bn_stats(d, dev(sx), qp_dev_from(px), dev(sw), qp_dev_from(pw), want_acc=True)
+    oy, oacc = oracle.qconv_fwd(od, sx, px, sw, pw)
+    same_ints(host(acc), oacc)
+    close(host(y), oy)
+    ost = oracle.range_bn_stats(oy)
+    sth = host(stats)
+    assert np.array_equal(sth[1:], ost[1:])      # min / max: exact
+    close(sth[0], ost[0])                        # mean: fp64 sum in another order
+
+
+def test_conv_statistics_at_full_size_feed_the_normalization():
+    # config-2 layer at batch 128: conv with statistics -> normalization from those statistics,
+    # float and 8-bit outputs, against the oracle run on the GPU's own conv result and statistics
+    q8t = require_gpu()
+    case = (128, 64, 56, 56, 64, 3, 3, 1, 1)
+    x, w, _ = synth.conv_layer(seed=11, N=128)
+    qx, px = q8t.quantize(dev(x), 8)
+    qw, pw = q8t.quantize(dev(w), 8)
+    d = q8t.conv_desc(*case)
+    y, _, stats = q8t.qconv_fwd_bn_stats(d, qx, px, qw, pw)
+    yh, sth = host(y), host(stats)
+    ost = oracle.range_bn_stats(yh)
+    assert np.array_equal(sth[1:], ost[1:])
+    close(sth[0], ost[0])
+    bn, q, qp = q8t.range_bn_fwd_apply(y, stats, eps=1e-5, quantized=True)
+    obn, _, oq, oqp = oracle.range_bn_fwd(yh, eps=1e-5, stats=sth, quantized=True)
+    same_ints(host(bn), obn)
+    same_qparams(q8t, qp, oqp)
+    same_ints(host(q), oq)
+
+
+@pytest.mark.parametrize("shape", [(6, 7, 16, 16), (3, 2, 40, 36), (4, 5, 3, 3), (64, 128, 1, 1)])
+def test_range_bn_forward_from_given_statistics(shape):
+    q8t = require_gpu()
+    x, _ = synth.range_bn_input(sum(shape), *shape)
+    g = synth.rng(7)
+    gamma = g.uniform(-1.5, 1.5, size=shape[1]).astype(np.float32)
+    beta = g.uniform(-0.5, 0.5, size=shape[1]).astype(np.float32)
+    _, stats, _, _ = q8t.range_bn_fwd(dev(x), dev(gamma), dev(beta), 1e-5)
+    sth = host(stats)
+    y, q, qp = q8t.range_bn_fwd_apply(dev(x), stats, dev(gamma), dev(beta), 1e-5, quantized=True)
+    oy, _, oq, oqp = oracle.range_bn_fwd(x, gamma, beta, 1e-5, stats=sth, quantized=True)
+    same_ints(host(y), oy)
+    same_qparams(q8t, qp, oqp)
+    same_ints(host(q), oq)
