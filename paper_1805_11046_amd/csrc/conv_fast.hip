@@ -404,8 +404,7 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             const int gr = g0 + (mt * kWaves + wave) * 16 + kb * 4;
-            const bool ok = gr < g1;
-            if (!STATS && !ok) continue;   // with statistics every lane stays for the wavefront shuffles
+            if (gr >= g1) continue;
             const uint32_t b = divc<PQC>((uint32_t)gr, g.dPQ);
             const uint32_t pos = (uint32_t)gr - b * PQ;
             uint32_t t[4];
@@ -420,24 +419,13 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
                 const int c2 = (int)((uint32_t)acc[mt][nt][2] + t[2] - csn[nt]);
                 const int c3 = (int)((uint32_t)acc[mt][nt][3] + t[3] - csn[nt]);
                 if (STATS) {
-                    // fold the 4 row groups (lanes 16 apart) inside the wavefront, then one LDS atomic per
-                    // channel; row groups past the end of the tile contribute neutral values
-                    long long sv = ok ? (long long)c0 + c1 + c2 + c3 : 0ll;
-                    int a = ok ? min(min(c0, c1), min(c2, c3)) : 2147483647;
-                    int bq = ok ? max(max(c0, c1), max(c2, c3)) : -2147483647 - 1;
-                    sv += __shfl_xor(sv, 16, 64);
-                    a = min(a, __shfl_xor(a, 16, 64));
-                    bq = max(bq, __shfl_xor(bq, 16, 64));
-                    sv += __shfl_xor(sv, 32, 64);
-                    a = min(a, __shfl_xor(a, 32, 64));
-                    bq = max(bq, __shfl_xor(bq, 32, 64));
-                    if (kb == 0) {
-                        atomicAdd(&st_sum[nt * 16 + l16], (unsigned long long)sv);
-                        atomicMin(&st_min[nt * 16 + l16], a);
-                        atomicMax(&st_max[nt * 16 + l16], bq);
-                    }
+                    // every lane adds its 4 rows straight into the workgroup's LDS slots (4 lanes per
+                    // channel collide; cheaper than folding them first through cross-lane moves, which
+                    // occupy the same LDS pipe)
+                    atomicAdd(&st_sum[nt * 16 + l16], (unsigned long long)((long long)c0 + c1 + c2 + c3));
+                    atomicMin(&st_min[nt * 16 + l16], min(min(c0, c1), min(c2, c3)));
+                    atomicMax(&st_max[nt * 16 + l16], max(max(c0, c1), max(c2, c3)));
                 }
-                if (STATS && !ok) continue;
                 if (acc_out) *reinterpret_cast<int4 *>(acc_out + o) = make_int4(c0, c1, c2, c3);
                 if (y) {
                     float4 f;
