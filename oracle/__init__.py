@@ -136,6 +136,24 @@ def dequantize(stored, qp):
     return out
 
 
+def quant_angle(x, stored, qp):
+    """Sec. 3 eq. (1).  Returns (x.Q(x), |x|^2, |Q(x)|^2, cos(theta)) as fp64."""
+    x = _f32(x)
+    stored = np.ascontiguousarray(stored, dtype=_stored_dtype(qp.bits))
+    assert x.size == stored.size
+    out = np.empty(4, np.float64)
+    lib().orc_quant_angle(_p(x), _p(stored), C.byref(qp), C.c_int64(x.size), _p(out))
+    return tuple(float(v) for v in out)
+
+
+def chunk_range(x, K):
+    """App. B: clamping range averaged over K contiguous chunks.  Returns (vmin, vmax) as fp32."""
+    x = _f32(x)
+    out = np.empty(2, np.float32)
+    lib().orc_chunk_range(_p(x), C.c_int64(x.size), C.c_int(int(K)), _p(out))
+    return np.float32(out[0]), np.float32(out[1])
+
+
 def _i8(a):
     return np.ascontiguousarray(a, dtype=np.int8)
 

@@ -210,6 +210,55 @@ void orc_dequantize(const void *stored, const orc_qparams *qp, int64_t n, float 
     }
 }
 
+/* Sec. 3, eq. (1): cosine of the angle between a tensor and its quantized copy,
+ * cos(theta) = (x . Q(x)) / (||x||_2 ||Q(x)||_2), with Q(x) the dequantized value of the stored
+ * code (fp32, as orc_dequantize returns it).  All three sums in fp64, index order.
+ * out[0] = x.Q(x), out[1] = ||x||^2, out[2] = ||Q(x)||^2, out[3] = cos(theta) (0 if a norm is 0). */
+void orc_quant_angle(const float *x, const void *stored, const orc_qparams *qp, int64_t n, double *out)
+{
+    int32_t half = 1 << (qp->bits - 1);
+    double dot = 0.0, nx = 0.0, nq = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        int32_t s = (qp->bits <= 8) ? (int32_t)((const int8_t *)stored)[i]
+                                    : (int32_t)((const int16_t *)stored)[i];
+        float xq = qp->scale * (float)(s + half - qp->zero_point);
+        dot += (double)x[i] * (double)xq;
+        nx += (double)x[i] * (double)x[i];
+        nq += (double)xq * (double)xq;
+    }
+    out[0] = dot;
+    out[1] = nx;
+    out[2] = nq;
+    out[3] = (nx > 0.0 && nq > 0.0) ? dot / sqrt(nx * nq) : 0.0;
+}
+
+/* App. B, clamping values of the activations: "the average of absolute maximum and minimum
+ * values of K chunks".  The flat tensor is cut into K contiguous chunks of ceil(n/K) elements
+ * (the last one may be shorter; when K does not divide n, chunks that would start past the end do
+ * not exist and are not counted); vmax = mean over chunks of the chunk maximum, vmin = mean of the
+ * chunk minimum.  The K values are summed in fp64 in chunk order and the mean is rounded
+ * to fp32 once.  range_out[0] = vmin, range_out[1] = vmax. */
+void orc_chunk_range(const float *x, int64_t n, int K, float *range_out)
+{
+    int64_t len = (n + K - 1) / K;
+    double smin = 0.0, smax = 0.0;
+    int used = 0;
+    for (int k = 0; k < K; ++k) {
+        int64_t lo = (int64_t)k * len, hi = lo + len < n ? lo + len : n;
+        if (lo >= hi) break;
+        float mn = x[lo], mx = x[lo];
+        for (int64_t i = lo + 1; i < hi; ++i) {
+            if (x[i] < mn) mn = x[i];
+            if (x[i] > mx) mx = x[i];
+        }
+        smin += (double)mn;
+        smax += (double)mx;
+        ++used;
+    }
+    range_out[0] = (float)(smin / (double)used);
+    range_out[1] = (float)(smax / (double)used);
+}
+
 /* stored code (int8 or int16) -> level minus zero point */
 static inline int32_t orc_centered8(const int8_t *s, int64_t i, const orc_qparams *qp)
 {
