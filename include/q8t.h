@@ -78,6 +78,28 @@ int q8t_quantize(const float *x, int64_t n, int bits, int stochastic, uint64_t s
 int q8t_quantize_with_range(const float *x, int64_t n, int bits, int stochastic, uint64_t seed,
                             const float *vmin_vmax, void *q_out, q8t_qparams *qp_out, void *stream);
 
+/* Clamping range of an activation tensor averaged over chunks (Appendix B, "Quantization methods":
+ * the clamping values of the activations are the average of the maximum and of the minimum over K
+ * chunks).  The flat tensor is cut into K contiguous chunks of ceil(n/K) elements (the last may be
+ * shorter; chunks that would start past the end do not exist and are not counted).
+ * range_out: 2 device floats {vmin, vmax} = fp32(mean of the chunk minima), fp32(mean of the chunk
+ * maxima), each mean taken in fp64 in chunk order.  Feed it to q8t_quantize_with_range: values
+ * outside saturate.  1 <= K <= min(n, 65535).  Workspace: device,
+ * q8t_chunk_range_workspace_size(n, K) bytes, 8-byte aligned.
+ * Errors: Q8T_ERR_SHAPE (n, K), Q8T_ERR_NULL, Q8T_ERR_WORKSPACE, Q8T_ERR_HIP. */
+size_t q8t_chunk_range_workspace_size(int64_t n, int K);
+int q8t_chunk_range(const float *x, int64_t n, int K, float *range_out, void *ws, void *stream);
+
+/* Angle between a tensor and its quantized copy (Section 3, eq. (1)):
+ * cos(theta) = (x . Q(x)) / (||x||_2 ||Q(x)||_2), Q(x) = scale * (level - zero_point) of the stored
+ * codes q (int8 for qp->bits <= 8, else int16; as q8t_dequantize returns them).
+ * out: 4 device doubles { x.Q(x), ||x||^2, ||Q(x)||^2, cos(theta) } (cos = 0 if a norm is 0); sums
+ * in fp64.  Workspace: device, q8t_quant_angle_workspace_size(n) bytes, 8-byte aligned.
+ * Errors: Q8T_ERR_SHAPE, Q8T_ERR_NULL, Q8T_ERR_WORKSPACE, Q8T_ERR_HIP. */
+size_t q8t_quant_angle_workspace_size(int64_t n);
+int q8t_quant_angle(const float *x, const void *q, const q8t_qparams *qp, int64_t n, double *out, void *ws,
+                    void *stream);
+
 /* Gradient bifurcation (Section 1; Section 7): one pass over g yields the 8-bit copy that feeds
  * the layer gradient and the 16-bit copy that feeds the weight gradient.  Both share g's min/max
  * and use stochastic rounding with their own seeds.  ws: q8t_quantize_workspace_size(n). */

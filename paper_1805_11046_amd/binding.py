@@ -62,6 +62,10 @@ _SIGS = {
     "q8t_range_bn_workspace_size": (_sz, [_i, _i, _i, _i]),
     "q8t_range_bn_fwd": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _vp]),
     "q8t_range_bn_bwd": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _f, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_chunk_range_workspace_size": (_sz, [_i64, _i]),
+    "q8t_chunk_range": (_i, [_vp, _i64, _i, _vp, _vp, _vp]),
+    "q8t_quant_angle_workspace_size": (_sz, [_i64]),
+    "q8t_quant_angle": (_i, [_vp, _vp, _vp, _i64, _vp, _vp, _vp]),
     "q8t_qconv_fwd_bn_stats_workspace_size": (_sz, [C.POINTER(ConvDesc)]),
     "q8t_qconv_fwd_bn_stats": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "q8t_range_bn_fwd_apply": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp]),
@@ -219,6 +223,27 @@ def qgemm_wgrad(qx, px, qdy16, pg16, want_acc=False, out=None, ws=None):
     assert M == M2 and qdy16.dtype == torch.int16
     return _fc(_lib.q8t_qgemm_wgrad, "q8t_qgemm_wgrad", qx, px, qdy16, pg16, M, N, K, (K, N), 2, torch.int64,
                want_acc, out, ws)
+
+
+def chunk_range(x, K, ws=None):
+    """Clamping range averaged over K contiguous chunks (App. B).  Returns a device tensor {vmin, vmax}."""
+    _dev(x)
+    n = x.numel()
+    out = torch.empty(2, dtype=torch.float32, device=x.device)
+    ws = ws if ws is not None else workspace(_lib.q8t_chunk_range_workspace_size(n, int(K)), x.device)
+    _check(_lib.q8t_chunk_range(_ptr(x), n, int(K), _ptr(out), _ptr(ws), _stream()), "q8t_chunk_range")
+    return out
+
+
+def quant_angle(x, q, qp, ws=None):
+    """Sec. 3 eq. (1).  Returns a device tensor of 4 doubles {x.Q(x), |x|^2, |Q(x)|^2, cos(theta)}."""
+    _dev(x), _dev(q)
+    n = x.numel()
+    assert q.numel() == n
+    out = torch.empty(4, dtype=torch.float64, device=x.device)
+    ws = ws if ws is not None else workspace(_lib.q8t_quant_angle_workspace_size(n), x.device)
+    _check(_lib.q8t_quant_angle(_ptr(x), _ptr(q), _ptr(qp), n, _ptr(out), _ptr(ws), _stream()), "q8t_quant_angle")
+    return out
 
 
 # ------------------------------------------------------------------ convolution products
