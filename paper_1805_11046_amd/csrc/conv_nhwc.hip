@@ -98,6 +98,49 @@ __global__ __launch_bounds__(kThreads) void to_nhwc(const int8_t *__restrict__ s
     if (rq == 0 && p0 + rp < HW) chansum[(size_t)n * HW + p0 + rp] = sum;
 }
 
+// Small planes (H*W <= 256): the 64 channels x H*W bytes of one image and channel chunk are one
+// contiguous stretch of the NCHW tensor; it is copied to LDS with 16-byte loads whatever H*W is,
+// and read back transposed.  One workgroup per image walks the channel chunks, so the channel sums
+// stay in registers.
+__global__ __launch_bounds__(kThreads) void to_nhwc_small(const int8_t *__restrict__ src, int C, int HW,
+                                                          int8_t *__restrict__ dst, int *__restrict__ chansum)
+{
+    extern __shared__ __align__(16) int8_t flat[];   // [64][HW]
+    const int n = blockIdx.x, tid = threadIdx.x;
+    const int items = HW * 4;                        // (position, 16-channel quarter), quarter fastest
+    int sum[4] = {0, 0, 0, 0};
+    for (int c0 = 0; c0 < C; c0 += 64) {
+        const uint4 *s4 = reinterpret_cast<const uint4 *>(src + ((size_t)n * C + c0) * HW);
+        for (int i = tid; i < HW * 4; i += kThreads) reinterpret_cast<uint4 *>(flat)[i] = s4[i];   // 64*HW/16 pieces
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int it = tid + k * kThreads;
+            if (it < items) {
+                const int p = it >> 2, q = it & 3;
+                uint32_t w[4];
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const int8_t *b = flat + (q * 16 + d * 4) * HW + p;
+                    w[d] = (uint32_t)(uint8_t)b[0] | ((uint32_t)(uint8_t)b[HW] << 8) | ((uint32_t)(uint8_t)b[2 * HW] << 16) |
+                           ((uint32_t)(uint8_t)b[3 * HW] << 24);
+                }
+                *reinterpret_cast<uint4 *>(dst + ((size_t)n * HW + p) * C + c0 + q * 16) = make_uint4(w[0], w[1], w[2], w[3]);
+                sum[k] += bytesum4(w[0]) + bytesum4(w[1]) + bytesum4(w[2]) + bytesum4(w[3]);
+            }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        int v = sum[k];
+        v += __shfl_xor(v, 1, Q8T_WAVE);
+        v += __shfl_xor(v, 2, Q8T_WAVE);
+        const int it = tid + k * kThreads;
+        if (it < items && (it & 3) == 0) chansum[(size_t)n * HW + (it >> 2)] = v;
+    }
+}
+
 // ---- 2. filter -> [tap][output channel][reduction channel], sums per output channel ------------
 // grid (OC, classes).  which 0: out = k, reduction = c;  which 1: out = c, reduction = k.
 __global__ __launch_bounds__(kThreads) void repack_taps(const int8_t *__restrict__ w, int Kf, int Cf, int R, int S,
@@ -391,7 +434,10 @@ int q8t_nhwc_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
     {
         const int HW = p.IH * p.IW;
         const dim3 grid((unsigned)((HW + 63) / 64), (unsigned)d->N);
-        if (HW % 4 == 0 && q8t_aligned(a, 4))
+        if (HW <= 256 && q8t_aligned(a, 16))
+            hipLaunchKernelGGL(to_nhwc_small, dim3((unsigned)d->N), dim3(kThreads), (size_t)64 * HW, st, (const int8_t *)a,
+                               p.red, HW, xn, chansum);
+        else if (HW % 4 == 0 && q8t_aligned(a, 4))
             hipLaunchKernelGGL(to_nhwc<4>, grid, dim3(kThreads), 0, st, (const int8_t *)a, p.red, HW, xn, chansum);
         else
             hipLaunchKernelGGL(to_nhwc<1>, grid, dim3(kThreads), 0, st, (const int8_t *)a, p.red, HW, xn, chansum);

@@ -166,7 +166,7 @@ template <typename OUT, bool STOCH, bool VEC>
 __global__ __launch_bounds__(kThreads) void quantize_apply(
     const float *__restrict__ x, int64_t n, int bits, uint32_t seed_lo, uint32_t seed_hi,
     const float2 *__restrict__ partials, int npartials, OUT *__restrict__ q_out,
-    q8t_qparams *__restrict__ qp_out, int rev)
+    q8t_qparams *__restrict__ qp_out)
 {
     __shared__ float smem[kThreads / 64];
     float vmin, vmax;
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(kThreads) void quantize_apply(
         const float4 *x4 = reinterpret_cast<const float4 *>(x);
         P *q4 = reinterpret_cast<P *>(q_out);
         const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
-        const int64_t lo = (int64_t)(rev ? gridDim.x - 1 - blockIdx.x : blockIdx.x) * per, hi = min(n4, lo + per);
+        const int64_t lo = (int64_t)blockIdx.x * per, hi = min(n4, lo + per);
         int64_t i = lo + threadIdx.x;
         for (; i + 3 * kThreads < hi; i += 4 * kThreads) {
             const float4 v0 = x4[i], v1 = x4[i + kThreads], v2 = x4[i + 2 * kThreads], v3 = x4[i + 3 * kThreads];
@@ -377,7 +377,7 @@ int launch_apply(const float *x, int64_t n, int bits, int stochastic, uint64_t s
     const int grid = grid_for(vec ? (n >> 2) : n, 4, 2048);
     const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
 #define Q8T_GO(S, V) \
-    hipLaunchKernelGGL((quantize_apply<OUT, S, V>), dim3(grid), dim3(kThreads), 0, st, x, n, bits, lo, hi, partials, npartials, q, qp, getenv("Q8T_DBG_REV") ? 1 : 0)
+    hipLaunchKernelGGL((quantize_apply<OUT, S, V>), dim3(grid), dim3(kThreads), 0, st, x, n, bits, lo, hi, partials, npartials, q, qp)
     if (stochastic) {
         if (vec) Q8T_GO(true, true); else Q8T_GO(true, false);
     } else {

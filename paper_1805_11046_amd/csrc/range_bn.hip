@@ -385,12 +385,11 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply(const float *__restrict
                                                          const double2 *__restrict__ parts, int split, double n,
                                                          float *__restrict__ dgamma, float *__restrict__ dbeta,
                                                          float cn, float eps, float *__restrict__ dx,
-                                                         float2 *__restrict__ mm_out, int rev)
+                                                         float2 *__restrict__ mm_out)
 {
     __shared__ float smf[kThreads / 64];
     float dmn = INFINITY, dmx = -INFINITY;   // range of the dx values this workgroup writes (if asked for)
-    for (int64_t pl0 = blockIdx.x; pl0 < planes; pl0 += gridDim.x) {
-        const int64_t pl = rev ? planes - 1 - pl0 : pl0;
+    for (int64_t pl = blockIdx.x; pl < planes; pl += gridDim.x) {
         const int c = (int)(pl % C);
         const float mn = stats[C + c], mx = stats[2 * C + c];
         const float inv = bn_inv(mn, mx, cn, eps);
@@ -629,14 +628,12 @@ static int range_bn_bwd_impl(const float *x, const float *dy, const float *stats
     const int64_t planes = (int64_t)N * C;
     if (HW >= 256) {
         // with a range output, one (min,max) pair per workgroup: keep the grid at 2048 workgroups
-        int64_t cap = 2048; if (getenv("Q8T_DBG_MMCAP")) cap = atoi(getenv("Q8T_DBG_MMCAP"));
-        const dim3 grid(mm_out ? (unsigned)(planes < cap ? planes : cap) : (unsigned)planes_grid(planes));
+        const dim3 grid(mm_out ? (unsigned)(planes < 2048 ? planes : 2048) : (unsigned)planes_grid(planes));
         if (mm_count) *mm_count = (int)grid.x;
-        if (getenv("Q8T_DBG_NOMM")) mm_out = nullptr;
         if (vec)
-            hipLaunchKernelGGL(bn_bwd_apply<true>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx, mm_out, getenv("Q8T_DBG_REV") ? 1 : 0);
+            hipLaunchKernelGGL(bn_bwd_apply<true>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx, mm_out);
         else
-            hipLaunchKernelGGL(bn_bwd_apply<false>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx, mm_out, getenv("Q8T_DBG_REV") ? 1 : 0);
+            hipLaunchKernelGGL(bn_bwd_apply<false>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx, mm_out);
     } else {
         const int64_t total = planes * HW;
         const dim3 grid((unsigned)((total + kThreads - 1) / kThreads < 65536 * 16 ? (total + kThreads - 1) / kThreads : 65536 * 16));
@@ -655,7 +652,7 @@ int q8t_range_bn_bwd(const float *x, const float *dy, const float *stats, int N,
 
 size_t q8t_range_bn_bwd_bifurcate_workspace_size(int N, int C, int H, int W)
 {
-    return q8t_range_bn_workspace_size(N, C, H, W) + 256 + 16384 * sizeof(float2);
+    return q8t_range_bn_workspace_size(N, C, H, W) + 256 + 2048 * sizeof(float2);
 }
 
 int q8t_range_bn_bwd_bifurcate(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,

@@ -226,7 +226,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
 #pragma unroll
             for (int s = 0; s < 3; ++s) {
                 const int tap = r * 3 + s;
-                if (plane == 0)   // wavefront-uniform: one plane gathers the column sums
+                if ((tap < 5) == (plane == 0))   // wavefront-uniform: the two planes share the column sums
                     cs[tap] = dot4_ones(f[s][0], dot4_ones(f[s][1], dot4_ones(f[s][2], dot4_ones(f[s][3], cs[tap]))));
 #pragma unroll
                 for (int mt = 0; mt < 4; ++mt)
@@ -313,10 +313,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
                 for (int j = 0; j < 4; ++j)
                     out[(((plane * 4 + mt) * 9 + t) * 4 + j) * 64 + lane] = acc[mt][t][j];
         if (kb == 0) {
-            if (plane == 0) {
 #pragma unroll
-                for (int t = 0; t < 9; ++t) out[TILE_INTS + t * 16 + l16] = cs[t];
-            }
+            for (int t = 0; t < 9; ++t)
+                if ((t < 5) == (plane == 0)) out[TILE_INTS + t * 16 + l16] = cs[t];
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt) out[TILE_INTS + 144 + plane * 64 + mt * 16 + l16] = rs[mt];
         }

@@ -493,7 +493,7 @@ bool make_plan(const q8t_conv_desc *d, Plan *p)
     if (crs > (1 << 24) || d->K > (1 << 22)) return false;
     p->CRS = (int)crs;
     p->Mtot = (int64_t)d->N * p->P * p->Q;
-    if (p->Mtot >= ((int64_t)1 << 40)) return false;
+    if (p->Mtot >= ((int64_t)1 << 36)) return false;
     if ((int64_t)d->N * d->C >= ((int64_t)1 << 31) || (int64_t)d->N * d->K >= ((int64_t)1 << 31)) return false;
     p->Mp = (p->Mtot + 63) & ~(int64_t)63;
     const int64_t widest = crs > d->K ? crs : d->K;
