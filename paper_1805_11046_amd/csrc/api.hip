@@ -18,6 +18,14 @@ int fc_check(int M, int N, int K, const void *a, const void *qa, const void *b, 
     return Q8T_OK;
 }
 
+// the im2col + GEMM form of a forward with few input channels pays off once the product is not tiny
+bool smallc_wanted(int which, const q8t_conv_desc *d)
+{
+    if (!q8t_smallc_conv_supported(which, d)) return false;
+    const int P = (d->H + 2 * d->pad - d->R) / d->stride + 1, Q = (d->W + 2 * d->pad - d->S) / d->stride + 1;
+    return (double)d->K * d->C * d->R * d->S * d->N * P * Q >= 4194304.0;
+}
+
 // the GEMM form of the weight gradient pays off once the product is not tiny
 bool wgrad_wants_gemm(const q8t_conv_desc *d)
 {
@@ -70,7 +78,8 @@ size_t q8t_qconv_workspace_size(const q8t_conv_desc *desc, int which)
     size_t g = q8t_generic_conv_ws(which, desc);
     size_t f = q8t_fast_conv_ws(which, desc);
     if (which == 2) f = q8t_fast_wgrad_ws(desc);
-    const size_t h = which < 2 ? q8t_nhwc_conv_ws(which, desc) : (wgrad_wants_gemm(desc) ? q8t_gemm_wgrad_ws(desc) : 0);
+    size_t h = which < 2 ? q8t_nhwc_conv_ws(which, desc) : (wgrad_wants_gemm(desc) ? q8t_gemm_wgrad_ws(desc) : 0);
+    if (smallc_wanted(which, desc)) h = q8t_smallc_conv_ws(which, desc);
     if (h > g) g = h;
     return g > f ? g : f;
 }
@@ -85,6 +94,7 @@ int q8t_qconv_fwd(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams
         return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, nullptr, ws, (hipStream_t)stream);
     if (q8t_nhwc_conv_supported(0, desc))
         return q8t_nhwc_conv(0, desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
+    if (smallc_wanted(0, desc)) return q8t_smallc_conv(desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
     return q8t_generic_conv(0, desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
 }
 

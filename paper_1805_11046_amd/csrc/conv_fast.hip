@@ -610,24 +610,21 @@ int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
     const int8_t *pa = (const int8_t *)a;
     int32_t *pacc = (int32_t *)out_acc;
     const bool sq = d->H == d->W;
-#define Q8T_CONV(T, WCV, V)                                                                                          \
-    {                                                                                                                \
-        rc = bnpart ? launch_conv<T, WCV, V, true>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc, bnpart)   \
-                    : launch_conv<T, WCV, V, false>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc, bnpart); \
-        goto launched;                                                                                               \
-    }
+#define Q8T_CONV(T, WCV, V)                                                                                        \
+    (bnpart ? launch_conv<T, WCV, V, true>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc, bnpart)         \
+            : launch_conv<T, WCV, V, false>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc, bnpart))
     if (taps == 9) {
-        if (sq && d->W == 56 && v16) Q8T_CONV(9, 56, true);
-        if (sq && d->W == 28 && v16) Q8T_CONV(9, 28, true);
-        if (sq && d->W == 14) Q8T_CONV(9, 14, false);
-        if (v16) Q8T_CONV(9, 0, true);
-        Q8T_CONV(9, 0, false);
+        if (sq && d->W == 56 && v16) rc = Q8T_CONV(9, 56, true);
+        else if (sq && d->W == 28 && v16) rc = Q8T_CONV(9, 28, true);
+        else if (sq && d->W == 14) rc = Q8T_CONV(9, 14, false);
+        else if (v16) rc = Q8T_CONV(9, 0, true);
+        else rc = Q8T_CONV(9, 0, false);
+    } else {
+        if (sq && d->W == 56 && v16) rc = Q8T_CONV(1, 56, true);
+        else if (v16) rc = Q8T_CONV(1, 0, true);
+        else rc = Q8T_CONV(1, 0, false);
     }
-    if (sq && d->W == 56 && v16) Q8T_CONV(1, 56, true);
-    if (v16) Q8T_CONV(1, 0, true);
-    Q8T_CONV(1, 0, false);
 #undef Q8T_CONV
-launched:
     if (rc) return rc;
     if (bn_stats) {
         const int nact = (g.M + sch.rpb - 1) / sch.rpb;

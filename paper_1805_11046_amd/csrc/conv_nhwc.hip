@@ -366,6 +366,126 @@ __global__ __launch_bounds__(C::THREADS, C::MINB) void igemm_nhwc(const int8_t *
     }
 }
 
+// ---- forward with few input channels (the network's first layer) --------------------------------
+// The reduction (c, r, s) of an output position is laid out explicitly: xn[m][Kc] with
+// Kc = C*R*S rounded up to a multiple of 64, entry c*R*S + r*S + s = the input code under that tap
+// (zero code in the padding and in the surplus columns), plus the row sum.  With the filter as
+// [K][Kc] (zeros in the surplus columns) the product is a 1x1 problem for igemm_nhwc.
+// One workgroup per (image, output row): the R input rows of every channel go to LDS once.
+__global__ __launch_bounds__(kThreads) void im2col_positions(const int8_t *__restrict__ x, int C, int H, int W, int R, int S,
+                                                             int stride, int pad, int P, int Q, int Kc,
+                                                             const q8t_qparams *__restrict__ qpx,
+                                                             int8_t *__restrict__ xn, int *__restrict__ rowsum)
+{
+    extern __shared__ __align__(16) int8_t lds[];
+    const int Wp = W + 2 * pad, CRS = C * R * S;
+    int8_t *rows = lds;                                   // [C*R][Wp]
+    int *lut = reinterpret_cast<int *>(lds + ((C * R * Wp + 15) & ~15));   // [Kc]: offset of column j in `rows`, -1: surplus
+    int *rsum = lut + Kc;                                                   // [Q]
+    const int n = blockIdx.y, p = blockIdx.x, tid = threadIdx.x;
+    const int zsx = qpx->zero_point - (1 << (qpx->bits - 1));
+    // wavefront w fills the staged rows w, w+4, ...: (channel, filter row) decoded once per row
+    for (int cr = tid >> 6; cr < C * R; cr += kThreads / 64) {
+        const int c = cr / R, r = cr - c * R;
+        const int h = p * stride + r - pad;
+        const bool hok = (unsigned)h < (unsigned)H;
+        const int8_t *src = x + (((size_t)n * C + c) * H + (hok ? h : 0)) * W;
+        for (int wp = tid & 63; wp < Wp; wp += 64) {
+            const int w = wp - pad;
+            rows[cr * Wp + wp] = (hok && (unsigned)w < (unsigned)W) ? src[w] : (int8_t)zsx;
+        }
+    }
+    for (int q = tid; q < Q; q += kThreads) rsum[q] = 0;
+    for (int j = tid; j < Kc; j += kThreads) {
+        int off = -1;
+        if (j < CRS) {
+            const int c = j / (R * S), t = j - c * R * S, r = t / S, s2 = t - r * S;
+            off = (c * R + r) * Wp + s2;
+        }
+        lut[j] = off;
+    }
+    __syncthreads();
+    const int chunks = Kc >> 4;
+    const size_t m0 = ((size_t)n * P + p) * Q;
+    const uint32_t zb = (uint32_t)(zsx & 255);
+    for (int it = tid; it < Q * chunks; it += kThreads) {
+        const int q = it / chunks, ch = it - q * chunks;
+        const int base = q * stride;
+        uint32_t w4[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            uint32_t v = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int off = lut[ch * 16 + d * 4 + e];
+                const uint32_t b = off >= 0 ? (uint32_t)(uint8_t)rows[off + base] : zb;
+                v |= b << (8 * e);
+            }
+            w4[d] = v;
+        }
+        *reinterpret_cast<uint4 *>(xn + (m0 + q) * Kc + ch * 16) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+        // row sums: every column of a position, surplus columns included
+        atomicAdd(&rsum[q], bytesum4(w4[0]) + bytesum4(w4[1]) + bytesum4(w4[2]) + bytesum4(w4[3]));
+    }
+    __syncthreads();
+    for (int q = tid; q < Q; q += kThreads) rowsum[m0 + q] = rsum[q];
+}
+
+// filter [K][C*R*S] -> [K][Kc] with zero surplus columns, sums per output channel, tap offset 0
+__global__ __launch_bounds__(kThreads) void repack_flat(const int8_t *__restrict__ w, int CRS, int Kc,
+                                                        int8_t *__restrict__ wt, int *__restrict__ colsum,
+                                                        int *__restrict__ tapoff)
+{
+    __shared__ int part[kThreads / 64];
+    const int k = blockIdx.x;
+    int sum = 0;
+    for (int j = threadIdx.x; j < Kc; j += kThreads) {
+        const int8_t v = j < CRS ? w[(size_t)k * CRS + j] : (int8_t)0;
+        wt[(size_t)k * Kc + j] = v;
+        sum += v;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, Q8T_WAVE);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        colsum[k] = part[0] + part[1] + part[2] + part[3];
+        if (k == 0) tapoff[0] = 0;
+    }
+}
+
+struct SmallPlan {
+    int P, Q, Kc;
+    size_t lds, o_rowsum, o_wt, o_colsum, o_tapoff, total;
+};
+
+inline size_t up256s(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// forward only: fewer than 64 input channels, output channels a multiple of 64
+bool make_small_plan(int which, const q8t_conv_desc *d, SmallPlan *p)
+{
+    if (which != 0) return false;
+    if (d->N <= 0 || d->C <= 0 || d->C >= 64 || d->K <= 0 || d->K % 64 || d->H <= 0 || d->W <= 0) return false;
+    if (d->R <= 0 || d->S <= 0 || d->R > 100 || d->S > 100 || d->stride < 1 || d->pad < 0 || d->pad > 100) return false;
+    if (d->H + 2 * d->pad < d->R || d->W + 2 * d->pad < d->S) return false;
+    const int64_t crs = (int64_t)d->C * d->R * d->S;
+    if (crs > 1024) return false;
+    p->Kc = (int)((crs + 63) / 64 * 64);
+    p->P = (d->H + 2 * d->pad - d->R) / d->stride + 1;
+    p->Q = (d->W + 2 * d->pad - d->S) / d->stride + 1;
+    if (d->N > 65535) return false;
+    const int64_t M = (int64_t)d->N * p->P * p->Q;
+    if (M >= ((int64_t)1 << 31) || (int64_t)d->N * d->C * d->H >= ((int64_t)1 << 31)) return false;
+    p->lds = (((size_t)d->C * d->R * (d->W + 2 * d->pad) + 15) & ~(size_t)15) + ((size_t)p->Kc + p->Q) * sizeof(int);
+    if (p->lds > 65536) return false;
+    p->o_rowsum = up256s((size_t)M * p->Kc);
+    p->o_wt = p->o_rowsum + up256s((size_t)M * sizeof(int));
+    p->o_colsum = p->o_wt + up256s((size_t)d->K * p->Kc);
+    p->o_tapoff = p->o_colsum + up256s((size_t)d->K * sizeof(int));
+    p->total = p->o_tapoff + 256;
+    return true;
+}
+
 struct Plan {
     int red, oc;          // reduction and output channels
     int IH, IW;           // operand spatial size
@@ -405,6 +525,64 @@ bool make_plan(int which, const q8t_conv_desc *d, Plan *p)
 }
 
 }  // namespace
+
+bool q8t_smallc_conv_supported(int which, const q8t_conv_desc *d)
+{
+    SmallPlan p;
+    return make_small_plan(which, d, &p);
+}
+
+size_t q8t_smallc_conv_ws(int which, const q8t_conv_desc *d)
+{
+    SmallPlan p;
+    return make_small_plan(which, d, &p) ? p.total : 0;
+}
+
+int q8t_smallc_conv(const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b, const q8t_qparams *qb,
+                    float *out_f, void *out_acc, void *ws, hipStream_t st)
+{
+    SmallPlan p;
+    if (!make_small_plan(0, d, &p)) return Q8T_ERR_SHAPE;
+    if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    int8_t *xn = (int8_t *)ws;
+    int *rowsum = (int *)((char *)ws + p.o_rowsum);
+    int8_t *wt = (int8_t *)ws + p.o_wt;
+    int *colsum = (int *)((char *)ws + p.o_colsum);
+    int *tapoff = (int *)((char *)ws + p.o_tapoff);
+    hipLaunchKernelGGL(im2col_positions, dim3((unsigned)p.P, (unsigned)d->N), dim3(kThreads), p.lds, st, (const int8_t *)a,
+                       d->C, d->H, d->W, d->R, d->S, d->stride, d->pad, p.P, p.Q, p.Kc, qa, xn, rowsum);
+    Q8T_LAUNCH_CHECK();
+    hipLaunchKernelGGL(repack_flat, dim3((unsigned)d->K), dim3(kThreads), 0, st, (const int8_t *)b, d->C * d->R * d->S, p.Kc,
+                       wt, colsum, tapoff);
+    Q8T_LAUNCH_CHECK();
+    Geo g;
+    g.N = d->N;
+    g.IH = p.P;
+    g.IW = p.Q;
+    g.Cp = p.Kc;
+    g.OH = p.P;
+    g.OW = p.Q;
+    g.ish = g.isw = 1;
+    g.OC = d->K;
+    g.OHf = p.P;
+    g.OWf = p.Q;
+    g.osh = g.osw = 1;
+    g.oph = g.opw = 0;
+    g.M = d->N * p.P * p.Q;
+    g.T = 1;
+    g.vec = q8t_aligned(out_f, 16) && q8t_aligned(out_acc, 16);
+#define Q8T_GO(CFG)                                                                                                   \
+    {                                                                                                                 \
+        const int64_t tiles = (int64_t)((g.M + CFG::BM - 1) / CFG::BM) * (d->K / CFG::BN);                            \
+        hipLaunchKernelGGL(igemm_nhwc<CFG>, dim3(q8t_gemm::xcd_grid(tiles)), dim3(CFG::THREADS), conv_lds_bytes<CFG>(), \
+                           st, xn, rowsum, wt, colsum, qa, qb, g, tapoff, out_f, (int32_t *)out_acc);                 \
+    }
+    if (d->K % 128 == 0) Q8T_GO(q8t_gemm::Mid)
+    else Q8T_GO(q8t_gemm::Small)
+#undef Q8T_GO
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
 
 bool q8t_nhwc_conv_supported(int which, const q8t_conv_desc *d)
 {

@@ -32,6 +32,12 @@ size_t q8t_nhwc_conv_ws(int which, const q8t_conv_desc *d);
 int q8t_nhwc_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
                   const q8t_qparams *qb, float *out_f, void *out_acc, void *ws, hipStream_t st);
 
+// forward with fewer than 64 input channels (first layer): explicit im2col rows + the same GEMM
+bool q8t_smallc_conv_supported(int which, const q8t_conv_desc *d);
+size_t q8t_smallc_conv_ws(int which, const q8t_conv_desc *d);
+int q8t_smallc_conv(const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b, const q8t_qparams *qb,
+                    float *out_f, void *out_acc, void *ws, hipStream_t st);
+
 // specialised 3x3 weight-gradient kernel (wgrad_fast.hip)
 bool q8t_fast_wgrad_supported(const q8t_conv_desc *d, const void *g16, const void *x, const void *dw,
                               const void *acc);

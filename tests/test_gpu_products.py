@@ -129,6 +129,9 @@ CONV_CASES = [
     (13, 24, 17, 13, 40, 3, 2, 2, 1),    # nothing a multiple of anything; 63-position planes in groups of 4 images
     (6, 128, 7, 7, 128, 3, 3, 1, 1),     # 49-position planes, last image group incomplete
     (5, 64, 9, 10, 64, 3, 3, 1, 1),      # 90-position planes in pairs, last pair incomplete
+    # forward with few input channels: explicit im2col rows + GEMM
+    (4, 16, 20, 20, 128, 3, 3, 1, 1),    # 144 columns -> 192, 128-wide tiles
+    (8, 5, 30, 17, 64, 5, 3, 2, 2),      # non-square filter, stride 2, 75 columns -> 128
 ]
 
 
