@@ -129,3 +129,78 @@ def test_layer_step_chain_stage_by_stage():
     diff = int((s8_free != host(g8)).sum())
     print("8-bit gradient codes differing from the un-forced oracle chain:", diff, "of", s8_free.size)
     assert diff <= 1e-4 * s8_free.size
+
+
+def _layer_forward(q8t, od, d, a_dev, w, tag):
+    """quantize -> conv (+ Range BN statistics from its epilogue) -> Range BN; every stage against
+    the oracle fed with the GPU's output of the stage before.  Returns what the backward needs."""
+    ah = host(a_dev)
+    qa, pa = q8t.quantize(a_dev, 8)
+    qw, pw = q8t.quantize(dev(w), 8)
+    sa, _, opa = oracle.quantize(ah, 8)
+    sw, _, opw = oracle.quantize(w, 8)
+    same_qparams(q8t, pa, opa)
+    same_ints(host(qa), sa)
+    same_ints(host(qw), sw)
+    y, acc, stats = q8t.qconv_fwd_bn_stats(d, qa, pa, qw, pw, want_acc=True)
+    oy, oacc = oracle.qconv_fwd(od, sa, opa, sw, opw)
+    same_ints(host(acc), oacc)
+    close(host(y), oy)
+    yh, sth = host(y), host(stats)
+    ost = oracle.range_bn_stats(yh)
+    assert np.array_equal(sth[1:], ost[1:]), tag
+    close(sth[0], ost[0])
+    bn, _, _ = q8t.range_bn_fwd_apply(y, stats, eps=1e-5)
+    obn, _, _, _ = oracle.range_bn_fwd(yh, eps=1e-5, stats=sth)
+    same_ints(host(bn), obn)
+    return dict(qa=qa, pa=pa, qw=qw, pw=pw, sa=sa, opa=opa, sw=sw, opw=opw, y=y, yh=yh, stats=stats, sth=sth, bn=bn)
+
+
+def _layer_backward(q8t, od, d, L, dbn_dev, seed):
+    """Range BN backward fused with the bifurcated quantization -> layer and weight gradients."""
+    dbn = host(dbn_dev)
+    g, dgam, dbet, g8, pg8, g16, pg16 = q8t.range_bn_bwd_bifurcate(L["y"], dbn_dev, L["stats"], None, 1e-5, seed, seed + 1)
+    og, odg, odb = oracle.range_bn_bwd(L["yh"], dbn, L["sth"], None, 1e-5)
+    close(host(g), og)
+    close(host(dgam), odg)
+    close(host(dbet), odb)
+    gh = host(g)
+    s8, _, o8 = oracle.quantize(gh, 8, True, seed=seed)
+    s16, _, o16 = oracle.quantize(gh, 16, True, seed=seed + 1)
+    same_qparams(q8t, pg8, o8)
+    same_qparams(q8t, pg16, o16)
+    same_ints(host(g8), s8)
+    same_ints(host(g16), s16)
+    dx, accd = q8t.qconv_dgrad(d, g8, pg8, L["qw"], L["pw"], want_acc=True)
+    odx, oaccd = oracle.qconv_dgrad(od, s8, o8, L["sw"], L["opw"])
+    same_ints(host(accd), oaccd)
+    close(host(dx), odx)
+    dw, accw = q8t.qconv_wgrad(d, L["qa"], L["pa"], g16, pg16, want_acc=True)
+    odw, oaccw = oracle.qconv_wgrad(od, L["sa"], L["opa"], s16, o16)
+    same_ints(host(accw), oaccw)
+    close(host(dw), odw)
+    return dx
+
+
+def test_config3_bottleneck_block_forward_and_backward_chain():
+    # 1x1 256->64, 3x3 64->64, 1x1 64->256 at 56x56, Range BN + ReLU after each (ReLU and its mask are
+    # plain elementwise glue outside the method, done with torch on the device), batch 4.
+    import torch
+    q8t = require_gpu()
+    N = 4
+    x, (w1, w2, w3), dout = synth.bottleneck_block(seed=4, N=N)
+    cases = [(N, 256, 56, 56, 64, 1, 1, 1, 0), (N, 64, 56, 56, 64, 3, 3, 1, 1), (N, 64, 56, 56, 256, 1, 1, 1, 0)]
+    ds = [q8t.conv_desc(*c) for c in cases]
+    ods = [oracle.conv_desc(*c) for c in cases]
+    a = dev(x)
+    layers = []
+    for i, w in enumerate((w1, w2, w3)):
+        L = _layer_forward(q8t, ods[i], ds[i], a, w, "layer %d" % i)
+        layers.append(L)
+        a = torch.relu(L["bn"])
+    grad = dev(dout)
+    for i in (2, 1, 0):
+        L = layers[i]
+        dbn = grad * (L["bn"] > 0).to(grad.dtype)       # ReLU backward
+        grad = _layer_backward(q8t, ods[i], ds[i], L, dbn.contiguous(), seed=100 + 10 * i)
+    assert tuple(grad.shape) == x.shape and bool(torch.isfinite(grad).all())
