@@ -200,8 +200,9 @@ int q8t_range_bn_bwd(const float *x, const float *dy, const float *stats, int N,
  * dx is written as fp32 and its min/max is taken in the same pass, so the quantizer needs no range
  * search of its own: one pass over dx less than q8t_range_bn_bwd followed by
  * q8t_quantize_bifurcate(dx, ...), with bit-identical results.  dx, q8_out, q16_out and both
- * parameter blocks are required; dgamma / dbeta stay nullable.  Requires H*W >= 256 (else
- * Q8T_ERR_SHAPE: use the two separate calls).  ws: q8t_range_bn_bwd_bifurcate_workspace_size. */
+ * parameter blocks are required; dgamma / dbeta stay nullable.  Planes of fewer than 256 positions
+ * run the two steps one after the other (same results, no pass saved).
+ * ws: q8t_range_bn_bwd_bifurcate_workspace_size. */
 size_t q8t_range_bn_bwd_bifurcate_workspace_size(int N, int C, int H, int W);
 int q8t_range_bn_bwd_bifurcate(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
                                const float *gamma, float eps, float *dx, float *dgamma, float *dbeta,

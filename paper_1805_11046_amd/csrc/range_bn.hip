@@ -662,9 +662,15 @@ int q8t_range_bn_bwd_bifurcate(const float *x, const float *dy, const float *sta
 {
     if (!dx || !q8_out || !qp8_out || !q16_out || !qp16_out) return Q8T_ERR_NULL;
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
-    if ((int64_t)H * W < 256) return Q8T_ERR_SHAPE;   // planes this small: use the two separate calls
     const size_t off = (q8t_range_bn_workspace_size(N, C, H, W) + 255) & ~(size_t)255;
     float2 *mm = (float2 *)((char *)ws + off);
+    if ((int64_t)H * W < 256) {
+        // planes this small take the flat backward kernel, which keeps no ranges: plain sequence
+        const int rc = range_bn_bwd_impl(x, dy, stats, N, C, H, W, gamma, eps, dx, dgamma, dbeta, ws, stream, nullptr, nullptr);
+        if (rc) return rc;
+        return q8t_quantize_bifurcate(dx, (int64_t)N * C * H * W, seed8, seed16, q8_out, qp8_out, q16_out, qp16_out, mm,
+                                      stream);
+    }
     int np = 0;
     const int rc = range_bn_bwd_impl(x, dy, stats, N, C, H, W, gamma, eps, dx, dgamma, dbeta, ws, stream, mm, &np);
     if (rc) return rc;

@@ -204,3 +204,96 @@ def test_config3_bottleneck_block_forward_and_backward_chain():
         dbn = grad * (L["bn"] > 0).to(grad.dtype)       # ReLU backward
         grad = _layer_backward(q8t, ods[i], ds[i], L, dbn.contiguous(), seed=100 + 10 * i)
     assert tuple(grad.shape) == x.shape and bool(torch.isfinite(grad).all())
+
+
+def test_config4_resnet18_training_step_chain():
+    # Full ResNet-18 forward + backward at batch 2 (the oracle re-runs every call of the method on the
+    # GPU's own inputs to that call: stage-by-stage bit-exact integers, floats within tolerance).
+    # Every conv / FC product and every BN is the library's; ReLU, pooling, the residual adds and the
+    # softmax cross-entropy are elementwise glue outside the method and are left to torch autograd.
+    import torch
+    import torch.nn.functional as F
+    q8t = require_gpu()
+    N = 2
+    g = synth.rng(44)
+    x = synth.normal(g, (N, 3, 224, 224), std=1.0)
+    labels = torch.as_tensor(g.integers(0, 1000, size=N), device="cuda:0")
+    state = {"seed": 1000, "n": 0}
+
+    def he(cout, cin, r):
+        return synth.normal(g, (cout, cin, r, r), std=(2.0 / (cin * r * r)) ** 0.5)
+
+    class ConvBN(torch.autograd.Function):
+        @staticmethod
+        def forward(ctx, a, w_np, stride, pad):
+            a = a.contiguous()
+            n, c, h, wd = a.shape
+            k, _, r, s = w_np.shape
+            case = (n, c, h, wd, k, r, s, stride, pad)
+            ctx.d, ctx.od = q8t.conv_desc(*case), oracle.conv_desc(*case)
+            ctx.L = _layer_forward(q8t, ctx.od, ctx.d, a, w_np, str(case))
+            state["n"] += 1
+            return ctx.L["bn"]
+
+        @staticmethod
+        def backward(ctx, dbn):
+            state["seed"] += 2
+            dx = _layer_backward(q8t, ctx.od, ctx.d, ctx.L, dbn.contiguous(), seed=state["seed"])
+            return dx, None, None, None
+
+    class Linear(torch.autograd.Function):
+        @staticmethod
+        def forward(ctx, a, w_np):
+            a = a.contiguous()
+            ah = host(a)
+            qa, pa = q8t.quantize(a, 8)
+            qw, pw = q8t.quantize(dev(w_np), 8)
+            sa, _, opa = oracle.quantize(ah, 8)
+            sw, _, opw = oracle.quantize(w_np, 8)
+            same_ints(host(qa), sa)
+            same_ints(host(qw), sw)
+            y, acc = q8t.qgemm_fwd(qa, pa, qw, pw, want_acc=True)
+            oy, oacc = oracle.qgemm_fwd(sa, opa, sw, opw)
+            same_ints(host(acc), oacc)
+            close(host(y), oy)
+            ctx.saved = (qa, pa, qw, pw, sa, opa, sw, opw)
+            return y
+
+        @staticmethod
+        def backward(ctx, dy):
+            qa, pa, qw, pw, sa, opa, sw, opw = ctx.saved
+            dy = dy.contiguous()
+            dyh = host(dy)
+            g8, pg8, g16, pg16 = q8t.quantize_bifurcate(dy, 7, 8)
+            s8, _, o8 = oracle.quantize(dyh, 8, True, seed=7)
+            s16, _, o16 = oracle.quantize(dyh, 16, True, seed=8)
+            same_ints(host(g8), s8)
+            same_ints(host(g16), s16)
+            dx, accd = q8t.qgemm_dgrad(g8, pg8, qw, pw, want_acc=True)
+            odx, oaccd = oracle.qgemm_dgrad(s8, o8, sw, opw)
+            same_ints(host(accd), oaccd)
+            close(host(dx), odx)
+            dw, accw = q8t.qgemm_wgrad(qa, pa, g16, pg16, want_acc=True)
+            odw, oaccw = oracle.qgemm_wgrad(sa, opa, s16, o16)
+            same_ints(host(accw), oaccw)
+            close(host(dw), odw)
+            return dx, None
+
+    def block(a, cin, cout, stride):
+        h = F.relu(ConvBN.apply(a, he(cout, cin, 3), stride, 1))
+        h = ConvBN.apply(h, he(cout, cout, 3), 1, 1)
+        sc = a if (stride == 1 and cin == cout) else ConvBN.apply(a, he(cout, cin, 1), stride, 0)
+        return F.relu(h + sc)
+
+    inp = dev(x).requires_grad_(True)
+    a = F.relu(ConvBN.apply(inp, he(64, 3, 7), 2, 3))
+    a = F.max_pool2d(a, 3, 2, 1)
+    for cin, cout, stride in [(64, 64, 1), (64, 64, 1), (64, 128, 2), (128, 128, 1), (128, 256, 2), (256, 256, 1),
+                              (256, 512, 2), (512, 512, 1)]:
+        a = block(a, cin, cout, stride)
+    a = F.adaptive_avg_pool2d(a, 1).flatten(1)
+    logits = Linear.apply(a, synth.normal(g, (512, 1000), std=(2.0 / 512) ** 0.5))
+    loss = F.cross_entropy(logits, labels)
+    loss.backward()
+    assert state["n"] == 20                    # 17 3x3 / 7x7 convs + 3 downsample 1x1
+    assert bool(torch.isfinite(inp.grad).all()) and float(inp.grad.abs().max()) > 0.0

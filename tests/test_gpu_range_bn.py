@@ -122,7 +122,7 @@ def test_rejects_degenerate_batch():
     assert e.value.code == -2
 
 
-@pytest.mark.parametrize("shape", [(6, 7, 16, 16), (3, 2, 40, 36), (128, 64, 56, 56)])
+@pytest.mark.parametrize("shape", [(6, 7, 16, 16), (3, 2, 40, 36), (128, 64, 56, 56), (5, 9, 7, 7), (64, 128, 1, 1)])
 def test_backward_fused_with_bifurcated_quantization(shape):
     # same results as the two separate calls; the codes are checked against the oracle's quantizer
     # run on the GPU's own dx (bit-exact), dx itself against the oracle within tolerance
