@@ -1,0 +1,219 @@
+"""Synthetic training steps (forward + backward) with every conv / FC product and every batch-norm
+running through the library: 8-bit forward and layer-gradient products, 16x8-bit weight gradients
+from the bifurcated gradient copies, Range BN with its statistics gathered in the conv epilogue
+(Sections 3, 4 and 7 of the paper).
+
+    python -m paper_1805_11046_amd.train_step --net resnet18   [--batch 256] [--steps 5] [--breakdown]
+    python -m paper_1805_11046_amd.train_step --net bottleneck [--batch 128] [--steps 20] [--breakdown]
+
+resnet18: the full network on 3x224x224 inputs ~N(0,1), 1000 classes, random labels.
+bottleneck: one ResNet-50 block, 1x1 256->64, 3x3 64->64, 1x1 64->256 at 56x56, each followed by
+Range BN (+ReLU), identity shortcut; inputs |N(0,1)|, output gradient ~N(0, sigma 1e-3).
+He-normal weights everywhere.
+
+ReLU, max/avg pooling, the residual additions and the softmax cross-entropy are elementwise glue
+outside the method; they are left to torch (autograd supplies their gradients).  The optimizer
+update is not part of the measured step.  Prints the step time and, with --breakdown, per entry
+point: time, share, integer throughput of the products (2 x multiply-accumulates of the layer, the
+weight gradient counted once although it executes two byte-plane products) and algorithmic bytes
+per second of the streaming calls.  Needs a GPU.
+"""
+import argparse
+import collections
+import time
+
+import torch
+import torch.nn.functional as F
+
+from . import binding as q8t
+
+_breakdown = False
+
+
+def _call(name, ops, nbytes, fn, *a, **k):
+    """Run one library call; with --breakdown also time it and book its integer operations and
+    algorithmic bytes under `name`."""
+    if not _breakdown:
+        return fn(*a, **k)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    r = fn(*a, **k)
+    e1.record()
+    _pending.append((name, ops, nbytes, e0, e1))
+    return r
+
+
+def _quantize(name, t):
+    n = t.numel()
+    # two passes over the fp32 tensor and one byte written; small tensors stay in registers (one pass)
+    return _call(name, 0, (9 if n > 65536 else 5) * n, q8t.quantize, t, 8)
+
+
+_pending = []
+_seed = [1]
+
+
+class ConvBN(torch.autograd.Function):
+    """quantize -> conv forward (+ Range BN statistics) -> Range BN;  backward: Range BN backward +
+    bifurcated gradient quantization -> layer gradient, weight gradient."""
+
+    @staticmethod
+    def forward(ctx, a, w, stride, pad, need_dx):
+        a = a.contiguous()
+        n, c, h, wd = a.shape
+        k, _, r, s = w.shape
+        d = q8t.conv_desc(n, c, h, wd, k, r, s, stride, pad)
+        qa, pa = _quantize("quantize (activations)", a)
+        qw, pw = _quantize("quantize (weights)", w)
+        ops = 2.0 * n * d.P * d.Q * k * c * r * s
+        nx, ny = a.numel(), n * k * d.P * d.Q
+        y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw)
+        bn, _, _ = _call("range_bn_fwd_apply", 0, 8 * ny, q8t.range_bn_fwd_apply, y, stats, None, None, 1e-5)
+        ctx.saved = (d, qa, pa, qw, pw, y, stats, need_dx, ops, nx, ny)
+        return bn
+
+    @staticmethod
+    def backward(ctx, dbn):
+        d, qa, pa, qw, pw, y, stats, need_dx, ops, nx, ny = ctx.saved
+        _seed[0] += 2
+        _, _, _, g8, pg8, g16, pg16 = _call("range_bn_bwd_bifurcate", 0, 27 * ny, q8t.range_bn_bwd_bifurcate, y,
+                                            dbn.contiguous(), stats, None, 1e-5, _seed[0], _seed[0] + 1)
+        dx = None
+        if need_dx:
+            dx, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw)
+        dw, _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16)
+        return dx, dw, None, None, None
+
+
+class Linear(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, a, w):
+        a = a.contiguous()
+        qa, pa = _quantize("quantize (activations)", a)
+        qw, pw = _quantize("quantize (weights)", w)
+        ops = 2.0 * a.shape[0] * a.shape[1] * w.shape[1]
+        y, _ = _call("qgemm_fwd", ops, a.numel() + w.numel() + 4 * a.shape[0] * w.shape[1], q8t.qgemm_fwd, qa, pa, qw, pw)
+        ctx.saved = (qa, pa, qw, pw, ops)
+        return y
+
+    @staticmethod
+    def backward(ctx, dy):
+        qa, pa, qw, pw, ops = ctx.saved
+        _seed[0] += 2
+        g8, pg8, g16, pg16 = _call("quantize_bifurcate", 0, 11 * dy.numel(), q8t.quantize_bifurcate, dy.contiguous(),
+                                   _seed[0], _seed[0] + 1)
+        dx, _ = _call("qgemm_dgrad", ops, dy.numel() + qw.numel() + 4 * qa.numel(), q8t.qgemm_dgrad, g8, pg8, qw, pw)
+        dw, _ = _call("qgemm_wgrad", ops, qa.numel() + 2 * dy.numel() + 4 * qw.numel(), q8t.qgemm_wgrad, qa, pa, g16, pg16)
+        return dx, dw
+
+
+STAGES = [(64, 64, 1), (64, 64, 1), (64, 128, 2), (128, 128, 1), (128, 256, 2), (256, 256, 1), (256, 512, 2), (512, 512, 1)]
+
+
+def _he(dev, gen, cout, cin, r):
+    w = torch.randn((cout, cin, r, r), device=dev, generator=gen) * (2.0 / (cin * r * r)) ** 0.5
+    return w.requires_grad_(True)
+
+
+def make_weights(dev, gen):
+    def he(cout, cin, r):
+        return _he(dev, gen, cout, cin, r)
+
+    ws = {"conv1": he(64, 3, 7), "blocks": []}
+    for cin, cout, stride in STAGES:
+        b = {"c1": he(cout, cin, 3), "c2": he(cout, cout, 3)}
+        if stride != 1 or cin != cout:
+            b["sc"] = he(cout, cin, 1)
+        ws["blocks"].append(b)
+    ws["fc"] = (torch.randn((512, 1000), device=dev, generator=gen) * (2.0 / 512) ** 0.5).requires_grad_(True)
+    return ws
+
+
+def step(x, labels, ws):
+    a = F.relu(ConvBN.apply(x, ws["conv1"], 2, 3, False))     # the network input needs no gradient
+    a = F.max_pool2d(a, 3, 2, 1)
+    for (cin, cout, stride), b in zip(STAGES, ws["blocks"]):
+        h = F.relu(ConvBN.apply(a, b["c1"], stride, 1, True))
+        h = ConvBN.apply(h, b["c2"], 1, 1, True)
+        sc = ConvBN.apply(a, b["sc"], stride, 0, True) if "sc" in b else a
+        a = F.relu(h + sc)
+    a = F.adaptive_avg_pool2d(a, 1).flatten(1)
+    loss = F.cross_entropy(Linear.apply(a, ws["fc"]), labels)
+    loss.backward()
+    return loss
+
+
+def bottleneck_step(x, gy, ws):
+    h = F.relu(ConvBN.apply(x, ws[0], 1, 0, True))
+    h = F.relu(ConvBN.apply(h, ws[1], 1, 1, True))
+    h = ConvBN.apply(h, ws[2], 1, 0, True)
+    out = F.relu(h + x)
+    out.backward(gy)
+    return out
+
+
+def main():
+    global _breakdown
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--net", choices=["resnet18", "bottleneck"], default="resnet18")
+    ap.add_argument("--batch", type=int, default=0, help="default 256 (resnet18) / 128 (bottleneck)")
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--breakdown", action="store_true")
+    args = ap.parse_args()
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0)
+    if args.net == "resnet18":
+        args.batch = args.batch or 256
+        ws = make_weights(dev, gen)
+        x = torch.randn((args.batch, 3, 224, 224), device=dev, generator=gen)
+        labels = torch.randint(0, 1000, (args.batch,), device=dev, generator=gen)
+        params = [ws["conv1"], ws["fc"]] + [w for b in ws["blocks"] for w in b.values()]
+
+        def one():
+            for p in params:
+                p.grad = None
+            return step(x, labels, ws)
+    else:
+        args.batch = args.batch or 128
+        params = [_he(dev, gen, 64, 256, 1), _he(dev, gen, 64, 64, 3), _he(dev, gen, 256, 64, 1)]
+        x = torch.randn((args.batch, 256, 56, 56), device=dev, generator=gen).abs_().requires_grad_(True)
+        gy = torch.randn((args.batch, 256, 56, 56), device=dev, generator=gen) * 1e-3
+
+        def one():
+            for p in params:
+                p.grad = None
+            x.grad = None
+            return bottleneck_step(x, gy, params).sum()
+
+    for _ in range(args.warmup):
+        loss = one()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        loss = one()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    assert bool(torch.isfinite(loss)) and all(p.grad is not None and bool(torch.isfinite(p.grad).all()) for p in params)
+    print("%s training step, batch %d: %.2f ms / step (%.0f images/s)" % (args.net, args.batch, ms, args.batch / ms * 1e3))
+    if args.breakdown:
+        _breakdown = True
+        one()
+        torch.cuda.synchronize()
+        acc = collections.defaultdict(lambda: [0.0, 0.0, 0.0, 0])
+        for name, ops, nbytes, e0, e1 in _pending:
+            a = acc[name]
+            a[0] += e0.elapsed_time(e1)
+            a[1] += ops
+            a[2] += nbytes
+            a[3] += 1
+        lib = sum(a[0] for a in acc.values())
+        print("library calls: %.2f ms of the step (each call timed with events, launch gaps included)" % lib)
+        print("  %-26s %6s %9s %9s %10s" % ("entry point", "calls", "ms", "TOP/s", "GB/s (alg.)"))
+        for name, (t, ops, nbytes, cnt) in sorted(acc.items(), key=lambda kv: -kv[1][0]):
+            print("  %-26s %6d %9.3f %9s %10.0f" % (name, cnt, t, "%.0f" % (ops / t / 1e9) if ops else "-", nbytes / t / 1e6))
+
+
+if __name__ == "__main__":
+    main()
