@@ -1,7 +1,6 @@
 // General MFMA path for the forward and layer-gradient convolutions (Section 4: both products
 // take 8-bit operands and accumulate in 32 bits): any filter size, stride and padding, for
-// channel counts that are multiples of 64.  Three launches per call (plus one per extra stride
-// class of a layer gradient):
+// channel counts that are multiples of 64.  Three launches per call:
 //
 //  1. to_nhwc      the NCHW int8 operand is rewritten channel-contiguous ([N][H][W][C]) into the
 //                  workspace, so that the 64 reduction channels of one filter tap are 64
@@ -19,8 +18,10 @@
 //
 // The layer gradient of a strided convolution is split into stride x stride classes of input
 // positions (same residue of (h, w) modulo the stride).  Inside a class every position sees the
-// same subset of filter taps at stride 1, so each class is one dense launch and no multiply is
-// spent on taps that cannot contribute.
+// same subset of filter taps at stride 1, so each class is a dense problem of its own and no
+// multiply is spent on taps that cannot contribute.  All classes run in one launch: the tile index
+// selects the class, and the classes of one region, which write interleaved elements of the same
+// result lines, are neighbours in the tile order.
 #include "q8t_common.h"
 #include "q8t_internal.h"
 #include "gemm_core.h"
@@ -41,15 +42,23 @@ struct ClassOffsets {
     int off[MAXCLS + 1];     // taps of class z are [off[z], off[z+1]) of the TapList
 };
 
+struct ClassGeo {            // per stride class: positions enumerated, rows, first tap, taps
+    int v[MAXCLS][5];        // OH, OW, M, first tap, number of taps
+};
+constexpr int CLS_INTS = 8;  // ints per class in the device copy of the table
+
 struct Geo {
     int N, IH, IW, Cp;       // staged operand: [N][IH][IW][Cp]
-    int OH, OW;              // output positions enumerated by this launch (rows m = (n, oh, ow))
+    int OH, OW;              // output positions enumerated by a class (rows m = (n, oh, ow))
     int ish, isw;            // operand step per output step
     int OC, OHf, OWf;        // NCHW result: channels, full height and width
     int osh, osw, oph, opw;  // result position = (oh*osh + oph, ow*osw + opw)
     int M;                   // N*OH*OW
-    int T;                   // taps of this launch
+    int T;                   // taps of a class
     int vec;                 // result pointers are 16-byte aligned
+    int ncls, mtiles;        // stride classes in this launch; row tiles of the largest class
+    int fill;                // stride 2, even result size, only class (0, 0) has taps: its workgroups
+                             // also write the zeros of the three empty classes
 };
 
 __device__ __forceinline__ int bytesum4(uint32_t v) { return __builtin_amdgcn_sdot4((int)v, 0x01010101, 0, false); }
@@ -145,15 +154,19 @@ __global__ __launch_bounds__(kThreads) void to_nhwc_small(const int8_t *__restri
 // grid (OC, classes).  which 0: out = k, reduction = c;  which 1: out = c, reduction = k.
 __global__ __launch_bounds__(kThreads) void repack_taps(const int8_t *__restrict__ w, int Kf, int Cf, int R, int S,
                                                         int which, TapList taps, TapList offs, ClassOffsets co,
-                                                        int8_t *__restrict__ wt, int *__restrict__ colsum,
-                                                        int *__restrict__ tapoff)
+                                                        ClassGeo cg, int8_t *__restrict__ wt,
+                                                        int *__restrict__ colsum, int *__restrict__ tapoff,
+                                                        int *__restrict__ clsinfo)
 {
     __shared__ int part[kThreads / 64];
     const int j = blockIdx.x, z = blockIdx.y;
-    // operand offsets of the taps, packed (dh in the low half), for the main kernel
-    if (j == 0 && z == 0 && threadIdx.x == 0)
+    // operand offsets of the taps, packed (dh in the low half), and the class table, for the main kernel
+    if (j == 0 && z == 0 && threadIdx.x == 0) {
         for (int tt = 0; tt < co.off[MAXCLS]; ++tt)
             tapoff[tt] = (int)((uint32_t)(uint16_t)(int16_t)offs.a[tt] | ((uint32_t)(uint16_t)(int16_t)offs.b[tt] << 16));
+        for (int c = 0; c < (int)gridDim.y; ++c)
+            for (int k = 0; k < 5; ++k) clsinfo[c * CLS_INTS + k] = cg.v[c][k];
+    }
     const int OC = which == 0 ? Kf : Cf, Cp = which == 0 ? Cf : Kf;
     const int RS = R * S;
     int sum = 0;
@@ -229,6 +242,7 @@ __global__ __launch_bounds__(C::THREADS, C::MINB) void igemm_nhwc(const int8_t *
                                                                    const q8t_qparams *__restrict__ qpa,
                                                                    const q8t_qparams *__restrict__ qpb, Geo g,
                                                                    const int *__restrict__ tapoff,
+                                                                   const int *__restrict__ clsinfo,
                                                                    float *__restrict__ out_f, int32_t *__restrict__ out_acc)
 {
     constexpr int MT = C::MT, NT = C::NT, BM = C::BM, BN = C::BN;
@@ -240,11 +254,26 @@ __global__ __launch_bounds__(C::THREADS, C::MINB) void igemm_nhwc(const int8_t *
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, kb = lane >> 4;
-    // logical tile order: output-channel tiles fastest (they share the operand rows)
-    const int ny = g.OC / BN, total = ((g.M + BM - 1) / BM) * ny;
+    // logical tile order: output-channel tiles fastest (they share the operand rows), then the stride
+    // classes of one row tile: they write interleaved elements of the same result lines, and run
+    // back to back on one XCD so that its L2 merges them before they go to memory
+    const int ny = g.OC / BN, total = g.mtiles * g.ncls * ny;
     const int lg = q8t_gemm::xcd_logical(blockIdx.x, total);
     if (lg >= total) return;
-    const int m0 = (lg / ny) * BM, n0 = (lg % ny) * BN;
+    const int n0 = (lg % ny) * BN, zc = (lg / ny) % g.ncls, m0 = (lg / (ny * g.ncls)) * BM;
+    {
+        const int *ci = clsinfo + zc * CLS_INTS;
+        g.OH = ci[0];
+        g.OW = ci[1];
+        g.M = ci[2];
+        g.T = ci[4];
+        g.oph = zc / g.osw;
+        g.opw = zc - g.oph * g.osw;
+        wt += (size_t)ci[3] * g.OC * g.Cp;
+        tapoff += ci[3];
+        colsum += (size_t)zc * g.OC;
+    }
+    if (m0 >= g.M) return;   // a smaller class: the whole workgroup leaves before any barrier
     const int za = qpa->zero_point - (1 << (qpa->bits - 1)), zb = qpb->zero_point - (1 << (qpb->bits - 1));
     const float sc = qpa->scale * qpb->scale;
     const int OHW = g.OH * g.OW;
@@ -336,6 +365,56 @@ __global__ __launch_bounds__(C::THREADS, C::MINB) void igemm_nhwc(const int8_t *
         for (int j = 0; j < 4; ++j) {
             o[j] = roff[r0 + j];
             t[j] = kzz - (uint32_t)zb * (uint32_t)rs[r0 + j];
+        }
+        if (g.fill) {
+            // result positions (2*oh, 2*ow): the lane's four rows are 8 consecutive floats of result row
+            // 2*oh when they share an image row, and row 2*oh + 1 is all zeros
+            const bool run = g.vec && o[0] >= 0 && o[1] == o[0] + 2 && o[2] == o[0] + 4 && o[3] == o[0] + 6;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const long long cb = (long long)(n0 + colbase + nt * 16 + l16) * plane;
+                int c[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) c[j] = (int)((uint32_t)acc[mt][nt][j] + t[j] - csn[nt]);
+                if (run && (((o[0] + cb) & 3) == 0)) {
+                    const long long b0 = o[0] + cb, b1 = b0 + g.OWf;   // OWf is even: b1 is 8-byte aligned
+                    if (out_acc) {
+                        *reinterpret_cast<int4 *>(out_acc + b0) = make_int4(c[0], 0, c[1], 0);
+                        *reinterpret_cast<int4 *>(out_acc + b0 + 4) = make_int4(c[2], 0, c[3], 0);
+                        *reinterpret_cast<int2 *>(out_acc + b1) = make_int2(0, 0);
+                        *reinterpret_cast<int2 *>(out_acc + b1 + 2) = make_int2(0, 0);
+                        *reinterpret_cast<int2 *>(out_acc + b1 + 4) = make_int2(0, 0);
+                        *reinterpret_cast<int2 *>(out_acc + b1 + 6) = make_int2(0, 0);
+                    }
+                    if (out_f) {
+                        *reinterpret_cast<float4 *>(out_f + b0) = make_float4(sc * (float)c[0], 0.f, sc * (float)c[1], 0.f);
+                        *reinterpret_cast<float4 *>(out_f + b0 + 4) = make_float4(sc * (float)c[2], 0.f, sc * (float)c[3], 0.f);
+                        *reinterpret_cast<float2 *>(out_f + b1) = make_float2(0.f, 0.f);
+                        *reinterpret_cast<float2 *>(out_f + b1 + 2) = make_float2(0.f, 0.f);
+                        *reinterpret_cast<float2 *>(out_f + b1 + 4) = make_float2(0.f, 0.f);
+                        *reinterpret_cast<float2 *>(out_f + b1 + 6) = make_float2(0.f, 0.f);
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (o[j] < 0) continue;
+                        const long long b = o[j] + cb;
+                        if (out_acc) {
+                            out_acc[b] = c[j];
+                            out_acc[b + 1] = 0;
+                            out_acc[b + g.OWf] = 0;
+                            out_acc[b + g.OWf + 1] = 0;
+                        }
+                        if (out_f) {
+                            out_f[b] = sc * (float)c[j];
+                            out_f[b + 1] = 0.f;
+                            out_f[b + g.OWf] = 0.f;
+                            out_f[b + g.OWf + 1] = 0.f;
+                        }
+                    }
+                }
+            }
+            continue;
         }
         const bool contig = g.vec && o[0] >= 0 && o[1] == o[0] + 1 && o[2] == o[0] + 2 && o[3] == o[0] + 3;
 #pragma unroll
@@ -432,9 +511,9 @@ __global__ __launch_bounds__(kThreads) void im2col_positions(const int8_t *__res
 }
 
 // filter [K][C*R*S] -> [K][Kc] with zero surplus columns, sums per output channel, tap offset 0
-__global__ __launch_bounds__(kThreads) void repack_flat(const int8_t *__restrict__ w, int CRS, int Kc,
-                                                        int8_t *__restrict__ wt, int *__restrict__ colsum,
-                                                        int *__restrict__ tapoff)
+__global__ __launch_bounds__(kThreads) void repack_flat(const int8_t *__restrict__ w, int CRS, int Kc, int OH, int OW,
+                                                        int M, int8_t *__restrict__ wt, int *__restrict__ colsum,
+                                                        int *__restrict__ tapoff, int *__restrict__ clsinfo)
 {
     __shared__ int part[kThreads / 64];
     const int k = blockIdx.x;
@@ -450,7 +529,14 @@ __global__ __launch_bounds__(kThreads) void repack_flat(const int8_t *__restrict
     __syncthreads();
     if (threadIdx.x == 0) {
         colsum[k] = part[0] + part[1] + part[2] + part[3];
-        if (k == 0) tapoff[0] = 0;
+        if (k == 0) {
+            tapoff[0] = 0;
+            clsinfo[0] = OH;
+            clsinfo[1] = OW;
+            clsinfo[2] = M;
+            clsinfo[3] = 0;
+            clsinfo[4] = 1;
+        }
     }
 }
 
@@ -490,8 +576,8 @@ struct Plan {
     int red, oc;          // reduction and output channels
     int IH, IW;           // operand spatial size
     int OHf, OWf;         // result spatial size
-    int ncls;             // launches of the main kernel
-    size_t o_chansum, o_wt, o_colsum, o_tapoff, total;
+    int ncls;             // stride classes
+    size_t o_chansum, o_wt, o_colsum, o_tapoff, o_cls, total;
 };
 
 inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -520,7 +606,8 @@ bool make_plan(int which, const q8t_conv_desc *d, Plan *p)
     p->o_wt = p->o_chansum + up256((size_t)ipos * sizeof(int));
     p->o_colsum = p->o_wt + up256((size_t)d->K * d->C * d->R * d->S);
     p->o_tapoff = p->o_colsum + up256((size_t)p->ncls * p->oc * sizeof(int));
-    p->total = p->o_tapoff + up256((MAXT + 3) * sizeof(int));
+    p->o_cls = p->o_tapoff + up256((MAXT + 3) * sizeof(int));
+    p->total = p->o_cls + up256((size_t)MAXCLS * CLS_INTS * sizeof(int));
     return true;
 }
 
@@ -552,8 +639,9 @@ int q8t_smallc_conv(const q8t_conv_desc *d, const void *a, const q8t_qparams *qa
     hipLaunchKernelGGL(im2col_positions, dim3((unsigned)p.P, (unsigned)d->N), dim3(kThreads), p.lds, st, (const int8_t *)a,
                        d->C, d->H, d->W, d->R, d->S, d->stride, d->pad, p.P, p.Q, p.Kc, qa, xn, rowsum);
     Q8T_LAUNCH_CHECK();
+    int *clsinfo = tapoff + 8;   // the tap table of this path has one entry
     hipLaunchKernelGGL(repack_flat, dim3((unsigned)d->K), dim3(kThreads), 0, st, (const int8_t *)b, d->C * d->R * d->S, p.Kc,
-                       wt, colsum, tapoff);
+                       p.P, p.Q, d->N * p.P * p.Q, wt, colsum, tapoff, clsinfo);
     Q8T_LAUNCH_CHECK();
     Geo g;
     g.N = d->N;
@@ -571,11 +659,14 @@ int q8t_smallc_conv(const q8t_conv_desc *d, const void *a, const q8t_qparams *qa
     g.M = d->N * p.P * p.Q;
     g.T = 1;
     g.vec = q8t_aligned(out_f, 16) && q8t_aligned(out_acc, 16);
+    g.ncls = 1;
+    g.fill = 0;
 #define Q8T_GO(CFG)                                                                                                   \
     {                                                                                                                 \
-        const int64_t tiles = (int64_t)((g.M + CFG::BM - 1) / CFG::BM) * (d->K / CFG::BN);                            \
+        g.mtiles = (g.M + CFG::BM - 1) / CFG::BM;                                                                     \
+        const int64_t tiles = (int64_t)g.mtiles * (d->K / CFG::BN);                                                   \
         hipLaunchKernelGGL(igemm_nhwc<CFG>, dim3(q8t_gemm::xcd_grid(tiles)), dim3(CFG::THREADS), conv_lds_bytes<CFG>(), \
-                           st, xn, rowsum, wt, colsum, qa, qb, g, tapoff, out_f, (int32_t *)out_acc);                 \
+                           st, xn, rowsum, wt, colsum, qa, qb, g, tapoff, clsinfo, out_f, (int32_t *)out_acc);        \
     }
     if (d->K % 128 == 0) Q8T_GO(q8t_gemm::Mid)
     else Q8T_GO(q8t_gemm::Small)
@@ -652,43 +743,52 @@ int q8t_nhwc_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
             }
     }
     for (int z = p.ncls; z <= MAXCLS; ++z) co.off[z] = nt;
+    // positions of every class
+    ClassGeo cg = {};
+    int maxM = 0;
+    for (int z = 0; z < p.ncls; ++z) {
+        int oh = p.OHf, ow = p.OWf;
+        if (which == 1) {
+            const int ph = z / stv, pw = z % stv;
+            oh = (p.OHf - ph + stv - 1) / stv;
+            ow = (p.OWf - pw + stv - 1) / stv;
+        }
+        const int m = oh > 0 && ow > 0 ? d->N * oh * ow : 0;
+        cg.v[z][0] = oh;
+        cg.v[z][1] = ow;
+        cg.v[z][2] = m;
+        cg.v[z][3] = co.off[z];
+        cg.v[z][4] = co.off[z + 1] - co.off[z];
+        if (m > maxM) maxM = m;
+    }
+    // stride 2 with taps in class (0, 0) only (a 1x1 filter without padding) and an even result size:
+    // that class's workgroups write the zeros of the other three as well
+    bool fill = which == 1 && stv == 2 && p.OHf % 2 == 0 && p.OWf % 2 == 0 && cg.v[0][4] > 0;
+    for (int z = 1; z < p.ncls; ++z) fill = fill && cg.v[z][4] == 0;
+    const int ncls = fill ? 1 : p.ncls;
+    if (fill) maxM = cg.v[0][2];
+    int *clsinfo = (int *)((char *)ws + p.o_cls);
     hipLaunchKernelGGL(repack_taps, dim3((unsigned)p.oc, (unsigned)p.ncls), dim3(kThreads), 0, st, (const int8_t *)b,
-                       d->K, d->C, d->R, d->S, which, rs_list, off_list, co, wt, colsum, tapoff);
+                       d->K, d->C, d->R, d->S, which, rs_list, off_list, co, cg, wt, colsum, tapoff, clsinfo);
     Q8T_LAUNCH_CHECK();
 
-    // 3. one launch per class
-    for (int z = 0; z < p.ncls; ++z) {
-        Geo g;
-        g.N = d->N;
-        g.IH = p.IH;
-        g.IW = p.IW;
-        g.Cp = p.red;
-        g.OC = p.oc;
-        g.OHf = p.OHf;
-        g.OWf = p.OWf;
-        if (which == 0) {
-            g.OH = p.OHf;
-            g.OW = p.OWf;
-            g.ish = g.isw = stv;
-            g.osh = g.osw = 1;
-            g.oph = g.opw = 0;
-        } else {
-            const int ph = z / stv, pw = z % stv;
-            g.OH = (p.OHf - ph + stv - 1) / stv;
-            g.OW = (p.OWf - pw + stv - 1) / stv;
-            g.ish = g.isw = 1;
-            g.osh = g.osw = stv;
-            g.oph = ph;
-            g.opw = pw;
-        }
-        if (g.OH <= 0 || g.OW <= 0) continue;
-        g.M = d->N * g.OH * g.OW;
-        g.T = co.off[z + 1] - co.off[z];
-        g.vec = q8t_aligned(out_f, 16) && q8t_aligned(out_acc, 16);
-        const int8_t *wz = wt + (size_t)co.off[z] * p.oc * p.red;
-        const int *cz = colsum + (size_t)z * p.oc;
-        // tile: 256 x 256 where the output channels allow it and the launch still fills the chip,
-        // else 128 x 128, else 128 x 64
+    // 3. one launch over all classes (the kernel picks its class from the tile index)
+    Geo g;
+    g.N = d->N;
+    g.IH = p.IH;
+    g.IW = p.IW;
+    g.Cp = p.red;
+    g.OC = p.oc;
+    g.OHf = p.OHf;
+    g.OWf = p.OWf;
+    g.ish = g.isw = which == 0 ? stv : 1;
+    g.osh = g.osw = which == 0 ? 1 : stv;
+    g.OH = g.OW = g.M = g.T = g.oph = g.opw = 0;   // per class, read by the kernel from the class table
+    g.vec = q8t_aligned(out_f, 16) && q8t_aligned(out_acc, 16);
+    g.ncls = ncls;
+    g.fill = fill ? 1 : 0;
+    // tile: 256 x 256 where the output channels allow it and the launch still fills the chip,
+    // else 128 x 128, else 128 x 64
 #define Q8T_GO(CFG)                                                                                                  \
     {                                                                                                                \
         static bool attr = false;                                                                                    \
@@ -698,15 +798,17 @@ int q8t_nhwc_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
                 return Q8T_ERR_HIP;                                                                                  \
             attr = true;                                                                                             \
         }                                                                                                            \
-        const int64_t tiles = (int64_t)((g.M + CFG::BM - 1) / CFG::BM) * (p.oc / CFG::BN);                           \
-        hipLaunchKernelGGL(igemm_nhwc<CFG>, dim3(q8t_gemm::xcd_grid(tiles)), dim3(CFG::THREADS), conv_lds_bytes<CFG>(), \
-                           st, xn, chansum, wz, cz, qa, qb, g, tapoff + co.off[z], out_f, (int32_t *)out_acc);       \
+        g.mtiles = (maxM + CFG::BM - 1) / CFG::BM;                                                                   \
+        const int64_t tiles = (int64_t)g.mtiles * ncls * (p.oc / CFG::BN);                                         \
+        if (tiles > 0)                                                                                               \
+            hipLaunchKernelGGL(igemm_nhwc<CFG>, dim3(q8t_gemm::xcd_grid(tiles)), dim3(CFG::THREADS),                 \
+                               conv_lds_bytes<CFG>(), st, xn, chansum, wt, colsum, qa, qb, g, tapoff, clsinfo, out_f, \
+                               (int32_t *)out_acc);                                                                  \
     }
-        if (p.oc % 256 == 0 && (int64_t)((g.M + 255) / 256) * (p.oc / 256) >= 128) Q8T_GO(q8t_gemm::Big)
-        else if (p.oc % 128 == 0) Q8T_GO(q8t_gemm::Mid)
-        else Q8T_GO(q8t_gemm::Small)
+    if (p.oc % 256 == 0 && (int64_t)((maxM + 255) / 256) * ncls * (p.oc / 256) >= 128) Q8T_GO(q8t_gemm::Big)
+    else if (p.oc % 128 == 0) Q8T_GO(q8t_gemm::Mid)
+    else Q8T_GO(q8t_gemm::Small)
 #undef Q8T_GO
-        Q8T_LAUNCH_CHECK();
-    }
+    Q8T_LAUNCH_CHECK();
     return Q8T_OK;
 }
