@@ -445,6 +445,194 @@ __global__ __launch_bounds__(C::THREADS, C::MINB) void igemm_nhwc(const int8_t *
     }
 }
 
+// ---- layer gradient at stride 2: the two stride classes (ph, 0) and (ph, 1) in one workgroup -----
+// Both classes enumerate the same positions (n, oh, ow) when the result width is even, and their
+// results are neighbours in memory: (2*oh + ph, 2*ow) and (2*oh + ph, 2*ow + 1).  A workgroup runs the
+// main loop once per class into two accumulator sets and writes 8-byte pairs (32-byte runs where a
+// lane's four rows share an image row) instead of isolated 4-byte elements, which is what the L2
+// request rate of a stride class on its own is bound by.
+template <class C>
+constexpr size_t conv_pair_lds_bytes()
+{
+    return conv_lds_bytes<C>() + C::BM * sizeof(int);
+}
+
+template <class C>
+__global__ __launch_bounds__(C::THREADS, 2) void igemm_nhwc_pair(const int8_t *__restrict__ xin,
+                                                                  const int *__restrict__ chansum,
+                                                                  const int8_t *__restrict__ wt,
+                                                                  const int *__restrict__ colsum,
+                                                                  const q8t_qparams *__restrict__ qpa,
+                                                                  const q8t_qparams *__restrict__ qpb, Geo g,
+                                                                  const int *__restrict__ tapoff,
+                                                                  const int *__restrict__ clsinfo,
+                                                                  float *__restrict__ out_f, int32_t *__restrict__ out_acc)
+{
+    constexpr int MT = C::MT, NT = C::NT, BM = C::BM, BN = C::BN;
+    extern __shared__ __align__(16) int8_t smem[];
+    int8_t *sA = smem, *sB = smem + 2 * BM * 64;
+    long long *roff = reinterpret_cast<long long *>(smem + C::LDS_BYTES);
+    int *rsA = reinterpret_cast<int *>(roff + BM);
+    int *rsB = rsA + BM;
+    int *stap = rsB + BM;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, kb = lane >> 4;
+    // logical tile order: output-channel tiles fastest, then the two row parities of one row tile
+    const int ny = g.OC / BN, total = g.mtiles * 2 * ny;
+    const int lg = q8t_gemm::xcd_logical(blockIdx.x, total);
+    if (lg >= total) return;
+    const int n0 = (lg % ny) * BN, ph = (lg / ny) & 1, m0 = (lg / (ny * 2)) * BM;
+    const int *ciA = clsinfo + (ph * 2) * CLS_INTS, *ciB = ciA + CLS_INTS;
+    const int OH = ciA[0], OW = ciA[1], M = ciA[2];
+    const int TA = ciA[4], TB = ciB[4];
+    if (m0 >= M) return;   // the whole workgroup leaves before any barrier
+    const int za = qpa->zero_point - (1 << (qpa->bits - 1)), zb = qpb->zero_point - (1 << (qpb->bits - 1));
+    const float sc = qpa->scale * qpb->scale;
+    const int OHW = OH * OW;
+
+    // the taps of the two classes are neighbours in the table
+    if (tid < TA + TB) stap[tid] = tapoff[ciA[3] + tid];
+    __syncthreads();
+    if (tid < BM) {
+        const int m = m0 + tid;
+        int sumA = 0, sumB = 0;
+        long long off = -1;
+        if (m < M) {
+            const int n = m / OHW, rem = m - n * OHW;
+            const int oh = rem / OW, ow = rem - oh * OW;
+            for (int t = 0; t < TA + TB; ++t) {
+                const int to = stap[t];
+                const int ih = oh + (int)(int16_t)(to & 0xFFFF), iw = ow + (to >> 16);
+                const int v = (unsigned)ih < (unsigned)g.IH && (unsigned)iw < (unsigned)g.IW
+                                  ? chansum[(n * g.IH + ih) * g.IW + iw]
+                                  : g.Cp * za;
+                sumA += t < TA ? v : 0;
+                sumB += t < TA ? 0 : v;
+            }
+            off = (long long)n * g.OC * g.OHf * g.OWf + (long long)(oh * 2 + ph) * g.OWf + ow * 2;
+        }
+        rsA[tid] = sumA;
+        rsB[tid] = sumB;
+        roff[tid] = off;
+    }
+    __syncthreads();
+
+    ConvOps<C> opsA;
+    opsA.xin = xin;
+    opsA.wt = wt + (size_t)ciA[3] * g.OC * g.Cp;
+    opsA.stap = (const __attribute__((address_space(3))) int *)stap;
+    opsA.IH = g.IH;
+    opsA.IW = g.IW;
+    opsA.Cp = g.Cp;
+    opsA.OC = g.OC;
+    opsA.CC = g.Cp >> 6;
+    opsA.q = tid & 3;
+    opsA.wrow = n0 + (tid >> 2);
+    opsA.padw = (uint32_t)(za & 255) * 0x01010101u;
+    opsA.lt = opsA.lc = 0;
+    {
+        const int am = m0 + (tid >> 2);
+        opsA.av0 = am < M;
+        opsA.an0 = opsA.ih0 = opsA.iw0 = 0;
+        if (opsA.av0) {
+            opsA.an0 = am / OHW;
+            const int rem = am - opsA.an0 * OHW;
+            opsA.ih0 = rem / OW;
+            opsA.iw0 = rem - opsA.ih0 * OW;
+        }
+        const int bm = am + C::RP;
+        opsA.av1 = bm < M;
+        opsA.an1 = opsA.ih1 = opsA.iw1 = 0;
+        if (opsA.av1) {
+            opsA.an1 = bm / OHW;
+            const int rem = bm - opsA.an1 * OHW;
+            opsA.ih1 = rem / OW;
+            opsA.iw1 = rem - opsA.ih1 * OW;
+        }
+    }
+    ConvOps<C> opsB = opsA;
+    opsB.wt = wt + (size_t)ciB[3] * g.OC * g.Cp;
+    opsB.stap = (const __attribute__((address_space(3))) int *)(stap + TA);
+
+    const int rowbase = C::rowbase(wave), colbase = C::colbase(wave);
+    v4i accA[MT][NT], accB[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) accA[mt][nt] = accB[mt][nt] = (v4i){0, 0, 0, 0};
+
+    q8t_gemm::pipeline<C>(opsA, TA * opsA.CC, sA, sB, accA);
+    q8t_gemm::pipeline<C>(opsB, TB * opsB.CC, sA, sB, accB);
+
+    // ---- epilogue: both classes corrected and dequantized, written as pairs ----
+    const uint32_t kzzA = (uint32_t)(TA * g.Cp) * (uint32_t)za * (uint32_t)zb;
+    const uint32_t kzzB = (uint32_t)(TB * g.Cp) * (uint32_t)za * (uint32_t)zb;
+    const long long plane = (long long)g.OHf * g.OWf;
+    const int *colA = colsum + (size_t)(ph * 2) * g.OC, *colB = colA + g.OC;
+    uint32_t csA[NT], csB[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        csA[nt] = (uint32_t)za * (uint32_t)colA[n0 + colbase + nt * 16 + l16];
+        csB[nt] = (uint32_t)za * (uint32_t)colB[n0 + colbase + nt * 16 + l16];
+    }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int r0 = rowbase + mt * 16 + kb * 4;
+        long long o[4];
+        uint32_t tA[4], tB[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            o[j] = roff[r0 + j];
+            tA[j] = kzzA - (uint32_t)zb * (uint32_t)rsA[r0 + j];
+            tB[j] = kzzB - (uint32_t)zb * (uint32_t)rsB[r0 + j];
+        }
+        const bool run = g.vec && o[0] >= 0 && o[1] == o[0] + 2 && o[2] == o[0] + 4 && o[3] == o[0] + 6;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const long long cb = (long long)(n0 + colbase + nt * 16 + l16) * plane;
+            int a[4], b[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                a[j] = (int)((uint32_t)accA[mt][nt][j] + tA[j] - csA[nt]);
+                b[j] = (int)((uint32_t)accB[mt][nt][j] + tB[j] - csB[nt]);
+            }
+            if (run && (((o[0] + cb) & 3) == 0)) {
+                if (out_acc) {
+                    *reinterpret_cast<int4 *>(out_acc + o[0] + cb) = make_int4(a[0], b[0], a[1], b[1]);
+                    *reinterpret_cast<int4 *>(out_acc + o[0] + cb + 4) = make_int4(a[2], b[2], a[3], b[3]);
+                }
+                if (out_f) {
+                    *reinterpret_cast<float4 *>(out_f + o[0] + cb) =
+                        make_float4(sc * (float)a[0], sc * (float)b[0], sc * (float)a[1], sc * (float)b[1]);
+                    *reinterpret_cast<float4 *>(out_f + o[0] + cb + 4) =
+                        make_float4(sc * (float)a[2], sc * (float)b[2], sc * (float)a[3], sc * (float)b[3]);
+                }
+            } else if (g.vec) {   // even result width and plane: every pair is 8-byte aligned
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (o[j] < 0) continue;
+                    if (out_acc) *reinterpret_cast<int2 *>(out_acc + o[j] + cb) = make_int2(a[j], b[j]);
+                    if (out_f) *reinterpret_cast<float2 *>(out_f + o[j] + cb) = make_float2(sc * (float)a[j], sc * (float)b[j]);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (o[j] < 0) continue;
+                    if (out_acc) {
+                        out_acc[o[j] + cb] = a[j];
+                        out_acc[o[j] + cb + 1] = b[j];
+                    }
+                    if (out_f) {
+                        out_f[o[j] + cb] = sc * (float)a[j];
+                        out_f[o[j] + cb + 1] = sc * (float)b[j];
+                    }
+                }
+            }
+        }
+    }
+}
+
 // ---- forward with few input channels (the network's first layer) --------------------------------
 // The reduction (c, r, s) of an output position is laid out explicitly: xn[m][Kc] with
 // Kc = C*R*S rounded up to a multiple of 64, entry c*R*S + r*S + s = the input code under that tap
@@ -787,6 +975,31 @@ int q8t_nhwc_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
     g.vec = q8t_aligned(out_f, 16) && q8t_aligned(out_acc, 16);
     g.ncls = ncls;
     g.fill = fill ? 1 : 0;
+    // stride 2 with an even result width: the classes (ph, 0) and (ph, 1) share their positions and are
+    // computed by one workgroup, which writes their interleaved results as pairs
+    if (which == 1 && stv == 2 && !fill && p.OWf % 2 == 0 && cg.v[0][2] > 0) {
+        const int pairM = cg.v[0][2];   // class (0, 0) is the larger row parity
+#define Q8T_GOP(CFG)                                                                                                 \
+    {                                                                                                                \
+        static bool attr = false;                                                                                    \
+        if (!attr && conv_pair_lds_bytes<CFG>() > 65536) {                                                           \
+            if (hipFuncSetAttribute((const void *)igemm_nhwc_pair<CFG>, hipFuncAttributeMaxDynamicSharedMemorySize,  \
+                                    (int)conv_pair_lds_bytes<CFG>()) != hipSuccess)                                  \
+                return Q8T_ERR_HIP;                                                                                  \
+            attr = true;                                                                                             \
+        }                                                                                                            \
+        g.mtiles = (pairM + CFG::BM - 1) / CFG::BM;                                                                  \
+        const int64_t tiles = (int64_t)g.mtiles * 2 * (p.oc / CFG::BN);                                              \
+        hipLaunchKernelGGL(igemm_nhwc_pair<CFG>, dim3(q8t_gemm::xcd_grid(tiles)), dim3(CFG::THREADS),                \
+                           conv_pair_lds_bytes<CFG>(), st, xn, chansum, wt, colsum, qa, qb, g, tapoff, clsinfo, out_f, \
+                           (int32_t *)out_acc);                                                                      \
+    }
+        if (p.oc % 128 == 0) Q8T_GOP(q8t_gemm::Mid)
+        else Q8T_GOP(q8t_gemm::Small)
+#undef Q8T_GOP
+        Q8T_LAUNCH_CHECK();
+        return Q8T_OK;
+    }
     // tile: 256 x 256 where the output channels allow it and the launch still fills the chip,
     // else 128 x 128, else 128 x 64
 #define Q8T_GO(CFG)                                                                                                  \

@@ -121,6 +121,7 @@ CONV_CASES = [
     (2, 64, 8, 8, 64, 2, 2, 2, 0),       # even filter size, no padding
     (130, 64, 3, 3, 64, 3, 3, 1, 1),     # many tiny images, ragged last tile
     (2, 64, 11, 9, 64, 3, 3, 2, 0),      # input rows and columns no output touches (zero layer gradient there)
+    (2, 64, 9, 12, 128, 3, 3, 2, 1),     # stride 2, even width: class pairs per workgroup, odd height (uneven row parities)
     (3, 64, 14, 18, 128, 1, 1, 2, 0),    # 1x1 at stride 2: three stride classes without taps, zero-filled by the fourth
     (2, 64, 15, 16, 64, 1, 1, 2, 0),     # the same with an odd height: empty classes handled on their own
     # GEMM form of the weight gradient (byte planes x im2col rows)
