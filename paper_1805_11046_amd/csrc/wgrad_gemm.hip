@@ -152,33 +152,57 @@ __global__ __launch_bounds__(kThreads) void im2col_rows(const int8_t *__restrict
 // NI images (NI*P*Q a multiple of 4, so that its stretch of every row starts on a dword), then
 // every thread builds, for one channel, one dword (4 consecutive positions) for each of the R*S
 // taps.  The input is read once instead of R*S times and every store is a full dword.
-__global__ __launch_bounds__(kThreads) void im2col_planes(const int8_t *__restrict__ x, ConvG g, int NI, int CG, int64_t Mtot,
-                                                          int64_t Mp, const q8t_qparams *__restrict__ qpx,
+// A staged plane has (H + 2*pad) rows of `pitch` bytes; the image starts at column L = pad rounded
+// up to a multiple of 4 and the pitch is a multiple of 4, so that an aligned dword of the input
+// (W % 4 == 0) is an aligned dword of the plane.
+struct PlaneG {
+    int L, pitch, PB;   // left margin, row pitch, bytes per plane (a multiple of 4)
+    int vec;            // the input can be read as aligned dwords
+};
+
+__global__ __launch_bounds__(kThreads) void im2col_planes(const int8_t *__restrict__ x, ConvG g, PlaneG pg, int NI, int CG,
+                                                          int64_t Mtot, int64_t Mp, const q8t_qparams *__restrict__ qpx,
                                                           int8_t *__restrict__ B)
 {
     extern __shared__ __align__(16) int8_t planes[];
     const int c0 = blockIdx.y * CG, n0 = blockIdx.x * NI;
     const int ni = min(NI, g.N - n0), cg = min(CG, g.C - c0);
-    const int Hp = g.H + 2 * g.pad, Wp = g.W + 2 * g.pad, PB = Hp * Wp;
+    const int PB = pg.PB, pitch = pg.pitch;
     const int PQ = g.P * g.Q, HW = g.H * g.W;
     const int zsx = qpx->zero_point - (1 << (qpx->bits - 1));
-    for (int i = threadIdx.x; i < cg * NI * PB; i += kThreads) planes[i] = (int8_t)zsx;
-    __syncthreads();
-    const float rHW = 1.0f / (float)HW, rW = 1.0f / (float)g.W, rPQ = 1.0f / (float)PQ, rQ = 1.0f / (float)g.Q;
-    // plane (cl, nl) sits at (cl*NI + nl)*PB
-    for (int i = threadIdx.x; i < cg * ni * HW; i += kThreads) {
-        const int pl = fdiv(i, HW, rHW), t = i - pl * HW, h = fdiv(t, g.W, rW), w = t - h * g.W;
-        const int cl = pl / ni, nl = pl - cl * ni;
-        planes[(cl * NI + nl) * PB + (h + g.pad) * Wp + w + g.pad] = x[((size_t)(n0 + nl) * g.C + c0 + cl) * HW + t];
+    const uint32_t zb = (uint32_t)(zsx & 255);
+    {
+        uint32_t *pw = reinterpret_cast<uint32_t *>(planes);
+        for (int i = threadIdx.x; i < (cg * NI * PB) >> 2; i += kThreads) pw[i] = zb * 0x01010101u;
     }
     __syncthreads();
+    // plane (cl, nl) sits at (cl*NI + nl)*PB
+    if (pg.vec) {
+        const int HW4 = HW >> 2, W4 = g.W >> 2;
+        const float rHW4 = 1.0f / (float)HW4, rW4 = 1.0f / (float)W4;
+        for (int i = threadIdx.x; i < cg * ni * HW4; i += kThreads) {
+            const int pl = fdiv(i, HW4, rHW4), t = i - pl * HW4, h = fdiv(t, W4, rW4), w4 = t - h * W4;
+            const int cl = pl / ni, nl = pl - cl * ni;
+            const uint32_t v = *reinterpret_cast<const uint32_t *>(x + ((size_t)(n0 + nl) * g.C + c0 + cl) * HW + (size_t)t * 4);
+            *reinterpret_cast<uint32_t *>(planes + (cl * NI + nl) * PB + (h + g.pad) * pitch + pg.L + w4 * 4) = v;
+        }
+    } else {
+        const float rHW = 1.0f / (float)HW, rW = 1.0f / (float)g.W;
+        for (int i = threadIdx.x; i < cg * ni * HW; i += kThreads) {
+            const int pl = fdiv(i, HW, rHW), t = i - pl * HW, h = fdiv(t, g.W, rW), w = t - h * g.W;
+            const int cl = pl / ni, nl = pl - cl * ni;
+            planes[(cl * NI + nl) * PB + (h + g.pad) * pitch + pg.L + w] = x[((size_t)(n0 + nl) * g.C + c0 + cl) * HW + t];
+        }
+    }
+    __syncthreads();
+    const float rPQ = 1.0f / (float)PQ, rQ = 1.0f / (float)g.Q;
     const int64_t mbase = (int64_t)n0 * PQ;
     const bool last = n0 + NI >= g.N;
     const int64_t mend = last ? Mp : mbase + (int64_t)NI * PQ;   // the last group also writes the padding
     const int ndw = (int)((mend - mbase) >> 2);
     const float rndw = 1.0f / (float)ndw;
     const int RS = g.R * g.S;
-    const uint32_t zb = (uint32_t)(zsx & 255);
+    const int col0 = pg.L - g.pad;   // plane column of input column -pad
     for (int it = threadIdx.x; it < cg * ndw; it += kThreads) {
         const int cl = fdiv(it, ndw, rndw), dp = it - cl * ndw;
         int off[4];
@@ -188,13 +212,13 @@ __global__ __launch_bounds__(kThreads) void im2col_planes(const int8_t *__restri
             off[j] = -1;
             if (mbase + e < Mtot) {
                 const int nl = fdiv(e, PQ, rPQ), t = e - nl * PQ, pp = fdiv(t, g.Q, rQ), qq = t - pp * g.Q;
-                off[j] = (cl * NI + nl) * PB + pp * g.stride * Wp + qq * g.stride;
+                off[j] = (cl * NI + nl) * PB + pp * g.stride * pitch + qq * g.stride + col0;
             }
         }
         int8_t *dst = B + ((size_t)(c0 + cl) * RS) * Mp + mbase + (int64_t)dp * 4;
         for (int r = 0; r < g.R; ++r)
             for (int s = 0; s < g.S; ++s) {
-                const int o = r * Wp + s;
+                const int o = r * pitch + s;
                 uint32_t v = 0;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -583,7 +607,12 @@ int q8t_gemm_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams
         const int64_t blocks = (chunks * p.CRS + kThreads - 1) / kThreads;
         const int PQ = p.P * p.Q;
         const int NI = PQ % 4 == 0 ? 1 : (PQ % 2 == 0 ? 2 : 4);
-        const size_t lds1 = (size_t)NI * (d->H + 2 * d->pad) * (d->W + 2 * d->pad);
+        PlaneG pg;
+        pg.L = (d->pad + 3) & ~3;
+        pg.pitch = (pg.L + d->W + d->pad + 3) & ~3;
+        pg.PB = (d->H + 2 * d->pad) * pg.pitch;
+        pg.vec = d->W % 4 == 0 && q8t_aligned(x, 4);
+        const size_t lds1 = (size_t)NI * pg.PB;
         // channels per workgroup: about 1024 dwords of work per tap, within 32 KB of LDS
         int CG = (int)(4096 / ((int64_t)NI * PQ) > 0 ? 4096 / ((int64_t)NI * PQ) : 1);
         if (lds1 * CG > 32768) CG = (int)(32768 / lds1 > 0 ? 32768 / lds1 : 1);
@@ -592,7 +621,7 @@ int q8t_gemm_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams
         if (lds <= 65536 && (int64_t)CG * (NI * (int64_t)PQ + 64) < (1 << 24) && (int64_t)CG * NI * d->H * d->W < (1 << 24) &&
             (d->C + CG - 1) / CG <= 65535)
             hipLaunchKernelGGL(im2col_planes, dim3((unsigned)((d->N + NI - 1) / NI), (unsigned)((d->C + CG - 1) / CG)),
-                               dim3(kThreads), lds, st, x, g, NI, CG, p.Mtot, p.Mp, qx, B);
+                               dim3(kThreads), lds, st, x, g, pg, NI, CG, p.Mtot, p.Mp, qx, B);
         else
             hipLaunchKernelGGL(im2col_rows, dim3((unsigned)blocks), dim3(kThreads), 0, st, x, g, p.Mtot, p.Mp, qx, B);
         Q8T_LAUNCH_CHECK();
