@@ -157,7 +157,7 @@ __global__ __launch_bounds__(kThreads) void im2col_rows(const int8_t *__restrict
 // (W % 4 == 0) is an aligned dword of the plane.
 struct PlaneG {
     int L, pitch, PB;   // left margin, row pitch, bytes per plane (a multiple of 4)
-    int vec;            // the input can be read as aligned dwords
+    int vec;            // bytes per aligned input load: 4, 2 or 1
 };
 
 __global__ __launch_bounds__(kThreads) void im2col_planes(const int8_t *__restrict__ x, ConvG g, PlaneG pg, int NI, int CG,
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void im2col_planes(const int8_t *__restri
     }
     __syncthreads();
     // plane (cl, nl) sits at (cl*NI + nl)*PB
-    if (pg.vec) {
+    if (pg.vec == 4) {
         const int HW4 = HW >> 2, W4 = g.W >> 2;
         const float rHW4 = 1.0f / (float)HW4, rW4 = 1.0f / (float)W4;
         for (int i = threadIdx.x; i < cg * ni * HW4; i += kThreads) {
@@ -185,6 +185,15 @@ __global__ __launch_bounds__(kThreads) void im2col_planes(const int8_t *__restri
             const int cl = pl / ni, nl = pl - cl * ni;
             const uint32_t v = *reinterpret_cast<const uint32_t *>(x + ((size_t)(n0 + nl) * g.C + c0 + cl) * HW + (size_t)t * 4);
             *reinterpret_cast<uint32_t *>(planes + (cl * NI + nl) * PB + (h + g.pad) * pitch + pg.L + w4 * 4) = v;
+        }
+    } else if (pg.vec == 2) {
+        const int HW2 = HW >> 1, W2 = g.W >> 1;
+        const float rHW2 = 1.0f / (float)HW2, rW2 = 1.0f / (float)W2;
+        for (int i = threadIdx.x; i < cg * ni * HW2; i += kThreads) {
+            const int pl = fdiv(i, HW2, rHW2), t = i - pl * HW2, h = fdiv(t, W2, rW2), w2 = t - h * W2;
+            const int cl = pl / ni, nl = pl - cl * ni;
+            const uint16_t v = *reinterpret_cast<const uint16_t *>(x + ((size_t)(n0 + nl) * g.C + c0 + cl) * HW + (size_t)t * 2);
+            *reinterpret_cast<uint16_t *>(planes + (cl * NI + nl) * PB + (h + g.pad) * pitch + pg.L + w2 * 2) = v;
         }
     } else {
         const float rHW = 1.0f / (float)HW, rW = 1.0f / (float)g.W;
@@ -611,7 +620,7 @@ int q8t_gemm_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams
         pg.L = (d->pad + 3) & ~3;
         pg.pitch = (pg.L + d->W + d->pad + 3) & ~3;
         pg.PB = (d->H + 2 * d->pad) * pg.pitch;
-        pg.vec = d->W % 4 == 0 && q8t_aligned(x, 4);
+        pg.vec = d->W % 4 == 0 && q8t_aligned(x, 4) ? 4 : (d->W % 2 == 0 && q8t_aligned(x, 2) ? 2 : 1);
         const size_t lds1 = (size_t)NI * pg.PB;
         // channels per workgroup: about 1024 dwords of work per tap, within 32 KB of LDS
         int CG = (int)(4096 / ((int64_t)NI * PQ) > 0 ? 4096 / ((int64_t)NI * PQ) : 1);
