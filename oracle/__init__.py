@@ -288,6 +288,37 @@ def range_bn_bwd(x, dy, stats, gamma=None, eps=0.0, sums=None):
     return dx, dgamma, dbeta
 
 
+def range_bn_relu_fwd(x, stats, gamma=None, beta=None, eps=0.0, quantized=False):
+    """Range BN followed by ReLU for given statistics.
+    Returns (y, q_stored or None, QParams or None)."""
+    x, stats = _f32(x), _f32(stats)
+    N, Cc, H, W = x.shape
+    gamma, beta = _opt_f32(gamma), _opt_f32(beta)
+    y = np.empty(x.shape, np.float32)
+    q = np.empty(x.shape, np.int8) if quantized else None
+    qp = QParams()
+    lib().orc_range_bn_relu_fwd_apply(_p(x), N, Cc, H, W, _p(gamma), _p(beta), C.c_float(eps),
+                                      _p(stats), _p(y), _p(q), C.byref(qp))
+    return y, q, (qp if quantized else None)
+
+
+def range_bn_relu_mask(x, dy, stats, gamma=None, beta=None, eps=0.0):
+    """The upstream gradient after the backward of the ReLU that follows a Range BN."""
+    x, dy, stats = _f32(x), _f32(dy), _f32(stats)
+    N, Cc, H, W = x.shape
+    gamma, beta = _opt_f32(gamma), _opt_f32(beta)
+    out = np.empty(x.shape, np.float32)
+    lib().orc_range_bn_relu_mask(_p(x), _p(dy), _p(stats), N, Cc, H, W, _p(gamma), _p(beta),
+                                 C.c_float(eps), _p(out))
+    return out
+
+
+def range_bn_relu_bwd(x, dy, stats, gamma=None, beta=None, eps=0.0, sums=None):
+    """Backward of Range BN + ReLU: the ReLU mask, then the Range BN backward on the masked
+    gradient.  Returns (dx, dgamma, dbeta)."""
+    return range_bn_bwd(x, range_bn_relu_mask(x, dy, stats, gamma, beta, eps), stats, gamma, eps, sums)
+
+
 def range_bn_fwd_f64(x, gamma=None, beta=None, eps=0.0):
     x = np.ascontiguousarray(x, dtype=np.float64)
     N, Cc, H, W = x.shape

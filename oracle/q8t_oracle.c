@@ -627,6 +627,80 @@ void orc_range_bn_bwd(const float *x, const float *dy, const float *stats, int N
     free(sums);
 }
 
+/*
+ * Range BN followed by ReLU, for GIVEN statistics (a widening of Section 4's remark that the
+ * normalizer already knows the extrema: the rectified output's range is known too).
+ *   v = max(BN(x), 0), taken as (BN(x) > 0 ? BN(x) : +0)
+ *  y        (nullable) fp32 output
+ *  q_stored (nullable) 8-bit per-tensor codes of v; range = the images of every channel's extrema
+ *           under the same map, rectified: [max(lo, 0), max(hi, 0)].
+ */
+void orc_range_bn_relu_fwd_apply(const float *x, int N, int C, int H, int W, const float *gamma,
+                                 const float *beta, float eps, const float *stats, float *y,
+                                 int8_t *q_stored, orc_qparams *qp_out)
+{
+    const int64_t HW = (int64_t)H * W;
+    const int64_t n = (int64_t)N * HW;
+    const float cn = (float)orc_range_bn_scale(n);
+    orc_qparams qp;
+    memset(&qp, 0, sizeof qp);
+    if (q_stored || qp_out) {
+        float vmin = INFINITY, vmax = -INFINITY;
+        for (int c = 0; c < C; ++c) {
+            float g = gamma ? gamma[c] : 1.0f, b = beta ? beta[c] : 0.0f;
+            float inv = orc_bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
+            float a = orc_bn_apply(stats[C + c], stats[c], inv, g, b);
+            float z = orc_bn_apply(stats[2 * C + c], stats[c], inv, g, b);
+            float lo = a < z ? a : z, hi = a < z ? z : a;
+            if (lo < vmin) vmin = lo;
+            if (hi > vmax) vmax = hi;
+        }
+        vmin = vmin > 0.0f ? vmin : 0.0f;
+        vmax = vmax > 0.0f ? vmax : 0.0f;
+        orc_qparams_from_range(vmin, vmax, 8, &qp);
+        if (qp_out) *qp_out = qp;
+    }
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < N; ++b)
+        for (int c = 0; c < C; ++c) {
+            float g = gamma ? gamma[c] : 1.0f, be = beta ? beta[c] : 0.0f;
+            float mu = stats[c];
+            float inv = orc_bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
+            int64_t base = ((int64_t)b * C + c) * HW;
+            for (int64_t i = 0; i < HW; ++i) {
+                float v = orc_bn_apply(x[base + i], mu, inv, g, be);
+                v = v > 0.0f ? v : 0.0f;
+                if (y) y[base + i] = v;
+                if (q_stored)
+                    q_stored[base + i] = (int8_t)(orc_level(v, &qp, 0, 0, 0) - 128);
+            }
+        }
+}
+
+/*
+ * Backward of the ReLU that follows a Range BN: the upstream gradient passes where the
+ * (recomputed, fp32) BN output is positive and is zero elsewhere (derivative 0 at 0).
+ * The Range BN backward then runs on the masked gradient.
+ */
+void orc_range_bn_relu_mask(const float *x, const float *dy, const float *stats, int N, int C, int H,
+                            int W, const float *gamma, const float *beta, float eps, float *dy_masked)
+{
+    const int64_t HW = (int64_t)H * W;
+    const int64_t n = (int64_t)N * HW;
+    const float cn = (float)orc_range_bn_scale(n);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < N; ++b)
+        for (int c = 0; c < C; ++c) {
+            float g = gamma ? gamma[c] : 1.0f, be = beta ? beta[c] : 0.0f;
+            float inv = orc_bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
+            int64_t base = ((int64_t)b * C + c) * HW;
+            for (int64_t i = 0; i < HW; ++i) {
+                float v = orc_bn_apply(x[base + i], stats[c], inv, g, be);
+                dy_masked[base + i] = v > 0.0f ? dy[base + i] : 0.0f;
+            }
+        }
+}
+
 /* ------------------------------------------------------------------ */
 /* fp64 definitions, used only to pin the fp32 sequences above.        */
 

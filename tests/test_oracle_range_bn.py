@@ -208,3 +208,83 @@ def test_backward_sums_feed_dgamma_and_dbeta():
     _, dgamma, dbeta = oracle.range_bn_bwd(x, dy, stats, None, 1e-5)
     assert np.allclose(dbeta, dy.astype(np.float64).sum(axis=(0, 2, 3)), rtol=1e-6)
     assert np.allclose(dgamma, (dy.astype(np.float64) * y).sum(axis=(0, 2, 3)), rtol=1e-6, atol=1e-6)
+
+
+# ---------------------------------------------------------------- Range BN followed by ReLU
+def test_relu_output_range_is_known_without_a_pass_over_the_data():
+    # the rectified output's extrema are the rectified images of the channel extrema: quantizing
+    # with that analytic range gives the codes a min/max search over the rectified output gives
+    x = _gauss(11, 8, 6, 7, 6)
+    g = np.random.default_rng(12)
+    gamma = g.uniform(-2, 2, 6).astype(np.float32)
+    beta = g.uniform(-1, 1, 6).astype(np.float32)
+    stats = oracle.range_bn_stats(x)
+    y0, _, _, _ = oracle.range_bn_fwd(x, gamma, beta, 1e-5, stats=stats)
+    y, q, qp = oracle.range_bn_relu_fwd(x, stats, gamma, beta, 1e-5, quantized=True)
+    assert (y >= 0).all() and np.array_equal(y[y0 > 0], y0[y0 > 0]) and (y[y0 <= 0] == 0).all()
+    assert qp.vmin == 0.0 and qp.vmax == y.max()
+    s2, _, qp2 = oracle.quantize(y, 8)
+    assert qp2.as_tuple() == qp.as_tuple()
+    assert np.array_equal(s2, q)
+    # zero is exactly representable: every rectified element sits on the zero point, whose
+    # dequantized value is exactly 0
+    assert (q[y == 0].astype(np.int32) + 128 == qp.zero_point).all()
+    assert (oracle.dequantize(q, qp)[y == 0] == 0).all()
+
+
+def test_relu_with_an_all_negative_output_degenerates_cleanly():
+    x = _gauss(13, 4, 2, 3, 3)
+    stats = oracle.range_bn_stats(x)
+    beta = np.full(2, -100.0, np.float32)
+    y, q, qp = oracle.range_bn_relu_fwd(x, stats, None, beta, 1e-5, quantized=True)
+    assert (y == 0).all() and qp.vmin == 0.0 and qp.vmax == 0.0
+    assert (oracle.dequantize(q, qp) == 0).all()
+
+
+def test_relu_backward_against_central_differences():
+    g = np.random.default_rng(14)
+    N, C, H, W = 3, 2, 2, 3
+    x = g.standard_normal((N, C, H, W)).astype(np.float32)
+    dy = g.standard_normal((N, C, H, W)).astype(np.float32)
+    gamma = g.uniform(0.5, 2, C).astype(np.float32)
+    beta = g.uniform(-0.5, 0.5, C).astype(np.float32)
+    eps = 1e-3
+    stats = oracle.range_bn_stats(x)
+    dx, dgamma, dbeta = oracle.range_bn_relu_bwd(x, dy, stats, gamma, beta, eps)
+    xd, dyd = x.astype(np.float64), dy.astype(np.float64)
+
+    def loss(xx, gg, bb):
+        return float((np.maximum(oracle.range_bn_fwd_f64(xx, gg, bb, eps), 0.0) * dyd).sum())
+
+    y64 = oracle.range_bn_fwd_f64(xd, gamma, beta, eps)
+    assert np.abs(y64).min() > 1e-3          # no element sits on the kink
+    assert (y64 > 0).any() and (y64 < 0).any()
+    h = 1e-6
+    num = np.zeros_like(xd)
+    for idx in np.ndindex(*x.shape):
+        xp, xm = xd.copy(), xd.copy()
+        xp[idx] += h
+        xm[idx] -= h
+        num[idx] = (loss(xp, gamma, beta) - loss(xm, gamma, beta)) / (2 * h)
+    assert np.allclose(dx, num, rtol=2e-4, atol=2e-5)
+    for c in range(C):
+        gp, gm = gamma.astype(np.float64).copy(), gamma.astype(np.float64).copy()
+        gp[c] += h
+        gm[c] -= h
+        assert dgamma[c] == pytest.approx((loss(xd, gp, beta) - loss(xd, gm, beta)) / (2 * h), rel=1e-4, abs=1e-5)
+        bp, bm = beta.astype(np.float64).copy(), beta.astype(np.float64).copy()
+        bp[c] += h
+        bm[c] -= h
+        assert dbeta[c] == pytest.approx((loss(xd, gamma, bp) - loss(xd, gamma, bm)) / (2 * h), rel=1e-4, abs=1e-5)
+
+
+def test_relu_mask_is_the_sign_of_the_forward_output():
+    x = _gauss(15, 4, 3, 5, 5)
+    g = np.random.default_rng(16)
+    dy = g.standard_normal(x.shape).astype(np.float32)
+    gamma = g.uniform(-2, 2, 3).astype(np.float32)
+    beta = g.uniform(-1, 1, 3).astype(np.float32)
+    stats = oracle.range_bn_stats(x)
+    y, _, _, _ = oracle.range_bn_fwd(x, gamma, beta, 1e-5, stats=stats)
+    m = oracle.range_bn_relu_mask(x, dy, stats, gamma, beta, 1e-5)
+    assert np.array_equal(m, np.where(y > 0, dy, np.float32(0)))
