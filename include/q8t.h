@@ -209,6 +209,28 @@ int q8t_range_bn_bwd_bifurcate(const float *x, const float *dy, const float *sta
                                uint64_t seed8, uint64_t seed16, int8_t *q8_out, q8t_qparams *qp8_out,
                                int16_t *q16_out, q8t_qparams *qp16_out, void *ws, void *stream);
 
+/* Range BN followed by ReLU in one pass (eq. (range) of Section 3, then max(., 0); the 8-bit
+ * output follows Section 4's remark that the normalizer already knows the extrema: the range of
+ * the rectified output is [max(lo, 0), max(hi, 0)] with lo / hi the images of the channel
+ * extrema, so zero is always a code).  Arguments as q8t_range_bn_fwd_apply; with q_out the codes
+ * are ready to be the next layer's 8-bit operand and y may be NULL, which leaves 5 bytes per
+ * element of traffic where normalization, rectification and quantization as separate passes
+ * move 25. */
+int q8t_range_bn_relu_fwd_apply(const float *x, int N, int C, int H, int W, const float *gamma, const float *beta,
+                                float eps, const float *stats, float *y, int8_t *q_out, q8t_qparams *qp_out,
+                                void *stream);
+
+/* Backward of the above fused with the bifurcated quantization: dy is the gradient with respect
+ * to the rectified output; it passes where the forward output gamma*xhat + beta (recomputed from
+ * x and stats in the forward's fp32 arithmetic) is positive and counts as zero elsewhere
+ * (derivative 0 at 0), then the rule of q8t_range_bn_bwd_bifurcate applies, dgamma / dbeta
+ * included.  beta is nullable (0).  Same workspace as q8t_range_bn_bwd_bifurcate. */
+int q8t_range_bn_relu_bwd_bifurcate(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
+                                    const float *gamma, const float *beta, float eps, float *dx, float *dgamma,
+                                    float *dbeta, uint64_t seed8, uint64_t seed16, int8_t *q8_out,
+                                    q8t_qparams *qp8_out, int16_t *q16_out, q8t_qparams *qp16_out, void *ws,
+                                    void *stream);
+
 /* C(n) = 1/sqrt(2 ln n) (Section 3), host arithmetic in double.  n >= 2. */
 double q8t_range_bn_scale(int64_t n);
 

@@ -69,6 +69,9 @@ _SIGS = {
     "q8t_qconv_fwd_bn_stats_workspace_size": (_sz, [C.POINTER(ConvDesc)]),
     "q8t_qconv_fwd_bn_stats": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "q8t_range_bn_fwd_apply": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_range_bn_relu_fwd_apply": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_range_bn_relu_bwd_bifurcate": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp, _u64, _u64, _vp,
+                                              _vp, _vp, _vp, _vp, _vp]),
     "q8t_range_bn_bwd_bifurcate_workspace_size": (_sz, [_i, _i, _i, _i]),
     "q8t_range_bn_bwd_bifurcate": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _f, _vp, _vp, _vp, _u64, _u64, _vp, _vp,
                                         _vp, _vp, _vp, _vp]),
@@ -332,6 +335,22 @@ def range_bn_fwd_apply(x, stats, gamma=None, beta=None, eps=0.0, quantized=False
     return y, q, qp
 
 
+def range_bn_relu_fwd_apply(x, stats, gamma=None, beta=None, eps=0.0, quantized=False, want_y=True, y_out=None,
+                            q_out=None, qp_out=None):
+    """Range BN + ReLU forward from given statistics.  Returns (y or None, q or None, qp or None)."""
+    _dev(x), _dev(stats)
+    N, Cc, H, W = x.shape
+    dev = x.device
+    y = y_out if y_out is not None else (torch.empty_like(x) if want_y else None)
+    q = qp = None
+    if quantized:
+        q = q_out if q_out is not None else torch.empty(x.shape, dtype=torch.int8, device=dev)
+        qp = qp_out if qp_out is not None else new_qparams(dev)
+    _check(_lib.q8t_range_bn_relu_fwd_apply(_ptr(x), N, Cc, H, W, _ptr(gamma), _ptr(beta), float(eps), _ptr(stats),
+                                            _ptr(y), _ptr(q), _ptr(qp), _stream()), "q8t_range_bn_relu_fwd_apply")
+    return y, q, qp
+
+
 def range_bn_bwd(x, dy, stats, gamma=None, eps=0.0, dx_out=None, ws=None):
     """Returns (dx, dgamma, dbeta)."""
     _dev(x), _dev(dy), _dev(stats)
@@ -344,6 +363,29 @@ def range_bn_bwd(x, dy, stats, gamma=None, eps=0.0, dx_out=None, ws=None):
     _check(_lib.q8t_range_bn_bwd(_ptr(x), _ptr(dy), _ptr(stats), N, Cc, H, W, _ptr(gamma), float(eps), _ptr(dx),
                                  _ptr(dgamma), _ptr(dbeta), _ptr(ws), _stream()), "q8t_range_bn_bwd")
     return dx, dgamma, dbeta
+
+
+def range_bn_relu_bwd_bifurcate(x, dy, stats, gamma=None, beta=None, eps=0.0, seed8=0, seed16=1, dx_out=None,
+                                q8_out=None, qp8_out=None, q16_out=None, qp16_out=None, ws=None):
+    """Backward of Range BN + ReLU + bifurcated quantization of dx in one call.
+    Returns (dx, dgamma, dbeta, q8, qp8, q16, qp16)."""
+    _dev(x), _dev(dy), _dev(stats)
+    N, Cc, H, W = x.shape
+    dev = x.device
+    dx = dx_out if dx_out is not None else torch.empty_like(x)
+    dgamma = torch.empty(Cc, dtype=torch.float32, device=dev)
+    dbeta = torch.empty(Cc, dtype=torch.float32, device=dev)
+    q8 = q8_out if q8_out is not None else torch.empty(x.shape, dtype=torch.int8, device=dev)
+    q16 = q16_out if q16_out is not None else torch.empty(x.shape, dtype=torch.int16, device=dev)
+    qp8 = qp8_out if qp8_out is not None else new_qparams(dev)
+    qp16 = qp16_out if qp16_out is not None else new_qparams(dev)
+    ws = ws if ws is not None else workspace(_lib.q8t_range_bn_bwd_bifurcate_workspace_size(N, Cc, H, W), dev)
+    _check(_lib.q8t_range_bn_relu_bwd_bifurcate(_ptr(x), _ptr(dy), _ptr(stats), N, Cc, H, W, _ptr(gamma), _ptr(beta),
+                                                float(eps), _ptr(dx), _ptr(dgamma), _ptr(dbeta),
+                                                int(seed8) & (2 ** 64 - 1), int(seed16) & (2 ** 64 - 1), _ptr(q8),
+                                                _ptr(qp8), _ptr(q16), _ptr(qp16), _ptr(ws), _stream()),
+           "q8t_range_bn_relu_bwd_bifurcate")
+    return dx, dgamma, dbeta, q8, qp8, q16, qp16
 
 
 def range_bn_bwd_bifurcate(x, dy, stats, gamma=None, eps=0.0, seed8=0, seed16=1, dx_out=None, q8_out=None,

@@ -159,7 +159,7 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_finalize(const FwdPartial *__
 // per-tensor range of the 8-bit output from ready-made statistics (one workgroup)
 __global__ __launch_bounds__(kThreads) void bn_qrange_from_stats(const float *__restrict__ stats, int C, float cn, float eps,
                                                                  const float *__restrict__ gamma,
-                                                                 const float *__restrict__ beta,
+                                                                 const float *__restrict__ beta, int relu,
                                                                  q8t_qparams *__restrict__ qp_out)
 {
     __shared__ float smf[kThreads / 64];
@@ -174,6 +174,10 @@ __global__ __launch_bounds__(kThreads) void bn_qrange_from_stats(const float *__
     }
     lo = block_min_f(lo, smf);
     hi = block_max_f(hi, smf);
+    if (relu) {   // the rectified output spans the rectified images of the extrema
+        lo = lo > 0.0f ? lo : 0.0f;
+        hi = hi > 0.0f ? hi : 0.0f;
+    }
     if (threadIdx.x == 0) *qp_out = make_qparams(lo, hi, 8);
 }
 
@@ -210,7 +214,7 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_apply(const float *__restrict
                                                          const float *__restrict__ beta, float cn,
                                                          float eps, float *__restrict__ y,
                                                          int8_t *__restrict__ q,
-                                                         const q8t_qparams *__restrict__ qp)
+                                                         const q8t_qparams *__restrict__ qp, int relu)
 {
     Affine a;
     if (QOUT) a = affine_of(*qp);
@@ -245,6 +249,12 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_apply(const float *__restrict
                 r.y = bn_map(v.y, mu, inv, g, b);
                 r.z = bn_map(v.z, mu, inv, g, b);
                 r.w = bn_map(v.w, mu, inv, g, b);
+                if (relu) {
+                    r.x = r.x > 0.0f ? r.x : 0.0f;
+                    r.y = r.y > 0.0f ? r.y : 0.0f;
+                    r.z = r.z > 0.0f ? r.z : 0.0f;
+                    r.w = r.w > 0.0f ? r.w : 0.0f;
+                }
                 if (y) o[i] = r;
                 if (QOUT) {
                     const int q0 = level_of<false>(r.x, a, 0) - 128, q1 = level_of<false>(r.y, a, 0) - 128,
@@ -255,7 +265,8 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_apply(const float *__restrict
             }
         } else {
             for (int i = threadIdx.x; i < HW; i += kThreads) {
-                const float r = bn_map(x[base + i], mu, inv, g, b);
+                float r = bn_map(x[base + i], mu, inv, g, b);
+                if (relu) r = r > 0.0f ? r : 0.0f;
                 if (y) y[base + i] = r;
                 if (QOUT) q[base + i] = (int8_t)(level_of<false>(r, a, 0) - 128);
             }
@@ -272,7 +283,7 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_apply_flat(const float *__res
                                                               const float *__restrict__ beta, float cn,
                                                               float eps, float *__restrict__ y,
                                                               int8_t *__restrict__ q,
-                                                              const q8t_qparams *__restrict__ qp)
+                                                              const q8t_qparams *__restrict__ qp, int relu)
 {
     Affine a;
     if (QOUT) a = affine_of(*qp);
@@ -280,7 +291,8 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_apply_flat(const float *__res
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
         const int c = (int)((i / HW) % C);
         const float inv = bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
-        const float r = bn_map(x[i], stats[c], inv, gamma ? gamma[c] : 1.0f, beta ? beta[c] : 0.0f);
+        float r = bn_map(x[i], stats[c], inv, gamma ? gamma[c] : 1.0f, beta ? beta[c] : 0.0f);
+        if (relu) r = r > 0.0f ? r : 0.0f;
         if (y) y[i] = r;
         if (QOUT) q[i] = (int8_t)(level_of<false>(r, a, 0) - 128);
     }
@@ -292,6 +304,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial(const float *__restri
                                                            const float *__restrict__ dy,
                                                            const float *__restrict__ stats, int N, int C,
                                                            int HW, int NB, float cn, float eps,
+                                                           const float *__restrict__ gamma,
+                                                           const float *__restrict__ beta, int relu,
                                                            double2 *__restrict__ parts)
 {
     __shared__ double smd[kThreads / 64];
@@ -299,6 +313,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial(const float *__restri
     const int b0 = sp * NB, b1 = min(N, b0 + NB);
     const float mu = stats[c];
     const float inv = bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
+    const float ga = gamma ? gamma[c] : 1.0f, be = beta ? beta[c] : 0.0f;
     double s0 = 0.0, s1 = 0.0;
     if (VEC) {
         const int hw4 = HW >> 2;
@@ -308,9 +323,16 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial(const float *__restri
             const float4 *pg = reinterpret_cast<const float4 *>(dy + base);
 #pragma unroll 2
             for (int i = threadIdx.x; i < hw4; i += kThreads) {
-                const float4 v = px[i], g = pg[i];
+                const float4 v = px[i];
+                float4 g = pg[i];
                 const float h0 = (v.x - mu) * inv, h1 = (v.y - mu) * inv, h2 = (v.z - mu) * inv,
                             h3 = (v.w - mu) * inv;
+                if (relu) {   // the gradient passes where the forward output was positive
+                    g.x = bn_map(v.x, mu, inv, ga, be) > 0.0f ? g.x : 0.0f;
+                    g.y = bn_map(v.y, mu, inv, ga, be) > 0.0f ? g.y : 0.0f;
+                    g.z = bn_map(v.z, mu, inv, ga, be) > 0.0f ? g.z : 0.0f;
+                    g.w = bn_map(v.w, mu, inv, ga, be) > 0.0f ? g.w : 0.0f;
+                }
                 s0 += (double)g.x;
                 s0 += (double)g.y;
                 s0 += (double)g.z;
@@ -327,8 +349,9 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial(const float *__restri
             const int b = b0 + idx / HW, i = idx % HW;
             const int64_t j = ((int64_t)b * C + c) * HW + i;
             const float h = (x[j] - mu) * inv;
-            s0 += (double)dy[j];
-            s1 += (double)dy[j] * (double)h;
+            const float d = relu && !(bn_map(x[j], mu, inv, ga, be) > 0.0f) ? 0.0f : dy[j];
+            s0 += (double)d;
+            s1 += (double)d * (double)h;
         }
     }
     s0 = block_sum_d(s0, smd);
@@ -385,7 +408,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply(const float *__restrict
                                                          const double2 *__restrict__ parts, int split, double n,
                                                          float *__restrict__ dgamma, float *__restrict__ dbeta,
                                                          float cn, float eps, float *__restrict__ dx,
-                                                         float2 *__restrict__ mm_out)
+                                                         float2 *__restrict__ mm_out,
+                                                         const float *__restrict__ beta, int relu)
 {
     __shared__ float smf[kThreads / 64];
     float dmn = INFINITY, dmx = -INFINITY;   // range of the dx values this workgroup writes (if asked for)
@@ -394,6 +418,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply(const float *__restrict
         const float mn = stats[C + c], mx = stats[2 * C + c];
         const float inv = bn_inv(mn, mx, cn, eps);
         const float g = gamma ? gamma[c] : 1.0f;
+        const float mu = stats[c], be = beta ? beta[c] : 0.0f;
         float2 k;
         if (parts) {
             const int lane = threadIdx.x & 63;
@@ -422,7 +447,14 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply(const float *__restrict
             const int hw4 = HW >> 2;
 #pragma unroll 2
             for (int i = threadIdx.x; i < hw4; i += kThreads) {
-                const float4 v = px[i], d = pg[i];
+                const float4 v = px[i];
+                float4 d = pg[i];
+                if (relu) {
+                    d.x = bn_map(v.x, mu, inv, g, be) > 0.0f ? d.x : 0.0f;
+                    d.y = bn_map(v.y, mu, inv, g, be) > 0.0f ? d.y : 0.0f;
+                    d.z = bn_map(v.z, mu, inv, g, be) > 0.0f ? d.z : 0.0f;
+                    d.w = bn_map(v.w, mu, inv, g, be) > 0.0f ? d.w : 0.0f;
+                }
                 float4 r;
                 r.x = bn_dx(v.x, d.x, g, k.x, inv, k.y, mn, mx);
                 r.y = bn_dx(v.y, d.y, g, k.x, inv, k.y, mn, mx);
@@ -436,7 +468,9 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply(const float *__restrict
             }
         } else {
             for (int i = threadIdx.x; i < HW; i += kThreads) {
-                const float r = bn_dx(x[base + i], dy[base + i], g, k.x, inv, k.y, mn, mx);
+                const float xv = x[base + i];
+                const float d = relu && !(bn_map(xv, mu, inv, g, be) > 0.0f) ? 0.0f : dy[base + i];
+                const float r = bn_dx(xv, d, g, k.x, inv, k.y, mn, mx);
                 dx[base + i] = r;
                 dmn = fminf(dmn, r);
                 dmx = fmaxf(dmx, r);
@@ -456,14 +490,17 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_flat(const float *__res
                                                               const float *__restrict__ stats,
                                                               const float *__restrict__ gamma,
                                                               const float2 *__restrict__ consts, float cn,
-                                                              float eps, float *__restrict__ dx)
+                                                              float eps, float *__restrict__ dx,
+                                                              const float *__restrict__ beta, int relu)
 {
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
         const int c = (int)((i / HW) % C);
         const float mn = stats[C + c], mx = stats[2 * C + c];
         const float2 k = consts[c];
-        dx[i] = bn_dx(x[i], dy[i], gamma ? gamma[c] : 1.0f, k.x, bn_inv(mn, mx, cn, eps), k.y, mn, mx);
+        const float g = gamma ? gamma[c] : 1.0f, inv = bn_inv(mn, mx, cn, eps);
+        const float d = relu && !(bn_map(x[i], stats[c], inv, g, beta ? beta[c] : 0.0f) > 0.0f) ? 0.0f : dy[i];
+        dx[i] = bn_dx(x[i], d, g, k.x, inv, k.y, mn, mx);
     }
 }
 
@@ -539,7 +576,7 @@ int q8t_range_bn_fwd(const float *x, int N, int C, int H, int W, const float *ga
     if (HW >= 256) {
         const dim3 grid(planes_grid(planes));
 #define Q8T_GO(V, Q) \
-    hipLaunchKernelGGL((bn_fwd_apply<V, Q>), grid, dim3(kThreads), 0, st, x, planes, C, HW, stats_out, fparts, nsplit, n, gamma, beta, cn, eps, y, q_out, qp_out)
+    hipLaunchKernelGGL((bn_fwd_apply<V, Q>), grid, dim3(kThreads), 0, st, x, planes, C, HW, stats_out, fparts, nsplit, n, gamma, beta, cn, eps, y, q_out, qp_out, 0)
         if (vec) { if (q_out) Q8T_GO(true, true); else Q8T_GO(true, false); }
         else     { if (q_out) Q8T_GO(false, true); else Q8T_GO(false, false); }
 #undef Q8T_GO
@@ -547,9 +584,9 @@ int q8t_range_bn_fwd(const float *x, int N, int C, int H, int W, const float *ga
         const int64_t total = planes * HW;
         const dim3 grid((unsigned)((total + kThreads - 1) / kThreads < 65536 * 16 ? (total + kThreads - 1) / kThreads : 65536 * 16));
         if (q_out)
-            hipLaunchKernelGGL(bn_fwd_apply_flat<true>, grid, dim3(kThreads), 0, st, x, total, C, HW, stats_out, gamma, beta, cn, eps, y, q_out, qp_out);
+            hipLaunchKernelGGL(bn_fwd_apply_flat<true>, grid, dim3(kThreads), 0, st, x, total, C, HW, stats_out, gamma, beta, cn, eps, y, q_out, qp_out, 0);
         else
-            hipLaunchKernelGGL(bn_fwd_apply_flat<false>, grid, dim3(kThreads), 0, st, x, total, C, HW, stats_out, gamma, beta, cn, eps, y, q_out, qp_out);
+            hipLaunchKernelGGL(bn_fwd_apply_flat<false>, grid, dim3(kThreads), 0, st, x, total, C, HW, stats_out, gamma, beta, cn, eps, y, q_out, qp_out, 0);
     }
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
@@ -557,8 +594,9 @@ int q8t_range_bn_fwd(const float *x, int N, int C, int H, int W, const float *ga
 
 // Forward with statistics that something else already produced (the convolution epilogue):
 // normalization (and 8-bit output) only, one pass over x.
-int q8t_range_bn_fwd_apply(const float *x, int N, int C, int H, int W, const float *gamma, const float *beta, float eps,
-                           const float *stats, float *y, int8_t *q_out, q8t_qparams *qp_out, void *stream)
+static int range_bn_fwd_apply_impl(const float *x, int N, int C, int H, int W, const float *gamma, const float *beta,
+                                   float eps, const float *stats, float *y, int8_t *q_out, q8t_qparams *qp_out,
+                                   void *stream, int relu)
 {
     const int rc = check_shape(N, C, H, W);
     if (rc) return rc;
@@ -570,7 +608,7 @@ int q8t_range_bn_fwd_apply(const float *x, int N, int C, int H, int W, const flo
     const bool vec = (HW % 4 == 0) && q8t_aligned(x, 16) && (!y || q8t_aligned(y, 16)) &&
                      (!q_out || q8t_aligned(q_out, 4));
     if (q_out) {
-        hipLaunchKernelGGL(bn_qrange_from_stats, dim3(1), dim3(kThreads), 0, st, stats, C, cn, eps, gamma, beta, qp_out);
+        hipLaunchKernelGGL(bn_qrange_from_stats, dim3(1), dim3(kThreads), 0, st, stats, C, cn, eps, gamma, beta, relu, qp_out);
         Q8T_LAUNCH_CHECK();
     }
     float *stats_rw = const_cast<float *>(stats);   // only read when no partial sums are passed
@@ -579,7 +617,7 @@ int q8t_range_bn_fwd_apply(const float *x, int N, int C, int H, int W, const flo
     if (HW >= 256) {
         const dim3 grid(planes_grid(planes));
 #define Q8T_GO(V, Q) \
-    hipLaunchKernelGGL((bn_fwd_apply<V, Q>), grid, dim3(kThreads), 0, st, x, planes, C, HW, stats_rw, fparts, 1, n, gamma, beta, cn, eps, y, q_out, qp_out)
+    hipLaunchKernelGGL((bn_fwd_apply<V, Q>), grid, dim3(kThreads), 0, st, x, planes, C, HW, stats_rw, fparts, 1, n, gamma, beta, cn, eps, y, q_out, qp_out, relu)
         if (vec) { if (q_out) Q8T_GO(true, true); else Q8T_GO(true, false); }
         else     { if (q_out) Q8T_GO(false, true); else Q8T_GO(false, false); }
 #undef Q8T_GO
@@ -587,17 +625,30 @@ int q8t_range_bn_fwd_apply(const float *x, int N, int C, int H, int W, const flo
         const int64_t total = planes * HW;
         const dim3 grid((unsigned)((total + kThreads - 1) / kThreads < 65536 * 16 ? (total + kThreads - 1) / kThreads : 65536 * 16));
         if (q_out)
-            hipLaunchKernelGGL(bn_fwd_apply_flat<true>, grid, dim3(kThreads), 0, st, x, total, C, HW, stats_rw, gamma, beta, cn, eps, y, q_out, qp_out);
+            hipLaunchKernelGGL(bn_fwd_apply_flat<true>, grid, dim3(kThreads), 0, st, x, total, C, HW, stats_rw, gamma, beta, cn, eps, y, q_out, qp_out, relu);
         else
-            hipLaunchKernelGGL(bn_fwd_apply_flat<false>, grid, dim3(kThreads), 0, st, x, total, C, HW, stats_rw, gamma, beta, cn, eps, y, q_out, qp_out);
+            hipLaunchKernelGGL(bn_fwd_apply_flat<false>, grid, dim3(kThreads), 0, st, x, total, C, HW, stats_rw, gamma, beta, cn, eps, y, q_out, qp_out, relu);
     }
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
 }
 
+int q8t_range_bn_fwd_apply(const float *x, int N, int C, int H, int W, const float *gamma, const float *beta, float eps,
+                           const float *stats, float *y, int8_t *q_out, q8t_qparams *qp_out, void *stream)
+{
+    return range_bn_fwd_apply_impl(x, N, C, H, W, gamma, beta, eps, stats, y, q_out, qp_out, stream, 0);
+}
+
+int q8t_range_bn_relu_fwd_apply(const float *x, int N, int C, int H, int W, const float *gamma, const float *beta,
+                                float eps, const float *stats, float *y, int8_t *q_out, q8t_qparams *qp_out,
+                                void *stream)
+{
+    return range_bn_fwd_apply_impl(x, N, C, H, W, gamma, beta, eps, stats, y, q_out, qp_out, stream, 1);
+}
+
 static int range_bn_bwd_impl(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
                              const float *gamma, float eps, float *dx, float *dgamma, float *dbeta, void *ws,
-                             void *stream, float2 *mm_out, int *mm_count)
+                             void *stream, float2 *mm_out, int *mm_count, const float *beta = nullptr, int relu = 0)
 {
     const int rc = check_shape(N, C, H, W);
     if (rc) return rc;
@@ -613,9 +664,9 @@ static int range_bn_bwd_impl(const float *x, const float *dy, const float *stats
     const int nsplit = (N + NB - 1) / NB;
     const bool vec = (HW % 4 == 0) && q8t_aligned(x, 16) && q8t_aligned(dy, 16) && (!dx || q8t_aligned(dx, 16));
     if (vec)
-        hipLaunchKernelGGL(bn_bwd_partial<true>, dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn, eps, parts);
+        hipLaunchKernelGGL(bn_bwd_partial<true>, dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn, eps, gamma, beta, relu, parts);
     else
-        hipLaunchKernelGGL(bn_bwd_partial<false>, dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn, eps, parts);
+        hipLaunchKernelGGL(bn_bwd_partial<false>, dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn, eps, gamma, beta, relu, parts);
     Q8T_LAUNCH_CHECK();
     const bool fused = dx && HW >= 256;
     if (mm_out && !fused) return Q8T_ERR_SHAPE;   // the fused range output exists for the plane kernel only
@@ -631,13 +682,13 @@ static int range_bn_bwd_impl(const float *x, const float *dy, const float *stats
         const dim3 grid(mm_out ? (unsigned)(planes < 2048 ? planes : 2048) : (unsigned)planes_grid(planes));
         if (mm_count) *mm_count = (int)grid.x;
         if (vec)
-            hipLaunchKernelGGL(bn_bwd_apply<true>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx, mm_out);
+            hipLaunchKernelGGL(bn_bwd_apply<true>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx, mm_out, beta, relu);
         else
-            hipLaunchKernelGGL(bn_bwd_apply<false>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx, mm_out);
+            hipLaunchKernelGGL(bn_bwd_apply<false>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx, mm_out, beta, relu);
     } else {
         const int64_t total = planes * HW;
         const dim3 grid((unsigned)((total + kThreads - 1) / kThreads < 65536 * 16 ? (total + kThreads - 1) / kThreads : 65536 * 16));
-        hipLaunchKernelGGL(bn_bwd_apply_flat, grid, dim3(kThreads), 0, st, x, dy, total, C, HW, stats, gamma, consts, cn, eps, dx);
+        hipLaunchKernelGGL(bn_bwd_apply_flat, grid, dim3(kThreads), 0, st, x, dy, total, C, HW, stats, gamma, consts, cn, eps, dx, beta, relu);
     }
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
@@ -655,10 +706,11 @@ size_t q8t_range_bn_bwd_bifurcate_workspace_size(int N, int C, int H, int W)
     return q8t_range_bn_workspace_size(N, C, H, W) + 256 + 2048 * sizeof(float2);
 }
 
-int q8t_range_bn_bwd_bifurcate(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
-                               const float *gamma, float eps, float *dx, float *dgamma, float *dbeta,
-                               uint64_t seed8, uint64_t seed16, int8_t *q8_out, q8t_qparams *qp8_out,
-                               int16_t *q16_out, q8t_qparams *qp16_out, void *ws, void *stream)
+static int range_bn_bwd_bifurcate_impl(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
+                                       const float *gamma, const float *beta, int relu, float eps, float *dx,
+                                       float *dgamma, float *dbeta, uint64_t seed8, uint64_t seed16, int8_t *q8_out,
+                                       q8t_qparams *qp8_out, int16_t *q16_out, q8t_qparams *qp16_out, void *ws,
+                                       void *stream)
 {
     if (!dx || !q8_out || !qp8_out || !q16_out || !qp16_out) return Q8T_ERR_NULL;
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
@@ -666,16 +718,36 @@ int q8t_range_bn_bwd_bifurcate(const float *x, const float *dy, const float *sta
     float2 *mm = (float2 *)((char *)ws + off);
     if ((int64_t)H * W < 256) {
         // planes this small take the flat backward kernel, which keeps no ranges: plain sequence
-        const int rc = range_bn_bwd_impl(x, dy, stats, N, C, H, W, gamma, eps, dx, dgamma, dbeta, ws, stream, nullptr, nullptr);
+        const int rc = range_bn_bwd_impl(x, dy, stats, N, C, H, W, gamma, eps, dx, dgamma, dbeta, ws, stream, nullptr, nullptr,
+                                         beta, relu);
         if (rc) return rc;
         return q8t_quantize_bifurcate(dx, (int64_t)N * C * H * W, seed8, seed16, q8_out, qp8_out, q16_out, qp16_out, mm,
                                       stream);
     }
     int np = 0;
-    const int rc = range_bn_bwd_impl(x, dy, stats, N, C, H, W, gamma, eps, dx, dgamma, dbeta, ws, stream, mm, &np);
+    const int rc = range_bn_bwd_impl(x, dy, stats, N, C, H, W, gamma, eps, dx, dgamma, dbeta, ws, stream, mm, &np, beta, relu);
     if (rc) return rc;
     return q8t_bifurcate_from_partials(dx, (int64_t)N * C * H * W, mm, np, seed8, seed16, q8_out, qp8_out, q16_out,
                                        qp16_out, (hipStream_t)stream);
+}
+
+int q8t_range_bn_bwd_bifurcate(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
+                               const float *gamma, float eps, float *dx, float *dgamma, float *dbeta,
+                               uint64_t seed8, uint64_t seed16, int8_t *q8_out, q8t_qparams *qp8_out,
+                               int16_t *q16_out, q8t_qparams *qp16_out, void *ws, void *stream)
+{
+    return range_bn_bwd_bifurcate_impl(x, dy, stats, N, C, H, W, gamma, nullptr, 0, eps, dx, dgamma, dbeta, seed8, seed16,
+                                       q8_out, qp8_out, q16_out, qp16_out, ws, stream);
+}
+
+int q8t_range_bn_relu_bwd_bifurcate(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
+                                    const float *gamma, const float *beta, float eps, float *dx, float *dgamma,
+                                    float *dbeta, uint64_t seed8, uint64_t seed16, int8_t *q8_out,
+                                    q8t_qparams *qp8_out, int16_t *q16_out, q8t_qparams *qp16_out, void *ws,
+                                    void *stream)
+{
+    return range_bn_bwd_bifurcate_impl(x, dy, stats, N, C, H, W, gamma, beta, 1, eps, dx, dgamma, dbeta, seed8, seed16,
+                                       q8_out, qp8_out, q16_out, qp16_out, ws, stream);
 }
 
 }  // extern "C"

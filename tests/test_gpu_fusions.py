@@ -80,3 +80,62 @@ def test_range_bn_forward_from_given_statistics(shape):
     same_ints(host(y), oy)
     same_qparams(q8t, qp, oqp)
     same_ints(host(q), oq)
+
+
+RELU_SHAPES = [(6, 7, 16, 16), (3, 2, 40, 36), (4, 5, 3, 3), (64, 128, 1, 1), (5, 9, 7, 7), (8, 5, 6, 7)]
+
+
+@pytest.mark.parametrize("shape", RELU_SHAPES)
+@pytest.mark.parametrize("affine", [False, True])
+def test_range_bn_relu_forward(shape, affine):
+    # normalization + ReLU + 8-bit output in one pass: everything elementwise, so bit for bit
+    q8t = require_gpu()
+    x, _ = synth.range_bn_input(sum(shape), *shape)
+    g = synth.rng(8)
+    gamma = g.uniform(-1.5, 1.5, size=shape[1]).astype(np.float32) if affine else None
+    beta = g.uniform(-0.5, 0.5, size=shape[1]).astype(np.float32) if affine else None
+    stats = oracle.range_bn_stats(x)
+    gd = None if gamma is None else dev(gamma)
+    bd = None if beta is None else dev(beta)
+    y, q, qp = q8t.range_bn_relu_fwd_apply(dev(x), dev(stats), gd, bd, 1e-5, quantized=True)
+    oy, oq, oqp = oracle.range_bn_relu_fwd(x, stats, gamma, beta, 1e-5, quantized=True)
+    same_ints(host(y), oy)
+    same_qparams(q8t, qp, oqp)
+    same_ints(host(q), oq)
+    # codes alone (no fp32 output): the form the next layer consumes
+    _, q2, qp2 = q8t.range_bn_relu_fwd_apply(dev(x), dev(stats), gd, bd, 1e-5, quantized=True, want_y=False)
+    same_ints(host(q2), oq)
+    same_qparams(q8t, qp2, oqp)
+
+
+@pytest.mark.parametrize("shape", RELU_SHAPES + [(16, 64, 56, 56)])
+def test_range_bn_relu_backward_with_bifurcated_quantization(shape):
+    q8t = require_gpu()
+    x, dy = synth.range_bn_input(3 + sum(shape), *shape)
+    g = synth.rng(9)
+    gamma = g.uniform(-1.5, 1.5, size=shape[1]).astype(np.float32)
+    beta = g.uniform(-0.5, 0.5, size=shape[1]).astype(np.float32)
+    eps = 1e-5
+    stats = oracle.range_bn_stats(x)
+    dx, dgamma, dbeta, q8, qp8, q16, qp16 = q8t.range_bn_relu_bwd_bifurcate(dev(x), dev(dy), dev(stats), dev(gamma),
+                                                                            dev(beta), eps, seed8=51, seed16=52)
+    odx, odg, odb = oracle.range_bn_relu_bwd(x, dy, stats, gamma, beta, eps)
+    close(host(dgamma), odg)
+    close(host(dbeta), odb)
+    dxh = host(dx)
+    close(dxh, odx)
+    # the same as masking first and calling the plain fused backward (bit for bit)
+    masked = oracle.range_bn_relu_mask(x, dy, stats, gamma, beta, eps)
+    dx2, dg2, db2, r8, rp8, r16, rp16 = q8t.range_bn_bwd_bifurcate(dev(x), dev(masked), dev(stats), dev(gamma), eps,
+                                                                   seed8=51, seed16=52)
+    assert np.array_equal(dxh, host(dx2))
+    assert np.array_equal(host(dgamma), host(dg2)) and np.array_equal(host(dbeta), host(db2))
+    same_ints(host(q8), host(r8))
+    same_ints(host(q16), host(r16))
+    # codes against the oracle's quantizer on the GPU's own dx
+    s8, _, o8 = oracle.quantize(dxh, 8, True, seed=51)
+    s16, _, o16 = oracle.quantize(dxh, 16, True, seed=52)
+    same_qparams(q8t, qp8, o8)
+    same_qparams(q8t, qp16, o16)
+    same_ints(host(q8), s8)
+    same_ints(host(q16), s16)
