@@ -13,7 +13,9 @@ He-normal weights everywhere.
 
 ReLU, max/avg pooling, the residual additions and the softmax cross-entropy are elementwise glue
 outside the method; they are left to torch (autograd supplies their gradients).  The optimizer
-update is not part of the measured step.  Prints the step time and, with --breakdown, per entry
+update is not part of the measured step.  Where a Range BN feeds a ReLU and then only the next
+convolution, the three passes (normalize, rectify, quantize) run as one that emits the 8-bit
+codes (--no-fuse keeps them apart).  Prints the step time and, with --breakdown, per entry
 point: time, share, integer throughput of the products (2 x multiply-accumulates of the layer, the
 weight gradient counted once although it executes two byte-plane products) and algorithmic bytes
 per second of the streaming calls.  Needs a GPU.
@@ -28,6 +30,7 @@ import torch.nn.functional as F
 from . import binding as q8t
 
 _breakdown = False
+_fuse = True
 
 
 def _call(name, ops, nbytes, fn, *a, **k):
@@ -85,6 +88,58 @@ class ConvBN(torch.autograd.Function):
         return dx, dw, None, None, None
 
 
+class ConvChain(torch.autograd.Function):
+    """conv -> Range BN -> ReLU -> conv -> Range BN [-> ReLU -> conv -> Range BN]: between two
+    convolutions the normalization, the ReLU and the 8-bit quantization of the next operand are one
+    pass that writes codes only (no fp32 activation, no separate quantization); in the backward
+    pass the ReLU mask is recomputed inside the Range BN backward."""
+
+    @staticmethod
+    def forward(ctx, a, need_dx, specs, *ws):
+        a = a.contiguous()
+        qa, pa = _quantize("quantize (activations)", a)
+        saved = []
+        shape = a.shape
+        for i, (w, (stride, pad)) in enumerate(zip(ws, specs)):
+            n, c, h, wd = shape
+            k, _, r, s = w.shape
+            d = q8t.conv_desc(n, c, h, wd, k, r, s, stride, pad)
+            qw, pw = _quantize("quantize (weights)", w)
+            ops = 2.0 * n * d.P * d.Q * k * c * r * s
+            nx, ny = n * c * h * wd, n * k * d.P * d.Q
+            y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw)
+            saved.append((d, qa, pa, qw, pw, y, stats, ops, nx, ny))
+            if i + 1 < len(ws):
+                _, qa, pa = _call("range_bn_relu_fwd_apply (int8 out)", 0, 5 * ny, q8t.range_bn_relu_fwd_apply, y, stats,
+                                  None, None, 1e-5, True, False)
+            else:
+                out, _, _ = _call("range_bn_fwd_apply", 0, 8 * ny, q8t.range_bn_fwd_apply, y, stats, None, None, 1e-5)
+            shape = (n, k, d.P, d.Q)
+        ctx.saved = (saved, need_dx)
+        return out
+
+    @staticmethod
+    def backward(ctx, g):
+        saved, need_dx = ctx.saved
+        g = g.contiguous()
+        dws = [None] * len(saved)
+        for i in range(len(saved) - 1, -1, -1):
+            d, qa, pa, qw, pw, y, stats, ops, nx, ny = saved[i]
+            _seed[0] += 2
+            if i + 1 == len(saved):
+                r = _call("range_bn_bwd_bifurcate", 0, 27 * ny, q8t.range_bn_bwd_bifurcate, y, g, stats, None, 1e-5,
+                          _seed[0], _seed[0] + 1)
+            else:
+                r = _call("range_bn_relu_bwd_bifurcate", 0, 27 * ny, q8t.range_bn_relu_bwd_bifurcate, y, g, stats, None,
+                          None, 1e-5, _seed[0], _seed[0] + 1)
+            g8, pg8, g16, pg16 = r[3:]
+            g = None
+            if i > 0 or need_dx:
+                g, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw)
+            dws[i], _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16)
+        return (g, None, None, *dws)
+
+
 class Linear(torch.autograd.Function):
     @staticmethod
     def forward(ctx, a, w):
@@ -133,8 +188,11 @@ def step(x, labels, ws):
     a = F.relu(ConvBN.apply(x, ws["conv1"], 2, 3, False))     # the network input needs no gradient
     a = F.max_pool2d(a, 3, 2, 1)
     for (cin, cout, stride), b in zip(STAGES, ws["blocks"]):
-        h = F.relu(ConvBN.apply(a, b["c1"], stride, 1, True))
-        h = ConvBN.apply(h, b["c2"], 1, 1, True)
+        if _fuse:
+            h = ConvChain.apply(a, True, ((stride, 1), (1, 1)), b["c1"], b["c2"])
+        else:
+            h = F.relu(ConvBN.apply(a, b["c1"], stride, 1, True))
+            h = ConvBN.apply(h, b["c2"], 1, 1, True)
         sc = ConvBN.apply(a, b["sc"], stride, 0, True) if "sc" in b else a
         a = F.relu(h + sc)
     a = F.adaptive_avg_pool2d(a, 1).flatten(1)
@@ -144,23 +202,29 @@ def step(x, labels, ws):
 
 
 def bottleneck_step(x, gy, ws):
-    h = F.relu(ConvBN.apply(x, ws[0], 1, 0, True))
-    h = F.relu(ConvBN.apply(h, ws[1], 1, 1, True))
-    h = ConvBN.apply(h, ws[2], 1, 0, True)
+    if _fuse:
+        h = ConvChain.apply(x, True, ((1, 0), (1, 1), (1, 0)), *ws)
+    else:
+        h = F.relu(ConvBN.apply(x, ws[0], 1, 0, True))
+        h = F.relu(ConvBN.apply(h, ws[1], 1, 1, True))
+        h = ConvBN.apply(h, ws[2], 1, 0, True)
     out = F.relu(h + x)
     out.backward(gy)
     return out
 
 
 def main():
-    global _breakdown
+    global _breakdown, _fuse
     ap = argparse.ArgumentParser()
     ap.add_argument("--net", choices=["resnet18", "bottleneck"], default="resnet18")
     ap.add_argument("--batch", type=int, default=0, help="default 256 (resnet18) / 128 (bottleneck)")
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--breakdown", action="store_true")
+    ap.add_argument("--no-fuse", action="store_true",
+                    help="Range BN, ReLU and the next layer's quantization as separate passes")
     args = ap.parse_args()
+    _fuse = not args.no_fuse
     dev = torch.device("cuda:0")
     gen = torch.Generator(device=dev)
     gen.manual_seed(0)
@@ -196,7 +260,8 @@ def main():
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) / args.steps * 1e3
     assert bool(torch.isfinite(loss)) and all(p.grad is not None and bool(torch.isfinite(p.grad).all()) for p in params)
-    print("%s training step, batch %d: %.2f ms / step (%.0f images/s)" % (args.net, args.batch, ms, args.batch / ms * 1e3))
+    print("%s training step, batch %d%s: %.2f ms / step (%.0f images/s)" % (
+        args.net, args.batch, "" if _fuse else " (unfused)", ms, args.batch / ms * 1e3))
     if args.breakdown:
         _breakdown = True
         one()
@@ -210,9 +275,9 @@ def main():
             a[3] += 1
         lib = sum(a[0] for a in acc.values())
         print("library calls: %.2f ms of the step (each call timed with events, launch gaps included)" % lib)
-        print("  %-26s %6s %9s %9s %10s" % ("entry point", "calls", "ms", "TOP/s", "GB/s (alg.)"))
+        print("  %-34s %6s %9s %9s %10s" % ("entry point", "calls", "ms", "TOP/s", "GB/s (alg.)"))
         for name, (t, ops, nbytes, cnt) in sorted(acc.items(), key=lambda kv: -kv[1][0]):
-            print("  %-26s %6d %9.3f %9s %10.0f" % (name, cnt, t, "%.0f" % (ops / t / 1e9) if ops else "-", nbytes / t / 1e6))
+            print("  %-34s %6d %9.3f %9s %10.0f" % (name, cnt, t, "%.0f" % (ops / t / 1e9) if ops else "-", nbytes / t / 1e6))
 
 
 if __name__ == "__main__":
