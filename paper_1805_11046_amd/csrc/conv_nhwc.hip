@@ -633,6 +633,72 @@ __global__ __launch_bounds__(C::THREADS, 2) void igemm_nhwc_pair(const int8_t *_
     }
 }
 
+// Stage the R input rows under output row p of image n, for every channel, into LDS:
+// rows[(c*R + r)*pitch + L + w] = x[n][c][p*stride + r - pad][w], the zero code everywhere else
+// (padding rows and columns).  L = pad rounded up to a multiple of 4 and pitch a multiple of 4, so
+// that aligned dwords of the input are aligned dwords of a staged row.  All loads of a pass are
+// issued before the first LDS store: a workgroup's input is a few KB and the pass would otherwise
+// be a chain of exposed memory latencies.
+__device__ __forceinline__ void stage_rows(const int8_t *__restrict__ x, int n, int C, int H, int W, int R, int stride,
+                                           int pad, int p, int L, int pitch, int za, bool vec4, int8_t *rows)
+{
+    constexpr int U = 6;
+    const int CR = C * R, tid = threadIdx.x;
+    {
+        uint32_t *r32 = reinterpret_cast<uint32_t *>(rows);
+        const uint32_t fill = (uint32_t)(za & 255) * 0x01010101u;
+        for (int i = tid; i < (CR * pitch) >> 2; i += kThreads) r32[i] = fill;
+    }
+    __syncthreads();
+    if (vec4) {
+        const int W4 = W >> 2, items = CR * W4;
+        for (int i0 = 0; i0 < items; i0 += kThreads * U) {
+            uint32_t v[U];
+            int dst[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * kThreads + tid;
+                dst[u] = -1;
+                v[u] = 0;
+                if (i < items) {
+                    const int cr = i / W4, w4 = i - cr * W4, c = cr / R, r = cr - c * R;
+                    const int h = p * stride + r - pad;
+                    if ((unsigned)h < (unsigned)H) {
+                        v[u] = *reinterpret_cast<const uint32_t *>(x + (((size_t)n * C + c) * H + h) * W + w4 * 4);
+                        dst[u] = cr * pitch + L + w4 * 4;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (dst[u] >= 0) *reinterpret_cast<uint32_t *>(rows + dst[u]) = v[u];
+        }
+    } else {
+        const int items = CR * W;
+        for (int i0 = 0; i0 < items; i0 += kThreads * U) {
+            int8_t v[U];
+            int dst[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * kThreads + tid;
+                dst[u] = -1;
+                v[u] = 0;
+                if (i < items) {
+                    const int cr = i / W, w = i - cr * W, c = cr / R, r = cr - c * R;
+                    const int h = p * stride + r - pad;
+                    if ((unsigned)h < (unsigned)H) {
+                        v[u] = x[(((size_t)n * C + c) * H + h) * W + w];
+                        dst[u] = cr * pitch + L + w;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (dst[u] >= 0) rows[dst[u]] = v[u];
+        }
+    }
+}
+
 // ---- forward with few input channels (the network's first layer) --------------------------------
 // The reduction (c, r, s) of an output position is laid out explicitly: xn[m][Kc] with
 // Kc = C*R*S rounded up to a multiple of 64, entry c*R*S + r*S + s = the input code under that tap
@@ -642,32 +708,23 @@ __global__ __launch_bounds__(C::THREADS, 2) void igemm_nhwc_pair(const int8_t *_
 __global__ __launch_bounds__(kThreads) void im2col_positions(const int8_t *__restrict__ x, int C, int H, int W, int R, int S,
                                                              int stride, int pad, int P, int Q, int Kc,
                                                              const q8t_qparams *__restrict__ qpx,
-                                                             int8_t *__restrict__ xn, int *__restrict__ rowsum)
+                                                             int8_t *__restrict__ xn, int *__restrict__ rowsum, int vec4)
 {
     extern __shared__ __align__(16) int8_t lds[];
-    const int Wp = W + 2 * pad, CRS = C * R * S;
+    const int CRS = C * R * S;
+    const int L = (pad + 3) & ~3, Wp = (L + W + pad + 3) & ~3;   // staged row: left margin, pitch
     int8_t *rows = lds;                                   // [C*R][Wp]
     int *lut = reinterpret_cast<int *>(lds + ((C * R * Wp + 15) & ~15));   // [Kc]: offset of column j in `rows`, -1: surplus
     int *rsum = lut + Kc;                                                   // [Q]
     const int n = blockIdx.y, p = blockIdx.x, tid = threadIdx.x;
     const int zsx = qpx->zero_point - (1 << (qpx->bits - 1));
-    // wavefront w fills the staged rows w, w+4, ...: (channel, filter row) decoded once per row
-    for (int cr = tid >> 6; cr < C * R; cr += kThreads / 64) {
-        const int c = cr / R, r = cr - c * R;
-        const int h = p * stride + r - pad;
-        const bool hok = (unsigned)h < (unsigned)H;
-        const int8_t *src = x + (((size_t)n * C + c) * H + (hok ? h : 0)) * W;
-        for (int wp = tid & 63; wp < Wp; wp += 64) {
-            const int w = wp - pad;
-            rows[cr * Wp + wp] = (hok && (unsigned)w < (unsigned)W) ? src[w] : (int8_t)zsx;
-        }
-    }
+    stage_rows(x, n, C, H, W, R, stride, pad, p, L, Wp, zsx, vec4 != 0, rows);
     for (int q = tid; q < Q; q += kThreads) rsum[q] = 0;
     for (int j = tid; j < Kc; j += kThreads) {
         int off = -1;
         if (j < CRS) {
             const int c = j / (R * S), t = j - c * R * S, r = t / S, s2 = t - r * S;
-            off = (c * R + r) * Wp + s2;
+            off = (c * R + r) * Wp + L - pad + s2;
         }
         lut[j] = off;
     }
@@ -696,6 +753,178 @@ __global__ __launch_bounds__(kThreads) void im2col_positions(const int8_t *__res
     }
     __syncthreads();
     for (int q = tid; q < Q; q += kThreads) rowsum[m0 + q] = rsum[q];
+}
+
+// The same forward in one kernel, for reductions of at most 256 columns: the rows of xn never leave
+// the compute unit.  One workgroup per (image, output row): the R input rows of every channel are
+// staged as above, the (position x Kc) operand tile is built in LDS in the fragment layout of
+// gemm_core.h, the [64][Kc] filter block sits beside it, and the four wavefronts multiply 16-row
+// tiles of positions against the 64 output channels.  HBM sees the int8 input once and the fp32
+// result once, instead of xn written and read back (Kc bytes per output position each way).
+// Column order of the fused form: the S taps of one (channel, filter row) are S consecutive bytes of
+// a staged row; they become a group of GP = 4 or 8 columns (the surplus ones hold the zero code and
+// meet zero filter entries), so that a 16-byte chunk of an operand row is 16 / GP unaligned LDS
+// reads of GP bytes instead of 16 single bytes.
+constexpr int FUSED_MAXQ = 128;   // positions per pass
+template <int GP>
+__global__ __launch_bounds__(kThreads) void smallc_fused(const int8_t *__restrict__ x, int C, int H, int W, int R, int S,
+                                                         int stride, int pad, int P, int Q, int Kc, int K,
+                                                         const int8_t *__restrict__ wt, const int *__restrict__ colsum,
+                                                         const q8t_qparams *__restrict__ qpx,
+                                                         const q8t_qparams *__restrict__ qpw, float *__restrict__ out_f,
+                                                         int32_t *__restrict__ out_acc, int vec, int vec4)
+{
+    extern __shared__ __align__(16) int8_t lds[];
+    const int KS = Kc >> 6;
+    const int L = (pad + 3) & ~3, Wp = (L + W + pad + 3) & ~3;   // staged row: left margin, pitch
+    int8_t *sA = lds;                                   // [KS][128][64]
+    int8_t *sB = sA + KS * FUSED_MAXQ * 64;             // [KS][64][64]
+    int *rsum = reinterpret_cast<int *>(sB + KS * 64 * 64);   // [128]
+    int8_t *rows = reinterpret_cast<int8_t *>(rsum + FUSED_MAXQ);   // [C*R][Wp] + 16 bytes of slack
+    const int n = blockIdx.y, p = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, kb = lane >> 4;
+    const int za = qpx->zero_point - (1 << (qpx->bits - 1)), zb = qpw->zero_point - (1 << (qpw->bits - 1));
+    const float sc = qpx->scale * qpw->scale;
+    stage_rows(x, n, C, H, W, R, stride, pad, p, L, Wp, za, vec4 != 0, rows);
+    const int CR = C * R;
+    const int chunks = Kc >> 4;
+    const uint32_t zbyte = (uint32_t)(za & 255);
+    const uint32_t kzz = (uint32_t)Kc * (uint32_t)za * (uint32_t)zb;
+    for (int k0 = 0; k0 < K; k0 += 64) {
+        for (int q0 = 0; q0 < Q; q0 += FUSED_MAXQ) {
+            const int qc = min(FUSED_MAXQ, Q - q0);
+            __syncthreads();   // staged rows and table ready; the previous pass has left sA / sB / rsum
+            if (tid < FUSED_MAXQ) rsum[tid] = 0;
+            // filter block: 64 output channels x Kc, 16-byte chunks, fragment layout
+            for (int it = tid; it < 64 * chunks; it += kThreads) {
+                const int row = it / chunks, ch = it - row * chunks;
+                const uint4 v = *reinterpret_cast<const uint4 *>(wt + (size_t)(k0 + row) * Kc + ch * 16);
+                *reinterpret_cast<uint4 *>(sB + (ch >> 2) * (64 * 64) + row * 64 + (((ch & 3) ^ q8t_gemm::swz(row)) * 16)) = v;
+            }
+            __syncthreads();   // rsum cleared before the sums below
+            // operand tile: rows = positions q0 .. q0 + qc (the rest of the last 16-row tile holds the zero code)
+            const int qpad = (qc + 15) & ~15;
+            for (int it = tid; it < qpad * chunks; it += kThreads) {
+                const int q = it / chunks, ch = it - q * chunks;
+                uint32_t w4[4] = {zbyte * 0x01010101u, zbyte * 0x01010101u, zbyte * 0x01010101u, zbyte * 0x01010101u};
+                if (q < qc) {
+                    const int base = (q0 + q) * stride + L - pad;
+                    if (GP == 8) {
+                        const uint64_t keep = S >= 8 ? ~0ull : ((1ull << (8 * S)) - 1);
+                        const uint64_t fill = (uint64_t)zbyte * 0x0101010101010101ull;
+#pragma unroll
+                        for (int t = 0; t < 2; ++t) {
+                            const int g = ch * 2 + t;
+                            uint64_t v = fill;
+                            if (g < CR) {
+                                __builtin_memcpy(&v, rows + g * Wp + base, 8);
+                                v = (v & keep) | (fill & ~keep);
+                            }
+                            w4[2 * t] = (uint32_t)v;
+                            w4[2 * t + 1] = (uint32_t)(v >> 32);
+                        }
+                    } else {
+                        const uint32_t keep = S >= 4 ? ~0u : ((1u << (8 * S)) - 1);
+                        const uint32_t fill = zbyte * 0x01010101u;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const int g = ch * 4 + t;
+                            uint32_t v = fill;
+                            if (g < CR) {
+                                __builtin_memcpy(&v, rows + g * Wp + base, 4);
+                                v = (v & keep) | (fill & ~keep);
+                            }
+                            w4[t] = v;
+                        }
+                    }
+                    atomicAdd(&rsum[q], bytesum4(w4[0]) + bytesum4(w4[1]) + bytesum4(w4[2]) + bytesum4(w4[3]));
+                }
+                *reinterpret_cast<uint4 *>(sA + (ch >> 2) * (FUSED_MAXQ * 64) + q * 64 + (((ch & 3) ^ q8t_gemm::swz(q)) * 16)) =
+                    make_uint4(w4[0], w4[1], w4[2], w4[3]);
+            }
+            __syncthreads();
+            // wavefront w: 16-row tiles w and w + 4, all four 16-channel tiles
+            v4i acc[2][4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = (v4i){0, 0, 0, 0};
+            const int mtiles = qpad >> 4;
+            for (int ks = 0; ks < KS; ++ks) {
+                v4i bf[4];
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) {
+                    const int row = nt * 16 + l16;
+                    bf[nt] = *reinterpret_cast<const v4i *>(sB + ks * (64 * 64) + row * 64 + ((kb ^ q8t_gemm::swz(row)) * 16));
+                }
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int mt = wave + i * 4;
+                    if (mt < mtiles) {   // uniform per wavefront
+                        const int row = mt * 16 + l16;
+                        const v4i af = *reinterpret_cast<const v4i *>(sA + ks * (FUSED_MAXQ * 64) + row * 64 +
+                                                                      ((kb ^ q8t_gemm::swz(row)) * 16));
+#pragma unroll
+                        for (int nt = 0; nt < 4; ++nt)
+                            acc[i][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af, bf[nt], acc[i][nt], 0, 0, 0);
+                    }
+                }
+            }
+            // epilogue: a lane holds 4 consecutive positions of one output channel
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int mt = wave + i * 4;
+                if (mt >= mtiles) continue;
+                const int r0 = mt * 16 + kb * 4;
+                uint32_t t[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) t[j] = kzz - (uint32_t)zb * (uint32_t)rsum[r0 + j];
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) {
+                    const int k = k0 + nt * 16 + l16;
+                    const uint32_t cs = (uint32_t)za * (uint32_t)colsum[k];
+                    int c4[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) c4[j] = (int)((uint32_t)acc[i][nt][j] + t[j] - cs);
+                    const size_t o = (((size_t)n * K + k) * P + p) * Q + q0 + r0;
+                    if (vec && r0 + 3 < qc) {
+                        if (out_acc) *reinterpret_cast<int4 *>(out_acc + o) = make_int4(c4[0], c4[1], c4[2], c4[3]);
+                        if (out_f)
+                            *reinterpret_cast<float4 *>(out_f + o) =
+                                make_float4(sc * (float)c4[0], sc * (float)c4[1], sc * (float)c4[2], sc * (float)c4[3]);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            if (r0 + j >= qc) continue;
+                            if (out_acc) out_acc[o + j] = c4[j];
+                            if (out_f) out_f[o + j] = sc * (float)c4[j];
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// filter [K][C*R*S] -> [K][Kc] in the grouped column order of smallc_fused (column g*GP + s = entry
+// (g, s) of the (channel, filter row) group g; zeros elsewhere), sums per output channel
+__global__ __launch_bounds__(kThreads) void repack_grouped(const int8_t *__restrict__ w, int CRS, int CR, int S, int GP, int Kc,
+                                                           int8_t *__restrict__ wt, int *__restrict__ colsum)
+{
+    __shared__ int part[kThreads / 64];
+    const int k = blockIdx.x;
+    int sum = 0;
+    for (int j = threadIdx.x; j < Kc; j += kThreads) {
+        const int g = j / GP, s2 = j - g * GP;
+        const int8_t v = (g < CR && s2 < S) ? w[(size_t)k * CRS + g * S + s2] : (int8_t)0;
+        wt[(size_t)k * Kc + j] = v;
+        sum += v;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, Q8T_WAVE);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = sum;
+    __syncthreads();
+    if (threadIdx.x == 0) colsum[k] = part[0] + part[1] + part[2] + part[3];
 }
 
 // filter [K][C*R*S] -> [K][Kc] with zero surplus columns, sums per output channel, tap offset 0
@@ -730,6 +959,7 @@ __global__ __launch_bounds__(kThreads) void repack_flat(const int8_t *__restrict
 
 struct SmallPlan {
     int P, Q, Kc;
+    int GP, Kf;   // fused form: columns per (channel, filter row) group (0: not available), padded reduction
     size_t lds, o_rowsum, o_wt, o_colsum, o_tapoff, total;
 };
 
@@ -750,11 +980,15 @@ bool make_small_plan(int which, const q8t_conv_desc *d, SmallPlan *p)
     if (d->N > 65535) return false;
     const int64_t M = (int64_t)d->N * p->P * p->Q;
     if (M >= ((int64_t)1 << 31) || (int64_t)d->N * d->C * d->H >= ((int64_t)1 << 31)) return false;
-    p->lds = (((size_t)d->C * d->R * (d->W + 2 * d->pad) + 15) & ~(size_t)15) + ((size_t)p->Kc + p->Q) * sizeof(int);
+    p->lds = (((size_t)d->C * d->R * ((((d->pad + 3) & ~3) + d->W + d->pad + 3) & ~3) + 15) & ~(size_t)15) +
+             ((size_t)p->Kc + p->Q) * sizeof(int);
     if (p->lds > 65536) return false;
+    p->GP = d->S <= 4 ? 4 : (d->S <= 8 ? 8 : 0);
+    p->Kf = p->GP ? (int)(((int64_t)d->C * d->R * p->GP + 63) / 64 * 64) : 0;
+    if (p->Kf > 256) p->GP = p->Kf = 0;
     p->o_rowsum = up256s((size_t)M * p->Kc);
     p->o_wt = p->o_rowsum + up256s((size_t)M * sizeof(int));
-    p->o_colsum = p->o_wt + up256s((size_t)d->K * p->Kc);
+    p->o_colsum = p->o_wt + up256s((size_t)d->K * (p->Kc > p->Kf ? p->Kc : p->Kf));
     p->o_tapoff = p->o_colsum + up256s((size_t)d->K * sizeof(int));
     p->total = p->o_tapoff + 256;
     return true;
@@ -824,12 +1058,35 @@ int q8t_smallc_conv(const q8t_conv_desc *d, const void *a, const q8t_qparams *qa
     int8_t *wt = (int8_t *)ws + p.o_wt;
     int *colsum = (int *)((char *)ws + p.o_colsum);
     int *tapoff = (int *)((char *)ws + p.o_tapoff);
-    hipLaunchKernelGGL(im2col_positions, dim3((unsigned)p.P, (unsigned)d->N), dim3(kThreads), p.lds, st, (const int8_t *)a,
-                       d->C, d->H, d->W, d->R, d->S, d->stride, d->pad, p.P, p.Q, p.Kc, qa, xn, rowsum);
-    Q8T_LAUNCH_CHECK();
+    // fused form: operand tile, filter block, row sums and staged rows all in LDS
+    const int Ls = (d->pad + 3) & ~3, pitch = (Ls + d->W + d->pad + 3) & ~3;
+    const int vec4 = d->W % 4 == 0 && q8t_aligned(a, 4);
+    const size_t fused_lds = (size_t)(p.Kf >> 6) * (FUSED_MAXQ + 64) * 64 + (size_t)FUSED_MAXQ * sizeof(int) +
+                             (((size_t)d->C * d->R * pitch + 15) & ~(size_t)15) + 16;
+    if (p.GP && fused_lds <= 65536) {
+        hipLaunchKernelGGL(repack_grouped, dim3((unsigned)d->K), dim3(kThreads), 0, st, (const int8_t *)b,
+                           d->C * d->R * d->S, d->C * d->R, d->S, p.GP, p.Kf, wt, colsum);
+        Q8T_LAUNCH_CHECK();
+        // 16-byte stores need rows of the result that start on 16 bytes
+        const int vec = p.Q % 4 == 0 && q8t_aligned(out_f, 16) && q8t_aligned(out_acc, 16);
+        const dim3 grid((unsigned)p.P, (unsigned)d->N);
+        if (p.GP == 8)
+            hipLaunchKernelGGL(smallc_fused<8>, grid, dim3(kThreads), fused_lds, st, (const int8_t *)a, d->C, d->H, d->W, d->R,
+                               d->S, d->stride, d->pad, p.P, p.Q, p.Kf, d->K, wt, colsum, qa, qb, out_f, (int32_t *)out_acc,
+                               vec, vec4);
+        else
+            hipLaunchKernelGGL(smallc_fused<4>, grid, dim3(kThreads), fused_lds, st, (const int8_t *)a, d->C, d->H, d->W, d->R,
+                               d->S, d->stride, d->pad, p.P, p.Q, p.Kf, d->K, wt, colsum, qa, qb, out_f, (int32_t *)out_acc,
+                               vec, vec4);
+        Q8T_LAUNCH_CHECK();
+        return Q8T_OK;
+    }
     int *clsinfo = tapoff + 8;   // the tap table of this path has one entry
     hipLaunchKernelGGL(repack_flat, dim3((unsigned)d->K), dim3(kThreads), 0, st, (const int8_t *)b, d->C * d->R * d->S, p.Kc,
                        p.P, p.Q, d->N * p.P * p.Q, wt, colsum, tapoff, clsinfo);
+    Q8T_LAUNCH_CHECK();
+    hipLaunchKernelGGL(im2col_positions, dim3((unsigned)p.P, (unsigned)d->N), dim3(kThreads), p.lds, st, (const int8_t *)a,
+                       d->C, d->H, d->W, d->R, d->S, d->stride, d->pad, p.P, p.Q, p.Kc, qa, xn, rowsum, vec4);
     Q8T_LAUNCH_CHECK();
     Geo g;
     g.N = d->N;

@@ -129,6 +129,9 @@ CONV_CASES = [
     (8, 256, 14, 14, 256, 3, 3, 1, 1),   # 14x14 planes, 256 channels
     (16, 512, 7, 7, 512, 3, 3, 1, 1),    # 7x7 planes, 512 channels
     (24, 64, 56, 56, 64, 1, 1, 1, 0),    # reduction longer than one overflow-free slice
+    (4, 3, 30, 26, 64, 7, 7, 2, 3),      # few input channels, fused forward: odd result width (scalar stores)
+    (1, 4, 8, 300, 64, 3, 3, 1, 1),      # ... result rows longer than one 128-position pass
+    (2, 8, 20, 20, 128, 3, 3, 1, 1),     # ... two blocks of 64 output channels
     (13, 24, 17, 13, 40, 3, 2, 2, 1),    # nothing a multiple of anything; 63-position planes in groups of 4 images
     (6, 128, 7, 7, 128, 3, 3, 1, 1),     # 49-position planes, last image group incomplete
     (5, 64, 9, 10, 64, 3, 3, 1, 1),      # 90-position planes in pairs, last pair incomplete
