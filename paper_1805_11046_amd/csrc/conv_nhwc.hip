@@ -772,8 +772,9 @@ __global__ __launch_bounds__(kThreads) void smallc_fused(const int8_t *__restric
                                                          const int8_t *__restrict__ wt, const int *__restrict__ colsum,
                                                          const q8t_qparams *__restrict__ qpx,
                                                          const q8t_qparams *__restrict__ qpw, float *__restrict__ out_f,
-                                                         int32_t *__restrict__ out_acc, int vec, int vec4)
+                                                         int32_t *__restrict__ out_acc, int vec, int vec4, int RPB)
 {
+    constexpr int U = 6;   // dwords of input a thread carries from one output row to the next
     extern __shared__ __align__(16) int8_t lds[];
     const int KS = Kc >> 6;
     const int L = (pad + 3) & ~3, Wp = (L + W + pad + 3) & ~3;   // staged row: left margin, pitch
@@ -781,123 +782,179 @@ __global__ __launch_bounds__(kThreads) void smallc_fused(const int8_t *__restric
     int8_t *sB = sA + KS * FUSED_MAXQ * 64;             // [KS][64][64]
     int *rsum = reinterpret_cast<int *>(sB + KS * 64 * 64);   // [128]
     int8_t *rows = reinterpret_cast<int8_t *>(rsum + FUSED_MAXQ);   // [C*R][Wp] + 16 bytes of slack
-    const int n = blockIdx.y, p = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int pbeg = blockIdx.x * RPB, pend = min(P, pbeg + RPB);
     const int l16 = lane & 15, kb = lane >> 4;
     const int za = qpx->zero_point - (1 << (qpx->bits - 1)), zb = qpw->zero_point - (1 << (qpw->bits - 1));
     const float sc = qpx->scale * qpw->scale;
-    stage_rows(x, n, C, H, W, R, stride, pad, p, L, Wp, za, vec4 != 0, rows);
     const int CR = C * R;
     const int chunks = Kc >> 4;
+    const float rchunks = 1.0f / (float)chunks;
     const uint32_t zbyte = (uint32_t)(za & 255);
     const uint32_t kzz = (uint32_t)Kc * (uint32_t)za * (uint32_t)zb;
-    for (int k0 = 0; k0 < K; k0 += 64) {
-        for (int q0 = 0; q0 < Q; q0 += FUSED_MAXQ) {
-            const int qc = min(FUSED_MAXQ, Q - q0);
-            __syncthreads();   // staged rows and table ready; the previous pass has left sA / sB / rsum
-            if (tid < FUSED_MAXQ) rsum[tid] = 0;
-            // filter block: 64 output channels x Kc, 16-byte chunks, fragment layout
-            for (int it = tid; it < 64 * chunks; it += kThreads) {
-                const int row = it / chunks, ch = it - row * chunks;
-                const uint4 v = *reinterpret_cast<const uint4 *>(wt + (size_t)(k0 + row) * Kc + ch * 16);
-                *reinterpret_cast<uint4 *>(sB + (ch >> 2) * (64 * 64) + row * 64 + (((ch & 3) ^ q8t_gemm::swz(row)) * 16)) = v;
-            }
-            __syncthreads();   // rsum cleared before the sums below
-            // operand tile: rows = positions q0 .. q0 + qc (the rest of the last 16-row tile holds the zero code)
-            const int qpad = (qc + 15) & ~15;
-            for (int it = tid; it < qpad * chunks; it += kThreads) {
-                const int q = it / chunks, ch = it - q * chunks;
-                uint32_t w4[4] = {zbyte * 0x01010101u, zbyte * 0x01010101u, zbyte * 0x01010101u, zbyte * 0x01010101u};
-                if (q < qc) {
-                    const int base = (q0 + q) * stride + L - pad;
-                    if (GP == 8) {
-                        const uint64_t keep = S >= 8 ? ~0ull : ((1ull << (8 * S)) - 1);
-                        const uint64_t fill = (uint64_t)zbyte * 0x0101010101010101ull;
+    // The workgroup walks RPB output rows.  When the input rows under one output row fit into U dwords
+    // per thread, the loads for the next output row are issued before the current one is multiplied
+    // and land in LDS afterwards: their latency is off the critical path.  Margins keep the zero code
+    // from the one fill below; rows outside the image are rewritten with it every time.
+    const int W4 = W >> 2, items = CR * W4;
+    const bool carry = vec4 && items <= kThreads * U;
+    const bool filter_once = K == 64;
+    uint32_t pv[U];
+    int pd[U], prow[U];        // LDS offset of the thread's dword (-1: none); filter row minus padding
+    const int8_t *psrc[U];     // its source, at input row 0
 #pragma unroll
-                        for (int t = 0; t < 2; ++t) {
-                            const int g = ch * 2 + t;
-                            uint64_t v = fill;
-                            if (g < CR) {
-                                __builtin_memcpy(&v, rows + g * Wp + base, 8);
-                                v = (v & keep) | (fill & ~keep);
+    for (int u = 0; u < U; ++u) {
+        const int i = u * kThreads + tid;
+        pd[u] = -1;
+        prow[u] = 0;
+        psrc[u] = x;
+        if (carry && i < items) {
+            const int cr = i / W4, w4 = i - cr * W4, c = cr / R, r = cr - c * R;
+            pd[u] = cr * Wp + L + w4 * 4;
+            prow[u] = r - pad;
+            psrc[u] = x + ((size_t)n * C + c) * H * W + w4 * 4;
+        }
+    }
+    auto issue = [&](int p) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int h = p * stride + prow[u];
+            pv[u] = zbyte * 0x01010101u;
+            if (pd[u] >= 0 && (unsigned)h < (unsigned)H) pv[u] = *reinterpret_cast<const uint32_t *>(psrc[u] + (size_t)h * W);
+        }
+    };
+    auto load_filter = [&](int k0) {
+        for (int it = tid; it < 64 * chunks; it += kThreads) {
+            const int row = it / chunks, ch = it - row * chunks;
+            const uint4 v = *reinterpret_cast<const uint4 *>(wt + (size_t)(k0 + row) * Kc + ch * 16);
+            *reinterpret_cast<uint4 *>(sB + (ch >> 2) * (64 * 64) + row * 64 + (((ch & 3) ^ q8t_gemm::swz(row)) * 16)) = v;
+        }
+    };
+    if (carry) {
+        issue(pbeg);
+        uint32_t *r32 = reinterpret_cast<uint32_t *>(rows);
+        for (int i = tid; i < (CR * Wp + 16) >> 2; i += kThreads) r32[i] = zbyte * 0x01010101u;
+    }
+    if (filter_once) load_filter(0);
+    for (int p = pbeg; p < pend; ++p) {
+        if (carry) {
+            __syncthreads();   // the fill, or the previous output row's operand tile, is done with `rows`
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (pd[u] >= 0) *reinterpret_cast<uint32_t *>(rows + pd[u]) = pv[u];
+            if (p + 1 < pend) issue(p + 1);
+        } else {
+            __syncthreads();
+            stage_rows(x, n, C, H, W, R, stride, pad, p, L, Wp, za, vec4 != 0, rows);
+        }
+        for (int k0 = 0; k0 < K; k0 += 64) {
+            for (int q0 = 0; q0 < Q; q0 += FUSED_MAXQ) {
+                const int qc = min(FUSED_MAXQ, Q - q0);
+                __syncthreads();   // staged rows ready; the previous pass has left sA / sB / rsum
+                if (tid < FUSED_MAXQ) rsum[tid] = 0;
+                if (!filter_once) load_filter(k0);
+                __syncthreads();   // rsum cleared before the sums below
+                // operand tile: rows = positions q0 .. q0 + qc (the rest of the last 16-row tile holds the zero code)
+                const int qpad = (qc + 15) & ~15;
+                for (int it = tid; it < qpad * chunks; it += kThreads) {
+                    // q = it / chunks for it < 2^11 * 16 through the float reciprocal, corrected by at most one
+                    int q = (int)((float)it * rchunks);
+                    q += (it - q * chunks >= chunks) ? 1 : 0;
+                    q -= (it - q * chunks < 0) ? 1 : 0;
+                    const int ch = it - q * chunks;
+                    uint32_t w4[4] = {zbyte * 0x01010101u, zbyte * 0x01010101u, zbyte * 0x01010101u, zbyte * 0x01010101u};
+                    if (q < qc) {
+                        const int base = (q0 + q) * stride + L - pad;
+                        if (GP == 8) {
+                            const uint64_t keep = S >= 8 ? ~0ull : ((1ull << (8 * S)) - 1);
+                            const uint64_t fill = (uint64_t)zbyte * 0x0101010101010101ull;
+#pragma unroll
+                            for (int t = 0; t < 2; ++t) {
+                                const int g = ch * 2 + t;
+                                uint64_t v = fill;
+                                if (g < CR) {
+                                    __builtin_memcpy(&v, rows + g * Wp + base, 8);
+                                    v = (v & keep) | (fill & ~keep);
+                                }
+                                w4[2 * t] = (uint32_t)v;
+                                w4[2 * t + 1] = (uint32_t)(v >> 32);
                             }
-                            w4[2 * t] = (uint32_t)v;
-                            w4[2 * t + 1] = (uint32_t)(v >> 32);
+                        } else {
+                            const uint32_t keep = S >= 4 ? ~0u : ((1u << (8 * S)) - 1);
+                            const uint32_t fill = zbyte * 0x01010101u;
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                const int g = ch * 4 + t;
+                                uint32_t v = fill;
+                                if (g < CR) {
+                                    __builtin_memcpy(&v, rows + g * Wp + base, 4);
+                                    v = (v & keep) | (fill & ~keep);
+                                }
+                                w4[t] = v;
+                            }
                         }
-                    } else {
-                        const uint32_t keep = S >= 4 ? ~0u : ((1u << (8 * S)) - 1);
-                        const uint32_t fill = zbyte * 0x01010101u;
+                        atomicAdd(&rsum[q], bytesum4(w4[0]) + bytesum4(w4[1]) + bytesum4(w4[2]) + bytesum4(w4[3]));
+                    }
+                    *reinterpret_cast<uint4 *>(sA + (ch >> 2) * (FUSED_MAXQ * 64) + q * 64 +
+                                               (((ch & 3) ^ q8t_gemm::swz(q)) * 16)) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+                }
+                __syncthreads();
+                // wavefront w: 16-row tiles w and w + 4, all four 16-channel tiles
+                v4i acc[2][4];
 #pragma unroll
-                        for (int t = 0; t < 4; ++t) {
-                            const int g = ch * 4 + t;
-                            uint32_t v = fill;
-                            if (g < CR) {
-                                __builtin_memcpy(&v, rows + g * Wp + base, 4);
-                                v = (v & keep) | (fill & ~keep);
-                            }
-                            w4[t] = v;
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[i][j] = (v4i){0, 0, 0, 0};
+                const int mtiles = qpad >> 4;
+                for (int ks = 0; ks < KS; ++ks) {
+                    v4i bf[4];
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) {
+                        const int row = nt * 16 + l16;
+                        bf[nt] = *reinterpret_cast<const v4i *>(sB + ks * (64 * 64) + row * 64 + ((kb ^ q8t_gemm::swz(row)) * 16));
+                    }
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        const int mt = wave + i * 4;
+                        if (mt < mtiles) {   // uniform per wavefront
+                            const int row = mt * 16 + l16;
+                            const v4i af = *reinterpret_cast<const v4i *>(sA + ks * (FUSED_MAXQ * 64) + row * 64 +
+                                                                          ((kb ^ q8t_gemm::swz(row)) * 16));
+#pragma unroll
+                            for (int nt = 0; nt < 4; ++nt)
+                                acc[i][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af, bf[nt], acc[i][nt], 0, 0, 0);
                         }
                     }
-                    atomicAdd(&rsum[q], bytesum4(w4[0]) + bytesum4(w4[1]) + bytesum4(w4[2]) + bytesum4(w4[3]));
                 }
-                *reinterpret_cast<uint4 *>(sA + (ch >> 2) * (FUSED_MAXQ * 64) + q * 64 + (((ch & 3) ^ q8t_gemm::swz(q)) * 16)) =
-                    make_uint4(w4[0], w4[1], w4[2], w4[3]);
-            }
-            __syncthreads();
-            // wavefront w: 16-row tiles w and w + 4, all four 16-channel tiles
-            v4i acc[2][4];
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = (v4i){0, 0, 0, 0};
-            const int mtiles = qpad >> 4;
-            for (int ks = 0; ks < KS; ++ks) {
-                v4i bf[4];
-#pragma unroll
-                for (int nt = 0; nt < 4; ++nt) {
-                    const int row = nt * 16 + l16;
-                    bf[nt] = *reinterpret_cast<const v4i *>(sB + ks * (64 * 64) + row * 64 + ((kb ^ q8t_gemm::swz(row)) * 16));
-                }
+                // epilogue: a lane holds 4 consecutive positions of one output channel
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
                     const int mt = wave + i * 4;
-                    if (mt < mtiles) {   // uniform per wavefront
-                        const int row = mt * 16 + l16;
-                        const v4i af = *reinterpret_cast<const v4i *>(sA + ks * (FUSED_MAXQ * 64) + row * 64 +
-                                                                      ((kb ^ q8t_gemm::swz(row)) * 16));
+                    if (mt >= mtiles) continue;
+                    const int r0 = mt * 16 + kb * 4;
+                    uint32_t t[4];
 #pragma unroll
-                        for (int nt = 0; nt < 4; ++nt)
-                            acc[i][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af, bf[nt], acc[i][nt], 0, 0, 0);
-                    }
-                }
-            }
-            // epilogue: a lane holds 4 consecutive positions of one output channel
+                    for (int j = 0; j < 4; ++j) t[j] = kzz - (uint32_t)zb * (uint32_t)rsum[r0 + j];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int mt = wave + i * 4;
-                if (mt >= mtiles) continue;
-                const int r0 = mt * 16 + kb * 4;
-                uint32_t t[4];
+                    for (int nt = 0; nt < 4; ++nt) {
+                        const int k = k0 + nt * 16 + l16;
+                        const uint32_t cs = (uint32_t)za * (uint32_t)colsum[k];
+                        int c4[4];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) t[j] = kzz - (uint32_t)zb * (uint32_t)rsum[r0 + j];
+                        for (int j = 0; j < 4; ++j) c4[j] = (int)((uint32_t)acc[i][nt][j] + t[j] - cs);
+                        const size_t o = (((size_t)n * K + k) * P + p) * Q + q0 + r0;
+                        if (vec && r0 + 3 < qc) {
+                            if (out_acc) *reinterpret_cast<int4 *>(out_acc + o) = make_int4(c4[0], c4[1], c4[2], c4[3]);
+                            if (out_f)
+                                *reinterpret_cast<float4 *>(out_f + o) =
+                                    make_float4(sc * (float)c4[0], sc * (float)c4[1], sc * (float)c4[2], sc * (float)c4[3]);
+                        } else {
 #pragma unroll
-                for (int nt = 0; nt < 4; ++nt) {
-                    const int k = k0 + nt * 16 + l16;
-                    const uint32_t cs = (uint32_t)za * (uint32_t)colsum[k];
-                    int c4[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) c4[j] = (int)((uint32_t)acc[i][nt][j] + t[j] - cs);
-                    const size_t o = (((size_t)n * K + k) * P + p) * Q + q0 + r0;
-                    if (vec && r0 + 3 < qc) {
-                        if (out_acc) *reinterpret_cast<int4 *>(out_acc + o) = make_int4(c4[0], c4[1], c4[2], c4[3]);
-                        if (out_f)
-                            *reinterpret_cast<float4 *>(out_f + o) =
-                                make_float4(sc * (float)c4[0], sc * (float)c4[1], sc * (float)c4[2], sc * (float)c4[3]);
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            if (r0 + j >= qc) continue;
-                            if (out_acc) out_acc[o + j] = c4[j];
-                            if (out_f) out_f[o + j] = sc * (float)c4[j];
+                            for (int j = 0; j < 4; ++j) {
+                                if (r0 + j >= qc) continue;
+                                if (out_acc) out_acc[o + j] = c4[j];
+                                if (out_f) out_f[o + j] = sc * (float)c4[j];
+                            }
                         }
                     }
                 }
@@ -1069,15 +1126,16 @@ int q8t_smallc_conv(const q8t_conv_desc *d, const void *a, const q8t_qparams *qa
         Q8T_LAUNCH_CHECK();
         // 16-byte stores need rows of the result that start on 16 bytes
         const int vec = p.Q % 4 == 0 && q8t_aligned(out_f, 16) && q8t_aligned(out_acc, 16);
-        const dim3 grid((unsigned)p.P, (unsigned)d->N);
+        const int RPB = 4;   // output rows per workgroup
+        const dim3 grid((unsigned)((p.P + RPB - 1) / RPB), (unsigned)d->N);
         if (p.GP == 8)
             hipLaunchKernelGGL(smallc_fused<8>, grid, dim3(kThreads), fused_lds, st, (const int8_t *)a, d->C, d->H, d->W, d->R,
                                d->S, d->stride, d->pad, p.P, p.Q, p.Kf, d->K, wt, colsum, qa, qb, out_f, (int32_t *)out_acc,
-                               vec, vec4);
+                               vec, vec4, RPB);
         else
             hipLaunchKernelGGL(smallc_fused<4>, grid, dim3(kThreads), fused_lds, st, (const int8_t *)a, d->C, d->H, d->W, d->R,
                                d->S, d->stride, d->pad, p.P, p.Q, p.Kf, d->K, wt, colsum, qa, qb, out_f, (int32_t *)out_acc,
-                               vec, vec4);
+                               vec, vec4, RPB);
         Q8T_LAUNCH_CHECK();
         return Q8T_OK;
     }
