@@ -459,7 +459,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_finish(const int32_t *__restri
                                                          const int *__restrict__ csum, int nz, int K, int CRS, int Rap,
                                                          int Rbp, int64_t Mp, const q8t_qparams *__restrict__ qpg,
                                                          const q8t_qparams *__restrict__ qpx, float *__restrict__ dw,
-                                                         int64_t *__restrict__ acc_out, int zgn, int tiled)
+                                                         int64_t *__restrict__ acc_out, int zgn, int tiled, int S, int GP)
 {
     __shared__ long long red[5][kThreads];
     const int per = kThreads / zgn;
@@ -471,6 +471,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_finish(const int32_t *__restri
     if (ok) {
         k = (int)(id / CRS);
         col = (int)(id - (int64_t)k * CRS);
+        // GP > 0: the partial sums keep the taps of one (channel, filter row) in groups of GP columns
+        if (GP) col = (col / S) * GP + col % S;
         // rows of the two byte planes: [all high | all low], or per `tiled` channels [high | low]
         const int rh = tiled ? (k / tiled) * 2 * tiled + (k % tiled) : k, rl = tiled ? rh + tiled : K + k;
         for (int z = zg; z < nz; z += zgn) {
@@ -514,6 +516,254 @@ struct Plan {
 };
 
 inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// ---- weight gradient of a layer with few input channels (the network's first layer), one kernel ----
+// GEMM view as above (rows = byte planes of g16 for 64 output channels, columns = (channel, filter
+// row) groups of GP taps, reduction = positions), but neither operand is laid out in HBM: a
+// workgroup walks output rows (n, p); for each it splits the 64 x Q gradient values into the two
+// byte planes straight into the LDS operand tile, stages the R input rows of every channel and
+// cuts the column operand out of them (16 consecutive positions of one tap = 16 bytes `stride`
+// apart in a staged row), multiplies, and keeps the 128 x Kf accumulator tile in registers until its
+// share of the rows is done.  Positions Q..127 of a row hold (0, zero code): they add nothing and
+// are counted in the reduction length handed to wgrad_finish.  The loads for the next output row
+// are issued before the current one is multiplied.
+// Needs: C*R*GP <= 256, stride 1 or 2, Q <= 128 and Q % 16 == 0, W % 4 == 0, 16-byte aligned g16
+// rows (Q % 8 == 0), at most UX dwords of input and UA / UB operand pieces per thread and row.
+template <int GP, int NT>
+__global__ __launch_bounds__(kThreads) void wgrad_smallc(const int16_t *__restrict__ g16, const int8_t *__restrict__ x, int C,
+                                                         int H, int W, int R, int S, int stride, int pad, int P, int Q, int K,
+                                                         int RB, int rows_total, const q8t_qparams *__restrict__ qpx,
+                                                         int32_t *__restrict__ part, int *__restrict__ rsum,
+                                                         int *__restrict__ csum)
+{
+    constexpr int Kf = NT * 16, UX = 6, UA = 4, UB = 5;
+    extern __shared__ __align__(16) int8_t lds[];
+    int8_t *sA = lds;                                    // [2][128][64]
+    int8_t *sB = sA + 2 * 128 * 64;                      // [2][Kf][64]
+    int *sums = reinterpret_cast<int *>(sB + 2 * Kf * 64);   // [128] rows of A', [Kf] rows of B'
+    int8_t *rows = reinterpret_cast<int8_t *>(sums + 128 + Kf);   // [C*R][Wp] + 16
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, kq = lane >> 4;
+    const int z = blockIdx.x, kblk = blockIdx.y;
+    const int row0 = z * RB, row1 = min(rows_total, row0 + RB);
+    const int zx = qpx->zero_point - (1 << (qpx->bits - 1));
+    const uint32_t zfill = (uint32_t)(zx & 255) * 0x01010101u;
+    const int CR = C * R, L = (pad + 3) & ~3, Wp = (L + W + pad + 3) & ~3;
+    const int W4 = W >> 2, Q8 = Q >> 3, Q16 = Q >> 4;
+
+    // ---- fixed roles of the thread ----
+    int xd[UX], xr[UX], xo[UX];          // input dwords: LDS offset (-1: none), filter row - pad, offset inside an image
+    int ag[UA], ad[UA];                  // gradient pieces of 8 values: offset inside an image, LDS offset (-1: none)
+    int bs[UB], bd[UB], bj[UB];          // column pieces of 16 positions: byte offset in `rows`, LDS offset (-1), column
+#pragma unroll
+    for (int u = 0; u < UX; ++u) {
+        const int i = u * kThreads + tid;
+        xd[u] = -1;
+        xr[u] = xo[u] = 0;
+        if (i < CR * W4) {
+            const int cr = i / W4, w4 = i - cr * W4, c = cr / R, r = cr - c * R;
+            xd[u] = cr * Wp + L + w4 * 4;
+            xr[u] = r - pad;
+            xo[u] = c * H * W + w4 * 4;
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UA; ++u) {
+        const int i = u * kThreads + tid;
+        ad[u] = -1;
+        ag[u] = 0;
+        if (i < 64 * Q8) {
+            const int k = i / Q8, ch = i - k * Q8, m = ch * 8;
+            ag[u] = (kblk * 64 + k) * P * Q + m;
+            ad[u] = (m >> 6) * (128 * 64) + k * 64 + ((((m & 63) >> 4) ^ q8t_gemm::swz(k)) * 16) + ((m >> 3) & 1) * 8;
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < UB; ++u) {
+        const int i = u * kThreads + tid;
+        bd[u] = -1;
+        bs[u] = bj[u] = 0;
+        if (i < CR * S * Q16) {
+            const int t = i / Q16, c = i - t * Q16, gg = t / S, s2 = t - gg * S, j = gg * GP + s2;
+            bj[u] = j;
+            bs[u] = gg * Wp + L - pad + s2 + stride * 16 * c;
+            bd[u] = (c >> 2) * (Kf * 64) + j * 64 + (((c & 3) ^ q8t_gemm::swz(j)) * 16);
+        }
+    }
+    // ---- LDS: A' zero, B' and the staged rows at the zero code ----
+    {
+        uint32_t *w = reinterpret_cast<uint32_t *>(sA);
+        for (int i = tid; i < (2 * 128 * 64) >> 2; i += kThreads) w[i] = 0;
+        w = reinterpret_cast<uint32_t *>(sB);
+        for (int i = tid; i < (2 * Kf * 64) >> 2; i += kThreads) w[i] = zfill;
+        w = reinterpret_cast<uint32_t *>(rows);
+        for (int i = tid; i < (CR * Wp + 16) >> 2; i += kThreads) w[i] = zfill;
+        for (int i = tid; i < 128 + Kf; i += kThreads) sums[i] = 0;
+    }
+    v4i acc[2][NT];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = (v4i){0, 0, 0, 0};
+    int sah[UA], sal[UA], sbs[UB];
+#pragma unroll
+    for (int u = 0; u < UA; ++u) sah[u] = sal[u] = 0;
+#pragma unroll
+    for (int u = 0; u < UB; ++u) sbs[u] = 0;
+
+    uint32_t xv[UX];
+    uint4 av[UA];
+    auto issue = [&](int row) {
+        const int n = row / P, p = row - n * P;
+        const int8_t *xb = x + (size_t)n * C * H * W;
+        const int16_t *gb = g16 + (size_t)n * K * P * Q + (size_t)p * Q;
+#pragma unroll
+        for (int u = 0; u < UX; ++u) {
+            const int h = p * stride + xr[u];
+            xv[u] = zfill;
+            if (xd[u] >= 0 && (unsigned)h < (unsigned)H) xv[u] = *reinterpret_cast<const uint32_t *>(xb + xo[u] + (size_t)h * W);
+        }
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            av[u] = make_uint4(0, 0, 0, 0);
+            if (ad[u] >= 0) av[u] = *reinterpret_cast<const uint4 *>(gb + ag[u]);
+        }
+    };
+    if (row0 < row1) issue(row0);
+    for (int row = row0; row < row1; ++row) {
+        __syncthreads();   // the fill, or the previous row's multiply, is done with sA / sB / rows
+#pragma unroll
+        for (int u = 0; u < UX; ++u)
+            if (xd[u] >= 0) *reinterpret_cast<uint32_t *>(rows + xd[u]) = xv[u];
+#pragma unroll
+        for (int u = 0; u < UA; ++u) {
+            if (ad[u] < 0) continue;
+            const uint32_t h0 = __builtin_amdgcn_perm(av[u].y, av[u].x, 0x07050301u);
+            const uint32_t h1 = __builtin_amdgcn_perm(av[u].w, av[u].z, 0x07050301u);
+            const uint32_t l0 = __builtin_amdgcn_perm(av[u].y, av[u].x, 0x06040200u) ^ 0x80808080u;
+            const uint32_t l1 = __builtin_amdgcn_perm(av[u].w, av[u].z, 0x06040200u) ^ 0x80808080u;
+            *reinterpret_cast<uint2 *>(sA + ad[u]) = make_uint2(h0, h1);
+            *reinterpret_cast<uint2 *>(sA + ad[u] + 64 * 64) = make_uint2(l0, l1);
+            sah[u] += bytesum4(h0) + bytesum4(h1);
+            sal[u] += bytesum4(l0) + bytesum4(l1);
+        }
+        if (row + 1 < row1) issue(row + 1);
+        __syncthreads();   // staged rows complete
+        // column operand: 16 positions of one tap are 16 bytes `stride` apart; read the aligned dwords
+        // that contain them, shift to the first byte, keep every stride-th byte
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            if (bd[u] < 0) continue;
+            const int a0 = bs[u] & ~3;
+            const uint32_t sh = (uint32_t)(bs[u] & 3);
+            uint32_t o[4];
+            if (stride == 1) {
+                uint32_t d[5];
+#pragma unroll
+                for (int i = 0; i < 5; ++i) d[i] = *reinterpret_cast<const uint32_t *>(rows + a0 + 4 * i);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o[i] = __builtin_amdgcn_alignbyte(d[i + 1], d[i], sh);
+            } else {
+                uint32_t d[9];
+#pragma unroll
+                for (int i = 0; i < 9; ++i) d[i] = *reinterpret_cast<const uint32_t *>(rows + a0 + 4 * i);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t e0 = __builtin_amdgcn_alignbyte(d[2 * i + 1], d[2 * i], sh);
+                    const uint32_t e1 = __builtin_amdgcn_alignbyte(d[2 * i + 2], d[2 * i + 1], sh);
+                    o[i] = __builtin_amdgcn_perm(e1, e0, 0x06040200u);   // bytes 0, 2, 4, 6 of the 8
+                }
+            }
+            *reinterpret_cast<uint4 *>(sB + bd[u]) = make_uint4(o[0], o[1], o[2], o[3]);
+            sbs[u] += bytesum4(o[0]) + bytesum4(o[1]) + bytesum4(o[2]) + bytesum4(o[3]);
+        }
+        __syncthreads();
+        // wavefront w multiplies rows [32w, 32w + 32) of A' (w < 2: high plane) against every column tile
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            v4i af[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int r = wave * 32 + i * 16 + l16;
+                af[i] = *reinterpret_cast<const v4i *>(sA + ks * (128 * 64) + r * 64 + ((kq ^ q8t_gemm::swz(r)) * 16));
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int r = nt * 16 + l16;
+                const v4i bf = *reinterpret_cast<const v4i *>(sB + ks * (Kf * 64) + r * 64 + ((kq ^ q8t_gemm::swz(r)) * 16));
+                acc[0][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[0], bf, acc[0][nt], 0, 0, 0);
+                acc[1][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(af[1], bf, acc[1][nt], 0, 0, 0);
+            }
+        }
+    }
+    // ---- byte sums of the rows of A' and B' (zero-point correction), then the partial tile ----
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < UA; ++u) {
+        if (ad[u] < 0) continue;
+        const int k = (u * kThreads + tid) / Q8;
+        atomicAdd(&sums[k], sah[u]);
+        atomicAdd(&sums[64 + k], sal[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < UB; ++u)
+        if (bd[u] >= 0) atomicAdd(&sums[128 + bj[u]], sbs[u]);
+    __syncthreads();
+    const int Rap = 2 * K;
+    if (tid < 128) rsum[(size_t)z * Rap + (tid < 64 ? kblk * 64 + tid : K + kblk * 64 + tid - 64)] = sums[tid];
+    // positions Q..127 of every row hold the zero code
+    if (kblk == 0 && tid < Kf) csum[(size_t)z * Kf + tid] = sums[128 + tid] + (row1 > row0 ? (row1 - row0) * (128 - Q) * zx : 0);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int lr = wave * 32 + i * 16 + kq * 4 + jj;
+            const int gr = lr < 64 ? kblk * 64 + lr : K + kblk * 64 + lr - 64;
+            int32_t *dst = part + ((size_t)z * Rap + gr) * Kf + l16;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) dst[nt * 16] = acc[i][nt][jj];
+        }
+}
+
+struct FusedPlan {
+    int P, Q, GP, Kf, nz, RB, rows;
+    size_t lds, o_rsum, o_csum, total;
+};
+
+bool make_fused_plan(const q8t_conv_desc *d, FusedPlan *p)
+{
+    if (d->N <= 0 || d->C <= 0 || d->C >= 64 || d->K <= 0 || d->K % 64 || d->H <= 0 || d->W <= 0) return false;
+    if (d->R <= 0 || d->S <= 0 || d->S > 8 || d->R > 100 || d->stride < 1 || d->stride > 2 || d->pad < 0 || d->pad > 100)
+        return false;
+    if (d->H + 2 * d->pad < d->R || d->W + 2 * d->pad < d->S || d->W % 4) return false;
+    p->P = (d->H + 2 * d->pad - d->R) / d->stride + 1;
+    p->Q = (d->W + 2 * d->pad - d->S) / d->stride + 1;
+    if (p->Q > 128 || p->Q % 16) return false;
+    p->GP = d->S <= 4 ? 4 : 8;
+    p->Kf = (d->C * d->R * p->GP + 63) / 64 * 64;
+    if (p->Kf > 256) return false;
+    const int CR = d->C * d->R, L = (d->pad + 3) & ~3, Wp = (L + d->W + d->pad + 3) & ~3;
+    // pieces per thread and output row
+    if (CR * (d->W / 4) > kThreads * 6 || 64 * (p->Q / 8) > kThreads * 4 || CR * d->S * (p->Q / 16) > kThreads * 5) return false;
+    const int64_t rows = (int64_t)d->N * p->P;
+    if (rows >= ((int64_t)1 << 30) || (int64_t)d->N * d->K * p->P * p->Q >= ((int64_t)1 << 31) ||
+        (int64_t)d->N * d->C * d->H * d->W >= ((int64_t)1 << 31))
+        return false;
+    p->rows = (int)rows;
+    // two workgroups per compute unit; a workgroup's accumulators take at most 512 rows of 128 products
+    int64_t nz = rows < 512 ? rows : 512;
+    if ((rows + nz - 1) / nz > 512) nz = (rows + 511) / 512;
+    if (nz > 65535) return false;
+    p->RB = (int)((rows + nz - 1) / nz);
+    p->nz = (int)((rows + p->RB - 1) / p->RB);
+    p->lds = (size_t)2 * 128 * 64 + (size_t)2 * p->Kf * 64 + (size_t)(128 + p->Kf) * sizeof(int) + (((size_t)CR * Wp + 15) & ~(size_t)15) + 16;
+    if (p->lds > 65536) return false;
+    p->o_rsum = up256((size_t)p->nz * 2 * d->K * p->Kf * sizeof(int32_t));
+    p->o_csum = p->o_rsum + up256((size_t)p->nz * 2 * d->K * sizeof(int));
+    p->total = p->o_csum + up256((size_t)p->nz * p->Kf * sizeof(int));
+    return true;
+}
+
 
 bool make_plan(const q8t_conv_desc *d, Plan *p)
 {
@@ -566,18 +816,48 @@ bool make_plan(const q8t_conv_desc *d, Plan *p)
 bool q8t_gemm_wgrad_supported(const q8t_conv_desc *d)
 {
     Plan p;
-    return make_plan(d, &p);
+    FusedPlan f;
+    return make_plan(d, &p) || make_fused_plan(d, &f);
 }
 
 size_t q8t_gemm_wgrad_ws(const q8t_conv_desc *d)
 {
     Plan p;
-    return make_plan(d, &p) ? p.total : 0;
+    FusedPlan f;
+    const size_t a = make_plan(d, &p) ? p.total : 0, b = make_fused_plan(d, &f) ? f.total : 0;
+    return a > b ? a : b;
 }
 
 int q8t_gemm_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams *qg, const int8_t *x,
                    const q8t_qparams *qx, float *dw, int64_t *acc_out, void *ws, hipStream_t st)
 {
+    FusedPlan f;
+    if (make_fused_plan(d, &f) && q8t_aligned(g16, 16) && q8t_aligned(x, 4)) {
+        if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+        int32_t *part = (int32_t *)ws;
+        int *rsum = (int *)((char *)ws + f.o_rsum);
+        int *csum = (int *)((char *)ws + f.o_csum);
+        const dim3 grid((unsigned)f.nz, (unsigned)(d->K / 64));
+#define Q8T_GO(GPV, NTV)                                                                                              \
+    hipLaunchKernelGGL((wgrad_smallc<GPV, NTV>), grid, dim3(kThreads), f.lds, st, g16, x, d->C, d->H, d->W, d->R, d->S, \
+                       d->stride, d->pad, f.P, f.Q, d->K, f.RB, f.rows, qx, part, rsum, csum)
+        const int nt = f.Kf / 16;
+        if (f.GP == 8) {
+            if (nt == 4) Q8T_GO(8, 4); else if (nt == 8) Q8T_GO(8, 8); else if (nt == 12) Q8T_GO(8, 12); else Q8T_GO(8, 16);
+        } else {
+            if (nt == 4) Q8T_GO(4, 4); else if (nt == 8) Q8T_GO(4, 8); else if (nt == 12) Q8T_GO(4, 12); else Q8T_GO(4, 16);
+        }
+#undef Q8T_GO
+        Q8T_LAUNCH_CHECK();
+        const int CRS = d->C * d->R * d->S;
+        const int64_t count = (int64_t)d->K * CRS;
+        const int zgn = f.nz >= 64 ? 16 : (f.nz >= 8 ? 4 : 1);
+        const int per = kThreads / zgn;
+        hipLaunchKernelGGL(wgrad_finish, dim3((unsigned)((count + per - 1) / per)), dim3(kThreads), 0, st, part, rsum, csum,
+                           f.nz, d->K, CRS, 2 * d->K, f.Kf, (int64_t)f.rows * 128, qg, qx, dw, acc_out, zgn, 0, d->S, f.GP);
+        Q8T_LAUNCH_CHECK();
+        return Q8T_OK;
+    }
     Plan p;
     if (!make_plan(d, &p)) return Q8T_ERR_SHAPE;
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
@@ -650,7 +930,7 @@ int q8t_gemm_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams
         const int per = kThreads / zgn;
         hipLaunchKernelGGL(wgrad_finish, dim3((unsigned)((count + per - 1) / per)), dim3(kThreads), 0, st,
                            part, rsum, csum, p.nz, d->K, p.CRS, p.Rap, p.Rbp, p.Mp, qg, qx, dw, acc_out, zgn,
-                           direct ? (p.cfg == 2 ? 128 : 64) : 0);
+                           direct ? (p.cfg == 2 ? 128 : 64) : 0, 1, 0);
         Q8T_LAUNCH_CHECK();
     }
     return Q8T_OK;

@@ -132,6 +132,9 @@ CONV_CASES = [
     (4, 3, 30, 26, 64, 7, 7, 2, 3),      # few input channels, fused forward: odd result width (scalar stores)
     (1, 4, 8, 300, 64, 3, 3, 1, 1),      # ... result rows longer than one 128-position pass
     (2, 8, 20, 20, 128, 3, 3, 1, 1),     # ... two blocks of 64 output channels
+    (4, 3, 64, 64, 64, 7, 7, 2, 3),      # few input channels: weight gradient in one kernel (operands cut out in LDS)
+    (8, 4, 16, 32, 64, 3, 3, 1, 1),      # ... stride 1, groups of 4 taps
+    (4, 3, 32, 32, 128, 7, 7, 2, 3),     # ... two blocks of 64 output channels
     (13, 24, 17, 13, 40, 3, 2, 2, 1),    # nothing a multiple of anything; 63-position planes in groups of 4 images
     (6, 128, 7, 7, 128, 3, 3, 1, 1),     # 49-position planes, last image group incomplete
     (5, 64, 9, 10, 64, 3, 3, 1, 1),      # 90-position planes in pairs, last pair incomplete
