@@ -85,12 +85,12 @@ class LayerStep:
             ("range_bn_fwd_apply", lambda s: q8t.range_bn_fwd_apply(self.y, self.stats, None, None, 1e-5,
                                                                     quantized=True, want_y=False, q_out=self.bnq,
                                                                     qp_out=self.pbn), 5.0 * n, 0),
-            # Range BN backward with the bifurcated quantization of its result: 20 B/element for the
-            # backward pass + 7 B/element (4 re-read, 1 + 2 written) for the two copies; the min/max
-            # of the gradient is taken while it is written
+            # Range BN backward with the bifurcated quantization of its result: 8 B/element for the
+            # sums (x, dy), which also yield the range of dx, then 8 read + 4 (dx) + 1 + 2 written
+            # in the second pass: the gradient is quantized where it is computed
             ("range_bn_bwd_bifurcate", lambda s: q8t.range_bn_bwd_bifurcate(
                 self.y, self.dout, self.stats, None, 1e-5, 2 * s + 1, 2 * s + 2, dx_out=self.g, q8_out=self.g8,
-                qp8_out=self.pg8, q16_out=self.g16, qp16_out=self.pg16), 27.0 * n, 0),
+                qp8_out=self.pg8, q16_out=self.g16, qp16_out=self.pg16), 23.0 * n, 0),
             ("qconv_dgrad", lambda s: q8t.qconv_dgrad(self.desc, self.g8, self.pg8, self.qw, self.pw, out=self.dx),
              1.0 * n + 4.0 * n, ops),
             ("qconv_wgrad", lambda s: q8t.qconv_wgrad(self.desc, self.qx, self.px, self.g16, self.pg16,

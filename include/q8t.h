@@ -195,13 +195,15 @@ int q8t_range_bn_bwd(const float *x, const float *dy, const float *stats, int N,
                      const float *gamma, float eps, float *dx, float *dgamma, float *dbeta, void *ws,
                      void *stream);
 
-/* Range BN backward fused with the bifurcated quantization of its result (Section 7 for the
+/* Range BN backward together with the bifurcated quantization of its result (Section 7 for the
  * backward rule; Sections 1 and 4 for the 8-bit / 16-bit stochastic copies of the layer gradient).
- * dx is written as fp32 and its min/max is taken in the same pass, so the quantizer needs no range
- * search of its own: one pass over dx less than q8t_range_bn_bwd followed by
- * q8t_quantize_bifurcate(dx, ...), with bit-identical results.  dx, q8_out, q16_out and both
- * parameter blocks are required; dgamma / dbeta stay nullable.  Planes of fewer than 256 positions
- * run the two steps one after the other (same results, no pass saved).
+ * Inside a channel dx is a monotone function of dy, apart from the -/+ term at the coordinates that
+ * attain the channel's max / min; the pass that takes the sums therefore also yields the exact range
+ * of dx (from the extremes of dy per kind of coordinate), and the second pass quantizes dx where it
+ * is computed: 8 + 8 + 3 bytes per element (+4 if dx is wanted) against 20 + 11 for
+ * q8t_range_bn_bwd followed by q8t_quantize_bifurcate, with bit-identical results.
+ * dx is nullable (the codes are all the rest of the backward pass consumes); q8_out, q16_out and
+ * both parameter blocks are required; dgamma / dbeta stay nullable.
  * ws: q8t_range_bn_bwd_bifurcate_workspace_size. */
 size_t q8t_range_bn_bwd_bifurcate_workspace_size(int N, int C, int H, int W);
 int q8t_range_bn_bwd_bifurcate(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
@@ -224,7 +226,7 @@ int q8t_range_bn_relu_fwd_apply(const float *x, int N, int C, int H, int W, cons
  * to the rectified output; it passes where the forward output gamma*xhat + beta (recomputed from
  * x and stats in the forward's fp32 arithmetic) is positive and counts as zero elsewhere
  * (derivative 0 at 0), then the rule of q8t_range_bn_bwd_bifurcate applies, dgamma / dbeta
- * included.  beta is nullable (0).  Same workspace as q8t_range_bn_bwd_bifurcate. */
+ * included.  beta and dx are nullable.  Same workspace as q8t_range_bn_bwd_bifurcate. */
 int q8t_range_bn_relu_bwd_bifurcate(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
                                     const float *gamma, const float *beta, float eps, float *dx, float *dgamma,
                                     float *dbeta, uint64_t seed8, uint64_t seed16, int8_t *q8_out,

@@ -366,13 +366,13 @@ def range_bn_bwd(x, dy, stats, gamma=None, eps=0.0, dx_out=None, ws=None):
 
 
 def range_bn_relu_bwd_bifurcate(x, dy, stats, gamma=None, beta=None, eps=0.0, seed8=0, seed16=1, dx_out=None,
-                                q8_out=None, qp8_out=None, q16_out=None, qp16_out=None, ws=None):
+                                q8_out=None, qp8_out=None, q16_out=None, qp16_out=None, ws=None, want_dx=True):
     """Backward of Range BN + ReLU + bifurcated quantization of dx in one call.
-    Returns (dx, dgamma, dbeta, q8, qp8, q16, qp16)."""
+    Returns (dx or None, dgamma, dbeta, q8, qp8, q16, qp16)."""
     _dev(x), _dev(dy), _dev(stats)
     N, Cc, H, W = x.shape
     dev = x.device
-    dx = dx_out if dx_out is not None else torch.empty_like(x)
+    dx = dx_out if dx_out is not None else (torch.empty_like(x) if want_dx else None)
     dgamma = torch.empty(Cc, dtype=torch.float32, device=dev)
     dbeta = torch.empty(Cc, dtype=torch.float32, device=dev)
     q8 = q8_out if q8_out is not None else torch.empty(x.shape, dtype=torch.int8, device=dev)
@@ -389,13 +389,13 @@ def range_bn_relu_bwd_bifurcate(x, dy, stats, gamma=None, beta=None, eps=0.0, se
 
 
 def range_bn_bwd_bifurcate(x, dy, stats, gamma=None, eps=0.0, seed8=0, seed16=1, dx_out=None, q8_out=None,
-                           qp8_out=None, q16_out=None, qp16_out=None, ws=None):
+                           qp8_out=None, q16_out=None, qp16_out=None, ws=None, want_dx=True):
     """Range BN backward + bifurcated quantization of dx in one call.
-    Returns (dx, dgamma, dbeta, q8, qp8, q16, qp16)."""
+    Returns (dx or None, dgamma, dbeta, q8, qp8, q16, qp16)."""
     _dev(x), _dev(dy), _dev(stats)
     N, Cc, H, W = x.shape
     dev = x.device
-    dx = dx_out if dx_out is not None else torch.empty_like(x)
+    dx = dx_out if dx_out is not None else (torch.empty_like(x) if want_dx else None)
     dgamma = torch.empty(Cc, dtype=torch.float32, device=dev)
     dbeta = torch.empty(Cc, dtype=torch.float32, device=dev)
     q8 = q8_out if q8_out is not None else torch.empty(x.shape, dtype=torch.int8, device=dev)

@@ -52,7 +52,3 @@ size_t q8t_gemm_wgrad_ws(const q8t_conv_desc *d);
 int q8t_gemm_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams *qg, const int8_t *x,
                    const q8t_qparams *qx, float *dw, int64_t *acc_out, void *ws, hipStream_t st);
 
-// bifurcated quantization from ready-made (min,max) pairs (quantize.hip)
-int q8t_bifurcate_from_partials(const float *g, int64_t n, const void *partials, int np, uint64_t seed8,
-                                uint64_t seed16, int8_t *q8_out, q8t_qparams *qp8_out, int16_t *q16_out,
-                                q8t_qparams *qp16_out, hipStream_t st);

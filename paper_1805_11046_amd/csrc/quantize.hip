@@ -86,67 +86,6 @@ __global__ __launch_bounds__(kThreads) void minmax_partials(const float *__restr
     if (threadIdx.x == 0) partials[blockIdx.x] = make_float2(mn, mx);
 }
 
-// ---- counter-based generator: 3 hashes serve the 4 elements of one group ----------------------
-__device__ __forceinline__ uint32_t mix32(uint32_t x)
-{
-    x ^= x >> 16;
-    x *= 0x6A09E667u;
-    x ^= x >> 15;
-    x *= 0xBB67AE85u;
-    x ^= x >> 16;
-    return x;
-}
-__device__ __forceinline__ void rng_group(uint32_t group, uint32_t seed_lo, uint32_t seed_hi,
-                                          uint32_t &w0, uint32_t &w1)
-{
-    const uint32_t phi = 0x9E3779B9u;
-    const uint32_t h = mix32(group * phi + seed_lo) ^ seed_hi;
-    w0 = mix32(h + phi);
-    w1 = mix32(h + 2u * phi);
-}
-__device__ __forceinline__ uint32_t rng_r16(int64_t i, uint32_t seed_lo, uint32_t seed_hi)
-{
-    uint32_t w0, w1;
-    rng_group((uint32_t)(i >> 2), seed_lo, seed_hi, w0, w1);
-    const uint32_t w = (i & 2) ? w1 : w0;
-    return (w >> (16 * (uint32_t)(i & 1))) & 0xFFFFu;
-}
-
-template <typename OUT>
-struct Pack4;
-template <>
-struct Pack4<int8_t> {
-    typedef uint32_t type;
-    static __device__ __forceinline__ uint32_t pack(int a, int b, int c, int d)
-    {
-        return (uint32_t)(a & 255) | ((uint32_t)(b & 255) << 8) | ((uint32_t)(c & 255) << 16) |
-               ((uint32_t)(d & 255) << 24);
-    }
-};
-template <>
-struct Pack4<int16_t> {
-    typedef uint2 type;
-    static __device__ __forceinline__ uint2 pack(int a, int b, int c, int d)
-    {
-        return make_uint2((uint32_t)(a & 65535) | ((uint32_t)(b & 65535) << 16),
-                          (uint32_t)(c & 65535) | ((uint32_t)(d & 65535) << 16));
-    }
-};
-
-template <typename OUT, bool STOCH>
-__device__ __forceinline__ typename Pack4<OUT>::type quant4(const float4 v, const Affine &a,
-                                                           uint32_t group, uint32_t seed_lo,
-                                                           uint32_t seed_hi)
-{
-    uint32_t w0 = 0, w1 = 0;
-    if (STOCH) rng_group(group, seed_lo, seed_hi, w0, w1);
-    const int q0 = level_of<STOCH>(v.x, a, w0 & 0xFFFFu) - a.half;
-    const int q1 = level_of<STOCH>(v.y, a, w0 >> 16) - a.half;
-    const int q2 = level_of<STOCH>(v.z, a, w1 & 0xFFFFu) - a.half;
-    const int q3 = level_of<STOCH>(v.w, a, w1 >> 16) - a.half;
-    return Pack4<OUT>::pack(q0, q1, q2, q3);
-}
-
 // every workgroup folds the partial pairs in the same order -> identical range everywhere
 __device__ __forceinline__ void fold_partials(const float2 *__restrict__ partials, int npartials,
                                               float *smem, float &vmin, float &vmax)
@@ -482,26 +421,6 @@ int q8t_quantize_bifurcate(const float *g, int64_t n, uint64_t seed8, uint64_t s
 }
 
 }  // extern "C"
-
-// internal: bifurcated quantization when (min,max) pairs of g already exist (produced by the
-// kernel that wrote g).  `partials` holds np <= 2048 float2 pairs.
-int q8t_bifurcate_from_partials(const float *g, int64_t n, const void *partials, int np, uint64_t seed8,
-                                uint64_t seed16, int8_t *q8_out, q8t_qparams *qp8_out, int16_t *q16_out,
-                                q8t_qparams *qp16_out, hipStream_t st)
-{
-    const bool vec = q8t_aligned(g, 16) && q8t_aligned(q8_out, 4) && q8t_aligned(q16_out, 8);
-    const int grid = grid_for(vec ? (n >> 2) : n, 2, 2048);
-    if (vec)
-        hipLaunchKernelGGL(quantize_bifurcate_apply<true>, dim3(grid), dim3(kThreads), 0, st, g, n,
-                           (uint32_t)seed8, (uint32_t)(seed8 >> 32), (uint32_t)seed16,
-                           (uint32_t)(seed16 >> 32), (const float2 *)partials, np, q8_out, qp8_out, q16_out, qp16_out);
-    else
-        hipLaunchKernelGGL(quantize_bifurcate_apply<false>, dim3(grid), dim3(kThreads), 0, st, g, n,
-                           (uint32_t)seed8, (uint32_t)(seed8 >> 32), (uint32_t)seed16,
-                           (uint32_t)(seed16 >> 32), (const float2 *)partials, np, q8_out, qp8_out, q16_out, qp16_out);
-    Q8T_LAUNCH_CHECK();
-    return Q8T_OK;
-}
 
 extern "C" {
 

@@ -408,11 +408,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply(const float *__restrict
                                                          const double2 *__restrict__ parts, int split, double n,
                                                          float *__restrict__ dgamma, float *__restrict__ dbeta,
                                                          float cn, float eps, float *__restrict__ dx,
-                                                         float2 *__restrict__ mm_out,
                                                          const float *__restrict__ beta, int relu)
 {
-    __shared__ float smf[kThreads / 64];
-    float dmn = INFINITY, dmx = -INFINITY;   // range of the dx values this workgroup writes (if asked for)
     for (int64_t pl = blockIdx.x; pl < planes; pl += gridDim.x) {
         const int c = (int)(pl % C);
         const float mn = stats[C + c], mx = stats[2 * C + c];
@@ -461,10 +458,6 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply(const float *__restrict
                 r.z = bn_dx(v.z, d.z, g, k.x, inv, k.y, mn, mx);
                 r.w = bn_dx(v.w, d.w, g, k.x, inv, k.y, mn, mx);
                 o[i] = r;
-                if (mm_out) {
-                    dmn = fminf(fminf(dmn, r.x), fminf(r.y, fminf(r.z, r.w)));
-                    dmx = fmaxf(fmaxf(dmx, r.x), fmaxf(r.y, fmaxf(r.z, r.w)));
-                }
             }
         } else {
             for (int i = threadIdx.x; i < HW; i += kThreads) {
@@ -472,15 +465,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply(const float *__restrict
                 const float d = relu && !(bn_map(xv, mu, inv, g, be) > 0.0f) ? 0.0f : dy[base + i];
                 const float r = bn_dx(xv, d, g, k.x, inv, k.y, mn, mx);
                 dx[base + i] = r;
-                dmn = fminf(dmn, r);
-                dmx = fmaxf(dmx, r);
             }
         }
-    }
-    if (mm_out) {
-        dmn = block_min_f(dmn, smf);
-        dmx = block_max_f(dmx, smf);
-        if (threadIdx.x == 0) mm_out[blockIdx.x] = make_float2(dmn, dmx);
     }
 }
 
@@ -501,6 +487,236 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply_flat(const float *__res
         const float g = gamma ? gamma[c] : 1.0f, inv = bn_inv(mn, mx, cn, eps);
         const float d = relu && !(bn_map(x[i], stats[c], inv, g, beta ? beta[c] : 0.0f) > 0.0f) ? 0.0f : dy[i];
         dx[i] = bn_dx(x[i], d, g, k.x, inv, k.y, mn, mx);
+    }
+}
+
+// ---- backward with its 8-bit / 16-bit copies, two passes -------------------------------------------
+// dx is an affine, monotone function of dy inside a channel (v = inv*(gamma*dy - mean_g); every fp32
+// step is monotone), except at the coordinates that attain the channel's max / min, which get -/+ kb.
+// So the range of dx follows from the extremes of dy per channel, kept apart for the four kinds of
+// coordinate (ordinary, at the max, at the min, at both), and pass 1 can collect those beside its
+// sums: no pass over dx is needed to find the quantizer's range, and dx itself need not be written
+// at all.  8 + 8 + 3 bytes per element (+4 with dx) instead of 27.
+struct BwdPartialQ {
+    double s0, s1;
+    float lo[4], hi[4];   // extremes of (masked) dy: ordinary, at max, at min, at both
+};
+
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void bn_bwdq_partial(const float *__restrict__ x, const float *__restrict__ dy,
+                                                            const float *__restrict__ stats, int N, int C, int HW, int NB,
+                                                            float cn, float eps, const float *__restrict__ gamma,
+                                                            const float *__restrict__ beta, int relu,
+                                                            BwdPartialQ *__restrict__ parts)
+{
+    __shared__ double smd[kThreads / 64];
+    __shared__ float smf[kThreads / 64];
+    const int c = blockIdx.x, sp = blockIdx.y;
+    const int b0 = sp * NB, b1 = min(N, b0 + NB);
+    const float mu = stats[c], mn = stats[C + c], mx = stats[2 * C + c];
+    const float inv = bn_inv(mn, mx, cn, eps);
+    const float ga = gamma ? gamma[c] : 1.0f, be = beta ? beta[c] : 0.0f;
+    double s0 = 0.0, s1 = 0.0;
+    float lo[4] = {INFINITY, INFINITY, INFINITY, INFINITY}, hi[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    auto one = [&](float xv, float d) {
+        if (relu) d = bn_map(xv, mu, inv, ga, be) > 0.0f ? d : 0.0f;
+        const float h = (xv - mu) * inv;
+        s0 += (double)d;
+        s1 += (double)d * (double)h;
+        if (xv == mx || xv == mn) {   // a few coordinates per channel
+            const int k = (xv == mx ? 1 : 0) + (xv == mn ? 2 : 0);
+#pragma unroll
+            for (int q = 1; q < 4; ++q)
+                if (k == q) {
+                    lo[q] = fminf(lo[q], d);
+                    hi[q] = fmaxf(hi[q], d);
+                }
+        } else {
+            lo[0] = fminf(lo[0], d);
+            hi[0] = fmaxf(hi[0], d);
+        }
+    };
+    if (VEC) {
+        const int hw4 = HW >> 2;
+        for (int b = b0; b < b1; ++b) {
+            const int64_t base = ((int64_t)b * C + c) * HW;
+            const float4 *px = reinterpret_cast<const float4 *>(x + base);
+            const float4 *pg = reinterpret_cast<const float4 *>(dy + base);
+#pragma unroll 2
+            for (int i = threadIdx.x; i < hw4; i += kThreads) {
+                const float4 v = px[i], g = pg[i];
+                one(v.x, g.x);
+                one(v.y, g.y);
+                one(v.z, g.z);
+                one(v.w, g.w);
+            }
+        }
+    } else {
+        const int cnt = (b1 - b0) * HW;
+        for (int idx = threadIdx.x; idx < cnt; idx += kThreads) {
+            const int b = b0 + idx / HW, i = idx % HW;
+            const int64_t j = ((int64_t)b * C + c) * HW + i;
+            one(x[j], dy[j]);
+        }
+    }
+    BwdPartialQ r;
+    r.s0 = block_sum_d(s0, smd);
+    r.s1 = block_sum_d(s1, smd);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        r.lo[q] = block_min_f(lo[q], smf);
+        r.hi[q] = block_max_f(hi[q], smf);
+    }
+    if (threadIdx.x == 0) parts[(int64_t)c * gridDim.y + sp] = r;
+}
+
+// dx of one coordinate of kind k (bit 0: at the max, bit 1: at the min), same operations as bn_dx
+__device__ __forceinline__ float bn_dx_kind(float dyv, float g, float mean_g, float inv, float kb, int k)
+{
+    const float gh = g * dyv;
+    const float t = gh - mean_g;
+    float v = inv * t;
+    if (k & 1) v = v - kb;
+    if (k & 2) v = v + kb;
+    return v;
+}
+
+// per-channel sums -> dgamma, dbeta, constants, and the range of dx over the workgroup's channels
+// (one channel per wavefront; pass 2 folds the workgroups' ranges).  A wavefront folds the slices of
+// a channel in the butterfly order of bn_bwd_apply (lane k holds slice k), so the constants are
+// bit-identical to that path.
+__global__ __launch_bounds__(kThreads) void bn_bwdq_finalize(const BwdPartialQ *__restrict__ parts, int C, int split, double n,
+                                                             float cn, float eps, const float *__restrict__ stats,
+                                                             const float *__restrict__ gamma, float *__restrict__ dgamma,
+                                                             float *__restrict__ dbeta, float2 *__restrict__ consts,
+                                                             float2 *__restrict__ mm)
+{
+    __shared__ float smf[kThreads / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float dmn = INFINITY, dmx = -INFINITY;
+    const int c = blockIdx.x * (kThreads / 64) + wave;
+    if (c < C) {
+        double s0 = 0.0, s1 = 0.0;
+        float lo[4] = {INFINITY, INFINITY, INFINITY, INFINITY}, hi[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        if (lane < split) {
+            const BwdPartialQ p = parts[(int64_t)c * split + lane];
+            s0 = p.s0;
+            s1 = p.s1;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                lo[q] = p.lo[q];
+                hi[q] = p.hi[q];
+            }
+        }
+        s0 = wave_reduce(s0, OpAddD());
+        s1 = wave_reduce(s1, OpAddD());
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            lo[q] = wave_reduce(lo[q], OpMin());
+            hi[q] = wave_reduce(hi[q], OpMax());
+        }
+        const float g = gamma ? gamma[c] : 1.0f;
+        const float inv = bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
+        const double A = (double)g * s0, B = (double)g * s1;
+        const float mean_g = (float)(A / n);
+        const float kb = (float)((double)inv * (double)cn * B);
+        if (lane == 0) {
+            if (dbeta) dbeta[c] = (float)s0;
+            if (dgamma) dgamma[c] = (float)s1;
+            consts[c] = make_float2(mean_g, kb);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (lo[q] > hi[q]) continue;   // no coordinate of this kind
+            const float a = bn_dx_kind(lo[q], g, mean_g, inv, kb, q), b = bn_dx_kind(hi[q], g, mean_g, inv, kb, q);
+            dmn = fminf(dmn, fminf(a, b));
+            dmx = fmaxf(dmx, fmaxf(a, b));
+        }
+    }
+    dmn = block_min_f(dmn, smf);
+    dmx = block_max_f(dmx, smf);
+    if (threadIdx.x == 0) mm[blockIdx.x] = make_float2(dmn, dmx);
+}
+
+// pass 2: dx (optional) and its two stochastic copies
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restrict__ x, const float *__restrict__ dy,
+                                                          int64_t planes, int C, int HW, const float *__restrict__ stats,
+                                                          const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                          int relu, const float2 *__restrict__ consts, float cn, float eps,
+                                                          uint32_t s8_lo, uint32_t s8_hi, uint32_t s16_lo, uint32_t s16_hi,
+                                                          const float2 *__restrict__ mm, int nmm,
+                                                          q8t_qparams *__restrict__ qp8_out,
+                                                          q8t_qparams *__restrict__ qp16_out, float *__restrict__ dx,
+                                                          int8_t *__restrict__ q8, int16_t *__restrict__ q16)
+{
+    // every workgroup folds the ranges of pass 1 (min / max: any order gives the same bits)
+    __shared__ float smf[kThreads / 64];
+    float vmin = INFINITY, vmax = -INFINITY;
+    for (int i = threadIdx.x; i < nmm; i += kThreads) {
+        const float2 p = mm[i];
+        vmin = fminf(vmin, p.x);
+        vmax = fmaxf(vmax, p.y);
+    }
+    vmin = block_min_f(vmin, smf);
+    vmax = block_max_f(vmax, smf);
+    const q8t_qparams qp8 = make_qparams(vmin, vmax, 8), qp16 = make_qparams(vmin, vmax, 16);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *qp8_out = qp8;
+        *qp16_out = qp16;
+    }
+    const Affine a8 = affine_of(qp8), a16 = affine_of(qp16);
+    if (VEC) {
+        for (int64_t pl = blockIdx.x; pl < planes; pl += gridDim.x) {
+            const int c = (int)(pl % C);
+            const float mu = stats[c], mn = stats[C + c], mx = stats[2 * C + c];
+            const float inv = bn_inv(mn, mx, cn, eps);
+            const float g = gamma ? gamma[c] : 1.0f, be = beta ? beta[c] : 0.0f;
+            const float2 k = consts[c];
+            const int64_t base = pl * HW;
+            const float4 *px = reinterpret_cast<const float4 *>(x + base);
+            const float4 *pg = reinterpret_cast<const float4 *>(dy + base);
+            float4 *o = reinterpret_cast<float4 *>(dx + base);
+            uint32_t *o8 = reinterpret_cast<uint32_t *>(q8 + base);
+            uint2 *o16 = reinterpret_cast<uint2 *>(q16 + base);
+            const int64_t g0 = base >> 2;   // generator group of the plane's first element
+            const int hw4 = HW >> 2;
+#pragma unroll 2
+            for (int i = threadIdx.x; i < hw4; i += kThreads) {
+                const float4 v = px[i];
+                float4 d = pg[i];
+                if (relu) {
+                    d.x = bn_map(v.x, mu, inv, g, be) > 0.0f ? d.x : 0.0f;
+                    d.y = bn_map(v.y, mu, inv, g, be) > 0.0f ? d.y : 0.0f;
+                    d.z = bn_map(v.z, mu, inv, g, be) > 0.0f ? d.z : 0.0f;
+                    d.w = bn_map(v.w, mu, inv, g, be) > 0.0f ? d.w : 0.0f;
+                }
+                float4 r;
+                r.x = bn_dx(v.x, d.x, g, k.x, inv, k.y, mn, mx);
+                r.y = bn_dx(v.y, d.y, g, k.x, inv, k.y, mn, mx);
+                r.z = bn_dx(v.z, d.z, g, k.x, inv, k.y, mn, mx);
+                r.w = bn_dx(v.w, d.w, g, k.x, inv, k.y, mn, mx);
+                if (dx) o[i] = r;
+                const uint32_t grp = (uint32_t)(g0 + i);
+                o8[i] = quant4<int8_t, true>(r, a8, grp, s8_lo, s8_hi);
+                o16[i] = quant4<int16_t, true>(r, a16, grp, s16_lo, s16_hi);
+            }
+        }
+    } else {
+        const int64_t total = planes * HW, stride = (int64_t)gridDim.x * kThreads;
+        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+            const int c = (int)((i / HW) % C);
+            const float mn = stats[C + c], mx = stats[2 * C + c];
+            const float inv = bn_inv(mn, mx, cn, eps);
+            const float g = gamma ? gamma[c] : 1.0f;
+            const float2 k = consts[c];
+            const float xv = x[i];
+            const float d = relu && !(bn_map(xv, stats[c], inv, g, beta ? beta[c] : 0.0f) > 0.0f) ? 0.0f : dy[i];
+            const float r = bn_dx(xv, d, g, k.x, inv, k.y, mn, mx);
+            if (dx) dx[i] = r;
+            q8[i] = (int8_t)(level_of<true>(r, a8, rng_r16(i, s8_lo, s8_hi)) - a8.half);
+            q16[i] = (int16_t)(level_of<true>(r, a16, rng_r16(i, s16_lo, s16_hi)) - a16.half);
+        }
     }
 }
 
@@ -648,8 +864,10 @@ int q8t_range_bn_relu_fwd_apply(const float *x, int N, int C, int H, int W, cons
 
 static int range_bn_bwd_impl(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
                              const float *gamma, float eps, float *dx, float *dgamma, float *dbeta, void *ws,
-                             void *stream, float2 *mm_out, int *mm_count, const float *beta = nullptr, int relu = 0)
+                             void *stream)
 {
+    const float *beta = nullptr;
+    const int relu = 0;
     const int rc = check_shape(N, C, H, W);
     if (rc) return rc;
     if (!x || !dy || !stats) return Q8T_ERR_NULL;
@@ -669,7 +887,6 @@ static int range_bn_bwd_impl(const float *x, const float *dy, const float *stats
         hipLaunchKernelGGL(bn_bwd_partial<false>, dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn, eps, gamma, beta, relu, parts);
     Q8T_LAUNCH_CHECK();
     const bool fused = dx && HW >= 256;
-    if (mm_out && !fused) return Q8T_ERR_SHAPE;   // the fused range output exists for the plane kernel only
     if (!fused) {
         hipLaunchKernelGGL(bn_bwd_finalize, dim3((C + kThreads - 1) / kThreads), dim3(kThreads), 0, st, parts, C,
                            nsplit, n, cn, eps, stats, gamma, dgamma, dbeta, consts);
@@ -678,13 +895,11 @@ static int range_bn_bwd_impl(const float *x, const float *dy, const float *stats
     if (!dx) return Q8T_OK;
     const int64_t planes = (int64_t)N * C;
     if (HW >= 256) {
-        // with a range output, one (min,max) pair per workgroup: keep the grid at 2048 workgroups
-        const dim3 grid(mm_out ? (unsigned)(planes < 2048 ? planes : 2048) : (unsigned)planes_grid(planes));
-        if (mm_count) *mm_count = (int)grid.x;
+        const dim3 grid((unsigned)planes_grid(planes));
         if (vec)
-            hipLaunchKernelGGL(bn_bwd_apply<true>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx, mm_out, beta, relu);
+            hipLaunchKernelGGL(bn_bwd_apply<true>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx, beta, relu);
         else
-            hipLaunchKernelGGL(bn_bwd_apply<false>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx, mm_out, beta, relu);
+            hipLaunchKernelGGL(bn_bwd_apply<false>, grid, dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, consts, parts, nsplit, n, dgamma, dbeta, cn, eps, dx, beta, relu);
     } else {
         const int64_t total = planes * HW;
         const dim3 grid((unsigned)((total + kThreads - 1) / kThreads < 65536 * 16 ? (total + kThreads - 1) / kThreads : 65536 * 16));
@@ -698,12 +913,14 @@ int q8t_range_bn_bwd(const float *x, const float *dy, const float *stats, int N,
                      const float *gamma, float eps, float *dx, float *dgamma, float *dbeta, void *ws,
                      void *stream)
 {
-    return range_bn_bwd_impl(x, dy, stats, N, C, H, W, gamma, eps, dx, dgamma, dbeta, ws, stream, nullptr, nullptr);
+    return range_bn_bwd_impl(x, dy, stats, N, C, H, W, gamma, eps, dx, dgamma, dbeta, ws, stream);
 }
 
 size_t q8t_range_bn_bwd_bifurcate_workspace_size(int N, int C, int H, int W)
 {
-    return q8t_range_bn_workspace_size(N, C, H, W) + 256 + 2048 * sizeof(float2);
+    (void)N; (void)H; (void)W;
+    if (C <= 0) return 0;
+    return (size_t)C * kMaxSplit * sizeof(BwdPartialQ) + (size_t)C * sizeof(float2) + (size_t)((C + 3) / 4) * sizeof(float2);
 }
 
 static int range_bn_bwd_bifurcate_impl(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
@@ -712,23 +929,46 @@ static int range_bn_bwd_bifurcate_impl(const float *x, const float *dy, const fl
                                        q8t_qparams *qp8_out, int16_t *q16_out, q8t_qparams *qp16_out, void *ws,
                                        void *stream)
 {
-    if (!dx || !q8_out || !qp8_out || !q16_out || !qp16_out) return Q8T_ERR_NULL;
-    if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
-    const size_t off = (q8t_range_bn_workspace_size(N, C, H, W) + 255) & ~(size_t)255;
-    float2 *mm = (float2 *)((char *)ws + off);
-    if ((int64_t)H * W < 256) {
-        // planes this small take the flat backward kernel, which keeps no ranges: plain sequence
-        const int rc = range_bn_bwd_impl(x, dy, stats, N, C, H, W, gamma, eps, dx, dgamma, dbeta, ws, stream, nullptr, nullptr,
-                                         beta, relu);
-        if (rc) return rc;
-        return q8t_quantize_bifurcate(dx, (int64_t)N * C * H * W, seed8, seed16, q8_out, qp8_out, q16_out, qp16_out, mm,
-                                      stream);
-    }
-    int np = 0;
-    const int rc = range_bn_bwd_impl(x, dy, stats, N, C, H, W, gamma, eps, dx, dgamma, dbeta, ws, stream, mm, &np, beta, relu);
+    const int rc = check_shape(N, C, H, W);
     if (rc) return rc;
-    return q8t_bifurcate_from_partials(dx, (int64_t)N * C * H * W, mm, np, seed8, seed16, q8_out, qp8_out, q16_out,
-                                       qp16_out, (hipStream_t)stream);
+    if (!x || !dy || !stats || !q8_out || !qp8_out || !q16_out || !qp16_out) return Q8T_ERR_NULL;
+    if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const int HW = H * W;
+    const double n = (double)N * HW;
+    const float cn = (float)q8t_range_bn_scale((int64_t)N * HW);
+    BwdPartialQ *parts = (BwdPartialQ *)ws;
+    float2 *consts = (float2 *)((char *)ws + (size_t)C * kMaxSplit * sizeof(BwdPartialQ));
+    const int split = split_for(N, C), NB = (N + split - 1) / split;
+    const int nsplit = (N + NB - 1) / NB;
+    const bool vec = (HW % 4 == 0) && q8t_aligned(x, 16) && q8t_aligned(dy, 16) && (!dx || q8t_aligned(dx, 16)) &&
+                     q8t_aligned(q8_out, 4) && q8t_aligned(q16_out, 8);
+    if (vec)
+        hipLaunchKernelGGL(bn_bwdq_partial<true>, dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn, eps,
+                           gamma, beta, relu, parts);
+    else
+        hipLaunchKernelGGL(bn_bwdq_partial<false>, dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn, eps,
+                           gamma, beta, relu, parts);
+    Q8T_LAUNCH_CHECK();
+    float2 *mm = consts + C;
+    const int nmm = (C + kThreads / 64 - 1) / (kThreads / 64);
+    hipLaunchKernelGGL(bn_bwdq_finalize, dim3(nmm), dim3(kThreads), 0, st, parts, C, nsplit, n, cn, eps, stats, gamma, dgamma,
+                       dbeta, consts, mm);
+    Q8T_LAUNCH_CHECK();
+    const int64_t planes = (int64_t)N * C;
+    const uint32_t s8l = (uint32_t)seed8, s8h = (uint32_t)(seed8 >> 32), s16l = (uint32_t)seed16, s16h = (uint32_t)(seed16 >> 32);
+    if (vec && HW >= 256) {
+        hipLaunchKernelGGL(bn_bwdq_apply<true>, dim3(planes_grid(planes)), dim3(kThreads), 0, st, x, dy, planes, C, HW, stats,
+                           gamma, beta, relu, consts, cn, eps, s8l, s8h, s16l, s16h, mm, nmm, qp8_out, qp16_out, dx, q8_out, q16_out);
+    } else {
+        const int64_t total = planes * HW;
+        const int64_t blocks = (total + kThreads - 1) / kThreads;
+        hipLaunchKernelGGL(bn_bwdq_apply<false>, dim3((unsigned)(blocks < 65536 * 16 ? blocks : 65536 * 16)), dim3(kThreads), 0,
+                           st, x, dy, planes, C, HW, stats, gamma, beta, relu, consts, cn, eps, s8l, s8h, s16l, s16h, mm, nmm,
+                           qp8_out, qp16_out, dx, q8_out, q16_out);
+    }
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
 }
 
 int q8t_range_bn_bwd_bifurcate(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,

@@ -79,8 +79,8 @@ class ConvBN(torch.autograd.Function):
     def backward(ctx, dbn):
         d, qa, pa, qw, pw, y, stats, need_dx, ops, nx, ny = ctx.saved
         _seed[0] += 2
-        _, _, _, g8, pg8, g16, pg16 = _call("range_bn_bwd_bifurcate", 0, 27 * ny, q8t.range_bn_bwd_bifurcate, y,
-                                            dbn.contiguous(), stats, None, 1e-5, _seed[0], _seed[0] + 1)
+        _, _, _, g8, pg8, g16, pg16 = _call("range_bn_bwd_bifurcate", 0, 19 * ny, q8t.range_bn_bwd_bifurcate, y,
+                                            dbn.contiguous(), stats, None, 1e-5, _seed[0], _seed[0] + 1, want_dx=False)
         dx = None
         if need_dx:
             dx, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw)
@@ -127,11 +127,11 @@ class ConvChain(torch.autograd.Function):
             d, qa, pa, qw, pw, y, stats, ops, nx, ny = saved[i]
             _seed[0] += 2
             if i + 1 == len(saved):
-                r = _call("range_bn_bwd_bifurcate", 0, 27 * ny, q8t.range_bn_bwd_bifurcate, y, g, stats, None, 1e-5,
-                          _seed[0], _seed[0] + 1)
+                r = _call("range_bn_bwd_bifurcate", 0, 19 * ny, q8t.range_bn_bwd_bifurcate, y, g, stats, None, 1e-5,
+                          _seed[0], _seed[0] + 1, want_dx=False)
             else:
-                r = _call("range_bn_relu_bwd_bifurcate", 0, 27 * ny, q8t.range_bn_relu_bwd_bifurcate, y, g, stats, None,
-                          None, 1e-5, _seed[0], _seed[0] + 1)
+                r = _call("range_bn_relu_bwd_bifurcate", 0, 19 * ny, q8t.range_bn_relu_bwd_bifurcate, y, g, stats, None,
+                          None, 1e-5, _seed[0], _seed[0] + 1, want_dx=False)
             g8, pg8, g16, pg16 = r[3:]
             g = None
             if i > 0 or need_dx:

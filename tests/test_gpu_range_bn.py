@@ -150,3 +150,48 @@ def test_backward_fused_with_bifurcated_quantization(shape):
     same_qparams(q8t, qp16, o16)
     same_ints(host(q8), s8)
     same_ints(host(q16), s16)
+
+
+@pytest.mark.parametrize("shape", [(6, 7, 16, 16), (5, 9, 7, 7), (16, 64, 56, 56)])
+def test_fused_backward_without_the_fp32_result(shape):
+    # the codes do not depend on whether dx itself is written
+    q8t = require_gpu()
+    x, dy, gamma, _ = _inputs(shape, 6)
+    stats = oracle.range_bn_stats(x)
+    xd, dyd, sd, gd = dev(x), dev(dy), dev(stats), dev(gamma)
+    dx, dg, db, q8, qp8, q16, qp16 = q8t.range_bn_bwd_bifurcate(xd, dyd, sd, gd, 1e-5, seed8=7, seed16=8)
+    nx, ng, nb, r8, rp8, r16, rp16 = q8t.range_bn_bwd_bifurcate(xd, dyd, sd, gd, 1e-5, seed8=7, seed16=8, want_dx=False)
+    assert nx is None
+    assert np.array_equal(host(dg), host(ng)) and np.array_equal(host(db), host(nb))
+    assert q8t.qparams_to_host(qp8) == q8t.qparams_to_host(rp8) and q8t.qparams_to_host(qp16) == q8t.qparams_to_host(rp16)
+    same_ints(host(q8), host(r8))
+    same_ints(host(q16), host(r16))
+
+
+def test_fused_backward_range_with_ties_and_a_constant_channel():
+    # the quantizer's range comes from the extremes of dy per kind of coordinate (ordinary, at the
+    # channel maximum, at the minimum, at both): several maxima, several minima, a constant channel
+    # (every coordinate is both) and a channel whose extreme dx sits on an extremal coordinate
+    q8t = require_gpu()
+    g = synth.rng(21)
+    N, C, H, W = 4, 5, 16, 16
+    x = g.standard_normal((N, C, H, W)).astype(np.float32)
+    x[:, 0].flat[[3, 77, 500]] = 9.0          # three maxima
+    x[:, 1].flat[[5, 6, 900]] = -9.0          # three minima
+    x[:, 2] = 1.25                            # constant: max == min everywhere
+    dy = (g.standard_normal((N, C, H, W)) * 1e-2).astype(np.float32)
+    dy[:, 3] *= 1e-3                          # tiny gradients: the +-kb terms dominate the channel's range
+    dy[0, 0].flat[3] = 5.0                    # the largest gradient sits on a maximum
+    gamma = np.array([1.5, -0.7, 1.0, 2.0, -1.0], np.float32)
+    eps = 1e-5
+    stats = oracle.range_bn_stats(x)
+    dx, dg, db, q8, qp8, q16, qp16 = q8t.range_bn_bwd_bifurcate(dev(x), dev(dy), dev(stats), dev(gamma), eps, seed8=3, seed16=4)
+    dxh = host(dx)
+    odx, _, _ = oracle.range_bn_bwd(x, dy, stats, gamma, eps)
+    close(dxh, odx)
+    s8, _, o8 = oracle.quantize(dxh, 8, True, seed=3)
+    s16, _, o16 = oracle.quantize(dxh, 16, True, seed=4)
+    same_qparams(q8t, qp8, o8)
+    same_qparams(q8t, qp16, o16)
+    same_ints(host(q8), s8)
+    same_ints(host(q16), s16)
