@@ -214,10 +214,41 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_apply(const float *__restrict
                                                          const float *__restrict__ beta, float cn,
                                                          float eps, float *__restrict__ y,
                                                          int8_t *__restrict__ q,
-                                                         const q8t_qparams *__restrict__ qp, int relu)
+                                                         const q8t_qparams *__restrict__ qp, int relu, int flat4)
 {
     Affine a;
     if (QOUT) a = affine_of(*qp);
+    if (VEC && flat4) {
+        // small planes, statistics given: one float4 per thread over the flat tensor
+        const int hw4 = HW >> 2;
+        const int64_t total4 = planes * hw4, stride = (int64_t)gridDim.x * kThreads;
+        for (int64_t i4 = (int64_t)blockIdx.x * kThreads + threadIdx.x; i4 < total4; i4 += stride) {
+            const int c = (int)((i4 / hw4) % C);
+            const float mu = stats[c];
+            const float inv = bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
+            const float g = gamma ? gamma[c] : 1.0f, b = beta ? beta[c] : 0.0f;
+            const float4 v = reinterpret_cast<const float4 *>(x)[i4];
+            float4 r;
+            r.x = bn_map(v.x, mu, inv, g, b);
+            r.y = bn_map(v.y, mu, inv, g, b);
+            r.z = bn_map(v.z, mu, inv, g, b);
+            r.w = bn_map(v.w, mu, inv, g, b);
+            if (relu) {
+                r.x = r.x > 0.0f ? r.x : 0.0f;
+                r.y = r.y > 0.0f ? r.y : 0.0f;
+                r.z = r.z > 0.0f ? r.z : 0.0f;
+                r.w = r.w > 0.0f ? r.w : 0.0f;
+            }
+            if (y) reinterpret_cast<float4 *>(y)[i4] = r;
+            if (QOUT) {
+                const int q0 = level_of<false>(r.x, a, 0) - 128, q1 = level_of<false>(r.y, a, 0) - 128,
+                          q2 = level_of<false>(r.z, a, 0) - 128, q3 = level_of<false>(r.w, a, 0) - 128;
+                reinterpret_cast<uint32_t *>(q)[i4] = (uint32_t)(q0 & 255) | ((uint32_t)(q1 & 255) << 8) |
+                                                      ((uint32_t)(q2 & 255) << 16) | ((uint32_t)(q3 & 255) << 24);
+            }
+        }
+        return;
+    }
     for (int64_t pl = blockIdx.x; pl < planes; pl += gridDim.x) {
         const int c = (int)(pl % C);
         float mu, cmn, cmx;
@@ -538,13 +569,29 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_partial(const float *__restr
     };
     if (VEC) {
         const int hw4 = HW >> 2;
-        for (int b = b0; b < b1; ++b) {
-            const int64_t base = ((int64_t)b * C + c) * HW;
-            const float4 *px = reinterpret_cast<const float4 *>(x + base);
-            const float4 *pg = reinterpret_cast<const float4 *>(dy + base);
+        if (hw4 >= kThreads) {
+            for (int b = b0; b < b1; ++b) {
+                const int64_t base = ((int64_t)b * C + c) * HW;
+                const float4 *px = reinterpret_cast<const float4 *>(x + base);
+                const float4 *pg = reinterpret_cast<const float4 *>(dy + base);
 #pragma unroll 2
-            for (int i = threadIdx.x; i < hw4; i += kThreads) {
-                const float4 v = px[i], g = pg[i];
+                for (int i = threadIdx.x; i < hw4; i += kThreads) {
+                    const float4 v = px[i], g = pg[i];
+                    one(v.x, g.x);
+                    one(v.y, g.y);
+                    one(v.z, g.z);
+                    one(v.w, g.w);
+                }
+            }
+        } else {
+            // planes smaller than a sweep of the workgroup: one loop over (image, float4) keeps the lanes busy
+            const int items = (b1 - b0) * hw4;
+#pragma unroll 2
+            for (int idx = threadIdx.x; idx < items; idx += kThreads) {
+                const int bl = idx / hw4, i = idx - bl * hw4;
+                const int64_t base = ((int64_t)(b0 + bl) * C + c) * HW;
+                const float4 v = reinterpret_cast<const float4 *>(x + base)[i];
+                const float4 g = reinterpret_cast<const float4 *>(dy + base)[i];
                 one(v.x, g.x);
                 one(v.y, g.y);
                 one(v.z, g.z);
@@ -666,7 +713,34 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restric
         *qp16_out = qp16;
     }
     const Affine a8 = affine_of(qp8), a16 = affine_of(qp16);
-    if (VEC) {
+    if (VEC && HW < 4 * kThreads) {
+        // small planes: one float4 per thread over the flat tensor (a float4 never leaves its plane)
+        const int hw4 = HW >> 2;
+        const int64_t total4 = planes * hw4, stride = (int64_t)gridDim.x * kThreads;
+        for (int64_t i4 = (int64_t)blockIdx.x * kThreads + threadIdx.x; i4 < total4; i4 += stride) {
+            const int c = (int)((i4 / hw4) % C);
+            const float mu = stats[c], mn = stats[C + c], mx = stats[2 * C + c];
+            const float inv = bn_inv(mn, mx, cn, eps);
+            const float g = gamma ? gamma[c] : 1.0f, be = beta ? beta[c] : 0.0f;
+            const float2 k = consts[c];
+            const float4 v = reinterpret_cast<const float4 *>(x)[i4];
+            float4 d = reinterpret_cast<const float4 *>(dy)[i4];
+            if (relu) {
+                d.x = bn_map(v.x, mu, inv, g, be) > 0.0f ? d.x : 0.0f;
+                d.y = bn_map(v.y, mu, inv, g, be) > 0.0f ? d.y : 0.0f;
+                d.z = bn_map(v.z, mu, inv, g, be) > 0.0f ? d.z : 0.0f;
+                d.w = bn_map(v.w, mu, inv, g, be) > 0.0f ? d.w : 0.0f;
+            }
+            float4 r;
+            r.x = bn_dx(v.x, d.x, g, k.x, inv, k.y, mn, mx);
+            r.y = bn_dx(v.y, d.y, g, k.x, inv, k.y, mn, mx);
+            r.z = bn_dx(v.z, d.z, g, k.x, inv, k.y, mn, mx);
+            r.w = bn_dx(v.w, d.w, g, k.x, inv, k.y, mn, mx);
+            if (dx) reinterpret_cast<float4 *>(dx)[i4] = r;
+            reinterpret_cast<uint32_t *>(q8)[i4] = quant4<int8_t, true>(r, a8, (uint32_t)i4, s8_lo, s8_hi);
+            reinterpret_cast<uint2 *>(q16)[i4] = quant4<int16_t, true>(r, a16, (uint32_t)i4, s16_lo, s16_hi);
+        }
+    } else if (VEC) {
         for (int64_t pl = blockIdx.x; pl < planes; pl += gridDim.x) {
             const int c = (int)(pl % C);
             const float mu = stats[c], mn = stats[C + c], mx = stats[2 * C + c];
@@ -792,7 +866,7 @@ int q8t_range_bn_fwd(const float *x, int N, int C, int H, int W, const float *ga
     if (HW >= 256) {
         const dim3 grid(planes_grid(planes));
 #define Q8T_GO(V, Q) \
-    hipLaunchKernelGGL((bn_fwd_apply<V, Q>), grid, dim3(kThreads), 0, st, x, planes, C, HW, stats_out, fparts, nsplit, n, gamma, beta, cn, eps, y, q_out, qp_out, 0)
+    hipLaunchKernelGGL((bn_fwd_apply<V, Q>), grid, dim3(kThreads), 0, st, x, planes, C, HW, stats_out, fparts, nsplit, n, gamma, beta, cn, eps, y, q_out, qp_out, 0, 0)
         if (vec) { if (q_out) Q8T_GO(true, true); else Q8T_GO(true, false); }
         else     { if (q_out) Q8T_GO(false, true); else Q8T_GO(false, false); }
 #undef Q8T_GO
@@ -830,10 +904,12 @@ static int range_bn_fwd_apply_impl(const float *x, int N, int C, int H, int W, c
     float *stats_rw = const_cast<float *>(stats);   // only read when no partial sums are passed
     const FwdPartial *fparts = nullptr;
     const int64_t planes = (int64_t)N * C;
-    if (HW >= 256) {
-        const dim3 grid(planes_grid(planes));
+    const int flat4 = vec && HW < 4 * kThreads;   // planes below 1024 positions: a float4 per thread
+    if (HW >= 256 || flat4) {
+        const int64_t blocks4 = (planes * (HW >> 2) + kThreads - 1) / kThreads;
+        const dim3 grid((unsigned)(flat4 ? (blocks4 < 65536 * 16 ? blocks4 : 65536 * 16) : planes_grid(planes)));
 #define Q8T_GO(V, Q) \
-    hipLaunchKernelGGL((bn_fwd_apply<V, Q>), grid, dim3(kThreads), 0, st, x, planes, C, HW, stats_rw, fparts, 1, n, gamma, beta, cn, eps, y, q_out, qp_out, relu)
+    hipLaunchKernelGGL((bn_fwd_apply<V, Q>), grid, dim3(kThreads), 0, st, x, planes, C, HW, stats_rw, fparts, 1, n, gamma, beta, cn, eps, y, q_out, qp_out, relu, flat4)
         if (vec) { if (q_out) Q8T_GO(true, true); else Q8T_GO(true, false); }
         else     { if (q_out) Q8T_GO(false, true); else Q8T_GO(false, false); }
 #undef Q8T_GO
@@ -957,8 +1033,11 @@ static int range_bn_bwd_bifurcate_impl(const float *x, const float *dy, const fl
     Q8T_LAUNCH_CHECK();
     const int64_t planes = (int64_t)N * C;
     const uint32_t s8l = (uint32_t)seed8, s8h = (uint32_t)(seed8 >> 32), s16l = (uint32_t)seed16, s16h = (uint32_t)(seed16 >> 32);
-    if (vec && HW >= 256) {
-        hipLaunchKernelGGL(bn_bwdq_apply<true>, dim3(planes_grid(planes)), dim3(kThreads), 0, st, x, dy, planes, C, HW, stats,
+    if (vec) {
+        // planes of at least 1024 positions: a workgroup per plane; smaller ones: a float4 per thread
+        const int64_t blocks4 = (planes * (HW >> 2) + kThreads - 1) / kThreads;
+        const int64_t gridx = HW >= 4 * kThreads ? planes_grid(planes) : (blocks4 < 65536 * 16 ? blocks4 : 65536 * 16);
+        hipLaunchKernelGGL(bn_bwdq_apply<true>, dim3((unsigned)gridx), dim3(kThreads), 0, st, x, dy, planes, C, HW, stats,
                            gamma, beta, relu, consts, cn, eps, s8l, s8h, s16l, s16h, mm, nmm, qp8_out, qp16_out, dx, q8_out, q16_out);
     } else {
         const int64_t total = planes * HW;
