@@ -31,6 +31,7 @@ from . import binding as q8t
 
 _breakdown = False
 _fuse = True
+_angles = None   # with --angles: {kind: [cosines]} of tensors against their quantized copies
 
 
 def _call(name, ops, nbytes, fn, *a, **k):
@@ -46,10 +47,28 @@ def _call(name, ops, nbytes, fn, *a, **k):
     return r
 
 
+def _angle(kind, t, q, qp):
+    if _angles is not None:
+        _angles.setdefault(kind, []).append(q8t.quant_angle(t, q, qp)[3])
+
+
 def _quantize(name, t):
     n = t.numel()
     # two passes over the fp32 tensor and one byte written; small tensors stay in registers (one pass)
-    return _call(name, 0, (9 if n > 65536 else 5) * n, q8t.quantize, t, 8)
+    q, qp = _call(name, 0, (9 if n > 65536 else 5) * n, q8t.quantize, t, 8)
+    _angle("weights, 8 bit" if "weights" in name else "activations, 8 bit", t, q, qp)
+    return q, qp
+
+
+def _bn_bwd(fn, name, ny, *args):
+    """Range BN backward + the two gradient copies; with --angles the fp32 gradient is kept for the
+    cosine against its copies."""
+    want = _angles is not None
+    r = _call(name, 0, (23 if want else 19) * ny, fn, *args, want_dx=want)
+    if want:
+        _angle("layer gradients, 8 bit", r[0], r[3], r[4])
+        _angle("layer gradients, 16 bit", r[0], r[5], r[6])
+    return r
 
 
 _pending = []
@@ -79,8 +98,8 @@ class ConvBN(torch.autograd.Function):
     def backward(ctx, dbn):
         d, qa, pa, qw, pw, y, stats, need_dx, ops, nx, ny = ctx.saved
         _seed[0] += 2
-        _, _, _, g8, pg8, g16, pg16 = _call("range_bn_bwd_bifurcate", 0, 19 * ny, q8t.range_bn_bwd_bifurcate, y,
-                                            dbn.contiguous(), stats, None, 1e-5, _seed[0], _seed[0] + 1, want_dx=False)
+        _, _, _, g8, pg8, g16, pg16 = _bn_bwd(q8t.range_bn_bwd_bifurcate, "range_bn_bwd_bifurcate", ny, y, dbn.contiguous(),
+                                              stats, None, 1e-5, _seed[0], _seed[0] + 1)
         dx = None
         if need_dx:
             dx, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw)
@@ -127,11 +146,11 @@ class ConvChain(torch.autograd.Function):
             d, qa, pa, qw, pw, y, stats, ops, nx, ny = saved[i]
             _seed[0] += 2
             if i + 1 == len(saved):
-                r = _call("range_bn_bwd_bifurcate", 0, 19 * ny, q8t.range_bn_bwd_bifurcate, y, g, stats, None, 1e-5,
-                          _seed[0], _seed[0] + 1, want_dx=False)
+                r = _bn_bwd(q8t.range_bn_bwd_bifurcate, "range_bn_bwd_bifurcate", ny, y, g, stats, None, 1e-5, _seed[0],
+                            _seed[0] + 1)
             else:
-                r = _call("range_bn_relu_bwd_bifurcate", 0, 19 * ny, q8t.range_bn_relu_bwd_bifurcate, y, g, stats, None,
-                          None, 1e-5, _seed[0], _seed[0] + 1, want_dx=False)
+                r = _bn_bwd(q8t.range_bn_relu_bwd_bifurcate, "range_bn_relu_bwd_bifurcate", ny, y, g, stats, None, None,
+                            1e-5, _seed[0], _seed[0] + 1)
             g8, pg8, g16, pg16 = r[3:]
             g = None
             if i > 0 or need_dx:
@@ -214,13 +233,16 @@ def bottleneck_step(x, gy, ws):
 
 
 def main():
-    global _breakdown, _fuse
+    global _breakdown, _fuse, _angles
     ap = argparse.ArgumentParser()
     ap.add_argument("--net", choices=["resnet18", "bottleneck"], default="resnet18")
     ap.add_argument("--batch", type=int, default=0, help="default 256 (resnet18) / 128 (bottleneck)")
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--breakdown", action="store_true")
+    ap.add_argument("--angles", action="store_true",
+                    help="after the timing, one more step that reports the cosine between tensors and their "
+                         "quantized copies (Sec. 3 eq. (1)) per kind of tensor")
     ap.add_argument("--no-fuse", action="store_true",
                     help="Range BN, ReLU and the next layer's quantization as separate passes")
     args = ap.parse_args()
@@ -262,6 +284,17 @@ def main():
     assert bool(torch.isfinite(loss)) and all(p.grad is not None and bool(torch.isfinite(p.grad).all()) for p in params)
     print("%s training step, batch %d%s: %.2f ms / step (%.0f images/s)" % (
         args.net, args.batch, "" if _fuse else " (unfused)", ms, args.batch / ms * 1e3))
+    if args.angles:
+        import math
+        _angles = {}
+        one()
+        torch.cuda.synchronize()
+        print("cosine between a tensor and its quantized copy, mean / min over the layers (angle of the mean):")
+        for kind, vals in sorted(_angles.items()):
+            c = torch.stack(vals).double().cpu()
+            print("  %-26s %3d tensors  mean %.8f  min %.8f  (%.3f deg)" % (
+                kind, len(vals), float(c.mean()), float(c.min()), math.degrees(math.acos(min(1.0, float(c.mean()))))))
+        _angles = None
     if args.breakdown:
         _breakdown = True
         one()
