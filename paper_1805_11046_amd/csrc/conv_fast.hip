@@ -330,15 +330,16 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
         }
     };
     // weights of (occ, cc): [tap][64 oc][64 ch] from the packed copy (L2-resident) into LDS.
-    // 16-byte pieces; the 4 pieces of a row are XOR-swizzled by the row so that the b128
-    // fragment reads of 16 consecutive rows are conflict-free
+    // 16-byte pieces; the 4 pieces of a row are XOR-swizzled by bits 1..2 of the row, which keeps the
+    // b128 fragment reads of 16 consecutive rows conflict-free (a 16-byte LDS read is served in
+    // phases of lanes {0-3, 12-15, 20-23, 24-27}, ...: see gemm_core.h)
     auto stage_b = [&](int cc) {
         const int8_t *src = wpk + (size_t)(occ * CC + cc) * TAPS * CH * CH;
 #pragma unroll
         for (int i = 0; i < B_VEC; ++i) {
             const int e = tid + i * kThreads, row = e >> 2, part = e & 3;
             if (e < B_PIECES)
-                *reinterpret_cast<uint4 *>(&Bs[row * CH + ((part ^ ((row >> 2) & 3)) << 4)]) =
+                *reinterpret_cast<uint4 *>(&Bs[row * CH + ((part ^ ((row >> 1) & 3)) << 4)]) =
                     *reinterpret_cast<const uint4 *>(src + (size_t)e * 16);
         }
     };
@@ -346,7 +347,7 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
     v4i acc[MT][4], accrs[MT];
     int abase[MT];
     const v4i ones = (v4i){0x01010101, 0x01010101, 0x01010101, 0x01010101};
-    const int bbase = l16 * CH + ((kb ^ (l16 >> 2)) << 4);
+    const int bbase = l16 * CH + ((kb ^ ((l16 >> 1) & 3)) << 4);
 
     prefetch(0);
     for (int step = 0; step < nsteps; ++step) {
