@@ -6,6 +6,11 @@
 //           -> apply (normalize, optional fused 8-bit output)          12 B/element (9 with int8 out)
 // backward: bwd_partial (fp64 sums of dy and dy*xhat) -> finalize (dgamma, dbeta, per-channel
 //           constants) -> apply (dx)                                    20 B/element
+// backward with the 8-bit / 16-bit stochastic copies of dx (gradient bifurcation, Sections 1, 4):
+//           bwdq_partial (the same sums + extremes of dy per kind of coordinate, which fix the
+//           range of dx) -> bwdq_finalize -> bwdq_apply (dx optional, codes written where dx is
+//           computed)                                                   19 B/element (23 with dx)
+// Every elementwise kernel takes an optional rectifier: Range BN followed by ReLU in one pass.
 #include "q8t_common.h"
 #include "q8t_internal.h"
 
