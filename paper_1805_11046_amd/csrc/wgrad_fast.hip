@@ -20,7 +20,13 @@
 // workgroup owns 64 rows x 16 channels x 9 taps x 2 byte planes = 72 MFMA tiles; wavefront
 // (plane, lane-of-K) holds 36 of them.  Per-slice int32 partials (each slice is far below the
 // 32-bit bound) are combined in int64 by wgrad_reduce, which also applies the zero-point
-// correction from the row / column sums gathered with v_dot4 beside the MFMAs.
+// correction from the row / column sums (columns with v_dot4 beside the MFMAs, rows with one more
+// MFMA per row tile against an all-ones operand).
+//
+// The loop is bound by the number of instructions a wavefront issues (two wavefronts per SIMD
+// reach about one vector instruction per 5-6 cycles, whatever its kind), not by the matrix pipe:
+// everything that is not an MFMA is kept off the per-chunk path where it can be (scalar bases +
+// per-thread constant offsets when the padded pitch divides the chunk, carried unit state).
 #include "q8t_common.h"
 #include "q8t_internal.h"
 
@@ -39,7 +45,7 @@ constexpr int A_BYTES = 2 * 64 * APITCH;
 constexpr int B_BYTES = 16 * BPITCH;
 constexpr int TILE_INTS = 2 * 4 * 9 * 4 * 64;          // [plane][mt][tap][j][lane]
 constexpr int PART_INTS = TILE_INTS + 9 * 16 + 2 * 64; // + column sums [tap][ch] + row sums [plane][row]
-constexpr int SLOT_INTS = 36 * 4 * 64 + 16 * 64;       // one wavefront's accumulators + its sums
+constexpr int SLOT_INTS = 36 * 4 * 64 + 25 * 64;       // one wavefront's accumulators + its 9 + 16 sums
 constexpr int BUF_BYTES = A_BYTES + B_BYTES;           // one staging buffer (two are used)
 constexpr int SMEM_BYTES = 2 * BUF_BYTES > 2 * SLOT_INTS * 4 ? 2 * BUF_BYTES : 2 * SLOT_INTS * 4;
 
@@ -75,7 +81,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
     if (kr >= g.S) return;
     const int cg = sub % g.ncg, rg = sub / g.ncg;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int plane = wave & 1, kl = wave >> 1;
     const int l16 = lane & 15, kb = lane >> 4;
 
@@ -92,11 +98,44 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
 #pragma unroll
         for (int t = 0; t < 9; ++t) acc[i][t] = (v4i){0, 0, 0, 0};
     int cs[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
-    int rs[4] = {0, 0, 0, 0};
+    // Row sums of the gradient bytes: one more MFMA per row tile against an all-ones operand puts
+    // them into accumulator layout (element j of lane (col, kb) = sum of row 4*kb + j, any col);
+    // the matrix pipe has room for it, the vector ALU does not.
+    v4i rs[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) rs[i] = (v4i){0, 0, 0, 0};
+    const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
 
     // staging registers: one chunk (64 gradient rows x 256 positions, 16 input channels x BROW)
     uint4 regA[4];
     uint2 regB[WIDE ? 2 : 4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) regA[i] = make_uint4(a_pad, a_pad, a_pad, a_pad);
+
+    // When the padded pitch divides the chunk (pitch 64 or 32), a chunk is a whole number of image
+    // rows: a thread's pieces keep their column and their row inside the chunk for the whole run,
+    // and only the chunk's first image row (uniform) changes.  Global offsets then split into a
+    // scalar base and a per-thread constant, and pad columns belong to the same lanes every time.
+    constexpr bool SEP = WC > 0 && KC % PITCHC == 0;
+    constexpr int RPC = SEP ? KC / PITCHC : 1;                    // image rows per chunk
+    constexpr int PIECE = WIDE ? 8 : 4, NB = WIDE ? 2 : 4;
+    constexpr int BPC = BROW / PIECE;                             // pieces per staged input channel
+    constexpr int RB = SEP ? (HALO + PITCHC - 1) / PITCHC : 0;    // image rows covered by the halo
+    constexpr int kNever = 1 << 24;                               // row offset of a lane that only ever stages padding
+    int a_dp = kNever, b_dp[NB];
+    uint32_t a_off = 0, b_off[NB];                                // byte offsets from the scalar bases
+    if (SEP) {
+        const int ta = PIECE * (WIDE ? (tid & 31) : lane), ra = ta / PITCHC, qa = ta - ra * PITCHC;
+        if (qa < WC) a_dp = ra;
+        a_off = (uint32_t)((WIDE ? (tid >> 5) * g.PQ : 0) + ra * WC + qa) * 2u;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int e = tid + kThreads * i, c = e / BPC, pi = e - c * BPC;
+            const int t = PIECE * pi - HALO + RB * PITCHC, rb = t / PITCHC, qb = t - rb * PITCHC;
+            b_dp[i] = (e < 16 * BPC && qb < WC) ? rb - RB : kNever;
+            b_off[i] = (uint32_t)(c * g.PQ + rb * WC + qb);
+        }
+    }
     // position / pitch: quotients are image rows (< 2^15), a float estimate with fix-up is exact
     auto pdiv = [&](uint32_t n) -> uint32_t {
         if (WC) return n / (uint32_t)(WC ? PITCHC : 1);
@@ -107,9 +146,45 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
         return q;
     };
 
-    auto load_regs = [&](int u) {
-        const int b = img0 + u / g.chunks, kp0 = (u % g.chunks) * KC;
-        if (WIDE) {
+    // Units are staged in order, so the (image, chunk) of the next one and its scalar base
+    // addresses are carried along instead of being derived from the unit index.
+    int l_b = img0, l_ck = 0;
+    const char *l_ga = reinterpret_cast<const char *>(g16 + ((int64_t)img0 * g.K + rg * 64) * g.PQ);
+    // the input offsets are counted from RB image rows above the chunk (never dereferenced there)
+    const char *l_xb = reinterpret_cast<const char *>(x) + ((int64_t)img0 * g.C + cg * 16) * g.PQ - RB * WC;
+    const int64_t wrap_ga = ((int64_t)g.K * g.PQ - (int64_t)g.chunks * RPC * WC) * 2;
+    const int64_t wrap_xb = (int64_t)g.C * g.PQ - (int64_t)g.chunks * RPC * WC;
+    auto load_regs = [&]() {
+        const int b = l_b, kp0 = l_ck * KC;
+        if (SEP) {
+            const int P0 = l_ck * RPC;
+            const char *ga = l_ga, *xb = l_xb;
+            if ((uint32_t)(P0 + a_dp) < (uint32_t)g.H) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    if (WIDE) {
+                        regA[i] = *reinterpret_cast<const uint4 *>(ga + (int64_t)i * 32 * g.PQ + a_off);
+                    } else {
+                        const uint2 v0 = *reinterpret_cast<const uint2 *>(ga + (int64_t)(wave + 16 * i) * 2 * g.PQ + a_off);
+                        const uint2 v1 = *reinterpret_cast<const uint2 *>(ga + (int64_t)(wave + 16 * i + 8) * 2 * g.PQ + a_off);
+                        regA[i] = make_uint4(v0.x, v0.y, v1.x, v1.y);
+                    }
+                }
+            } else if (a_dp != kNever) {   // rows past the image in a ragged last chunk
+#pragma unroll
+                for (int i = 0; i < 4; ++i) regA[i] = make_uint4(a_pad, a_pad, a_pad, a_pad);
+            }
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const bool ld = (uint32_t)(P0 + b_dp[i]) < (uint32_t)g.H;
+                regB[i] = make_uint2(b_pad, b_pad);
+                if (WIDE) {
+                    if (ld) regB[i] = *reinterpret_cast<const uint2 *>(xb + b_off[i]);
+                } else {
+                    if (ld) regB[i].x = *reinterpret_cast<const uint32_t *>(xb + b_off[i]);
+                }
+            }
+        } else if (WIDE) {
             // pieces of 8 positions: 16-byte gradient loads, 8-byte input loads (the vector memory
             // pipeline is paid per instruction, not per byte)
 #pragma unroll
@@ -161,6 +236,14 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
                     regB[i].x = *reinterpret_cast<const uint32_t *>(x + ((int64_t)b * g.C + cg * 16 + c) * g.PQ + p * Wd + qq);
             }
         }
+        if (++l_ck == g.chunks) {
+            l_ck = 0;
+            ++l_b;
+            l_ga += wrap_ga;
+            l_xb += wrap_xb;
+        }
+        l_ga += RPC * WC * 2;
+        l_xb += RPC * WC;
     };
     auto write_lds = [&](int buf) {
         uint8_t *A = smem + buf * BUF_BYTES, *B = A + A_BYTES;
@@ -200,15 +283,17 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
             }
         }
     };
-    auto compute = [&](int u, int buf) {
+    int c_ck = 0;   // chunk (within its image) of the next unit to be multiplied
+    auto compute = [&](int buf) {
         const uint8_t *A = smem + buf * BUF_BYTES, *B = A + A_BYTES;
-        const int kstart = (u % g.chunks) * KC + kl * 64;
+        const int kstart = c_ck * KC + kl * 64;
+        if (++c_ck == g.chunks) c_ck = 0;
         if (kstart >= g.Lp) return;   // wavefront-uniform: ragged last chunk of an image
         v4i a[4];
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) {
             a[mt] = *reinterpret_cast<const v4i *>(&A[(plane * 64 + mt * 16 + l16) * APITCH + kl * 64 + kb * 16]);
-            rs[mt] = dot4_ones(a[mt][0], dot4_ones(a[mt][1], dot4_ones(a[mt][2], dot4_ones(a[mt][3], rs[mt]))));
+            rs[mt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mt], ones, rs[mt], 0, 0, 0);
         }
 #pragma unroll
         for (int r = 0; r < 3; ++r) {
@@ -226,8 +311,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
 #pragma unroll
             for (int s = 0; s < 3; ++s) {
                 const int tap = r * 3 + s;
-                if ((tap < 5) == (plane == 0))   // wavefront-uniform: the two planes share the column sums
+                if ((tap < 5) == (plane == 0)) {   // wavefront-uniform: the two planes share the column sums
+                    asm volatile("" ::: "memory");  // keep this a scalar branch (no compute-both-and-select)
                     cs[tap] = dot4_ones(f[s][0], dot4_ones(f[s][1], dot4_ones(f[s][2], dot4_ones(f[s][3], cs[tap]))));
+                }
 #pragma unroll
                 for (int mt = 0; mt < 4; ++mt)
                     acc[mt][tap] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[mt], f[s], acc[mt][tap], 0, 0, 0);
@@ -240,32 +327,27 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
     // matrix instructions while the other occupies the vector-memory and LDS pipes.
     const bool late = wave >= 4;
     if (units > 0) {
-        load_regs(0);
+        load_regs();
         write_lds(0);
-        if (units > 1) load_regs(1);
+        if (units > 1) load_regs();
     }
     __syncthreads();
     for (int u = 0; u < units; ++u) {
         const int cur = u & 1;
-        if (!late) compute(u, cur);
+        if (!late) compute(cur);
         if (u + 1 < units) {
             write_lds(cur ^ 1);
-            if (u + 2 < units) load_regs(u + 2);
+            if (u + 2 < units) load_regs();
         }
-        if (late) compute(u, cur);
+        if (late) compute(cur);
         q8t_lds_barrier();
     }
 
-    // fold the 4 k-blocks of the row / column sums
+    // fold the 4 k-blocks of the column sums
 #pragma unroll
     for (int t = 0; t < 9; ++t) {
         cs[t] += __shfl_xor(cs[t], 16, 64);
         cs[t] += __shfl_xor(cs[t], 32, 64);
-    }
-#pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
-        rs[mt] += __shfl_xor(rs[mt], 16, 64);
-        rs[mt] += __shfl_xor(rs[mt], 32, 64);
     }
 
     // ---- sum the 4 K-lanes of each plane through LDS: (1 -> 0), (3 -> 2), then (2 -> 0) ----
@@ -285,7 +367,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
 #pragma unroll
             for (int t = 0; t < 9; ++t) slot[36 * 4 * 64 + t * 64 + lane] = cs[t];
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) slot[36 * 4 * 64 + (9 + mt) * 64 + lane] = rs[mt];
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) slot[36 * 4 * 64 + (9 + mt * 4 + j) * 64 + lane] = rs[mt][j];
         }
         q8t_lds_barrier();
         if (kl == dst) {
@@ -298,7 +382,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
 #pragma unroll
             for (int t = 0; t < 9; ++t) cs[t] += slot[36 * 4 * 64 + t * 64 + lane];
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) rs[mt] += slot[36 * 4 * 64 + (9 + mt) * 64 + lane];
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) rs[mt][j] += slot[36 * 4 * 64 + (9 + mt * 4 + j) * 64 + lane];
         }
     }
 
@@ -316,8 +402,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3(const int16_t *__restri
 #pragma unroll
             for (int t = 0; t < 9; ++t)
                 if ((t < 5) == (plane == 0)) out[TILE_INTS + t * 16 + l16] = cs[t];
+        }
+        if (l16 == 0) {
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) out[TILE_INTS + 144 + plane * 64 + mt * 16 + l16] = rs[mt];
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) out[TILE_INTS + 144 + plane * 64 + mt * 16 + kb * 4 + j] = rs[mt][j];
         }
     }
 }
