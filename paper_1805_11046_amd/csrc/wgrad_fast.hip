@@ -27,6 +27,8 @@
 // reach about one vector instruction per 5-6 cycles, whatever its kind), not by the matrix pipe:
 // everything that is not an MFMA is kept off the per-chunk path where it can be (scalar bases +
 // per-thread constant offsets when the padded pitch divides the chunk, carried unit state).
+#include <type_traits>
+
 #include "q8t_common.h"
 #include "q8t_internal.h"
 
@@ -452,6 +454,301 @@ __global__ __launch_bounds__(256) void wgrad_reduce(const int *__restrict__ part
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Second form of the same product for the widths whose padded pitch divides the chunk (56 -> 64,
+// 28 -> 32).  The horizontal tap moves to the gradient operand: with p' = p + (s-1),
+//   dW[k,c,r,s] = sum_p' g[k, p' - (s-1)] * x[c, p' + (r-1)*pitch],
+// so the input fragments are plain 16-byte aligned LDS reads and only the gradient fragment of a
+// wavefront is shifted (8 v_alignbyte per K-step).  A wavefront owns 16 gradient rows x 32 input
+// channels x 9 taps of one byte plane and walks all four K-steps of a chunk itself: there is no
+// split of the reduction inside the workgroup, so the per-chunk cost of staging, barrier and loop
+// is paid once per 72 MFMAs instead of once per 36, and nothing is folded through LDS at the end.
+// Row sums (one per shift) and column sums (one per vertical tap) come from MFMAs against an
+// all-ones operand; the column sums are gathered by one wavefront only.
+// Terms whose shifted position falls outside the processed range pair a padding column of x
+// (zero-point code) with a gradient: they are zero in real arithmetic and are left out of the
+// products and of all three sums alike, so the integer identity of wgrad_reduce_v2 stays exact.
+constexpr int A_LEFT = 16;                       // bytes before the chunk in a gradient row: padding columns, set once
+constexpr int APITCH2 = A_LEFT + KC + 32;        // 304 = 19 x 16; holds the 8 positions after the chunk as well
+constexpr int HALO2 = 64;
+constexpr int BROW2 = KC + 2 * HALO2;
+constexpr int BPITCH2 = BROW2 + 16;              // 400 = 25 x 16
+constexpr int CH2 = 32;                          // input channels per workgroup
+constexpr int A2_BYTES = 2 * 64 * APITCH2;
+constexpr int BUF2_BYTES = A2_BYTES + CH2 * BPITCH2;
+constexpr int SMEM2_BYTES = 2 * BUF2_BYTES;
+constexpr int TILE2_INTS = 2 * 4 * 2 * 9 * 4 * 64;              // [plane][mt][ct][tap][j][lane]
+constexpr int PART2_INTS = TILE2_INTS + 3 * CH2 + 2 * 3 * 64;   // + column sums [r][ch] + row sums [plane][s][row]
+
+template <int WC>
+__global__ __launch_bounds__(kThreads) void wgrad_s1_3x3_v2(const int16_t *__restrict__ g16,
+                                                             const int8_t *__restrict__ x,
+                                                             const q8t_qparams *__restrict__ qpg,
+                                                             const q8t_qparams *__restrict__ qpx, WGeom g,
+                                                             int *__restrict__ partial)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    constexpr bool WIDE = WC % 8 == 0;
+    constexpr int PITCHC = WIDE ? WC + 8 : WC + 4;
+    static_assert(KC % PITCHC == 0 && HALO2 % PITCHC == 0, "the pitch must divide the chunk and the halo");
+    constexpr int RPC = KC / PITCHC, RB = HALO2 / PITCHC;   // image rows per chunk / per halo
+    constexpr int PIECE = WIDE ? 8 : 4;                     // positions per staged piece
+    constexpr int APR = KC / PIECE;                         // gradient pieces per row
+    constexpr int NA = 64 * APR / kThreads;                 // gradient pieces per thread (4 or 8)
+    constexpr int ROWSTEP = kThreads / APR;                 // rows between a thread's pieces
+    constexpr int BPC = BROW2 / PIECE;                      // input pieces per channel
+    constexpr int NB = CH2 * BPC / kThreads;                // input pieces per thread (3 or 6)
+    constexpr int kNever = 1 << 24;
+
+    const int bid = blockIdx.x;
+    const int xcd = bid & 7, jj = bid >> 3;
+    const int per = g.ncg * g.nrg;
+    const int sub = jj % per, kr = (jj / per) * 8 + xcd;
+    if (kr >= g.S) return;
+    const int cg = sub % g.ncg, rg = sub / g.ncg;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int plane = wave & 1, mt = wave >> 1;
+    const int l16 = lane & 15, kb = lane >> 4;
+    const bool cswave = wave == 0;
+
+    const int zsg = qpg->zero_point - (1 << (qpg->bits - 1)), zsx = qpx->zero_point - (1 << (qpx->bits - 1));
+    const uint32_t a_pad = (uint32_t)(zsg & 0xFFFF) * 0x00010001u;
+    const uint32_t b_pad = (uint32_t)(zsx & 255) * 0x01010101u;
+
+    const int img0 = kr * g.ipr, img1 = min(g.N, img0 + g.ipr);
+    const int units = (img1 - img0) * g.chunks;
+
+    v4i acc[2][9], rs[3], csacc[2][3];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+#pragma unroll
+        for (int t = 0; t < 9; ++t) acc[c][t] = (v4i){0, 0, 0, 0};
+#pragma unroll
+        for (int r = 0; r < 3; ++r) csacc[c][r] = (v4i){0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int t = 0; t < 3; ++t) rs[t] = (v4i){0, 0, 0, 0};
+    const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
+
+    // the bytes before the chunk in every gradient row are padding columns: zero code, set once
+    {
+        const uint32_t hi4 = (uint32_t)((zsg >> 8) & 255) * 0x01010101u;
+        const uint32_t lo4 = (uint32_t)((zsg & 255) ^ 0x80) * 0x01010101u;
+        const int buf = tid >> 8, prow = (tid >> 1) & 127, half = tid & 1;
+        const uint32_t v = prow < 64 ? hi4 : lo4;
+        *reinterpret_cast<uint2 *>(&smem[buf * BUF2_BYTES + prow * APITCH2 + 8 * half]) = make_uint2(v, v);
+    }
+
+    // per-thread constants of the staging: row inside the chunk, column, global byte offset
+    using AReg = typename std::conditional<WIDE, uint4, uint2>::type;
+    AReg regA[NA], regH;
+    uint2 regB[NB];
+    const int pa = tid % APR, ta = PIECE * pa, ra = ta / PITCHC, qa = ta - ra * PITCHC;
+    const int a_dp = qa < WC ? ra : kNever;
+    const uint32_t a_off = (uint32_t)((tid / APR) * g.PQ + ra * WC + qa) * 2u;
+    const uint32_t h_off = (uint32_t)(tid * g.PQ + RPC * WC) * 2u;          // threads 0..63: the piece after the chunk
+    int b_dp[NB];
+    uint32_t b_off[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int e = tid + kThreads * i, c = e / BPC, pi = e - c * BPC;
+        const int t = PIECE * pi, rb = t / PITCHC, qb = t - rb * PITCHC;
+        b_dp[i] = qb < WC ? rb - RB : kNever;
+        b_off[i] = (uint32_t)(c * g.PQ + rb * WC + qb);
+    }
+    auto pad_a = [&]() {
+        AReg v;
+        if constexpr (WIDE) v = make_uint4(a_pad, a_pad, a_pad, a_pad);
+        else v = make_uint2(a_pad, a_pad);
+        return v;
+    };
+#pragma unroll
+    for (int i = 0; i < NA; ++i) regA[i] = pad_a();
+    regH = pad_a();
+
+    int l_ck = 0;
+    const char *l_ga = reinterpret_cast<const char *>(g16 + ((int64_t)img0 * g.K + rg * 64) * g.PQ);
+    const char *l_xb = reinterpret_cast<const char *>(x) + ((int64_t)img0 * g.C + cg * CH2) * g.PQ - RB * WC;
+    const int64_t wrap_ga = ((int64_t)g.K * g.PQ - (int64_t)g.chunks * RPC * WC) * 2;
+    const int64_t wrap_xb = (int64_t)g.C * g.PQ - (int64_t)g.chunks * RPC * WC;
+    auto load_regs = [&]() {
+        const int P0 = l_ck * RPC;
+        const char *ga = l_ga, *xb = l_xb;
+        if ((uint32_t)(P0 + a_dp) < (uint32_t)g.H) {
+#pragma unroll
+            for (int i = 0; i < NA; ++i)
+                regA[i] = *reinterpret_cast<const AReg *>(ga + (int64_t)i * ROWSTEP * 2 * g.PQ + a_off);
+        } else if (a_dp != kNever) {   // rows past the image in a ragged last chunk
+#pragma unroll
+            for (int i = 0; i < NA; ++i) regA[i] = pad_a();
+        }
+        if (wave == 0) {               // first positions of the image row after the chunk
+            if (P0 + RPC < g.H) regH = *reinterpret_cast<const AReg *>(ga + h_off);
+            else regH = pad_a();
+        }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const bool ld = (uint32_t)(P0 + b_dp[i]) < (uint32_t)g.H;
+            regB[i] = make_uint2(b_pad, b_pad);
+            if (WIDE) {
+                if (ld) regB[i] = *reinterpret_cast<const uint2 *>(xb + b_off[i]);
+            } else {
+                if (ld) regB[i].x = *reinterpret_cast<const uint32_t *>(xb + b_off[i]);
+            }
+        }
+        if (++l_ck == g.chunks) {
+            l_ck = 0;
+            l_ga += wrap_ga;
+            l_xb += wrap_xb;
+        }
+        l_ga += RPC * WC * 2;
+        l_xb += RPC * WC;
+    };
+    auto split_store = [&](uint8_t *A, int row, int col, const AReg &v) {
+        if constexpr (WIDE) {
+            const uint32_t h0 = __builtin_amdgcn_perm(v.y, v.x, 0x07050301), h1 = __builtin_amdgcn_perm(v.w, v.z, 0x07050301);
+            const uint32_t l0 = __builtin_amdgcn_perm(v.y, v.x, 0x06040200) ^ 0x80808080u;
+            const uint32_t l1 = __builtin_amdgcn_perm(v.w, v.z, 0x06040200) ^ 0x80808080u;
+            *reinterpret_cast<uint2 *>(&A[row * APITCH2 + A_LEFT + col]) = make_uint2(h0, h1);
+            *reinterpret_cast<uint2 *>(&A[(64 + row) * APITCH2 + A_LEFT + col]) = make_uint2(l0, l1);
+        } else {
+            const uint32_t h = __builtin_amdgcn_perm(v.y, v.x, 0x07050301);
+            const uint32_t l = __builtin_amdgcn_perm(v.y, v.x, 0x06040200) ^ 0x80808080u;
+            *reinterpret_cast<uint32_t *>(&A[row * APITCH2 + A_LEFT + col]) = h;
+            *reinterpret_cast<uint32_t *>(&A[(64 + row) * APITCH2 + A_LEFT + col]) = l;
+        }
+    };
+    auto write_lds = [&](int buf) {
+        uint8_t *A = smem + buf * BUF2_BYTES, *B = A + A2_BYTES;
+#pragma unroll
+        for (int i = 0; i < NA; ++i) split_store(A, tid / APR + ROWSTEP * i, PIECE * pa, regA[i]);
+        if (wave == 0) split_store(A, tid, KC, regH);
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int e = tid + kThreads * i, c = e / BPC, pi = e - c * BPC;
+            if (WIDE) *reinterpret_cast<uint2 *>(&B[c * BPITCH2 + 8 * pi]) = regB[i];
+            else *reinterpret_cast<uint32_t *>(&B[c * BPITCH2 + 4 * pi]) = regB[i].x;
+        }
+    };
+    int c_ck = 0;
+    auto compute = [&](int buf) {
+        const uint8_t *A = smem + buf * BUF2_BYTES, *B = A + A2_BYTES;
+        const int k0 = c_ck * KC;
+        if (++c_ck == g.chunks) c_ck = 0;
+        const uint8_t *Ar = A + (plane * 64 + mt * 16 + l16) * APITCH2 + A_LEFT + kb * 16;
+        const uint8_t *Br = B + l16 * BPITCH2 + HALO2 + kb * 16;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (k0 + ks * 64 >= g.Lp) break;   // uniform: ragged last chunk of an image
+            const v4i c = *reinterpret_cast<const v4i *>(Ar + ks * 64);
+            const uint32_t dm1 = *reinterpret_cast<const uint32_t *>(Ar + ks * 64 - 4);
+            const uint32_t dp1 = *reinterpret_cast<const uint32_t *>(Ar + ks * 64 + 16);
+            auto ab = [](int hi, int lo, int n) { return (int)__builtin_amdgcn_alignbyte((uint32_t)hi, (uint32_t)lo, n); };
+            v4i fa[3];
+            fa[0] = (v4i){ab(c[1], c[0], 1), ab(c[2], c[1], 1), ab(c[3], c[2], 1), ab((int)dp1, c[3], 1)};   // g[p' + 1]
+            fa[1] = c;
+            fa[2] = (v4i){ab(c[0], (int)dm1, 3), ab(c[1], c[0], 3), ab(c[2], c[1], 3), ab(c[3], c[2], 3)};   // g[p' - 1]
+#pragma unroll
+            for (int s = 0; s < 3; ++s) rs[s] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[s], ones, rs[s], 0, 0, 0);
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+                for (int r = 0; r < 3; ++r) {
+                    const v4i fb = *reinterpret_cast<const v4i *>(Br + ct * 16 * BPITCH2 + ks * 64 + (r - 1) * PITCHC);
+                    if (cswave) {
+                        asm volatile("" ::: "memory");   // keep this a scalar branch
+                        csacc[ct][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, fb, csacc[ct][r], 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int s = 0; s < 3; ++s)
+                        acc[ct][r * 3 + s] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[s], fb, acc[ct][r * 3 + s], 0, 0, 0);
+                }
+        }
+    };
+
+    const bool late = wave >= 4;
+    if (units > 0) {
+        load_regs();
+        write_lds(0);
+        if (units > 1) load_regs();
+    }
+    __syncthreads();
+    for (int u = 0; u < units; ++u) {
+        const int cur = u & 1;
+        if (!late) compute(cur);
+        if (u + 1 < units) {
+            write_lds(cur ^ 1);
+            if (u + 2 < units) load_regs();
+        }
+        if (late) compute(cur);
+        q8t_lds_barrier();
+    }
+
+    int *out = partial + ((int64_t)(kr * g.nrg + rg) * g.ncg + cg) * PART2_INTS;
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                out[((((plane * 4 + mt) * 2 + ct) * 9 + t) * 4 + j) * 64 + lane] = acc[ct][t][j];
+    if (cswave && kb == 0) {
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int r = 0; r < 3; ++r) out[TILE2_INTS + r * CH2 + ct * 16 + l16] = csacc[ct][r][0];
+    }
+    if (l16 == 0) {
+#pragma unroll
+        for (int s = 0; s < 3; ++s)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                out[TILE2_INTS + 3 * CH2 + (plane * 3 + s) * 64 + mt * 16 + kb * 4 + j] = rs[s][j];
+    }
+}
+
+// int64 reduction over the k-ranges for wgrad_s1_3x3_v2: the column sum depends on the vertical tap,
+// the row sums on the horizontal one.
+__global__ __launch_bounds__(256) void wgrad_reduce_v2(const int *__restrict__ partial, WGeom g,
+                                                       const q8t_qparams *__restrict__ qpg,
+                                                       const q8t_qparams *__restrict__ qpx, float *__restrict__ dw,
+                                                       int64_t *__restrict__ acc_out)
+{
+    __shared__ int64_t fold[4][64];
+    const int sub = blockIdx.y;
+    const int cg = sub % g.ncg, rg = sub / g.ncg;
+    const int lane = threadIdx.x & 63, quarter = threadIdx.x >> 6;
+    const int idx = blockIdx.x * 64 + lane;   // (((mt*2 + ct)*9 + tap)*4 + j)*64 + lane, < 18432
+    const int j = (idx >> 6) & 3, t2 = idx >> 8;
+    const int tap = t2 % 9, ct = (t2 / 9) & 1, mt = t2 / 18;
+    const int r = tap / 3, s = tap - 3 * r;
+    const int row_l = mt * 16 + (lane >> 4) * 4 + j, ch_l = ct * 16 + (lane & 15);
+
+    const int zsg = qpg->zero_point - (1 << (qpg->bits - 1)), zsx = qpx->zero_point - (1 << (qpx->bits - 1));
+    const int64_t ca = 128 - zsg;
+    const int ksteps_img = (g.Lp + 63) / 64;
+    int64_t v = 0;
+    for (int kr = quarter; kr < g.S; kr += 4) {
+        const int *p = partial + ((int64_t)(kr * g.nrg + rg) * g.ncg + cg) * PART2_INTS;
+        const int nimg = min(g.N, (kr + 1) * g.ipr) - kr * g.ipr;
+        const int64_t Kp = (int64_t)nimg * ksteps_img * 64;
+        const int64_t hi = p[idx], lo = p[TILE2_INTS / 2 + idx];
+        const int64_t csv = p[TILE2_INTS + r * CH2 + ch_l];
+        const int64_t rsh = p[TILE2_INTS + 3 * CH2 + s * 64 + row_l], rsl = p[TILE2_INTS + 3 * CH2 + (3 + s) * 64 + row_l];
+        v += 256 * hi + lo + ca * csv - (int64_t)zsx * (256 * rsh + rsl + ca * Kp);
+    }
+    fold[quarter][lane] = v;
+    __syncthreads();
+    if (quarter == 0) {
+        v = fold[0][lane] + fold[1][lane] + fold[2][lane] + fold[3][lane];
+        const double sc = (double)(qpg->scale * qpx->scale);
+        const int64_t o = ((int64_t)(rg * 64 + row_l) * g.C + cg * CH2 + ch_l) * 9 + tap;
+        if (acc_out) acc_out[o] = v;
+        if (dw) dw[o] = (float)((double)v * sc);
+    }
+}
+
 bool wgrad_shape_ok(const q8t_conv_desc *d)
 {
     if (d->stride != 1 || d->R != 3 || d->S != 3 || d->pad != 1) return false;
@@ -461,6 +758,9 @@ bool wgrad_shape_ok(const q8t_conv_desc *d)
     return true;
 }
 
+// widths served by wgrad_s1_3x3_v2
+bool wgrad_v2_ok(const q8t_conv_desc *d) { return (d->W == 56 || d->W == 28) && d->C % CH2 == 0; }
+
 WGeom wgrad_geom(const q8t_conv_desc *d)
 {
     WGeom g;
@@ -469,7 +769,7 @@ WGeom wgrad_geom(const q8t_conv_desc *d)
     g.Lp = d->H * g.pitch;
     g.rpitch = 1.0f / (float)g.pitch;
     g.chunks = (g.Lp + KC - 1) / KC;
-    g.ncg = d->C / 16;
+    g.ncg = wgrad_v2_ok(d) ? d->C / CH2 : d->C / 16;
     g.nrg = d->K / 64;
     int want = 256 / (g.ncg * g.nrg);        // one workgroup per compute unit
     if (want < 1) want = 1;
@@ -498,6 +798,22 @@ int launch_wgrad(int blocks, hipStream_t st, const int16_t *g16, const int8_t *x
     return Q8T_OK;
 }
 
+template <int WC>
+int launch_wgrad_v2(int blocks, hipStream_t st, const int16_t *g16, const int8_t *x, const q8t_qparams *qg,
+                    const q8t_qparams *qx, const WGeom &g, int *ws)
+{
+    static bool attr = false;
+    if (!attr) {
+        if (hipFuncSetAttribute((const void *)wgrad_s1_3x3_v2<WC>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                SMEM2_BYTES) != hipSuccess)
+            return Q8T_ERR_HIP;
+        attr = true;
+    }
+    hipLaunchKernelGGL(wgrad_s1_3x3_v2<WC>, dim3(blocks), dim3(kThreads), SMEM2_BYTES, st, g16, x, qg, qx, g, ws);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
+
 }  // namespace
 
 bool q8t_fast_wgrad_supported(const q8t_conv_desc *d, const void *g16, const void *x, const void *dw,
@@ -512,7 +828,7 @@ size_t q8t_fast_wgrad_ws(const q8t_conv_desc *d)
 {
     if (!wgrad_shape_ok(d)) return 0;
     const WGeom g = wgrad_geom(d);
-    return (size_t)g.S * g.nrg * g.ncg * PART_INTS * sizeof(int);
+    return (size_t)g.S * g.nrg * g.ncg * (wgrad_v2_ok(d) ? PART2_INTS : PART_INTS) * sizeof(int);
 }
 
 int q8t_fast_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams *qg, const int8_t *x,
@@ -522,6 +838,15 @@ int q8t_fast_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams
     const WGeom g = wgrad_geom(d);
     const int per = g.ncg * g.nrg;
     const int blocks = ((g.S + 7) / 8) * 8 * per;
+    if (wgrad_v2_ok(d)) {
+        const int rc2 = d->W == 56 ? launch_wgrad_v2<56>(blocks, st, g16, x, qg, qx, g, (int *)ws)
+                                   : launch_wgrad_v2<28>(blocks, st, g16, x, qg, qx, g, (int *)ws);
+        if (rc2) return rc2;
+        hipLaunchKernelGGL(wgrad_reduce_v2, dim3(TILE2_INTS / 2 / 64, per), dim3(256), 0, st, (const int *)ws, g, qg,
+                           qx, dw, acc_out);
+        Q8T_LAUNCH_CHECK();
+        return Q8T_OK;
+    }
     const int rc = d->W == 56   ? launch_wgrad<56>(blocks, st, g16, x, qg, qx, g, (int *)ws)
                    : d->W == 28 ? launch_wgrad<28>(blocks, st, g16, x, qg, qx, g, (int *)ws)
                                 : launch_wgrad<0>(blocks, st, g16, x, qg, qx, g, (int *)ws);
