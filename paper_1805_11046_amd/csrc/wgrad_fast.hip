@@ -464,15 +464,19 @@ __global__ __launch_bounds__(256) void wgrad_reduce(const int *__restrict__ part
 // split of the reduction inside the workgroup, so the per-chunk cost of staging, barrier and loop
 // is paid once per 72 MFMAs instead of once per 36, and nothing is folded through LDS at the end.
 // Row sums (one per shift) and column sums (one per vertical tap) come from MFMAs against an
-// all-ones operand; the column sums are gathered by one wavefront only.
+// all-ones operand; the six column sums (2 channel tiles x 3 vertical taps) are dealt out to six
+// wavefronts, one extra fragment read and MFMA per K-step each.
 // Terms whose shifted position falls outside the processed range pair a padding column of x
 // (zero-point code) with a gradient: they are zero in real arithmetic and are left out of the
 // products and of all three sums alike, so the integer identity of wgrad_reduce_v2 stays exact.
 constexpr int A_LEFT = 16;                       // bytes before the chunk in a gradient row: padding columns, set once
-constexpr int APITCH2 = A_LEFT + KC + 32;        // 304 = 19 x 16; holds the 8 positions after the chunk as well
+// Row pitches of 8, 24, 40 or 56 dwords (mod 64) make the 16-byte fragment reads of a wavefront
+// (16 rows x 4 neighbouring 16-byte columns) conflict-free under the 4-phase service order of
+// ds_read_b128.
+constexpr int APITCH2 = A_LEFT + KC + 16;        // 288 B = 72 dwords; holds the 8 positions after the chunk as well
 constexpr int HALO2 = 64;
 constexpr int BROW2 = KC + 2 * HALO2;
-constexpr int BPITCH2 = BROW2 + 16;              // 400 = 25 x 16
+constexpr int BPITCH2 = BROW2 + 32;              // 416 B = 104 dwords
 constexpr int CH2 = 32;                          // input channels per workgroup
 constexpr int A2_BYTES = 2 * 64 * APITCH2;
 constexpr int BUF2_BYTES = A2_BYTES + CH2 * BPITCH2;
@@ -510,7 +514,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3_v2(const int16_t *__res
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int plane = wave & 1, mt = wave >> 1;
     const int l16 = lane & 15, kb = lane >> 4;
-    const bool cswave = wave == 0;
+    const int csq = wave < 6 ? wave : wave - 6;   // (channel tile, vertical tap) whose column sums this wavefront gathers
+    const int cs_ct = csq / 3, cs_r = csq - 3 * cs_ct;
 
     const int zsg = qpg->zero_point - (1 << (qpg->bits - 1)), zsx = qpx->zero_point - (1 << (qpx->bits - 1));
     const uint32_t a_pad = (uint32_t)(zsg & 0xFFFF) * 0x00010001u;
@@ -519,14 +524,11 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3_v2(const int16_t *__res
     const int img0 = kr * g.ipr, img1 = min(g.N, img0 + g.ipr);
     const int units = (img1 - img0) * g.chunks;
 
-    v4i acc[2][9], rs[3], csacc[2][3];
+    v4i acc[2][9], rs[3], csacc = {0, 0, 0, 0};
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
+    for (int c = 0; c < 2; ++c)
 #pragma unroll
         for (int t = 0; t < 9; ++t) acc[c][t] = (v4i){0, 0, 0, 0};
-#pragma unroll
-        for (int r = 0; r < 3; ++r) csacc[c][r] = (v4i){0, 0, 0, 0};
-    }
 #pragma unroll
     for (int t = 0; t < 3; ++t) rs[t] = (v4i){0, 0, 0, 0};
     const v4i ones = {0x01010101, 0x01010101, 0x01010101, 0x01010101};
@@ -638,6 +640,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3_v2(const int16_t *__res
         if (++c_ck == g.chunks) c_ck = 0;
         const uint8_t *Ar = A + (plane * 64 + mt * 16 + l16) * APITCH2 + A_LEFT + kb * 16;
         const uint8_t *Br = B + l16 * BPITCH2 + HALO2 + kb * 16;
+        const uint8_t *Bcs = Br + cs_ct * 16 * BPITCH2 + (cs_r - 1) * PITCHC;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             if (k0 + ks * 64 >= g.Lp) break;   // uniform: ragged last chunk of an image
@@ -651,15 +654,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3_v2(const int16_t *__res
             fa[2] = (v4i){ab(c[0], (int)dm1, 3), ab(c[1], c[0], 3), ab(c[2], c[1], 3), ab(c[3], c[2], 3)};   // g[p' - 1]
 #pragma unroll
             for (int s = 0; s < 3; ++s) rs[s] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[s], ones, rs[s], 0, 0, 0);
+            csacc = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, *reinterpret_cast<const v4i *>(Bcs + ks * 64), csacc, 0, 0, 0);
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
                 for (int r = 0; r < 3; ++r) {
                     const v4i fb = *reinterpret_cast<const v4i *>(Br + ct * 16 * BPITCH2 + ks * 64 + (r - 1) * PITCHC);
-                    if (cswave) {
-                        asm volatile("" ::: "memory");   // keep this a scalar branch
-                        csacc[ct][r] = __builtin_amdgcn_mfma_i32_16x16x64_i8(ones, fb, csacc[ct][r], 0, 0, 0);
-                    }
 #pragma unroll
                     for (int s = 0; s < 3; ++s)
                         acc[ct][r * 3 + s] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[s], fb, acc[ct][r * 3 + s], 0, 0, 0);
@@ -693,12 +693,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3_v2(const int16_t *__res
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 out[((((plane * 4 + mt) * 2 + ct) * 9 + t) * 4 + j) * 64 + lane] = acc[ct][t][j];
-    if (cswave && kb == 0) {
-#pragma unroll
-        for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-            for (int r = 0; r < 3; ++r) out[TILE2_INTS + r * CH2 + ct * 16 + l16] = csacc[ct][r][0];
-    }
+    if (wave < 6 && kb == 0) out[TILE2_INTS + cs_r * CH2 + cs_ct * 16 + l16] = csacc[0];
     if (l16 == 0) {
 #pragma unroll
         for (int s = 0; s < 3; ++s)
@@ -710,12 +705,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3_v2(const int16_t *__res
 
 // int64 reduction over the k-ranges for wgrad_s1_3x3_v2: the column sum depends on the vertical tap,
 // the row sums on the horizontal one.
-__global__ __launch_bounds__(256) void wgrad_reduce_v2(const int *__restrict__ partial, WGeom g,
+constexpr int RQ2 = 16;   // most interleaved subsets of the k-ranges per workgroup (one wavefront each)
+__global__ __launch_bounds__(64 * RQ2) void wgrad_reduce_v2(const int *__restrict__ partial, WGeom g,
                                                        const q8t_qparams *__restrict__ qpg,
                                                        const q8t_qparams *__restrict__ qpx, float *__restrict__ dw,
                                                        int64_t *__restrict__ acc_out)
 {
-    __shared__ int64_t fold[4][64];
+    __shared__ int64_t fold[RQ2][64];
     const int sub = blockIdx.y;
     const int cg = sub % g.ncg, rg = sub / g.ncg;
     const int lane = threadIdx.x & 63, quarter = threadIdx.x >> 6;
@@ -729,7 +725,8 @@ __global__ __launch_bounds__(256) void wgrad_reduce_v2(const int *__restrict__ p
     const int64_t ca = 128 - zsg;
     const int ksteps_img = (g.Lp + 63) / 64;
     int64_t v = 0;
-    for (int kr = quarter; kr < g.S; kr += 4) {
+    const int nq = blockDim.x >> 6;
+    for (int kr = quarter; kr < g.S; kr += nq) {
         const int *p = partial + ((int64_t)(kr * g.nrg + rg) * g.ncg + cg) * PART2_INTS;
         const int nimg = min(g.N, (kr + 1) * g.ipr) - kr * g.ipr;
         const int64_t Kp = (int64_t)nimg * ksteps_img * 64;
@@ -741,7 +738,8 @@ __global__ __launch_bounds__(256) void wgrad_reduce_v2(const int *__restrict__ p
     fold[quarter][lane] = v;
     __syncthreads();
     if (quarter == 0) {
-        v = fold[0][lane] + fold[1][lane] + fold[2][lane] + fold[3][lane];
+        v = 0;
+        for (int q = 0; q < nq; ++q) v += fold[q][lane];
         const double sc = (double)(qpg->scale * qpx->scale);
         const int64_t o = ((int64_t)(rg * 64 + row_l) * g.C + cg * CH2 + ch_l) * 9 + tap;
         if (acc_out) acc_out[o] = v;
@@ -842,7 +840,7 @@ int q8t_fast_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams
         const int rc2 = d->W == 56 ? launch_wgrad_v2<56>(blocks, st, g16, x, qg, qx, g, (int *)ws)
                                    : launch_wgrad_v2<28>(blocks, st, g16, x, qg, qx, g, (int *)ws);
         if (rc2) return rc2;
-        hipLaunchKernelGGL(wgrad_reduce_v2, dim3(TILE2_INTS / 2 / 64, per), dim3(256), 0, st, (const int *)ws, g, qg,
+        hipLaunchKernelGGL(wgrad_reduce_v2, dim3(TILE2_INTS / 2 / 64, per), dim3(g.S >= 64 ? 64 * RQ2 : 256), 0, st, (const int *)ws, g, qg,
                            qx, dw, acc_out);
         Q8T_LAUNCH_CHECK();
         return Q8T_OK;
