@@ -109,6 +109,10 @@ CONV_CASES = [
     (1, 64, 60, 56, 64, 3, 3, 1, 1),     # last chunk of the image is ragged
     (2, 32, 30, 56, 64, 3, 3, 1, 1),     # width 56, height not a multiple of the 4 rows per staged chunk
     (2, 16, 5, 28, 128, 3, 3, 1, 1),     # width 28, image shorter than one staged chunk
+    (2, 32, 5, 28, 64, 3, 3, 1, 1),      # shifted-gradient weight gradient: image shorter than one chunk
+    (1, 32, 9, 28, 64, 3, 3, 1, 1),      # ... second chunk holds a single image row
+    (3, 32, 3, 56, 64, 3, 3, 1, 1),      # ... width 56, three rows
+    (5, 96, 8, 56, 128, 3, 3, 1, 1),     # ... three channel groups, two row groups, two whole chunks per image
     (2, 64, 56, 56, 256, 1, 1, 1, 0),    # 1x1 at the full plane size
     (40, 64, 6, 6, 64, 3, 3, 1, 1),      # one 256-row tile spans several small images
     (9, 64, 14, 14, 128, 3, 3, 1, 1),
