@@ -20,6 +20,8 @@
 //    sums taken) by a small pre-pass; row sums of A come from v_dot4 on the fragments already in
 //    registers.  Epilogue: zero-point correction, dequantization, float4 stores (4 consecutive
 //    positions of one output channel per lane).
+#include <type_traits>
+
 #include "q8t_common.h"
 #include "q8t_internal.h"
 
@@ -39,6 +41,8 @@ constexpr int MAXR9 = 464;       // staged rows (padded coordinates) of the 3x3 
 constexpr int MAXR1 = BM;        // 1x1 variant: no halo, no padding
 constexpr int MAX_SLABS = 4;     // staging iterations per wavefront (28 slabs of 64 lanes at most)
 constexpr int kSkip = -1000000;  // marks a staging slot with nothing to store
+constexpr int MARGIN = 20;       // spare LDS rows on either side of the staged rows: a staging lane whose group of
+                                 // positions hangs over the staged range stores there instead of testing every row
 
 struct FastDiv {
     uint32_t d;
@@ -155,11 +159,11 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
     // per-channel statistics of this workgroup's outputs (integer accumulators: exact, order-free)
     __shared__ unsigned long long st_sum[STATS ? CH : 1];
     __shared__ int st_min[STATS ? CH : 1], st_max[STATS ? CH : 1];
-    constexpr int A_BYTES = (TAPS == 9 ? MAXR9 : MAXR1) * ROWB;
+    constexpr int A_BYTES = ((TAPS == 9 ? MAXR9 : MAXR1) + 2 * MARGIN) * ROWB;
     constexpr int B_PIECES = TAPS * CH * 4;            // 16-byte pieces of the weight chunk
     constexpr int B_VEC = (B_PIECES + kThreads - 1) / kThreads;
     constexpr int PQC = WC * WC, W1C = (TAPS == 9 && WC) ? WC + 1 : WC, IMGC = (TAPS == 9 && WC) ? (WC + 1) * (WC + 1) : PQC;
-    uint8_t *As = smem;
+    uint8_t *As = smem + MARGIN * ROWB;
     uint8_t *Bs = smem + A_BYTES;
 
     const int W = WC ? WC : g.W, PQ = WC ? PQC : g.PQ;
@@ -258,7 +262,7 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
                     r = (int)(b * IMG + pos + p + W1) - a0;
                     pthr[it] = W - 1 - (int)(pos - p * W);   // positions after this one sit one row further
                 }
-                if (r > -4 && r < sch.maxr) {   // rows outside [0, maxr) are dropped at the store
+                if (r > -4 && r < sch.maxr) {   // rows outside [0, maxr) land in the spare rows
                     prow[it] = r;
                     const int8_t *src = x + ((size_t)(b * g.C + cc * CH + cg * 4) * PQ + pos);
 #pragma unroll
@@ -288,8 +292,8 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
                     }
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const int row = prow[0] + 4 * j4 + i + bump;
-                        if (row >= 0 && row < sch.maxr) *reinterpret_cast<uint32_t *>(&As[row * ROWB + cg * 4]) = out[i];
+                        const int row = prow[0] + 4 * j4 + i + bump;   // in (-MARGIN, maxr + MARGIN)
+                        *reinterpret_cast<uint32_t *>(&As[row * ROWB + cg * 4]) = out[i];
                     }
                 }
             }
@@ -302,8 +306,8 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
                 transpose4x4(pa[it], out);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const int row = prow[it] + i + ((TAPS == 9 && i > pthr[it]) ? 1 : 0);
-                    if (row >= 0 && row < sch.maxr) *reinterpret_cast<uint32_t *>(&As[row * ROWB + cg * 4]) = out[i];
+                    const int row = prow[it] + i + ((TAPS == 9 && i > pthr[it]) ? 1 : 0);   // in (-4, maxr + 4)
+                    *reinterpret_cast<uint32_t *>(&As[row * ROWB + cg * 4]) = out[i];
                 }
             }
         }
@@ -399,9 +403,12 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
         // by contract), dequantization, 4 consecutive positions of one output channel per lane ----
         const uint32_t Kp = (uint32_t)(g.C * TAPS);
         const uint32_t kzz = Kp * (uint32_t)za * (uint32_t)zb;
-        uint32_t csn[4];
+        uint32_t ncs[4];   // minus the column term, so that a correction is one three-operand add
 #pragma unroll
-        for (int nt = 0; nt < 4; ++nt) csn[nt] = (uint32_t)za * (uint32_t)colsum[occ * CH + nt * 16 + l16];
+        for (int nt = 0; nt < 4; ++nt) ncs[nt] = 0u - (uint32_t)za * (uint32_t)colsum[occ * CH + nt * 16 + l16];
+        // FLOAT_ONLY: the usual call (float result, no integer copy) without the two pointer tests per store
+        auto emit = [&](auto float_only) {
+        constexpr bool FLOAT_ONLY = decltype(float_only)::value;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             const int gr = g0 + (mt * kWaves + wave) * 16 + kb * 4;
@@ -415,10 +422,10 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt) {
                 const size_t o = o0 + (size_t)(nt * 16) * PQ;
-                const int c0 = (int)((uint32_t)acc[mt][nt][0] + t[0] - csn[nt]);
-                const int c1 = (int)((uint32_t)acc[mt][nt][1] + t[1] - csn[nt]);
-                const int c2 = (int)((uint32_t)acc[mt][nt][2] + t[2] - csn[nt]);
-                const int c3 = (int)((uint32_t)acc[mt][nt][3] + t[3] - csn[nt]);
+                const int c0 = (int)((uint32_t)acc[mt][nt][0] + t[0] + ncs[nt]);
+                const int c1 = (int)((uint32_t)acc[mt][nt][1] + t[1] + ncs[nt]);
+                const int c2 = (int)((uint32_t)acc[mt][nt][2] + t[2] + ncs[nt]);
+                const int c3 = (int)((uint32_t)acc[mt][nt][3] + t[3] + ncs[nt]);
                 if (STATS) {
                     // every lane adds its 4 rows straight into the workgroup's LDS slots (4 lanes per
                     // channel collide; cheaper than folding them first through cross-lane moves, which
@@ -427,8 +434,8 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
                     atomicMin(&st_min[nt * 16 + l16], min(min(c0, c1), min(c2, c3)));
                     atomicMax(&st_max[nt * 16 + l16], max(max(c0, c1), max(c2, c3)));
                 }
-                if (acc_out) *reinterpret_cast<int4 *>(acc_out + o) = make_int4(c0, c1, c2, c3);
-                if (y) {
+                if (!FLOAT_ONLY && acc_out) *reinterpret_cast<int4 *>(acc_out + o) = make_int4(c0, c1, c2, c3);
+                if (FLOAT_ONLY || y) {
                     float4 f;
                     f.x = sc * (float)c0;
                     f.y = sc * (float)c1;
@@ -438,6 +445,9 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
                 }
             }
         }
+        };
+        if (y && !acc_out) emit(std::true_type{});
+        else emit(std::false_type{});
     }
     if (STATS) {
         __syncthreads();
@@ -496,7 +506,7 @@ __global__ __launch_bounds__(256) void conv_stats_finalize(const ConvStat *__res
 template <int TAPS>
 constexpr size_t smem_bytes()
 {
-    return (size_t)(TAPS == 9 ? MAXR9 : MAXR1) * ROWB + (size_t)TAPS * CH * CH;
+    return (size_t)((TAPS == 9 ? MAXR9 : MAXR1) + 2 * MARGIN) * ROWB + (size_t)TAPS * CH * CH;
 }
 
 // LDS rows (padded coordinates) one sub-tile can touch
