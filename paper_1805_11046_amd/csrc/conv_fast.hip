@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
     const int row_end = min(g.M, row_begin + sch.rpb);
     if (row_begin >= row_end) return;
     const int occ = blockIdx.y;  // output-channel chunk
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     if (STATS && tid < CH) {
         st_sum[tid] = 0ull;
         st_min[tid] = 2147483647;
@@ -350,7 +350,8 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
 
     v4i acc[MT][4], accrs[MT];
     int abase[MT];
-    const v4i ones = (v4i){0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    v4i ones = (v4i){0x01010101, 0x01010101, 0x01010101, 0x01010101};
+    asm volatile("" : "+v"(ones));   // opaque: kept in four registers instead of being rebuilt before every use
     const int bbase = l16 * CH + ((kb ^ ((l16 >> 1) & 3)) << 4);
 
     prefetch(0);
