@@ -836,6 +836,12 @@ __global__ __launch_bounds__(kThreads) void smallc_fused(const int8_t *__restric
         for (int i = tid; i < (CR * Wp + 16) >> 2; i += kThreads) r32[i] = zbyte * 0x01010101u;
     }
     if (filter_once) load_filter(0);
+    // with a single group of 64 output channels the column terms of the epilogue are loaded once
+    uint32_t cs_once[4] = {0u, 0u, 0u, 0u};
+    if (filter_once) {
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) cs_once[nt] = (uint32_t)za * (uint32_t)colsum[nt * 16 + l16];
+    }
     for (int p = pbeg; p < pend; ++p) {
         if (carry) {
             __syncthreads();   // the fill, or the previous output row's operand tile, is done with `rows`
@@ -938,7 +944,7 @@ __global__ __launch_bounds__(kThreads) void smallc_fused(const int8_t *__restric
 #pragma unroll
                     for (int nt = 0; nt < 4; ++nt) {
                         const int k = k0 + nt * 16 + l16;
-                        const uint32_t cs = (uint32_t)za * (uint32_t)colsum[k];
+                        const uint32_t cs = filter_once ? cs_once[nt] : (uint32_t)za * (uint32_t)colsum[k];
                         int c4[4];
 #pragma unroll
                         for (int j = 0; j < 4; ++j) c4[j] = (int)((uint32_t)acc[i][nt][j] + t[j] - cs);
