@@ -90,7 +90,7 @@ int q8t_quantize_with_range(const float *x, int64_t n, int bits, int stochastic,
 size_t q8t_chunk_range_workspace_size(int64_t n, int K);
 int q8t_chunk_range(const float *x, int64_t n, int K, float *range_out, void *ws, void *stream);
 
-/* Angle between a tensor and its quantized copy (Section 3, eq. (1)):
+/* Angle between a tensor and its quantized copy (Section 5.1 (Problem Statement), eq. (1)):
  * cos(theta) = (x . Q(x)) / (||x||_2 ||Q(x)||_2), Q(x) = scale * (level - zero_point) of the stored
  * codes q (int8 for qp->bits <= 8, else int16; as q8t_dequantize returns them).
  * out: 4 device doubles { x.Q(x), ||x||^2, ||Q(x)||^2, cos(theta) } (cos = 0 if a norm is 0); sums

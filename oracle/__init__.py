@@ -137,7 +137,7 @@ def dequantize(stored, qp):
 
 
 def quant_angle(x, stored, qp):
-    """Sec. 3 eq. (1).  Returns (x.Q(x), |x|^2, |Q(x)|^2, cos(theta)) as fp64."""
+    """Sec. 5.1 (Problem Statement), eq. (1).  Returns (x.Q(x), |x|^2, |Q(x)|^2, cos(theta)) as fp64."""
     x = _f32(x)
     stored = np.ascontiguousarray(stored, dtype=_stored_dtype(qp.bits))
     assert x.size == stored.size

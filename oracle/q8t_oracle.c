@@ -210,7 +210,7 @@ void orc_dequantize(const void *stored, const orc_qparams *qp, int64_t n, float 
     }
 }
 
-/* Sec. 3, eq. (1): cosine of the angle between a tensor and its quantized copy,
+/* Sec. 5.1 (Problem Statement), eq. (1): cosine of the angle between a tensor and its quantized copy,
  * cos(theta) = (x . Q(x)) / (||x||_2 ||Q(x)||_2), with Q(x) the dequantized value of the stored
  * code (fp32, as orc_dequantize returns it).  All three sums in fp64, index order.
  * out[0] = x.Q(x), out[1] = ||x||^2, out[2] = ||Q(x)||^2, out[3] = cos(theta) (0 if a norm is 0). */

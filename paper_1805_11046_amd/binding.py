@@ -239,7 +239,7 @@ def chunk_range(x, K, ws=None):
 
 
 def quant_angle(x, q, qp, ws=None):
-    """Sec. 3 eq. (1).  Returns a device tensor of 4 doubles {x.Q(x), |x|^2, |Q(x)|^2, cos(theta)}."""
+    """Sec. 5.1 (Problem Statement), eq. (1).  Returns a device tensor of 4 doubles {x.Q(x), |x|^2, |Q(x)|^2, cos(theta)}."""
     _dev(x), _dev(q)
     n = x.numel()
     assert q.numel() == n

@@ -1,6 +1,6 @@
 // Two small reductions around the quantizer.
 //
-//  q8t_quant_angle   Sec. 3, eq. (1): cos(theta) = (x . Q(x)) / (||x|| ||Q(x)||) between a tensor and
+//  q8t_quant_angle   Sec. 5.1 (Problem Statement), eq. (1): cos(theta) = (x . Q(x)) / (||x|| ||Q(x)||) between a tensor and
 //                    the dequantized value of its stored codes; the paper's measure of how well a
 //                    quantizer preserves direction.  Three fp64 sums in one pass over x and q.
 //  q8t_chunk_range   App. B: clamping range of an activation tensor as the average, over K

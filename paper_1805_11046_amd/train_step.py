@@ -242,7 +242,7 @@ def main():
     ap.add_argument("--breakdown", action="store_true")
     ap.add_argument("--angles", action="store_true",
                     help="after the timing, one more step that reports the cosine between tensors and their "
-                         "quantized copies (Sec. 3 eq. (1)) per kind of tensor")
+                         "quantized copies (Sec. 5.1 (Problem Statement), eq. (1)) per kind of tensor")
     ap.add_argument("--no-fuse", action="store_true",
                     help="Range BN, ReLU and the next layer's quantization as separate passes")
     args = ap.parse_args()

@@ -1,4 +1,4 @@
-"""GPU parity: angle diagnostic (Sec. 3 eq. 1) and chunk-averaged clamping range (App. B)."""
+"""GPU parity: angle diagnostic (Sec. 5.1 eq. 1) and chunk-averaged clamping range (App. B)."""
 import numpy as np
 import pytest
 

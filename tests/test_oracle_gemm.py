@@ -68,6 +68,7 @@ def test_fc_float_outputs_and_library_matmul():
     assert np.array_equal(y, np.float32(px.scale * pw.scale) * acc.astype(np.float32))
     dx, acc = oracle.qgemm_dgrad(sg, pg, sw, pw)
     assert np.array_equal(acc, ag @ aw.T)
+    assert np.array_equal(dx, np.float32(pg.scale * pw.scale) * acc.astype(np.float32))
     dw, acc = oracle.qgemm_wgrad(sx, px, sg16, pg16)
     assert np.array_equal(acc, ax.T @ ag16)
     ref = (acc.astype(np.float64) * float(np.float32(pg16.scale * px.scale))).astype(np.float32)
@@ -189,6 +190,55 @@ def test_conv_gradients_against_pure_python_loops(case):
                                     ref_dw[k, c, r, s] += ag16[n, k, p, q] * ax[n, c, h, w]
     assert np.array_equal(dg, ref_dx)
     assert np.array_equal(wg, ref_dw)
+
+
+def _f32_product(sa, sb, acc):
+    """fl32(s_a*s_b) * (float)acc: the product of two fp32 scales is exact in double, so one cast
+    rounds it once; numpy's float32 multiply rounds the second product once."""
+    return np.float32(sa * sb) * acc.astype(np.float32)
+
+
+def _f64_product(sa, sb, acc):
+    """(float)((double)acc * (double)fl32(s_a*s_b))"""
+    return (acc.astype(np.float64) * float(np.float32(sa * sb))).astype(np.float32)
+
+
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_float_outputs_use_the_scales_of_their_own_operands(case):
+    # every operand gets its own scale, so a swapped or missing scale changes the result
+    g = np.random.default_rng(15)
+    d, (sx, ax, px), (sw, aw, pw), (sg, ag, pg), (sg16, ag16, pg16) = _conv_case(g, case)
+    assert len({px.scale, pw.scale, pg.scale, pg16.scale}) == 4
+    y, acc = oracle.qconv_fwd(d, sx, px, sw, pw)
+    assert np.array_equal(y, _f32_product(px.scale, pw.scale, acc))
+    dx, acc = oracle.qconv_dgrad(d, sg, pg, sw, pw)
+    assert np.array_equal(dx, _f32_product(pg.scale, pw.scale, acc))
+    dw, acc = oracle.qconv_wgrad(d, sx, px, sg16, pg16)
+    assert np.array_equal(dw, _f64_product(pg16.scale, px.scale, acc))
+
+
+def test_float_outputs_with_power_of_two_scales_are_exact_multiples():
+    # scales 1/2, 1/4, 1/8, 1/16: every float result is the accumulator times a power of two,
+    # i.e. the exact real value rounded to fp32 once (closed form)
+    g = np.random.default_rng(16)
+    case = (2, 3, 6, 5, 4, 3, 3, 1, 1)
+    d, (sx, ax, _), (sw, aw, _), (sg, ag, _), (sg16, ag16, _) = _conv_case(g, case)
+    px, pw, pg, pg16 = _qp(0.5, 7, 8), _qp(0.25, 130, 8), _qp(0.125, 99, 8), _qp(0.0625, 30000, 16)
+    y, acc = oracle.qconv_fwd(d, sx, px, sw, pw)
+    assert np.array_equal(y, (acc / 8.0).astype(np.float32))
+    dx, acc = oracle.qconv_dgrad(d, sg, pg, sw, pw)
+    assert np.array_equal(dx, (acc / 32.0).astype(np.float32))
+    dw, acc = oracle.qconv_wgrad(d, sx, px, sg16, pg16)
+    assert np.array_equal(dw, (acc / 32.0).astype(np.float32))
+    M, K, N = 6, 9, 5
+    fx, fw = sx.reshape(-1)[:M * K].reshape(M, K), sw.reshape(-1)[:K * N].reshape(K, N)
+    fg, fg16 = sg.reshape(-1)[:M * N].reshape(M, N), sg16.reshape(-1)[:M * N].reshape(M, N)
+    y, acc = oracle.qgemm_fwd(fx, px, fw, pw)
+    assert np.array_equal(y, (acc / 8.0).astype(np.float32))
+    dx, acc = oracle.qgemm_dgrad(fg, pg, fw, pw)
+    assert np.array_equal(dx, (acc / 32.0).astype(np.float32))
+    dw, acc = oracle.qgemm_wgrad(fx, px, fg16, pg16)
+    assert np.array_equal(dw, (acc / 32.0).astype(np.float32))
 
 
 def test_conv_1x1_is_a_plain_matrix_product():
