@@ -9,8 +9,10 @@
  *  - Every pointer is a DEVICE pointer unless the comment says "host".  The caller owns every
  *    buffer, including the workspace `ws` (size from the matching *_workspace_size query, 256-byte
  *    aligned; contents on entry are irrelevant, contents on return are unspecified).
- *  - The library allocates nothing, keeps no global state and never synchronizes the host: all
- *    work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *  - The library allocates nothing and never synchronizes the host: all work is enqueued on
+ *    `stream` (a hipStream_t passed as void*; NULL = the default stream).  The only state it keeps
+ *    between calls is, per device, the address of the static scratch array of q8t_quantize_noalloc
+ *    (looked up once, under a mutex); results never depend on earlier calls.
  *  - Float tensors are contiguous NCHW (conv / Range BN) or row-major (FC).
  *  - Quantized payloads are SIGNED: an M-bit level q in [0, 2^M-1] is stored as q - 2^(M-1),
  *    int8 for M <= 8 and int16 for 8 < M <= 16, in the same logical layout as the float source.
@@ -71,6 +73,24 @@ typedef struct {
 size_t q8t_quantize_workspace_size(int64_t n);
 int q8t_quantize(const float *x, int64_t n, int bits, int stochastic, uint64_t seed, void *q_out,
                  q8t_qparams *qp_out, void *ws, void *stream);
+
+/* For callers that cannot allocate device memory or carry a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): q8t_quantize with the (min,max) pairs of
+ * its first pass kept in a file-scope `static __device__` array of the library (8 KiB; every GPU the
+ * library runs on holds its own copy until the process ends) instead of a caller workspace.  Same
+ * arguments, checks and results as q8t_quantize, bit for bit.  Calls no hipMalloc / hipFree and no
+ * allocating routine.  n <= Q8T_NOALLOC_MAX_ELEMENTS, else Q8T_ERR_SHAPE (the scratch does not grow
+ * with n; the limit is that of the 32-bit group counter of the generator, as for q8t_quantize).
+ * The device that `stream` belongs to must be the current device.  All calls on one GPU share that
+ * GPU's array: the pairs a call reads are the ones it has just written (nothing needs to start at
+ * zero), but two calls that overlap in time on one GPU (different streams) race on it.
+ * q8t_init() looks up the array's device address for the current device (what the first call on a
+ * device does by itself); call it once per device before stream capture.  Returns Q8T_OK or
+ * Q8T_ERR_HIP. */
+#define Q8T_NOALLOC_MAX_ELEMENTS ((int64_t)1 << 34)
+int q8t_init(void);
+int q8t_quantize_noalloc(const float *x, int64_t n, int bits, int stochastic, uint64_t seed, void *q_out,
+                         q8t_qparams *qp_out, void *stream);
 
 /* Same, with the range supplied instead of searched: vmin_vmax points to 2 device floats
  * (Section 4: the range of an activation is already known to the preceding Range BN).  Values

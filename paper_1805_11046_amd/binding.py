@@ -48,6 +48,8 @@ _vp, _i, _i64, _u64, _f, _sz = C.c_void_p, C.c_int, C.c_int64, C.c_uint64, C.c_f
 _SIGS = {
     "q8t_quantize_workspace_size": (_sz, [_i64]),
     "q8t_quantize": (_i, [_vp, _i64, _i, _i, _u64, _vp, _vp, _vp, _vp]),
+    "q8t_init": (_i, []),
+    "q8t_quantize_noalloc": (_i, [_vp, _i64, _i, _i, _u64, _vp, _vp, _vp]),
     "q8t_quantize_with_range": (_i, [_vp, _i64, _i, _i, _u64, _vp, _vp, _vp, _vp]),
     "q8t_quantize_bifurcate": (_i, [_vp, _i64, _u64, _u64, _vp, _vp, _vp, _vp, _vp, _vp]),
     "q8t_dequantize": (_i, [_vp, _vp, _i64, _vp, _vp]),
@@ -152,6 +154,20 @@ def quantize(x, bits=8, stochastic=False, seed=0, q_out=None, qp_out=None, ws=No
     _check(_lib.q8t_quantize(_ptr(x), n, bits, int(bool(stochastic)), int(seed) & (2 ** 64 - 1), _ptr(q),
                              _ptr(qp), _ptr(ws), _stream()), "q8t_quantize")
     return q, qp
+
+
+def init():
+    """Per-device set-up of the allocation-free entry point (the current device)."""
+    _check(_lib.q8t_init(), "q8t_init")
+
+
+def quantize_noalloc(x, q_out, qp_out, bits=8, stochastic=False, seed=0):
+    """q8t_quantize without a workspace: the library's static scratch array holds the partial results.
+    The caller supplies every buffer; nothing is allocated here either."""
+    _dev(x)
+    _check(_lib.q8t_quantize_noalloc(_ptr(x), x.numel(), bits, int(bool(stochastic)), int(seed) & (2 ** 64 - 1),
+                                     _ptr(q_out), _ptr(qp_out), _stream()), "q8t_quantize_noalloc")
+    return q_out, qp_out
 
 
 def quantize_with_range(x, vmin_vmax, bits=8, stochastic=False, seed=0, q_out=None, qp_out=None):

@@ -8,6 +8,8 @@
 //                        every workgroup, so they all agree bit for bit), derives scale and zero
 //                        point, then quantizes its share: 4 elements -> one packed store.
 // HBM-bound: 9 algorithmic bytes per element for 8-bit output (4 read + 4 re-read + 1 written).
+#include <mutex>
+
 #include "q8t_common.h"
 #include "q8t_internal.h"
 
@@ -15,6 +17,14 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kMaxPartials = 1024;
+}  // namespace
+
+// Scratch of q8t_quantize_noalloc: the (min,max) pairs of pass 1.  Every GPU the library runs on
+// holds its own copy at its own address until the process ends.  In host code this name is only a
+// handle for hipGetSymbolAddress; kernels and copies take the per-device address kept below.
+static __device__ __align__(256) unsigned char scratch[sizeof(float2) * kMaxPartials];
+
+namespace {
 constexpr int kSmallThreads = 1024;
 constexpr int64_t kSmallN = 1 << 16;   // below this, one workgroup does both passes
 
@@ -339,9 +349,49 @@ int launch_minmax(const float *x, int64_t n, float2 *partials, hipStream_t st)
     return grid;
 }
 
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_addr[kMaxDevices];   // device address of `scratch` on each device, 0 = not asked yet
+
+// address of this device's copy of `scratch` (asked from the runtime once per device)
+int scratch_of_current_device(float2 **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return Q8T_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_addr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return Q8T_ERR_HIP;
+        g_scratch_addr[dev] = p;
+    }
+    *out = (float2 *)g_scratch_addr[dev];
+    return Q8T_OK;
+}
+
+int quantize_impl(const float *x, int64_t n, int bits, int stochastic, uint64_t seed, void *q_out,
+                  q8t_qparams *qp_out, float2 *partials, hipStream_t st);
+
 }  // namespace
 
 extern "C" {
+
+int q8t_init(void)
+{
+    float2 *p;
+    return scratch_of_current_device(&p);
+}
+
+int q8t_quantize_noalloc(const float *x, int64_t n, int bits, int stochastic, uint64_t seed, void *q_out,
+                         q8t_qparams *qp_out, void *stream)
+{
+    if (n < 0 || n > Q8T_NOALLOC_MAX_ELEMENTS) return Q8T_ERR_SHAPE;
+    if (bits < 2 || bits > 16) return Q8T_ERR_BITS;
+    if (!qp_out || (n > 0 && (!x || !q_out))) return Q8T_ERR_NULL;
+    float2 *partials;
+    const int rc = scratch_of_current_device(&partials);
+    if (rc) return rc;
+    return quantize_impl(x, n, bits, stochastic, seed, q_out, qp_out, partials, (hipStream_t)stream);
+}
 
 size_t q8t_quantize_workspace_size(int64_t n)
 {
@@ -356,7 +406,17 @@ int q8t_quantize(const float *x, int64_t n, int bits, int stochastic, uint64_t s
     if (bits < 2 || bits > 16) return Q8T_ERR_BITS;
     if (!qp_out || (n > 0 && (!x || !q_out))) return Q8T_ERR_NULL;
     if (!ws || !q8t_aligned(ws, 8)) return Q8T_ERR_WORKSPACE;
-    hipStream_t st = (hipStream_t)stream;
+    return quantize_impl(x, n, bits, stochastic, seed, q_out, qp_out, (float2 *)ws, (hipStream_t)stream);
+}
+
+}  // extern "C"
+
+namespace {
+
+// both passes of q8t_quantize / q8t_quantize_noalloc; arguments already checked
+int quantize_impl(const float *x, int64_t n, int bits, int stochastic, uint64_t seed, void *q_out,
+                  q8t_qparams *qp_out, float2 *partials, hipStream_t st)
+{
     if (n > 0 && n <= kSmallN) {
         const uint32_t lo = (uint32_t)seed, hi = (uint32_t)(seed >> 32);
 #define Q8T_SMALL(T, S, V) hipLaunchKernelGGL((quantize_small<T, S, V>), dim3(1), dim3(kSmallThreads), 0, st, x, (int)n, bits, lo, hi, (T *)q_out, qp_out)
@@ -372,13 +432,16 @@ int q8t_quantize(const float *x, int64_t n, int bits, int stochastic, uint64_t s
         Q8T_LAUNCH_CHECK();
         return Q8T_OK;
     }
-    float2 *partials = (float2 *)ws;
     const int np = launch_minmax(x, n, partials, st);
     Q8T_LAUNCH_CHECK();
     if (bits <= 8)
         return launch_apply<int8_t>(x, n, bits, stochastic, seed, partials, np, (int8_t *)q_out, qp_out, st);
     return launch_apply<int16_t>(x, n, bits, stochastic, seed, partials, np, (int16_t *)q_out, qp_out, st);
 }
+
+}  // namespace
+
+extern "C" {
 
 int q8t_quantize_with_range(const float *x, int64_t n, int bits, int stochastic, uint64_t seed,
                             const float *vmin_vmax, void *q_out, q8t_qparams *qp_out, void *stream)

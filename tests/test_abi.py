@@ -61,5 +61,7 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.q8t_quantize(None, 16, 8, 0, 0, None, None, None, None) == -1      # NULL
     assert L.q8t_quantize(None, -1, 8, 0, 0, None, None, None, None) == -2      # shape
     assert L.q8t_quantize(None, 16, 17, 0, 0, None, None, None, None) == -3     # bits
+    assert L.q8t_quantize_noalloc(None, (1 << 34) + 1, 8, 0, 0, None, None, None) == -2   # beyond the maximum
+    assert L.q8t_quantize_noalloc(None, 16, 8, 0, 0, None, None, None) == -1
     assert L.q8t_qgemm_fwd(None, None, None, None, 0, 1, 1, None, None, None, None) == -2
     assert L.q8t_range_bn_fwd(None, 1, 1, 1, 1, None, None, 0.0, None, None, None, None, None, None) == -2
