@@ -256,6 +256,14 @@ int q8t_range_bn_relu_bwd_bifurcate(const float *x, const float *dy, const float
 /* C(n) = 1/sqrt(2 ln n) (Section 3), host arithmetic in double.  n >= 2. */
 double q8t_range_bn_scale(int64_t n);
 
+/* Measurement aid, not a step of the method: a plain streaming kernel of known traffic with the access
+ * shape of the library's HBM-bound calls (every workgroup streams one contiguous slice, four 16-byte
+ * accesses in flight per lane).  mode 0: dst = src (bytes read and bytes written); mode 1: src is
+ * read only (dst receives 8 KiB of checksums, at most 32 KiB: size it >= 32 KiB); mode 2: dst is
+ * filled with zeros.  bytes: multiple of 16, >= 65536; src / dst: device, 16-byte aligned, must not
+ * overlap.  Errors: Q8T_ERR_SHAPE, Q8T_ERR_NULL, Q8T_ERR_HIP. */
+int q8t_probe_stream(int mode, const void *src, void *dst, int64_t bytes, void *stream);
+
 /* Library version string (host pointer, static storage). */
 const char *q8t_version(void);
 

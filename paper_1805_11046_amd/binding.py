@@ -77,6 +77,7 @@ _SIGS = {
     "q8t_range_bn_bwd_bifurcate_workspace_size": (_sz, [_i, _i, _i, _i]),
     "q8t_range_bn_bwd_bifurcate": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _f, _vp, _vp, _vp, _u64, _u64, _vp, _vp,
                                         _vp, _vp, _vp, _vp]),
+    "q8t_probe_stream": (_i, [_i, _vp, _vp, _i64, _vp]),
     "q8t_range_bn_scale": (C.c_double, [_i64]),
     "q8t_version": (C.c_char_p, []),
 }
@@ -137,6 +138,11 @@ def qparams_to_host(qp):
 
 def version():
     return _lib.q8t_version().decode()
+
+
+def probe_stream(mode, src, dst, nbytes):
+    """Plain streaming kernel of known traffic (0 copy, 1 read only, 2 fill); see q8t.h."""
+    _check(_lib.q8t_probe_stream(int(mode), _ptr(src), _ptr(dst), int(nbytes), _stream()), "q8t_probe_stream")
 
 
 def range_bn_scale(n):

@@ -4,22 +4,25 @@
 // Section 4, eq. (grad_layer)).
 //
 // GEMM view: rows = flattened (image, y, x) output positions, cols = output channels,
-// reduction = (tap, input channel).  Per workgroup: 256 consecutive rows x 64 output channels,
-// 4 wavefronts of 64x64 (4x4 v_mfma_i32_16x16x64_i8 tiles); one MFMA K-step = one filter tap over
-// 64 input channels.
+// reduction = (tap, input channel); one MFMA K-step (v_mfma_i32_16x16x64_i8) = one filter tap over
+// 64 input channels.  Persistent workgroups of 8 wavefronts own contiguous row ranges and walk them
+// in sub-tiles of 256 rows x 64 output channels (two 16-row m-tiles per wavefront), the next
+// sub-tile's activations prefetched into registers while the current one is multiplied.
 //
-// Data movement (the kernel is HBM-bound for 64-channel layers: 1 byte in, 4 bytes out per element):
+// Data movement (64-channel layers move 1 byte in and 4 bytes out per element; what bounds the
+// kernel in practice is instruction issue: staging, transposition and epilogue outweigh the MFMAs):
 //  * activations are NCHW int8, but MFMA wants the reduction index contiguous per lane, so the
-//    tile (with its halo of W+1 positions on either side) is transposed on the way into LDS:
-//    each lane loads 4 positions x 4 channels as 4 dwords, transposes 4x4 bytes with v_perm and
-//    writes [position][channel] rows of 80 bytes (64 + 16 pad: 16-byte aligned, conflict-free
-//    ds_read_b128 for the A fragments);
-//  * a tap is a row offset into that tile; taps that fall outside the image are replaced by the
-//    operand's zero point per lane (border predicates), so padding contributes exactly nothing;
+//    tile (with its halo) is transposed on the way into LDS: each lane loads 16 positions x 4
+//    channels as four 16-byte loads, transposes 4x4 bytes with v_perm and writes
+//    [position][channel] rows of 80 bytes (64 + 16 pad: conflict-free ds_read_b128 fragments);
+//  * LDS rows use padded coordinates: one row holding the operand's zero point after every image row
+//    and between images, so a tap is a constant row offset and padding needs no per-lane masks
+//    (a padded tap contributes exactly nothing to the corrected accumulator);
 //  * weights are repacked once per call into [tap][out-channel][in-channel] (and their per-channel
-//    sums taken) by a small pre-pass; row sums of A come from v_dot4 on the fragments already in
-//    registers.  Epilogue: zero-point correction, dequantization, float4 stores (4 consecutive
-//    positions of one output channel per lane).
+//    sums taken) by a small pre-pass; row sums of A come from one extra MFMA per m-tile and tap
+//    against an all-ones operand, which delivers them in the accumulator layout.  Epilogue:
+//    zero-point correction, dequantization, float4 stores (4 consecutive positions of one output
+//    channel per lane); the STATS variant also folds the exact integer sum / min / max per channel.
 #include <type_traits>
 
 #include "q8t_common.h"
@@ -564,13 +567,10 @@ int launch_conv(dim3 grid, hipStream_t st, const int8_t *a, const int8_t *wpk, c
                 const q8t_qparams *qa, const q8t_qparams *qb, const FastGeom &g, const Sched &sch, float *out_f,
                 int32_t *out_acc, ConvStat *bnpart)
 {
-    static bool attr = false;
-    if (!attr && smem_bytes<TAPS>() > 65536) {
-        if (hipFuncSetAttribute((const void *)conv_s1_kernel<TAPS, WC, V16, STATS>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)smem_bytes<TAPS>()) != hipSuccess)
-            return Q8T_ERR_HIP;
-        attr = true;
-    }
+    static Q8tLdsOptIn optin;
+    if (smem_bytes<TAPS>() > 65536 &&
+        q8t_allow_lds(optin, (const void *)conv_s1_kernel<TAPS, WC, V16, STATS>, smem_bytes<TAPS>()) != Q8T_OK)
+        return Q8T_ERR_HIP;
     hipLaunchKernelGGL((conv_s1_kernel<TAPS, WC, V16, STATS>), grid, dim3(kThreads), smem_bytes<TAPS>(), st, a, wpk, colsum, qa,
                        qb, g, sch, out_f, out_acc, bnpart);
     Q8T_LAUNCH_CHECK();

@@ -1302,13 +1302,9 @@ int q8t_nhwc_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
         const int pairM = cg.v[0][2];   // class (0, 0) is the larger row parity
 #define Q8T_GOP(CFG)                                                                                                 \
     {                                                                                                                \
-        static bool attr = false;                                                                                    \
-        if (!attr && conv_pair_lds_bytes<CFG>() > 65536) {                                                           \
-            if (hipFuncSetAttribute((const void *)igemm_nhwc_pair<CFG>, hipFuncAttributeMaxDynamicSharedMemorySize,  \
-                                    (int)conv_pair_lds_bytes<CFG>()) != hipSuccess)                                  \
-                return Q8T_ERR_HIP;                                                                                  \
-            attr = true;                                                                                             \
-        }                                                                                                            \
+        static Q8tLdsOptIn optin;                                                                                    \
+        if (conv_pair_lds_bytes<CFG>() > 65536 && q8t_allow_lds(optin, (const void *)igemm_nhwc_pair<CFG>, conv_pair_lds_bytes<CFG>()) != Q8T_OK)      \
+            return Q8T_ERR_HIP;                                                                                      \
         g.mtiles = (pairM + CFG::BM - 1) / CFG::BM;                                                                  \
         const int64_t tiles = (int64_t)g.mtiles * 2 * (p.oc / CFG::BN);                                              \
         hipLaunchKernelGGL(igemm_nhwc_pair<CFG>, dim3(q8t_gemm::xcd_grid(tiles)), dim3(CFG::THREADS),                \
@@ -1325,13 +1321,9 @@ int q8t_nhwc_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
     // else 128 x 128, else 128 x 64
 #define Q8T_GO(CFG)                                                                                                  \
     {                                                                                                                \
-        static bool attr = false;                                                                                    \
-        if (!attr && conv_lds_bytes<CFG>() > 65536) {                                                                \
-            if (hipFuncSetAttribute((const void *)igemm_nhwc<CFG>, hipFuncAttributeMaxDynamicSharedMemorySize,       \
-                                    (int)conv_lds_bytes<CFG>()) != hipSuccess)                                       \
-                return Q8T_ERR_HIP;                                                                                  \
-            attr = true;                                                                                             \
-        }                                                                                                            \
+        static Q8tLdsOptIn optin;                                                                                    \
+        if (conv_lds_bytes<CFG>() > 65536 && q8t_allow_lds(optin, (const void *)igemm_nhwc<CFG>, conv_lds_bytes<CFG>()) != Q8T_OK)      \
+            return Q8T_ERR_HIP;                                                                                      \
         g.mtiles = (maxM + CFG::BM - 1) / CFG::BM;                                                                   \
         const int64_t tiles = (int64_t)g.mtiles * ncls * (p.oc / CFG::BN);                                         \
         if (tiles > 0)                                                                                               \

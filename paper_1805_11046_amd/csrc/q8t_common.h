@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "q8t.h"
 
 #define Q8T_WAVE 64
@@ -13,6 +15,24 @@
     } while (0)
 
 static inline bool q8t_aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+// A kernel that wants more than 64 KB of dynamic LDS has to be given a higher limit first.  One
+// flag per kernel (a function-local static at the launch site) remembers, per device, that this
+// was done: atomic, so host threads may race here, and raising the limit twice is harmless.
+struct Q8tLdsOptIn {
+    std::atomic<uint64_t> done{0};
+};
+static inline int q8t_allow_lds(Q8tLdsOptIn &flag, const void *kernel, size_t bytes)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return Q8T_ERR_HIP;
+    const uint64_t bit = (uint64_t)1 << (dev & 63);
+    if (flag.done.load(std::memory_order_acquire) & bit) return Q8T_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess)
+        return Q8T_ERR_HIP;
+    flag.done.fetch_or(bit, std::memory_order_release);
+    return Q8T_OK;
+}
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains every global load
 // in flight (s_waitcnt vmcnt(0)), which serialises a software pipeline that prefetches the next

@@ -784,13 +784,8 @@ template <int WC>
 int launch_wgrad(int blocks, hipStream_t st, const int16_t *g16, const int8_t *x, const q8t_qparams *qg,
                  const q8t_qparams *qx, const WGeom &g, int *ws)
 {
-    static bool attr = false;
-    if (!attr) {
-        if (hipFuncSetAttribute((const void *)wgrad_s1_3x3<WC>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                SMEM_BYTES) != hipSuccess)
-            return Q8T_ERR_HIP;
-        attr = true;
-    }
+    static Q8tLdsOptIn optin;
+    if (q8t_allow_lds(optin, (const void *)wgrad_s1_3x3<WC>, SMEM_BYTES) != Q8T_OK) return Q8T_ERR_HIP;
     hipLaunchKernelGGL(wgrad_s1_3x3<WC>, dim3(blocks), dim3(kThreads), SMEM_BYTES, st, g16, x, qg, qx, g, ws);
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
@@ -800,13 +795,8 @@ template <int WC>
 int launch_wgrad_v2(int blocks, hipStream_t st, const int16_t *g16, const int8_t *x, const q8t_qparams *qg,
                     const q8t_qparams *qx, const WGeom &g, int *ws)
 {
-    static bool attr = false;
-    if (!attr) {
-        if (hipFuncSetAttribute((const void *)wgrad_s1_3x3_v2<WC>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                SMEM2_BYTES) != hipSuccess)
-            return Q8T_ERR_HIP;
-        attr = true;
-    }
+    static Q8tLdsOptIn optin;
+    if (q8t_allow_lds(optin, (const void *)wgrad_s1_3x3_v2<WC>, SMEM2_BYTES) != Q8T_OK) return Q8T_ERR_HIP;
     hipLaunchKernelGGL(wgrad_s1_3x3_v2<WC>, dim3(blocks), dim3(kThreads), SMEM2_BYTES, st, g16, x, qg, qx, g, ws);
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;

@@ -29,22 +29,42 @@ import torch.nn.functional as F
 
 from . import binding as q8t
 
-_breakdown = False
+_breakdown = False   # time every library call with events
+_bracket = None      # or only the calls of this entry point
 _fuse = True
 _angles = None   # with --angles: {kind: [cosines]} of tensors against their quantized copies
 
 
-def _call(name, ops, nbytes, fn, *a, **k):
-    """Run one library call; with --breakdown also time it and book its integer operations and
-    algorithmic bytes under `name`."""
-    if not _breakdown:
+def _call(name, ops, nbytes, fn, *a, tag="", **k):
+    """Run one library call; with --breakdown (or for the one entry point being bracketed) also time
+    it with events on the launch stream and book its integer operations and algorithmic bytes under
+    `name` (and `tag`, the layer it belongs to)."""
+    if not (_breakdown or _bracket == name):
         return fn(*a, **k)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     r = fn(*a, **k)
     e1.record()
-    _pending.append((name, ops, nbytes, e0, e1))
+    _pending.append((name, tag, ops, nbytes, e0, e1))
     return r
+
+
+def record(breakdown=False, bracket=None):
+    """Switch the event timing of library calls on or off (see _call)."""
+    global _breakdown, _bracket
+    _breakdown, _bracket = breakdown, bracket
+
+
+def drain():
+    """The (name, tag, ops, bytes, microseconds) records collected since the last drain (synchronizes)."""
+    torch.cuda.synchronize()
+    out = [(n, t, o, b, e0.elapsed_time(e1) * 1e3) for n, t, o, b, e0, e1 in _pending]
+    del _pending[:]
+    return out
+
+
+def _tag(d):
+    return "%dx%d%s %d->%d @%d" % (d.R, d.S, "/%d" % d.stride if d.stride > 1 else "", d.C, d.K, d.H)
 
 
 def _angle(kind, t, q, qp):
@@ -89,7 +109,7 @@ class ConvBN(torch.autograd.Function):
         qw, pw = _quantize("quantize (weights)", w)
         ops = 2.0 * n * d.P * d.Q * k * c * r * s
         nx, ny = a.numel(), n * k * d.P * d.Q
-        y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw)
+        y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw, tag=_tag(d))
         bn, _, _ = _call("range_bn_fwd_apply", 0, 8 * ny, q8t.range_bn_fwd_apply, y, stats, None, None, 1e-5)
         ctx.saved = (d, qa, pa, qw, pw, y, stats, need_dx, ops, nx, ny)
         return bn
@@ -102,8 +122,8 @@ class ConvBN(torch.autograd.Function):
                                               stats, None, 1e-5, _seed[0], _seed[0] + 1)
         dx = None
         if need_dx:
-            dx, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw)
-        dw, _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16)
+            dx, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d))
+        dw, _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
         return dx, dw, None, None, None
 
 
@@ -126,7 +146,7 @@ class ConvChain(torch.autograd.Function):
             qw, pw = _quantize("quantize (weights)", w)
             ops = 2.0 * n * d.P * d.Q * k * c * r * s
             nx, ny = n * c * h * wd, n * k * d.P * d.Q
-            y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw)
+            y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw, tag=_tag(d))
             saved.append((d, qa, pa, qw, pw, y, stats, ops, nx, ny))
             if i + 1 < len(ws):
                 _, qa, pa = _call("range_bn_relu_fwd_apply (int8 out)", 0, 5 * ny, q8t.range_bn_relu_fwd_apply, y, stats,
@@ -154,8 +174,8 @@ class ConvChain(torch.autograd.Function):
             g8, pg8, g16, pg16 = r[3:]
             g = None
             if i > 0 or need_dx:
-                g, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw)
-            dws[i], _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16)
+                g, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d))
+            dws[i], _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
         return (g, None, None, *dws)
 
 
@@ -300,7 +320,7 @@ def main():
         one()
         torch.cuda.synchronize()
         acc = collections.defaultdict(lambda: [0.0, 0.0, 0.0, 0])
-        for name, ops, nbytes, e0, e1 in _pending:
+        for name, _, ops, nbytes, e0, e1 in _pending:
             a = acc[name]
             a[0] += e0.elapsed_time(e1)
             a[1] += ops
