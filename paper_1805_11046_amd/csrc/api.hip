@@ -77,7 +77,11 @@ size_t q8t_qconv_workspace_size(const q8t_conv_desc *desc, int which)
     if (!desc || which < 0 || which > 2) return 0;
     size_t g = q8t_generic_conv_ws(which, desc);
     size_t f = q8t_fast_conv_ws(which, desc);
-    if (which == 2) f = q8t_fast_wgrad_ws(desc);
+    if (which == 2) {
+        f = q8t_fast_wgrad_ws(desc);
+        const size_t pw = q8t_planes_wgrad_ws(desc);
+        if (pw > f) f = pw;
+    }
     size_t h = which < 2 ? q8t_nhwc_conv_ws(which, desc) : (wgrad_wants_gemm(desc) ? q8t_gemm_wgrad_ws(desc) : 0);
     if (smallc_wanted(which, desc)) h = q8t_smallc_conv_ws(which, desc);
     if (h > g) g = h;
@@ -143,6 +147,8 @@ int q8t_qconv_wgrad(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qpara
     if (!desc || !qx || !px || !qdy16 || !pg16 || (!dw && !acc_out)) return Q8T_ERR_NULL;
     const int rc = q8t_conv_reduction_check(2, desc);
     if (rc) return rc;
+    if (q8t_planes_wgrad_supported(desc, qdy16, qx, dw, acc_out))
+        return q8t_planes_wgrad(desc, qdy16, pg16, qx, px, dw, acc_out, ws, (hipStream_t)stream);
     if (q8t_fast_wgrad_supported(desc, qdy16, qx, dw, acc_out))
         return q8t_fast_wgrad(desc, qdy16, pg16, qx, px, dw, acc_out, ws, (hipStream_t)stream);
     if (wgrad_wants_gemm(desc))

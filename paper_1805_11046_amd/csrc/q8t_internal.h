@@ -52,3 +52,11 @@ size_t q8t_gemm_wgrad_ws(const q8t_conv_desc *d);
 int q8t_gemm_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams *qg, const int8_t *x,
                    const q8t_qparams *qx, float *dw, int64_t *acc_out, void *ws, hipStream_t st);
 
+
+// weight gradient of 3x3 convolutions with 14x14 or 7x7 result planes, stride 1 or 2: padded planes in
+// LDS, no operand rewritten in HBM (wgrad_planes.hip)
+bool q8t_planes_wgrad_supported(const q8t_conv_desc *d, const void *g16, const void *x, const void *dw,
+                                const void *acc);
+size_t q8t_planes_wgrad_ws(const q8t_conv_desc *d);
+int q8t_planes_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams *qg, const int8_t *x,
+                     const q8t_qparams *qx, float *dw, int64_t *acc_out, void *ws, hipStream_t st);

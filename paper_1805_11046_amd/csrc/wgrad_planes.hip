@@ -1,0 +1,537 @@
+// Weight gradient of 3x3 convolutions whose result planes are 14x14 or 7x7 (stride 1 or 2, pad 1):
+//   dW[k,c,r,s] = sum_{n,p,q} g16[n,k,p,q] * x8[n,c,p*st+r-1,q*st+s-1]      (Section 4, eq. (grad_weight))
+// with the 16-bit copy of the gradient (Sections 1, 7) and the 8-bit layer input, exact in integers.
+//
+// GEMM view: rows = output channel k (two byte planes: s = 256*hi + lo + 128), cols = (input
+// channel c, tap), reduction = (image, position).  Both operands are contiguous along the
+// reduction in NCHW, so nothing is transposed; no operand is rewritten in HBM.
+//
+// Padded planes.  Inside LDS a 14x14 plane is a 16x16 block of bytes (7x7: 8x8): pad columns, then
+// the data of an image row, and pad rows after the last image row, all pads holding the operand's
+// zero point.  A chunk of the reduction is 256 such padded positions (one 14x14 plane or four 7x7
+// planes) = 8 MFMA K-steps of 32.  In these coordinates a filter tap is a byte offset; the pad
+// before one row is the pad after the previous one, and the pad rows of one plane separate it from
+// the next one.  Staging writes data positions only, the pads are set once per workgroup.
+//   * the vertical tap is an offset of +-pitch on the input operand (aligned 16-byte LDS reads for
+//     pitch 16, 8-byte reads for pitch 8);
+//   * the horizontal tap is moved to the gradient operand (p' = p + s - 1), whose fragment is
+//     shifted by one byte with v_alignbyte: two aligned reads instead of an unaligned one;
+//   * stride 2: the input plane (2P x 2P) is de-interleaved into its four (row parity, column
+//     parity) classes while it is staged; every tap then reads one class at offset 0 or -1 in
+//     either direction, the same structure as stride 1.
+// Because position 0 and the last position of a chunk are pads and the margins of a row hold zero
+// codes, the row sums of the gradient do not depend on the shift; the column sums of the input
+// depend on the vertical offset (one per variant of the input fragment).
+//
+// What bounds kernels of this kind on gfx950 is the number of instructions a wavefront issues per
+// MFMA, so the product runs on v_mfma_i32_32x32x32_i8 (twice the work per instruction and per
+// fragment of v_mfma_i32_16x16x64_i8) with a register tile that reuses every fragment three times:
+// a wavefront holds 32 rows x 32 channels x 9 taps of one byte plane = 9 accumulator tiles (144
+// registers, all of them in the accumulation registers), fed per K-step by one gradient read
+// (shifted twice in registers) and 3 (stride 2: 6) input reads.  A workgroup is eight wavefronts
+// (row half, byte plane, channel half), two per SIMD: 64 output channels x 64 input channels and a
+// range of images.  Row and column sums for the zero-point correction are v_dot4 on fragments,
+// dealt out over the wavefronts that share them.  Partial sums
+// per image range are int32 (a range stays below the 32-bit bound) and are combined in int64 by
+// wgrad_planes_finish together with the zero-point correction and the dequantization.
+#include <type_traits>
+
+#include "q8t_common.h"
+#include "q8t_internal.h"
+
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kThreads = 512;
+constexpr int KC = 256;                 // padded positions per chunk (8 K-steps of 32)
+constexpr int LEFT = 16;                // bytes before the chunk in an LDS row (margin / halo)
+constexpr int ROWP = 336;               // LDS bytes per operand row: 16 + 256 + 16 and a spare 48, so that the pitch is
+                                        // 84 dwords = 20 mod 64: 16 rows of 16-byte fragments fall into 16 distinct bank groups
+constexpr int KT = 64;                  // output channels per workgroup
+constexpr int CT = 64;                  // input channels per workgroup
+
+struct PGeom {
+    int N, C, K;
+    int S, ipr;      // image ranges, images per range (a multiple of the images per chunk)
+    int nrg, ncg;    // row groups (K/64), channel groups (C/64)
+};
+
+template <int P_, int STRIDE_>
+struct Shape {
+    static constexpr int P = P_, STRIDE = STRIDE_;
+    static constexpr int PT = P == 14 ? 16 : 8;          // padded row pitch
+    static constexpr int LEADC = PT - P;                 // pad columns, at the start of a row (so that position 0 is a pad)
+    static constexpr int PL = PT * PT;                   // padded positions per plane
+    static constexpr int NIMG = KC / PL;                 // planes per chunk
+    static constexpr int TAPS = 9;
+    static constexpr int NCLS = STRIDE == 1 ? 1 : 4;     // parity classes of the input plane
+    static constexpr int NBV = STRIDE == 1 ? 3 : 6;      // distinct input fragments per K-step
+    static constexpr int NAS = STRIDE == 1 ? 3 : 2;      // distinct shifts of the gradient fragment
+    static constexpr int WIN = P * STRIDE;               // input plane edge
+    static constexpr int A_BYTES = 2 * KT * ROWP;
+    static constexpr int CLSB = CT * ROWP;               // bytes of one parity class
+    static constexpr int B_BYTES = NCLS * CLSB;
+    static constexpr int BUF = A_BYTES + B_BYTES;
+    static constexpr bool DB = STRIDE == 1;              // two LDS buffers (stride 2: the four classes leave room for one)
+    static constexpr int SMEM = (DB ? 2 : 1) * BUF;
+    static constexpr int HALF_INTS = 4 * TAPS * 16 * 64;     // accumulators of one byte plane: [row half][channel half][tap][reg][lane]
+    static constexpr int TILE_INTS = 2 * HALF_INTS;
+    static constexpr int PART_INTS = TILE_INTS + NBV * CT + 2 * KT;   // + column sums [variant][ch] + row sums [plane][row]
+    static constexpr int CSW = (NBV + 3) / 4;            // column sums gathered per wavefront (variants 4i + its index among the four that share a channel half)
+
+    // tap t = 3r + s -> variant of the input fragment, shift index of the gradient fragment
+    //   stride 1: variant r (offset (r-1)*PT), gradient g[p' - (s-1)]: shift index s = {+1, 0, -1}
+    //   stride 2: input row 2p+r-1 -> (parity, offset) r=0:(1,-PT) r=1:(0,0) r=2:(1,0); column likewise
+    //             s=0:(1,-1) s=1:(0,0) s=2:(1,0); the -1 moves to the gradient as g[p'+1]: shift index {+1, 0}
+    static __host__ __device__ constexpr int bvar(int t) { return STRIDE == 1 ? t / 3 : (t / 3) * 2 + (((t % 3) & 1) ? 0 : 1); }
+    static __host__ __device__ constexpr int ashift(int t) { return STRIDE == 1 ? t % 3 : ((t % 3) == 0 ? 0 : 1); }
+    static __host__ __device__ constexpr int bcls(int v) { return STRIDE == 1 ? 0 : ((v >> 1) == 1 ? 0 : 2) + (v & 1); }
+    static __host__ __device__ constexpr int boff(int v) { return STRIDE == 1 ? (v - 1) * PT : ((v >> 1) == 0 ? -PT : 0); }
+};
+
+__device__ __forceinline__ int dot4_ones(int v, int acc) { return __builtin_amdgcn_sdot4(v, 0x01010101, acc, false); }
+
+template <class SH>
+__global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restrict__ g16, const int8_t *__restrict__ x,
+                                                         const q8t_qparams *__restrict__ qpg,
+                                                         const q8t_qparams *__restrict__ qpx, PGeom g,
+                                                         int *__restrict__ partial)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    constexpr int P = SH::P, PT = SH::PT, PL = SH::PL, NIMG = SH::NIMG, TAPS = SH::TAPS;
+    constexpr int NBV = SH::NBV, NAS = SH::NAS, WIN = SH::WIN, STRIDE = SH::STRIDE;
+    constexpr int PP = P * P, WW = WIN * WIN;
+    constexpr int G_U4 = KT * PP * 2 / 16, X_U4 = CT * WW / 16;            // 16-byte pieces of one image's tiles
+    constexpr int GS = (G_U4 + kThreads - 1) / kThreads, XS = (X_U4 + kThreads - 1) / kThreads;
+    constexpr int GPC = P == 14 ? 4 : 8;                                    // LDS pieces per 16 bytes of gradient
+    constexpr int XPC = STRIDE == 1 ? (P == 14 ? 8 : 16) : (P == 14 ? 4 : 8);
+    constexpr int NPART = 4;                                                // staging is spread over 4 of the 8 K-steps
+    static_assert(G_U4 * 16 == KT * PP * 2 && X_U4 * 16 == CT * WW, "tiles are whole 16-byte pieces");
+
+    // XCD-aware decode (workgroup b runs on XCD b % 8): every XCD gets a contiguous run of the
+    // (image range, tile pair) list, so workgroups that share an image range, and with it their
+    // operands, share an L2, and all XCDs are busy whatever the number of ranges
+    const int per = g.ncg * g.nrg;
+    const int wi = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    if (wi >= g.S * per) return;
+    const int kr = wi / per, sub = wi - kr * per;
+    const int cg = sub % g.ncg, rg = sub / g.ncg;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r32 = lane & 31, kh = lane >> 5;    // row (or channel) of the lane's fragment, its 16-byte half of the K-step
+    const int kt = wave & 1, pl = (wave >> 1) & 1, ch = wave >> 2;   // row half (32 output channels), byte plane, channel half (32 input channels)
+
+    const int zsg = qpg->zero_point - (1 << (qpg->bits - 1)), zsx = qpx->zero_point - (1 << (qpx->bits - 1));
+    const uint32_t a_pad = (uint32_t)(zsg & 0xFFFF) * 0x00010001u;   // two zero codes of the gradient
+    const uint32_t b_pad = (uint32_t)(zsx & 255) * 0x01010101u;
+
+    // ---- pads, margins and halos: every byte of the buffers starts as its operand's zero code ----
+    {
+        const uint32_t hi4 = (uint32_t)((zsg >> 8) & 255) * 0x01010101u;
+        const uint32_t lo4 = (uint32_t)((zsg & 255) ^ 0x80) * 0x01010101u;
+        for (int i = tid; i < SH::SMEM / 16; i += kThreads) {
+            const int o = (i * 16) % SH::BUF;
+            const uint32_t v = o < KT * ROWP ? hi4 : (o < SH::A_BYTES ? lo4 : b_pad);
+            *reinterpret_cast<uint4 *>(&smem[i * 16]) = make_uint4(v, v, v, v);
+        }
+    }
+
+    // ---- per-thread staging plan: LDS byte offsets of the pieces of its 16-byte loads (per image) ----
+    // gradient: offset of the high byte plane inside the A region; the low plane is KT rows further
+    uint32_t ga[GS][GPC / 2];
+#pragma unroll
+    for (int s = 0; s < GS; ++s)
+#pragma unroll
+        for (int q = 0; q < GPC; q += 2) {
+            uint32_t pk = 0;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int e = 8 * (tid + kThreads * s) + (P == 14 ? 2 : 1) * (q + h);   // value index in [KT][PP]
+                const int row = e / PP, pos = e - row * PP, y = pos / P, xq = pos - y * P;
+                pk |= (uint32_t)((row * ROWP + LEFT + y * PT + SH::LEADC + xq) & 0xFFFF) << (16 * h);
+            }
+            ga[s][q / 2] = pk;
+        }
+    // input: offset inside the B region (stride 2: of the even-column class of the piece's row parity)
+    uint32_t xa[XS][XPC / 2];
+#pragma unroll
+    for (int s = 0; s < XS; ++s)
+#pragma unroll
+        for (int q = 0; q < XPC; q += 2) {
+            uint32_t pk = 0;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int e = 16 * (tid + kThreads * s) + (16 / XPC) * (q + h);         // byte index in [CT][WW]
+                const int c = e / WW, pos = e - c * WW, y = pos / WIN, xq = pos - y * WIN;
+                int o;
+                if (STRIDE == 1) o = c * ROWP + LEFT + y * PT + SH::LEADC + xq;
+                else o = c * ROWP + LEFT + (y >> 1) * PT + SH::LEADC + (xq >> 1) + ((y & 1) << 15);   // bit 15: odd input row
+                pk |= (uint32_t)(o & 0xFFFF) << (16 * h);
+            }
+            xa[s][q / 2] = pk;
+        }
+    static_assert(CT * ROWP <= 32768, "bit 15 of a packed input offset is the row parity");
+    const bool g_last = tid + kThreads * (GS - 1) < G_U4, x_last = tid + kThreads * (XS - 1) < X_U4;
+
+    const int img0 = kr * g.ipr, img1 = min(g.N, img0 + g.ipr);
+    const int units = (img1 - img0 + NIMG - 1) / NIMG;
+
+    v16i acc[TAPS];
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[t][j] = 0;
+    int rsum = 0, csum[SH::CSW];
+#pragma unroll
+    for (int i = 0; i < SH::CSW; ++i) csum[i] = 0;
+
+    uint4 rgr[NIMG * GS], rxr[NIMG * XS];
+    const uint4 *gsrc = reinterpret_cast<const uint4 *>(g16 + ((int64_t)img0 * g.K + rg * KT) * PP);
+    const uint4 *xsrc = reinterpret_cast<const uint4 *>(x + ((int64_t)img0 * g.C + cg * CT) * WW);
+    const int64_t gstep = (int64_t)g.K * PP * 2 / 16, xstep = (int64_t)g.C * WW / 16;   // 16-byte pieces per image
+    int l_img = img0;                      // first image of the chunk that is being loaded
+    // The 16-byte pieces that write_part(., part) puts into LDS, for the chunk starting at image l_img.
+    // Every load is issued unconditionally (straight-line code lets the compiler wait for exactly the
+    // loads it needs instead of for all of them): a thread without a piece in its last slot reads
+    // piece 0 of the tile, an image past the range re-reads the chunk's first image, and neither is
+    // used.  Every index stays inside the tile of an image of the range.
+    const int g_lastoff = g_last ? tid + (GS - 1) * kThreads : 0, x_lastoff = x_last ? tid + (XS - 1) * kThreads : 0;
+    auto load_part = [&](int part) {
+#pragma unroll
+        for (int i = 0; i < NIMG * GS; ++i)
+            if (i % NPART == part) {
+                const int m = i / GS, sl = i % GS;
+                const bool have = m == 0 || l_img + m < img1;
+                const uint4 v = gsrc[(have ? m * gstep : 0) + (sl < GS - 1 ? tid + sl * kThreads : g_lastoff)];
+                rgr[i] = have ? v : make_uint4(a_pad, a_pad, a_pad, a_pad);
+            }
+#pragma unroll
+        for (int i = 0; i < NIMG * XS; ++i)
+            if ((i + 2) % NPART == part) {
+                const int m = i / XS, sl = i % XS;
+                const bool have = m == 0 || l_img + m < img1;
+                const uint4 v = xsrc[(have ? m * xstep : 0) + (sl < XS - 1 ? tid + sl * kThreads : x_lastoff)];
+                rxr[i] = have ? v : make_uint4(b_pad, b_pad, b_pad, b_pad);
+            }
+    };
+    // the chunk after this one, or this one again when it is the last (its reload is never used)
+    auto next_chunk = [&]() {
+        const bool more = l_img + NIMG < img1;
+        gsrc += more ? NIMG * gstep : 0;
+        xsrc += more ? NIMG * xstep : 0;
+        l_img += more ? NIMG : 0;
+    };
+    auto comp = [](const uint4 &v, int i) -> uint32_t { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; };
+    // one staged 16-byte piece of the gradient -> the two byte planes in LDS
+    auto write_g = [&](uint8_t *A, int m, int s) {
+        if (!(s < GS - 1 || g_last)) return;
+        const uint4 v = rgr[m * GS + s];
+        uint8_t *Am = A + m * PL;
+#pragma unroll
+        for (int q = 0; q < GPC; ++q) {
+            const uint32_t o = (ga[s][q / 2] >> (16 * (q & 1))) & 0xFFFFu;
+            if (P == 14) {     // two values: both high bytes, both low bytes (flipped: lo - 128)
+                const uint32_t d = comp(v, q) ^ 0x00800080u;
+                *reinterpret_cast<uint16_t *>(Am + o) = (uint16_t)__builtin_amdgcn_perm(0u, d, 0x0C0C0301u);
+                *reinterpret_cast<uint16_t *>(Am + o + KT * ROWP) = (uint16_t)__builtin_amdgcn_perm(0u, d, 0x0C0C0200u);
+            } else {
+                const uint32_t d = (comp(v, q >> 1) ^ 0x00800080u) >> (16 * (q & 1));
+                Am[o] = (uint8_t)(d >> 8);
+                Am[o + KT * ROWP] = (uint8_t)d;
+            }
+        }
+    };
+    auto write_x = [&](uint8_t *B, int m, int s) {
+        if (!(s < XS - 1 || x_last)) return;
+        const uint4 v = rxr[m * XS + s];
+        uint8_t *Bm = B + m * PL;
+#pragma unroll
+        for (int q = 0; q < XPC; ++q) {
+            const uint32_t pk = (xa[s][q / 2] >> (16 * (q & 1))) & 0xFFFFu;
+            if (STRIDE == 1 && P == 14) {
+                *reinterpret_cast<uint16_t *>(Bm + pk) = (uint16_t)(comp(v, q >> 1) >> (16 * (q & 1)));
+            } else if (STRIDE == 1) {
+                Bm[pk] = (uint8_t)(comp(v, q >> 2) >> (8 * (q & 3)));
+            } else {
+                const uint32_t o = (pk & 0x7FFFu) + (pk >> 15) * (2 * SH::CLSB);   // classes of odd input rows come third and fourth
+                if (P == 14) {      // 4 bytes of one input row: even columns -> class b = 0, odd -> b = 1
+                    const uint32_t d = comp(v, q);
+                    *reinterpret_cast<uint16_t *>(Bm + o) = (uint16_t)__builtin_amdgcn_perm(0u, d, 0x0C0C0200u);
+                    *reinterpret_cast<uint16_t *>(Bm + o + SH::CLSB) = (uint16_t)__builtin_amdgcn_perm(0u, d, 0x0C0C0301u);
+                } else {
+                    const uint32_t d = comp(v, q >> 1) >> (16 * (q & 1));
+                    Bm[o] = (uint8_t)d;
+                    Bm[o + SH::CLSB] = (uint8_t)(d >> 8);
+                }
+            }
+        }
+    };
+    auto write_part = [&](int buf, int part) {
+        uint8_t *A = smem + buf * SH::BUF, *B = A + SH::A_BYTES;
+#pragma unroll
+        for (int i = 0; i < NIMG * GS; ++i)
+            if (i % NPART == part) write_g(A, i / GS, i % GS);
+#pragma unroll
+        for (int i = 0; i < NIMG * XS; ++i)
+            if ((i + 2) % NPART == part) write_x(B, i / XS, i % XS);
+    };
+    auto ab = [](int hi, int lo, int n) { return (int)__builtin_amdgcn_alignbyte((uint32_t)hi, (uint32_t)lo, n); };
+
+    // Column sums: the NBV input fragments of a channel half are dealt out over the four wavefronts
+    // that share them (variant 4i + (wave & 3) in slot i); each reads its fragments once more for the
+    // sums (no branches in the K-step; a slot beyond the last variant repeats variant 0 and is not
+    // written out).  Row sums of the gradient come from the wavefront's own fragment.
+    int cs_off[SH::CSW];
+#pragma unroll
+    for (int i = 0; i < SH::CSW; ++i) {
+        int v = 4 * i + (wave & 3);
+        if (v >= NBV) v = 0;
+        int cls, off;
+        if (STRIDE == 1) { cls = 0; off = (v - 1) * PT; }
+        else { cls = ((v >> 1) == 1 ? 0 : 2) + (v & 1); off = (v >> 1) == 0 ? -PT : 0; }
+        cs_off[i] = __builtin_amdgcn_readfirstlane(cls * SH::CLSB + off);
+    }
+
+    auto read_b = [&](const uint8_t *bp, bool aligned) {
+        v4i fb;
+        if (aligned) {
+            fb = *reinterpret_cast<const v4i *>(bp);
+        } else {   // pitch 8: the vertical offset is half a fragment, two 8-byte reads
+            const int2 b0 = *reinterpret_cast<const int2 *>(bp), b1 = *reinterpret_cast<const int2 *>(bp + 8);
+            fb = (v4i){b0.x, b0.y, b1.x, b1.y};
+        }
+        return fb;
+    };
+
+    // stage: the chunk held in registers goes to the other buffer, a quarter after the fragment reads
+    // of every other K-step, and the registers just written are loaded again at once with the chunk
+    // after that one, so that a load has a whole chunk of MFMAs to arrive
+    auto compute = [&](int buf, auto stage_tag) {
+        constexpr bool stage = decltype(stage_tag)::value;
+        const uint8_t *A = smem + buf * SH::BUF, *B = A + SH::A_BYTES;
+        const uint8_t *Ar = A + (pl * KT + kt * 32 + r32) * ROWP + LEFT + kh * 16;
+        const uint8_t *Br = B + (ch * 32 + r32) * ROWP + LEFT + kh * 16;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            v4i fa[NAS];
+            {
+                const uint8_t *ap = Ar + ks * 32;
+                const v4i c = *reinterpret_cast<const v4i *>(ap);
+                const int dp1 = *reinterpret_cast<const int *>(ap + 16);
+                fa[0] = (v4i){ab(c[1], c[0], 1), ab(c[2], c[1], 1), ab(c[3], c[2], 1), ab(dp1, c[3], 1)};   // g[p' + 1]
+                fa[1] = c;
+                if (NAS == 3) {
+                    const int dm1 = *reinterpret_cast<const int *>(ap - 4);
+                    fa[NAS - 1] = (v4i){ab(c[0], dm1, 3), ab(c[1], c[0], 3), ab(c[2], c[1], 3), ab(c[3], c[2], 3)};   // g[p' - 1]
+                }
+                rsum = dot4_ones(c[0], dot4_ones(c[1], dot4_ones(c[2], dot4_ones(c[3], rsum))));
+            }
+            if (stage && (ks & 1) == 0) {
+                write_part(buf ^ 1, ks >> 1);
+                load_part(ks >> 1);
+            }
+#pragma unroll
+            for (int i = 0; i < SH::CSW; ++i) {
+                const v4i fb = read_b(Br + cs_off[i] + ks * 32, PT == 16);
+                csum[i] = dot4_ones(fb[0], dot4_ones(fb[1], dot4_ones(fb[2], dot4_ones(fb[3], csum[i]))));
+            }
+#pragma unroll
+            for (int v = 0; v < NBV; ++v) {
+                const v4i fb = read_b(Br + SH::bcls(v) * SH::CLSB + ks * 32 + SH::boff(v), PT == 16 || SH::boff(v) == 0);
+#pragma unroll
+                for (int t = 0; t < TAPS; ++t)
+                    if (SH::bvar(t) == v)
+                        acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[SH::ashift(t)], fb, acc[t], 0, 0, 0);
+            }
+        }
+    };
+
+    __syncthreads();                       // the zero codes are in place
+    if (SH::DB) {
+        if (units > 0) {
+#pragma unroll
+            for (int part = 0; part < NPART; ++part) load_part(part);
+            next_chunk();
+#pragma unroll
+            for (int part = 0; part < NPART; ++part) write_part(0, part);
+#pragma unroll
+            for (int part = 0; part < NPART; ++part) load_part(part);
+            next_chunk();
+        }
+        __syncthreads();
+        for (int u = 0; u + 1 < units; ++u) {
+            compute(u & 1, std::true_type());   // multiplies chunk u; chunk u+1: registers -> other buffer; chunk u+2: loads issued
+            next_chunk();
+            q8t_lds_barrier();
+        }
+        if (units > 0) compute((units - 1) & 1, std::false_type());
+    } else {
+        // one buffer: multiply, then (behind a barrier) write the chunk held in registers and load the next
+        if (units > 0) {
+#pragma unroll
+            for (int part = 0; part < NPART; ++part) load_part(part);
+            next_chunk();
+        }
+        for (int u = 0; u < units; ++u) {
+#pragma unroll
+            for (int part = 0; part < NPART; ++part) write_part(0, part);
+#pragma unroll
+            for (int part = 0; part < NPART; ++part) load_part(part);
+            next_chunk();
+            q8t_lds_barrier();
+            compute(0, std::false_type());
+            q8t_lds_barrier();
+        }
+    }
+
+    // ---- partial result of this image range: accumulators in register order, then the sums ----
+    int *out = partial + ((int64_t)(kr * g.nrg + rg) * g.ncg + cg) * SH::PART_INTS;
+#pragma unroll
+    for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            out[((((pl * 2 + kt) * 2 + ch) * TAPS + t) * 16 + j) * 64 + lane] = acc[t][j];
+    // a lane holds the sum over its 16-byte half of every K-step: fold the two halves
+    rsum += __shfl_xor(rsum, 32, 64);
+    if (kh == 0 && ch == 0) out[SH::TILE_INTS + NBV * CT + pl * KT + kt * 32 + r32] = rsum;
+#pragma unroll
+    for (int i = 0; i < SH::CSW; ++i) {
+        const int v = 4 * i + (wave & 3);
+        const int c = csum[i] + __shfl_xor(csum[i], 32, 64);
+        if (kh == 0 && v < NBV) out[SH::TILE_INTS + v * CT + ch * 32 + r32] = c;
+    }
+}
+
+// int64 reduction over the image ranges + zero-point correction + dequantization.  With
+// a = 256*hi + lo + (128 - zg) the gradient level minus its zero point and b = x - zx:
+//   sum a*b = 256*sum(hi*x) + sum(lo*x) + (128 - zg)*colsum(x) - zx*(256*rowsum(hi) + rowsum(lo) + (128 - zg)*Kp)
+// over the Kp padded positions of the range (pads contribute a = 0 and b = 0).
+constexpr int RQ = 16;   // interleaved subsets of the image ranges per workgroup (one wavefront each)
+template <class SH>
+__global__ __launch_bounds__(64 * RQ) void wgrad_planes_finish(const int *__restrict__ partial, PGeom g,
+                                                              const q8t_qparams *__restrict__ qpg,
+                                                              const q8t_qparams *__restrict__ qpx,
+                                                              float *__restrict__ dw, int64_t *__restrict__ acc_out)
+{
+    __shared__ int64_t fold[RQ][64];
+    constexpr int TAPS = SH::TAPS, NBV = SH::NBV;
+    const int sub = blockIdx.y;
+    const int cg = sub % g.ncg, rg = sub / g.ncg;
+    const int lane = threadIdx.x & 63, quarter = threadIdx.x >> 6;
+    const int idx = blockIdx.x * 64 + lane;   // ((((kt*2 + ch)*TAPS + tap)*16 + reg)*64 + lane
+    const int reg = (idx >> 6) & 15, rest = idx >> 10;
+    const int tap = rest % TAPS, ch = (rest / TAPS) & 1, kt = rest / (2 * TAPS);
+    // 32x32 accumulator tile: lane = column + 32 * ((row / 4) % 2), register = 4 * (row / 8) + row % 4
+    const int row_l = kt * 32 + 8 * (reg >> 2) + 4 * (lane >> 5) + (reg & 3), ch_l = ch * 32 + (lane & 31);
+    const int bv = SH::bvar(tap);
+
+    const int zsg = qpg->zero_point - (1 << (qpg->bits - 1)), zsx = qpx->zero_point - (1 << (qpx->bits - 1));
+    const int64_t ca = 128 - zsg;
+    int64_t v = 0;
+    const int nq = blockDim.x >> 6;
+    for (int kr = quarter; kr < g.S; kr += nq) {
+        const int *p = partial + ((int64_t)(kr * g.nrg + rg) * g.ncg + cg) * SH::PART_INTS;
+        const int nimg = min(g.N, (kr + 1) * g.ipr) - kr * g.ipr;
+        const int64_t Kp = (int64_t)((nimg + SH::NIMG - 1) / SH::NIMG) * KC;
+        const int64_t hi = p[idx], lo = p[SH::HALF_INTS + idx];
+        const int64_t csv = p[SH::TILE_INTS + bv * CT + ch_l];
+        const int64_t rsh = p[SH::TILE_INTS + NBV * CT + row_l], rsl = p[SH::TILE_INTS + NBV * CT + KT + row_l];
+        v += 256 * hi + lo + ca * csv - (int64_t)zsx * (256 * rsh + rsl + ca * Kp);
+    }
+    fold[quarter][lane] = v;
+    __syncthreads();
+    if (quarter == 0) {
+        v = 0;
+        for (int q = 0; q < nq; ++q) v += fold[q][lane];
+        const double sc = (double)(qpg->scale * qpx->scale);
+        const int64_t o = ((int64_t)(rg * KT + row_l) * g.C + cg * CT + ch_l) * TAPS + tap;
+        if (acc_out) acc_out[o] = v;
+        if (dw) dw[o] = (float)((double)v * sc);
+    }
+}
+
+// 0 = not served; else the result plane edge (14 or 7)
+int planes_edge(const q8t_conv_desc *d)
+{
+    if (d->R != 3 || d->S != 3 || d->pad != 1 || (d->stride != 1 && d->stride != 2)) return 0;
+    if (d->H != d->W || d->K % KT || d->C % CT) return 0;
+    const int P = (d->H + 2 - 3) / d->stride + 1;
+    if ((P != 14 && P != 7) || d->H != P * d->stride) return 0;
+    return P;
+}
+
+template <class SH>
+PGeom planes_geom(const q8t_conv_desc *d)
+{
+    PGeom g;
+    g.N = d->N; g.C = d->C; g.K = d->K;
+    g.nrg = d->K / KT;
+    g.ncg = d->C / CT;
+    const int chunks = (d->N + SH::NIMG - 1) / SH::NIMG;
+    int want = 256 / (g.nrg * g.ncg);          // one workgroup per compute unit
+    if (want < 1) want = 1;
+    if (want > chunks) want = chunks;
+    int cpr = (chunks + want - 1) / want;      // chunks per range
+    if (cpr > 511) cpr = 511;                  // 2^14 * 256 * 511 < 2^31: the 32-bit partial sums cannot overflow
+    g.ipr = cpr * SH::NIMG;
+    g.S = (d->N + g.ipr - 1) / g.ipr;
+    return g;
+}
+
+template <class SH>
+int launch_planes(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams *qg, const int8_t *x,
+                  const q8t_qparams *qx, float *dw, int64_t *acc_out, void *ws, hipStream_t st)
+{
+    const PGeom g = planes_geom<SH>(d);
+    const int per = g.nrg * g.ncg;
+    const int blocks = ((g.S * per + 7) / 8) * 8;
+    static Q8tLdsOptIn optin;
+    if (q8t_allow_lds(optin, (const void *)wgrad_planes<SH>, SH::SMEM) != Q8T_OK) return Q8T_ERR_HIP;
+    hipLaunchKernelGGL(wgrad_planes<SH>, dim3(blocks), dim3(kThreads), SH::SMEM, st, g16, x, qg, qx, g, (int *)ws);
+    Q8T_LAUNCH_CHECK();
+    hipLaunchKernelGGL(wgrad_planes_finish<SH>, dim3(SH::HALF_INTS / 64, per), dim3(g.S >= 16 ? 64 * RQ : 256), 0, st,
+                       (const int *)ws, g, qg, qx, dw, acc_out);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
+
+template <class SH>
+size_t planes_ws(const q8t_conv_desc *d)
+{
+    const PGeom g = planes_geom<SH>(d);
+    return (size_t)g.S * g.nrg * g.ncg * SH::PART_INTS * sizeof(int);
+}
+
+}  // namespace
+
+bool q8t_planes_wgrad_supported(const q8t_conv_desc *d, const void *g16, const void *x, const void *dw, const void *acc)
+{
+    const int P = planes_edge(d);
+    if (!P) return false;
+    // 7x7 planes at stride 1 (byte-granular staging of both operands) are faster as byte planes +
+    // im2col rows + GEMM once the batch is large; the kernel stays available for them below that
+    if (P == 7 && d->stride == 1 && (int64_t)d->N * d->K * d->C >= ((int64_t)1 << 24)) return false;
+    return q8t_aligned(g16, 16) && q8t_aligned(x, 16) && q8t_aligned(dw, 4) && q8t_aligned(acc, 8);
+}
+
+size_t q8t_planes_wgrad_ws(const q8t_conv_desc *d)
+{
+    const int P = planes_edge(d);
+    if (!P) return 0;
+    if (d->stride == 1) return P == 14 ? planes_ws<Shape<14, 1>>(d) : planes_ws<Shape<7, 1>>(d);
+    return P == 14 ? planes_ws<Shape<14, 2>>(d) : planes_ws<Shape<7, 2>>(d);
+}
+
+int q8t_planes_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams *qg, const int8_t *x,
+                     const q8t_qparams *qx, float *dw, int64_t *acc_out, void *ws, hipStream_t st)
+{
+    if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    const int P = planes_edge(d);
+    if (d->stride == 1)
+        return P == 14 ? launch_planes<Shape<14, 1>>(d, g16, qg, x, qx, dw, acc_out, ws, st)
+                       : launch_planes<Shape<7, 1>>(d, g16, qg, x, qx, dw, acc_out, ws, st);
+    return P == 14 ? launch_planes<Shape<14, 2>>(d, g16, qg, x, qx, dw, acc_out, ws, st)
+                   : launch_planes<Shape<7, 2>>(d, g16, qg, x, qx, dw, acc_out, ws, st);
+}

@@ -144,6 +144,12 @@ CONV_CASES = [
     (13, 24, 17, 13, 40, 3, 2, 2, 1),    # nothing a multiple of anything; 63-position planes in groups of 4 images
     (6, 128, 7, 7, 128, 3, 3, 1, 1),     # 49-position planes, last image group incomplete
     (5, 64, 9, 10, 64, 3, 3, 1, 1),      # 90-position planes in pairs, last pair incomplete
+    # weight gradient on padded 14x14 / 7x7 planes in LDS (stride 1 and 2)
+    (2, 64, 28, 28, 128, 3, 3, 2, 1),    # stride 2 -> 14x14: the input plane is split into its four parity classes
+    (5, 64, 14, 14, 64, 3, 3, 2, 1),     # stride 2 -> 7x7: chunks of four planes, the last one with a single image
+    (40, 64, 28, 28, 64, 3, 3, 2, 1),    # one image range per image
+    (37, 64, 7, 7, 64, 3, 3, 1, 1),      # ten image ranges, the last chunk incomplete
+    (19, 64, 14, 14, 128, 3, 3, 1, 1),   # two row groups
     # forward with few input channels: explicit im2col rows + GEMM
     (4, 16, 20, 20, 128, 3, 3, 1, 1),    # 144 columns -> 192, 128-wide tiles
     (8, 5, 30, 17, 64, 5, 3, 2, 2),      # non-square filter, stride 2, 75 columns -> 128
