@@ -335,3 +335,56 @@ def standard_bn_f64(x):
     y = np.empty(x.shape, np.float64)
     lib().orc_standard_bn_f64(_p(x), N, Cc, H, W, _p(y))
     return y
+
+
+# ------------------------------------------------------------------ ternarized back-propagation
+def ternarize(x, seed=0):
+    """Stochastic ternarization (appendix "Additional Experiments").  Returns (codes int8 in
+    {-1,0,1} shaped like x, scale = max|x| as fp32)."""
+    x = _f32(x)
+    codes = np.empty(x.shape, np.int8)
+    scale = C.c_float()
+    lib().orc_ternarize(_p(x), C.c_int64(x.size), C.c_uint64(int(seed)), _p(codes), C.byref(scale))
+    return codes, np.float32(scale.value)
+
+
+def binarize(x):
+    """+1 for x >= 0, -1 otherwise (int8)."""
+    x = _f32(x)
+    codes = np.empty(x.shape, np.int8)
+    lib().orc_binarize(_p(x), C.c_int64(x.size), _p(codes))
+    return codes
+
+
+def pack_bits(codes, transpose=False):
+    """Bit rows (uint32 words) of a 2-D matrix of +-1 codes; see orc_pack_bits."""
+    codes = _i8(codes)
+    rows, cols = codes.shape
+    nr, nc = (cols, rows) if transpose else (rows, cols)
+    out = np.empty((nr, (nc + 31) // 32), np.uint32)
+    lib().orc_pack_bits(_p(codes), rows, cols, int(bool(transpose)), _p(out))
+    return out
+
+
+def xnor_gemm(abits, wbits, K):
+    """y[m,n] = sum_k a[m,k] w[n,k] over +-1 values given as bit rows of K bits (int32)."""
+    abits = np.ascontiguousarray(abits, dtype=np.uint32)
+    wbits = np.ascontiguousarray(wbits, dtype=np.uint32)
+    M, N = abits.shape[0], wbits.shape[0]
+    assert abits.shape[1] == wbits.shape[1] == (K + 31) // 32
+    y = np.empty((M, N), np.int32)
+    lib().orc_xnor_gemm(_p(abits), _p(wbits), M, N, int(K), _p(y))
+    return y
+
+
+def tern_wgrad_multi(g, a_codes, S, seed=0):
+    """Algorithm 1 for an FC layer: g [M,N] fp32, a_codes [M,K] +-1.  Returns (dW [K,N] fp32, acc int64)."""
+    g = _f32(g)
+    a_codes = _i8(a_codes)
+    M, N = g.shape
+    M2, K = a_codes.shape
+    assert M == M2
+    dw = np.empty((K, N), np.float32)
+    acc = np.empty((K, N), np.int64)
+    lib().orc_tern_wgrad_multi(_p(g), _p(a_codes), M, N, K, int(S), C.c_uint64(int(seed)), _p(dw), _p(acc))
+    return dw, acc

@@ -16,6 +16,8 @@
  *   - Range BN forward ....................... Section 3, eq. (range), C(n) = 1/sqrt(2 ln n)
  *   - Range BN backward ...................... Section 7 (derivative of max/min is one at the
  *                                              coordinates attaining them, zero elsewhere)
+ *   - stochastic ternarization, binarization, XNOR + population count product,
+ *     multiple stochastic ternarization sampling   appendix "Additional Experiments", Algorithm 1
  *
  * Floating point: rounding decisions (the integer codes) are taken in fp32 with
  * a fixed operation order -- one rounding per written operation, no fused
@@ -755,4 +757,112 @@ void orc_standard_bn_f64(const double *x, int N, int C, int H, int W, double *y)
                 y[j] = (x[j] - mu) / sd;
             }
     }
+}
+
+/* ------------------------------------------------------------------ */
+/* Ternarized back-propagation (appendix "Additional Experiments").     */
+/* The paper names the operations (stochastic ternarization of the      */
+/* gradient, binarized weights and activations, XNOR + population       */
+/* count products, Algorithm 1) without defining them; the readings     */
+/* are: StcTern(g)_i = sign(g_i) with probability |g_i| / max|g| and 0   */
+/* otherwise (unbiased once multiplied by max|g|), the draw taken from  */
+/* the same counter-based generator as the stochastic rounding; a       */
+/* binarized value is +1 for x >= 0 and -1 otherwise.                   */
+
+/* codes in {-1, 0, +1}; *scale = max |x| (0 for an all-zero tensor: every code is 0) */
+void orc_ternarize(const float *x, int64_t n, uint64_t seed, int8_t *codes, float *scale)
+{
+    float s = 0.0f;
+    for (int64_t i = 0; i < n; ++i) {
+        const float a = fabsf(x[i]);
+        if (a > s) s = a;
+    }
+    *scale = s;
+    if (s == 0.0f) {
+        for (int64_t i = 0; i < n; ++i) codes[i] = 0;
+        return;
+    }
+    const float inv = 1.0f / s;
+    for (int64_t i = 0; i < n; ++i) {
+        const float p = fabsf(x[i]) * inv;                 /* probability of a non-zero code */
+        const float lhs = p * 65536.0f;
+        const float rhs = (float)orc_r16((uint64_t)i, seed) + 0.5f;
+        const int keep = lhs > rhs;
+        codes[i] = (int8_t)(keep ? (x[i] < 0.0f ? -1 : 1) : 0);
+    }
+}
+
+/* binarized value: +1 for x >= 0, -1 otherwise */
+void orc_binarize(const float *x, int64_t n, int8_t *codes)
+{
+    for (int64_t i = 0; i < n; ++i) codes[i] = (int8_t)(x[i] >= 0.0f ? 1 : -1);
+}
+
+/* Bits of a [rows][cols] matrix of +-1 codes, bit = 1 for +1.  transpose = 0: one bit row per
+ * matrix row, out[rows][ceil(cols/32)], bit j of word w = column 32w + j.  transpose = 1: one bit
+ * row per matrix column, out[cols][ceil(rows/32)], bit j of word w = row 32w + j.  Bits past the
+ * end of a bit row are 0. */
+void orc_pack_bits(const int8_t *codes, int rows, int cols, int transpose, uint32_t *out)
+{
+    const int nr = transpose ? cols : rows, nc = transpose ? rows : cols;
+    const int words = (nc + 31) / 32;
+    for (int r = 0; r < nr; ++r)
+        for (int w = 0; w < words; ++w) {
+            uint32_t v = 0;
+            for (int j = 0; j < 32; ++j) {
+                const int c = 32 * w + j;
+                if (c >= nc) break;
+                const int8_t code = transpose ? codes[(int64_t)c * cols + r] : codes[(int64_t)r * cols + c];
+                if (code > 0) v |= (uint32_t)1 << j;
+            }
+            out[(int64_t)r * words + w] = v;
+        }
+}
+
+/* y[m][n] = sum_k a[m][k] * w[n][k] over +-1 values given as bit rows of K bits (what an XNOR +
+ * population count computes: matches minus mismatches), written out from the definition */
+void orc_xnor_gemm(const uint32_t *abits, const uint32_t *wbits, int M, int N, int K, int32_t *y)
+{
+    const int words = (K + 31) / 32;
+#pragma omp parallel for
+    for (int m = 0; m < M; ++m)
+        for (int n = 0; n < N; ++n) {
+            int32_t acc = 0;
+            for (int k = 0; k < K; ++k) {
+                const int a = (abits[(int64_t)m * words + k / 32] >> (k % 32)) & 1 ? 1 : -1;
+                const int w = (wbits[(int64_t)n * words + k / 32] >> (k % 32)) & 1 ? 1 : -1;
+                acc += a * w;
+            }
+            y[(int64_t)m * N + n] = acc;
+        }
+}
+
+/* Algorithm 1 (multiple stochastic ternarization sampling) for a fully connected layer:
+ * g [M][N] gradient, a [M][K] binarized layer input (+-1 codes), S samples;
+ *   for s = 1..S: t = StcTern(g) (seed + s - 1);  acc[k][n] += sum_m a[m][k] * t[m][n]
+ *   dW[k][n] = max|g| * acc[k][n] / S
+ * acc (nullable) receives the integer sum over all samples. */
+void orc_tern_wgrad_multi(const float *g, const int8_t *a, int M, int N, int K, int S, uint64_t seed,
+                          float *dw, int64_t *acc_out)
+{
+    const int64_t n = (int64_t)M * N;
+    int8_t *t = (int8_t *)malloc((size_t)(n > 0 ? n : 1));
+    int64_t *acc = (int64_t *)calloc((size_t)K * N, sizeof(int64_t));
+    float scale = 0.0f;
+    for (int s = 0; s < S; ++s) {
+        orc_ternarize(g, n, seed + (uint64_t)s, t, &scale);
+#pragma omp parallel for
+        for (int k = 0; k < K; ++k)
+            for (int c = 0; c < N; ++c) {
+                int64_t v = 0;
+                for (int m = 0; m < M; ++m) v += (int64_t)a[(int64_t)m * K + k] * (int64_t)t[(int64_t)m * N + c];
+                acc[(int64_t)k * N + c] += v;
+            }
+    }
+    for (int64_t i = 0; i < (int64_t)K * N; ++i) {
+        if (acc_out) acc_out[i] = acc[i];
+        if (dw) dw[i] = (float)((double)acc[i] * (double)scale / (double)S);
+    }
+    free(acc);
+    free(t);
 }
