@@ -256,6 +256,43 @@ int q8t_range_bn_relu_bwd_bifurcate(const float *x, const float *dy, const float
 /* C(n) = 1/sqrt(2 ln n) (Section 3), host arithmetic in double.  n >= 2. */
 double q8t_range_bn_scale(int64_t n);
 
+/* ---------------------------------------------------------------------------------------------
+ * Ternarized back-propagation (appendix "Additional Experiments": gradients ternarized
+ * stochastically, weights and activations binarized, products by XNOR + population count, and
+ * Algorithm 1, multiple stochastic ternarization sampling, for the weight gradient).  The paper
+ * names these operations without defining them; the readings are
+ *   StcTern(g)_i = sign(g_i) with probability |g_i| / max|g|, else 0 (unbiased once scaled by max|g|),
+ *                  kept iff fl32(fl32(|g_i| * fl32(1/max|g|)) * 65536) > r + 0.5 with r the 16 bits of
+ *                  the generator of q8t_quantize for (seed, flat index i);
+ *   binarized x  = +1 for x >= 0, -1 otherwise.
+ *
+ * q8t_ternarize: g: n floats -> t_out: n int8 codes in {-1, 0, +1}; scale_out: 1 device float =
+ * max|g| (0 for an all-zero tensor, whose codes are all 0).  ws: q8t_ternarize_workspace_size(n)
+ * bytes, 4-byte aligned.  n <= 2^34.
+ * q8t_binarize: x: n floats -> codes: n int8 in {-1, +1}.
+ * q8t_pack_bits: codes [rows][cols] (+-1, row-major) -> bit rows of uint32 words, bit = 1 for +1.
+ *   transpose = 0: out[rows][ceil(cols/32)], bit j of word w = column 32w + j;
+ *   transpose = 1: out[cols][ceil(rows/32)], bit j of word w = row 32w + j (a bit row per column).
+ *   Bits past the end of a bit row are 0.
+ * q8t_xnor_gemm: y[m][n] = sum_k a[m][k] * w[n][k] over +-1 values, from bit rows a_bits
+ *   [M][ceil(K/32)] and w_bits [N][ceil(K/32)] (the forward product of a binarized layer:
+ *   matches minus mismatches = 2 * popcount(xnor) - K).  y: M*N int32, row-major.
+ * q8t_tern_wgrad_multi: Algorithm 1 for a fully connected layer.  g [M][N]: gradient (floats),
+ *   a_codes [M][K]: binarized layer input (+-1 int8), S >= 1 samples, sample s drawn with seed + s:
+ *     acc[k][n] = sum_{s<S} sum_m a[m][k] * StcTern_s(g)[m][n]      (exact, S*M < 2^31 else
+ *     Q8T_ERR_OVERFLOW);   dW[k][n] = (float)((double)acc * (double)max|g| / (double)S).
+ *   dw [K][N] floats and acc_out [K][N] int64 are each nullable (not both).  ws:
+ *   q8t_tern_wgrad_multi_workspace_size bytes, 4-byte aligned.
+ * Errors: Q8T_ERR_SHAPE, Q8T_ERR_NULL, Q8T_ERR_WORKSPACE, Q8T_ERR_OVERFLOW, Q8T_ERR_HIP. */
+size_t q8t_ternarize_workspace_size(int64_t n);
+int q8t_ternarize(const float *g, int64_t n, uint64_t seed, int8_t *t_out, float *scale_out, void *ws, void *stream);
+int q8t_binarize(const float *x, int64_t n, int8_t *codes, void *stream);
+int q8t_pack_bits(const int8_t *codes, int rows, int cols, int transpose, uint32_t *out, void *stream);
+int q8t_xnor_gemm(const uint32_t *a_bits, const uint32_t *w_bits, int M, int N, int K, int32_t *y, void *stream);
+size_t q8t_tern_wgrad_multi_workspace_size(int M, int N, int K);
+int q8t_tern_wgrad_multi(const float *g, const int8_t *a_codes, int M, int N, int K, int S, uint64_t seed, float *dw,
+                         int64_t *acc_out, void *ws, void *stream);
+
 /* Measurement aid, not a step of the method: a plain streaming kernel of known traffic with the access
  * shape of the library's HBM-bound calls (every workgroup streams one contiguous slice, four 16-byte
  * accesses in flight per lane).  mode 0: dst = src (bytes read and bytes written); mode 1: src is

@@ -78,6 +78,13 @@ _SIGS = {
     "q8t_range_bn_bwd_bifurcate": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _f, _vp, _vp, _vp, _u64, _u64, _vp, _vp,
                                         _vp, _vp, _vp, _vp]),
     "q8t_probe_stream": (_i, [_i, _vp, _vp, _i64, _vp]),
+    "q8t_ternarize_workspace_size": (_sz, [_i64]),
+    "q8t_ternarize": (_i, [_vp, _i64, _u64, _vp, _vp, _vp, _vp]),
+    "q8t_binarize": (_i, [_vp, _i64, _vp, _vp]),
+    "q8t_pack_bits": (_i, [_vp, _i, _i, _i, _vp, _vp]),
+    "q8t_xnor_gemm": (_i, [_vp, _vp, _i, _i, _i, _vp, _vp]),
+    "q8t_tern_wgrad_multi_workspace_size": (_sz, [_i, _i, _i]),
+    "q8t_tern_wgrad_multi": (_i, [_vp, _vp, _i, _i, _i, _i, _u64, _vp, _vp, _vp, _vp]),
     "q8t_range_bn_scale": (C.c_double, [_i64]),
     "q8t_version": (C.c_char_p, []),
 }
@@ -430,3 +437,58 @@ def range_bn_bwd_bifurcate(x, dy, stats, gamma=None, eps=0.0, seed8=0, seed16=1,
                                            int(seed16) & (2 ** 64 - 1), _ptr(q8), _ptr(qp8), _ptr(q16), _ptr(qp16),
                                            _ptr(ws), _stream()), "q8t_range_bn_bwd_bifurcate")
     return dx, dgamma, dbeta, q8, qp8, q16, qp16
+
+
+# ------------------------------------------------------------------ ternarized back-propagation
+def ternarize(g, seed=0, ws=None):
+    """Stochastic ternarization.  Returns (codes int8 in {-1,0,1}, scale: device tensor of 1 float = max|g|)."""
+    _dev(g)
+    n = g.numel()
+    t = torch.empty(g.shape, dtype=torch.int8, device=g.device)
+    scale = torch.empty(1, dtype=torch.float32, device=g.device)
+    ws = ws if ws is not None else workspace(_lib.q8t_ternarize_workspace_size(n), g.device)
+    _check(_lib.q8t_ternarize(_ptr(g), n, int(seed) & (2 ** 64 - 1), _ptr(t), _ptr(scale), _ptr(ws), _stream()),
+           "q8t_ternarize")
+    return t, scale
+
+
+def binarize(x):
+    """+1 for x >= 0, -1 otherwise (int8)."""
+    _dev(x)
+    codes = torch.empty(x.shape, dtype=torch.int8, device=x.device)
+    _check(_lib.q8t_binarize(_ptr(x), x.numel(), _ptr(codes), _stream()), "q8t_binarize")
+    return codes
+
+
+def pack_bits(codes, transpose=False):
+    """Bit rows (int32 tensor holding the uint32 words) of a 2-D matrix of +-1 codes."""
+    _dev(codes)
+    rows, cols = codes.shape
+    nr, nc = (cols, rows) if transpose else (rows, cols)
+    out = torch.empty((nr, (nc + 31) // 32), dtype=torch.int32, device=codes.device)
+    _check(_lib.q8t_pack_bits(_ptr(codes), rows, cols, int(bool(transpose)), _ptr(out), _stream()), "q8t_pack_bits")
+    return out
+
+
+def xnor_gemm(a_bits, w_bits, K):
+    """y[m,n] = sum_k a[m,k] w[n,k] over +-1 values given as bit rows of K bits (int32)."""
+    _dev(a_bits), _dev(w_bits)
+    M, N = a_bits.shape[0], w_bits.shape[0]
+    assert a_bits.shape[1] == w_bits.shape[1] == (K + 31) // 32
+    y = torch.empty((M, N), dtype=torch.int32, device=a_bits.device)
+    _check(_lib.q8t_xnor_gemm(_ptr(a_bits), _ptr(w_bits), M, N, int(K), _ptr(y), _stream()), "q8t_xnor_gemm")
+    return y
+
+
+def tern_wgrad_multi(g, a_codes, S, seed=0, want_acc=False, ws=None):
+    """Algorithm 1 (multiple stochastic ternarization sampling) for an FC layer.  Returns (dW [K,N], acc or None)."""
+    _dev(g), _dev(a_codes)
+    M, N = g.shape
+    M2, K = a_codes.shape
+    assert M == M2 and a_codes.dtype == torch.int8
+    dw = torch.empty((K, N), dtype=torch.float32, device=g.device)
+    acc = torch.empty((K, N), dtype=torch.int64, device=g.device) if want_acc else None
+    ws = ws if ws is not None else workspace(_lib.q8t_tern_wgrad_multi_workspace_size(M, N, K), g.device)
+    _check(_lib.q8t_tern_wgrad_multi(_ptr(g), _ptr(a_codes), M, N, K, int(S), int(seed) & (2 ** 64 - 1), _ptr(dw),
+                                     _ptr(acc), _ptr(ws), _stream()), "q8t_tern_wgrad_multi")
+    return dw, acc
