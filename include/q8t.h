@@ -296,7 +296,7 @@ int q8t_tern_wgrad_multi(const float *g, const int8_t *a_codes, int M, int N, in
 /* Measurement aid, not a step of the method: a plain streaming kernel of known traffic with the access
  * shape of the library's HBM-bound calls (every workgroup streams one contiguous slice, four 16-byte
  * accesses in flight per lane).  mode 0: dst = src (bytes read and bytes written); mode 1: src is
- * read only (dst receives 8 KiB of checksums, at most 32 KiB: size it >= 32 KiB); mode 2: dst is
+ * read only (dst receives checksums, at most 64 KiB: size it >= 64 KiB); mode 2: dst is
  * filled with zeros.  bytes: multiple of 16, >= 65536; src / dst: device, 16-byte aligned, must not
  * overlap.  Errors: Q8T_ERR_SHAPE, Q8T_ERR_NULL, Q8T_ERR_HIP. */
 int q8t_probe_stream(int mode, const void *src, void *dst, int64_t bytes, void *stream);

@@ -388,3 +388,42 @@ def tern_wgrad_multi(g, a_codes, S, seed=0):
     acc = np.empty((K, N), np.int64)
     lib().orc_tern_wgrad_multi(_p(g), _p(a_codes), M, N, K, int(S), C.c_uint64(int(seed)), _p(dw), _p(acc))
     return dw, acc
+
+
+# ------------------------------------------------------------------ network plumbing (not from the paper)
+def range_bn_relu_maxpool_fwd(x, stats, gamma=None, beta=None, eps=0.0):
+    """relu(Range BN(x)) followed by 3x3 / stride 2 / pad 1 max pooling.  Returns (pooled fp32, idx uint8)."""
+    x, stats = _f32(x), _f32(stats)
+    N, Cc, H, W = x.shape
+    gamma, beta = _opt_f32(gamma), _opt_f32(beta)
+    P, Q = (H - 1) // 2 + 1, (W - 1) // 2 + 1
+    out = np.empty((N, Cc, P, Q), np.float32)
+    idx = np.empty((N, Cc, P, Q), np.uint8)
+    lib().orc_range_bn_relu_maxpool_fwd(_p(x), N, Cc, H, W, _p(gamma), _p(beta), C.c_float(eps), _p(stats), _p(out), _p(idx))
+    return out, idx
+
+
+def maxpool_relu_bwd(gpool, idx, H, W):
+    gpool = _f32(gpool)
+    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    N, Cc = gpool.shape[:2]
+    dy = np.empty((N, Cc, H, W), np.float32)
+    lib().orc_maxpool_relu_bwd(_p(gpool), _p(idx), N, Cc, H, W, _p(dy))
+    return dy
+
+
+def add_relu(a, b):
+    """Returns (relu(a + b), its maximum as fp32)."""
+    a, b = _f32(a), _f32(b)
+    out = np.empty(a.shape, np.float32)
+    mx = C.c_float()
+    lib().orc_add_relu(_p(a), _p(b), C.c_int64(a.size), _p(out), C.byref(mx))
+    return out, np.float32(mx.value)
+
+
+def relu_bwd_add(g, out, other=None):
+    g, out = _f32(g), _f32(out)
+    other = _opt_f32(other)
+    res = np.empty(g.shape, np.float32)
+    lib().orc_relu_bwd_add(_p(g), _p(out), _p(other), C.c_int64(g.size), _p(res))
+    return res

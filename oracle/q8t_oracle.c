@@ -866,3 +866,86 @@ void orc_tern_wgrad_multi(const float *g, const int8_t *a, int M, int N, int K, 
     free(acc);
     free(t);
 }
+
+/* ------------------------------------------------------------------ */
+/* Network plumbing around the method (not from the paper): the stem of */
+/* a ResNet follows its first Range BN + ReLU with a 3x3 / stride 2 /   */
+/* pad 1 max pooling.  Pooling and the residual additions are plain      */
+/* definitions; they are here so that the fused GPU forms have a         */
+/* reference.                                                            */
+
+/* out[n][c][p][q] = max over the window rows 2p-1..2p+1, cols 2q-1..2q+1 (inside the plane) of
+ * v = relu(Range BN(x)) for given statistics; idx = position of the FIRST maximum inside the
+ * window in row-major order (3*i + j), or 255 when the maximum is not positive (nothing passes
+ * a gradient back through the rectifier then).  P = (H - 1)/2 + 1, Q = (W - 1)/2 + 1. */
+void orc_range_bn_relu_maxpool_fwd(const float *x, int N, int C, int H, int W, const float *gamma,
+                                   const float *beta, float eps, const float *stats, float *out,
+                                   uint8_t *idx)
+{
+    const int64_t HW = (int64_t)H * W;
+    const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1;
+    float *v = (float *)malloc(sizeof(float) * (size_t)N * C * HW);
+    orc_range_bn_relu_fwd_apply(x, N, C, H, W, gamma, beta, eps, stats, v, NULL, NULL);
+#pragma omp parallel for
+    for (int64_t pl = 0; pl < (int64_t)N * C; ++pl)
+        for (int p = 0; p < P; ++p)
+            for (int q = 0; q < Q; ++q) {
+                float best = -INFINITY;
+                int where = 255;
+                for (int i = 0; i < 3; ++i)
+                    for (int j = 0; j < 3; ++j) {
+                        const int h = 2 * p - 1 + i, w = 2 * q - 1 + j;
+                        if (h < 0 || h >= H || w < 0 || w >= W) continue;
+                        const float t = v[pl * HW + (int64_t)h * W + w];
+                        if (t > best) {
+                            best = t;
+                            where = 3 * i + j;
+                        }
+                    }
+                out[(pl * P + p) * Q + q] = best;
+                idx[(pl * P + p) * Q + q] = (uint8_t)(best > 0.0f ? where : 255);
+            }
+    free(v);
+}
+
+/* gradient with respect to the Range BN output of the stem: every window hands its gradient to the
+ * position idx names (none for 255); contributions of the (up to four) windows that share a position
+ * are added in window order */
+void orc_maxpool_relu_bwd(const float *gpool, const uint8_t *idx, int N, int C, int H, int W, float *dy)
+{
+    const int64_t HW = (int64_t)H * W;
+    const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1;
+    memset(dy, 0, sizeof(float) * (size_t)N * C * HW);
+#pragma omp parallel for
+    for (int64_t pl = 0; pl < (int64_t)N * C; ++pl)
+        for (int p = 0; p < P; ++p)
+            for (int q = 0; q < Q; ++q) {
+                const int k = idx[(pl * P + p) * Q + q];
+                if (k == 255) continue;
+                const int h = 2 * p - 1 + k / 3, w = 2 * q - 1 + k % 3;
+                dy[pl * HW + (int64_t)h * W + w] += gpool[(pl * P + p) * Q + q];
+            }
+}
+
+/* out = relu(a + b), elementwise; *vmax (nullable) = max of out (its min is 0 or positive: the
+ * range of the rectified sum, widened to contain 0, is [0, vmax]) */
+void orc_add_relu(const float *a, const float *b, int64_t n, float *out, float *vmax)
+{
+    float mx = 0.0f;
+    for (int64_t i = 0; i < n; ++i) {
+        const float s = a[i] + b[i];
+        const float r = s > 0.0f ? s : 0.0f;
+        out[i] = r;
+        if (r > mx) mx = r;
+    }
+    if (vmax) *vmax = mx;
+}
+
+/* backward of out = relu(.): g passes where out > 0; with `other` (nullable) added to it */
+void orc_relu_bwd_add(const float *g, const float *out, const float *other, int64_t n, float *res)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        const float m = out[i] > 0.0f ? g[i] : 0.0f;
+        res[i] = other ? m + other[i] : m;
+    }
+}

@@ -45,6 +45,38 @@ __device__ __forceinline__ void q8t_lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// 16-byte loads of streamed tensors: non-temporal, measured 8-12% faster than plain loads on cold
+// tensors (6.4 against 5.7 TB/s for a read-only stream).  q8t_ld_last: the last pass of a call over
+// its input; q8t_ld_first: the first of two passes over the same tensor.  Kept apart because the
+// second pass can find part of the tensor in the Infinity Cache: measured inside the step, both
+// non-temporal is the best setting for quantize and Range BN forward and neutral for the two-pass
+// Range BN backward, while a plain first pass with a non-temporal second one is 15% slower there.
+typedef float q8t_f4 __attribute__((ext_vector_type(4)));
+#ifndef Q8T_NT_LAST
+#define Q8T_NT_LAST 1
+#endif
+#ifndef Q8T_NT_FIRST
+#define Q8T_NT_FIRST 1
+#endif
+__device__ __forceinline__ float4 q8t_ld_last(const float4 *p)
+{
+#if Q8T_NT_LAST
+    const q8t_f4 v = __builtin_nontemporal_load(reinterpret_cast<const q8t_f4 *>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+#else
+    return *p;
+#endif
+}
+__device__ __forceinline__ float4 q8t_ld_first(const float4 *p)
+{
+#if Q8T_NT_FIRST
+    const q8t_f4 v = __builtin_nontemporal_load(reinterpret_cast<const q8t_f4 *>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+#else
+    return *p;
+#endif
+}
+
 // ---- wavefront (64 lanes) and workgroup reductions ------------------------------------------
 template <typename T, typename Op>
 __device__ __forceinline__ T wave_reduce(T v, Op op)

@@ -73,13 +73,13 @@ __global__ __launch_bounds__(kThreads) void minmax_partials(const float *__restr
         const int64_t lo = (int64_t)blockIdx.x * per, hi = min(n4, lo + per);
         int64_t i = lo + threadIdx.x;
         for (; i + 3 * kThreads < hi; i += 4 * kThreads) {
-            const float4 a = x4[i], b = x4[i + kThreads], c = x4[i + 2 * kThreads], d = x4[i + 3 * kThreads];
+            const float4 a = q8t_ld_first(x4 + i), b = q8t_ld_first(x4 + i + kThreads), c = q8t_ld_first(x4 + i + 2 * kThreads), d = q8t_ld_first(x4 + i + 3 * kThreads);
             mm4(mn, mx, a);
             mm4(mn, mx, b);
             mm4(mn, mx, c);
             mm4(mn, mx, d);
         }
-        for (; i < hi; i += kThreads) mm4(mn, mx, x4[i]);
+        for (; i < hi; i += kThreads) mm4(mn, mx, q8t_ld_first(x4 + i));
         const int64_t tail = (n4 << 2) + gid;  // the n % 4 leftover elements
         if (tail < n) {
             mn = fminf(mn, x[tail]);
@@ -135,13 +135,13 @@ __global__ __launch_bounds__(kThreads) void quantize_apply(
         const int64_t lo = (int64_t)blockIdx.x * per, hi = min(n4, lo + per);
         int64_t i = lo + threadIdx.x;
         for (; i + 3 * kThreads < hi; i += 4 * kThreads) {
-            const float4 v0 = x4[i], v1 = x4[i + kThreads], v2 = x4[i + 2 * kThreads], v3 = x4[i + 3 * kThreads];
+            const float4 v0 = q8t_ld_last(x4 + i), v1 = q8t_ld_last(x4 + i + kThreads), v2 = q8t_ld_last(x4 + i + 2 * kThreads), v3 = q8t_ld_last(x4 + i + 3 * kThreads);
             q4[i] = quant4<OUT, STOCH>(v0, a, (uint32_t)i, seed_lo, seed_hi);
             q4[i + kThreads] = quant4<OUT, STOCH>(v1, a, (uint32_t)(i + kThreads), seed_lo, seed_hi);
             q4[i + 2 * kThreads] = quant4<OUT, STOCH>(v2, a, (uint32_t)(i + 2 * kThreads), seed_lo, seed_hi);
             q4[i + 3 * kThreads] = quant4<OUT, STOCH>(v3, a, (uint32_t)(i + 3 * kThreads), seed_lo, seed_hi);
         }
-        for (; i < hi; i += kThreads) q4[i] = quant4<OUT, STOCH>(x4[i], a, (uint32_t)i, seed_lo, seed_hi);
+        for (; i < hi; i += kThreads) q4[i] = quant4<OUT, STOCH>(q8t_ld_last(x4 + i), a, (uint32_t)i, seed_lo, seed_hi);
         const int64_t tail = (n4 << 2) + gid;
         if (tail < n) {
             const uint32_t r = STOCH ? rng_r16(tail, seed_lo, seed_hi) : 0u;
@@ -267,14 +267,14 @@ __global__ __launch_bounds__(kThreads) void quantize_bifurcate_apply(
         const int64_t lo = (int64_t)blockIdx.x * per, hi = min(n4, lo + per);
         int64_t i = lo + threadIdx.x;
         for (; i + kThreads < hi; i += 2 * kThreads) {
-            const float4 v0 = x4[i], v1 = x4[i + kThreads];
+            const float4 v0 = q8t_ld_last(x4 + i), v1 = q8t_ld_last(x4 + i + kThreads);
             o8[i] = quant4<int8_t, true>(v0, a8, (uint32_t)i, s8_lo, s8_hi);
             o16[i] = quant4<int16_t, true>(v0, a16, (uint32_t)i, s16_lo, s16_hi);
             o8[i + kThreads] = quant4<int8_t, true>(v1, a8, (uint32_t)(i + kThreads), s8_lo, s8_hi);
             o16[i + kThreads] = quant4<int16_t, true>(v1, a16, (uint32_t)(i + kThreads), s16_lo, s16_hi);
         }
         for (; i < hi; i += kThreads) {
-            const float4 v0 = x4[i];
+            const float4 v0 = q8t_ld_last(x4 + i);
             o8[i] = quant4<int8_t, true>(v0, a8, (uint32_t)i, s8_lo, s8_hi);
             o16[i] = quant4<int16_t, true>(v0, a16, (uint32_t)i, s16_lo, s16_hi);
         }

@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kThreads) void bn_stats_partial(const float *__rest
             const float4 *p = reinterpret_cast<const float4 *>(x + ((int64_t)b * C + c) * HW);
 #pragma unroll 4
             for (int i = threadIdx.x; i < hw4; i += kThreads) {
-                const float4 v = p[i];
+                const float4 v = q8t_ld_first(p + i);
                 sum += (double)v.x;
                 sum += (double)v.y;
                 sum += (double)v.z;
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_apply(const float *__restrict
             const float mu = stats[c];
             const float inv = bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
             const float g = gamma ? gamma[c] : 1.0f, b = beta ? beta[c] : 0.0f;
-            const float4 v = reinterpret_cast<const float4 *>(x)[i4];
+            const float4 v = q8t_ld_last(reinterpret_cast<const float4 *>(x) + i4);
             float4 r;
             r.x = bn_map(v.x, mu, inv, g, b);
             r.y = bn_map(v.y, mu, inv, g, b);
@@ -279,7 +279,7 @@ __global__ __launch_bounds__(kThreads) void bn_fwd_apply(const float *__restrict
             const int hw4 = HW >> 2;
 #pragma unroll 4
             for (int i = threadIdx.x; i < hw4; i += kThreads) {
-                const float4 v = p[i];
+                const float4 v = q8t_ld_last(p + i);
                 float4 r;
                 r.x = bn_map(v.x, mu, inv, g, b);
                 r.y = bn_map(v.y, mu, inv, g, b);
@@ -359,8 +359,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_partial(const float *__restri
             const float4 *pg = reinterpret_cast<const float4 *>(dy + base);
 #pragma unroll 2
             for (int i = threadIdx.x; i < hw4; i += kThreads) {
-                const float4 v = px[i];
-                float4 g = pg[i];
+                const float4 v = q8t_ld_first(px + i);
+                float4 g = q8t_ld_first(pg + i);
                 const float h0 = (v.x - mu) * inv, h1 = (v.y - mu) * inv, h2 = (v.z - mu) * inv,
                             h3 = (v.w - mu) * inv;
                 if (relu) {   // the gradient passes where the forward output was positive
@@ -480,8 +480,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwd_apply(const float *__restrict
             const int hw4 = HW >> 2;
 #pragma unroll 2
             for (int i = threadIdx.x; i < hw4; i += kThreads) {
-                const float4 v = px[i];
-                float4 d = pg[i];
+                const float4 v = q8t_ld_last(px + i);
+                float4 d = q8t_ld_last(pg + i);
                 if (relu) {
                     d.x = bn_map(v.x, mu, inv, g, be) > 0.0f ? d.x : 0.0f;
                     d.y = bn_map(v.y, mu, inv, g, be) > 0.0f ? d.y : 0.0f;
@@ -581,7 +581,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_partial(const float *__restr
                 const float4 *pg = reinterpret_cast<const float4 *>(dy + base);
 #pragma unroll 2
                 for (int i = threadIdx.x; i < hw4; i += kThreads) {
-                    const float4 v = px[i], g = pg[i];
+                    const float4 v = q8t_ld_first(px + i), g = q8t_ld_first(pg + i);
                     one(v.x, g.x);
                     one(v.y, g.y);
                     one(v.z, g.z);
@@ -595,8 +595,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_partial(const float *__restr
             for (int idx = threadIdx.x; idx < items; idx += kThreads) {
                 const int bl = idx / hw4, i = idx - bl * hw4;
                 const int64_t base = ((int64_t)(b0 + bl) * C + c) * HW;
-                const float4 v = reinterpret_cast<const float4 *>(x + base)[i];
-                const float4 g = reinterpret_cast<const float4 *>(dy + base)[i];
+                const float4 v = q8t_ld_first(reinterpret_cast<const float4 *>(x + base) + i);
+                const float4 g = q8t_ld_first(reinterpret_cast<const float4 *>(dy + base) + i);
                 one(v.x, g.x);
                 one(v.y, g.y);
                 one(v.z, g.z);
@@ -728,8 +728,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restric
             const float inv = bn_inv(mn, mx, cn, eps);
             const float g = gamma ? gamma[c] : 1.0f, be = beta ? beta[c] : 0.0f;
             const float2 k = consts[c];
-            const float4 v = reinterpret_cast<const float4 *>(x)[i4];
-            float4 d = reinterpret_cast<const float4 *>(dy)[i4];
+            const float4 v = q8t_ld_last(reinterpret_cast<const float4 *>(x) + i4);
+            float4 d = q8t_ld_last(reinterpret_cast<const float4 *>(dy) + i4);
             if (relu) {
                 d.x = bn_map(v.x, mu, inv, g, be) > 0.0f ? d.x : 0.0f;
                 d.y = bn_map(v.y, mu, inv, g, be) > 0.0f ? d.y : 0.0f;
@@ -762,8 +762,8 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restric
             const int hw4 = HW >> 2;
 #pragma unroll 2
             for (int i = threadIdx.x; i < hw4; i += kThreads) {
-                const float4 v = px[i];
-                float4 d = pg[i];
+                const float4 v = q8t_ld_last(px + i);
+                float4 d = q8t_ld_last(pg + i);
                 if (relu) {
                     d.x = bn_map(v.x, mu, inv, g, be) > 0.0f ? d.x : 0.0f;
                     d.y = bn_map(v.y, mu, inv, g, be) > 0.0f ? d.y : 0.0f;

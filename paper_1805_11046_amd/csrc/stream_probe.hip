@@ -1,12 +1,21 @@
 // Plain streaming kernels of known traffic: the measured ceiling that the HBM-bound calls of the
-// library (quantize, Range BN) are compared with.  Same access shape as those calls: every
-// workgroup streams one contiguous slice with four 16-byte accesses in flight per lane.
+// library (quantize, Range BN) are compared with.  The access shape is the best of a sweep on this
+// chip (slices against grid strides, 1024 to 32768 workgroups, 1 to 8 accesses in flight, plain
+// against non-temporal loads): every workgroup streams one contiguous slice, non-temporal loads,
+// two to four 16-byte accesses in flight per lane, 4096 workgroups.
 #include "q8t_common.h"
 #include "q8t_internal.h"
 
 namespace {
 
 constexpr int kThreads = 256;
+
+typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ldnt(const uint4 *p)
+{
+    const u4v v = __builtin_nontemporal_load(reinterpret_cast<const u4v *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
 
 // mode 0: dst = src (bytes read + bytes written); mode 1: read only (one word per workgroup
 // written, so that the loads cannot be dropped); mode 2: fill dst with zeros
@@ -24,7 +33,7 @@ __global__ __launch_bounds__(kThreads) void probe_stream(const uint4 *__restrict
             dst[i + 2 * kThreads] = acc;
             dst[i + 3 * kThreads] = acc;
         } else {
-            const uint4 a = src[i], b = src[i + kThreads], c = src[i + 2 * kThreads], d = src[i + 3 * kThreads];
+            const uint4 a = ldnt(src + i), b = ldnt(src + i + kThreads), c = ldnt(src + i + 2 * kThreads), d = ldnt(src + i + 3 * kThreads);
             if (MODE == 0) {
                 dst[i] = a;
                 dst[i + kThreads] = b;
@@ -42,7 +51,7 @@ __global__ __launch_bounds__(kThreads) void probe_stream(const uint4 *__restrict
         if (MODE == 2) {
             dst[i] = acc;
         } else {
-            const uint4 a = src[i];
+            const uint4 a = ldnt(src + i);
             if (MODE == 0) {
                 dst[i] = a;
             } else {
@@ -72,8 +81,8 @@ int q8t_probe_stream(int mode, const void *src, void *dst, int64_t bytes, void *
     if (!dst || (mode != 2 && !src)) return Q8T_ERR_NULL;
     if (!q8t_aligned(dst, 16) || (src && !q8t_aligned(src, 16))) return Q8T_ERR_SHAPE;
     const int64_t n16 = bytes / 16;
-    int64_t g = (n16 + (int64_t)kThreads * 8 - 1) / ((int64_t)kThreads * 8);
-    const int grid = (int)(g < 1 ? 1 : (g > 2048 ? 2048 : g));
+    int64_t g = (n16 + (int64_t)kThreads * 4 - 1) / ((int64_t)kThreads * 4);
+    const int grid = (int)(g < 1 ? 1 : (g > 4096 ? 4096 : g));
     hipStream_t st = (hipStream_t)stream;
     const uint4 *s = (const uint4 *)src;
     uint4 *d = (uint4 *)dst;

@@ -1,0 +1,56 @@
+"""Pins for the oracle's network plumbing (pooling behind the first Range BN + ReLU, residual add +
+ReLU): against torch's CPU routines.  CPU only."""
+import numpy as np
+import torch
+import torch.nn.functional as F
+
+import oracle
+
+
+def _data(seed, shape):
+    g = np.random.default_rng(seed)
+    return g.standard_normal(shape).astype(np.float32)
+
+
+def test_stem_pooling_forward_is_max_pool_of_the_rectified_normalization():
+    for shape in ((2, 3, 8, 8), (1, 2, 7, 9), (2, 4, 12, 10)):
+        x = _data(sum(shape), shape)
+        stats = oracle.range_bn_stats(x)
+        gamma, beta = _data(1, shape[1]), _data(2, shape[1])
+        v, _, _ = oracle.range_bn_relu_fwd(x, stats, gamma, beta, 1e-5)
+        out, idx = oracle.range_bn_relu_maxpool_fwd(x, stats, gamma, beta, 1e-5)
+        ref = F.max_pool2d(torch.from_numpy(v), 3, 2, 1).numpy()
+        assert np.array_equal(out, ref)
+        # idx names a position that holds the maximum, or 255 where the maximum is not positive
+        N, C, H, W = shape
+        for n, c, p, q in np.ndindex(out.shape):
+            k = int(idx[n, c, p, q])
+            if out[n, c, p, q] <= 0:
+                assert k == 255
+            else:
+                h, w = 2 * p - 1 + k // 3, 2 * q - 1 + k % 3
+                assert 0 <= h < H and 0 <= w < W and v[n, c, h, w] == out[n, c, p, q]
+
+
+def test_stem_pooling_backward_against_autograd():
+    shape = (2, 3, 9, 10)
+    x = _data(5, shape)
+    stats = oracle.range_bn_stats(x)
+    out, idx = oracle.range_bn_relu_maxpool_fwd(x, stats, None, None, 1e-5)
+    g = _data(6, out.shape)
+    dy = oracle.maxpool_relu_bwd(g, idx, shape[2], shape[3])
+    y, _, _, _ = oracle.range_bn_fwd(x, eps=1e-5, stats=stats)        # before the rectifier
+    t = torch.from_numpy(y).requires_grad_(True)
+    F.max_pool2d(torch.relu(t), 3, 2, 1).backward(torch.from_numpy(g))
+    assert np.allclose(dy, t.grad.numpy(), rtol=1e-6, atol=1e-7)     # continuous data: no ties among positive values
+
+
+def test_add_relu_and_its_backward():
+    a, b = _data(7, (3, 4, 5, 6)), _data(8, (3, 4, 5, 6))
+    out, mx = oracle.add_relu(a, b)
+    assert np.array_equal(out, np.maximum(a + b, 0)) and mx == out.max()
+    g, o = _data(9, a.shape), _data(10, a.shape)
+    assert np.array_equal(oracle.relu_bwd_add(g, out), np.where(out > 0, g, 0))
+    assert np.array_equal(oracle.relu_bwd_add(g, out, o), np.where(out > 0, g, np.float32(0)) + o)
+    z, mz = oracle.add_relu(-np.abs(a), -np.abs(b))
+    assert not z.any() and mz == 0
