@@ -345,17 +345,22 @@ def main():
         loss = one()
     torch.cuda.synchronize()
 
-    # every library call timed in sequence (2 steps), to find the entry point with the largest share
-    BREAK_STEPS = 2
+    # every library call timed in sequence, to find the entry point with the largest share.  Three
+    # steps are recorded and the one with the smallest total is reported: a step now and then carries
+    # a stall of several ms in one call (the allocator behind the glue returning memory to the driver)
     ts.record(breakdown=True)
-    for _ in range(BREAK_STEPS):
+    one()            # one untimed step in this mode: its events and buffers exist afterwards
+    ts.drain()
+    per_step = []
+    for _ in range(3):
         one()
-    records = ts.drain()
+        per_step.append(ts.drain())
     ts.record()
-    calls, by = summarize_calls(records, BREAK_STEPS)
+    records = min(per_step, key=lambda r: sum(x[4] for x in r))
+    calls, by = summarize_calls(records, 1)
     dominant = max(by, key=lambda k: by[k]["us"])
-    useful_ops = sum(r[2] for r in records) / BREAK_STEPS
-    library_ms = sum(r[4] for r in records) / BREAK_STEPS / 1e3
+    useful_ops = sum(r[2] for r in records)
+    library_ms = sum(r[4] for r in records) / 1e3
 
     # the timed region: K whole steps; only the dominant entry point carries events
     ts.record(bracket=dominant)

@@ -293,6 +293,33 @@ size_t q8t_tern_wgrad_multi_workspace_size(int M, int N, int K);
 int q8t_tern_wgrad_multi(const float *g, const int8_t *a_codes, int M, int N, int K, int S, uint64_t seed, float *dw,
                          int64_t *acc_out, void *ws, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Network plumbing around the method (not from the paper; what a ResNet training step needs between
+ * the calls above), fused with its neighbours so that the large activation tensors cross HBM once.
+ *
+ * q8t_range_bn_relu_maxpool_fwd: relu(Range BN(x)) for given statistics (as
+ *   q8t_range_bn_relu_fwd_apply) followed by 3x3 / stride 2 / pad 1 max pooling, without writing the
+ *   normalized tensor.  x [N,C,H,W]; stats [3][C]; out [N,C,P,Q] floats with P = (H-1)/2 + 1,
+ *   Q = (W-1)/2 + 1; idx [N,C,P,Q] bytes: position 3*i + j of the first maximum inside its window
+ *   (row-major), 255 where the maximum is not positive (the rectifier passes no gradient there).
+ * q8t_maxpool_relu_bwd: gradient with respect to the Range BN output: dy [N,C,H,W] receives, at
+ *   every position, the sum of gpool over the windows whose idx names it (0 elsewhere).  Feed it to
+ *   q8t_range_bn_bwd / q8t_range_bn_bwd_bifurcate (not the ReLU variants: the mask is in idx).
+ * q8t_add_relu_quantize: out = relu(a + b) (n floats each) and, if q_out != NULL, its 8-bit codes
+ *   and parameters exactly as q8t_quantize(out, n, 8, 0, ...) would give them: the first pass leaves
+ *   the maximum behind (the minimum of the rectified sum, widened to contain 0, is 0), so only the
+ *   second pass of the quantization runs.  ws: q8t_add_relu_quantize_workspace_size(n) bytes,
+ *   8-byte aligned.
+ * q8t_relu_bwd_add: res = (out > 0 ? g : 0) + other (other nullable: nothing added).
+ * Errors: Q8T_ERR_SHAPE, Q8T_ERR_NULL, Q8T_ERR_WORKSPACE, Q8T_ERR_HIP. */
+int q8t_range_bn_relu_maxpool_fwd(const float *x, int N, int C, int H, int W, const float *gamma, const float *beta, float eps,
+                                  const float *stats, float *out, uint8_t *idx, void *stream);
+int q8t_maxpool_relu_bwd(const float *gpool, const uint8_t *idx, int N, int C, int H, int W, float *dy, void *stream);
+size_t q8t_add_relu_quantize_workspace_size(int64_t n);
+int q8t_add_relu_quantize(const float *a, const float *b, int64_t n, float *out, int8_t *q_out, q8t_qparams *qp_out, void *ws,
+                          void *stream);
+int q8t_relu_bwd_add(const float *g, const float *out, const float *other, int64_t n, float *res, void *stream);
+
 /* Measurement aid, not a step of the method: a plain streaming kernel of known traffic with the access
  * shape of the library's HBM-bound calls (every workgroup streams one contiguous slice, four 16-byte
  * accesses in flight per lane).  mode 0: dst = src (bytes read and bytes written); mode 1: src is

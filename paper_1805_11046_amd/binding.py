@@ -78,6 +78,11 @@ _SIGS = {
     "q8t_range_bn_bwd_bifurcate": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _f, _vp, _vp, _vp, _u64, _u64, _vp, _vp,
                                         _vp, _vp, _vp, _vp]),
     "q8t_probe_stream": (_i, [_i, _vp, _vp, _i64, _vp]),
+    "q8t_range_bn_relu_maxpool_fwd": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp, _vp]),
+    "q8t_maxpool_relu_bwd": (_i, [_vp, _vp, _i, _i, _i, _i, _vp, _vp]),
+    "q8t_add_relu_quantize_workspace_size": (_sz, [_i64]),
+    "q8t_add_relu_quantize": (_i, [_vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_relu_bwd_add": (_i, [_vp, _vp, _vp, _i64, _vp, _vp]),
     "q8t_ternarize_workspace_size": (_sz, [_i64]),
     "q8t_ternarize": (_i, [_vp, _i64, _u64, _vp, _vp, _vp, _vp]),
     "q8t_binarize": (_i, [_vp, _i64, _vp, _vp]),
@@ -492,3 +497,47 @@ def tern_wgrad_multi(g, a_codes, S, seed=0, want_acc=False, ws=None):
     _check(_lib.q8t_tern_wgrad_multi(_ptr(g), _ptr(a_codes), M, N, K, int(S), int(seed) & (2 ** 64 - 1), _ptr(dw),
                                      _ptr(acc), _ptr(ws), _stream()), "q8t_tern_wgrad_multi")
     return dw, acc
+
+
+# ------------------------------------------------------------------ network plumbing (not from the paper)
+def range_bn_relu_maxpool_fwd(x, stats, gamma=None, beta=None, eps=0.0):
+    """relu(Range BN(x)) + 3x3 / stride 2 / pad 1 max pooling in one pass.  Returns (pooled fp32, idx uint8)."""
+    _dev(x), _dev(stats)
+    N, Cc, H, W = x.shape
+    P, Q = (H - 1) // 2 + 1, (W - 1) // 2 + 1
+    out = torch.empty((N, Cc, P, Q), dtype=torch.float32, device=x.device)
+    idx = torch.empty((N, Cc, P, Q), dtype=torch.uint8, device=x.device)
+    _check(_lib.q8t_range_bn_relu_maxpool_fwd(_ptr(x), N, Cc, H, W, _ptr(gamma), _ptr(beta), float(eps), _ptr(stats), _ptr(out),
+                                              _ptr(idx), _stream()), "q8t_range_bn_relu_maxpool_fwd")
+    return out, idx
+
+
+def maxpool_relu_bwd(gpool, idx, H, W):
+    """Upstream gradient of the Range BN in front of ReLU + max pooling, from the pooled gradient and idx."""
+    _dev(gpool), _dev(idx)
+    N, Cc = gpool.shape[:2]
+    dy = torch.empty((N, Cc, H, W), dtype=torch.float32, device=gpool.device)
+    _check(_lib.q8t_maxpool_relu_bwd(_ptr(gpool), _ptr(idx), N, Cc, H, W, _ptr(dy), _stream()), "q8t_maxpool_relu_bwd")
+    return dy
+
+
+def add_relu_quantize(a, b, quantized=True, ws=None):
+    """relu(a + b) and (optionally) its 8-bit codes + parameters.  Returns (out, q or None, qp or None)."""
+    _dev(a), _dev(b)
+    assert a.shape == b.shape
+    n = a.numel()
+    out = torch.empty_like(a)
+    q = torch.empty(a.shape, dtype=torch.int8, device=a.device) if quantized else None
+    qp = new_qparams(a.device) if quantized else None
+    ws = ws if ws is not None else workspace(_lib.q8t_add_relu_quantize_workspace_size(n), a.device)
+    _check(_lib.q8t_add_relu_quantize(_ptr(a), _ptr(b), n, _ptr(out), _ptr(q), _ptr(qp), _ptr(ws), _stream()),
+           "q8t_add_relu_quantize")
+    return out, q, qp
+
+
+def relu_bwd_add(g, out, other=None):
+    """(out > 0 ? g : 0) + other."""
+    _dev(g), _dev(out)
+    res = torch.empty_like(g)
+    _check(_lib.q8t_relu_bwd_add(_ptr(g), _ptr(out), _ptr(other), g.numel(), _ptr(res), _stream()), "q8t_relu_bwd_add")
+    return res

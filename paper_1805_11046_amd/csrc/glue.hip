@@ -1,0 +1,362 @@
+// Network plumbing around the method (not from the paper): the pieces of a ResNet training step
+// that sit between the library's products and normalizations, fused with their neighbours so that
+// the large activation tensors make one trip through HBM instead of three:
+//   * stem: Range BN (Section 3, eq. (range)) + ReLU + 3x3 / stride 2 / pad 1 max pooling in one
+//     pass, and the matching backward that hands the Range BN backward its upstream gradient;
+//   * block end: residual sum + ReLU, which also leaves the maximum of its result behind, so the
+//     8-bit quantization of the next layer's operand (Appendix B) needs no min/max pass (the
+//     minimum of a rectified tensor, widened to contain 0, is 0);
+//   * ReLU backward, optionally added to the gradient of the other branch.
+#include "q8t_common.h"
+#include "q8t_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kMaxPartials = 1024;
+
+// 1 / (C(n) * (max - min) + eps) and gamma * ((x - mu) * inv) + beta: one fp32 rounding per
+// operation, the same sequence as the Range BN kernels (the results must agree bit for bit)
+__device__ __forceinline__ float g_bn_inv(float mn, float mx, float cn, float eps)
+{
+    const float range = mx - mn;
+    const float scaled = cn * range;
+    const float denom = scaled + eps;
+    return 1.0f / denom;
+}
+__device__ __forceinline__ float g_bn_relu(float x, float mu, float inv, float g, float b)
+{
+    const float cen = x - mu;
+    const float xh = cen * inv;
+    const float sc = xh * g;
+    const float y = sc + b;
+    return y > 0.0f ? y : 0.0f;
+}
+
+// quotient n / d for n < 2^22 (positions inside one plane): float estimate + fix-up
+__device__ __forceinline__ int small_div(int n, int d, float rd)
+{
+    int q = (int)((float)n * rd);
+    const int r = n - q * d;
+    q += r >= d ? 1 : 0;
+    q -= r < 0 ? 1 : 0;
+    return q;
+}
+
+// a workgroup per (image, channel) plane (32-bit index arithmetic inside it).  VEC (W a multiple of 4):
+// a thread owns two neighbouring pooled columns 2t, 2t+1 of a pooled row; their windows span the input
+// columns 4t-1 .. 4t+3 = one scalar and one aligned 16-byte load per input row, normalized once each.
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void bn_relu_maxpool_fwd(const float *__restrict__ x, int C, int H, int W, int P, int Q,
+                                                                const float *__restrict__ stats, const float *__restrict__ gamma,
+                                                                const float *__restrict__ beta, float cn, float eps,
+                                                                float *__restrict__ out, uint8_t *__restrict__ idx)
+{
+    const int64_t pl = blockIdx.x;
+    const int c = (int)(pl % C);
+    const float mu = stats[c];
+    const float inv = g_bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
+    const float g = gamma ? gamma[c] : 1.0f, b = beta ? beta[c] : 0.0f;
+    const float *xp = x + pl * (int64_t)H * W;
+    float *op = out + pl * (int64_t)P * Q;
+    uint8_t *ip = idx + pl * (int64_t)P * Q;
+    if (VEC) {
+        const int Q2 = Q >> 1;                 // W % 4 == 0: Q = W / 2 is even
+        const float rq = 1.0f / (float)Q2;
+        for (int o = threadIdx.x; o < P * Q2; o += kThreads) {
+            const int p = small_div(o, Q2, rq), t = o - p * Q2;
+            float b0 = -INFINITY, b1 = -INFINITY;
+            int w0 = 255, w1 = 255;
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const int h = 2 * p - 1 + i;
+                if (h < 0 || h >= H) continue;
+                const float *row = xp + h * W + 4 * t;
+                const float4 v = *reinterpret_cast<const float4 *>(row);
+                float e[5];
+                e[0] = t > 0 ? g_bn_relu(row[-1], mu, inv, g, b) : -INFINITY;     // column 4t-1 (outside for t = 0)
+                e[1] = g_bn_relu(v.x, mu, inv, g, b);
+                e[2] = g_bn_relu(v.y, mu, inv, g, b);
+                e[3] = g_bn_relu(v.z, mu, inv, g, b);
+                e[4] = g_bn_relu(v.w, mu, inv, g, b);
+#pragma unroll
+                for (int j = 0; j < 3; ++j) {      // the first maximum in row-major order
+                    if (e[j] > b0) { b0 = e[j]; w0 = 3 * i + j; }
+                    if (e[j + 2] > b1) { b1 = e[j + 2]; w1 = 3 * i + j; }
+                }
+            }
+            *reinterpret_cast<float2 *>(op + p * Q + 2 * t) = make_float2(b0, b1);
+            *reinterpret_cast<uchar2 *>(ip + p * Q + 2 * t) =
+                make_uchar2((unsigned char)(b0 > 0.0f ? w0 : 255), (unsigned char)(b1 > 0.0f ? w1 : 255));
+        }
+        return;
+    }
+    const float rq = 1.0f / (float)Q;
+    for (int o = threadIdx.x; o < P * Q; o += kThreads) {
+        const int p = small_div(o, Q, rq), q = o - p * Q;
+        float best = -INFINITY;
+        int where = 255;
+#pragma unroll
+        for (int i = 0; i < 3; ++i) {
+            const int h = 2 * p - 1 + i;
+            if (h < 0 || h >= H) continue;
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                const int w = 2 * q - 1 + j;
+                if (w < 0 || w >= W) continue;
+                const float v = g_bn_relu(xp[h * W + w], mu, inv, g, b);
+                if (v > best) {       // the first maximum in row-major order
+                    best = v;
+                    where = 3 * i + j;
+                }
+            }
+        }
+        op[o] = best;
+        ip[o] = (uint8_t)(best > 0.0f ? where : 255);
+    }
+}
+
+// gradient that reaches position (h, w): an even row / column belongs to one window, an odd one to
+// two; windows in the order a scatter over the pooled plane visits them (rows ascending, then columns)
+__device__ __forceinline__ float pool_bwd_at(const float *__restrict__ gp, const uint8_t *__restrict__ ip, int h, int w, int P, int Q)
+{
+    const int p1 = (h + 1) >> 1, p0 = p1 - (h & 1);
+    const int q1 = (w + 1) >> 1, q0 = q1 - (w & 1);
+    float acc = 0.0f;
+    for (int p = p0; p <= p1; ++p) {
+        if (p >= P) continue;
+        for (int q = q0; q <= q1; ++q) {
+            if (q >= Q) continue;
+            const int local = 3 * (h - (2 * p - 1)) + (w - (2 * q - 1));
+            if (ip[p * Q + q] == local) acc += gp[p * Q + q];
+        }
+    }
+    return acc;
+}
+
+// a workgroup per plane; with W a multiple of 4 a thread writes 4 neighbouring positions at once
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void maxpool_relu_bwd(const float *__restrict__ gpool, const uint8_t *__restrict__ idx, int H,
+                                                             int W, int P, int Q, float *__restrict__ dy)
+{
+    const int64_t pl = blockIdx.x;
+    const float *gp = gpool + pl * (int64_t)P * Q;
+    const uint8_t *ip = idx + pl * (int64_t)P * Q;
+    float *dp = dy + pl * (int64_t)H * W;
+    if (VEC) {
+        // positions w..w+3 (w a multiple of 4) of row h meet the pooled columns qa = w/2, qa+1, qa+2 at fixed places
+        // inside their windows: w -> (qa, col 1); w+1 -> (qa, 2), (qa+1, 0); w+2 -> (qa+1, 1); w+3 -> (qa+1, 2), (qa+2, 0);
+        // an even row h meets pooled row h/2 at window row 1, an odd one rows (h-1)/2 and (h+1)/2 at window rows 2 and 0
+        const int W4 = W >> 2;
+        const float rw = 1.0f / (float)W4;
+        for (int e = threadIdx.x; e < H * W4; e += kThreads) {
+            const int h = small_div(e, W4, rw), qa = 2 * (e - h * W4);
+            float4 r = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            const int np = (h & 1) ? 2 : 1;
+            for (int k = 0; k < np; ++k) {
+                const int p = (h >> 1) + k, i = (h & 1) ? 2 - 2 * k : 1;
+                if (p >= P) break;
+                const uint8_t *ir = ip + p * Q + qa;
+                const float *gr = gp + p * Q + qa;
+                const int ia = ir[0], ib = ir[1], ic = qa + 2 < Q ? ir[2] : 255;     // Q = W / 2 is even: qa + 1 < Q
+                const float ga = gr[0], gb = gr[1], gc = qa + 2 < Q ? gr[2] : 0.0f;
+                r.x += ia == 3 * i + 1 ? ga : 0.0f;
+                r.y += ia == 3 * i + 2 ? ga : 0.0f;
+                r.y += ib == 3 * i ? gb : 0.0f;
+                r.z += ib == 3 * i + 1 ? gb : 0.0f;
+                r.w += ib == 3 * i + 2 ? gb : 0.0f;
+                r.w += ic == 3 * i ? gc : 0.0f;
+            }
+            reinterpret_cast<float4 *>(dp)[e] = r;
+        }
+    } else {
+        const float rw = 1.0f / (float)W;
+        for (int e = threadIdx.x; e < H * W; e += kThreads) {
+            const int h = small_div(e, W, rw), w = e - h * W;
+            dp[e] = pool_bwd_at(gp, ip, h, w, P, Q);
+        }
+    }
+}
+
+__device__ __forceinline__ float block_max(float v, float *smem)
+{
+    v = wave_reduce(v, OpMax());
+    if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = smem[0];
+    for (int w = 1; w < kThreads / 64; ++w) r = fmaxf(r, smem[w]);
+    return r;
+}
+
+// out = relu(a + b); one (0, max) pair per workgroup for the quantization that follows
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void add_relu_fwd(const float *__restrict__ a, const float *__restrict__ b, int64_t n,
+                                                         float *__restrict__ out, float2 *__restrict__ partials)
+{
+    __shared__ float smem[kThreads / 64];
+    float mx = 0.0f;
+    if (VEC) {
+        const int64_t n4 = n >> 2;
+        const float4 *a4 = reinterpret_cast<const float4 *>(a), *b4 = reinterpret_cast<const float4 *>(b);
+        float4 *o4 = reinterpret_cast<float4 *>(out);
+        const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
+        const int64_t lo = (int64_t)blockIdx.x * per, hi = min(n4, lo + per);
+#pragma unroll 2
+        for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads) {
+            const float4 u = q8t_ld_last(a4 + i), v = q8t_ld_last(b4 + i);
+            float4 r;
+            r.x = u.x + v.x; r.y = u.y + v.y; r.z = u.z + v.z; r.w = u.w + v.w;
+            r.x = r.x > 0.0f ? r.x : 0.0f; r.y = r.y > 0.0f ? r.y : 0.0f;
+            r.z = r.z > 0.0f ? r.z : 0.0f; r.w = r.w > 0.0f ? r.w : 0.0f;
+            o4[i] = r;
+            mx = fmaxf(fmaxf(mx, r.x), fmaxf(r.y, fmaxf(r.z, r.w)));
+        }
+        const int64_t tail = (n4 << 2) + (int64_t)blockIdx.x * kThreads + threadIdx.x;
+        if (tail < n) {
+            const float s = a[tail] + b[tail];
+            const float r = s > 0.0f ? s : 0.0f;
+            out[tail] = r;
+            mx = fmaxf(mx, r);
+        }
+    } else {
+        const int64_t stride = (int64_t)gridDim.x * kThreads;
+        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+            const float s = a[i] + b[i];
+            const float r = s > 0.0f ? s : 0.0f;
+            out[i] = r;
+            mx = fmaxf(mx, r);
+        }
+    }
+    mx = block_max(mx, smem);
+    if (threadIdx.x == 0) partials[blockIdx.x] = make_float2(0.0f, mx);
+}
+
+// res = (out > 0 ? g : 0) [+ other]
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void relu_bwd_add(const float *__restrict__ g, const float *__restrict__ outv,
+                                                         const float *__restrict__ other, int64_t n, float *__restrict__ res)
+{
+    if (VEC) {
+        const int64_t n4 = n >> 2;
+        const float4 *g4 = reinterpret_cast<const float4 *>(g), *o4 = reinterpret_cast<const float4 *>(outv);
+        const float4 *t4 = reinterpret_cast<const float4 *>(other);
+        float4 *r4 = reinterpret_cast<float4 *>(res);
+        const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
+        const int64_t lo = (int64_t)blockIdx.x * per, hi = min(n4, lo + per);
+#pragma unroll 2
+        for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads) {
+            const float4 u = q8t_ld_last(g4 + i), v = q8t_ld_last(o4 + i);
+            float4 r;
+            r.x = v.x > 0.0f ? u.x : 0.0f; r.y = v.y > 0.0f ? u.y : 0.0f;
+            r.z = v.z > 0.0f ? u.z : 0.0f; r.w = v.w > 0.0f ? u.w : 0.0f;
+            if (other) {
+                const float4 t = q8t_ld_last(t4 + i);
+                r.x = r.x + t.x; r.y = r.y + t.y; r.z = r.z + t.z; r.w = r.w + t.w;
+            }
+            r4[i] = r;
+        }
+        const int64_t tail = (n4 << 2) + (int64_t)blockIdx.x * kThreads + threadIdx.x;
+        if (tail < n) {
+            const float m = outv[tail] > 0.0f ? g[tail] : 0.0f;
+            res[tail] = other ? m + other[tail] : m;
+        }
+    } else {
+        const int64_t stride = (int64_t)gridDim.x * kThreads;
+        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+            const float m = outv[i] > 0.0f ? g[i] : 0.0f;
+            res[i] = other ? m + other[i] : m;
+        }
+    }
+}
+
+int grid_for(int64_t items, int per_thread, int cap)
+{
+    int64_t g = (items + (int64_t)kThreads * per_thread - 1) / ((int64_t)kThreads * per_thread);
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+constexpr int64_t kMaxElements = (int64_t)1 << 34;
+
+}  // namespace
+
+extern "C" {
+
+int q8t_range_bn_relu_maxpool_fwd(const float *x, int N, int C, int H, int W, const float *gamma, const float *beta, float eps,
+                                  const float *stats, float *out, uint8_t *idx, void *stream)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || (int64_t)N * H * W < 2) return Q8T_ERR_SHAPE;
+    if ((int64_t)N * C * H * W > kMaxElements) return Q8T_ERR_SHAPE;
+    if (!x || !stats || !out || !idx) return Q8T_ERR_NULL;
+    const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1;
+    const int64_t planes = (int64_t)N * C;
+    if (planes > 0x7FFFFFFF || (int64_t)H * W >= (1 << 22)) return Q8T_ERR_SHAPE;
+    const float cn = (float)q8t_range_bn_scale((int64_t)N * H * W);
+    if (W % 4 == 0 && q8t_aligned(x, 16) && q8t_aligned(out, 8) && q8t_aligned(idx, 2))
+        hipLaunchKernelGGL(bn_relu_maxpool_fwd<true>, dim3((unsigned)planes), dim3(kThreads), 0, (hipStream_t)stream, x, C, H, W, P,
+                           Q, stats, gamma, beta, cn, eps, out, idx);
+    else
+        hipLaunchKernelGGL(bn_relu_maxpool_fwd<false>, dim3((unsigned)planes), dim3(kThreads), 0, (hipStream_t)stream, x, C, H, W,
+                           P, Q, stats, gamma, beta, cn, eps, out, idx);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
+
+int q8t_maxpool_relu_bwd(const float *gpool, const uint8_t *idx, int N, int C, int H, int W, float *dy, void *stream)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0) return Q8T_ERR_SHAPE;
+    if ((int64_t)N * C * H * W > kMaxElements) return Q8T_ERR_SHAPE;
+    if (!gpool || !idx || !dy) return Q8T_ERR_NULL;
+    const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1;
+    const int64_t planes = (int64_t)N * C;
+    if (planes > 0x7FFFFFFF || (int64_t)H * W >= (1 << 22)) return Q8T_ERR_SHAPE;
+    if (W % 4 == 0 && q8t_aligned(dy, 16))
+        hipLaunchKernelGGL(maxpool_relu_bwd<true>, dim3((unsigned)planes), dim3(kThreads), 0, (hipStream_t)stream, gpool, idx, H, W,
+                           P, Q, dy);
+    else
+        hipLaunchKernelGGL(maxpool_relu_bwd<false>, dim3((unsigned)planes), dim3(kThreads), 0, (hipStream_t)stream, gpool, idx, H, W,
+                           P, Q, dy);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
+
+size_t q8t_add_relu_quantize_workspace_size(int64_t n)
+{
+    (void)n;
+    return sizeof(float2) * kMaxPartials;
+}
+
+int q8t_add_relu_quantize(const float *a, const float *b, int64_t n, float *out, int8_t *q_out, q8t_qparams *qp_out, void *ws,
+                          void *stream)
+{
+    if (n <= 0 || n > kMaxElements) return Q8T_ERR_SHAPE;
+    if (!a || !b || !out || (q_out && !qp_out)) return Q8T_ERR_NULL;
+    if (!ws || !q8t_aligned(ws, 8)) return Q8T_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const bool vec = q8t_aligned(a, 16) && q8t_aligned(b, 16) && q8t_aligned(out, 16);
+    const int grid = grid_for(vec ? (n >> 2) : n, 4, kMaxPartials);
+    if (vec)
+        hipLaunchKernelGGL(add_relu_fwd<true>, dim3(grid), dim3(kThreads), 0, st, a, b, n, out, (float2 *)ws);
+    else
+        hipLaunchKernelGGL(add_relu_fwd<false>, dim3(grid), dim3(kThreads), 0, st, a, b, n, out, (float2 *)ws);
+    Q8T_LAUNCH_CHECK();
+    if (!q_out) return Q8T_OK;
+    return q8t_quantize8_from_partials(out, n, ws, grid, q_out, qp_out, st);
+}
+
+int q8t_relu_bwd_add(const float *g, const float *out, const float *other, int64_t n, float *res, void *stream)
+{
+    if (n <= 0 || n > kMaxElements) return Q8T_ERR_SHAPE;
+    if (!g || !out || !res) return Q8T_ERR_NULL;
+    const bool vec = q8t_aligned(g, 16) && q8t_aligned(out, 16) && q8t_aligned(res, 16) && q8t_aligned(other, 16);
+    const int grid = grid_for(vec ? (n >> 2) : n, 4, 4096);
+    if (vec)
+        hipLaunchKernelGGL(relu_bwd_add<true>, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, g, out, other, n, res);
+    else
+        hipLaunchKernelGGL(relu_bwd_add<false>, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, g, out, other, n, res);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
+
+}  // extern "C"

@@ -60,3 +60,7 @@ bool q8t_planes_wgrad_supported(const q8t_conv_desc *d, const void *g16, const v
 size_t q8t_planes_wgrad_ws(const q8t_conv_desc *d);
 int q8t_planes_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams *qg, const int8_t *x,
                      const q8t_qparams *qx, float *dw, int64_t *acc_out, void *ws, hipStream_t st);
+
+// quantize.hip: nearest 8-bit quantization of x with the range given as npairs (<= 1024) float2 (min, max) pairs
+int q8t_quantize8_from_partials(const float *x, int64_t n, const void *minmax_pairs, int npairs, int8_t *q_out,
+                                q8t_qparams *qp_out, hipStream_t st);

@@ -441,6 +441,14 @@ int quantize_impl(const float *x, int64_t n, int bits, int stochastic, uint64_t 
 
 }  // namespace
 
+// second pass of q8t_quantize alone, the range given as up to 1024 (min, max) pairs that a producing
+// kernel left behind (glue.hip: the rectified residual sum knows its maximum when it is written)
+int q8t_quantize8_from_partials(const float *x, int64_t n, const void *minmax_pairs, int npairs, int8_t *q_out,
+                                q8t_qparams *qp_out, hipStream_t st)
+{
+    return launch_apply<int8_t>(x, n, 8, 0, 0, (const float2 *)minmax_pairs, npairs, q_out, qp_out, st);
+}
+
 extern "C" {
 
 int q8t_quantize_with_range(const float *x, int64_t n, int bits, int stochastic, uint64_t seed,

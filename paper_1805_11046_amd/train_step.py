@@ -72,7 +72,13 @@ def _angle(kind, t, q, qp):
         _angles.setdefault(kind, []).append(q8t.quant_angle(t, q, qp)[3])
 
 
+_qcache = {}   # data_ptr of an activation -> (codes, parameters) left behind by the kernel that wrote it
+
+
 def _quantize(name, t):
+    hit = _qcache.get(t.data_ptr())
+    if hit is not None and hit[0].shape == t.shape:
+        return hit
     n = t.numel()
     # two passes over the fp32 tensor and one byte written; small tensors stay in registers (one pass)
     q, qp = _call(name, 0, (9 if n > 65536 else 5) * n, q8t.quantize, t, 8)
@@ -125,6 +131,59 @@ class ConvBN(torch.autograd.Function):
             dx, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d))
         dw, _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
         return dx, dw, None, None, None
+
+
+class StemConvBNPool(torch.autograd.Function):
+    """First layer: quantize -> conv forward (+ Range BN statistics) -> Range BN + ReLU + 3x3/2 max pooling in one
+    pass (the normalized 112x112 tensor is never written); backward: pooled gradient -> upstream gradient of the
+    Range BN (one pass) -> Range BN backward + bifurcated quantization -> weight gradient.  The network input
+    needs no gradient."""
+
+    @staticmethod
+    def forward(ctx, a, w, stride, pad):
+        a = a.contiguous()
+        n, c, h, wd = a.shape
+        k, _, r, s = w.shape
+        d = q8t.conv_desc(n, c, h, wd, k, r, s, stride, pad)
+        qa, pa = _quantize("quantize (activations)", a)
+        qw, pw = _quantize("quantize (weights)", w)
+        ops = 2.0 * n * d.P * d.Q * k * c * r * s
+        nx, ny = a.numel(), n * k * d.P * d.Q
+        y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw, tag=_tag(d))
+        pooled, idx = _call("range_bn_relu_maxpool_fwd", 0, 4 * ny + 5 * (ny // 4), q8t.range_bn_relu_maxpool_fwd, y, stats,
+                            None, None, 1e-5)
+        ctx.saved = (d, qa, pa, y, stats, idx, ops, nx, ny)
+        return pooled
+
+    @staticmethod
+    def backward(ctx, gp):
+        d, qa, pa, y, stats, idx, ops, nx, ny = ctx.saved
+        _seed[0] += 2
+        dy = _call("maxpool_relu_bwd", 0, 5 * (ny // 4) + 4 * ny, q8t.maxpool_relu_bwd, gp.contiguous(), idx, d.P, d.Q)
+        _, _, _, g8, pg8, g16, pg16 = _bn_bwd(q8t.range_bn_bwd_bifurcate, "range_bn_bwd_bifurcate", ny, y, dy, stats, None, 1e-5,
+                                              _seed[0], _seed[0] + 1)
+        dw, _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
+        return None, dw, None, None
+
+
+class AddRelu(torch.autograd.Function):
+    """End of a residual block: relu(h + shortcut) in one pass that also leaves the 8-bit codes of the result behind
+    for the convolutions that read it next (no min/max pass: the range of a rectified tensor is [0, max])."""
+
+    @staticmethod
+    def forward(ctx, h, sc, quantized):
+        n = h.numel()
+        out, q, qp = _call("add_relu_quantize", 0, (17 if quantized else 12) * n, q8t.add_relu_quantize, h.contiguous(),
+                           sc.contiguous(), quantized)
+        if quantized:
+            _qcache[out.data_ptr()] = (q, qp)
+        ctx.out = out
+        return out
+
+    @staticmethod
+    def backward(ctx, g):
+        gm = _call("relu_bwd_add", 0, 12 * g.numel(), q8t.relu_bwd_add, g.contiguous(), ctx.out)
+        return gm, gm, None
 
 
 class ConvChain(torch.autograd.Function):
@@ -224,16 +283,21 @@ def make_weights(dev, gen):
 
 
 def step(x, labels, ws):
-    a = F.relu(ConvBN.apply(x, ws["conv1"], 2, 3, False))     # the network input needs no gradient
-    a = F.max_pool2d(a, 3, 2, 1)
-    for (cin, cout, stride), b in zip(STAGES, ws["blocks"]):
+    _qcache.clear()
+    if _fuse:
+        a = StemConvBNPool.apply(x, ws["conv1"], 2, 3)
+    else:
+        a = F.relu(ConvBN.apply(x, ws["conv1"], 2, 3, False))     # the network input needs no gradient
+        a = F.max_pool2d(a, 3, 2, 1)
+    last = len(ws["blocks"]) - 1
+    for i, ((cin, cout, stride), b) in enumerate(zip(STAGES, ws["blocks"])):
         if _fuse:
             h = ConvChain.apply(a, True, ((stride, 1), (1, 1)), b["c1"], b["c2"])
         else:
             h = F.relu(ConvBN.apply(a, b["c1"], stride, 1, True))
             h = ConvBN.apply(h, b["c2"], 1, 1, True)
         sc = ConvBN.apply(a, b["sc"], stride, 0, True) if "sc" in b else a
-        a = F.relu(h + sc)
+        a = AddRelu.apply(h, sc, i != last) if _fuse else F.relu(h + sc)
     a = F.adaptive_avg_pool2d(a, 1).flatten(1)
     loss = F.cross_entropy(Linear.apply(a, ws["fc"]), labels)
     loss.backward()

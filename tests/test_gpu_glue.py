@@ -1,0 +1,59 @@
+"""GPU parity of the network plumbing (stem pooling fused with Range BN + ReLU, residual add + ReLU with
+the quantization of its result, ReLU backward) against the oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from gpu_util import close, dev, host, require_gpu, same_ints, same_qparams
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 8, 8), (1, 2, 7, 9), (3, 64, 112, 112), (2, 5, 33, 20), (1, 1, 1, 2)])
+def test_stem_pooling_forward_and_backward(shape):
+    q8t = require_gpu()
+    g = synth.rng(sum(shape))
+    x = synth.normal(g, shape, std=1.0)
+    C = shape[1]
+    gamma = synth.normal(g, (C,), std=1.0)
+    beta = synth.normal(g, (C,), std=0.3)
+    stats = oracle.range_bn_stats(x)
+    out, idx = q8t.range_bn_relu_maxpool_fwd(dev(x), dev(stats), dev(gamma), dev(beta), 1e-5)
+    oout, oidx = oracle.range_bn_relu_maxpool_fwd(x, stats, gamma, beta, 1e-5)
+    same_ints(host(out), oout)          # a maximum of bit-identical values
+    same_ints(host(idx), oidx)
+    gp = synth.normal(g, oout.shape, std=1e-2)
+    dy = q8t.maxpool_relu_bwd(dev(gp), idx, shape[2], shape[3])
+    ody = oracle.maxpool_relu_bwd(gp, oidx, shape[2], shape[3])
+    close(host(dy), ody)                # up to four float terms per position, added in the same order
+    same_ints(host(dy) == 0, ody == 0)
+
+
+@pytest.mark.parametrize("n", [1, 7, 4099, 1 << 20, (1 << 22) + 5])
+def test_add_relu_with_quantization_matches_the_separate_steps(n):
+    q8t = require_gpu()
+    g = synth.rng(n)
+    a, b = synth.normal(g, (n,), std=1.0), synth.normal(g, (n,), std=0.5)
+    out, q, qp = q8t.add_relu_quantize(dev(a), dev(b))
+    oout, omax = oracle.add_relu(a, b)
+    same_ints(host(out), oout)
+    sq, _, oqp = oracle.quantize(oout, 8)        # the plain two-pass quantization of the result
+    same_qparams(q8t, qp, oqp)
+    same_ints(host(q), sq)
+    out2, q2, _ = q8t.add_relu_quantize(dev(a), dev(b), quantized=False)
+    assert q2 is None and np.array_equal(host(out2), oout)
+    # nothing positive: range [0, 0]
+    out3, q3, qp3 = q8t.add_relu_quantize(dev(-np.abs(a)), dev(-np.abs(b)))
+    sq3, _, oqp3 = oracle.quantize(np.zeros(n, np.float32), 8)
+    same_qparams(q8t, qp3, oqp3)
+    same_ints(host(q3), sq3)
+
+
+@pytest.mark.parametrize("n", [1, 6, 4099, (1 << 21) + 3])
+def test_relu_backward_with_and_without_the_other_branch(n):
+    q8t = require_gpu()
+    g = synth.rng(n + 1)
+    gr, out, other = synth.normal(g, (n,), std=1.0), np.maximum(synth.normal(g, (n,), std=1.0), 0), synth.normal(g, (n,), std=1.0)
+    same_ints(host(q8t.relu_bwd_add(dev(gr), dev(out))), oracle.relu_bwd_add(gr, out))
+    same_ints(host(q8t.relu_bwd_add(dev(gr), dev(out), dev(other))), oracle.relu_bwd_add(gr, out, other))
