@@ -34,6 +34,14 @@ bool wgrad_wants_gemm(const q8t_conv_desc *d)
     return (double)d->K * d->C * d->R * d->S * d->N * P * Q >= 4194304.0;
 }
 
+// bytes of partial statistics that the forward kernel for this shape writes from its epilogue (0: none there)
+size_t stats_in_epilogue_ws(const q8t_conv_desc *d)
+{
+    if (q8t_nhwc_conv_supported(0, d)) return q8t_nhwc_conv_stats_ws(d);
+    if (smallc_wanted(0, d)) return q8t_smallc_conv_stats_ws(d);
+    return 0;
+}
+
 }  // namespace
 
 extern "C" {
@@ -97,8 +105,8 @@ int q8t_qconv_fwd(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams
     if (q8t_fast_conv_supported(0, desc, qx, qw, y, acc_out))
         return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, nullptr, ws, (hipStream_t)stream);
     if (q8t_nhwc_conv_supported(0, desc))
-        return q8t_nhwc_conv(0, desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
-    if (smallc_wanted(0, desc)) return q8t_smallc_conv(desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
+        return q8t_nhwc_conv(0, desc, qx, px, qw, pw, y, acc_out, nullptr, nullptr, ws, (hipStream_t)stream);
+    if (smallc_wanted(0, desc)) return q8t_smallc_conv(desc, qx, px, qw, pw, y, acc_out, nullptr, nullptr, ws, (hipStream_t)stream);
     return q8t_generic_conv(0, desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
 }
 
@@ -107,7 +115,12 @@ size_t q8t_qconv_fwd_bn_stats_workspace_size(const q8t_conv_desc *desc)
     if (!desc || desc->stride < 1) return 0;
     const int P = (desc->H + 2 * desc->pad - desc->R) / desc->stride + 1, Q = (desc->W + 2 * desc->pad - desc->S) / desc->stride + 1;
     const size_t c = (q8t_qconv_workspace_size(desc, 0) + 255) & ~(size_t)255;
-    return c + q8t_range_bn_workspace_size(desc->N, desc->K, P, Q);
+    // behind the product's own workspace: the partial statistics of its epilogue, or the workspace of a
+    // statistics pass over the result where the kernel for this shape gathers none
+    size_t s = q8t_range_bn_workspace_size(desc->N, desc->K, P, Q);
+    const size_t e = stats_in_epilogue_ws(desc);
+    if (e > s) s = e;
+    return c + s;
 }
 
 int q8t_qconv_fwd_bn_stats(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams *px, const int8_t *qw,
@@ -121,6 +134,11 @@ int q8t_qconv_fwd_bn_stats(const q8t_conv_desc *desc, const int8_t *qx, const q8
     // and then the statistics pass of the Range BN over its result
     if (q8t_fast_conv_supported(0, desc, qx, qw, y, acc_out))
         return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, stats_out, ws, (hipStream_t)stream);
+    void *sws = (char *)ws + ((q8t_qconv_workspace_size(desc, 0) + 255) & ~(size_t)255);
+    if (q8t_nhwc_conv_supported(0, desc))
+        return q8t_nhwc_conv(0, desc, qx, px, qw, pw, y, acc_out, stats_out, sws, ws, (hipStream_t)stream);
+    if (smallc_wanted(0, desc) && q8t_smallc_conv_stats_ws(desc))
+        return q8t_smallc_conv(desc, qx, px, qw, pw, y, acc_out, stats_out, sws, ws, (hipStream_t)stream);
     const int rc2 = q8t_qconv_fwd(desc, qx, px, qw, pw, y, acc_out, ws, stream);
     if (rc2) return rc2;
     const int P = (desc->H + 2 * desc->pad - desc->R) / desc->stride + 1, Q = (desc->W + 2 * desc->pad - desc->S) / desc->stride + 1;
@@ -137,7 +155,7 @@ int q8t_qconv_dgrad(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qpar
     if (q8t_fast_conv_supported(1, desc, qdy, qw, dx, acc_out))
         return q8t_fast_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, nullptr, ws, (hipStream_t)stream);
     if (q8t_nhwc_conv_supported(1, desc))
-        return q8t_nhwc_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, ws, (hipStream_t)stream);
+        return q8t_nhwc_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, nullptr, nullptr, ws, (hipStream_t)stream);
     return q8t_generic_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, ws, (hipStream_t)stream);
 }
 

@@ -127,13 +127,7 @@ __device__ __forceinline__ int dot4_ones(int v, int acc) { return __builtin_amdg
 // it in sub-tiles of 256 rows.  Consecutive workgroup ids go round-robin over the 8 XCDs, so the
 // ranges are dealt out such that each XCD works on one contiguous stretch of the tensor
 // (neighbouring ranges share halo rows, and then an L2).
-// Per-workgroup statistics of the corrected integer outputs of one output channel, for the Range
-// BN that follows the convolution (Sec. 3; Sec. 4 notes that the normalizer already knows the
-// range).  y = scale*acc is monotone in acc, so min/max of y are the images of these.
-struct ConvStat {
-    long long sum;
-    int mn, mx;
-};
+typedef Q8tConvStat ConvStat;
 
 struct Sched {
     int nbx;          // workgroups along the rows (multiple of 8)
@@ -543,6 +537,14 @@ FastDiv mkdiv(int d)
 }
 
 }  // namespace
+
+int q8t_conv_stats_finalize(const Q8tConvStat *part, int K, int nbx, int nact, double n, const q8t_qparams *qa,
+                            const q8t_qparams *qb, float *stats, hipStream_t st)
+{
+    hipLaunchKernelGGL(conv_stats_finalize, dim3((unsigned)K), dim3(256), 0, st, part, K, nbx, nact, n, qa, qb, stats);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
 
 bool q8t_fast_conv_supported(int which, const q8t_conv_desc *d, const void *a, const void *b, const void *out_f,
                              const void *out_acc)

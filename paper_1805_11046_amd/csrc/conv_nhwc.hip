@@ -243,7 +243,8 @@ __global__ __launch_bounds__(C::THREADS, C::MINB) void igemm_nhwc(const int8_t *
                                                                    const q8t_qparams *__restrict__ qpb, Geo g,
                                                                    const int *__restrict__ tapoff,
                                                                    const int *__restrict__ clsinfo,
-                                                                   float *__restrict__ out_f, int32_t *__restrict__ out_acc)
+                                                                   float *__restrict__ out_f, int32_t *__restrict__ out_acc,
+                                                                   Q8tConvStat *__restrict__ bnpart)
 {
     constexpr int MT = C::MT, NT = C::NT, BM = C::BM, BN = C::BN;
     extern __shared__ __align__(16) int8_t smem[];
@@ -356,6 +357,15 @@ __global__ __launch_bounds__(C::THREADS, C::MINB) void igemm_nhwc(const int8_t *
     uint32_t csn[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) csn[nt] = (uint32_t)za * (uint32_t)colsum[n0 + colbase + nt * 16 + l16];
+    // statistics of the lane's output channels over its rows, for the Range BN behind a forward product
+    long long st_s[NT];
+    int st_mn[NT], st_mx[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        st_s[nt] = 0;
+        st_mn[nt] = 2147483647;
+        st_mx[nt] = -2147483647 - 1;
+    }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
         const int r0 = rowbase + mt * 16 + kb * 4;
@@ -423,6 +433,15 @@ __global__ __launch_bounds__(C::THREADS, C::MINB) void igemm_nhwc(const int8_t *
             int c[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) c[j] = (int)((uint32_t)acc[mt][nt][j] + t[j] - csn[nt]);
+            if (bnpart) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (o[j] >= 0) {
+                        st_s[nt] += c[j];
+                        st_mn[nt] = min(st_mn[nt], c[j]);
+                        st_mx[nt] = max(st_mx[nt], c[j]);
+                    }
+            }
             if (contig && (((o[0] + cb) & 3) == 0)) {
                 if (out_acc) *reinterpret_cast<int4 *>(out_acc + o[0] + cb) = make_int4(c[0], c[1], c[2], c[3]);
                 if (out_f) {
@@ -441,6 +460,34 @@ __global__ __launch_bounds__(C::THREADS, C::MINB) void igemm_nhwc(const int8_t *
                     if (out_f) out_f[o[j] + cb] = sc * (float)c[j];
                 }
             }
+        }
+    }
+    if (bnpart) {
+        // fold the lanes that share a channel through LDS slots (the operand tiles are no longer needed)
+        unsigned long long *slot_s = reinterpret_cast<unsigned long long *>(smem);
+        int *slot_mn = reinterpret_cast<int *>(slot_s + BN), *slot_mx = slot_mn + BN;
+        __syncthreads();
+        if (tid < BN) {
+            slot_s[tid] = 0;
+            slot_mn[tid] = 2147483647;
+            slot_mx[tid] = -2147483647 - 1;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int ch = colbase + nt * 16 + l16;
+            atomicAdd(&slot_s[ch], (unsigned long long)st_s[nt]);
+            atomicMin(&slot_mn[ch], st_mn[nt]);
+            atomicMax(&slot_mx[ch], st_mx[nt]);
+        }
+        __syncthreads();
+        if (tid < BN) {
+            const int k = n0 + tid;
+            Q8tConvStat r;
+            r.sum = (long long)slot_s[tid];
+            r.mn = slot_mn[tid];
+            r.mx = slot_mx[tid];
+            bnpart[((size_t)(k >> 6) * g.mtiles + m0 / BM) * 64 + (k & 63)] = r;
         }
     }
 }
@@ -772,7 +819,8 @@ __global__ __launch_bounds__(kThreads) void smallc_fused(const int8_t *__restric
                                                          const int8_t *__restrict__ wt, const int *__restrict__ colsum,
                                                          const q8t_qparams *__restrict__ qpx,
                                                          const q8t_qparams *__restrict__ qpw, float *__restrict__ out_f,
-                                                         int32_t *__restrict__ out_acc, int vec, int vec4, int RPB)
+                                                         int32_t *__restrict__ out_acc, int vec, int vec4, int RPB,
+                                                         Q8tConvStat *__restrict__ bnpart)
 {
     constexpr int U = 6;   // dwords of input a thread carries from one output row to the next
     extern __shared__ __align__(16) int8_t lds[];
@@ -799,6 +847,14 @@ __global__ __launch_bounds__(kThreads) void smallc_fused(const int8_t *__restric
     const int W4 = W >> 2, items = CR * W4;
     const bool carry = vec4 && items <= kThreads * U;
     const bool filter_once = K == 64;
+    // statistics of the lane's four output channels (bnpart is only given with one block of 64 channels)
+    long long st_s[4] = {0, 0, 0, 0};
+    int st_mn[4], st_mx[4];
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+        st_mn[nt] = 2147483647;
+        st_mx[nt] = -2147483647 - 1;
+    }
     uint32_t pv[U];
     int pd[U], prow[U];        // LDS offset of the thread's dword (-1: none); filter row minus padding
     const int8_t *psrc[U];     // its source, at input row 0
@@ -948,6 +1004,15 @@ __global__ __launch_bounds__(kThreads) void smallc_fused(const int8_t *__restric
                         int c4[4];
 #pragma unroll
                         for (int j = 0; j < 4; ++j) c4[j] = (int)((uint32_t)acc[i][nt][j] + t[j] - cs);
+                        if (bnpart) {
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+                                if (r0 + j < qc) {
+                                    st_s[nt] += c4[j];
+                                    st_mn[nt] = min(st_mn[nt], c4[j]);
+                                    st_mx[nt] = max(st_mx[nt], c4[j]);
+                                }
+                        }
                         const size_t o = (((size_t)n * K + k) * P + p) * Q + q0 + r0;
                         if (vec && r0 + 3 < qc) {
                             if (out_acc) *reinterpret_cast<int4 *>(out_acc + o) = make_int4(c4[0], c4[1], c4[2], c4[3]);
@@ -965,6 +1030,32 @@ __global__ __launch_bounds__(kThreads) void smallc_fused(const int8_t *__restric
                     }
                 }
             }
+        }
+    }
+    if (bnpart) {
+        // fold the 16 lanes that share a channel through LDS slots (the operand tile is no longer needed)
+        unsigned long long *slot_s = reinterpret_cast<unsigned long long *>(lds);
+        int *slot_mn = reinterpret_cast<int *>(slot_s + 64), *slot_mx = slot_mn + 64;
+        __syncthreads();
+        if (tid < 64) {
+            slot_s[tid] = 0;
+            slot_mn[tid] = 2147483647;
+            slot_mx[tid] = -2147483647 - 1;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            atomicAdd(&slot_s[nt * 16 + l16], (unsigned long long)st_s[nt]);
+            atomicMin(&slot_mn[nt * 16 + l16], st_mn[nt]);
+            atomicMax(&slot_mx[nt * 16 + l16], st_mx[nt]);
+        }
+        __syncthreads();
+        if (tid < 64) {
+            Q8tConvStat r;
+            r.sum = (long long)slot_s[tid];
+            r.mn = slot_mn[tid];
+            r.mx = slot_mx[tid];
+            bnpart[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 64 + tid] = r;
         }
     }
 }
@@ -1110,12 +1201,33 @@ size_t q8t_smallc_conv_ws(int which, const q8t_conv_desc *d)
     return make_small_plan(which, d, &p) ? p.total : 0;
 }
 
+namespace {
+// the fused kernel runs (operand tile, filter block, row sums and staged rows fit into 64 KB of LDS)
+bool smallc_is_fused(const q8t_conv_desc *d, const SmallPlan &p)
+{
+    const int Ls = (d->pad + 3) & ~3, pitch = (Ls + d->W + d->pad + 3) & ~3;
+    const size_t fused_lds = (size_t)(p.Kf >> 6) * (FUSED_MAXQ + 64) * 64 + (size_t)FUSED_MAXQ * sizeof(int) +
+                             (((size_t)d->C * d->R * pitch + 15) & ~(size_t)15) + 16;
+    return p.GP && fused_lds <= 65536;
+}
+constexpr int kSmallRPB = 4;   // output rows per workgroup of the fused kernel
+}  // namespace
+
+size_t q8t_smallc_conv_stats_ws(const q8t_conv_desc *d)
+{
+    SmallPlan p;
+    if (!make_small_plan(0, d, &p) || d->K != 64 || !smallc_is_fused(d, p)) return 0;
+    return (size_t)((p.P + kSmallRPB - 1) / kSmallRPB) * d->N * 64 * sizeof(Q8tConvStat);
+}
+
 int q8t_smallc_conv(const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b, const q8t_qparams *qb,
-                    float *out_f, void *out_acc, void *ws, hipStream_t st)
+                    float *out_f, void *out_acc, float *bn_stats, void *stats_ws, void *ws, hipStream_t st)
 {
     SmallPlan p;
     if (!make_small_plan(0, d, &p)) return Q8T_ERR_SHAPE;
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    if (bn_stats && (!q8t_smallc_conv_stats_ws(d) || !stats_ws || !q8t_aligned(stats_ws, 16))) return Q8T_ERR_WORKSPACE;
+    Q8tConvStat *bnp = bn_stats ? (Q8tConvStat *)stats_ws : (Q8tConvStat *)nullptr;
     int8_t *xn = (int8_t *)ws;
     int *rowsum = (int *)((char *)ws + p.o_rowsum);
     int8_t *wt = (int8_t *)ws + p.o_wt;
@@ -1132,17 +1244,21 @@ int q8t_smallc_conv(const q8t_conv_desc *d, const void *a, const q8t_qparams *qa
         Q8T_LAUNCH_CHECK();
         // 16-byte stores need rows of the result that start on 16 bytes
         const int vec = p.Q % 4 == 0 && q8t_aligned(out_f, 16) && q8t_aligned(out_acc, 16);
-        const int RPB = 4;   // output rows per workgroup
+        const int RPB = kSmallRPB;
         const dim3 grid((unsigned)((p.P + RPB - 1) / RPB), (unsigned)d->N);
         if (p.GP == 8)
             hipLaunchKernelGGL(smallc_fused<8>, grid, dim3(kThreads), fused_lds, st, (const int8_t *)a, d->C, d->H, d->W, d->R,
                                d->S, d->stride, d->pad, p.P, p.Q, p.Kf, d->K, wt, colsum, qa, qb, out_f, (int32_t *)out_acc,
-                               vec, vec4, RPB);
+                               vec, vec4, RPB, bnp);
         else
             hipLaunchKernelGGL(smallc_fused<4>, grid, dim3(kThreads), fused_lds, st, (const int8_t *)a, d->C, d->H, d->W, d->R,
                                d->S, d->stride, d->pad, p.P, p.Q, p.Kf, d->K, wt, colsum, qa, qb, out_f, (int32_t *)out_acc,
-                               vec, vec4, RPB);
+                               vec, vec4, RPB, bnp);
         Q8T_LAUNCH_CHECK();
+        if (bnp) {
+            const int nwg = (int)(grid.x * grid.y);
+            return q8t_conv_stats_finalize(bnp, 64, nwg, nwg, (double)d->N * p.P * p.Q, qa, qb, bn_stats, st);
+        }
         return Q8T_OK;
     }
     int *clsinfo = tapoff + 8;   // the tap table of this path has one entry
@@ -1175,7 +1291,8 @@ int q8t_smallc_conv(const q8t_conv_desc *d, const void *a, const q8t_qparams *qa
         g.mtiles = (g.M + CFG::BM - 1) / CFG::BM;                                                                     \
         const int64_t tiles = (int64_t)g.mtiles * (d->K / CFG::BN);                                                   \
         hipLaunchKernelGGL(igemm_nhwc<CFG>, dim3(q8t_gemm::xcd_grid(tiles)), dim3(CFG::THREADS), conv_lds_bytes<CFG>(), \
-                           st, xn, rowsum, wt, colsum, qa, qb, g, tapoff, clsinfo, out_f, (int32_t *)out_acc);        \
+                           st, xn, rowsum, wt, colsum, qa, qb, g, tapoff, clsinfo, out_f, (int32_t *)out_acc,         \
+                           (Q8tConvStat *)nullptr);                                                                \
     }
     if (d->K % 128 == 0) Q8T_GO(q8t_gemm::Mid)
     else Q8T_GO(q8t_gemm::Small)
@@ -1196,12 +1313,24 @@ size_t q8t_nhwc_conv_ws(int which, const q8t_conv_desc *d)
     return make_plan(which, d, &p) ? p.total : 0;
 }
 
+size_t q8t_nhwc_conv_stats_ws(const q8t_conv_desc *d)
+{
+    Plan p;
+    if (!make_plan(0, d, &p)) return 0;
+    // one partial per (128-row tile, output channel); larger tiles need fewer
+    const int64_t M = (int64_t)d->N * p.OHf * p.OWf;
+    return (size_t)((M + 127) / 128) * p.oc * sizeof(Q8tConvStat);
+}
+
 int q8t_nhwc_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
-                  const q8t_qparams *qb, float *out_f, void *out_acc, void *ws, hipStream_t st)
+                  const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *stats_ws, void *ws,
+                  hipStream_t st)
 {
     Plan p;
     if (!make_plan(which, d, &p)) return Q8T_ERR_SHAPE;
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    if (bn_stats && (which != 0 || !stats_ws || !q8t_aligned(stats_ws, 16))) return Q8T_ERR_WORKSPACE;
+    Q8tConvStat *bnp = bn_stats ? (Q8tConvStat *)stats_ws : (Q8tConvStat *)nullptr;
     int8_t *xn = (int8_t *)ws;
     int *chansum = (int *)((char *)ws + p.o_chansum);
     int8_t *wt = (int8_t *)ws + p.o_wt;
@@ -1329,12 +1458,14 @@ int q8t_nhwc_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
         if (tiles > 0)                                                                                               \
             hipLaunchKernelGGL(igemm_nhwc<CFG>, dim3(q8t_gemm::xcd_grid(tiles)), dim3(CFG::THREADS),                 \
                                conv_lds_bytes<CFG>(), st, xn, chansum, wt, colsum, qa, qb, g, tapoff, clsinfo, out_f, \
-                               (int32_t *)out_acc);                                                                  \
+                               (int32_t *)out_acc, bnp);                                                             \
     }
     if (p.oc % 256 == 0 && (int64_t)((maxM + 255) / 256) * ncls * (p.oc / 256) >= 128) Q8T_GO(q8t_gemm::Big)
     else if (p.oc % 128 == 0) Q8T_GO(q8t_gemm::Mid)
     else Q8T_GO(q8t_gemm::Small)
 #undef Q8T_GO
     Q8T_LAUNCH_CHECK();
+    if (bnp)   // forward: one class, every row tile wrote its partial
+        return q8t_conv_stats_finalize(bnp, p.oc, g.mtiles, g.mtiles, (double)maxM, qa, qb, bn_stats, st);
     return Q8T_OK;
 }

@@ -14,6 +14,18 @@ int q8t_generic_conv(int which, const q8t_conv_desc *d, const void *a, const q8t
 size_t q8t_generic_conv_ws(int which, const q8t_conv_desc *d);
 int q8t_conv_reduction_check(int which, const q8t_conv_desc *d);
 
+// Per-workgroup statistics of the corrected integer outputs of one output channel, gathered in a
+// convolution's epilogue for the Range BN that follows it (Sec. 3; Sec. 4: the normalizer already
+// knows the range).  y = scale * acc is monotone in acc, so min / max of y are the images of these.
+// Layout of a partial buffer: [channel / 64][nbx workgroups][channel % 64].
+struct Q8tConvStat {
+    long long sum;
+    int mn, mx;
+};
+// stats[0][k] = mean, [1][k] = min, [2][k] = max over n values per channel, from nact (<= nbx) partials (conv_fast.hip)
+int q8t_conv_stats_finalize(const Q8tConvStat *part, int K, int nbx, int nact, double n, const q8t_qparams *qa,
+                            const q8t_qparams *qb, float *stats, hipStream_t st);
+
 // specialised convolution kernels (conv_fast.hip)
 bool q8t_fast_conv_supported(int which, const q8t_conv_desc *d, const void *a, const void *b, const void *out_f,
                              const void *out_acc);
@@ -29,14 +41,20 @@ int q8t_range_bn_stats(const float *x, int N, int C, int H, int W, float *stats_
 // layer gradient, channel counts that are multiples of 64
 bool q8t_nhwc_conv_supported(int which, const q8t_conv_desc *d);
 size_t q8t_nhwc_conv_ws(int which, const q8t_conv_desc *d);
+// bn_stats (nullable, forward only): [3][K] mean / min / max of the float result, gathered in the epilogue
+// through stats_ws (q8t_nhwc_conv_stats_ws bytes, 16-byte aligned)
 int q8t_nhwc_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
-                  const q8t_qparams *qb, float *out_f, void *out_acc, void *ws, hipStream_t st);
+                  const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *stats_ws, void *ws,
+                  hipStream_t st);
+size_t q8t_nhwc_conv_stats_ws(const q8t_conv_desc *d);
 
 // forward with fewer than 64 input channels (first layer): explicit im2col rows + the same GEMM
 bool q8t_smallc_conv_supported(int which, const q8t_conv_desc *d);
 size_t q8t_smallc_conv_ws(int which, const q8t_conv_desc *d);
+// bn_stats as for q8t_nhwc_conv; only where q8t_smallc_conv_stats_ws(d) != 0 (one block of 64 output channels, fused kernel)
 int q8t_smallc_conv(const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b, const q8t_qparams *qb,
-                    float *out_f, void *out_acc, void *ws, hipStream_t st);
+                    float *out_f, void *out_acc, float *bn_stats, void *stats_ws, void *ws, hipStream_t st);
+size_t q8t_smallc_conv_stats_ws(const q8t_conv_desc *d);
 
 // specialised 3x3 weight-gradient kernel (wgrad_fast.hip)
 bool q8t_fast_wgrad_supported(const q8t_conv_desc *d, const void *g16, const void *x, const void *dw,

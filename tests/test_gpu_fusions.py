@@ -15,8 +15,17 @@ CASES = [
     (9, 64, 14, 14, 128, 3, 3, 1, 1),    # two output-channel chunks
     (2, 256, 10, 10, 64, 1, 1, 1, 0),
     (40, 64, 6, 6, 64, 3, 3, 1, 1),      # more workgroups than rows to give them: inactive ones must not count
-    (2, 64, 16, 16, 128, 3, 3, 2, 1),    # other shapes: product, then the statistics pass
-    (2, 3, 7, 6, 4, 3, 3, 1, 1),
+    (2, 64, 16, 16, 128, 3, 3, 2, 1),    # strided: statistics from the epilogue of the implicit-GEMM kernel
+    (5, 64, 28, 28, 128, 3, 3, 2, 1),    # ragged last row tile
+    (3, 128, 14, 14, 256, 3, 3, 2, 1),   # 256-channel tiles
+    (7, 64, 28, 28, 128, 1, 1, 2, 0),    # 1x1 projection at stride 2
+    (11, 256, 7, 7, 512, 3, 3, 1, 1),    # 7x7 planes
+    (3, 128, 15, 13, 64, 3, 3, 1, 1),    # odd plane at stride 1
+    (6, 3, 64, 64, 64, 7, 7, 2, 3),      # first layer: statistics from the fused small-channel kernel
+    (3, 3, 45, 52, 64, 7, 7, 2, 3),      # ... ragged rows per workgroup
+    (2, 3, 224, 224, 64, 7, 7, 2, 3),    # ... at its real plane size
+    (2, 3, 7, 6, 4, 3, 3, 1, 1),         # other shapes: product, then the statistics pass
+    (2, 3, 32, 32, 32, 7, 7, 2, 3),
 ]
 
 
