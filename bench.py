@@ -116,7 +116,30 @@ def roofline_of(name, records, steps):
     roof["kernel"] = name
     roof["launches_per_step"] = launches // steps
     roof["us_per_step"] = round(us / steps, 1)
+    roof["per_launch"]["algorithmic_bytes"] = round(nbytes / launches)
+    roof["traffic"], src = measured_traffic(name, launches // steps)
+    if src:
+        roof["traffic_source"] = src
     return roof
+
+
+def measured_traffic(name, launches_per_step):
+    """HBM bytes per launch from the committed counter summary of this same workload (two rocprofv3 --pmc runs,
+    calibrated on the copy kernel); None where the summary has no entry for the call or the batch is another one"""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic_resnet18_b256.json")
+    try:
+        with open(path) as f:
+            table = json.load(f)
+    except (OSError, ValueError):
+        return None, None
+    src = "profiles/hbm_traffic_resnet18_b256.json, measured at commit %s" % table.get("_measured_at_commit", "?")
+    for key, per_step in table.items():
+        if key.startswith("_") or key.endswith("_factor"):
+            continue
+        names = [k.strip() for k in key.replace("(+relu)", "").split("+")]
+        if name in names and len(names) == 1:
+            return round(per_step / launches_per_step), src
+    return None, None
 
 
 def resnet18(torch, batch, seed):
@@ -375,6 +398,9 @@ def main():
     assert bool(torch.isfinite(loss)) and all(p.grad is not None for p in params)
     ms_per_step = dt / args.steps * 1e3
     roofline = roofline_of(dominant, dom_records, args.steps)
+    if args.batch != 256:
+        roofline["traffic"] = None   # the counter summary is of the batch-256 step
+        roofline.pop("traffic_source", None)
 
     res = {
         "metric": "int8 qgemm TOPS (fwd/dgrad/wgrad, % MFMA peak); Range BN + quantize GB/s",
