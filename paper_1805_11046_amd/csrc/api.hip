@@ -85,6 +85,10 @@ size_t q8t_qconv_workspace_size(const q8t_conv_desc *desc, int which)
     if (!desc || which < 0 || which > 2) return 0;
     size_t g = q8t_generic_conv_ws(which, desc);
     size_t f = q8t_fast_conv_ws(which, desc);
+    if (which < 2) {
+        const size_t wd = q8t_wide_conv_ws(which, desc);
+        if (wd > f) f = wd;
+    }
     if (which == 2) {
         f = q8t_fast_wgrad_ws(desc);
         const size_t pw = q8t_planes_wgrad_ws(desc);
@@ -102,6 +106,8 @@ int q8t_qconv_fwd(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams
     if (!desc || !qx || !px || !qw || !pw || (!y && !acc_out)) return Q8T_ERR_NULL;
     const int rc = q8t_conv_reduction_check(0, desc);
     if (rc) return rc;
+    if (q8t_wide_conv_supported(0, desc, qx, y, acc_out))
+        return q8t_wide_conv(0, desc, qx, px, qw, pw, y, acc_out, nullptr, ws, (hipStream_t)stream);
     if (q8t_fast_conv_supported(0, desc, qx, qw, y, acc_out))
         return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, nullptr, ws, (hipStream_t)stream);
     if (q8t_nhwc_conv_supported(0, desc))
@@ -132,6 +138,8 @@ int q8t_qconv_fwd_bn_stats(const q8t_conv_desc *desc, const int8_t *qx, const q8
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
     // the specialised kernel gathers the statistics in its epilogue; other shapes run the product
     // and then the statistics pass of the Range BN over its result
+    if (q8t_wide_conv_supported(0, desc, qx, y, acc_out))
+        return q8t_wide_conv(0, desc, qx, px, qw, pw, y, acc_out, stats_out, ws, (hipStream_t)stream);
     if (q8t_fast_conv_supported(0, desc, qx, qw, y, acc_out))
         return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, stats_out, ws, (hipStream_t)stream);
     void *sws = (char *)ws + ((q8t_qconv_workspace_size(desc, 0) + 255) & ~(size_t)255);
@@ -152,6 +160,8 @@ int q8t_qconv_dgrad(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qpar
     if (!desc || !qdy || !pg || !qw || !pw || (!dx && !acc_out)) return Q8T_ERR_NULL;
     const int rc = q8t_conv_reduction_check(1, desc);
     if (rc) return rc;
+    if (q8t_wide_conv_supported(1, desc, qdy, dx, acc_out))
+        return q8t_wide_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, nullptr, ws, (hipStream_t)stream);
     if (q8t_fast_conv_supported(1, desc, qdy, qw, dx, acc_out))
         return q8t_fast_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, nullptr, ws, (hipStream_t)stream);
     if (q8t_nhwc_conv_supported(1, desc))

@@ -34,6 +34,13 @@ size_t q8t_fast_conv_ws(int which, const q8t_conv_desc *d);
 int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
                   const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *ws, hipStream_t st);
 
+// 3x3 stride-1 layers with many channels on small planes: 128 x 256 tiles, activations staged once per
+// 64-channel chunk, weights streamed (conv_wide.hip).  Same contract as q8t_fast_conv.
+bool q8t_wide_conv_supported(int which, const q8t_conv_desc *d, const void *a, const void *out_f, const void *out_acc);
+size_t q8t_wide_conv_ws(int which, const q8t_conv_desc *d);
+int q8t_wide_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
+                  const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *ws, hipStream_t st);
+
 // Range BN statistics of an NCHW tensor alone (range_bn.hip); ws as for q8t_range_bn_fwd
 int q8t_range_bn_stats(const float *x, int N, int C, int H, int W, float *stats_out, void *ws, hipStream_t st);
 

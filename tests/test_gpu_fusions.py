@@ -15,6 +15,8 @@ CASES = [
     (9, 64, 14, 14, 128, 3, 3, 1, 1),    # two output-channel chunks
     (2, 256, 10, 10, 64, 1, 1, 1, 0),
     (40, 64, 6, 6, 64, 3, 3, 1, 1),      # more workgroups than rows to give them: inactive ones must not count
+    (3, 256, 14, 14, 256, 3, 3, 1, 1),   # wide-tile kernel: statistics per 32x32 tile column, ragged last tile
+    (5, 256, 7, 7, 512, 3, 3, 1, 1),     # ... unaligned planes, two column tiles
     (2, 64, 16, 16, 128, 3, 3, 2, 1),    # strided: statistics from the epilogue of the implicit-GEMM kernel
     (5, 64, 28, 28, 128, 3, 3, 2, 1),    # ragged last row tile
     (3, 128, 14, 14, 256, 3, 3, 2, 1),   # 256-channel tiles
