@@ -311,6 +311,9 @@ int q8t_tern_wgrad_multi(const float *g, const int8_t *a_codes, int M, int N, in
  *   second pass of the quantization runs.  ws: q8t_add_relu_quantize_workspace_size(n) bytes,
  *   8-byte aligned.
  * q8t_relu_bwd_add: res = (out > 0 ? g : 0) + other (other nullable: nothing added).
+ * q8t_relu_bwd_sum: the gradient that reaches a rectified tensor `out` from its two consumers (a residual
+ *   block's convolutions and its shortcut): res = out > 0 ? g1 + g2 : 0 in one pass, instead of a sum and a
+ *   masking pass.  out nullable: plain sum; g2 nullable: nothing added.
  * Errors: Q8T_ERR_SHAPE, Q8T_ERR_NULL, Q8T_ERR_WORKSPACE, Q8T_ERR_HIP. */
 int q8t_range_bn_relu_maxpool_fwd(const float *x, int N, int C, int H, int W, const float *gamma, const float *beta, float eps,
                                   const float *stats, float *out, uint8_t *idx, void *stream);
@@ -319,6 +322,7 @@ size_t q8t_add_relu_quantize_workspace_size(int64_t n);
 int q8t_add_relu_quantize(const float *a, const float *b, int64_t n, float *out, int8_t *q_out, q8t_qparams *qp_out, void *ws,
                           void *stream);
 int q8t_relu_bwd_add(const float *g, const float *out, const float *other, int64_t n, float *res, void *stream);
+int q8t_relu_bwd_sum(const float *g1, const float *g2, const float *out, int64_t n, float *res, void *stream);
 
 /* Measurement aid, not a step of the method: a plain streaming kernel of known traffic with the access
  * shape of the library's HBM-bound calls (every workgroup streams one contiguous slice, four 16-byte

@@ -421,6 +421,14 @@ def add_relu(a, b):
     return out, np.float32(mx.value)
 
 
+def relu_bwd_sum(g1, g2=None, out=None):
+    g1 = _f32(g1)
+    g2, out = _opt_f32(g2), _opt_f32(out)
+    res = np.empty(g1.shape, np.float32)
+    lib().orc_relu_bwd_sum(_p(g1), _p(g2), _p(out), C.c_int64(g1.size), _p(res))
+    return res
+
+
 def relu_bwd_add(g, out, other=None):
     g, out = _f32(g), _f32(out)
     other = _opt_f32(other)

@@ -941,6 +941,16 @@ void orc_add_relu(const float *a, const float *b, int64_t n, float *out, float *
     if (vmax) *vmax = mx;
 }
 
+/* gradient reaching a rectified tensor `out` from two consumers: (g1 + g2) where out > 0, else 0; out NULL: no
+ * rectifier in between (plain sum); g2 NULL: nothing added */
+void orc_relu_bwd_sum(const float *g1, const float *g2, const float *out, int64_t n, float *res)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        const float s = g2 ? g1[i] + g2[i] : g1[i];
+        res[i] = (!out || out[i] > 0.0f) ? s : 0.0f;
+    }
+}
+
 /* backward of out = relu(.): g passes where out > 0; with `other` (nullable) added to it */
 void orc_relu_bwd_add(const float *g, const float *out, const float *other, int64_t n, float *res)
 {

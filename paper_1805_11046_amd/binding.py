@@ -83,6 +83,7 @@ _SIGS = {
     "q8t_add_relu_quantize_workspace_size": (_sz, [_i64]),
     "q8t_add_relu_quantize": (_i, [_vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp]),
     "q8t_relu_bwd_add": (_i, [_vp, _vp, _vp, _i64, _vp, _vp]),
+    "q8t_relu_bwd_sum": (_i, [_vp, _vp, _vp, _i64, _vp, _vp]),
     "q8t_ternarize_workspace_size": (_sz, [_i64]),
     "q8t_ternarize": (_i, [_vp, _i64, _u64, _vp, _vp, _vp, _vp]),
     "q8t_binarize": (_i, [_vp, _i64, _vp, _vp]),
@@ -533,6 +534,14 @@ def add_relu_quantize(a, b, quantized=True, ws=None):
     _check(_lib.q8t_add_relu_quantize(_ptr(a), _ptr(b), n, _ptr(out), _ptr(q), _ptr(qp), _ptr(ws), _stream()),
            "q8t_add_relu_quantize")
     return out, q, qp
+
+
+def relu_bwd_sum(g1, g2=None, out=None):
+    """out > 0 ? g1 + g2 : 0 (out None: no mask; g2 None: nothing added)."""
+    _dev(g1)
+    res = torch.empty_like(g1)
+    _check(_lib.q8t_relu_bwd_sum(_ptr(g1), _ptr(g2), _ptr(out), g1.numel(), _ptr(res), _stream()), "q8t_relu_bwd_sum")
+    return res
 
 
 def relu_bwd_add(g, out, other=None):

@@ -231,6 +231,46 @@ __global__ __launch_bounds__(kThreads) void add_relu_fwd(const float *__restrict
     if (threadIdx.x == 0) partials[blockIdx.x] = make_float2(0.0f, mx);
 }
 
+// res = out > 0 ? g1 + g2 : 0 (out nullable: no mask; g2 nullable: nothing added)
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void relu_bwd_sum(const float *__restrict__ g1, const float *__restrict__ g2,
+                                                         const float *__restrict__ outv, int64_t n, float *__restrict__ res)
+{
+    if (VEC) {
+        const int64_t n4 = n >> 2;
+        const float4 *a4 = reinterpret_cast<const float4 *>(g1), *b4 = reinterpret_cast<const float4 *>(g2);
+        const float4 *o4 = reinterpret_cast<const float4 *>(outv);
+        float4 *r4 = reinterpret_cast<float4 *>(res);
+        const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
+        const int64_t lo = (int64_t)blockIdx.x * per, hi = min(n4, lo + per);
+#pragma unroll 2
+        for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads) {
+            float4 r = q8t_ld_last(a4 + i);
+            if (g2) {
+                const float4 t = q8t_ld_last(b4 + i);
+                r.x = r.x + t.x; r.y = r.y + t.y; r.z = r.z + t.z; r.w = r.w + t.w;
+            }
+            if (outv) {
+                const float4 v = q8t_ld_last(o4 + i);
+                r.x = v.x > 0.0f ? r.x : 0.0f; r.y = v.y > 0.0f ? r.y : 0.0f;
+                r.z = v.z > 0.0f ? r.z : 0.0f; r.w = v.w > 0.0f ? r.w : 0.0f;
+            }
+            r4[i] = r;
+        }
+        const int64_t tail = (n4 << 2) + (int64_t)blockIdx.x * kThreads + threadIdx.x;
+        if (tail < n) {
+            const float s = g2 ? g1[tail] + g2[tail] : g1[tail];
+            res[tail] = (!outv || outv[tail] > 0.0f) ? s : 0.0f;
+        }
+    } else {
+        const int64_t stride = (int64_t)gridDim.x * kThreads;
+        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+            const float s = g2 ? g1[i] + g2[i] : g1[i];
+            res[i] = (!outv || outv[i] > 0.0f) ? s : 0.0f;
+        }
+    }
+}
+
 // res = (out > 0 ? g : 0) [+ other]
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void relu_bwd_add(const float *__restrict__ g, const float *__restrict__ outv,
@@ -343,6 +383,20 @@ int q8t_add_relu_quantize(const float *a, const float *b, int64_t n, float *out,
     Q8T_LAUNCH_CHECK();
     if (!q_out) return Q8T_OK;
     return q8t_quantize8_from_partials(out, n, ws, grid, q_out, qp_out, st);
+}
+
+int q8t_relu_bwd_sum(const float *g1, const float *g2, const float *out, int64_t n, float *res, void *stream)
+{
+    if (n <= 0 || n > kMaxElements) return Q8T_ERR_SHAPE;
+    if (!g1 || !res) return Q8T_ERR_NULL;
+    const bool vec = q8t_aligned(g1, 16) && q8t_aligned(g2, 16) && q8t_aligned(out, 16) && q8t_aligned(res, 16);
+    const int grid = grid_for(vec ? (n >> 2) : n, 4, 4096);
+    if (vec)
+        hipLaunchKernelGGL(relu_bwd_sum<true>, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, g1, g2, out, n, res);
+    else
+        hipLaunchKernelGGL(relu_bwd_sum<false>, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, g1, g2, out, n, res);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
 }
 
 int q8t_relu_bwd_add(const float *g, const float *out, const float *other, int64_t n, float *res, void *stream)

@@ -98,38 +98,54 @@ def _bn_bwd(fn, name, ny, *args):
 
 
 _pending = []
-_seed = [1]
+_layer = [0]   # layers are numbered in forward order; a layer's backward draws its two roundings with seeds 2 id + 1, + 2
+
+
+def _next_layer():
+    _layer[0] += 1
+    return _layer[0]
+
+
+def _convbn_fwd(a, w, stride, pad):
+    """quantize -> conv forward (+ Range BN statistics) -> Range BN; returns the normalized tensor and what
+    the backward pass needs"""
+    a = a.contiguous()
+    n, c, h, wd = a.shape
+    k, _, r, s = w.shape
+    d = q8t.conv_desc(n, c, h, wd, k, r, s, stride, pad)
+    qa, pa = _quantize("quantize (activations)", a)
+    qw, pw = _quantize("quantize (weights)", w)
+    ops = 2.0 * n * d.P * d.Q * k * c * r * s
+    nx, ny = a.numel(), n * k * d.P * d.Q
+    y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw, tag=_tag(d))
+    bn, _, _ = _call("range_bn_fwd_apply", 0, 8 * ny, q8t.range_bn_fwd_apply, y, stats, None, None, 1e-5)
+    return bn, (d, qa, pa, qw, pw, y, stats, ops, nx, ny, _next_layer())
+
+
+def _convbn_bwd(saved, dbn, need_dx):
+    """Range BN backward + bifurcated gradient quantization -> layer gradient, weight gradient"""
+    d, qa, pa, qw, pw, y, stats, ops, nx, ny, lid = saved
+    _, _, _, g8, pg8, g16, pg16 = _bn_bwd(q8t.range_bn_bwd_bifurcate, "range_bn_bwd_bifurcate", ny, y, dbn.contiguous(),
+                                          stats, None, 1e-5, 2 * lid + 1, 2 * lid + 2)
+    dx = None
+    if need_dx:
+        dx, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d))
+    dw, _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
+    return dx, dw
 
 
 class ConvBN(torch.autograd.Function):
-    """quantize -> conv forward (+ Range BN statistics) -> Range BN;  backward: Range BN backward +
-    bifurcated gradient quantization -> layer gradient, weight gradient."""
+    """conv + Range BN as one autograd node (see _convbn_fwd / _convbn_bwd)."""
 
     @staticmethod
     def forward(ctx, a, w, stride, pad, need_dx):
-        a = a.contiguous()
-        n, c, h, wd = a.shape
-        k, _, r, s = w.shape
-        d = q8t.conv_desc(n, c, h, wd, k, r, s, stride, pad)
-        qa, pa = _quantize("quantize (activations)", a)
-        qw, pw = _quantize("quantize (weights)", w)
-        ops = 2.0 * n * d.P * d.Q * k * c * r * s
-        nx, ny = a.numel(), n * k * d.P * d.Q
-        y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw, tag=_tag(d))
-        bn, _, _ = _call("range_bn_fwd_apply", 0, 8 * ny, q8t.range_bn_fwd_apply, y, stats, None, None, 1e-5)
-        ctx.saved = (d, qa, pa, qw, pw, y, stats, need_dx, ops, nx, ny)
+        bn, ctx.saved = _convbn_fwd(a, w, stride, pad)
+        ctx.need_dx = need_dx
         return bn
 
     @staticmethod
     def backward(ctx, dbn):
-        d, qa, pa, qw, pw, y, stats, need_dx, ops, nx, ny = ctx.saved
-        _seed[0] += 2
-        _, _, _, g8, pg8, g16, pg16 = _bn_bwd(q8t.range_bn_bwd_bifurcate, "range_bn_bwd_bifurcate", ny, y, dbn.contiguous(),
-                                              stats, None, 1e-5, _seed[0], _seed[0] + 1)
-        dx = None
-        if need_dx:
-            dx, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d))
-        dw, _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
+        dx, dw = _convbn_bwd(ctx.saved, dbn, ctx.need_dx)
         return dx, dw, None, None, None
 
 
@@ -152,90 +168,109 @@ class StemConvBNPool(torch.autograd.Function):
         y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw, tag=_tag(d))
         pooled, idx = _call("range_bn_relu_maxpool_fwd", 0, 4 * ny + 5 * (ny // 4), q8t.range_bn_relu_maxpool_fwd, y, stats,
                             None, None, 1e-5)
-        ctx.saved = (d, qa, pa, y, stats, idx, ops, nx, ny)
+        ctx.saved = (d, qa, pa, y, stats, idx, ops, nx, ny, _next_layer())
         return pooled
 
     @staticmethod
     def backward(ctx, gp):
-        d, qa, pa, y, stats, idx, ops, nx, ny = ctx.saved
-        _seed[0] += 2
+        d, qa, pa, y, stats, idx, ops, nx, ny, lid = ctx.saved
         dy = _call("maxpool_relu_bwd", 0, 5 * (ny // 4) + 4 * ny, q8t.maxpool_relu_bwd, gp.contiguous(), idx, d.P, d.Q)
         _, _, _, g8, pg8, g16, pg16 = _bn_bwd(q8t.range_bn_bwd_bifurcate, "range_bn_bwd_bifurcate", ny, y, dy, stats, None, 1e-5,
-                                              _seed[0], _seed[0] + 1)
+                                              2 * lid + 1, 2 * lid + 2)
         dw, _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
         return None, dw, None, None
 
 
-class AddRelu(torch.autograd.Function):
-    """End of a residual block: relu(h + shortcut) in one pass that also leaves the 8-bit codes of the result behind
-    for the convolutions that read it next (no min/max pass: the range of a rectified tensor is [0, max])."""
+def _chain_fwd(a, specs, ws):
+    """conv -> Range BN -> ReLU -> conv -> Range BN [-> ReLU -> conv -> Range BN]: between two
+    convolutions the normalization, the ReLU and the 8-bit quantization of the next operand are one
+    pass that writes codes only (no fp32 activation, no separate quantization)"""
+    a = a.contiguous()
+    qa, pa = _quantize("quantize (activations)", a)
+    saved = []
+    shape = a.shape
+    for i, (w, (stride, pad)) in enumerate(zip(ws, specs)):
+        n, c, h, wd = shape
+        k, _, r, s = w.shape
+        d = q8t.conv_desc(n, c, h, wd, k, r, s, stride, pad)
+        qw, pw = _quantize("quantize (weights)", w)
+        ops = 2.0 * n * d.P * d.Q * k * c * r * s
+        nx, ny = n * c * h * wd, n * k * d.P * d.Q
+        y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw, tag=_tag(d))
+        saved.append((d, qa, pa, qw, pw, y, stats, ops, nx, ny, _next_layer()))
+        if i + 1 < len(ws):
+            _, qa, pa = _call("range_bn_relu_fwd_apply (int8 out)", 0, 5 * ny, q8t.range_bn_relu_fwd_apply, y, stats,
+                              None, None, 1e-5, True, False)
+        else:
+            out, _, _ = _call("range_bn_fwd_apply", 0, 8 * ny, q8t.range_bn_fwd_apply, y, stats, None, None, 1e-5)
+        shape = (n, k, d.P, d.Q)
+    return out, saved
 
-    @staticmethod
-    def forward(ctx, h, sc, quantized):
-        n = h.numel()
-        out, q, qp = _call("add_relu_quantize", 0, (17 if quantized else 12) * n, q8t.add_relu_quantize, h.contiguous(),
-                           sc.contiguous(), quantized)
-        if quantized:
-            _qcache[out.data_ptr()] = (q, qp)
-        ctx.out = out
-        return out
 
-    @staticmethod
-    def backward(ctx, g):
-        gm = _call("relu_bwd_add", 0, 12 * g.numel(), q8t.relu_bwd_add, g.contiguous(), ctx.out)
-        return gm, gm, None
+def _chain_bwd(saved, g, need_dx):
+    """backward of _chain_fwd: the ReLU mask is recomputed inside the Range BN backward"""
+    g = g.contiguous()
+    dws = [None] * len(saved)
+    for i in range(len(saved) - 1, -1, -1):
+        d, qa, pa, qw, pw, y, stats, ops, nx, ny, lid = saved[i]
+        if i + 1 == len(saved):
+            r = _bn_bwd(q8t.range_bn_bwd_bifurcate, "range_bn_bwd_bifurcate", ny, y, g, stats, None, 1e-5, 2 * lid + 1,
+                        2 * lid + 2)
+        else:
+            r = _bn_bwd(q8t.range_bn_relu_bwd_bifurcate, "range_bn_relu_bwd_bifurcate", ny, y, g, stats, None, None,
+                        1e-5, 2 * lid + 1, 2 * lid + 2)
+        g8, pg8, g16, pg16 = r[3:]
+        g = None
+        if i > 0 or need_dx:
+            g, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d))
+        dws[i], _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
+    return g, dws
 
 
 class ConvChain(torch.autograd.Function):
-    """conv -> Range BN -> ReLU -> conv -> Range BN [-> ReLU -> conv -> Range BN]: between two
-    convolutions the normalization, the ReLU and the 8-bit quantization of the next operand are one
-    pass that writes codes only (no fp32 activation, no separate quantization); in the backward
-    pass the ReLU mask is recomputed inside the Range BN backward."""
+    """a chain of convolutions with fused Range BN / ReLU / quantization between them as one autograd node"""
 
     @staticmethod
     def forward(ctx, a, need_dx, specs, *ws):
-        a = a.contiguous()
-        qa, pa = _quantize("quantize (activations)", a)
-        saved = []
-        shape = a.shape
-        for i, (w, (stride, pad)) in enumerate(zip(ws, specs)):
-            n, c, h, wd = shape
-            k, _, r, s = w.shape
-            d = q8t.conv_desc(n, c, h, wd, k, r, s, stride, pad)
-            qw, pw = _quantize("quantize (weights)", w)
-            ops = 2.0 * n * d.P * d.Q * k * c * r * s
-            nx, ny = n * c * h * wd, n * k * d.P * d.Q
-            y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw, tag=_tag(d))
-            saved.append((d, qa, pa, qw, pw, y, stats, ops, nx, ny))
-            if i + 1 < len(ws):
-                _, qa, pa = _call("range_bn_relu_fwd_apply (int8 out)", 0, 5 * ny, q8t.range_bn_relu_fwd_apply, y, stats,
-                                  None, None, 1e-5, True, False)
-            else:
-                out, _, _ = _call("range_bn_fwd_apply", 0, 8 * ny, q8t.range_bn_fwd_apply, y, stats, None, None, 1e-5)
-            shape = (n, k, d.P, d.Q)
+        out, saved = _chain_fwd(a, specs, ws)
         ctx.saved = (saved, need_dx)
         return out
 
     @staticmethod
     def backward(ctx, g):
         saved, need_dx = ctx.saved
-        g = g.contiguous()
-        dws = [None] * len(saved)
-        for i in range(len(saved) - 1, -1, -1):
-            d, qa, pa, qw, pw, y, stats, ops, nx, ny = saved[i]
-            _seed[0] += 2
-            if i + 1 == len(saved):
-                r = _bn_bwd(q8t.range_bn_bwd_bifurcate, "range_bn_bwd_bifurcate", ny, y, g, stats, None, 1e-5, _seed[0],
-                            _seed[0] + 1)
-            else:
-                r = _bn_bwd(q8t.range_bn_relu_bwd_bifurcate, "range_bn_relu_bwd_bifurcate", ny, y, g, stats, None, None,
-                            1e-5, _seed[0], _seed[0] + 1)
-            g8, pg8, g16, pg16 = r[3:]
-            g = None
-            if i > 0 or need_dx:
-                g, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d))
-            dws[i], _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
+        g, dws = _chain_bwd(saved, g, need_dx)
         return (g, None, None, *dws)
+
+
+class ResBlock(torch.autograd.Function):
+    """A whole basic block as one node: conv chain + shortcut (identity or 1x1 conv + Range BN) + add + ReLU with the
+    8-bit codes of the result left behind.  Its input gets gradients from both branches; they are summed -- and, when
+    the input is itself the rectified output of the previous block, masked by that rectifier -- in one pass
+    (`mask_input`), so the previous block receives an already masked gradient (`grad_is_masked`) and no separate
+    sum and masking passes run between blocks."""
+
+    @staticmethod
+    def forward(ctx, a, stride, quantized, mask_input, grad_is_masked, w1, w2, wsc):
+        h, chain = _chain_fwd(a, ((stride, 1), (1, 1)), (w1, w2))
+        sc, scs = (a, None) if wsc is None else _convbn_fwd(a, wsc, stride, 0)
+        n = h.numel()
+        out, q, qp = _call("add_relu_quantize", 0, (17 if quantized else 12) * n, q8t.add_relu_quantize, h.contiguous(),
+                           sc.contiguous(), quantized)
+        if quantized:
+            _qcache[out.data_ptr()] = (q, qp)
+        ctx.saved = (chain, scs, a if mask_input else None, out, grad_is_masked)
+        return out
+
+    @staticmethod
+    def backward(ctx, g):
+        chain, scs, a, out, grad_is_masked = ctx.saved
+        g = g.contiguous()
+        gm = g if grad_is_masked else _call("relu_bwd_add", 0, 12 * g.numel(), q8t.relu_bwd_add, g, out)
+        gc, (dw1, dw2) = _chain_bwd(chain, gm, True)
+        gs, dwsc = (gm, None) if scs is None else _convbn_bwd(scs, gm, True)
+        ga = _call("relu_bwd_sum", 0, (16 if a is not None else 12) * gc.numel(), q8t.relu_bwd_sum, gc, gs, a)
+        return ga, None, None, None, None, dw1, dw2, dwsc
 
 
 class Linear(torch.autograd.Function):
@@ -246,15 +281,14 @@ class Linear(torch.autograd.Function):
         qw, pw = _quantize("quantize (weights)", w)
         ops = 2.0 * a.shape[0] * a.shape[1] * w.shape[1]
         y, _ = _call("qgemm_fwd", ops, a.numel() + w.numel() + 4 * a.shape[0] * w.shape[1], q8t.qgemm_fwd, qa, pa, qw, pw)
-        ctx.saved = (qa, pa, qw, pw, ops)
+        ctx.saved = (qa, pa, qw, pw, ops, _next_layer())
         return y
 
     @staticmethod
     def backward(ctx, dy):
-        qa, pa, qw, pw, ops = ctx.saved
-        _seed[0] += 2
+        qa, pa, qw, pw, ops, lid = ctx.saved
         g8, pg8, g16, pg16 = _call("quantize_bifurcate", 0, 11 * dy.numel(), q8t.quantize_bifurcate, dy.contiguous(),
-                                   _seed[0], _seed[0] + 1)
+                                   2 * lid + 1, 2 * lid + 2)
         dx, _ = _call("qgemm_dgrad", ops, dy.numel() + qw.numel() + 4 * qa.numel(), q8t.qgemm_dgrad, g8, pg8, qw, pw)
         dw, _ = _call("qgemm_wgrad", ops, qa.numel() + 2 * dy.numel() + 4 * qw.numel(), q8t.qgemm_wgrad, qa, pa, g16, pg16)
         return dx, dw
@@ -284,6 +318,7 @@ def make_weights(dev, gen):
 
 def step(x, labels, ws):
     _qcache.clear()
+    _layer[0] = 0
     if _fuse:
         a = StemConvBNPool.apply(x, ws["conv1"], 2, 3)
     else:
@@ -292,12 +327,14 @@ def step(x, labels, ws):
     last = len(ws["blocks"]) - 1
     for i, ((cin, cout, stride), b) in enumerate(zip(STAGES, ws["blocks"])):
         if _fuse:
-            h = ConvChain.apply(a, True, ((stride, 1), (1, 1)), b["c1"], b["c2"])
+            # the first block's input is the pooled tensor (its rectifier is inside the pooling indices); the last
+            # block's output goes to torch's pooling, which hands back an unmasked gradient
+            a = ResBlock.apply(a, stride, i != last, i != 0, i != last, b["c1"], b["c2"], b.get("sc"))
         else:
             h = F.relu(ConvBN.apply(a, b["c1"], stride, 1, True))
             h = ConvBN.apply(h, b["c2"], 1, 1, True)
-        sc = ConvBN.apply(a, b["sc"], stride, 0, True) if "sc" in b else a
-        a = AddRelu.apply(h, sc, i != last) if _fuse else F.relu(h + sc)
+            sc = ConvBN.apply(a, b["sc"], stride, 0, True) if "sc" in b else a
+            a = F.relu(h + sc)
     a = F.adaptive_avg_pool2d(a, 1).flatten(1)
     loss = F.cross_entropy(Linear.apply(a, ws["fc"]), labels)
     loss.backward()
@@ -305,6 +342,7 @@ def step(x, labels, ws):
 
 
 def bottleneck_step(x, gy, ws):
+    _layer[0] = 0
     if _fuse:
         h = ConvChain.apply(x, True, ((1, 0), (1, 1), (1, 0)), *ws)
     else:

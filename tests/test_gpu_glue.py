@@ -57,3 +57,7 @@ def test_relu_backward_with_and_without_the_other_branch(n):
     gr, out, other = synth.normal(g, (n,), std=1.0), np.maximum(synth.normal(g, (n,), std=1.0), 0), synth.normal(g, (n,), std=1.0)
     same_ints(host(q8t.relu_bwd_add(dev(gr), dev(out))), oracle.relu_bwd_add(gr, out))
     same_ints(host(q8t.relu_bwd_add(dev(gr), dev(out), dev(other))), oracle.relu_bwd_add(gr, out, other))
+    # the sum of two consumers' gradients, masked in the same pass
+    same_ints(host(q8t.relu_bwd_sum(dev(gr), dev(other), dev(out))), oracle.relu_bwd_sum(gr, other, out))
+    same_ints(host(q8t.relu_bwd_sum(dev(gr), dev(other))), oracle.relu_bwd_sum(gr, other))
+    same_ints(host(q8t.relu_bwd_sum(dev(gr), None, dev(out))), oracle.relu_bwd_sum(gr, None, out))

@@ -1,0 +1,36 @@
+"""The chained training step (paper_1805_11046_amd.train_step): the fused node structure (stem pooling inside the
+Range BN pass, whole residual blocks as one node with the masked gradient sum, codes handed from layer to layer)
+must give what the plain structure gives (every Range BN, ReLU, pooling, sum and quantization its own pass, torch's
+autograd for the glue): same loss, same weight gradients.  Both run the same library products; a layer's stochastic
+roundings are seeded by its position in the network, so the two structures draw the same random numbers."""
+import pytest
+
+from gpu_util import require_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def test_fused_and_plain_resnet18_steps_agree():
+    require_gpu()
+    import torch
+    from paper_1805_11046_amd import train_step as ts
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    ws = ts.make_weights(dev, gen)
+    x = torch.randn((4, 3, 224, 224), device=dev, generator=gen)
+    labels = torch.randint(0, 1000, (4,), device=dev, generator=gen)
+    params = [ws["conv1"], ws["fc"]] + [w for b in ws["blocks"] for w in b.values()]
+    results = []
+    for fuse in (True, False):
+        ts._fuse = fuse
+        for p in params:
+            p.grad = None
+        loss = ts.step(x, labels, ws)
+        torch.cuda.synchronize()
+        results.append((float(loss.detach()), [p.grad.clone() for p in params]))
+    ts._fuse = True
+    (lf, gf), (lp, gp) = results
+    assert lf == lp
+    for i, (a, b) in enumerate(zip(gf, gp)):
+        assert torch.equal(a, b), "gradient of parameter %d differs: max |diff| %g" % (i, float((a - b).abs().max()))

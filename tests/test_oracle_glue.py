@@ -52,5 +52,14 @@ def test_add_relu_and_its_backward():
     g, o = _data(9, a.shape), _data(10, a.shape)
     assert np.array_equal(oracle.relu_bwd_add(g, out), np.where(out > 0, g, 0))
     assert np.array_equal(oracle.relu_bwd_add(g, out, o), np.where(out > 0, g, np.float32(0)) + o)
+    # two consumers of a rectified tensor: the sum of their gradients, masked once (torch's own backward of
+    # relu(t) feeding two branches)
+    assert np.array_equal(oracle.relu_bwd_sum(g, o, out), np.where(out > 0, g + o, np.float32(0)))
+    assert np.array_equal(oracle.relu_bwd_sum(g, o), g + o)
+    assert np.array_equal(oracle.relu_bwd_sum(g, None, out), oracle.relu_bwd_add(g, out))
+    t = torch.from_numpy(a + b).requires_grad_(True)
+    r = torch.relu(t)
+    (r * torch.from_numpy(g) + r * torch.from_numpy(o)).sum().backward()
+    assert np.allclose(oracle.relu_bwd_sum(g, o, out), t.grad.numpy(), rtol=1e-6, atol=1e-7)
     z, mz = oracle.add_relu(-np.abs(a), -np.abs(b))
     assert not z.any() and mz == 0
