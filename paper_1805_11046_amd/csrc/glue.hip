@@ -134,15 +134,32 @@ __device__ __forceinline__ float pool_bwd_at(const float *__restrict__ gp, const
     return acc;
 }
 
-// a workgroup per plane; with W a multiple of 4 a thread writes 4 neighbouring positions at once
-template <bool VEC>
+// a workgroup per plane; with W a multiple of 4 a thread writes 4 neighbouring positions at once.  LDS: the pooled
+// plane and its indices are first copied into LDS with wide coalesced loads and gathered from there (a position
+// looks at up to six pooled elements: as global loads those dozen narrow accesses per 16 bytes written bound
+// the kernel at a third of the streaming rate)
+template <bool VEC, bool LDS>
 __global__ __launch_bounds__(kThreads) void maxpool_relu_bwd(const float *__restrict__ gpool, const uint8_t *__restrict__ idx, int H,
                                                              int W, int P, int Q, float *__restrict__ dy)
 {
+    extern __shared__ __attribute__((aligned(16))) uint8_t pool_lds[];
     const int64_t pl = blockIdx.x;
     const float *gp = gpool + pl * (int64_t)P * Q;
     const uint8_t *ip = idx + pl * (int64_t)P * Q;
     float *dp = dy + pl * (int64_t)H * W;
+    if (LDS) {
+        // P * Q is a multiple of 16 here and both planes start 16-byte aligned
+        const int PQ = P * Q;
+        float *sg = reinterpret_cast<float *>(pool_lds);
+        uint8_t *si = pool_lds + (size_t)PQ * sizeof(float);
+        for (int i = threadIdx.x; i < PQ / 4; i += kThreads)
+            reinterpret_cast<float4 *>(sg)[i] = q8t_ld_last(reinterpret_cast<const float4 *>(gp) + i);
+        for (int i = threadIdx.x; i < PQ / 16; i += kThreads)
+            reinterpret_cast<uint4 *>(si)[i] = reinterpret_cast<const uint4 *>(ip)[i];
+        __syncthreads();
+        gp = sg;
+        ip = si;
+    }
     if (VEC) {
         // positions w..w+3 (w a multiple of 4) of row h meet the pooled columns qa = w/2, qa+1, qa+2 at fixed places
         // inside their windows: w -> (qa, col 1); w+1 -> (qa, 2), (qa+1, 0); w+2 -> (qa+1, 1); w+3 -> (qa+1, 2), (qa+2, 0);
@@ -351,12 +368,18 @@ int q8t_maxpool_relu_bwd(const float *gpool, const uint8_t *idx, int N, int C, i
     const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1;
     const int64_t planes = (int64_t)N * C;
     if (planes > 0x7FFFFFFF || (int64_t)H * W >= (1 << 22)) return Q8T_ERR_SHAPE;
-    if (W % 4 == 0 && q8t_aligned(dy, 16))
-        hipLaunchKernelGGL(maxpool_relu_bwd<true>, dim3((unsigned)planes), dim3(kThreads), 0, (hipStream_t)stream, gpool, idx, H, W,
-                           P, Q, dy);
-    else
-        hipLaunchKernelGGL(maxpool_relu_bwd<false>, dim3((unsigned)planes), dim3(kThreads), 0, (hipStream_t)stream, gpool, idx, H, W,
-                           P, Q, dy);
+    const int PQ = P * Q;
+    const size_t lds = (size_t)PQ * 5;
+    if (W % 4 == 0 && q8t_aligned(dy, 16)) {
+        if (PQ % 16 == 0 && lds <= 48 * 1024 && q8t_aligned(gpool, 16) && q8t_aligned(idx, 16))
+            hipLaunchKernelGGL((maxpool_relu_bwd<true, true>), dim3((unsigned)planes), dim3(kThreads), lds, (hipStream_t)stream,
+                               gpool, idx, H, W, P, Q, dy);
+        else
+            hipLaunchKernelGGL((maxpool_relu_bwd<true, false>), dim3((unsigned)planes), dim3(kThreads), 0, (hipStream_t)stream,
+                               gpool, idx, H, W, P, Q, dy);
+    } else
+        hipLaunchKernelGGL((maxpool_relu_bwd<false, false>), dim3((unsigned)planes), dim3(kThreads), 0, (hipStream_t)stream, gpool,
+                           idx, H, W, P, Q, dy);
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
 }

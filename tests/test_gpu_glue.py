@@ -10,7 +10,7 @@ from gpu_util import close, dev, host, require_gpu, same_ints, same_qparams
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("shape", [(2, 3, 8, 8), (1, 2, 7, 9), (3, 64, 112, 112), (2, 5, 33, 20), (1, 1, 1, 2)])
+@pytest.mark.parametrize("shape", [(2, 3, 8, 8), (1, 2, 7, 9), (3, 64, 112, 112), (2, 5, 33, 20), (1, 1, 1, 2), (2, 4, 16, 24)])
 def test_stem_pooling_forward_and_backward(shape):
     q8t = require_gpu()
     g = synth.rng(sum(shape))
