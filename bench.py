@@ -391,6 +391,7 @@ def main():
     t0 = time.perf_counter()
     for _ in range(args.steps):
         loss = one()
+    issue = time.perf_counter() - t0   # the host has queued every launch; the GPU is still working
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     dom_records = ts.drain()
@@ -415,7 +416,8 @@ def main():
                    "global_batch": args.batch,
                    "value_is": "useful int8 ops of all products of the step / whole step time (glue in torch included)",
                    "images_per_s": round(args.batch / ms_per_step * 1e3, 1),
-                   "library_calls_ms_per_step": round(library_ms, 3)},
+                   "library_calls_ms_per_step": round(library_ms, 3),
+                   "host_issue_ms_per_step": round(issue / args.steps * 1e3, 3)},
         "roofline": roofline,
         "calls": calls,
         "stream_ceiling": stream_ceiling(q8t, torch),
