@@ -879,6 +879,80 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restric
     }
 }
 
+// pass 2 for planes whose size is not a multiple of 4 (7x7): groups of four consecutive elements of the flat tensor
+// (one generator call per group and copy, packed stores), the channel looked up per element since a group can
+// straddle planes.  total is a multiple of 4.
+__global__ __launch_bounds__(kThreads) void bn_bwdq_apply_flat4(const float *__restrict__ x, const float *__restrict__ dy,
+                                                                int64_t total4, int C, int HW, const float *__restrict__ stats,
+                                                                const float *__restrict__ gamma, const float *__restrict__ beta,
+                                                                int relu, const float2 *__restrict__ consts, float cn, float eps,
+                                                                uint32_t s8_lo, uint32_t s8_hi, uint32_t s16_lo, uint32_t s16_hi,
+                                                                const float2 *__restrict__ mm, int nmm,
+                                                                q8t_qparams *__restrict__ qp8_out,
+                                                                q8t_qparams *__restrict__ qp16_out, float *__restrict__ dx,
+                                                                int8_t *__restrict__ q8, int16_t *__restrict__ q16,
+                                                                const int *__restrict__ crowded)
+{
+    __shared__ float smf[kThreads / 64];
+    float vmin = INFINITY, vmax = -INFINITY;
+    for (int i = threadIdx.x; i < nmm; i += kThreads) {
+        const float2 p = mm[i];
+        vmin = fminf(vmin, p.x);
+        vmax = fmaxf(vmax, p.y);
+    }
+    vmin = block_min_f(vmin, smf);
+    vmax = block_max_f(vmax, smf);
+    const q8t_qparams qp8 = make_qparams(vmin, vmax, 8), qp16 = make_qparams(vmin, vmax, 16);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *qp8_out = qp8;
+        *qp16_out = qp16;
+    }
+    const Affine a8 = affine_of(qp8), a16 = affine_of(qp16);
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i4 = (int64_t)blockIdx.x * kThreads + threadIdx.x; i4 < total4; i4 += stride) {
+        const float4 d4 = q8t_ld_last(reinterpret_cast<const float4 *>(dy) + i4);
+        const float dv[4] = {d4.x, d4.y, d4.z, d4.w};
+        const int64_t pl0 = (4 * i4) / HW;             // plane of the group's first element
+        const int off0 = (int)(4 * i4 - pl0 * HW);
+        float rv[4];
+        bool need_x = relu != 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = (int)((pl0 + (off0 + j >= HW ? 1 : 0)) % C);   // HW >= 4: a group meets at most two planes
+            need_x = need_x || !crowded || crowded[c];
+        }
+        float xv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (need_x) {
+            const float4 x4 = q8t_ld_last(reinterpret_cast<const float4 *>(x) + i4);
+            xv[0] = x4.x; xv[1] = x4.y; xv[2] = x4.z; xv[3] = x4.w;
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = (int)((pl0 + (off0 + j >= HW ? 1 : 0)) % C);
+            const float mn = stats[C + c], mx = stats[2 * C + c];
+            const float inv = bn_inv(mn, mx, cn, eps);
+            const float g = gamma ? gamma[c] : 1.0f;
+            const float2 k = consts[c];
+            if (need_x) {
+                float d = dv[j];
+                if (relu) {
+                    const float be = beta ? beta[c] : 0.0f;
+                    const float out = bn_map(xv[j], stats[c], inv, g, be);
+                    d = out > 0.0f ? d : 0.0f;
+                }
+                // a channel that is not crowded gets its extremal coordinates from the patch kernel: ordinary rule here
+                rv[j] = (crowded && !crowded[c]) ? bn_dx_kind(d, g, k.x, inv, k.y, 0) : bn_dx(xv[j], d, g, k.x, inv, k.y, mn, mx);
+            } else {
+                rv[j] = bn_dx_kind(dv[j], g, k.x, inv, k.y, 0);
+            }
+        }
+        const float4 r = make_float4(rv[0], rv[1], rv[2], rv[3]);
+        if (dx) reinterpret_cast<float4 *>(dx)[i4] = r;
+        reinterpret_cast<uint32_t *>(q8)[i4] = quant4<int8_t, true>(r, a8, (uint32_t)i4, s8_lo, s8_hi);
+        reinterpret_cast<uint2 *>(q16)[i4] = quant4<int16_t, true>(r, a16, (uint32_t)i4, s16_lo, s16_hi);
+    }
+}
+
 // after pass 2: the listed coordinates (at the channel's max or min) get their real dx and codes
 __global__ __launch_bounds__(64) void bn_bwdq_fixup(const float *__restrict__ x, const float *__restrict__ dy, int C, int HW,
                                                     int split, const float *__restrict__ stats,
@@ -1149,7 +1223,10 @@ static int range_bn_bwd_bifurcate_impl(const float *x, const float *dy, const fl
     // Measured: -6% only, the pass is as much bound by the ~45 vector operations per element of the two hashed
     // roundings as by memory; with the rectifier the mask bytes cost more than the x they replace (+4%), so that
     // variant keeps reading x (flags == NULL; the kernels still take them).
-    const bool nox = vec && !relu;
+    const int64_t total = (int64_t)N * C * HW;
+    const bool flat4 = !vec && HW >= 4 && total % 4 == 0 && q8t_aligned(x, 16) && q8t_aligned(dy, 16) &&
+                       (!dx || q8t_aligned(dx, 16)) && q8t_aligned(q8_out, 4) && q8t_aligned(q16_out, 8);
+    const bool nox = (vec || flat4) && !relu;
     ExtList *lists = nox ? (ExtList *)((char *)ws + bwdq_head_bytes(C)) : (ExtList *)nullptr;
     int *crowded = nox ? (int *)((char *)lists + align16((size_t)C * kMaxSplit * sizeof(ExtList))) : (int *)nullptr;
     uint8_t *flags = nullptr;
@@ -1179,8 +1256,17 @@ static int range_bn_bwd_bifurcate_impl(const float *x, const float *dy, const fl
             hipLaunchKernelGGL(bn_bwdq_fixup, dim3(C), dim3(64), 0, st, x, dy, C, HW, nsplit, stats, gamma, beta, relu, consts, cn,
                                eps, s8l, s8h, s16l, s16h, qp8_out, qp16_out, lists, crowded, dx, q8_out, q16_out);
         }
+    } else if (flat4) {
+        const int64_t blocks4 = (total / 4 + kThreads - 1) / kThreads;
+        hipLaunchKernelGGL(bn_bwdq_apply_flat4, dim3((unsigned)(blocks4 < 65536 * 16 ? blocks4 : 65536 * 16)), dim3(kThreads), 0, st,
+                           x, dy, total / 4, C, HW, stats, gamma, beta, relu, consts, cn, eps, s8l, s8h, s16l, s16h, mm, nmm,
+                           qp8_out, qp16_out, dx, q8_out, q16_out, crowded);
+        if (nox) {
+            Q8T_LAUNCH_CHECK();
+            hipLaunchKernelGGL(bn_bwdq_fixup, dim3(C), dim3(64), 0, st, x, dy, C, HW, nsplit, stats, gamma, beta, relu, consts, cn,
+                               eps, s8l, s8h, s16l, s16h, qp8_out, qp16_out, lists, crowded, dx, q8_out, q16_out);
+        }
     } else {
-        const int64_t total = planes * HW;
         const int64_t blocks = (total + kThreads - 1) / kThreads;
         hipLaunchKernelGGL(bn_bwdq_apply<false>, dim3((unsigned)(blocks < 65536 * 16 ? blocks : 65536 * 16)), dim3(kThreads), 0,
                            st, x, dy, planes, C, HW, stats, gamma, beta, relu, consts, cn, eps, s8l, s8h, s16l, s16h, mm, nmm,

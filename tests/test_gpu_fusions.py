@@ -119,7 +119,7 @@ def test_range_bn_relu_forward(shape, affine):
     same_qparams(q8t, qp2, oqp)
 
 
-@pytest.mark.parametrize("shape", RELU_SHAPES + [(16, 64, 56, 56)])
+@pytest.mark.parametrize("shape", RELU_SHAPES + [(16, 64, 56, 56), (8, 12, 7, 7)])
 def test_range_bn_relu_backward_with_bifurcated_quantization(shape):
     q8t = require_gpu()
     x, dy = synth.range_bn_input(3 + sum(shape), *shape)

@@ -122,7 +122,8 @@ def test_rejects_degenerate_batch():
     assert e.value.code == -2
 
 
-@pytest.mark.parametrize("shape", [(6, 7, 16, 16), (3, 2, 40, 36), (128, 64, 56, 56), (5, 9, 7, 7), (64, 128, 1, 1)])
+@pytest.mark.parametrize("shape", [(6, 7, 16, 16), (3, 2, 40, 36), (128, 64, 56, 56), (5, 9, 7, 7), (64, 128, 1, 1),
+                                   (8, 12, 7, 7), (4, 8, 5, 5), (32, 64, 7, 7)])   # the last three: flat groups of four
 def test_backward_fused_with_bifurcated_quantization(shape):
     # same results as the two separate calls; the codes are checked against the oracle's quantizer
     # run on the GPU's own dx (bit-exact), dx itself against the oracle within tolerance
@@ -168,16 +169,17 @@ def test_fused_backward_without_the_fp32_result(shape):
     same_ints(host(q16), host(r16))
 
 
-def test_fused_backward_range_with_ties_and_a_constant_channel():
+@pytest.mark.parametrize("hw", [(16, 16), (7, 7)])
+def test_fused_backward_range_with_ties_and_a_constant_channel(hw):
     # the quantizer's range comes from the extremes of dy per kind of coordinate (ordinary, at the
     # channel maximum, at the minimum, at both): several maxima, several minima, a constant channel
     # (every coordinate is both) and a channel whose extreme dx sits on an extremal coordinate
     q8t = require_gpu()
     g = synth.rng(21)
-    N, C, H, W = 4, 5, 16, 16
+    N, C, (H, W) = 4, 5, hw
     x = g.standard_normal((N, C, H, W)).astype(np.float32)
-    x[:, 0].flat[[3, 77, 500]] = 9.0          # three maxima
-    x[:, 1].flat[[5, 6, 900]] = -9.0          # three minima
+    x[:, 0].flat[[3, 77, 150]] = 9.0          # three maxima
+    x[:, 1].flat[[5, 6, 190]] = -9.0          # three minima
     x[:, 2] = 1.25                            # constant: max == min everywhere
     dy = (g.standard_normal((N, C, H, W)) * 1e-2).astype(np.float32)
     dy[:, 3] *= 1e-3                          # tiny gradients: the +-kb terms dominate the channel's range
