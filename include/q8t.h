@@ -92,6 +92,16 @@ int q8t_init(void);
 int q8t_quantize_noalloc(const float *x, int64_t n, int bits, int stochastic, uint64_t seed, void *q_out,
                          q8t_qparams *qp_out, void *stream);
 
+/* Several tensors at once (the weights of a network at the start of a step: dozens of small tensors, each of
+ * which would otherwise cost one or two launches of its own).  x, n, q_out, qp_out: HOST arrays of `count`
+ * entries; x[t], q_out[t], qp_out[t] are device pointers, n[t] the element count of tensor t.  Nearest rounding,
+ * bits <= 8, every tensor with its own range: the result for tensor t is that of
+ * q8t_quantize(x[t], n[t], bits, 0, ...), bit for bit.  Two launches per 32 tensors.
+ * ws: q8t_quantize_multi_workspace_size(count, n) bytes (n: the same host array). */
+size_t q8t_quantize_multi_workspace_size(int count, const int64_t *n);
+int q8t_quantize_multi(int count, const float *const *x, const int64_t *n, int bits, int8_t *const *q_out,
+                       q8t_qparams *const *qp_out, void *ws, void *stream);
+
 /* Same, with the range supplied instead of searched: vmin_vmax points to 2 device floats
  * (Section 4: the range of an activation is already known to the preceding Range BN).  Values
  * outside the range saturate.  Needs no workspace. */

@@ -48,6 +48,8 @@ _vp, _i, _i64, _u64, _f, _sz = C.c_void_p, C.c_int, C.c_int64, C.c_uint64, C.c_f
 _SIGS = {
     "q8t_quantize_workspace_size": (_sz, [_i64]),
     "q8t_quantize": (_i, [_vp, _i64, _i, _i, _u64, _vp, _vp, _vp, _vp]),
+    "q8t_quantize_multi_workspace_size": (_sz, [_i, _vp]),
+    "q8t_quantize_multi": (_i, [_i, _vp, _vp, _i, _vp, _vp, _vp, _vp]),
     "q8t_init": (_i, []),
     "q8t_quantize_noalloc": (_i, [_vp, _i64, _i, _i, _u64, _vp, _vp, _vp]),
     "q8t_quantize_with_range": (_i, [_vp, _i64, _i, _i, _u64, _vp, _vp, _vp, _vp]),
@@ -182,6 +184,24 @@ def quantize(x, bits=8, stochastic=False, seed=0, q_out=None, qp_out=None, ws=No
     _check(_lib.q8t_quantize(_ptr(x), n, bits, int(bool(stochastic)), int(seed) & (2 ** 64 - 1), _ptr(q),
                              _ptr(qp), _ptr(ws), _stream()), "q8t_quantize")
     return q, qp
+
+
+def quantize_multi(tensors, bits=8):
+    """Nearest-rounding quantization of several tensors (each with its own range) in two launches.
+    Returns [(codes, qparams), ...] in the order of `tensors`."""
+    count = len(tensors)
+    for t in tensors:
+        _dev(t)
+    dev = tensors[0].device
+    qs = [torch.empty(t.shape, dtype=torch.int8, device=dev) for t in tensors]
+    qps = torch.empty((count, 6), dtype=torch.int32, device=dev)     # one q8t_qparams (24 bytes) per row
+    xs = (C.c_void_p * count)(*[t.data_ptr() for t in tensors])
+    ns = (C.c_int64 * count)(*[t.numel() for t in tensors])
+    qo = (C.c_void_p * count)(*[q.data_ptr() for q in qs])
+    po = (C.c_void_p * count)(*[qps[i].data_ptr() for i in range(count)])
+    ws = workspace(_lib.q8t_quantize_multi_workspace_size(count, ns), dev)
+    _check(_lib.q8t_quantize_multi(count, xs, ns, bits, qo, po, _ptr(ws), _stream()), "q8t_quantize_multi")
+    return [(qs[i], qps[i]) for i in range(count)]
 
 
 def init():

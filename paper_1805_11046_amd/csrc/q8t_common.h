@@ -14,7 +14,7 @@
         if (hipGetLastError() != hipSuccess) return Q8T_ERR_HIP; \
     } while (0)
 
-static inline bool q8t_aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+static inline __host__ __device__ bool q8t_aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
 // A kernel that wants more than 64 KB of dynamic LDS has to be given a higher limit first.  One
 // flag per kernel (a function-local static at the launch site) remembers, per device, that this

@@ -371,6 +371,75 @@ int scratch_of_current_device(float2 **out)
 int quantize_impl(const float *x, int64_t n, int bits, int stochastic, uint64_t seed, void *q_out,
                   q8t_qparams *qp_out, float2 *partials, hipStream_t st);
 
+// ---- several tensors in two launches (the weights of a network at the start of a step) ----------
+// Every tensor keeps its own range: the result for tensor t is that of q8t_quantize(x[t], n[t], bits, 0, ...).
+// A workgroup handles kMultiBlock consecutive elements of one tensor; the table that maps workgroups to
+// tensors travels as a kernel argument.
+constexpr int kMultiMax = 32;
+constexpr int kMultiBlock = 16384;
+struct MultiArgs {
+    const float *x[kMultiMax];
+    int8_t *q[kMultiMax];
+    q8t_qparams *qp[kMultiMax];
+    int64_t n[kMultiMax];
+    int first[kMultiMax + 1];   // first workgroup of tensor t; first[count] = number of workgroups
+    int count, bits;
+};
+
+__device__ __forceinline__ int multi_tensor_of(const MultiArgs &a, int b)
+{
+    int t = 0;
+    while (t + 1 < a.count && a.first[t + 1] <= b) ++t;
+    return t;
+}
+
+__global__ __launch_bounds__(kThreads) void multi_minmax(const MultiArgs a, float2 *__restrict__ partials)
+{
+    __shared__ float smem[kThreads / 64];
+    const int b = blockIdx.x, t = multi_tensor_of(a, b);
+    const float *x = a.x[t];
+    const int64_t lo = (int64_t)(b - a.first[t]) * kMultiBlock, hi = min(a.n[t], lo + kMultiBlock);
+    float mn = INFINITY, mx = -INFINITY;
+    if (q8t_aligned(x, 16)) {
+        const int64_t hi4 = lo + ((hi - lo) & ~(int64_t)3);   // lo is a multiple of 4
+        for (int64_t i = lo + 4 * threadIdx.x; i < hi4; i += 4 * kThreads) mm4(mn, mx, *reinterpret_cast<const float4 *>(x + i));
+        for (int64_t i = hi4 + threadIdx.x; i < hi; i += kThreads) {
+            mn = fminf(mn, x[i]);
+            mx = fmaxf(mx, x[i]);
+        }
+    } else {
+        for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads) {
+            mn = fminf(mn, x[i]);
+            mx = fmaxf(mx, x[i]);
+        }
+    }
+    mn = block_reduce_min(mn, smem);
+    mx = block_reduce_max(mx, smem);
+    if (threadIdx.x == 0) partials[b] = make_float2(mn, mx);
+}
+
+__global__ __launch_bounds__(kThreads) void multi_apply(const MultiArgs a, const float2 *__restrict__ partials)
+{
+    __shared__ float smem[kThreads / 64];
+    const int b = blockIdx.x, t = multi_tensor_of(a, b);
+    float vmin, vmax;
+    fold_partials(partials + a.first[t], a.first[t + 1] - a.first[t], smem, vmin, vmax);   // min / max: any order, same bits
+    const q8t_qparams qp = make_qparams(vmin, vmax, a.bits);
+    if (b == a.first[t] && threadIdx.x == 0) *a.qp[t] = qp;
+    const Affine af = affine_of(qp);
+    const float *x = a.x[t];
+    int8_t *q = a.q[t];
+    const int64_t lo = (int64_t)(b - a.first[t]) * kMultiBlock, hi = min(a.n[t], lo + kMultiBlock);
+    if (q8t_aligned(x, 16) && q8t_aligned(q, 4)) {
+        const int64_t hi4 = lo + ((hi - lo) & ~(int64_t)3);
+        for (int64_t i = lo + 4 * threadIdx.x; i < hi4; i += 4 * kThreads)
+            *reinterpret_cast<uint32_t *>(q + i) = quant4<int8_t, false>(*reinterpret_cast<const float4 *>(x + i), af, 0u, 0u, 0u);
+        for (int64_t i = hi4 + threadIdx.x; i < hi; i += kThreads) q[i] = (int8_t)(level_of<false>(x[i], af, 0u) - af.half);
+    } else {
+        for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads) q[i] = (int8_t)(level_of<false>(x[i], af, 0u) - af.half);
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -391,6 +460,48 @@ int q8t_quantize_noalloc(const float *x, int64_t n, int bits, int stochastic, ui
     const int rc = scratch_of_current_device(&partials);
     if (rc) return rc;
     return quantize_impl(x, n, bits, stochastic, seed, q_out, qp_out, partials, (hipStream_t)stream);
+}
+
+size_t q8t_quantize_multi_workspace_size(int count, const int64_t *n)
+{
+    if (count <= 0 || !n) return 0;
+    size_t blocks = 0;
+    for (int t = 0; t < count; ++t) blocks += (size_t)((n[t] > 0 ? n[t] : 0) + kMultiBlock - 1) / kMultiBlock + 1;
+    return blocks * sizeof(float2);
+}
+
+int q8t_quantize_multi(int count, const float *const *x, const int64_t *n, int bits, int8_t *const *q_out,
+                       q8t_qparams *const *qp_out, void *ws, void *stream)
+{
+    if (count <= 0 || !x || !n || !q_out || !qp_out) return count <= 0 ? Q8T_ERR_SHAPE : Q8T_ERR_NULL;
+    if (bits < 2 || bits > 8) return Q8T_ERR_BITS;
+    for (int t = 0; t < count; ++t) {
+        if (n[t] <= 0 || n[t] > ((int64_t)1 << 34)) return Q8T_ERR_SHAPE;
+        if (!x[t] || !q_out[t] || !qp_out[t]) return Q8T_ERR_NULL;
+    }
+    if (!ws || !q8t_aligned(ws, 8)) return Q8T_ERR_WORKSPACE;
+    float2 *partials = (float2 *)ws;
+    for (int t0 = 0; t0 < count; t0 += kMultiMax) {
+        MultiArgs a;
+        a.count = count - t0 < kMultiMax ? count - t0 : kMultiMax;
+        a.bits = bits;
+        int blocks = 0;
+        for (int t = 0; t < a.count; ++t) {
+            a.x[t] = x[t0 + t];
+            a.q[t] = q_out[t0 + t];
+            a.qp[t] = qp_out[t0 + t];
+            a.n[t] = n[t0 + t];
+            a.first[t] = blocks;
+            blocks += (int)((n[t0 + t] + kMultiBlock - 1) / kMultiBlock);
+        }
+        a.first[a.count] = blocks;
+        hipLaunchKernelGGL(multi_minmax, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a, partials);
+        Q8T_LAUNCH_CHECK();
+        hipLaunchKernelGGL(multi_apply, dim3(blocks), dim3(kThreads), 0, (hipStream_t)stream, a, (const float2 *)partials);
+        Q8T_LAUNCH_CHECK();
+        partials += blocks;
+    }
+    return Q8T_OK;
 }
 
 size_t q8t_quantize_workspace_size(int64_t n)

@@ -316,9 +316,22 @@ def make_weights(dev, gen):
     return ws
 
 
+def _quantize_weights(tensors):
+    """all weight tensors of the network in one call (two launches instead of one or two per tensor); the layers
+    find the codes in the cache when they ask for them"""
+    tensors = [t if t.is_contiguous() else t.contiguous() for t in tensors]
+    n = sum(t.numel() for t in tensors)
+    res = _call("quantize (weights)", 0, 9 * n, q8t.quantize_multi, [t.detach() for t in tensors], 8)
+    for t, (q, qp) in zip(tensors, res):
+        _angle("weights, 8 bit", t, q, qp)
+        _qcache[t.data_ptr()] = (q, qp)
+
+
 def step(x, labels, ws):
     _qcache.clear()
     _layer[0] = 0
+    if _fuse:
+        _quantize_weights([ws["conv1"], ws["fc"]] + [w for b in ws["blocks"] for w in b.values()])
     if _fuse:
         a = StemConvBNPool.apply(x, ws["conv1"], 2, 3)
     else:

@@ -103,3 +103,30 @@ def test_error_codes_on_device_arguments():
     assert e.value.code == -3
     with pytest.raises(ValueError):
         q8t.quantize(torch.ones(8), 8)
+
+
+def test_several_tensors_in_one_call_each_with_its_own_range():
+    # weights of a network: sizes from a few elements to several workgroups, a count above one launch's table,
+    # a tensor whose storage is not 16-byte aligned; every result equals the single-tensor call and the oracle
+    q8t = require_gpu()
+    import torch
+    g = synth.rng(77)
+    sizes = [1, 3, 7, 16384, 16385, 36864, 70001, 147456, 5, 64 * 3 * 49] + [257 + 13 * i for i in range(30)]
+    host_t = [(g.standard_normal(n) * g.uniform(0.01, 3.0) + g.uniform(-1, 1)).astype(np.float32) for n in sizes]
+    dev_t = [dev(t) for t in host_t]
+    odd = dev(np.concatenate([np.zeros(1, np.float32), host_t[6]]))[1:]     # same values, storage shifted by 4 bytes
+    assert odd.data_ptr() % 16 != 0
+    dev_t.append(odd)
+    host_t.append(host_t[6])
+    res = q8t.quantize_multi(dev_t, 8)
+    for t, (q, qp), d in zip(host_t, res, dev_t):
+        oq, _, oqp = oracle.quantize(t, 8)
+        same_qparams(q8t, qp, oqp)
+        same_ints(host(q), oq)
+        q1, qp1 = q8t.quantize(d.contiguous(), 8)
+        assert torch.equal(q1, q)
+    res5 = q8t.quantize_multi(dev_t[:4], 5)
+    for t, (q, qp) in zip(host_t, res5):
+        oq, _, oqp = oracle.quantize(t, 5)
+        same_qparams(q8t, qp, oqp)
+        same_ints(host(q), oq)
