@@ -90,7 +90,10 @@ def _bn_bwd(fn, name, ny, *args):
     """Range BN backward + the two gradient copies; with --angles the fp32 gradient is kept for the
     cosine against its copies."""
     want = _angles is not None
-    r = _call(name, 0, (23 if want else 19) * ny, fn, *args, want_dx=want)
+    # algorithmic bytes per element: pass 1 reads x and dy (8), pass 2 reads dy (4; and x again under the rectifier,
+    # whose mask it recomputes) and writes the two copies (3), plus dx (4) when it is wanted
+    per = (19 if "relu" in name else 15) + (4 if want else 0)
+    r = _call(name, 0, per * ny, fn, *args, want_dx=want)
     if want:
         _angle("layer gradients, 8 bit", r[0], r[3], r[4])
         _angle("layer gradients, 16 bit", r[0], r[5], r[6])
