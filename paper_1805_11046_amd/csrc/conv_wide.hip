@@ -1,12 +1,12 @@
 // int8 implicit-GEMM convolution for the layers with many channels on small planes (3x3, stride 1,
-// pad 1; reduction channels a multiple of 128, output channels a multiple of 256; e.g. 256 -> 256 on
-// 14x14 and 512 -> 512 on 7x7): forward, and the layer gradient as the same convolution with the
+// pad 1; reduction channels a multiple of 64, output channels a multiple of 128, planes up to 32 wide; e.g.
+// 128 -> 128 on 28x28, 256 -> 256 on 14x14 and 512 -> 512 on 7x7): forward, and the layer gradient as the same convolution with the
 // filter flipped and its channel roles swapped (Section 4, eq. (grad_layer)).
 //
 // GEMM view: rows = flattened (image, y, x) positions, cols = output channels, reduction = (64
-// input channels, tap).  A workgroup of 4 wavefronts owns 128 rows x 256 output channels; every
-// wavefront multiplies all 128 rows against its own 64 output channels (eight 32x32 accumulators,
-// v_mfma_i32_32x32x32_i8).  What this buys over a 64-channel output tile:
+// input channels, tap).  A workgroup of 4 wavefronts owns 128 rows x 256 output channels (128 where the
+// layer has no multiple of 256); every wavefront multiplies all 128 rows against its own 64 (32) output
+// channels (eight or four 32x32 accumulators, v_mfma_i32_32x32x32_i8).  What this buys over a 64-channel output tile:
 //  * the activations of a 64-channel chunk (128 rows + halo) are staged ONCE and serve 9 taps x 256
 //    output channels: they sit in LDS in padded coordinates (a zero-point row after every image row
 //    and one between images), so a tap is a constant row offset, an immediate in the LDS read;
@@ -32,10 +32,10 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
-constexpr int BM = 128, BN = 256, CH = 64;
+constexpr int BM = 128, CH = 64;   // rows per workgroup, channels per chunk; columns per workgroup: 128 or 256
 constexpr int ROWB = 80;
 constexpr int MARG = 8;          // spare LDS rows on either side of an activation buffer (pieces that hang over)
-constexpr int MAXR = 224;        // rows of one activation buffer
+constexpr int MAXR = 256;        // rows of one activation buffer (one thread per row sums it)
 constexpr int MAXSLOT = 5;       // staging pieces per thread and chunk
 constexpr int kSkip = -1000000;   // a piece with nothing to store
 
@@ -52,19 +52,20 @@ struct WideGeom {
     int last_dword;      // index of the last aligned dword of the operand
 };
 
-// Packed filter: block (oc / 256, chunk, tap) of 16 KB = [wavefront = oc % 256 / 64][column tile = oc % 64 / 32]
-// [K half = ch % 64 / 32][lane = (ch % 32 / 16) * 32 + oc % 32][16 bytes = ch % 16]: every MFMA operand of a
-// wavefront is one 16-byte load per lane, 1 KB contiguous per instruction.  forward: W'(oc,ch,r,s) =
+// Packed filter, BN = 256 or 128 columns per workgroup: block (oc / BN, chunk, tap) of BN x 64 bytes =
+// [32-column tile = oc % BN / 32 (a wavefront owns BN / 128 consecutive ones)][K half = ch % 64 / 32]
+// [lane = (ch % 32 / 16) * 32 + oc % 32][16 bytes = ch % 16]: every MFMA operand of a wavefront is one 16-byte
+// load per lane, 1 KB contiguous per instruction.  forward: W'(oc,ch,r,s) =
 // W[oc][ch][r][s]; layer gradient: W'(oc,ch,r,s) = W[ch][oc][2-r][2-s] (oc = input channel of the layer);
 // colsum[oc] = sum of W'(oc,.,.)
 constexpr int kRepackThreads = 256;
-__global__ __launch_bounds__(kRepackThreads) void repack_wide(const int8_t *__restrict__ w, int Kf, int Cf, int dgrad,
+__global__ __launch_bounds__(kRepackThreads) void repack_wide(const int8_t *__restrict__ w, int Kf, int Cf, int dgrad, int BN,
                                                               int8_t *__restrict__ out, int *__restrict__ colsum)
 {
     __shared__ int red[kRepackThreads / 64];
     const int CHN = dgrad ? Kf : Cf;
     const int oc = blockIdx.x, CC = CHN / CH;
-    const int o256 = oc % BN;
+    const int o256 = oc % BN, WN = BN / 4;   // columns of one wavefront: 64 or 32
     int sum = 0;
     // a thread gathers the 16 reduction channels of one (tap, 16-channel group) and writes them as one piece
     for (int e = threadIdx.x; e < 9 * (CHN / 16); e += kRepackThreads) {
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(kRepackThreads) void repack_wide(const int8_t *__re
             pk[i >> 2] |= (uint32_t)(v & 255) << (8 * (i & 3));
         }
         const int64_t blk = ((int64_t)(oc / BN) * CC + ch0 / CH) * 9 + tap;
-        const int frag = ((o256 / 64) * 2 + (o256 % 64) / 32) * 2 + c64 / 32;
+        const int frag = (o256 / 32) * 2 + c64 / 32;   // (wavefront, column tile) = o256 / WN, (o256 % WN) / 32 in one index
         *reinterpret_cast<uint4 *>(out + blk * (BN * CH) + frag * 1024 + (((c64 % 32) / 16) * 32 + oc % 32) * 16) =
             make_uint4(pk[0], pk[1], pk[2], pk[3]);
     }
@@ -108,7 +109,8 @@ __device__ __forceinline__ void transpose4x4(const uint32_t in[4], uint32_t out[
 }
 
 // AL: the plane size is a multiple of 4 (aligned dwords per channel).  NS: staging pieces per thread.
-template <bool AL, int NS, bool STATS>
+// NTW: 32-column tiles per wavefront (2: 256 output channels per workgroup, 1: 128).
+template <bool AL, int NS, bool STATS, int NTW>
 __global__ __launch_bounds__(kThreads, AL ? 2 : 1) void conv_wide_kernel(const int8_t *__restrict__ x,
                                                                         const int8_t *__restrict__ wpk,
                                                                         const int *__restrict__ colsum,
@@ -118,6 +120,7 @@ __global__ __launch_bounds__(kThreads, AL ? 2 : 1) void conv_wide_kernel(const i
                                                                         int32_t *__restrict__ acc_out,
                                                                         Q8tConvStat *__restrict__ bnpart)
 {
+    constexpr int BN = 128 * NTW, WN = 32 * NTW;   // columns of the workgroup, of a wavefront
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     const int A_BYTES = (g.maxr + 2 * MARG) * ROWB;   // one activation buffer with its spare rows
     uint8_t *As = smem + MARG * ROWB;                  // buffer b at As + b * A_BYTES
@@ -241,7 +244,7 @@ __global__ __launch_bounds__(kThreads, AL ? 2 : 1) void conv_wide_kernel(const i
     // ---- weights: a wavefront's 64 output channels are its own, so their fragments go from memory straight to
     // registers; block (chunk, tap) holds, per wavefront, four 1 KB fragments (column tile, K half) in lane order ----
     const int nsteps = CC * 9;
-    const int8_t *wsrc = wpk + (size_t)blockIdx.y * CC * 9 * BN * CH + wave * 4096 + lane * 16;
+    const int8_t *wsrc = wpk + (size_t)blockIdx.y * CC * 9 * BN * CH + wave * (2048 * NTW) + lane * 16;
     struct BFrag {
         v4i n0k0, n0k1, n1k0, n1k1;   // named members: the sets stay in registers
     };
@@ -251,8 +254,13 @@ __global__ __launch_bounds__(kThreads, AL ? 2 : 1) void conv_wide_kernel(const i
         BFrag f;
         f.n0k0 = *reinterpret_cast<const v4i *>(src);
         f.n0k1 = *reinterpret_cast<const v4i *>(src + 1024);
-        f.n1k0 = *reinterpret_cast<const v4i *>(src + 2048);
-        f.n1k1 = *reinterpret_cast<const v4i *>(src + 3072);
+        if (NTW == 2) {
+            f.n1k0 = *reinterpret_cast<const v4i *>(src + 2048);
+            f.n1k1 = *reinterpret_cast<const v4i *>(src + 3072);
+        } else {
+            f.n1k0 = f.n0k0;
+            f.n1k1 = f.n0k1;
+        }
         return f;
     };
 
@@ -265,11 +273,11 @@ __global__ __launch_bounds__(kThreads, AL ? 2 : 1) void conv_wide_kernel(const i
         arow[mt] = (apad(gr) - a0 - (W1 + 1)) * ROWB + hk * 16;   // row of the tap (0, 0); tap (dr, ds) adds dr * W1 + ds
     }
 
-    v16i acc[4][2];
+    v16i acc[4][NTW];
 #pragma unroll
     for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
+        for (int nt = 0; nt < NTW; ++nt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mt][nt][r] = 0;
     int srow = 0;
@@ -291,9 +299,9 @@ __global__ __launch_bounds__(kThreads, AL ? 2 : 1) void conv_wide_kernel(const i
     };
     auto mma = [&](int mt, const AFrag a, const BFrag b) {
         acc[mt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a.k0, b.n0k0, acc[mt][0], 0, 0, 0);
-        acc[mt][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a.k0, b.n1k0, acc[mt][1], 0, 0, 0);
+        if (NTW == 2) acc[mt][NTW - 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a.k0, b.n1k0, acc[mt][NTW - 1], 0, 0, 0);
         acc[mt][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a.k1, b.n0k1, acc[mt][0], 0, 0, 0);
-        acc[mt][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a.k1, b.n1k1, acc[mt][1], 0, 0, 0);
+        if (NTW == 2) acc[mt][NTW - 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a.k1, b.n1k1, acc[mt][NTW - 1], 0, 0, 0);
     };
 
     load_a(0);
@@ -310,26 +318,27 @@ __global__ __launch_bounds__(kThreads, AL ? 2 : 1) void conv_wide_kernel(const i
         const int s = cc * 9 + T, buf = cc & 1;
         const BFrag &cur = T % 3 == 0 ? bf0 : (T % 3 == 1 ? bf1 : bf2);
         const BFrag nxt = load_b(s + 2);
+        constexpr int NM = 2 * NTW;   // MFMAs per 32-row group
         af1 = read_a(buf, T, 1);
         mma(0, af0, cur);
         __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
         af0 = read_a(buf, T, 2);
         mma(1, af1, cur);
         __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+        if (NTW == 2) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
         af1 = read_a(buf, T, 3);
         mma(2, af0, cur);
         __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
         if (T < 8) af0 = read_a(buf, T + 1, 0);   // the next chunk's activations may not be in LDS yet
         mma(3, af1, cur);
         if (T < 8) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+        if (NTW == 2) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
         __builtin_amdgcn_sched_barrier(0);
         if (T % 3 == 0) bf2 = nxt;        // set (T + 2) % 3 was last used in the previous step
         else if (T % 3 == 1) bf0 = nxt;
@@ -387,8 +396,8 @@ __global__ __launch_bounds__(kThreads, AL ? 2 : 1) void conv_wide_kernel(const i
     // so that a store instruction writes 32 consecutive positions of two channels instead of 64 lone dwords
     int *T = reinterpret_cast<int *>(smem) + wave * (32 * 36);   // [32 channels][36]: the activation buffers are free now
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        const int n = n0 + wave * 64 + nt * 32 + l32;
+    for (int nt = 0; nt < NTW; ++nt) {
+        const int n = n0 + wave * WN + nt * 32 + l32;
         const uint32_t ncs = 0u - (uint32_t)za * (uint32_t)colsum[n];
         long long st_s = 0;
         int st_mn = 2147483647, st_mx = -2147483647 - 1;
@@ -445,7 +454,7 @@ __global__ __launch_bounds__(kThreads, AL ? 2 : 1) void conv_wide_kernel(const i
                 // lane -> position l32 of the tile; 16 instructions cover the 32 channels two at a time
                 const int row = mt * 32 + l32;
                 const bool live = g0 + row < g1;
-                const size_t obase = (size_t)OOFF[row] + (size_t)(n0 + wave * 64 + nt * 32) * PQ;
+                const size_t obase = (size_t)OOFF[row] + (size_t)(n0 + wave * WN + nt * 32) * PQ;
 #pragma unroll
                 for (int k = 0; k < 16; ++k) {
                     const int col = 2 * k + hk;
@@ -483,7 +492,7 @@ bool make_geom(int which, const q8t_conv_desc *d, WideGeom *g)
     g->PQ = d->H * d->W;
     g->C = which == 0 ? d->C : d->K;
     g->K = which == 0 ? d->K : d->C;
-    if (g->C % 128 || g->K % BN) return false;
+    if (g->C % CH || g->K % 128) return false;
     if (d->W < 4 || d->H < 2 || d->W > 32) return false;
     const int64_t M = (int64_t)d->N * g->PQ;
     if (M * g->C >= ((int64_t)1 << 31) || M * g->K >= ((int64_t)1 << 31)) return false;
@@ -514,15 +523,15 @@ size_t lds_bytes(const WideGeom &g)
     return (size_t)2 * (g.maxr + 2 * MARG) * ROWB + (size_t)(MAXR + 2 * BM) * sizeof(int);
 }
 
-template <bool AL, int NS, bool STATS>
+template <bool AL, int NS, bool STATS, int NTW>
 int launch(const WideGeom &g, hipStream_t st, const int8_t *a, const int8_t *wpk, const int *colsum, const q8t_qparams *qa,
            const q8t_qparams *qb, float *out_f, int32_t *out_acc, Q8tConvStat *bnpart)
 {
     static Q8tLdsOptIn optin;
     const size_t lds = lds_bytes(g);
-    if (q8t_allow_lds(optin, (const void *)conv_wide_kernel<AL, NS, STATS>, 96 * 1024) != Q8T_OK) return Q8T_ERR_HIP;
-    const dim3 grid((unsigned)((g.nbx + 7) / 8 * 8), (unsigned)(g.K / BN));
-    hipLaunchKernelGGL((conv_wide_kernel<AL, NS, STATS>), grid, dim3(kThreads), lds, st, a, wpk, colsum, qa, qb, g, out_f,
+    if (q8t_allow_lds(optin, (const void *)conv_wide_kernel<AL, NS, STATS, NTW>, 96 * 1024) != Q8T_OK) return Q8T_ERR_HIP;
+    const dim3 grid((unsigned)((g.nbx + 7) / 8 * 8), (unsigned)(g.K / (128 * NTW)));
+    hipLaunchKernelGGL((conv_wide_kernel<AL, NS, STATS, NTW>), grid, dim3(kThreads), lds, st, a, wpk, colsum, qa, qb, g, out_f,
                        out_acc, bnpart);
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
@@ -534,6 +543,10 @@ bool q8t_wide_conv_supported(int which, const q8t_conv_desc *d, const void *a, c
 {
     WideGeom g;
     if (!make_geom(which, d, &g)) return false;
+    // 128-column tiles (layers without a multiple of 256 output channels) read every activation fragment for half
+    // the MFMAs: measured slower than the 64-column kernel on 128 -> 128 @28 (67 against 58 us), so they only serve
+    // planes that kernel does not take (sizes that are not multiples of 4)
+    if (g.K % 256 != 0 && g.PQ % 4 == 0) return false;
     return q8t_aligned(a, 4) && q8t_aligned(out_f, 16) && q8t_aligned(out_acc, 16);
 }
 
@@ -558,21 +571,24 @@ int q8t_wide_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
     int *colsum = (int *)((char *)ws + ((wbytes + 255) & ~(size_t)255));
     Q8tConvStat *bnpart = bn_stats ? (Q8tConvStat *)((char *)colsum + (((size_t)g.K * sizeof(int) + 255) & ~(size_t)255))
                                    : (Q8tConvStat *)nullptr;
+    const int ntw = g.K % 256 == 0 ? 2 : 1;
     hipLaunchKernelGGL(repack_wide, dim3((unsigned)g.K), dim3(kRepackThreads), 0, st, (const int8_t *)b, d->K, d->C, which,
-                       wpk, colsum);
+                       128 * ntw, wpk, colsum);
     Q8T_LAUNCH_CHECK();
     const int8_t *pa = (const int8_t *)a;
     int32_t *pacc = (int32_t *)out_acc;
     const bool al = g.PQ % 4 == 0;
     int rc;
-#define Q8T_WIDE(ALV, NSV)                                                                                          \
-    (bnpart ? launch<ALV, NSV, true>(g, st, pa, wpk, colsum, qa, qb, out_f, pacc, bnpart)                           \
-            : launch<ALV, NSV, false>(g, st, pa, wpk, colsum, qa, qb, out_f, pacc, bnpart))
+#define Q8T_WIDE2(ALV, NSV, NT)                                                                                     \
+    (bnpart ? launch<ALV, NSV, true, NT>(g, st, pa, wpk, colsum, qa, qb, out_f, pacc, bnpart)                       \
+            : launch<ALV, NSV, false, NT>(g, st, pa, wpk, colsum, qa, qb, out_f, pacc, bnpart))
+#define Q8T_WIDE(ALV, NSV) (ntw == 2 ? Q8T_WIDE2(ALV, NSV, 2) : Q8T_WIDE2(ALV, NSV, 1))
     if (al)
         rc = g.nslot <= 3 ? Q8T_WIDE(true, 3) : Q8T_WIDE(true, 5);
     else
         rc = g.nslot <= 4 ? Q8T_WIDE(false, 4) : Q8T_WIDE(false, 5);
 #undef Q8T_WIDE
+#undef Q8T_WIDE2
     if (rc) return rc;
     if (bnpart) return q8t_conv_stats_finalize(bnpart, g.K, g.nbx, g.nbx, (double)g.M, qa, qb, bn_stats, st);
     return Q8T_OK;

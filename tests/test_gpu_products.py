@@ -130,7 +130,8 @@ CONV_CASES = [
     (2, 64, 9, 12, 128, 3, 3, 2, 1),     # stride 2, even width: class pairs per workgroup, odd height (uneven row parities)
     (3, 64, 14, 18, 128, 1, 1, 2, 0),    # 1x1 at stride 2: three stride classes without taps, zero-filled by the fourth
     (2, 64, 15, 16, 64, 1, 1, 2, 0),     # the same with an odd height: empty classes handled on their own
-    # wide-tile kernel (3x3 stride 1, reduction channels % 128, output channels % 256, small planes)
+    # wide-tile kernel (3x3 stride 1, reduction channels % 64, output channels % 256 -- or % 128 on planes whose size
+    # is not a multiple of 4 --, small planes)
     (3, 256, 14, 14, 256, 3, 3, 1, 1),   # 588 rows: four full tiles and a ragged one
     (5, 512, 7, 7, 512, 3, 3, 1, 1),     # 49-position planes (pieces cut out of unaligned dwords), two column tiles
     (2, 128, 14, 14, 256, 3, 3, 1, 1),   # two chunks; the layer gradient (128 outputs) stays on the 64-column kernel
@@ -138,6 +139,9 @@ CONV_CASES = [
     (2, 256, 16, 16, 256, 3, 3, 1, 1),   # one tile = half an image
     (9, 256, 4, 4, 256, 3, 3, 1, 1),     # a tile spans eight tiny images
     (6, 256, 5, 5, 256, 3, 3, 1, 1),     # ... with unaligned planes
+    (3, 64, 14, 14, 256, 3, 3, 1, 1),    # a single 64-channel chunk
+    (7, 128, 7, 7, 128, 3, 3, 1, 1),     # 128-column tiles (one 32-column tile per wavefront)
+    (4, 64, 7, 7, 384, 3, 3, 1, 1),      # ... three of them, one chunk
     # GEMM form of the weight gradient (byte planes x im2col rows)
     (16, 3, 32, 32, 64, 7, 7, 2, 3),     # first-layer shape: 3 input channels, 147 columns
     (8, 256, 14, 14, 256, 3, 3, 1, 1),   # 14x14 planes, 256 channels
