@@ -429,11 +429,8 @@ def range_bn_bwd(x, dy, stats, gamma=None, eps=0.0, dx_out=None, ws=None):
     return dx, dgamma, dbeta
 
 
-def range_bn_relu_bwd_bifurcate(x, dy, stats, gamma=None, beta=None, eps=0.0, seed8=0, seed16=1, dx_out=None,
-                                q8_out=None, qp8_out=None, q16_out=None, qp16_out=None, ws=None, want_dx=True):
-    """Backward of Range BN + ReLU + bifurcated quantization of dx in one call.
-    Returns (dx or None, dgamma, dbeta, q8, qp8, q16, qp16)."""
-    _dev(x), _dev(dy), _dev(stats)
+def _bn_bwd_bifurcate_buffers(x, dx_out, q8_out, qp8_out, q16_out, qp16_out, ws, want_dx):
+    """output buffers and workspace shared by the two fused backward calls"""
     N, Cc, H, W = x.shape
     dev = x.device
     dx = dx_out if dx_out is not None else (torch.empty_like(x) if want_dx else None)
@@ -444,6 +441,17 @@ def range_bn_relu_bwd_bifurcate(x, dy, stats, gamma=None, beta=None, eps=0.0, se
     qp8 = qp8_out if qp8_out is not None else new_qparams(dev)
     qp16 = qp16_out if qp16_out is not None else new_qparams(dev)
     ws = ws if ws is not None else workspace(_lib.q8t_range_bn_bwd_bifurcate_workspace_size(N, Cc, H, W), dev)
+    return dx, dgamma, dbeta, q8, qp8, q16, qp16, ws
+
+
+def range_bn_relu_bwd_bifurcate(x, dy, stats, gamma=None, beta=None, eps=0.0, seed8=0, seed16=1, dx_out=None,
+                                q8_out=None, qp8_out=None, q16_out=None, qp16_out=None, ws=None, want_dx=True):
+    """Backward of Range BN + ReLU + bifurcated quantization of dx in one call.
+    Returns (dx or None, dgamma, dbeta, q8, qp8, q16, qp16)."""
+    _dev(x), _dev(dy), _dev(stats)
+    N, Cc, H, W = x.shape
+    dx, dgamma, dbeta, q8, qp8, q16, qp16, ws = _bn_bwd_bifurcate_buffers(x, dx_out, q8_out, qp8_out, q16_out, qp16_out,
+                                                                          ws, want_dx)
     _check(_lib.q8t_range_bn_relu_bwd_bifurcate(_ptr(x), _ptr(dy), _ptr(stats), N, Cc, H, W, _ptr(gamma), _ptr(beta),
                                                 float(eps), _ptr(dx), _ptr(dgamma), _ptr(dbeta),
                                                 int(seed8) & (2 ** 64 - 1), int(seed16) & (2 ** 64 - 1), _ptr(q8),
@@ -458,15 +466,8 @@ def range_bn_bwd_bifurcate(x, dy, stats, gamma=None, eps=0.0, seed8=0, seed16=1,
     Returns (dx or None, dgamma, dbeta, q8, qp8, q16, qp16)."""
     _dev(x), _dev(dy), _dev(stats)
     N, Cc, H, W = x.shape
-    dev = x.device
-    dx = dx_out if dx_out is not None else (torch.empty_like(x) if want_dx else None)
-    dgamma = torch.empty(Cc, dtype=torch.float32, device=dev)
-    dbeta = torch.empty(Cc, dtype=torch.float32, device=dev)
-    q8 = q8_out if q8_out is not None else torch.empty(x.shape, dtype=torch.int8, device=dev)
-    q16 = q16_out if q16_out is not None else torch.empty(x.shape, dtype=torch.int16, device=dev)
-    qp8 = qp8_out if qp8_out is not None else new_qparams(dev)
-    qp16 = qp16_out if qp16_out is not None else new_qparams(dev)
-    ws = ws if ws is not None else workspace(_lib.q8t_range_bn_bwd_bifurcate_workspace_size(N, Cc, H, W), dev)
+    dx, dgamma, dbeta, q8, qp8, q16, qp16, ws = _bn_bwd_bifurcate_buffers(x, dx_out, q8_out, qp8_out, q16_out, qp16_out,
+                                                                          ws, want_dx)
     _check(_lib.q8t_range_bn_bwd_bifurcate(_ptr(x), _ptr(dy), _ptr(stats), N, Cc, H, W, _ptr(gamma), float(eps),
                                            _ptr(dx), _ptr(dgamma), _ptr(dbeta), int(seed8) & (2 ** 64 - 1),
                                            int(seed16) & (2 ** 64 - 1), _ptr(q8), _ptr(qp8), _ptr(q16), _ptr(qp16),

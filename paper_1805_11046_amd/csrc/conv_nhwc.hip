@@ -1114,6 +1114,7 @@ __global__ __launch_bounds__(kThreads) void repack_flat(const int8_t *__restrict
 struct SmallPlan {
     int P, Q, Kc;
     int GP, Kf;   // fused form: columns per (channel, filter row) group (0: not available), padded reduction
+    bool fused;   // the fused kernel runs (decided from the shape alone, so the workspace query agrees with the call)
     size_t lds, o_rowsum, o_wt, o_colsum, o_tapoff, total;
 };
 
@@ -1140,8 +1141,17 @@ bool make_small_plan(int which, const q8t_conv_desc *d, SmallPlan *p)
     p->GP = d->S <= 4 ? 4 : (d->S <= 8 ? 8 : 0);
     p->Kf = p->GP ? (int)(((int64_t)d->C * d->R * p->GP + 63) / 64 * 64) : 0;
     if (p->Kf > 256) p->GP = p->Kf = 0;
-    p->o_rowsum = up256s((size_t)M * p->Kc);
-    p->o_wt = p->o_rowsum + up256s((size_t)M * sizeof(int));
+    // the fused kernel (operand tile, filter block, row sums and staged rows in 64 KB of LDS) needs neither the
+    // explicit im2col rows nor their row sums in the workspace: for the first layer of a ResNet at batch 256 those
+    // would be 630 MB that nothing touches
+    {
+        const int Ls = (d->pad + 3) & ~3, pitch = (Ls + d->W + d->pad + 3) & ~3;
+        const size_t fused_lds = (size_t)(p->Kf >> 6) * (FUSED_MAXQ + 64) * 64 + (size_t)FUSED_MAXQ * sizeof(int) +
+                                 (((size_t)d->C * d->R * pitch + 15) & ~(size_t)15) + 16;
+        p->fused = p->GP && fused_lds <= 65536;
+    }
+    p->o_rowsum = p->fused ? 0 : up256s((size_t)M * p->Kc);
+    p->o_wt = p->o_rowsum + (p->fused ? 0 : up256s((size_t)M * sizeof(int)));
     p->o_colsum = p->o_wt + up256s((size_t)d->K * (p->Kc > p->Kf ? p->Kc : p->Kf));
     p->o_tapoff = p->o_colsum + up256s((size_t)d->K * sizeof(int));
     p->total = p->o_tapoff + 256;
@@ -1205,10 +1215,8 @@ namespace {
 // the fused kernel runs (operand tile, filter block, row sums and staged rows fit into 64 KB of LDS)
 bool smallc_is_fused(const q8t_conv_desc *d, const SmallPlan &p)
 {
-    const int Ls = (d->pad + 3) & ~3, pitch = (Ls + d->W + d->pad + 3) & ~3;
-    const size_t fused_lds = (size_t)(p.Kf >> 6) * (FUSED_MAXQ + 64) * 64 + (size_t)FUSED_MAXQ * sizeof(int) +
-                             (((size_t)d->C * d->R * pitch + 15) & ~(size_t)15) + 16;
-    return p.GP && fused_lds <= 65536;
+    (void)d;
+    return p.fused;
 }
 constexpr int kSmallRPB = 4;   // output rows per workgroup of the fused kernel
 }  // namespace
@@ -1238,7 +1246,7 @@ int q8t_smallc_conv(const q8t_conv_desc *d, const void *a, const q8t_qparams *qa
     const int vec4 = d->W % 4 == 0 && q8t_aligned(a, 4);
     const size_t fused_lds = (size_t)(p.Kf >> 6) * (FUSED_MAXQ + 64) * 64 + (size_t)FUSED_MAXQ * sizeof(int) +
                              (((size_t)d->C * d->R * pitch + 15) & ~(size_t)15) + 16;
-    if (p.GP && fused_lds <= 65536) {
+    if (p.fused) {
         hipLaunchKernelGGL(repack_grouped, dim3((unsigned)d->K), dim3(kThreads), 0, st, (const int8_t *)b,
                            d->C * d->R * d->S, d->C * d->R, d->S, p.GP, p.Kf, wt, colsum);
         Q8T_LAUNCH_CHECK();

@@ -51,6 +51,10 @@ def test_host_only_calls():
     assert (d.P, d.Q) == (56, 56)
     for which in (0, 1, 2):
         assert binding._lib.q8t_qconv_workspace_size(ctypes.byref(d), which) >= 0
+    # the first layer of a ResNet at batch 256 runs on the kernel that builds its operand in LDS: its workspace is
+    # the packed filter, not 630 MB of explicit im2col rows
+    d1 = binding.conv_desc(256, 3, 224, 224, 64, 7, 7, 2, 3)
+    assert 0 < binding._lib.q8t_qconv_workspace_size(ctypes.byref(d1), 0) < (1 << 20)
     assert "gfx950" in binding.version()
 
 
