@@ -320,6 +320,12 @@ int q8t_tern_wgrad_multi(const float *g, const int8_t *a_codes, int M, int N, in
  *   the maximum behind (the minimum of the rectified sum, widened to contain 0, is 0), so only the
  *   second pass of the quantization runs.  ws: q8t_add_relu_quantize_workspace_size(n) bytes,
  *   8-byte aligned.
+ * q8t_range_bn_add_relu_quantize: the tail of a residual block in one pass: out = relu(bn(x) + o) with bn the
+ *   elementwise stage of Range BN from given statistics (q8t_range_bn_fwd_apply's arithmetic, eq. (range) of
+ *   Section 3) and o = other, or bn'(other) from other_stats / other_gamma / other_beta when other_stats != NULL
+ *   (a shortcut that is itself convolution + Range BN); 8-bit codes as for q8t_add_relu_quantize.  x, other, out:
+ *   [N,C,H,W]; stats, other_stats: [3][C]; gamma / beta pointers nullable.  The normalized tensors are never
+ *   written: 12 (+5 for the codes) bytes per element instead of 20 (+5).  ws: q8t_add_relu_quantize_workspace_size.
  * q8t_relu_bwd_add: res = (out > 0 ? g : 0) + other (other nullable: nothing added).
  * q8t_relu_bwd_sum: the gradient that reaches a rectified tensor `out` from its two consumers (a residual
  *   block's convolutions and its shortcut): res = out > 0 ? g1 + g2 : 0 in one pass, instead of a sum and a
@@ -331,6 +337,10 @@ int q8t_maxpool_relu_bwd(const float *gpool, const uint8_t *idx, int N, int C, i
 size_t q8t_add_relu_quantize_workspace_size(int64_t n);
 int q8t_add_relu_quantize(const float *a, const float *b, int64_t n, float *out, int8_t *q_out, q8t_qparams *qp_out, void *ws,
                           void *stream);
+int q8t_range_bn_add_relu_quantize(const float *x, const float *stats, const float *gamma, const float *beta,
+                                   const float *other, const float *other_stats, const float *other_gamma,
+                                   const float *other_beta, int N, int C, int H, int W, float eps, float *out, int8_t *q_out,
+                                   q8t_qparams *qp_out, void *ws, void *stream);
 int q8t_relu_bwd_add(const float *g, const float *out, const float *other, int64_t n, float *res, void *stream);
 int q8t_relu_bwd_sum(const float *g1, const float *g2, const float *out, int64_t n, float *res, void *stream);
 

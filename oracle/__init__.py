@@ -421,6 +421,19 @@ def add_relu(a, b):
     return out, np.float32(mx.value)
 
 
+def range_bn_add_relu(x, stats, other, gamma=None, beta=None, other_stats=None, other_gamma=None, other_beta=None,
+                      eps=0.0):
+    """relu(bn(x; stats) + o), o = other or bn(other; other_stats); returns (out, max of out)"""
+    x, other, stats = _f32(x), _f32(other), _f32(stats)
+    N, Cc, H, W = x.shape
+    out = np.empty(x.shape, np.float32)
+    mx = C.c_float(0.0)
+    lib().orc_range_bn_add_relu(_p(x), _p(stats), _p(_opt_f32(gamma)), _p(_opt_f32(beta)), _p(other),
+                                _p(_opt_f32(other_stats)), _p(_opt_f32(other_gamma)), _p(_opt_f32(other_beta)),
+                                N, Cc, H, W, C.c_float(eps), _p(out), C.byref(mx))
+    return out, float(np.float32(mx.value))
+
+
 def relu_bwd_sum(g1, g2=None, out=None):
     g1 = _f32(g1)
     g2, out = _opt_f32(g2), _opt_f32(out)

@@ -941,6 +941,40 @@ void orc_add_relu(const float *a, const float *b, int64_t n, float *out, float *
     if (vmax) *vmax = mx;
 }
 
+/* tail of a residual block in one pass: out = relu(bn(x) + o), bn = the elementwise stage of Range BN from given
+ * statistics (orc_range_bn_fwd_apply's arithmetic), o = other, or bn'(other) from its own statistics when
+ * other_stats is given (a shortcut that is itself convolution + Range BN); *vmax (nullable) = max of out */
+void orc_range_bn_add_relu(const float *x, const float *stats, const float *gamma, const float *beta,
+                           const float *other, const float *other_stats, const float *other_gamma,
+                           const float *other_beta, int N, int C, int H, int W, float eps, float *out, float *vmax)
+{
+    const int64_t HW = (int64_t)H * W;
+    const float cn = (float)orc_range_bn_scale((int64_t)N * HW);
+    float mx = 0.0f;
+    for (int b = 0; b < N; ++b)
+        for (int c = 0; c < C; ++c) {
+            const float g = gamma ? gamma[c] : 1.0f, be = beta ? beta[c] : 0.0f;
+            const float inv = orc_bn_inv(stats[C + c], stats[2 * C + c], cn, eps);
+            float og = 1.0f, obe = 0.0f, oinv = 0.0f, omu = 0.0f;
+            if (other_stats) {
+                og = other_gamma ? other_gamma[c] : 1.0f;
+                obe = other_beta ? other_beta[c] : 0.0f;
+                oinv = orc_bn_inv(other_stats[C + c], other_stats[2 * C + c], cn, eps);
+                omu = other_stats[c];
+            }
+            const int64_t base = ((int64_t)b * C + c) * HW;
+            for (int64_t i = 0; i < HW; ++i) {
+                const float v = orc_bn_apply(x[base + i], stats[c], inv, g, be);
+                const float o = other_stats ? orc_bn_apply(other[base + i], omu, oinv, og, obe) : other[base + i];
+                const float s = v + o;
+                const float r = s > 0.0f ? s : 0.0f;
+                out[base + i] = r;
+                if (r > mx) mx = r;
+            }
+        }
+    if (vmax) *vmax = mx;
+}
+
 /* gradient reaching a rectified tensor `out` from two consumers: (g1 + g2) where out > 0, else 0; out NULL: no
  * rectifier in between (plain sum); g2 NULL: nothing added */
 void orc_relu_bwd_sum(const float *g1, const float *g2, const float *out, int64_t n, float *res)

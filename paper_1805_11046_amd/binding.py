@@ -84,6 +84,7 @@ _SIGS = {
     "q8t_maxpool_relu_bwd": (_i, [_vp, _vp, _i, _i, _i, _i, _vp, _vp]),
     "q8t_add_relu_quantize_workspace_size": (_sz, [_i64]),
     "q8t_add_relu_quantize": (_i, [_vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_range_bn_add_relu_quantize": (_i, [_vp] * 8 + [_i, _i, _i, _i, _f, _vp, _vp, _vp, _vp, _vp]),
     "q8t_relu_bwd_add": (_i, [_vp, _vp, _vp, _i64, _vp, _vp]),
     "q8t_relu_bwd_sum": (_i, [_vp, _vp, _vp, _i64, _vp, _vp]),
     "q8t_ternarize_workspace_size": (_sz, [_i64]),
@@ -563,6 +564,22 @@ def add_relu_quantize(a, b, quantized=True, ws=None):
     ws = ws if ws is not None else workspace(_lib.q8t_add_relu_quantize_workspace_size(n), a.device)
     _check(_lib.q8t_add_relu_quantize(_ptr(a), _ptr(b), n, _ptr(out), _ptr(q), _ptr(qp), _ptr(ws), _stream()),
            "q8t_add_relu_quantize")
+    return out, q, qp
+
+
+def range_bn_add_relu_quantize(x, stats, other, gamma=None, beta=None, other_stats=None, other_gamma=None,
+                               other_beta=None, eps=0.0, quantized=True):
+    """relu(bn(x; stats) + o), o = other or bn(other; other_stats), and the 8-bit codes of the result.
+    Returns (out, codes or None, qparams or None)."""
+    _dev(x), _dev(other), _dev(stats)
+    N, Cc, H, W = x.shape
+    out = torch.empty_like(x)
+    q = torch.empty(x.shape, dtype=torch.int8, device=x.device) if quantized else None
+    qp = new_qparams(x.device) if quantized else None
+    ws = workspace(_lib.q8t_add_relu_quantize_workspace_size(x.numel()), x.device)
+    _check(_lib.q8t_range_bn_add_relu_quantize(_ptr(x), _ptr(stats), _ptr(gamma), _ptr(beta), _ptr(other), _ptr(other_stats),
+                                               _ptr(other_gamma), _ptr(other_beta), N, Cc, H, W, float(eps), _ptr(out),
+                                               _ptr(q), _ptr(qp), _ptr(ws), _stream()), "q8t_range_bn_add_relu_quantize")
     return out, q, qp
 
 

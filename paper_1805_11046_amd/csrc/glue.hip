@@ -248,6 +248,82 @@ __global__ __launch_bounds__(kThreads) void add_relu_fwd(const float *__restrict
     if (threadIdx.x == 0) partials[blockIdx.x] = make_float2(0.0f, mx);
 }
 
+// tail of a residual block: out = relu(bn(x) + o), o = other or bn'(other) (a shortcut that is convolution + Range BN);
+// one (0, max) pair per workgroup for the quantization that follows.  hw4 > 0: planes are whole float4 groups.
+__device__ __forceinline__ float g_bn(float x, float mu, float inv, float g, float b)
+{
+    const float cen = x - mu;
+    const float xh = cen * inv;
+    const float sc = xh * g;
+    return sc + b;
+}
+struct TailBN {
+    const float *stats, *gamma, *beta;   // stats == NULL: the operand is taken as it is
+};
+__device__ __forceinline__ void tail_consts(const TailBN &t, int c, int C, float cn, float eps, float &mu, float &inv, float &g, float &b)
+{
+    mu = t.stats[c];
+    inv = g_bn_inv(t.stats[C + c], t.stats[2 * C + c], cn, eps);
+    g = t.gamma ? t.gamma[c] : 1.0f;
+    b = t.beta ? t.beta[c] : 0.0f;
+}
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void bn_add_relu_fwd(const float *__restrict__ x, TailBN bx, const float *__restrict__ other,
+                                                            TailBN bo, int64_t n, int C, int HW, float cn, float eps,
+                                                            float *__restrict__ out, float2 *__restrict__ partials)
+{
+    __shared__ float smem[kThreads / 64];
+    float mx = 0.0f;
+    if (VEC) {
+        const uint32_t hw4 = (uint32_t)(HW >> 2);
+        const int64_t n4 = n >> 2;
+        const float4 *x4 = reinterpret_cast<const float4 *>(x), *o4 = reinterpret_cast<const float4 *>(other);
+        float4 *r4 = reinterpret_cast<float4 *>(out);
+        const int64_t per = (n4 + gridDim.x - 1) / gridDim.x;
+        const int64_t lo = (int64_t)blockIdx.x * per, hi = min(n4, lo + per);
+#pragma unroll 2
+        for (int64_t i = lo + threadIdx.x; i < hi; i += kThreads) {
+            const int c = (int)(((uint32_t)i / hw4) % (uint32_t)C);   // n4 < 2^32 (checked on the host)
+            float mu, inv, g, b;
+            tail_consts(bx, c, C, cn, eps, mu, inv, g, b);
+            const float4 u = q8t_ld_last(x4 + i);
+            float4 v = q8t_ld_last(o4 + i);
+            if (bo.stats) {
+                float omu, oinv, og, ob;
+                tail_consts(bo, c, C, cn, eps, omu, oinv, og, ob);
+                v.x = g_bn(v.x, omu, oinv, og, ob); v.y = g_bn(v.y, omu, oinv, og, ob);
+                v.z = g_bn(v.z, omu, oinv, og, ob); v.w = g_bn(v.w, omu, oinv, og, ob);
+            }
+            float4 r;
+            r.x = g_bn(u.x, mu, inv, g, b) + v.x; r.y = g_bn(u.y, mu, inv, g, b) + v.y;
+            r.z = g_bn(u.z, mu, inv, g, b) + v.z; r.w = g_bn(u.w, mu, inv, g, b) + v.w;
+            r.x = r.x > 0.0f ? r.x : 0.0f; r.y = r.y > 0.0f ? r.y : 0.0f;
+            r.z = r.z > 0.0f ? r.z : 0.0f; r.w = r.w > 0.0f ? r.w : 0.0f;
+            r4[i] = r;
+            mx = fmaxf(fmaxf(mx, r.x), fmaxf(r.y, fmaxf(r.z, r.w)));
+        }
+    } else {
+        const int64_t stride = (int64_t)gridDim.x * kThreads;
+        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+            const int c = (int)((i / HW) % C);
+            float mu, inv, g, b;
+            tail_consts(bx, c, C, cn, eps, mu, inv, g, b);
+            float v = other[i];
+            if (bo.stats) {
+                float omu, oinv, og, ob;
+                tail_consts(bo, c, C, cn, eps, omu, oinv, og, ob);
+                v = g_bn(v, omu, oinv, og, ob);
+            }
+            const float s = g_bn(x[i], mu, inv, g, b) + v;
+            const float r = s > 0.0f ? s : 0.0f;
+            out[i] = r;
+            mx = fmaxf(mx, r);
+        }
+    }
+    mx = block_max(mx, smem);
+    if (threadIdx.x == 0) partials[blockIdx.x] = make_float2(0.0f, mx);
+}
+
 // res = out > 0 ? g1 + g2 : 0 (out nullable: no mask; g2 nullable: nothing added)
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void relu_bwd_sum(const float *__restrict__ g1, const float *__restrict__ g2,
@@ -403,6 +479,34 @@ int q8t_add_relu_quantize(const float *a, const float *b, int64_t n, float *out,
         hipLaunchKernelGGL(add_relu_fwd<true>, dim3(grid), dim3(kThreads), 0, st, a, b, n, out, (float2 *)ws);
     else
         hipLaunchKernelGGL(add_relu_fwd<false>, dim3(grid), dim3(kThreads), 0, st, a, b, n, out, (float2 *)ws);
+    Q8T_LAUNCH_CHECK();
+    if (!q_out) return Q8T_OK;
+    return q8t_quantize8_from_partials(out, n, ws, grid, q_out, qp_out, st);
+}
+
+int q8t_range_bn_add_relu_quantize(const float *x, const float *stats, const float *gamma, const float *beta,
+                                   const float *other, const float *other_stats, const float *other_gamma,
+                                   const float *other_beta, int N, int C, int H, int W, float eps, float *out, int8_t *q_out,
+                                   q8t_qparams *qp_out, void *ws, void *stream)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || (int64_t)N * H * W < 2) return Q8T_ERR_SHAPE;
+    const int64_t n = (int64_t)N * C * H * W;
+    if (n > kMaxElements || (int64_t)H * W > (1 << 30)) return Q8T_ERR_SHAPE;
+    if (!x || !stats || !other || !out || (q_out && !qp_out)) return Q8T_ERR_NULL;
+    if (!ws || !q8t_aligned(ws, 8)) return Q8T_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const int HW = H * W;
+    const float cn = (float)q8t_range_bn_scale((int64_t)N * HW);
+    const bool vec = HW % 4 == 0 && (n >> 2) < ((int64_t)1 << 32) && q8t_aligned(x, 16) && q8t_aligned(other, 16) &&
+                     q8t_aligned(out, 16);
+    const int grid = grid_for(vec ? (n >> 2) : n, 4, kMaxPartials);
+    const TailBN bx = {stats, gamma, beta}, bo = {other_stats, other_gamma, other_beta};
+    if (vec)
+        hipLaunchKernelGGL(bn_add_relu_fwd<true>, dim3(grid), dim3(kThreads), 0, st, x, bx, other, bo, n, C, HW, cn, eps, out,
+                           (float2 *)ws);
+    else
+        hipLaunchKernelGGL(bn_add_relu_fwd<false>, dim3(grid), dim3(kThreads), 0, st, x, bx, other, bo, n, C, HW, cn, eps, out,
+                           (float2 *)ws);
     Q8T_LAUNCH_CHECK();
     if (!q_out) return Q8T_OK;
     return q8t_quantize8_from_partials(out, n, ws, grid, q_out, qp_out, st);

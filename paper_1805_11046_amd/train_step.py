@@ -109,9 +109,9 @@ def _next_layer():
     return _layer[0]
 
 
-def _convbn_fwd(a, w, stride, pad):
-    """quantize -> conv forward (+ Range BN statistics) -> Range BN; returns the normalized tensor and what
-    the backward pass needs"""
+def _convbn_fwd(a, w, stride, pad, apply=True):
+    """quantize -> conv forward (+ Range BN statistics) -> Range BN; returns the normalized tensor (apply=False: the
+    conv result and its statistics, for a consumer that normalizes on the fly) and what the backward pass needs"""
     a = a.contiguous()
     n, c, h, wd = a.shape
     k, _, r, s = w.shape
@@ -121,8 +121,11 @@ def _convbn_fwd(a, w, stride, pad):
     ops = 2.0 * n * d.P * d.Q * k * c * r * s
     nx, ny = a.numel(), n * k * d.P * d.Q
     y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw, tag=_tag(d))
+    saved = (d, qa, pa, qw, pw, y, stats, ops, nx, ny, _next_layer())
+    if not apply:
+        return (y, stats), saved
     bn, _, _ = _call("range_bn_fwd_apply", 0, 8 * ny, q8t.range_bn_fwd_apply, y, stats, None, None, 1e-5)
-    return bn, (d, qa, pa, qw, pw, y, stats, ops, nx, ny, _next_layer())
+    return bn, saved
 
 
 def _convbn_bwd(saved, dbn, need_dx):
@@ -184,7 +187,7 @@ class StemConvBNPool(torch.autograd.Function):
         return None, dw, None, None
 
 
-def _chain_fwd(a, specs, ws):
+def _chain_fwd(a, specs, ws, apply_last=True):
     """conv -> Range BN -> ReLU -> conv -> Range BN [-> ReLU -> conv -> Range BN]: between two
     convolutions the normalization, the ReLU and the 8-bit quantization of the next operand are one
     pass that writes codes only (no fp32 activation, no separate quantization)"""
@@ -204,8 +207,10 @@ def _chain_fwd(a, specs, ws):
         if i + 1 < len(ws):
             _, qa, pa = _call("range_bn_relu_fwd_apply (int8 out)", 0, 5 * ny, q8t.range_bn_relu_fwd_apply, y, stats,
                               None, None, 1e-5, True, False)
-        else:
+        elif apply_last:
             out, _, _ = _call("range_bn_fwd_apply", 0, 8 * ny, q8t.range_bn_fwd_apply, y, stats, None, None, 1e-5)
+        else:
+            out = (y, stats)     # the consumer normalizes on the fly
         shape = (n, k, d.P, d.Q)
     return out, saved
 
@@ -255,11 +260,18 @@ class ResBlock(torch.autograd.Function):
 
     @staticmethod
     def forward(ctx, a, stride, quantized, mask_input, grad_is_masked, w1, w2, wsc):
-        h, chain = _chain_fwd(a, ((stride, 1), (1, 1)), (w1, w2))
-        sc, scs = (a, None) if wsc is None else _convbn_fwd(a, wsc, stride, 0)
-        n = h.numel()
-        out, q, qp = _call("add_relu_quantize", 0, (17 if quantized else 12) * n, q8t.add_relu_quantize, h.contiguous(),
-                           sc.contiguous(), quantized)
+        # the last Range BN of the chain, the shortcut's Range BN (if it has one), the sum, the rectifier and the
+        # 8-bit codes of the result are one pass over the conv results
+        (y2, st2), chain = _chain_fwd(a, ((stride, 1), (1, 1)), (w1, w2), apply_last=False)
+        n = y2.numel()
+        if wsc is None:
+            scs = None
+            out, q, qp = _call("range_bn_add_relu_quantize", 0, (17 if quantized else 12) * n, q8t.range_bn_add_relu_quantize,
+                               y2, st2, a.contiguous(), eps=1e-5, quantized=quantized)
+        else:
+            (ysc, stsc), scs = _convbn_fwd(a, wsc, stride, 0, apply=False)
+            out, q, qp = _call("range_bn_add_relu_quantize", 0, (17 if quantized else 12) * n, q8t.range_bn_add_relu_quantize,
+                               y2, st2, ysc, other_stats=stsc, eps=1e-5, quantized=quantized)
         if quantized:
             _qcache[out.data_ptr()] = (q, qp)
         ctx.saved = (chain, scs, a if mask_input else None, out, grad_is_masked)

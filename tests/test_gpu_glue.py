@@ -61,3 +61,30 @@ def test_relu_backward_with_and_without_the_other_branch(n):
     same_ints(host(q8t.relu_bwd_sum(dev(gr), dev(other), dev(out))), oracle.relu_bwd_sum(gr, other, out))
     same_ints(host(q8t.relu_bwd_sum(dev(gr), dev(other))), oracle.relu_bwd_sum(gr, other))
     same_ints(host(q8t.relu_bwd_sum(dev(gr), None, dev(out))), oracle.relu_bwd_sum(gr, None, out))
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 8, 8), (3, 5, 7, 7), (4, 64, 14, 14), (2, 6, 5, 6), (16, 64, 56, 56)])
+def test_block_tail_range_bn_add_relu_quantize(shape):
+    # relu(bn(x) + o) and its 8-bit codes in one call, the shortcut plain or normalized by its own statistics
+    q8t = require_gpu()
+    g = synth.rng(sum(shape) + 3)
+    x, o = synth.normal(g, shape, std=1.0), synth.normal(g, shape, std=1.0)
+    C = shape[1]
+    gamma, beta = g.uniform(-1.5, 1.5, C).astype(np.float32), g.uniform(-0.5, 0.5, C).astype(np.float32)
+    og, ob = g.uniform(0.5, 1.5, C).astype(np.float32), g.uniform(-0.5, 0.5, C).astype(np.float32)
+    eps = 1e-5
+    st, so = oracle.range_bn_stats(x), oracle.range_bn_stats(o)
+    out, q, qp = q8t.range_bn_add_relu_quantize(dev(x), dev(st), dev(o), dev(gamma), dev(beta), eps=eps)
+    oout, _ = oracle.range_bn_add_relu(x, st, o, gamma, beta, eps=eps)
+    same_ints(host(out), oout)
+    sq, _, oqp = oracle.quantize(oout, 8)
+    same_qparams(q8t, qp, oqp)
+    same_ints(host(q), sq)
+    out2, q2, qp2 = q8t.range_bn_add_relu_quantize(dev(x), dev(st), dev(o), None, None, dev(so), dev(og), dev(ob), eps)
+    oout2, _ = oracle.range_bn_add_relu(x, st, o, None, None, so, og, ob, eps)
+    same_ints(host(out2), oout2)
+    sq2, _, oqp2 = oracle.quantize(oout2, 8)
+    same_qparams(q8t, qp2, oqp2)
+    same_ints(host(q2), sq2)
+    out3, q3, _ = q8t.range_bn_add_relu_quantize(dev(x), dev(st), dev(o), dev(gamma), dev(beta), eps=eps, quantized=False)
+    assert q3 is None and np.array_equal(host(out3), oout)

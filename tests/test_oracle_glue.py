@@ -63,3 +63,34 @@ def test_add_relu_and_its_backward():
     assert np.allclose(oracle.relu_bwd_sum(g, o, out), t.grad.numpy(), rtol=1e-6, atol=1e-7)
     z, mz = oracle.add_relu(-np.abs(a), -np.abs(b))
     assert not z.any() and mz == 0
+
+
+def test_block_tail_in_one_pass_equals_its_pieces_and_torch():
+    # relu(bn(x) + o): bit-identical to the separately pinned pieces (Range BN elementwise stage from given
+    # statistics, then add + ReLU), and equal to the formula evaluated by torch in fp64 within fp32 rounding
+    x, o = _data(31, (3, 4, 5, 6)), _data(32, (3, 4, 5, 6))
+    g = np.random.default_rng(5)
+    gamma, beta = g.uniform(-1.5, 1.5, 4).astype(np.float32), g.uniform(-0.5, 0.5, 4).astype(np.float32)
+    og, ob = g.uniform(0.5, 1.5, 4).astype(np.float32), g.uniform(-0.5, 0.5, 4).astype(np.float32)
+    eps = 1e-5
+    st, so = oracle.range_bn_stats(x), oracle.range_bn_stats(o)
+    bn, _, _, _ = oracle.range_bn_fwd(x, gamma, beta, eps, stats=st)
+    out, mx = oracle.range_bn_add_relu(x, st, o, gamma, beta, eps=eps)
+    ref, rmx = oracle.add_relu(bn, o)
+    assert np.array_equal(out, ref) and mx == rmx == out.max()
+    bno, _, _, _ = oracle.range_bn_fwd(o, og, ob, eps, stats=so)
+    out2, mx2 = oracle.range_bn_add_relu(x, st, o, gamma, beta, so, og, ob, eps)
+    ref2, _ = oracle.add_relu(bn, bno)
+    assert np.array_equal(out2, ref2) and mx2 == out2.max()
+    n = x.shape[0] * x.shape[2] * x.shape[3]
+    cn = (2.0 * np.log(n)) ** -0.5
+
+    def bn64(t, s, ga, be):
+        t = torch.from_numpy(t).double()
+        mu, mn, mxx = (torch.from_numpy(s[i]).double().view(1, -1, 1, 1) for i in range(3))
+        return (t - mu) / (cn * (mxx - mn) + eps) * torch.from_numpy(ga).double().view(1, -1, 1, 1) + \
+            torch.from_numpy(be).double().view(1, -1, 1, 1)
+    t2 = torch.relu(bn64(x, st, gamma, beta) + bn64(o, so, og, ob)).numpy()
+    assert np.allclose(out2, t2, rtol=1e-5, atol=1e-5)
+    t1 = torch.relu(bn64(x, st, gamma, beta) + torch.from_numpy(o).double()).numpy()
+    assert np.allclose(out, t1, rtol=1e-5, atol=1e-5)
