@@ -232,8 +232,9 @@ int q8t_range_bn_bwd(const float *x, const float *dy, const float *stats, int N,
  * of dx (from the extremes of dy per kind of coordinate), and the second pass quantizes dx where it
  * is computed: 8 + 8 + 3 bytes per element (+4 if dx is wanted) against 20 + 11 for
  * q8t_range_bn_bwd followed by q8t_quantize_bifurcate, with bit-identical results.
- * dx is nullable (the codes are all the rest of the backward pass consumes); q8_out, q16_out and
- * both parameter blocks are required; dgamma / dbeta stay nullable.
+ * dx is nullable (the codes are all the rest of the backward pass consumes); q16_out and qp16_out are
+ * required; q8_out is nullable, with qp8_out (the first layer of a network: its input needs no gradient,
+ * so only the weight gradient's 16-bit operand is wanted); dgamma / dbeta stay nullable.
  * ws: q8t_range_bn_bwd_bifurcate_workspace_size. */
 size_t q8t_range_bn_bwd_bifurcate_workspace_size(int N, int C, int H, int W);
 int q8t_range_bn_bwd_bifurcate(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
@@ -315,6 +316,14 @@ int q8t_tern_wgrad_multi(const float *g, const int8_t *a_codes, int M, int N, in
  * q8t_maxpool_relu_bwd: gradient with respect to the Range BN output: dy [N,C,H,W] receives, at
  *   every position, the sum of gpool over the windows whose idx names it (0 elsewhere).  Feed it to
  *   q8t_range_bn_bwd / q8t_range_bn_bwd_bifurcate (not the ReLU variants: the mask is in idx).
+ * q8t_maxpool_range_bn_bwd_bifurcate: q8t_maxpool_relu_bwd followed by q8t_range_bn_bwd_bifurcate (Section 7's
+ *   backward rule, Sections 1 and 4 for the copies) with bit-identical codes, parameters, dgamma and dbeta, but
+ *   without the unpooled gradient ever being written: both passes gather it from gpool and idx, one pooled plane at a
+ *   time.  x [N,C,H,W]: the Range BN input; gpool, idx [N,C,P,Q]; no dx output; q8_out / qp8_out nullable as above.
+ *   Planes of at least 1024 positions with W a multiple of 4, (P*Q) a multiple of 16 and P*Q <= 12288 are served
+ *   directly and need x, gpool, idx 16-byte aligned (q8_out 4, q16_out 8), else Q8T_ERR_SHAPE; for every other
+ *   shape the unpooled gradient goes through the workspace.  ws:
+ *   q8t_maxpool_range_bn_bwd_bifurcate_workspace_size bytes, 16-byte aligned.
  * q8t_add_relu_quantize: out = relu(a + b) (n floats each) and, if q_out != NULL, its 8-bit codes
  *   and parameters exactly as q8t_quantize(out, n, 8, 0, ...) would give them: the first pass leaves
  *   the maximum behind (the minimum of the rectified sum, widened to contain 0, is 0), so only the
@@ -334,6 +343,11 @@ int q8t_tern_wgrad_multi(const float *g, const int8_t *a_codes, int M, int N, in
 int q8t_range_bn_relu_maxpool_fwd(const float *x, int N, int C, int H, int W, const float *gamma, const float *beta, float eps,
                                   const float *stats, float *out, uint8_t *idx, void *stream);
 int q8t_maxpool_relu_bwd(const float *gpool, const uint8_t *idx, int N, int C, int H, int W, float *dy, void *stream);
+size_t q8t_maxpool_range_bn_bwd_bifurcate_workspace_size(int N, int C, int H, int W);
+int q8t_maxpool_range_bn_bwd_bifurcate(const float *x, const float *gpool, const uint8_t *idx, const float *stats, int N, int C,
+                                       int H, int W, const float *gamma, float eps, float *dgamma, float *dbeta, uint64_t seed8,
+                                       uint64_t seed16, int8_t *q8_out, q8t_qparams *qp8_out, int16_t *q16_out,
+                                       q8t_qparams *qp16_out, void *ws, void *stream);
 size_t q8t_add_relu_quantize_workspace_size(int64_t n);
 int q8t_add_relu_quantize(const float *a, const float *b, int64_t n, float *out, int8_t *q_out, q8t_qparams *qp_out, void *ws,
                           void *stream);

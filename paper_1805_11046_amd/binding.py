@@ -82,6 +82,9 @@ _SIGS = {
     "q8t_probe_stream": (_i, [_i, _vp, _vp, _i64, _vp]),
     "q8t_range_bn_relu_maxpool_fwd": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp, _vp]),
     "q8t_maxpool_relu_bwd": (_i, [_vp, _vp, _i, _i, _i, _i, _vp, _vp]),
+    "q8t_maxpool_range_bn_bwd_bifurcate_workspace_size": (_sz, [_i, _i, _i, _i]),
+    "q8t_maxpool_range_bn_bwd_bifurcate": (_i, [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _f, _vp, _vp, _u64, _u64, _vp, _vp,
+                                                _vp, _vp, _vp, _vp]),
     "q8t_add_relu_quantize_workspace_size": (_sz, [_i64]),
     "q8t_add_relu_quantize": (_i, [_vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp]),
     "q8t_range_bn_add_relu_quantize": (_i, [_vp] * 8 + [_i, _i, _i, _i, _f, _vp, _vp, _vp, _vp, _vp]),
@@ -430,18 +433,21 @@ def range_bn_bwd(x, dy, stats, gamma=None, eps=0.0, dx_out=None, ws=None):
     return dx, dgamma, dbeta
 
 
-def _bn_bwd_bifurcate_buffers(x, dx_out, q8_out, qp8_out, q16_out, qp16_out, ws, want_dx):
-    """output buffers and workspace shared by the two fused backward calls"""
+def _bn_bwd_bifurcate_buffers(x, dx_out, q8_out, qp8_out, q16_out, qp16_out, ws, want_dx, want_q8=True, ws_size=None):
+    """output buffers and workspace shared by the fused backward calls (want_q8=False: no 8-bit copy, q8 = qp8 = None)"""
     N, Cc, H, W = x.shape
     dev = x.device
     dx = dx_out if dx_out is not None else (torch.empty_like(x) if want_dx else None)
     dgamma = torch.empty(Cc, dtype=torch.float32, device=dev)
     dbeta = torch.empty(Cc, dtype=torch.float32, device=dev)
-    q8 = q8_out if q8_out is not None else torch.empty(x.shape, dtype=torch.int8, device=dev)
+    q8 = qp8 = None
+    if want_q8:
+        q8 = q8_out if q8_out is not None else torch.empty(x.shape, dtype=torch.int8, device=dev)
+        qp8 = qp8_out if qp8_out is not None else new_qparams(dev)
     q16 = q16_out if q16_out is not None else torch.empty(x.shape, dtype=torch.int16, device=dev)
-    qp8 = qp8_out if qp8_out is not None else new_qparams(dev)
     qp16 = qp16_out if qp16_out is not None else new_qparams(dev)
-    ws = ws if ws is not None else workspace(_lib.q8t_range_bn_bwd_bifurcate_workspace_size(N, Cc, H, W), dev)
+    size = (ws_size or _lib.q8t_range_bn_bwd_bifurcate_workspace_size)(N, Cc, H, W)
+    ws = ws if ws is not None else workspace(size, dev)
     return dx, dgamma, dbeta, q8, qp8, q16, qp16, ws
 
 
@@ -462,13 +468,13 @@ def range_bn_relu_bwd_bifurcate(x, dy, stats, gamma=None, beta=None, eps=0.0, se
 
 
 def range_bn_bwd_bifurcate(x, dy, stats, gamma=None, eps=0.0, seed8=0, seed16=1, dx_out=None, q8_out=None,
-                           qp8_out=None, q16_out=None, qp16_out=None, ws=None, want_dx=True):
+                           qp8_out=None, q16_out=None, qp16_out=None, ws=None, want_dx=True, want_q8=True):
     """Range BN backward + bifurcated quantization of dx in one call.
-    Returns (dx or None, dgamma, dbeta, q8, qp8, q16, qp16)."""
+    Returns (dx or None, dgamma, dbeta, q8, qp8, q16, qp16); want_q8=False leaves q8 = qp8 = None."""
     _dev(x), _dev(dy), _dev(stats)
     N, Cc, H, W = x.shape
     dx, dgamma, dbeta, q8, qp8, q16, qp16, ws = _bn_bwd_bifurcate_buffers(x, dx_out, q8_out, qp8_out, q16_out, qp16_out,
-                                                                          ws, want_dx)
+                                                                          ws, want_dx, want_q8)
     _check(_lib.q8t_range_bn_bwd_bifurcate(_ptr(x), _ptr(dy), _ptr(stats), N, Cc, H, W, _ptr(gamma), float(eps),
                                            _ptr(dx), _ptr(dgamma), _ptr(dbeta), int(seed8) & (2 ** 64 - 1),
                                            int(seed16) & (2 ** 64 - 1), _ptr(q8), _ptr(qp8), _ptr(q16), _ptr(qp16),
@@ -551,6 +557,21 @@ def maxpool_relu_bwd(gpool, idx, H, W):
     dy = torch.empty((N, Cc, H, W), dtype=torch.float32, device=gpool.device)
     _check(_lib.q8t_maxpool_relu_bwd(_ptr(gpool), _ptr(idx), N, Cc, H, W, _ptr(dy), _stream()), "q8t_maxpool_relu_bwd")
     return dy
+
+
+def maxpool_range_bn_bwd_bifurcate(x, gpool, idx, stats, gamma=None, eps=0.0, seed8=0, seed16=1, want_q8=True, ws=None):
+    """maxpool_relu_bwd followed by range_bn_bwd_bifurcate without the unpooled gradient in memory.
+    Returns (dgamma, dbeta, q8, qp8, q16, qp16); want_q8=False leaves q8 = qp8 = None."""
+    _dev(x), _dev(gpool), _dev(idx), _dev(stats)
+    N, Cc, H, W = x.shape
+    assert tuple(gpool.shape) == (N, Cc, (H - 1) // 2 + 1, (W - 1) // 2 + 1) and gpool.shape == idx.shape
+    _, dgamma, dbeta, q8, qp8, q16, qp16, ws = _bn_bwd_bifurcate_buffers(
+        x, None, None, None, None, None, ws, False, want_q8, _lib.q8t_maxpool_range_bn_bwd_bifurcate_workspace_size)
+    _check(_lib.q8t_maxpool_range_bn_bwd_bifurcate(_ptr(x), _ptr(gpool), _ptr(idx), _ptr(stats), N, Cc, H, W, _ptr(gamma),
+                                                   float(eps), _ptr(dgamma), _ptr(dbeta), int(seed8) & (2 ** 64 - 1),
+                                                   int(seed16) & (2 ** 64 - 1), _ptr(q8), _ptr(qp8), _ptr(q16), _ptr(qp16),
+                                                   _ptr(ws), _stream()), "q8t_maxpool_range_bn_bwd_bifurcate")
+    return dgamma, dbeta, q8, qp8, q16, qp16
 
 
 def add_relu_quantize(a, b, quantized=True, ws=None):

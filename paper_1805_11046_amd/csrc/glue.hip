@@ -9,8 +9,11 @@
 //   * ReLU backward, optionally added to the gradient of the other branch.
 #include "q8t_common.h"
 #include "q8t_internal.h"
+#include "pool_gather.h"
 
 namespace {
+
+using q8t_pool::small_div;
 
 constexpr int kThreads = 256;
 constexpr int kMaxPartials = 1024;
@@ -31,16 +34,6 @@ __device__ __forceinline__ float g_bn_relu(float x, float mu, float inv, float g
     const float sc = xh * g;
     const float y = sc + b;
     return y > 0.0f ? y : 0.0f;
-}
-
-// quotient n / d for n < 2^22 (positions inside one plane): float estimate + fix-up
-__device__ __forceinline__ int small_div(int n, int d, float rd)
-{
-    int q = (int)((float)n * rd);
-    const int r = n - q * d;
-    q += r >= d ? 1 : 0;
-    q -= r < 0 ? 1 : 0;
-    return q;
 }
 
 // a workgroup per (image, channel) plane (32-bit index arithmetic inside it).  VEC (W a multiple of 4):
@@ -116,24 +109,6 @@ __global__ __launch_bounds__(kThreads) void bn_relu_maxpool_fwd(const float *__r
     }
 }
 
-// gradient that reaches position (h, w): an even row / column belongs to one window, an odd one to
-// two; windows in the order a scatter over the pooled plane visits them (rows ascending, then columns)
-__device__ __forceinline__ float pool_bwd_at(const float *__restrict__ gp, const uint8_t *__restrict__ ip, int h, int w, int P, int Q)
-{
-    const int p1 = (h + 1) >> 1, p0 = p1 - (h & 1);
-    const int q1 = (w + 1) >> 1, q0 = q1 - (w & 1);
-    float acc = 0.0f;
-    for (int p = p0; p <= p1; ++p) {
-        if (p >= P) continue;
-        for (int q = q0; q <= q1; ++q) {
-            if (q >= Q) continue;
-            const int local = 3 * (h - (2 * p - 1)) + (w - (2 * q - 1));
-            if (ip[p * Q + q] == local) acc += gp[p * Q + q];
-        }
-    }
-    return acc;
-}
-
 // a workgroup per plane; with W a multiple of 4 a thread writes 4 neighbouring positions at once.  LDS: the pooled
 // plane and its indices are first copied into LDS with wide coalesced loads and gathered from there (a position
 // looks at up to six pooled elements: as global loads those dozen narrow accesses per 16 bytes written bound
@@ -149,48 +124,23 @@ __global__ __launch_bounds__(kThreads) void maxpool_relu_bwd(const float *__rest
     float *dp = dy + pl * (int64_t)H * W;
     if (LDS) {
         // P * Q is a multiple of 16 here and both planes start 16-byte aligned
-        const int PQ = P * Q;
-        float *sg = reinterpret_cast<float *>(pool_lds);
-        uint8_t *si = pool_lds + (size_t)PQ * sizeof(float);
-        for (int i = threadIdx.x; i < PQ / 4; i += kThreads)
-            reinterpret_cast<float4 *>(sg)[i] = q8t_ld_last(reinterpret_cast<const float4 *>(gp) + i);
-        for (int i = threadIdx.x; i < PQ / 16; i += kThreads)
-            reinterpret_cast<uint4 *>(si)[i] = reinterpret_cast<const uint4 *>(ip)[i];
+        q8t_pool::stage_plane<kThreads>(gp, ip, P * Q, pool_lds);
         __syncthreads();
-        gp = sg;
-        ip = si;
+        gp = reinterpret_cast<const float *>(pool_lds);
+        ip = pool_lds + (size_t)P * Q * sizeof(float);
     }
     if (VEC) {
-        // positions w..w+3 (w a multiple of 4) of row h meet the pooled columns qa = w/2, qa+1, qa+2 at fixed places
-        // inside their windows: w -> (qa, col 1); w+1 -> (qa, 2), (qa+1, 0); w+2 -> (qa+1, 1); w+3 -> (qa+1, 2), (qa+2, 0);
-        // an even row h meets pooled row h/2 at window row 1, an odd one rows (h-1)/2 and (h+1)/2 at window rows 2 and 0
         const int W4 = W >> 2;
         const float rw = 1.0f / (float)W4;
         for (int e = threadIdx.x; e < H * W4; e += kThreads) {
             const int h = small_div(e, W4, rw), qa = 2 * (e - h * W4);
-            float4 r = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            const int np = (h & 1) ? 2 : 1;
-            for (int k = 0; k < np; ++k) {
-                const int p = (h >> 1) + k, i = (h & 1) ? 2 - 2 * k : 1;
-                if (p >= P) break;
-                const uint8_t *ir = ip + p * Q + qa;
-                const float *gr = gp + p * Q + qa;
-                const int ia = ir[0], ib = ir[1], ic = qa + 2 < Q ? ir[2] : 255;     // Q = W / 2 is even: qa + 1 < Q
-                const float ga = gr[0], gb = gr[1], gc = qa + 2 < Q ? gr[2] : 0.0f;
-                r.x += ia == 3 * i + 1 ? ga : 0.0f;
-                r.y += ia == 3 * i + 2 ? ga : 0.0f;
-                r.y += ib == 3 * i ? gb : 0.0f;
-                r.z += ib == 3 * i + 1 ? gb : 0.0f;
-                r.w += ib == 3 * i + 2 ? gb : 0.0f;
-                r.w += ic == 3 * i ? gc : 0.0f;
-            }
-            reinterpret_cast<float4 *>(dp)[e] = r;
+            reinterpret_cast<float4 *>(dp)[e] = q8t_pool::bwd_gather4(gp, ip, h, qa, P, Q);
         }
     } else {
         const float rw = 1.0f / (float)W;
         for (int e = threadIdx.x; e < H * W; e += kThreads) {
             const int h = small_div(e, W, rw), w = e - h * W;
-            dp[e] = pool_bwd_at(gp, ip, h, w, P, Q);
+            dp[e] = q8t_pool::bwd_at(gp, ip, h, w, P, Q);
         }
     }
 }
@@ -445,7 +395,7 @@ int q8t_maxpool_relu_bwd(const float *gpool, const uint8_t *idx, int N, int C, i
     const int64_t planes = (int64_t)N * C;
     if (planes > 0x7FFFFFFF || (int64_t)H * W >= (1 << 22)) return Q8T_ERR_SHAPE;
     const int PQ = P * Q;
-    const size_t lds = (size_t)PQ * 5;
+    const size_t lds = q8t_pool::lds_bytes(PQ);
     if (W % 4 == 0 && q8t_aligned(dy, 16)) {
         if (PQ % 16 == 0 && lds <= 48 * 1024 && q8t_aligned(gpool, 16) && q8t_aligned(idx, 16))
             hipLaunchKernelGGL((maxpool_relu_bwd<true, true>), dim3((unsigned)planes), dim3(kThreads), lds, (hipStream_t)stream,

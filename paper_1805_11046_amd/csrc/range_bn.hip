@@ -13,6 +13,7 @@
 // Every elementwise kernel takes an optional rectifier: Range BN followed by ReLU in one pass.
 #include "q8t_common.h"
 #include "q8t_internal.h"
+#include "pool_gather.h"
 
 namespace {
 
@@ -548,14 +549,31 @@ struct ExtList {
     int b[kExtCap], pos[kExtCap];   // image, position inside the plane
 };
 
-template <bool VEC>
+// POOL: the upstream gradient is not a tensor in memory but the backward of the stem's 3x3 / stride 2 max pooling,
+// gathered from the pooled gradient and the window indices (one pooled plane at a time staged in LDS); planes of at
+// least 4 * kThreads positions with a width that is a multiple of 4.
+struct PoolSrc {
+    const float *g;
+    const uint8_t *idx;
+    int W4, P, Q;    // float4 groups per row of the unpooled plane, pooled plane
+    float rw4;       // 1 / W4
+};
+__device__ __forceinline__ float4 pool_grad4(const PoolSrc &ps, const uint8_t *lds, int i)
+{
+    const int h = q8t_pool::small_div(i, ps.W4, ps.rw4), qa = 2 * (i - h * ps.W4);
+    return q8t_pool::bwd_gather4(reinterpret_cast<const float *>(lds), lds + (size_t)ps.P * ps.Q * sizeof(float), h, qa, ps.P,
+                                 ps.Q);
+}
+
+template <bool VEC, bool POOL = false>
 __global__ __launch_bounds__(kThreads) void bn_bwdq_partial(const float *__restrict__ x, const float *__restrict__ dy,
                                                             const float *__restrict__ stats, int N, int C, int HW, int NB,
                                                             float cn, float eps, const float *__restrict__ gamma,
                                                             const float *__restrict__ beta, int relu,
                                                             BwdPartialQ *__restrict__ parts, ExtList *__restrict__ lists,
-                                                            uint8_t *__restrict__ flags)
+                                                            uint8_t *__restrict__ flags, const PoolSrc pool)
 {
+    extern __shared__ __attribute__((aligned(16))) uint8_t pool_lds[];
     __shared__ double smd[kThreads / 64];
     __shared__ float smf[kThreads / 64];
     __shared__ int ext_cnt, ext_b[kExtCap], ext_pos[kExtCap];
@@ -605,9 +623,16 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_partial(const float *__restr
                 const int64_t base = ((int64_t)b * C + c) * HW;
                 const float4 *px = reinterpret_cast<const float4 *>(x + base);
                 const float4 *pg = reinterpret_cast<const float4 *>(dy + base);
+                if (POOL) {
+                    __syncthreads();   // the gather of the previous plane is over
+                    const int64_t pp = ((int64_t)b * C + c) * (pool.P * pool.Q);
+                    q8t_pool::stage_plane<kThreads>(pool.g + pp, pool.idx + pp, pool.P * pool.Q, pool_lds);
+                    __syncthreads();
+                }
 #pragma unroll 2
                 for (int i = threadIdx.x; i < hw4; i += kThreads) {
-                    const float4 v = q8t_ld_first(px + i), g = q8t_ld_first(pg + i);
+                    const float4 v = q8t_ld_first(px + i);
+                    const float4 g = POOL ? pool_grad4(pool, pool_lds, i) : q8t_ld_first(pg + i);
                     const uint32_t m = one(v.x, g.x, b, 4 * i) | (one(v.y, g.y, b, 4 * i + 1) << 1) |
                                        (one(v.z, g.z, b, 4 * i + 2) << 2) | (one(v.w, g.w, b, 4 * i + 3) << 3);
                     if (flags) flags[(base >> 2) + i] = (uint8_t)m;
@@ -730,7 +755,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_finalize(const BwdPartialQ *
 }
 
 // pass 2: dx (optional) and its two stochastic copies
-template <bool VEC>
+template <bool VEC, bool POOL = false>
 __global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restrict__ x, const float *__restrict__ dy,
                                                           int64_t planes, int C, int HW, const float *__restrict__ stats,
                                                           const float *__restrict__ gamma, const float *__restrict__ beta,
@@ -740,8 +765,11 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restric
                                                           q8t_qparams *__restrict__ qp8_out,
                                                           q8t_qparams *__restrict__ qp16_out, float *__restrict__ dx,
                                                           int8_t *__restrict__ q8, int16_t *__restrict__ q16,
-                                                          const int *__restrict__ crowded, const uint8_t *__restrict__ flags)
+                                                          const int *__restrict__ crowded, const uint8_t *__restrict__ flags,
+                                                          const PoolSrc pool)
 {
+    extern __shared__ __attribute__((aligned(16))) uint8_t pool_lds[];
+    // q8 == NULL: the 16-bit copy alone (a layer whose input needs no gradient)
     // crowded != NULL: x is read only for channels marked there; elsewhere every coordinate is treated as an
     // ordinary one (mask from `flags` under the rectifier) and bn_bwdq_fixup rewrites the listed ones afterwards
     // every workgroup folds the ranges of pass 1 (min / max: any order gives the same bits)
@@ -756,7 +784,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restric
     vmax = block_max_f(vmax, smf);
     const q8t_qparams qp8 = make_qparams(vmin, vmax, 8), qp16 = make_qparams(vmin, vmax, 16);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        *qp8_out = qp8;
+        if (qp8_out) *qp8_out = qp8;
         *qp16_out = qp16;
     }
     const Affine a8 = affine_of(qp8), a16 = affine_of(qp16);
@@ -798,7 +826,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restric
                 r.w = bn_dx(v.w, d.w, g, k.x, inv, k.y, mn, mx);
             }
             if (dx) reinterpret_cast<float4 *>(dx)[i4] = r;
-            reinterpret_cast<uint32_t *>(q8)[i4] = quant4<int8_t, true>(r, a8, (uint32_t)i4, s8_lo, s8_hi);
+            if (q8) reinterpret_cast<uint32_t *>(q8)[i4] = quant4<int8_t, true>(r, a8, (uint32_t)i4, s8_lo, s8_hi);
             reinterpret_cast<uint2 *>(q16)[i4] = quant4<int16_t, true>(r, a16, (uint32_t)i4, s16_lo, s16_hi);
         }
     } else if (VEC) {
@@ -816,11 +844,17 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restric
             uint2 *o16 = reinterpret_cast<uint2 *>(q16 + base);
             const int64_t g0 = base >> 2;   // generator group of the plane's first element
             const int hw4 = HW >> 2;
+            if (POOL) {
+                __syncthreads();   // the gather of the previous plane is over
+                const int64_t pp = pl * (pool.P * pool.Q);
+                q8t_pool::stage_plane<kThreads>(pool.g + pp, pool.idx + pp, pool.P * pool.Q, pool_lds);
+                __syncthreads();
+            }
             if (crowded && !crowded[c]) {
                 const uint8_t *pf = flags + g0;
 #pragma unroll 2
                 for (int i = threadIdx.x; i < hw4; i += kThreads) {
-                    float4 d = q8t_ld_last(pg + i);
+                    float4 d = POOL ? pool_grad4(pool, pool_lds, i) : q8t_ld_last(pg + i);
                     if (relu) {
                         const uint32_t m = pf[i];
                         d.x = (m & 1u) ? d.x : 0.0f;
@@ -835,7 +869,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restric
                     r.w = bn_dx_kind(d.w, g, k.x, inv, k.y, 0);
                     if (dx) o[i] = r;
                     const uint32_t grp = (uint32_t)(g0 + i);
-                    o8[i] = quant4<int8_t, true>(r, a8, grp, s8_lo, s8_hi);
+                    if (q8) o8[i] = quant4<int8_t, true>(r, a8, grp, s8_lo, s8_hi);
                     o16[i] = quant4<int16_t, true>(r, a16, grp, s16_lo, s16_hi);
                 }
                 continue;
@@ -843,7 +877,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restric
 #pragma unroll 2
             for (int i = threadIdx.x; i < hw4; i += kThreads) {
                 const float4 v = q8t_ld_last(px + i);
-                float4 d = q8t_ld_last(pg + i);
+                float4 d = POOL ? pool_grad4(pool, pool_lds, i) : q8t_ld_last(pg + i);
                 if (relu) {
                     d.x = bn_map(v.x, mu, inv, g, be) > 0.0f ? d.x : 0.0f;
                     d.y = bn_map(v.y, mu, inv, g, be) > 0.0f ? d.y : 0.0f;
@@ -857,7 +891,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restric
                 r.w = bn_dx(v.w, d.w, g, k.x, inv, k.y, mn, mx);
                 if (dx) o[i] = r;
                 const uint32_t grp = (uint32_t)(g0 + i);
-                o8[i] = quant4<int8_t, true>(r, a8, grp, s8_lo, s8_hi);
+                if (q8) o8[i] = quant4<int8_t, true>(r, a8, grp, s8_lo, s8_hi);
                 o16[i] = quant4<int16_t, true>(r, a16, grp, s16_lo, s16_hi);
             }
         }
@@ -873,7 +907,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restric
             const float d = relu && !(bn_map(xv, stats[c], inv, g, beta ? beta[c] : 0.0f) > 0.0f) ? 0.0f : dy[i];
             const float r = bn_dx(xv, d, g, k.x, inv, k.y, mn, mx);
             if (dx) dx[i] = r;
-            q8[i] = (int8_t)(level_of<true>(r, a8, rng_r16(i, s8_lo, s8_hi)) - a8.half);
+            if (q8) q8[i] = (int8_t)(level_of<true>(r, a8, rng_r16(i, s8_lo, s8_hi)) - a8.half);
             q16[i] = (int16_t)(level_of<true>(r, a16, rng_r16(i, s16_lo, s16_hi)) - a16.half);
         }
     }
@@ -904,7 +938,7 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply_flat4(const float *__r
     vmax = block_max_f(vmax, smf);
     const q8t_qparams qp8 = make_qparams(vmin, vmax, 8), qp16 = make_qparams(vmin, vmax, 16);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        *qp8_out = qp8;
+        if (qp8_out) *qp8_out = qp8;
         *qp16_out = qp16;
     }
     const Affine a8 = affine_of(qp8), a16 = affine_of(qp16);
@@ -948,12 +982,13 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply_flat4(const float *__r
         }
         const float4 r = make_float4(rv[0], rv[1], rv[2], rv[3]);
         if (dx) reinterpret_cast<float4 *>(dx)[i4] = r;
-        reinterpret_cast<uint32_t *>(q8)[i4] = quant4<int8_t, true>(r, a8, (uint32_t)i4, s8_lo, s8_hi);
+        if (q8) reinterpret_cast<uint32_t *>(q8)[i4] = quant4<int8_t, true>(r, a8, (uint32_t)i4, s8_lo, s8_hi);
         reinterpret_cast<uint2 *>(q16)[i4] = quant4<int16_t, true>(r, a16, (uint32_t)i4, s16_lo, s16_hi);
     }
 }
 
 // after pass 2: the listed coordinates (at the channel's max or min) get their real dx and codes
+template <bool POOL = false>
 __global__ __launch_bounds__(64) void bn_bwdq_fixup(const float *__restrict__ x, const float *__restrict__ dy, int C, int HW,
                                                     int split, const float *__restrict__ stats,
                                                     const float *__restrict__ gamma, const float *__restrict__ beta, int relu,
@@ -961,7 +996,8 @@ __global__ __launch_bounds__(64) void bn_bwdq_fixup(const float *__restrict__ x,
                                                     uint32_t s8_hi, uint32_t s16_lo, uint32_t s16_hi,
                                                     const q8t_qparams *__restrict__ qp8, const q8t_qparams *__restrict__ qp16,
                                                     const ExtList *__restrict__ lists, const int *__restrict__ crowded,
-                                                    float *__restrict__ dx, int8_t *__restrict__ q8, int16_t *__restrict__ q16)
+                                                    float *__restrict__ dx, int8_t *__restrict__ q8, int16_t *__restrict__ q16,
+                                                    const PoolSrc pool)
 {
     const int c = blockIdx.x;
     if (crowded[c]) return;
@@ -969,17 +1005,25 @@ __global__ __launch_bounds__(64) void bn_bwdq_fixup(const float *__restrict__ x,
     const float inv = bn_inv(mn, mx, cn, eps);
     const float g = gamma ? gamma[c] : 1.0f, be = beta ? beta[c] : 0.0f;
     const float2 k = consts[c];
-    const Affine a8 = affine_of(*qp8), a16 = affine_of(*qp16);
+    const Affine a16 = affine_of(*qp16), a8 = q8 ? affine_of(*qp8) : a16;
     for (int e = threadIdx.x; e < split * kExtCap; e += 64) {
         const int sp = e / kExtCap, slot = e - sp * kExtCap;
         const ExtList *l = lists + (int64_t)c * split + sp;
         if (slot >= l->cnt) continue;
         const int64_t j = ((int64_t)l->b[slot] * C + c) * HW + l->pos[slot];
         const float xv = x[j];
-        const float d = relu && !(bn_map(xv, mu, inv, g, be) > 0.0f) ? 0.0f : dy[j];
+        float up;
+        if (POOL) {
+            const int W = 4 * pool.W4, h = l->pos[slot] / W, w = l->pos[slot] - h * W;
+            const int64_t pp = ((int64_t)l->b[slot] * C + c) * (pool.P * pool.Q);
+            up = q8t_pool::bwd_at(pool.g + pp, pool.idx + pp, h, w, pool.P, pool.Q);
+        } else {
+            up = dy[j];
+        }
+        const float d = relu && !(bn_map(xv, mu, inv, g, be) > 0.0f) ? 0.0f : up;
         const float r = bn_dx(xv, d, g, k.x, inv, k.y, mn, mx);
         if (dx) dx[j] = r;
-        q8[j] = (int8_t)(level_of<true>(r, a8, rng_r16(j, s8_lo, s8_hi)) - a8.half);
+        if (q8) q8[j] = (int8_t)(level_of<true>(r, a8, rng_r16(j, s8_lo, s8_hi)) - a8.half);
         q16[j] = (int16_t)(level_of<true>(r, a16, rng_r16(j, s16_lo, s16_hi)) - a16.half);
     }
 }
@@ -1199,15 +1243,26 @@ size_t q8t_range_bn_bwd_bifurcate_workspace_size(int N, int C, int H, int W)
     return bwdq_fixed_bytes(C);
 }
 
+// the pooled-gradient variant serves planes of at least 4 * kThreads positions whose width is a multiple of 4 and
+// whose pooled plane (a multiple of 16 elements) fits in LDS; other shapes go through an unpooled gradient
+static bool pooled_direct(int H, int W)
+{
+    const int P = (H - 1) / 2 + 1, Q = (W - 1) / 2 + 1;
+    return W % 4 == 0 && (int64_t)H * W >= 4 * kThreads && (int64_t)H * W < (1 << 22) && (P * Q) % 16 == 0 &&
+           q8t_pool::lds_bytes(P * Q) <= 60 * 1024;
+}
+
+// gpool / idx != NULL: dy is not read; the upstream gradient is gathered from the pooled one (pooled_direct shapes)
 static int range_bn_bwd_bifurcate_impl(const float *x, const float *dy, const float *stats, int N, int C, int H, int W,
                                        const float *gamma, const float *beta, int relu, float eps, float *dx,
                                        float *dgamma, float *dbeta, uint64_t seed8, uint64_t seed16, int8_t *q8_out,
                                        q8t_qparams *qp8_out, int16_t *q16_out, q8t_qparams *qp16_out, void *ws,
-                                       void *stream)
+                                       void *stream, const float *gpool = nullptr, const uint8_t *idx = nullptr)
 {
     const int rc = check_shape(N, C, H, W);
     if (rc) return rc;
-    if (!x || !dy || !stats || !q8_out || !qp8_out || !q16_out || !qp16_out) return Q8T_ERR_NULL;
+    const bool pooled = gpool != nullptr;
+    if (!x || (!dy && !pooled) || !stats || (q8_out && !qp8_out) || !q16_out || !qp16_out) return Q8T_ERR_NULL;
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     const int HW = H * W;
@@ -1219,6 +1274,9 @@ static int range_bn_bwd_bifurcate_impl(const float *x, const float *dy, const fl
     const int nsplit = (N + NB - 1) / NB;
     const bool vec = (HW % 4 == 0) && q8t_aligned(x, 16) && q8t_aligned(dy, 16) && (!dx || q8t_aligned(dx, 16)) &&
                      q8t_aligned(q8_out, 4) && q8t_aligned(q16_out, 8);
+    if (pooled && !(vec && !relu && pooled_direct(H, W) && q8t_aligned(gpool, 16) && q8t_aligned(idx, 16))) return Q8T_ERR_SHAPE;
+    PoolSrc pool = {gpool, idx, W >> 2, (H - 1) / 2 + 1, (W - 1) / 2 + 1, 1.0f / (float)(W >> 2 ? W >> 2 : 1)};
+    const size_t pool_lds = pooled ? q8t_pool::lds_bytes(pool.P * pool.Q) : 0;
     // Without the rectifier (and with float4 access) pass 2 leaves x alone: 15 instead of 19 bytes per element.
     // Measured: -6% only, the pass is as much bound by the ~45 vector operations per element of the two hashed
     // roundings as by memory; with the rectifier the mask bytes cost more than the x they replace (+4%), so that
@@ -1230,12 +1288,15 @@ static int range_bn_bwd_bifurcate_impl(const float *x, const float *dy, const fl
     ExtList *lists = nox ? (ExtList *)((char *)ws + bwdq_head_bytes(C)) : (ExtList *)nullptr;
     int *crowded = nox ? (int *)((char *)lists + align16((size_t)C * kMaxSplit * sizeof(ExtList))) : (int *)nullptr;
     uint8_t *flags = nullptr;
-    if (vec)
-        hipLaunchKernelGGL(bn_bwdq_partial<true>, dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn, eps,
-                           gamma, beta, relu, parts, lists, flags);
+    if (pooled)
+        hipLaunchKernelGGL((bn_bwdq_partial<true, true>), dim3(C, nsplit), dim3(kThreads), pool_lds, st, x, dy, stats, N, C, HW, NB,
+                           cn, eps, gamma, beta, relu, parts, lists, flags, pool);
+    else if (vec)
+        hipLaunchKernelGGL((bn_bwdq_partial<true, false>), dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn,
+                           eps, gamma, beta, relu, parts, lists, flags, pool);
     else
-        hipLaunchKernelGGL(bn_bwdq_partial<false>, dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn, eps,
-                           gamma, beta, relu, parts, lists, flags);
+        hipLaunchKernelGGL((bn_bwdq_partial<false, false>), dim3(C, nsplit), dim3(kThreads), 0, st, x, dy, stats, N, C, HW, NB, cn,
+                           eps, gamma, beta, relu, parts, lists, flags, pool);
     Q8T_LAUNCH_CHECK();
     float2 *mm = consts + C;
     const int nmm = (C + kThreads / 64 - 1) / (kThreads / 64);
@@ -1248,13 +1309,24 @@ static int range_bn_bwd_bifurcate_impl(const float *x, const float *dy, const fl
         // planes of at least 1024 positions: a workgroup per plane; smaller ones: a float4 per thread
         const int64_t blocks4 = (planes * (HW >> 2) + kThreads - 1) / kThreads;
         const int64_t gridx = HW >= 4 * kThreads ? planes_grid(planes) : (blocks4 < 65536 * 16 ? blocks4 : 65536 * 16);
-        hipLaunchKernelGGL(bn_bwdq_apply<true>, dim3((unsigned)gridx), dim3(kThreads), 0, st, x, dy, planes, C, HW, stats,
-                           gamma, beta, relu, consts, cn, eps, s8l, s8h, s16l, s16h, mm, nmm, qp8_out, qp16_out, dx, q8_out, q16_out,
-                           crowded, flags);
+        if (pooled)
+            hipLaunchKernelGGL((bn_bwdq_apply<true, true>), dim3((unsigned)gridx), dim3(kThreads), pool_lds, st, x, dy, planes, C,
+                               HW, stats, gamma, beta, relu, consts, cn, eps, s8l, s8h, s16l, s16h, mm, nmm, qp8_out, qp16_out, dx,
+                               q8_out, q16_out, crowded, flags, pool);
+        else
+            hipLaunchKernelGGL((bn_bwdq_apply<true, false>), dim3((unsigned)gridx), dim3(kThreads), 0, st, x, dy, planes, C, HW,
+                               stats, gamma, beta, relu, consts, cn, eps, s8l, s8h, s16l, s16h, mm, nmm, qp8_out, qp16_out, dx,
+                               q8_out, q16_out, crowded, flags, pool);
         if (nox) {
             Q8T_LAUNCH_CHECK();
-            hipLaunchKernelGGL(bn_bwdq_fixup, dim3(C), dim3(64), 0, st, x, dy, C, HW, nsplit, stats, gamma, beta, relu, consts, cn,
-                               eps, s8l, s8h, s16l, s16h, qp8_out, qp16_out, lists, crowded, dx, q8_out, q16_out);
+            if (pooled)
+                hipLaunchKernelGGL(bn_bwdq_fixup<true>, dim3(C), dim3(64), 0, st, x, dy, C, HW, nsplit, stats, gamma, beta, relu,
+                                   consts, cn, eps, s8l, s8h, s16l, s16h, qp8_out, qp16_out, lists, crowded, dx, q8_out, q16_out,
+                                   pool);
+            else
+                hipLaunchKernelGGL(bn_bwdq_fixup<false>, dim3(C), dim3(64), 0, st, x, dy, C, HW, nsplit, stats, gamma, beta, relu,
+                                   consts, cn, eps, s8l, s8h, s16l, s16h, qp8_out, qp16_out, lists, crowded, dx, q8_out, q16_out,
+                                   pool);
         }
     } else if (flat4) {
         const int64_t blocks4 = (total / 4 + kThreads - 1) / kThreads;
@@ -1263,14 +1335,15 @@ static int range_bn_bwd_bifurcate_impl(const float *x, const float *dy, const fl
                            qp8_out, qp16_out, dx, q8_out, q16_out, crowded);
         if (nox) {
             Q8T_LAUNCH_CHECK();
-            hipLaunchKernelGGL(bn_bwdq_fixup, dim3(C), dim3(64), 0, st, x, dy, C, HW, nsplit, stats, gamma, beta, relu, consts, cn,
-                               eps, s8l, s8h, s16l, s16h, qp8_out, qp16_out, lists, crowded, dx, q8_out, q16_out);
+            hipLaunchKernelGGL(bn_bwdq_fixup<false>, dim3(C), dim3(64), 0, st, x, dy, C, HW, nsplit, stats, gamma, beta, relu,
+                               consts, cn, eps, s8l, s8h, s16l, s16h, qp8_out, qp16_out, lists, crowded, dx, q8_out, q16_out, pool);
         }
     } else {
         const int64_t blocks = (total + kThreads - 1) / kThreads;
-        hipLaunchKernelGGL(bn_bwdq_apply<false>, dim3((unsigned)(blocks < 65536 * 16 ? blocks : 65536 * 16)), dim3(kThreads), 0,
-                           st, x, dy, planes, C, HW, stats, gamma, beta, relu, consts, cn, eps, s8l, s8h, s16l, s16h, mm, nmm,
-                           qp8_out, qp16_out, dx, q8_out, q16_out, (const int *)nullptr, (const uint8_t *)nullptr);
+        hipLaunchKernelGGL((bn_bwdq_apply<false, false>), dim3((unsigned)(blocks < 65536 * 16 ? blocks : 65536 * 16)),
+                           dim3(kThreads), 0, st, x, dy, planes, C, HW, stats, gamma, beta, relu, consts, cn, eps, s8l, s8h, s16l,
+                           s16h, mm, nmm, qp8_out, qp16_out, dx, q8_out, q16_out, (const int *)nullptr, (const uint8_t *)nullptr,
+                           pool);
     }
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
@@ -1292,6 +1365,37 @@ int q8t_range_bn_relu_bwd_bifurcate(const float *x, const float *dy, const float
                                     void *stream)
 {
     return range_bn_bwd_bifurcate_impl(x, dy, stats, N, C, H, W, gamma, beta, 1, eps, dx, dgamma, dbeta, seed8, seed16,
+                                       q8_out, qp8_out, q16_out, qp16_out, ws, stream);
+}
+
+size_t q8t_maxpool_range_bn_bwd_bifurcate_workspace_size(int N, int C, int H, int W)
+{
+    if (C <= 0 || N <= 0 || H <= 0 || W <= 0) return 0;
+    const size_t fixed = align16(bwdq_fixed_bytes(C));
+    return pooled_direct(H, W) ? fixed : fixed + sizeof(float) * (size_t)N * C * H * W;
+}
+
+int q8t_maxpool_range_bn_bwd_bifurcate(const float *x, const float *gpool, const uint8_t *idx, const float *stats, int N, int C,
+                                       int H, int W, const float *gamma, float eps, float *dgamma, float *dbeta, uint64_t seed8,
+                                       uint64_t seed16, int8_t *q8_out, q8t_qparams *qp8_out, int16_t *q16_out,
+                                       q8t_qparams *qp16_out, void *ws, void *stream)
+{
+    const int rc = check_shape(N, C, H, W);
+    if (rc) return rc;
+    if (!gpool || !idx) return Q8T_ERR_NULL;
+    if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    if (pooled_direct(H, W)) {
+        if (!q8t_aligned(x, 16) || !q8t_aligned(gpool, 16) || !q8t_aligned(idx, 16) || !q8t_aligned(q8_out, 4) ||
+            !q8t_aligned(q16_out, 8))
+            return Q8T_ERR_SHAPE;
+        return range_bn_bwd_bifurcate_impl(x, nullptr, stats, N, C, H, W, gamma, nullptr, 0, eps, nullptr, dgamma, dbeta, seed8,
+                                           seed16, q8_out, qp8_out, q16_out, qp16_out, ws, stream, gpool, idx);
+    }
+    // other shapes: the unpooled gradient goes through the workspace
+    float *dy = (float *)((char *)ws + align16(bwdq_fixed_bytes(C)));
+    const int rp = q8t_maxpool_relu_bwd(gpool, idx, N, C, H, W, dy, stream);
+    if (rp) return rp;
+    return range_bn_bwd_bifurcate_impl(x, dy, stats, N, C, H, W, gamma, nullptr, 0, eps, nullptr, dgamma, dbeta, seed8, seed16,
                                        q8_out, qp8_out, q16_out, qp16_out, ws, stream);
 }
 

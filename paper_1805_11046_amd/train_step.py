@@ -157,9 +157,9 @@ class ConvBN(torch.autograd.Function):
 
 class StemConvBNPool(torch.autograd.Function):
     """First layer: quantize -> conv forward (+ Range BN statistics) -> Range BN + ReLU + 3x3/2 max pooling in one
-    pass (the normalized 112x112 tensor is never written); backward: pooled gradient -> upstream gradient of the
-    Range BN (one pass) -> Range BN backward + bifurcated quantization -> weight gradient.  The network input
-    needs no gradient."""
+    pass (the normalized 112x112 tensor is never written); backward: pooled gradient -> Range BN backward + 16-bit
+    copy of its result, the upstream gradient of the Range BN gathered from the pooled one on the fly -> weight
+    gradient.  The network input needs no gradient."""
 
     @staticmethod
     def forward(ctx, a, w, stride, pad):
@@ -180,9 +180,17 @@ class StemConvBNPool(torch.autograd.Function):
     @staticmethod
     def backward(ctx, gp):
         d, qa, pa, y, stats, idx, ops, nx, ny, lid = ctx.saved
-        dy = _call("maxpool_relu_bwd", 0, 5 * (ny // 4) + 4 * ny, q8t.maxpool_relu_bwd, gp.contiguous(), idx, d.P, d.Q)
-        _, _, _, g8, pg8, g16, pg16 = _bn_bwd(q8t.range_bn_bwd_bifurcate, "range_bn_bwd_bifurcate", ny, y, dy, stats, None, 1e-5,
-                                              2 * lid + 1, 2 * lid + 2)
+        if _angles is None:
+            # the unpooled gradient is never written: both passes gather it from the pooled one; no 8-bit copy (the
+            # network input needs no gradient).  Bytes: x once (4), the pooled gradient and its indices twice
+            # (2 * 5 / 4), the 16-bit copy (2)
+            _, _, _, _, g16, pg16 = _call("maxpool_range_bn_bwd_bifurcate", 0, 6 * ny + 10 * (ny // 4),
+                                          q8t.maxpool_range_bn_bwd_bifurcate, y, gp.contiguous(), idx, stats, None, 1e-5,
+                                          2 * lid + 1, 2 * lid + 2, False)
+        else:
+            dy = _call("maxpool_relu_bwd", 0, 5 * (ny // 4) + 4 * ny, q8t.maxpool_relu_bwd, gp.contiguous(), idx, d.P, d.Q)
+            _, _, _, g8, pg8, g16, pg16 = _bn_bwd(q8t.range_bn_bwd_bifurcate, "range_bn_bwd_bifurcate", ny, y, dy, stats, None,
+                                                  1e-5, 2 * lid + 1, 2 * lid + 2)
         dw, _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
         return None, dw, None, None
 

@@ -88,3 +88,44 @@ def test_block_tail_range_bn_add_relu_quantize(shape):
     same_ints(host(q2), sq2)
     out3, q3, _ = q8t.range_bn_add_relu_quantize(dev(x), dev(st), dev(o), dev(gamma), dev(beta), eps=eps, quantized=False)
     assert q3 is None and np.array_equal(host(out3), oout)
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 32, 32), (3, 64, 112, 112), (2, 4, 36, 32), (5, 2, 64, 48),   # gathered in both passes
+                                   (2, 3, 8, 8), (1, 2, 7, 9), (2, 5, 33, 20)])                           # through the workspace
+@pytest.mark.parametrize("want_q8", [True, False])
+def test_stem_backward_from_the_pooled_gradient(shape, want_q8):
+    # pooling backward + Range BN backward + bifurcated quantization in one call: bit-identical to the separate calls
+    # (which have their own parity tests), and the decoded 16-bit copy within one level of the oracle's dx
+    q8t = require_gpu()
+    g = synth.rng(sum(shape) + 1)
+    N, C, H, W = shape
+    x = synth.normal(g, shape, std=1.0)
+    x[:, 0].flat[[3, 17, (N - 1) * H * W + 5]] = 9.0        # several maxima: listed and patched after pass 2
+    if C > 2:
+        x[:, 2] = 0.75                            # a constant channel: every coordinate is extremal (crowded)
+    gamma = synth.normal(g, (C,), std=1.0)
+    beta = synth.normal(g, (C,), std=0.3)
+    stats = oracle.range_bn_stats(x)
+    xd, sd, gd = dev(x), dev(stats), dev(gamma)
+    _, idx = q8t.range_bn_relu_maxpool_fwd(xd, sd, gd, dev(beta), 1e-5)
+    gp = synth.normal(g, tuple(idx.shape), std=1e-2)
+    gpd = dev(gp)
+    dg, db, q8, qp8, q16, qp16 = q8t.maxpool_range_bn_bwd_bifurcate(xd, gpd, idx, sd, gd, 1e-5, seed8=5, seed16=6, want_q8=want_q8)
+    dy = q8t.maxpool_relu_bwd(gpd, idx, H, W)
+    _, rg, rb, r8, rp8, r16, rp16 = q8t.range_bn_bwd_bifurcate(xd, dy, sd, gd, 1e-5, seed8=5, seed16=6, want_dx=False)
+    assert np.array_equal(host(dg), host(rg)) and np.array_equal(host(db), host(rb))
+    assert q8t.qparams_to_host(qp16) == q8t.qparams_to_host(rp16)
+    same_ints(host(q16), host(r16))
+    if want_q8:
+        assert q8t.qparams_to_host(qp8) == q8t.qparams_to_host(rp8)
+        same_ints(host(q8), host(r8))
+    else:
+        assert q8 is None and qp8 is None
+    ody = oracle.maxpool_relu_bwd(gp, host(idx), H, W)
+    odx, odg, odb = oracle.range_bn_bwd(x, ody, stats, gamma, 1e-5)
+    close(host(dg), odg)
+    close(host(db), odb)
+    _, _, scale, _, zero_point, bits = q8t.qparams_to_host(qp16)
+    assert bits == 16
+    dec = (host(q16).astype(np.float64) + 32768 - zero_point) * scale
+    assert np.max(np.abs(dec - odx)) <= 1.001 * scale + 1e-5 * np.max(np.abs(odx))
