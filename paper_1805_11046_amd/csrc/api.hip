@@ -38,8 +38,9 @@ bool wgrad_wants_gemm(const q8t_conv_desc *d)
 size_t stats_in_epilogue_ws(const q8t_conv_desc *d)
 {
     if (q8t_nhwc_conv_supported(0, d)) return q8t_nhwc_conv_stats_ws(d);
-    if (smallc_wanted(0, d)) return q8t_smallc_conv_stats_ws(d);
-    return 0;
+    size_t s = smallc_wanted(0, d) ? q8t_smallc_conv_stats_ws(d) : 0;
+    const size_t f = q8t_first_conv_stats_ws(d);   // which of the two runs also depends on the pointers
+    return f > s ? f : s;
 }
 
 }  // namespace
@@ -96,6 +97,7 @@ size_t q8t_qconv_workspace_size(const q8t_conv_desc *desc, int which)
     }
     size_t h = which < 2 ? q8t_nhwc_conv_ws(which, desc) : (wgrad_wants_gemm(desc) ? q8t_gemm_wgrad_ws(desc) : 0);
     if (smallc_wanted(which, desc)) h = q8t_smallc_conv_ws(which, desc);
+    if (which == 0 && q8t_first_conv_ws(desc) > h) h = q8t_first_conv_ws(desc);
     if (h > g) g = h;
     return g > f ? g : f;
 }
@@ -112,6 +114,8 @@ int q8t_qconv_fwd(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams
         return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, nullptr, ws, (hipStream_t)stream);
     if (q8t_nhwc_conv_supported(0, desc))
         return q8t_nhwc_conv(0, desc, qx, px, qw, pw, y, acc_out, nullptr, nullptr, ws, (hipStream_t)stream);
+    if (q8t_first_conv_supported(desc, qx, y, acc_out))
+        return q8t_first_conv(desc, qx, px, qw, pw, y, acc_out, nullptr, nullptr, ws, (hipStream_t)stream);
     if (smallc_wanted(0, desc)) return q8t_smallc_conv(desc, qx, px, qw, pw, y, acc_out, nullptr, nullptr, ws, (hipStream_t)stream);
     return q8t_generic_conv(0, desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
 }
@@ -145,6 +149,8 @@ int q8t_qconv_fwd_bn_stats(const q8t_conv_desc *desc, const int8_t *qx, const q8
     void *sws = (char *)ws + ((q8t_qconv_workspace_size(desc, 0) + 255) & ~(size_t)255);
     if (q8t_nhwc_conv_supported(0, desc))
         return q8t_nhwc_conv(0, desc, qx, px, qw, pw, y, acc_out, stats_out, sws, ws, (hipStream_t)stream);
+    if (q8t_first_conv_supported(desc, qx, y, acc_out))
+        return q8t_first_conv(desc, qx, px, qw, pw, y, acc_out, stats_out, sws, ws, (hipStream_t)stream);
     if (smallc_wanted(0, desc) && q8t_smallc_conv_stats_ws(desc))
         return q8t_smallc_conv(desc, qx, px, qw, pw, y, acc_out, stats_out, sws, ws, (hipStream_t)stream);
     const int rc2 = q8t_qconv_fwd(desc, qx, px, qw, pw, y, acc_out, ws, stream);

@@ -63,6 +63,14 @@ int q8t_smallc_conv(const q8t_conv_desc *d, const void *a, const q8t_qparams *qa
                     float *out_f, void *out_acc, float *bn_stats, void *stats_ws, void *ws, hipStream_t st);
 size_t q8t_smallc_conv_stats_ws(const q8t_conv_desc *d);
 
+// forward with very few input channels and 64 output channels, filter rows of at most 8 taps: operand fragments read
+// straight from a staged band of input rows, filter in registers (conv_first.hip).  Contract of q8t_smallc_conv.
+bool q8t_first_conv_supported(const q8t_conv_desc *d, const void *a, const void *out_f, const void *out_acc);
+size_t q8t_first_conv_ws(const q8t_conv_desc *d);
+size_t q8t_first_conv_stats_ws(const q8t_conv_desc *d);
+int q8t_first_conv(const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b, const q8t_qparams *qb,
+                   float *out_f, void *out_acc, float *bn_stats, void *stats_ws, void *ws, hipStream_t st);
+
 // specialised 3x3 weight-gradient kernel (wgrad_fast.hip)
 bool q8t_fast_wgrad_supported(const q8t_conv_desc *d, const void *g16, const void *x, const void *dw,
                               const void *acc);

@@ -165,6 +165,11 @@ CONV_CASES = [
     # forward with few input channels: explicit im2col rows + GEMM
     (4, 16, 20, 20, 128, 3, 3, 1, 1),    # 144 columns -> 192, 128-wide tiles
     (8, 5, 30, 17, 64, 5, 3, 2, 2),      # non-square filter, stride 2, 75 columns -> 128
+    # forward with few input channels and 64 output channels: fragments read from a staged band of input rows
+    (3, 2, 20, 24, 64, 5, 5, 3, 2),      # stride 3, 10 groups of 5 taps (two K-steps), ragged last band
+    (2, 1, 12, 16, 64, 3, 8, 1, 0),      # one channel, rows of 8 taps, no padding (a single K-step)
+    (2, 6, 40, 40, 64, 5, 3, 1, 1),      # 30 groups (four K-steps), 40 positions per row: a ragged last tile
+    (1, 3, 224, 224, 64, 7, 7, 2, 3),    # the first layer of a ResNet at its real plane size
 ]
 
 
@@ -200,7 +205,8 @@ def test_conv_products(case):
 
 
 @pytest.mark.parametrize("case", [(2, 64, 14, 14, 64, 3, 3, 1, 1), (2, 64, 9, 11, 128, 3, 3, 2, 1),
-                                  (2, 16, 9, 9, 24, 3, 3, 1, 1), (2, 64, 10, 10, 128, 1, 1, 1, 0)])
+                                  (2, 16, 9, 9, 24, 3, 3, 1, 1), (2, 64, 10, 10, 128, 1, 1, 1, 0),
+                                  (2, 3, 16, 16, 64, 7, 7, 2, 3)])
 def test_conv_products_below_8_and_16_bits(case):
     # widths M < 8 (and < 16 for the weight-gradient operand) are stored as level - 2^(M-1) in the
     # same containers; every kernel family has to take the stored zero point from the width
