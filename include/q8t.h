@@ -193,6 +193,19 @@ int q8t_qconv_wgrad(const q8t_conv_desc *desc /* host */, const int8_t *qx, cons
                     const int16_t *qdy16, const q8t_qparams *pg16, float *dw, int64_t *acc_out,
                     void *ws, void *stream);
 
+/* The layer gradient of the first convolution of a residual block (Section 4, eq. (grad_layer): the dgrad
+ * product above) together with the plumbing that ends the block's backward pass:
+ *   dx[i] = act[i] > 0 ? dgrad[i] + other[i] : 0
+ * with dgrad the float result q8t_qconv_dgrad would store, other [N,C,H,W] the gradient of the block's other
+ * branch (nullable: nothing is added) and act [N,C,H,W] the block's input, through whose rectifier the
+ * gradient passes.  Bit-identical to q8t_qconv_dgrad followed by q8t_relu_bwd_sum; where the kernel for the
+ * shape has the step in its epilogue (3x3 / 1x1 stride-1 layers on large planes; other, act and dx
+ * 16-byte aligned) the product's result never makes the round trip through memory (12 instead of 20
+ * bytes per element); other shapes run the two steps one after the other, the second in place.  ws: q8t_qconv_workspace_size(desc, 1).  Errors as q8t_qconv_dgrad. */
+int q8t_qconv_dgrad_relu_sum(const q8t_conv_desc *desc /* host */, const int8_t *qdy, const q8t_qparams *pg,
+                             const int8_t *qw, const q8t_qparams *pw, const float *other, const float *act,
+                             float *dx, void *ws, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Range Batch-Norm over NCHW (Section 3, eq. (range); FC activations: H = W = 1).
  * Per channel c over its n = N*H*W values:

@@ -62,6 +62,7 @@ _SIGS = {
     "q8t_qconv_workspace_size": (_sz, [C.POINTER(ConvDesc), _i]),
     "q8t_qconv_fwd": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "q8t_qconv_dgrad": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_qconv_dgrad_relu_sum": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "q8t_qconv_wgrad": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "q8t_range_bn_workspace_size": (_sz, [_i, _i, _i, _i]),
     "q8t_range_bn_fwd": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -358,6 +359,23 @@ def qconv_dgrad(d, qdy, pg, qw, pw, want_acc=False, out=None, ws=None):
     assert tuple(qdy.shape) == (d.N, d.K, d.P, d.Q) and tuple(qw.shape) == (d.K, d.C, d.R, d.S)
     return _conv(_lib.q8t_qconv_dgrad, "q8t_qconv_dgrad", d, qdy, pg, qw, pw, (d.N, d.C, d.H, d.W), 1,
                  torch.int32, want_acc, out, ws)
+
+
+def qconv_dgrad_relu_sum(d, qdy, pg, qw, pw, other, act, out=None, ws=None):
+    """act > 0 ? dgrad + other : 0 (other may be None): the layer gradient of a residual block's first convolution
+    with the end of the block's backward pass in its epilogue.  Returns dx."""
+    _dev(qdy), _dev(qw), _dev(act)
+    shape = (d.N, d.C, d.H, d.W)
+    assert tuple(qdy.shape) == (d.N, d.K, d.P, d.Q) and tuple(qw.shape) == (d.K, d.C, d.R, d.S)
+    assert tuple(act.shape) == shape and act.dtype == torch.float32 and act.is_contiguous()
+    if other is not None:
+        _dev(other)
+        assert tuple(other.shape) == shape and other.dtype == torch.float32 and other.is_contiguous()
+    dx = out if out is not None else torch.empty(shape, dtype=torch.float32, device=qdy.device)
+    ws = ws if ws is not None else workspace(_lib.q8t_qconv_workspace_size(C.byref(d), 1), qdy.device)
+    _check(_lib.q8t_qconv_dgrad_relu_sum(C.byref(d), _ptr(qdy), _ptr(pg), _ptr(qw), _ptr(pw), _ptr(other), _ptr(act), _ptr(dx),
+                                         _ptr(ws), _stream()), "q8t_qconv_dgrad_relu_sum")
+    return dx
 
 
 def qconv_wgrad(d, qx, px, qdy16, pg16, want_acc=False, out=None, ws=None):

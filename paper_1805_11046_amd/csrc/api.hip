@@ -175,6 +175,26 @@ int q8t_qconv_dgrad(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qpar
     return q8t_generic_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, ws, (hipStream_t)stream);
 }
 
+int q8t_qconv_dgrad_relu_sum(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qparams *pg, const int8_t *qw,
+                             const q8t_qparams *pw, const float *other, const float *act, float *dx, void *ws, void *stream)
+{
+    if (!desc || !qdy || !pg || !qw || !pw || !act || !dx) return Q8T_ERR_NULL;
+    const int rc = q8t_conv_reduction_check(1, desc);
+    if (rc) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const Q8tReluSum rs = {other, act};
+    const bool al = q8t_aligned(other, 16) && q8t_aligned(act, 16) && q8t_aligned(dx, 16);
+    // The register-tile kernel of the large planes finishes the block's gradient in its epilogue.  Measured on the
+    // other kernels (stride-2 pairs, wide tiles on 14x14 / 7x7 planes): the two extra operands cost their exposed
+    // write-out more than the separate pass does, so those shapes, like every other one, run the product and then
+    // the plumbing pass in place.
+    if (al && !q8t_wide_conv_supported(1, desc, qdy, dx, nullptr) && q8t_fast_conv_supported(1, desc, qdy, qw, dx, nullptr))
+        return q8t_fast_conv(1, desc, qdy, pg, qw, pw, dx, nullptr, nullptr, ws, st, &rs);
+    const int r2 = q8t_qconv_dgrad(desc, qdy, pg, qw, pw, dx, nullptr, ws, stream);
+    if (r2) return r2;
+    return q8t_relu_bwd_sum(dx, other, act, (int64_t)desc->N * desc->C * desc->H * desc->W, dx, stream);
+}
+
 int q8t_qconv_wgrad(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams *px, const int16_t *qdy16,
                     const q8t_qparams *pg16, float *dw, int64_t *acc_out, void *ws, void *stream)
 {

@@ -142,7 +142,7 @@ struct Sched {
 // zero point:  A(b,p,q) = b*(H+1)*(W+1) + (p+1)*(W+1) + q.  A filter tap is then the constant
 // row offset dr*(W+1) + ds for every output position, borders included -- no per-lane masks.
 // WC > 0 fixes a square image size at compile time (cheap index arithmetic, immediate offsets).
-template <int TAPS, int WC, bool V16, bool STATS>
+template <int TAPS, int WC, bool V16, bool STATS, bool FUSE>
 __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__restrict__ x,
                                                               const int8_t *__restrict__ wpk,
                                                               const int *__restrict__ colsum,
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
                                                               const q8t_qparams *__restrict__ qpb,
                                                               const FastGeom g, const Sched sch,
                                                               float *__restrict__ y, int32_t *__restrict__ acc_out,
-                                                              ConvStat *__restrict__ bnpart)
+                                                              ConvStat *__restrict__ bnpart, const Q8tReluSum fuse)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     // per-channel statistics of this workgroup's outputs (integer accumulators: exact, order-free)
@@ -444,7 +444,58 @@ __global__ __launch_bounds__(kThreads, 4) void conv_s1_kernel(const int8_t *__re
             }
         }
         };
-        if (y && !acc_out) emit(std::true_type{});
+        // With the end of a residual block in the epilogue (relu_sum.h) the two extra operands of a store are loaded one
+        // store ahead: a load issued only where its value is needed would put a full memory latency in front of every store.
+        auto emit_fused = [&]() {
+            size_t ob[MT];
+            bool live[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int gr = g0 + (mt * kWaves + wave) * 16 + kb * 4;
+                live[mt] = gr < g1;
+                const uint32_t b = divc<PQC>((uint32_t)(live[mt] ? gr : 0), g.dPQ);
+                const uint32_t pos = (uint32_t)(live[mt] ? gr : 0) - b * PQ;
+                ob[mt] = (size_t)(b * g.K + occ * CH + l16) * PQ + pos;
+            }
+            float4 nx_o = make_float4(0.0f, 0.0f, 0.0f, 0.0f), nx_a = nx_o;
+            auto fetch = [&](size_t o) {
+                nx_a = *reinterpret_cast<const float4 *>(fuse.act + o);
+                if (fuse.other) nx_o = *reinterpret_cast<const float4 *>(fuse.other + o);
+            };
+            if (live[0]) fetch(ob[0]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                if (!live[mt]) continue;
+                uint32_t t[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) t[j] = kzz - (uint32_t)zb * (uint32_t)accrs[mt][j];
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) {
+                    const size_t o = ob[mt] + (size_t)(nt * 16) * PQ;
+                    const float4 cu_o = nx_o, cu_a = nx_a;
+                    if (nt < 3) fetch(o + (size_t)16 * PQ);
+                    else if (mt + 1 < MT && live[mt + 1 < MT ? mt + 1 : mt]) fetch(ob[mt + 1 < MT ? mt + 1 : mt]);
+                    float4 f;
+                    f.x = sc * (float)(int)((uint32_t)acc[mt][nt][0] + t[0] + ncs[nt]);
+                    f.y = sc * (float)(int)((uint32_t)acc[mt][nt][1] + t[1] + ncs[nt]);
+                    f.z = sc * (float)(int)((uint32_t)acc[mt][nt][2] + t[2] + ncs[nt]);
+                    f.w = sc * (float)(int)((uint32_t)acc[mt][nt][3] + t[3] + ncs[nt]);
+                    if (fuse.other) {
+                        f.x = f.x + cu_o.x;
+                        f.y = f.y + cu_o.y;
+                        f.z = f.z + cu_o.z;
+                        f.w = f.w + cu_o.w;
+                    }
+                    f.x = cu_a.x > 0.0f ? f.x : 0.0f;
+                    f.y = cu_a.y > 0.0f ? f.y : 0.0f;
+                    f.z = cu_a.z > 0.0f ? f.z : 0.0f;
+                    f.w = cu_a.w > 0.0f ? f.w : 0.0f;
+                    *reinterpret_cast<float4 *>(y + o) = f;
+                }
+            }
+        };
+        if (FUSE) emit_fused();
+        else if (y && !acc_out) emit(std::true_type{});
         else emit(std::false_type{});
     }
     if (STATS) {
@@ -564,25 +615,32 @@ size_t q8t_fast_conv_ws(int which, const q8t_conv_desc *d)
            (size_t)oc * 512 * sizeof(ConvStat);
 }
 
-template <int TAPS, int WC, bool V16, bool STATS>
+template <int TAPS, int WC, bool V16, bool STATS, bool FUSE>
 int launch_conv(dim3 grid, hipStream_t st, const int8_t *a, const int8_t *wpk, const int *colsum,
                 const q8t_qparams *qa, const q8t_qparams *qb, const FastGeom &g, const Sched &sch, float *out_f,
-                int32_t *out_acc, ConvStat *bnpart)
+                int32_t *out_acc, ConvStat *bnpart, const Q8tReluSum &fuse)
 {
     static Q8tLdsOptIn optin;
     if (smem_bytes<TAPS>() > 65536 &&
-        q8t_allow_lds(optin, (const void *)conv_s1_kernel<TAPS, WC, V16, STATS>, smem_bytes<TAPS>()) != Q8T_OK)
+        q8t_allow_lds(optin, (const void *)conv_s1_kernel<TAPS, WC, V16, STATS, FUSE>, smem_bytes<TAPS>()) != Q8T_OK)
         return Q8T_ERR_HIP;
-    hipLaunchKernelGGL((conv_s1_kernel<TAPS, WC, V16, STATS>), grid, dim3(kThreads), smem_bytes<TAPS>(), st, a, wpk, colsum, qa,
-                       qb, g, sch, out_f, out_acc, bnpart);
+    hipLaunchKernelGGL((conv_s1_kernel<TAPS, WC, V16, STATS, FUSE>), grid, dim3(kThreads), smem_bytes<TAPS>(), st, a, wpk, colsum, qa,
+                       qb, g, sch, out_f, out_acc, bnpart, fuse);
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
 }
 
 int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
-                  const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *ws, hipStream_t st)
+                  const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *ws, hipStream_t st,
+                  const Q8tReluSum *relu_sum)
 {
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    Q8tReluSum fuse = {nullptr, nullptr};
+    if (relu_sum) {
+        if (bn_stats || which != 1) return Q8T_ERR_SHAPE;
+        if (!out_f || !q8t_aligned(relu_sum->act, 16) || !q8t_aligned(relu_sum->other, 16)) return Q8T_ERR_SHAPE;
+        fuse = *relu_sum;
+    }
     const int taps = d->R * d->S;
     const size_t wbytes = (size_t)d->K * d->C * taps;
     const int oc_all = which == 0 ? d->K : d->C;
@@ -625,8 +683,9 @@ int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
     int32_t *pacc = (int32_t *)out_acc;
     const bool sq = d->H == d->W;
 #define Q8T_CONV(T, WCV, V)                                                                                        \
-    (bnpart ? launch_conv<T, WCV, V, true>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc, bnpart)         \
-            : launch_conv<T, WCV, V, false>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc, bnpart))
+    (bnpart ? launch_conv<T, WCV, V, true, false>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc, bnpart, fuse)      \
+            : (fuse.act ? launch_conv<T, WCV, V, false, true>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc, bnpart, fuse) \
+                        : launch_conv<T, WCV, V, false, false>(grid, st, pa, wpk, colsum, qa, qb, g, sch, out_f, pacc, bnpart, fuse)))
     if (taps == 9) {
         if (sq && d->W == 56 && v16) rc = Q8T_CONV(9, 56, true);
         else if (sq && d->W == 28 && v16) rc = Q8T_CONV(9, 28, true);

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include "q8t.h"
+#include "relu_sum.h"
 
 // general kernel (igemm_generic.hip).  which: 0 fwd, 1 dgrad, 2 wgrad.  For wgrad the 16-bit
 // operand is passed first (a, qa).
@@ -31,8 +32,11 @@ bool q8t_fast_conv_supported(int which, const q8t_conv_desc *d, const void *a, c
                              const void *out_acc);
 size_t q8t_fast_conv_ws(int which, const q8t_conv_desc *d);
 // bn_stats (nullable, forward only): [3][K] mean / min / max of the float result per output channel
+// relu_sum (nullable, layer gradient with a float result): the epilogue stores act > 0 ? result + other : 0
+// (relu_sum.h); act and other 16-byte aligned
 int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
-                  const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *ws, hipStream_t st);
+                  const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *ws, hipStream_t st,
+                  const Q8tReluSum *relu_sum = nullptr);
 
 // 3x3 stride-1 layers with many channels on small planes: 128 x 256 tiles, activations staged once per
 // 64-channel chunk, weights streamed (conv_wide.hip).  Same contract as q8t_fast_conv.

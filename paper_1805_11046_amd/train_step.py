@@ -223,8 +223,10 @@ def _chain_fwd(a, specs, ws, apply_last=True):
     return out, saved
 
 
-def _chain_bwd(saved, g, need_dx):
-    """backward of _chain_fwd: the ReLU mask is recomputed inside the Range BN backward"""
+def _chain_bwd(saved, g, need_dx, block_end=None):
+    """backward of _chain_fwd: the ReLU mask is recomputed inside the Range BN backward.  block_end = (other, act):
+    the chain is the main branch of a residual block; the layer gradient of its first convolution then also adds
+    the other branch's gradient and applies the mask of the block's input (act > 0) in its epilogue."""
     g = g.contiguous()
     dws = [None] * len(saved)
     for i in range(len(saved) - 1, -1, -1):
@@ -237,7 +239,11 @@ def _chain_bwd(saved, g, need_dx):
                         1e-5, 2 * lid + 1, 2 * lid + 2)
         g8, pg8, g16, pg16 = r[3:]
         g = None
-        if i > 0 or need_dx:
+        if i == 0 and block_end is not None:
+            other, act = block_end
+            g = _call("qconv_dgrad", ops, ny + (12 if other is not None else 8) * nx, q8t.qconv_dgrad_relu_sum, d, g8, pg8,
+                      qw, pw, other, act, tag=_tag(d))
+        elif i > 0 or need_dx:
             g, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d))
         dws[i], _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
     return g, dws
@@ -290,9 +296,12 @@ class ResBlock(torch.autograd.Function):
         chain, scs, a, out, grad_is_masked = ctx.saved
         g = g.contiguous()
         gm = g if grad_is_masked else _call("relu_bwd_add", 0, 12 * g.numel(), q8t.relu_bwd_add, g, out)
-        gc, (dw1, dw2) = _chain_bwd(chain, gm, True)
         gs, dwsc = (gm, None) if scs is None else _convbn_bwd(scs, gm, True)
-        ga = _call("relu_bwd_sum", 0, (16 if a is not None else 12) * gc.numel(), q8t.relu_bwd_sum, gc, gs, a)
+        if a is not None:
+            ga, (dw1, dw2) = _chain_bwd(chain, gm, True, (gs, a))
+        else:
+            gc, (dw1, dw2) = _chain_bwd(chain, gm, True)
+            ga = _call("relu_bwd_sum", 0, 12 * gc.numel(), q8t.relu_bwd_sum, gc, gs, None)
         return ga, None, None, None, None, dw1, dw2, dwsc
 
 

@@ -150,3 +150,39 @@ def test_range_bn_relu_backward_with_bifurcated_quantization(shape):
     same_qparams(q8t, qp16, o16)
     same_ints(host(q8), s8)
     same_ints(host(q16), s16)
+
+
+@pytest.mark.parametrize("case", [
+    (3, 64, 56, 56, 64, 3, 3, 1, 1),     # 3x3 stride 1 on 56x56 planes: the register-tile kernel's epilogue
+    (3, 128, 28, 28, 128, 3, 3, 1, 1),   # ... 28x28
+    (5, 256, 14, 14, 256, 3, 3, 1, 1),   # wide-tile kernel, aligned planes
+    (6, 512, 7, 7, 512, 3, 3, 1, 1),     # ... 7x7 planes: the transposed write-out
+    (3, 64, 28, 28, 128, 3, 3, 2, 1),    # stride 2: the two column classes of a row written as pairs
+    (2, 128, 14, 14, 256, 3, 3, 2, 1),
+    (2, 64, 15, 13, 64, 3, 3, 1, 1),     # odd plane: scalar stores
+    (2, 64, 14, 14, 128, 1, 1, 2, 0),    # shapes without the step in an epilogue: product, then the plumbing pass
+    (2, 24, 9, 9, 40, 3, 3, 1, 1),
+])
+@pytest.mark.parametrize("with_other", [True, False])
+def test_layer_gradient_with_the_end_of_the_block_in_its_epilogue(case, with_other):
+    # dx = act > 0 ? dgrad + other : 0 in one call: bit-identical to the two separate calls, and both against the oracle
+    q8t = require_gpu()
+    g = synth.rng(sum(case) + 3)
+    N, C, H, W, K, R, S, st, pad = case
+    od = oracle.conv_desc(*case)
+    sg, pg = _rand_q(g, (N, K, od.P, od.Q))
+    sw, pw = _rand_q(g, (K, C, R, S))
+    other = synth.normal(g, (N, C, H, W), std=3.0) if with_other else None
+    act = synth.normal(g, (N, C, H, W), std=1.0)
+    act[act < 0.3] = 0.0                       # a rectified tensor: many exact zeros
+    d = q8t.conv_desc(*case)
+    dpg, dpw = qp_dev_from(pg), qp_dev_from(pw)
+    od_dev = None if other is None else dev(other)
+    dx = q8t.qconv_dgrad_relu_sum(d, dev(sg), dpg, dev(sw), dpw, od_dev, dev(act))
+    plain, _ = q8t.qconv_dgrad(d, dev(sg), dpg, dev(sw), dpw)
+    ref = q8t.relu_bwd_sum(plain, od_dev, dev(act))
+    assert np.array_equal(host(dx), host(ref))
+    odx, _ = oracle.qconv_dgrad(od, sg, pg, sw, pw)
+    ores = oracle.relu_bwd_sum(odx, other, act)
+    close(host(dx), ores)
+    same_ints(host(dx) == 0, ores == 0)
