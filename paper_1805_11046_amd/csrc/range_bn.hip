@@ -19,6 +19,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kMaxSplit = 64;
+constexpr int kApplyBlocks = 4096;   // workgroups of the second pass of the fused backward (16 per compute unit)
 
 struct FwdPartial {
     double sum;
@@ -790,10 +791,19 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply(const float *__restric
     const Affine a8 = affine_of(qp8), a16 = affine_of(qp16);
     if (VEC && HW < 4 * kThreads) {
         // small planes: one float4 per thread over the flat tensor (a float4 never leaves its plane)
+        // The channel of a float4: the 64-bit division is done once per workgroup and sweep, on the index of the
+        // workgroup's first float4; a thread is at most kThreads float4s past it, which a float reciprocal
+        // resolves (as a 64-bit division and a modulo per thread this lookup cost as much as half the rounding work).
         const int hw4 = HW >> 2;
+        const float rhw4 = 1.0f / (float)hw4, rC = 1.0f / (float)C;
         const int64_t total4 = planes * hw4, stride = (int64_t)gridDim.x * kThreads;
-        for (int64_t i4 = (int64_t)blockIdx.x * kThreads + threadIdx.x; i4 < total4; i4 += stride) {
-            const int c = (int)((i4 / hw4) % C);
+        for (int64_t b4 = (int64_t)blockIdx.x * kThreads; b4 < total4; b4 += stride) {
+            const int64_t pl0 = b4 / hw4;                         // uniform in the workgroup
+            const int rem0 = (int)(b4 - pl0 * hw4), c0 = (int)(pl0 % C);
+            const int64_t i4 = b4 + threadIdx.x;
+            if (i4 >= total4) continue;
+            const int cc = c0 + q8t_pool::small_div(rem0 + (int)threadIdx.x, hw4, rhw4);   // < C + kThreads + 1
+            const int c = cc - q8t_pool::small_div(cc, C, rC) * C;
             const float mu = stats[c], mn = stats[C + c], mx = stats[2 * C + c];
             const float inv = bn_inv(mn, mx, cn, eps);
             const float g = gamma ? gamma[c] : 1.0f, be = beta ? beta[c] : 0.0f;
@@ -943,41 +953,71 @@ __global__ __launch_bounds__(kThreads) void bn_bwdq_apply_flat4(const float *__r
     }
     const Affine a8 = affine_of(qp8), a16 = affine_of(qp16);
     const int64_t stride = (int64_t)gridDim.x * kThreads;
-    for (int64_t i4 = (int64_t)blockIdx.x * kThreads + threadIdx.x; i4 < total4; i4 += stride) {
+    const float rHW = 1.0f / (float)HW, rC = 1.0f / (float)C;
+    const bool small = HW < (1 << 20) && C < (1 << 21);   // the float-reciprocal quotients below are exact in this range
+    for (int64_t b4 = (int64_t)blockIdx.x * kThreads; b4 < total4; b4 += stride) {
+        const int64_t i4 = b4 + threadIdx.x;
+        if (i4 >= total4) continue;
+        // plane and offset of the group's first element, channel of that plane and of the next one (HW >= 4: a group
+        // meets at most two planes).  One 64-bit division per workgroup and sweep; a thread is at most
+        // 4 * kThreads elements past the workgroup's first one.
+        int off0, ca, cb;
+        if (small) {
+            const int64_t plb = (4 * b4) / HW;                   // uniform in the workgroup
+            const int remb = (int)(4 * b4 - plb * HW), cbase = (int)(plb % C);
+            const int el = remb + 4 * (int)threadIdx.x;
+            const int dpl = q8t_pool::small_div(el, HW, rHW);
+            off0 = el - dpl * HW;
+            const int cc = cbase + dpl;
+            ca = cc - q8t_pool::small_div(cc, C, rC) * C;
+        } else {
+            const int64_t pl0 = (4 * i4) / HW;
+            off0 = (int)(4 * i4 - pl0 * HW);
+            ca = (int)(pl0 % C);
+        }
+        cb = ca + 1 == C ? 0 : ca + 1;
+        const bool two = off0 + 3 >= HW;                        // the group straddles two planes
         const float4 d4 = q8t_ld_last(reinterpret_cast<const float4 *>(dy) + i4);
         const float dv[4] = {d4.x, d4.y, d4.z, d4.w};
-        const int64_t pl0 = (4 * i4) / HW;             // plane of the group's first element
-        const int off0 = (int)(4 * i4 - pl0 * HW);
         float rv[4];
-        bool need_x = relu != 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int c = (int)((pl0 + (off0 + j >= HW ? 1 : 0)) % C);   // HW >= 4: a group meets at most two planes
-            need_x = need_x || !crowded || crowded[c];
-        }
+        const bool need_x = relu != 0 || !crowded || crowded[ca] || (two && crowded[cb]);
         float xv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         if (need_x) {
             const float4 x4 = q8t_ld_last(reinterpret_cast<const float4 *>(x) + i4);
             xv[0] = x4.x; xv[1] = x4.y; xv[2] = x4.z; xv[3] = x4.w;
         }
+        // per-channel constants of the first plane, and of the second one where the group straddles
+        struct Ch {
+            float mu, mn, mx, inv, g, be;
+            float2 k;
+            bool plain;   // not crowded: extremal coordinates come from the patch kernel, ordinary rule here
+        };
+        auto load = [&](int c) {
+            Ch h;
+            h.mu = stats[c];
+            h.mn = stats[C + c];
+            h.mx = stats[2 * C + c];
+            h.inv = bn_inv(h.mn, h.mx, cn, eps);
+            h.g = gamma ? gamma[c] : 1.0f;
+            h.be = beta ? beta[c] : 0.0f;
+            h.k = consts[c];
+            h.plain = crowded && !crowded[c];
+            return h;
+        };
+        const Ch ha = load(ca);
+        const Ch hb = two ? load(cb) : ha;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int c = (int)((pl0 + (off0 + j >= HW ? 1 : 0)) % C);
-            const float mn = stats[C + c], mx = stats[2 * C + c];
-            const float inv = bn_inv(mn, mx, cn, eps);
-            const float g = gamma ? gamma[c] : 1.0f;
-            const float2 k = consts[c];
+            const Ch &h = off0 + j >= HW ? hb : ha;
             if (need_x) {
                 float d = dv[j];
                 if (relu) {
-                    const float be = beta ? beta[c] : 0.0f;
-                    const float out = bn_map(xv[j], stats[c], inv, g, be);
+                    const float out = bn_map(xv[j], h.mu, h.inv, h.g, h.be);
                     d = out > 0.0f ? d : 0.0f;
                 }
-                // a channel that is not crowded gets its extremal coordinates from the patch kernel: ordinary rule here
-                rv[j] = (crowded && !crowded[c]) ? bn_dx_kind(d, g, k.x, inv, k.y, 0) : bn_dx(xv[j], d, g, k.x, inv, k.y, mn, mx);
+                rv[j] = h.plain ? bn_dx_kind(d, h.g, h.k.x, h.inv, h.k.y, 0) : bn_dx(xv[j], d, h.g, h.k.x, h.inv, h.k.y, h.mn, h.mx);
             } else {
-                rv[j] = bn_dx_kind(dv[j], g, k.x, inv, k.y, 0);
+                rv[j] = bn_dx_kind(dv[j], h.g, h.k.x, h.inv, h.k.y, 0);
             }
         }
         const float4 r = make_float4(rv[0], rv[1], rv[2], rv[3]);
@@ -1308,7 +1348,10 @@ static int range_bn_bwd_bifurcate_impl(const float *x, const float *dy, const fl
     if (vec) {
         // planes of at least 1024 positions: a workgroup per plane; smaller ones: a float4 per thread
         const int64_t blocks4 = (planes * (HW >> 2) + kThreads - 1) / kThreads;
-        const int64_t gridx = HW >= 4 * kThreads ? planes_grid(planes) : (blocks4 < 65536 * 16 ? blocks4 : 65536 * 16);
+        // at most kApplyBlocks workgroups, which sweep: every workgroup first folds the ranges of pass 1 and derives the
+        // two quantizers, and with one short-lived workgroup per 256 float4s that prologue cost a quarter of the pass
+        const int64_t gridx = HW >= 4 * kThreads ? (planes < kApplyBlocks ? planes : kApplyBlocks)
+                                                 : (blocks4 < kApplyBlocks ? blocks4 : kApplyBlocks);
         if (pooled)
             hipLaunchKernelGGL((bn_bwdq_apply<true, true>), dim3((unsigned)gridx), dim3(kThreads), pool_lds, st, x, dy, planes, C,
                                HW, stats, gamma, beta, relu, consts, cn, eps, s8l, s8h, s16l, s16h, mm, nmm, qp8_out, qp16_out, dx,
@@ -1330,7 +1373,7 @@ static int range_bn_bwd_bifurcate_impl(const float *x, const float *dy, const fl
         }
     } else if (flat4) {
         const int64_t blocks4 = (total / 4 + kThreads - 1) / kThreads;
-        hipLaunchKernelGGL(bn_bwdq_apply_flat4, dim3((unsigned)(blocks4 < 65536 * 16 ? blocks4 : 65536 * 16)), dim3(kThreads), 0, st,
+        hipLaunchKernelGGL(bn_bwdq_apply_flat4, dim3((unsigned)(blocks4 < kApplyBlocks ? blocks4 : kApplyBlocks)), dim3(kThreads), 0, st,
                            x, dy, total / 4, C, HW, stats, gamma, beta, relu, consts, cn, eps, s8l, s8h, s16l, s16h, mm, nmm,
                            qp8_out, qp16_out, dx, q8_out, q16_out, crowded);
         if (nox) {
