@@ -705,18 +705,21 @@ __global__ __launch_bounds__(kThreads) void wgrad_s1_3x3_v2(const int16_t *__res
 
 // int64 reduction over the k-ranges for wgrad_s1_3x3_v2: the column sum depends on the vertical tap,
 // the row sums on the horizontal one.
+// A thread owns four neighbouring accumulator entries (four input channels of one output channel and tap) and walks
+// its share of the ranges with 16-byte loads; the wavefronts of a workgroup take interleaved subsets of the ranges
+// and fold through LDS.
 constexpr int RQ2 = 16;   // most interleaved subsets of the k-ranges per workgroup (one wavefront each)
 __global__ __launch_bounds__(64 * RQ2) void wgrad_reduce_v2(const int *__restrict__ partial, WGeom g,
                                                        const q8t_qparams *__restrict__ qpg,
                                                        const q8t_qparams *__restrict__ qpx, float *__restrict__ dw,
                                                        int64_t *__restrict__ acc_out)
 {
-    __shared__ int64_t fold[RQ2][64];
+    __shared__ int64_t fold[RQ2][4][64];
     const int sub = blockIdx.y;
     const int cg = sub % g.ncg, rg = sub / g.ncg;
-    const int lane = threadIdx.x & 63, quarter = threadIdx.x >> 6;
-    const int idx = blockIdx.x * 64 + lane;   // (((mt*2 + ct)*9 + tap)*4 + j)*64 + lane, < 18432
-    const int j = (idx >> 6) & 3, t2 = idx >> 8;
+    const int ln = threadIdx.x & 63, quarter = threadIdx.x >> 6, nq = blockDim.x >> 6;
+    const int idx = (blockIdx.x * 64 + ln) * 4;   // (((mt*2 + ct)*9 + tap)*4 + j)*64 + lane, < 9216 (a multiple of 256)
+    const int lane = idx & 63, j = (idx >> 6) & 3, t2 = idx >> 8;
     const int tap = t2 % 9, ct = (t2 / 9) & 1, mt = t2 / 18;
     const int r = tap / 3, s = tap - 3 * r;
     const int row_l = mt * 16 + (lane >> 4) * 4 + j, ch_l = ct * 16 + (lane & 15);
@@ -724,26 +727,36 @@ __global__ __launch_bounds__(64 * RQ2) void wgrad_reduce_v2(const int *__restric
     const int zsg = qpg->zero_point - (1 << (qpg->bits - 1)), zsx = qpx->zero_point - (1 << (qpx->bits - 1));
     const int64_t ca = 128 - zsg;
     const int ksteps_img = (g.Lp + 63) / 64;
-    int64_t v = 0;
-    const int nq = blockDim.x >> 6;
+    int64_t v[4] = {0, 0, 0, 0};
+#pragma unroll 4
     for (int kr = quarter; kr < g.S; kr += nq) {
         const int *p = partial + ((int64_t)(kr * g.nrg + rg) * g.ncg + cg) * PART2_INTS;
         const int nimg = min(g.N, (kr + 1) * g.ipr) - kr * g.ipr;
         const int64_t Kp = (int64_t)nimg * ksteps_img * 64;
-        const int64_t hi = p[idx], lo = p[TILE2_INTS / 2 + idx];
-        const int64_t csv = p[TILE2_INTS + r * CH2 + ch_l];
+        const v4i hi = *reinterpret_cast<const v4i *>(p + idx), lo = *reinterpret_cast<const v4i *>(p + TILE2_INTS / 2 + idx);
+        const v4i csv = *reinterpret_cast<const v4i *>(p + TILE2_INTS + r * CH2 + ch_l);
         const int64_t rsh = p[TILE2_INTS + 3 * CH2 + s * 64 + row_l], rsl = p[TILE2_INTS + 3 * CH2 + (3 + s) * 64 + row_l];
-        v += 256 * hi + lo + ca * csv - (int64_t)zsx * (256 * rsh + rsl + ca * Kp);
+        const int64_t common = (int64_t)zsx * (256 * rsh + rsl + ca * Kp);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] += 256 * (int64_t)hi[e] + (int64_t)lo[e] + ca * (int64_t)csv[e] - common;
     }
-    fold[quarter][lane] = v;
-    __syncthreads();
-    if (quarter == 0) {
-        v = 0;
-        for (int q = 0; q < nq; ++q) v += fold[q][lane];
-        const double sc = (double)(qpg->scale * qpx->scale);
-        const int64_t o = ((int64_t)(rg * 64 + row_l) * g.C + cg * CH2 + ch_l) * 9 + tap;
-        if (acc_out) acc_out[o] = v;
-        if (dw) dw[o] = (float)((double)v * sc);
+    if (nq > 1) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) fold[quarter][e][ln] = v[e];
+        __syncthreads();
+        if (quarter != 0) return;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v[e] = 0;
+            for (int q = 0; q < nq; ++q) v[e] += fold[q][e][ln];
+        }
+    }
+    const double sc = (double)(qpg->scale * qpx->scale);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int64_t o = ((int64_t)(rg * 64 + row_l) * g.C + cg * CH2 + ch_l + e) * 9 + tap;
+        if (acc_out) acc_out[o] = v[e];
+        if (dw) dw[o] = (float)((double)v[e] * sc);
     }
 }
 
@@ -830,8 +843,10 @@ int q8t_fast_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams
         const int rc2 = d->W == 56 ? launch_wgrad_v2<56>(blocks, st, g16, x, qg, qx, g, (int *)ws)
                                    : launch_wgrad_v2<28>(blocks, st, g16, x, qg, qx, g, (int *)ws);
         if (rc2) return rc2;
-        hipLaunchKernelGGL(wgrad_reduce_v2, dim3(TILE2_INTS / 2 / 64, per), dim3(g.S >= 64 ? 64 * RQ2 : 256), 0, st, (const int *)ws, g, qg,
-                           qx, dw, acc_out);
+        int nq = 1;   // wavefronts per workgroup: each walks two ranges or more (measured best: 16 wavefronts of one range each spend their time starting up)
+        while (nq < RQ2 && g.S >= 4 * nq) nq *= 2;
+        hipLaunchKernelGGL(wgrad_reduce_v2, dim3(TILE2_INTS / 2 / 256, per), dim3(64 * nq), 0, st, (const int *)ws, g, qg, qx, dw,
+                           acc_out);
         Q8T_LAUNCH_CHECK();
         return Q8T_OK;
     }

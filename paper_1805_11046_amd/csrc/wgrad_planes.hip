@@ -408,20 +408,24 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
 // a = 256*hi + lo + (128 - zg) the gradient level minus its zero point and b = x - zx:
 //   sum a*b = 256*sum(hi*x) + sum(lo*x) + (128 - zg)*colsum(x) - zx*(256*rowsum(hi) + rowsum(lo) + (128 - zg)*Kp)
 // over the Kp padded positions of the range (pads contribute a = 0 and b = 0).
-constexpr int RQ = 16;   // interleaved subsets of the image ranges per workgroup (one wavefront each)
+// A thread owns four neighbouring accumulator entries (four input channels of one output channel and tap) and walks
+// its share of the image ranges with 16-byte loads, several ranges in flight; the wavefronts of a workgroup take
+// interleaved subsets of the ranges and fold through LDS.  (One entry per thread and one range per wavefront, the
+// first form of this kernel, spent most of its time starting workgroups: 31 -> 18 us for 256 -> 256 @14 at batch 256.)
+constexpr int kFinishMaxQ = 16;
 template <class SH>
-__global__ __launch_bounds__(64 * RQ) void wgrad_planes_finish(const int *__restrict__ partial, PGeom g,
-                                                              const q8t_qparams *__restrict__ qpg,
-                                                              const q8t_qparams *__restrict__ qpx,
-                                                              float *__restrict__ dw, int64_t *__restrict__ acc_out)
+__global__ __launch_bounds__(64 * kFinishMaxQ) void wgrad_planes_finish(const int *__restrict__ partial, PGeom g,
+                                                                       const q8t_qparams *__restrict__ qpg,
+                                                                       const q8t_qparams *__restrict__ qpx,
+                                                                       float *__restrict__ dw, int64_t *__restrict__ acc_out)
 {
-    __shared__ int64_t fold[RQ][64];
+    __shared__ int64_t fold[kFinishMaxQ][4][64];
     constexpr int TAPS = SH::TAPS, NBV = SH::NBV;
     const int sub = blockIdx.y;
     const int cg = sub % g.ncg, rg = sub / g.ncg;
-    const int lane = threadIdx.x & 63, quarter = threadIdx.x >> 6;
-    const int idx = blockIdx.x * 64 + lane;   // ((((kt*2 + ch)*TAPS + tap)*16 + reg)*64 + lane
-    const int reg = (idx >> 6) & 15, rest = idx >> 10;
+    const int ln = threadIdx.x & 63, quarter = threadIdx.x >> 6, nq = blockDim.x >> 6;
+    const int idx = (blockIdx.x * 64 + ln) * 4;   // ((((kt*2 + ch)*TAPS + tap)*16 + reg)*64 + lane; HALF_INTS is a multiple of 256
+    const int lane = idx & 63, reg = (idx >> 6) & 15, rest = idx >> 10;
     const int tap = rest % TAPS, ch = (rest / TAPS) & 1, kt = rest / (2 * TAPS);
     // 32x32 accumulator tile: lane = column + 32 * ((row / 4) % 2), register = 4 * (row / 8) + row % 4
     const int row_l = kt * 32 + 8 * (reg >> 2) + 4 * (lane >> 5) + (reg & 3), ch_l = ch * 32 + (lane & 31);
@@ -429,26 +433,36 @@ __global__ __launch_bounds__(64 * RQ) void wgrad_planes_finish(const int *__rest
 
     const int zsg = qpg->zero_point - (1 << (qpg->bits - 1)), zsx = qpx->zero_point - (1 << (qpx->bits - 1));
     const int64_t ca = 128 - zsg;
-    int64_t v = 0;
-    const int nq = blockDim.x >> 6;
+    int64_t v[4] = {0, 0, 0, 0};
+#pragma unroll 4
     for (int kr = quarter; kr < g.S; kr += nq) {
         const int *p = partial + ((int64_t)(kr * g.nrg + rg) * g.ncg + cg) * SH::PART_INTS;
         const int nimg = min(g.N, (kr + 1) * g.ipr) - kr * g.ipr;
         const int64_t Kp = (int64_t)((nimg + SH::NIMG - 1) / SH::NIMG) * KC;
-        const int64_t hi = p[idx], lo = p[SH::HALF_INTS + idx];
-        const int64_t csv = p[SH::TILE_INTS + bv * CT + ch_l];
+        const v4i hi = *reinterpret_cast<const v4i *>(p + idx), lo = *reinterpret_cast<const v4i *>(p + SH::HALF_INTS + idx);
+        const v4i csv = *reinterpret_cast<const v4i *>(p + SH::TILE_INTS + bv * CT + ch_l);
         const int64_t rsh = p[SH::TILE_INTS + NBV * CT + row_l], rsl = p[SH::TILE_INTS + NBV * CT + KT + row_l];
-        v += 256 * hi + lo + ca * csv - (int64_t)zsx * (256 * rsh + rsl + ca * Kp);
+        const int64_t common = (int64_t)zsx * (256 * rsh + rsl + ca * Kp);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] += 256 * (int64_t)hi[j] + (int64_t)lo[j] + ca * (int64_t)csv[j] - common;
     }
-    fold[quarter][lane] = v;
-    __syncthreads();
-    if (quarter == 0) {
-        v = 0;
-        for (int q = 0; q < nq; ++q) v += fold[q][lane];
-        const double sc = (double)(qpg->scale * qpx->scale);
-        const int64_t o = ((int64_t)(rg * KT + row_l) * g.C + cg * CT + ch_l) * TAPS + tap;
-        if (acc_out) acc_out[o] = v;
-        if (dw) dw[o] = (float)((double)v * sc);
+    if (nq > 1) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fold[quarter][j][ln] = v[j];
+        __syncthreads();
+        if (quarter != 0) return;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            v[j] = 0;
+            for (int q = 0; q < nq; ++q) v[j] += fold[q][j][ln];
+        }
+    }
+    const double sc = (double)(qpg->scale * qpx->scale);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int64_t o = ((int64_t)(rg * KT + row_l) * g.C + cg * CT + ch_l + j) * TAPS + tap;
+        if (acc_out) acc_out[o] = v[j];
+        if (dw) dw[o] = (float)((double)v[j] * sc);
     }
 }
 
@@ -491,8 +505,11 @@ int launch_planes(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams 
     if (q8t_allow_lds(optin, (const void *)wgrad_planes<SH>, SH::SMEM) != Q8T_OK) return Q8T_ERR_HIP;
     hipLaunchKernelGGL(wgrad_planes<SH>, dim3(blocks), dim3(kThreads), SH::SMEM, st, g16, x, qg, qx, g, (int *)ws);
     Q8T_LAUNCH_CHECK();
-    hipLaunchKernelGGL(wgrad_planes_finish<SH>, dim3(SH::HALF_INTS / 64, per), dim3(g.S >= 16 ? 64 * RQ : 256), 0, st,
-                       (const int *)ws, g, qg, qx, dw, acc_out);
+    // wavefronts per workgroup: each walks two ranges or more (measured best: 16 wavefronts of one range each spend their time starting up)
+    int nq = 1;
+    while (nq < kFinishMaxQ && g.S >= 4 * nq) nq *= 2;
+    hipLaunchKernelGGL(wgrad_planes_finish<SH>, dim3(SH::HALF_INTS / 256, per), dim3(64 * nq), 0, st, (const int *)ws, g, qg, qx,
+                       dw, acc_out);
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
 }
