@@ -337,6 +337,12 @@ int q8t_tern_wgrad_multi(const float *g, const int8_t *a_codes, int M, int N, in
  *   directly and need x, gpool, idx 16-byte aligned (q8_out 4, q16_out 8), else Q8T_ERR_SHAPE; for every other
  *   shape the unpooled gradient goes through the workspace.  ws:
  *   q8t_maxpool_range_bn_bwd_bifurcate_workspace_size bytes, 16-byte aligned.
+ * q8t_relu_bwd_sum_lattice: q8t_relu_bwd_sum where the second gradient is that of a tensor read at every
+ *   stride-th row and column only (the input of a 1x1 convolution with that stride and no padding: its layer
+ *   gradient is the stride-1 product on the sampled positions and zero elsewhere): g1, out, res [N,C,H,W],
+ *   g2s [N,C,ceil(H/stride),ceil(W/stride)]; res = out > 0 ? g1 + t : 0 with t = g2s[h/stride][w/stride] where h
+ *   and w are multiples of stride, else 0; bit-identical to the plain call with the zero-filled gradient, which
+ *   then never has to be written or read (out nullable: no mask).
  * q8t_add_relu_quantize: out = relu(a + b) (n floats each) and, if q_out != NULL, its 8-bit codes
  *   and parameters exactly as q8t_quantize(out, n, 8, 0, ...) would give them: the first pass leaves
  *   the maximum behind (the minimum of the rectified sum, widened to contain 0, is 0), so only the
@@ -370,6 +376,8 @@ int q8t_range_bn_add_relu_quantize(const float *x, const float *stats, const flo
                                    q8t_qparams *qp_out, void *ws, void *stream);
 int q8t_relu_bwd_add(const float *g, const float *out, const float *other, int64_t n, float *res, void *stream);
 int q8t_relu_bwd_sum(const float *g1, const float *g2, const float *out, int64_t n, float *res, void *stream);
+int q8t_relu_bwd_sum_lattice(const float *g1, const float *g2s, const float *out, int N, int C, int H, int W, int stride,
+                             float *res, void *stream);
 
 /* Measurement aid, not a step of the method: a plain streaming kernel of known traffic with the access
  * shape of the library's HBM-bound calls (every workgroup streams one contiguous slice, four 16-byte

@@ -442,6 +442,16 @@ def relu_bwd_sum(g1, g2=None, out=None):
     return res
 
 
+def relu_bwd_sum_lattice(g1, g2s, out, stride):
+    g1, g2s = _f32(g1), _f32(g2s)
+    out = _opt_f32(out)
+    N, Cc, H, W = g1.shape
+    assert g2s.shape == (N, Cc, (H + stride - 1) // stride, (W + stride - 1) // stride)
+    res = np.empty(g1.shape, np.float32)
+    lib().orc_relu_bwd_sum_lattice(_p(g1), _p(g2s), _p(out), N, Cc, H, W, int(stride), _p(res))
+    return res
+
+
 def relu_bwd_add(g, out, other=None):
     g, out = _f32(g), _f32(out)
     other = _opt_f32(other)

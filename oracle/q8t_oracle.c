@@ -985,6 +985,23 @@ void orc_relu_bwd_sum(const float *g1, const float *g2, const float *out, int64_
     }
 }
 
+/* the same where the second gradient lives on a lattice: g2s [N,C,ceil(H/s),ceil(W/s)] is the gradient of a tensor
+ * that was read at every s-th row and column only (a 1x1 convolution with stride s and no padding), so it reaches
+ * position (h, w) of the [N,C,H,W] tensor only where h and w are multiples of s; elsewhere 0 is added */
+void orc_relu_bwd_sum_lattice(const float *g1, const float *g2s, const float *out, int N, int C, int H, int W, int s,
+                              float *res)
+{
+    const int Hs = (H + s - 1) / s, Ws = (W + s - 1) / s;
+    for (int64_t pl = 0; pl < (int64_t)N * C; ++pl)
+        for (int h = 0; h < H; ++h)
+            for (int w = 0; w < W; ++w) {
+                const int64_t i = (pl * H + h) * W + w;
+                const float t = (h % s == 0 && w % s == 0) ? g2s[(pl * Hs + h / s) * Ws + w / s] : 0.0f;
+                const float sum = g1[i] + t;
+                res[i] = (!out || out[i] > 0.0f) ? sum : 0.0f;
+            }
+}
+
 /* backward of out = relu(.): g passes where out > 0; with `other` (nullable) added to it */
 void orc_relu_bwd_add(const float *g, const float *out, const float *other, int64_t n, float *res)
 {

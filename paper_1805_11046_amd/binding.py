@@ -91,6 +91,7 @@ _SIGS = {
     "q8t_range_bn_add_relu_quantize": (_i, [_vp] * 8 + [_i, _i, _i, _i, _f, _vp, _vp, _vp, _vp, _vp]),
     "q8t_relu_bwd_add": (_i, [_vp, _vp, _vp, _i64, _vp, _vp]),
     "q8t_relu_bwd_sum": (_i, [_vp, _vp, _vp, _i64, _vp, _vp]),
+    "q8t_relu_bwd_sum_lattice": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _i, _vp, _vp]),
     "q8t_ternarize_workspace_size": (_sz, [_i64]),
     "q8t_ternarize": (_i, [_vp, _i64, _u64, _vp, _vp, _vp, _vp]),
     "q8t_binarize": (_i, [_vp, _i64, _vp, _vp]),
@@ -627,6 +628,17 @@ def relu_bwd_sum(g1, g2=None, out=None):
     _dev(g1)
     res = torch.empty_like(g1)
     _check(_lib.q8t_relu_bwd_sum(_ptr(g1), _ptr(g2), _ptr(out), g1.numel(), _ptr(res), _stream()), "q8t_relu_bwd_sum")
+    return res
+
+
+def relu_bwd_sum_lattice(g1, g2s, out, stride):
+    """out > 0 ? g1 + t : 0, t = g2s on the lattice of rows / columns that are multiples of stride, 0 elsewhere."""
+    _dev(g1), _dev(g2s)
+    N, Cc, H, W = g1.shape
+    assert tuple(g2s.shape) == (N, Cc, (H + stride - 1) // stride, (W + stride - 1) // stride)
+    res = torch.empty_like(g1)
+    _check(_lib.q8t_relu_bwd_sum_lattice(_ptr(g1), _ptr(g2s), _ptr(out), N, Cc, H, W, int(stride), _ptr(res), _stream()),
+           "q8t_relu_bwd_sum_lattice")
     return res
 
 

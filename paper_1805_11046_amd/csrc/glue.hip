@@ -274,6 +274,69 @@ __global__ __launch_bounds__(kThreads) void bn_add_relu_fwd(const float *__restr
     if (threadIdx.x == 0) partials[blockIdx.x] = make_float2(0.0f, mx);
 }
 
+// res = out > 0 ? g1 + t : 0 with t = g2s at the positions whose row and column are even (stride 2: the lattice a
+// 1x1 / stride-2 convolution reads), 0 elsewhere; the addition is performed everywhere (x + 0 is not x for x = -0), so
+// the result is bit-identical to the plain sum with the zero-filled gradient.  A wavefront per plane and sweep.
+// ROWS4: W is a multiple of 4, so a float4 stays inside an image row; otherwise only the plane is a multiple of 4.
+template <bool ROWS4>
+__global__ __launch_bounds__(kThreads) void relu_bwd_sum_lattice2(const float *__restrict__ g1, const float *__restrict__ g2s,
+                                                                  const float *__restrict__ outv, int64_t planes, int H, int W,
+                                                                  int Hs, int Ws, float *__restrict__ res)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6, nw = (int64_t)gridDim.x * (kThreads / 64);
+    const int hw4 = (H * W) >> 2, W4 = W >> 2;
+    const float rW4 = 1.0f / (float)(W4 > 0 ? W4 : 1), rW = 1.0f / (float)W;
+    for (int64_t pl = wave; pl < planes; pl += nw) {
+        const float4 *a4 = reinterpret_cast<const float4 *>(g1) + pl * hw4;
+        const float4 *o4 = reinterpret_cast<const float4 *>(outv) + pl * hw4;
+        float4 *r4 = reinterpret_cast<float4 *>(res) + pl * hw4;
+        const float *sp = g2s + pl * (int64_t)Hs * Ws;
+        for (int i = lane; i < hw4; i += 64) {
+            float4 r = q8t_ld_last(a4 + i);
+            float4 t = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (ROWS4) {
+                const int h = small_div(i, W4, rW4), w0 = 4 * (i - h * W4);
+                if (!(h & 1)) {
+                    const float2 p = *reinterpret_cast<const float2 *>(sp + (h >> 1) * Ws + (w0 >> 1));
+                    t.x = p.x;
+                    t.z = p.y;
+                }
+            } else {
+                float tv[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int e = 4 * i + j, h = small_div(e, W, rW), w = e - h * W;
+                    tv[j] = (!(h & 1) && !(w & 1)) ? sp[(h >> 1) * Ws + (w >> 1)] : 0.0f;
+                }
+                t = make_float4(tv[0], tv[1], tv[2], tv[3]);
+            }
+            r.x = r.x + t.x; r.y = r.y + t.y; r.z = r.z + t.z; r.w = r.w + t.w;
+            if (outv) {
+                const float4 v = q8t_ld_last(o4 + i);
+                r.x = v.x > 0.0f ? r.x : 0.0f; r.y = v.y > 0.0f ? r.y : 0.0f;
+                r.z = v.z > 0.0f ? r.z : 0.0f; r.w = v.w > 0.0f ? r.w : 0.0f;
+            }
+            r4[i] = r;
+        }
+    }
+}
+
+// any stride and shape, one element per thread and sweep
+__global__ __launch_bounds__(kThreads) void relu_bwd_sum_lattice_any(const float *__restrict__ g1, const float *__restrict__ g2s,
+                                                                     const float *__restrict__ outv, int64_t n, int H, int W,
+                                                                     int Hs, int Ws, int s, float *__restrict__ res)
+{
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += stride) {
+        const int64_t row = i / W, pl = row / H;
+        const int w = (int)(i - row * W), h = (int)(row - pl * H);
+        const float t = (h % s == 0 && w % s == 0) ? g2s[(pl * Hs + h / s) * Ws + w / s] : 0.0f;
+        const float sum = g1[i] + t;
+        res[i] = (!outv || outv[i] > 0.0f) ? sum : 0.0f;
+    }
+}
+
 // res = out > 0 ? g1 + g2 : 0 (out nullable: no mask; g2 nullable: nothing added)
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void relu_bwd_sum(const float *__restrict__ g1, const float *__restrict__ g2,
@@ -472,6 +535,33 @@ int q8t_relu_bwd_sum(const float *g1, const float *g2, const float *out, int64_t
         hipLaunchKernelGGL(relu_bwd_sum<true>, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, g1, g2, out, n, res);
     else
         hipLaunchKernelGGL(relu_bwd_sum<false>, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, g1, g2, out, n, res);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}
+
+int q8t_relu_bwd_sum_lattice(const float *g1, const float *g2s, const float *out, int N, int C, int H, int W, int stride,
+                             float *res, void *stream)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || stride < 1) return Q8T_ERR_SHAPE;
+    const int64_t planes = (int64_t)N * C, n = planes * H * W;
+    if (n > kMaxElements || (int64_t)H * W >= (1 << 22)) return Q8T_ERR_SHAPE;
+    if (!g1 || !g2s || !res) return Q8T_ERR_NULL;
+    const int Hs = (H + stride - 1) / stride, Ws = (W + stride - 1) / stride;
+    hipStream_t st = (hipStream_t)stream;
+    const bool vec = stride == 2 && (H * W) % 4 == 0 && W % 2 == 0 && H % 2 == 0 && q8t_aligned(g1, 16) && q8t_aligned(g2s, 16) &&
+                     q8t_aligned(out, 16) && q8t_aligned(res, 16);
+    if (vec) {
+        // a wavefront per plane and sweep
+        const int64_t wgs = (planes + kThreads / 64 - 1) / (kThreads / 64);
+        const dim3 grid((unsigned)(wgs < 4096 ? wgs : 4096));
+        if (W % 4 == 0)
+            hipLaunchKernelGGL(relu_bwd_sum_lattice2<true>, grid, dim3(kThreads), 0, st, g1, g2s, out, planes, H, W, Hs, Ws, res);
+        else
+            hipLaunchKernelGGL(relu_bwd_sum_lattice2<false>, grid, dim3(kThreads), 0, st, g1, g2s, out, planes, H, W, Hs, Ws, res);
+    } else {
+        const int grid = grid_for(n, 4, 4096);
+        hipLaunchKernelGGL(relu_bwd_sum_lattice_any, dim3(grid), dim3(kThreads), 0, st, g1, g2s, out, n, H, W, Hs, Ws, stride, res);
+    }
     Q8T_LAUNCH_CHECK();
     return Q8T_OK;
 }

@@ -128,13 +128,18 @@ def _convbn_fwd(a, w, stride, pad, apply=True):
     return bn, saved
 
 
-def _convbn_bwd(saved, dbn, need_dx):
-    """Range BN backward + bifurcated gradient quantization -> layer gradient, weight gradient"""
+def _convbn_bwd(saved, dbn, need_dx, lattice=False):
+    """Range BN backward + bifurcated gradient quantization -> layer gradient, weight gradient.  lattice: for a 1x1
+    layer with a stride and no padding the layer gradient is returned on the positions the layer read (the stride-1
+    product at the reduced resolution; it is zero everywhere else), for q8t.relu_bwd_sum_lattice"""
     d, qa, pa, qw, pw, y, stats, ops, nx, ny, lid = saved
     _, _, _, g8, pg8, g16, pg16 = _bn_bwd(q8t.range_bn_bwd_bifurcate, "range_bn_bwd_bifurcate", ny, y, dbn.contiguous(),
                                           stats, None, 1e-5, 2 * lid + 1, 2 * lid + 2)
     dx = None
-    if need_dx:
+    if need_dx and lattice:
+        ds = q8t.conv_desc(d.N, d.C, d.P, d.Q, d.K, 1, 1, 1, 0)
+        dx, _ = _call("qconv_dgrad", ops, ny + 4 * (nx // (d.stride * d.stride)), q8t.qconv_dgrad, ds, g8, pg8, qw, pw, tag=_tag(d))
+    elif need_dx:
         dx, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d))
     dw, _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
     return dx, dw
@@ -296,6 +301,13 @@ class ResBlock(torch.autograd.Function):
         chain, scs, a, out, grad_is_masked = ctx.saved
         g = g.contiguous()
         gm = g if grad_is_masked else _call("relu_bwd_add", 0, 12 * g.numel(), q8t.relu_bwd_add, g, out)
+        stride = chain[0][0].stride
+        if scs is not None and a is not None and stride > 1:
+            # the shortcut's gradient stays on the lattice its 1x1 layer read: no zero-filled tensor is written or read
+            gs, dwsc = _convbn_bwd(scs, gm, True, lattice=True)
+            gc, (dw1, dw2) = _chain_bwd(chain, gm, True)
+            ga = _call("relu_bwd_sum", 0, 12 * gc.numel() + 4 * gs.numel(), q8t.relu_bwd_sum_lattice, gc, gs, a, stride)
+            return ga, None, None, None, None, dw1, dw2, dwsc
         gs, dwsc = (gm, None) if scs is None else _convbn_bwd(scs, gm, True)
         if a is not None:
             ga, (dw1, dw2) = _chain_bwd(chain, gm, True, (gs, a))

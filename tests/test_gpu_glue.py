@@ -129,3 +129,24 @@ def test_stem_backward_from_the_pooled_gradient(shape, want_q8):
     assert bits == 16
     dec = (host(q16).astype(np.float64) + 32768 - zero_point) * scale
     assert np.max(np.abs(dec - odx)) <= 1.001 * scale + 1e-5 * np.max(np.abs(odx))
+
+
+@pytest.mark.parametrize("shape,stride", [((2, 3, 8, 12), 2), ((3, 64, 56, 56), 2), ((5, 16, 28, 28), 2), ((2, 4, 14, 14), 2),
+                                          ((1, 2, 7, 9), 2), ((2, 2, 9, 10), 3), ((1, 1, 4, 4), 1)])
+@pytest.mark.parametrize("masked", [True, False])
+def test_sum_with_a_gradient_on_the_lattice_of_a_strided_1x1_layer(shape, stride, masked):
+    q8t = require_gpu()
+    g = synth.rng(sum(shape) + stride)
+    N, C, H, W = shape
+    g1 = synth.normal(g, shape, std=1.0)
+    g1[0, 0, 0, :2] = -0.0                      # x + 0 is not x for x = -0: the addition happens everywhere
+    g2s = synth.normal(g, (N, C, (H + stride - 1) // stride, (W + stride - 1) // stride), std=1.0)
+    out = np.maximum(synth.normal(g, shape, std=1.0), 0).astype(np.float32) if masked else None
+    od = None if out is None else dev(out)
+    res = q8t.relu_bwd_sum_lattice(dev(g1), dev(g2s), od, stride)
+    exp = oracle.relu_bwd_sum_lattice(g1, g2s, out, stride)
+    same_ints(host(res).view(np.int32), exp.view(np.int32))
+    full = np.zeros(shape, np.float32)
+    full[:, :, ::stride, ::stride] = g2s
+    plain = q8t.relu_bwd_sum(dev(g1), dev(full), od)
+    assert np.array_equal(host(res).view(np.int32), host(plain).view(np.int32))

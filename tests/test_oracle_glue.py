@@ -1,6 +1,7 @@
 """Pins for the oracle's network plumbing (pooling behind the first Range BN + ReLU, residual add +
 ReLU): against torch's CPU routines.  CPU only."""
 import numpy as np
+import pytest
 import torch
 import torch.nn.functional as F
 
@@ -63,6 +64,26 @@ def test_add_relu_and_its_backward():
     assert np.allclose(oracle.relu_bwd_sum(g, o, out), t.grad.numpy(), rtol=1e-6, atol=1e-7)
     z, mz = oracle.add_relu(-np.abs(a), -np.abs(b))
     assert not z.any() and mz == 0
+
+
+@pytest.mark.parametrize("shape,stride", [((2, 3, 8, 12), 2), ((1, 2, 7, 9), 2), ((2, 2, 9, 10), 3), ((1, 1, 4, 4), 1)])
+def test_sum_with_a_gradient_that_lives_on_a_lattice(shape, stride):
+    # the gradient of a tensor that a 1x1 / stride-s convolution read: zero off the lattice.  Pinned against the
+    # plain sum with the zero-filled tensor written out, and against torch's backward of x[..., ::s, ::s]
+    N, Cc, H, W = shape
+    g1, out = _data(31, shape), np.maximum(_data(32, shape), 0)
+    sub = (N, Cc, (H + stride - 1) // stride, (W + stride - 1) // stride)
+    g2s = _data(33, sub)
+    full = np.zeros(shape, np.float32)
+    full[:, :, ::stride, ::stride] = g2s
+    got = oracle.relu_bwd_sum_lattice(g1, g2s, out, stride)
+    assert np.array_equal(got, oracle.relu_bwd_sum(g1, full, out))
+    assert np.array_equal(oracle.relu_bwd_sum_lattice(g1, g2s, None, stride), g1 + full)
+    t = torch.from_numpy(_data(34, shape)).requires_grad_(True)
+    r = torch.relu(t)
+    ((r * torch.from_numpy(g1)).sum() + (r[:, :, ::stride, ::stride] * torch.from_numpy(g2s)).sum()).backward()
+    mine = oracle.relu_bwd_sum_lattice(g1, g2s, r.detach().numpy(), stride)
+    assert np.allclose(mine, t.grad.numpy(), rtol=1e-6, atol=1e-7)
 
 
 def test_block_tail_in_one_pass_equals_its_pieces_and_torch():
