@@ -43,6 +43,21 @@ size_t stats_in_epilogue_ws(const q8t_conv_desc *d)
     return f > s ? f : s;
 }
 
+// A 1x1 convolution with a stride and no padding is the stride-1 layer on the positions it reads: where the
+// register-tile kernel takes that reduced shape, the forward product gathers those codes into the workspace
+// (a quarter of the operand at stride 2) and runs there, instead of rewriting the whole operand channel-contiguous
+// for the general strided path.
+bool lattice_forward(const q8t_conv_desc *d, q8t_conv_desc *sub)
+{
+    if (d->R != 1 || d->S != 1 || d->pad != 0 || d->stride < 2 || d->H < 1 || d->W < 1) return false;
+    *sub = *d;
+    sub->H = (d->H - 1) / d->stride + 1;
+    sub->W = (d->W - 1) / d->stride + 1;
+    sub->stride = 1;
+    return q8t_fast_conv_ws(0, sub) != 0;   // the shape is one the register-tile kernel takes
+}
+size_t lattice_codes_bytes(const q8t_conv_desc *sub) { return ((size_t)sub->N * sub->C * sub->H * sub->W + 255) & ~(size_t)255; }
+
 }  // namespace
 
 extern "C" {
@@ -98,6 +113,11 @@ size_t q8t_qconv_workspace_size(const q8t_conv_desc *desc, int which)
     size_t h = which < 2 ? q8t_nhwc_conv_ws(which, desc) : (wgrad_wants_gemm(desc) ? q8t_gemm_wgrad_ws(desc) : 0);
     if (smallc_wanted(which, desc)) h = q8t_smallc_conv_ws(which, desc);
     if (which == 0 && q8t_first_conv_ws(desc) > h) h = q8t_first_conv_ws(desc);
+    q8t_conv_desc sub;
+    if (which == 0 && lattice_forward(desc, &sub)) {
+        const size_t l = lattice_codes_bytes(&sub) + q8t_fast_conv_ws(0, &sub);
+        if (l > h) h = l;
+    }
     if (h > g) g = h;
     return g > f ? g : f;
 }
@@ -108,6 +128,16 @@ int q8t_qconv_fwd(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams
     if (!desc || !qx || !px || !qw || !pw || (!y && !acc_out)) return Q8T_ERR_NULL;
     const int rc = q8t_conv_reduction_check(0, desc);
     if (rc) return rc;
+    q8t_conv_desc sub;
+    if (lattice_forward(desc, &sub) && ws && q8t_aligned(ws, 16)) {
+        int8_t *codes = (int8_t *)ws;
+        void *ws2 = (char *)ws + lattice_codes_bytes(&sub);
+        if (q8t_fast_conv_supported(0, &sub, codes, qw, y, acc_out)) {
+            const int rs = q8t_subsample_codes(qx, desc->N, desc->C, desc->H, desc->W, desc->stride, codes, (hipStream_t)stream);
+            if (rs) return rs;
+            return q8t_fast_conv(0, &sub, codes, px, qw, pw, y, acc_out, nullptr, ws2, (hipStream_t)stream);
+        }
+    }
     if (q8t_wide_conv_supported(0, desc, qx, y, acc_out))
         return q8t_wide_conv(0, desc, qx, px, qw, pw, y, acc_out, nullptr, ws, (hipStream_t)stream);
     if (q8t_fast_conv_supported(0, desc, qx, qw, y, acc_out))
@@ -140,6 +170,16 @@ int q8t_qconv_fwd_bn_stats(const q8t_conv_desc *desc, const int8_t *qx, const q8
     const int rc = q8t_conv_reduction_check(0, desc);
     if (rc) return rc;
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    q8t_conv_desc sub;
+    if (lattice_forward(desc, &sub)) {
+        int8_t *codes = (int8_t *)ws;
+        void *ws2 = (char *)ws + lattice_codes_bytes(&sub);
+        if (q8t_fast_conv_supported(0, &sub, codes, qw, y, acc_out)) {
+            const int rs = q8t_subsample_codes(qx, desc->N, desc->C, desc->H, desc->W, desc->stride, codes, (hipStream_t)stream);
+            if (rs) return rs;
+            return q8t_fast_conv(0, &sub, codes, px, qw, pw, y, acc_out, stats_out, ws2, (hipStream_t)stream);
+        }
+    }
     // the specialised kernel gathers the statistics in its epilogue; other shapes run the product
     // and then the statistics pass of the Range BN over its result
     if (q8t_wide_conv_supported(0, desc, qx, y, acc_out))

@@ -274,6 +274,35 @@ __global__ __launch_bounds__(kThreads) void bn_add_relu_fwd(const float *__restr
     if (threadIdx.x == 0) partials[blockIdx.x] = make_float2(0.0f, mx);
 }
 
+// out[pl][p][q] = x[pl][p * s][q * s] for 8-bit codes: the operand of a 1x1 convolution with stride s and no padding,
+// which is the stride-1 layer on these positions.  PAIRS (s = 2, Q a multiple of 4, rows 8-byte aligned): a thread turns
+// 8 input bytes into 4 output bytes with one byte permute.
+template <bool PAIRS>
+__global__ __launch_bounds__(kThreads) void subsample_codes(const int8_t *__restrict__ x, int64_t planes, int H, int W, int P,
+                                                            int Q, int s, int8_t *__restrict__ out)
+{
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    if (PAIRS) {
+        const int Q4 = Q >> 2;
+        const int64_t total = planes * P * Q4;
+        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+            const int64_t row = i / Q4;                       // (plane, p)
+            const int q4 = (int)(i - row * Q4);
+            const int64_t pl = row / P;
+            const int p = (int)(row - pl * P);
+            const uint2 v = *reinterpret_cast<const uint2 *>(x + (pl * H + 2 * p) * W + 8 * q4);
+            reinterpret_cast<uint32_t *>(out)[i] = __builtin_amdgcn_perm(v.y, v.x, 0x06040200);   // bytes 0, 2, 4, 6
+        }
+    } else {
+        const int64_t total = planes * P * Q;
+        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += stride) {
+            const int64_t row = i / Q, pl = row / P;
+            const int q = (int)(i - row * Q), p = (int)(row - pl * P);
+            out[i] = x[(pl * H + (int64_t)p * s) * W + (int64_t)q * s];
+        }
+    }
+}
+
 // res = out > 0 ? g1 + t : 0 with t = g2s at the positions whose row and column are even (stride 2: the lattice a
 // 1x1 / stride-2 convolution reads), 0 elsewhere; the addition is performed everywhere (x + 0 is not x for x = -0), so
 // the result is bit-identical to the plain sum with the zero-filled gradient.  A wavefront per plane and sweep.
@@ -581,3 +610,18 @@ int q8t_relu_bwd_add(const float *g, const float *out, const float *other, int64
 }
 
 }  // extern "C"
+
+int q8t_subsample_codes(const int8_t *x, int N, int C, int H, int W, int s, int8_t *out, hipStream_t st)
+{
+    const int P = (H - 1) / s + 1, Q = (W - 1) / s + 1;
+    const int64_t planes = (int64_t)N * C;
+    const bool pairs = s == 2 && W % 8 == 0 && q8t_aligned(x, 8) && q8t_aligned(out, 4);   // then Q = W / 2 is a multiple of 4
+    if (pairs)
+        hipLaunchKernelGGL(subsample_codes<true>, dim3(grid_for(planes * P * (Q >> 2), 4, 4096)), dim3(kThreads), 0, st, x, planes,
+                           H, W, P, Q, s, out);
+    else
+        hipLaunchKernelGGL(subsample_codes<false>, dim3(grid_for(planes * P * Q, 4, 4096)), dim3(kThreads), 0, st, x, planes, H, W,
+                           P, Q, s, out);
+    Q8T_LAUNCH_CHECK();
+    return Q8T_OK;
+}

@@ -98,6 +98,10 @@ size_t q8t_planes_wgrad_ws(const q8t_conv_desc *d);
 int q8t_planes_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qparams *qg, const int8_t *x,
                      const q8t_qparams *qx, float *dw, int64_t *acc_out, void *ws, hipStream_t st);
 
+// glue.hip: out [N,C,P,Q] = x[.., p*s, q*s] of 8-bit codes, P = (H-1)/s + 1, Q = (W-1)/s + 1 (the operand of a 1x1
+// convolution with stride s and no padding, which is the stride-1 layer on these positions)
+int q8t_subsample_codes(const int8_t *x, int N, int C, int H, int W, int s, int8_t *out, hipStream_t st);
+
 // quantize.hip: nearest 8-bit quantization of x with the range given as npairs (<= 1024) float2 (min, max) pairs
 int q8t_quantize8_from_partials(const float *x, int64_t n, const void *minmax_pairs, int npairs, int8_t *q_out,
                                 q8t_qparams *qp_out, hipStream_t st);

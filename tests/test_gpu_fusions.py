@@ -20,7 +20,9 @@ CASES = [
     (2, 64, 16, 16, 128, 3, 3, 2, 1),    # strided: statistics from the epilogue of the implicit-GEMM kernel
     (5, 64, 28, 28, 128, 3, 3, 2, 1),    # ragged last row tile
     (3, 128, 14, 14, 256, 3, 3, 2, 1),   # 256-channel tiles
-    (7, 64, 28, 28, 128, 1, 1, 2, 0),    # 1x1 projection at stride 2
+    (7, 64, 28, 28, 128, 1, 1, 2, 0),    # 1x1 projection at stride 2 (runs as the stride-1 layer on the gathered positions)
+    (3, 128, 56, 56, 64, 1, 1, 2, 0),    # ... on large planes
+    (5, 64, 14, 14, 128, 1, 1, 2, 0),    # ... 7x7 result planes: the general strided path
     (11, 256, 7, 7, 512, 3, 3, 1, 1),    # 7x7 planes
     (3, 128, 15, 13, 64, 3, 3, 1, 1),    # odd plane at stride 1
     (6, 3, 64, 64, 64, 7, 7, 2, 3),      # first layer: statistics from the fused small-channel kernel

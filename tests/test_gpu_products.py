@@ -170,6 +170,10 @@ CONV_CASES = [
     (2, 1, 12, 16, 64, 3, 8, 1, 0),      # one channel, rows of 8 taps, no padding (a single K-step)
     (2, 6, 40, 40, 64, 5, 3, 1, 1),      # 30 groups (four K-steps), 40 positions per row: a ragged last tile
     (1, 3, 224, 224, 64, 7, 7, 2, 3),    # the first layer of a ResNet at its real plane size
+    # 1x1 with a stride, no padding: forward as the stride-1 layer on the gathered positions
+    (3, 64, 56, 56, 128, 1, 1, 2, 0),    # rows of a multiple of 8 codes: gathered with byte permutes
+    (2, 64, 20, 12, 64, 1, 1, 2, 0),     # ... scalar gather
+    (2, 64, 17, 29, 128, 1, 1, 3, 0),    # stride 3, sizes that are no multiples of it (6 x 10 positions)
 ]
 
 
