@@ -173,6 +173,36 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
             xa[s][q / 2] = pk;
         }
     static_assert(CT * ROWP <= 32768, "bit 15 of a packed input offset is the row parity");
+    // 7x7 planes: a 16-byte piece of the contiguous tile covers parts of three image rows at byte granularity, which made
+    // staging (a byte store per value) cost as much as the MFMAs.  There a thread stages whole image rows instead: the
+    // 7 values of a row and the value before them (or, for the first row of a plane, the value behind them, shifted
+    // in registers) are one unaligned 16-byte (gradient) or 8-byte (input) global load, the value before the row
+    // becomes the pad, and a padded row goes to LDS as one aligned 8-byte store per byte plane.
+    constexpr bool ROWG = P == 7 && STRIDE == 1, ROWX = ROWG;   // (at stride 2 the row tasks cost registers and gained nothing)
+    constexpr int GROWS = KT * P * NIMG, XROWS = CT * P * NIMG;
+    constexpr int GT = ROWG ? (GROWS + kThreads - 1) / kThreads : 1, XT = ROWX ? (XROWS + kThreads - 1) / kThreads : 1;
+    static_assert(!ROWG || (GT <= NIMG * GS && XT <= NIMG * XS), "the row tasks reuse the registers of the pieces");
+    int rg_off[GT], rg_lds[GT], rx_off[XT], rx_lds[XT];   // byte offset in the image's tile (-1: no task) / in the LDS region
+    int rg_img[GT], rx_img[XT];
+    bool rg_first[GT], rx_first[XT];
+#pragma unroll
+    for (int s2 = 0; s2 < GT; ++s2) {
+        const int t = tid + s2 * kThreads, tt = t < GROWS ? t : 0;
+        const int m = tt / (KT * P), rr = tt - m * (KT * P), k = rr / P, r = rr - k * P;
+        rg_img[s2] = m;
+        rg_first[s2] = r == 0;
+        rg_off[s2] = ROWG && t < GROWS ? (k * PP + r * P) * 2 - (r ? 2 : 0) : -1;
+        rg_lds[s2] = m * PL + k * ROWP + LEFT + r * PT;
+    }
+#pragma unroll
+    for (int s2 = 0; s2 < XT; ++s2) {
+        const int t = tid + s2 * kThreads, tt = t < XROWS ? t : 0;
+        const int m = tt / (CT * P), rr = tt - m * (CT * P), c = rr / P, r = rr - c * P;
+        rx_img[s2] = m;
+        rx_first[s2] = r == 0;
+        rx_off[s2] = ROWX && t < XROWS ? c * WW + r * P - (r ? 1 : 0) : -1;
+        rx_lds[s2] = m * PL + c * ROWP + LEFT + r * PT;
+    }
     const bool g_last = tid + kThreads * (GS - 1) < G_U4, x_last = tid + kThreads * (XS - 1) < X_U4;
 
     const int img0 = kr * g.ipr, img1 = min(g.N, img0 + g.ipr);
@@ -199,8 +229,30 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
     // used.  Every index stays inside the tile of an image of the range.
     const int g_lastoff = g_last ? tid + (GS - 1) * kThreads : 0, x_lastoff = x_last ? tid + (XS - 1) * kThreads : 0;
     auto load_part = [&](int part) {
+        if constexpr (ROWG) {
 #pragma unroll
-        for (int i = 0; i < NIMG * GS; ++i)
+            for (int i = 0; i < GT; ++i)
+                if (i % NPART == part) {
+                    const bool have = rg_off[i] >= 0 && (rg_img[i] == 0 || l_img + rg_img[i] < img1);
+                    uint4 v = make_uint4(a_pad, a_pad, a_pad, a_pad);
+                    if (have)
+                        __builtin_memcpy(&v, reinterpret_cast<const uint8_t *>(gsrc) + rg_img[i] * gstep * 16 + rg_off[i], 16);
+                    rgr[i] = v;
+                }
+        }
+        if constexpr (ROWX) {
+#pragma unroll
+            for (int i = 0; i < XT; ++i)
+                if ((i + 2) % NPART == part) {
+                    const bool have = rx_off[i] >= 0 && (rx_img[i] == 0 || l_img + rx_img[i] < img1);
+                    uint2 v = make_uint2(b_pad, b_pad);
+                    if (have)
+                        __builtin_memcpy(&v, reinterpret_cast<const uint8_t *>(xsrc) + rx_img[i] * xstep * 16 + rx_off[i], 8);
+                    rxr[i] = make_uint4(v.x, v.y, 0u, 0u);
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < (ROWG ? 0 : NIMG * GS); ++i)
             if (i % NPART == part) {
                 const int m = i / GS, sl = i % GS;
                 const bool have = m == 0 || l_img + m < img1;
@@ -208,7 +260,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
                 rgr[i] = have ? v : make_uint4(a_pad, a_pad, a_pad, a_pad);
             }
 #pragma unroll
-        for (int i = 0; i < NIMG * XS; ++i)
+        for (int i = 0; i < (ROWX ? 0 : NIMG * XS); ++i)
             if ((i + 2) % NPART == part) {
                 const int m = i / XS, sl = i % XS;
                 const bool have = m == 0 || l_img + m < img1;
@@ -268,13 +320,38 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
             }
         }
     };
+    auto abu = [](uint32_t hi, uint32_t lo, int n) { return __builtin_amdgcn_alignbyte(hi, lo, n); };
     auto write_part = [&](int buf, int part) {
         uint8_t *A = smem + buf * SH::BUF, *B = A + SH::A_BYTES;
+        if constexpr (ROWG) {
 #pragma unroll
-        for (int i = 0; i < NIMG * GS; ++i)
+            for (int i = 0; i < GT; ++i)
+                if (i % NPART == part && rg_off[i] >= 0) {
+                    uint4 w = rgr[i];
+                    if (rg_first[i]) w = make_uint4(w.x << 16, abu(w.y, w.x, 2), abu(w.z, w.y, 2), abu(w.w, w.z, 2));
+                    w.x = (w.x & 0xFFFF0000u) | (a_pad & 0xFFFFu);          // the value before the row is the pad
+                    const uint32_t d0 = w.x ^ 0x00800080u, d1 = w.y ^ 0x00800080u, d2 = w.z ^ 0x00800080u, d3 = w.w ^ 0x00800080u;
+                    *reinterpret_cast<uint2 *>(A + rg_lds[i]) =
+                        make_uint2(__builtin_amdgcn_perm(d1, d0, 0x07050301u), __builtin_amdgcn_perm(d3, d2, 0x07050301u));
+                    *reinterpret_cast<uint2 *>(A + rg_lds[i] + KT * ROWP) =
+                        make_uint2(__builtin_amdgcn_perm(d1, d0, 0x06040200u), __builtin_amdgcn_perm(d3, d2, 0x06040200u));
+                }
+        }
+        if constexpr (ROWX) {
+#pragma unroll
+            for (int i = 0; i < XT; ++i)
+                if ((i + 2) % NPART == part && rx_off[i] >= 0) {
+                    uint2 w = make_uint2(rxr[i].x, rxr[i].y);
+                    if (rx_first[i]) w = make_uint2(w.x << 8, abu(w.y, w.x, 3));
+                    w.x = (w.x & 0xFFFFFF00u) | (b_pad & 0xFFu);
+                    *reinterpret_cast<uint2 *>(B + rx_lds[i]) = w;
+                }
+        }
+#pragma unroll
+        for (int i = 0; i < (ROWG ? 0 : NIMG * GS); ++i)
             if (i % NPART == part) write_g(A, i / GS, i % GS);
 #pragma unroll
-        for (int i = 0; i < NIMG * XS; ++i)
+        for (int i = 0; i < (ROWX ? 0 : NIMG * XS); ++i)
             if ((i + 2) % NPART == part) write_x(B, i / XS, i % XS);
     };
     auto ab = [](int hi, int lo, int n) { return (int)__builtin_amdgcn_alignbyte((uint32_t)hi, (uint32_t)lo, n); };
@@ -527,9 +604,6 @@ bool q8t_planes_wgrad_supported(const q8t_conv_desc *d, const void *g16, const v
 {
     const int P = planes_edge(d);
     if (!P) return false;
-    // 7x7 planes at stride 1 (byte-granular staging of both operands) are faster as byte planes +
-    // im2col rows + GEMM once the batch is large; the kernel stays available for them below that
-    if (P == 7 && d->stride == 1 && (int64_t)d->N * d->K * d->C >= ((int64_t)1 << 24)) return false;
     return q8t_aligned(g16, 16) && q8t_aligned(x, 16) && q8t_aligned(dw, 4) && q8t_aligned(acc, 8);
 }
 
