@@ -93,6 +93,11 @@ struct Shape {
 
 __device__ __forceinline__ int dot4_ones(int v, int acc) { return __builtin_amdgcn_sdot4(v, 0x01010101, acc, false); }
 
+// gradient staged by image rows (see the kernel): everywhere but on 7x7 planes at stride 2, where the row tasks cost
+// registers and gained nothing
+template <int P, int STRIDE>
+constexpr bool kRowG = !(P == 7 && STRIDE == 2);
+
 template <class SH>
 __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restrict__ g16, const int8_t *__restrict__ x,
                                                          const q8t_qparams *__restrict__ qpg,
@@ -173,15 +178,18 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
             xa[s][q / 2] = pk;
         }
     static_assert(CT * ROWP <= 32768, "bit 15 of a packed input offset is the row parity");
-    // 7x7 planes: a 16-byte piece of the contiguous tile covers parts of three image rows at byte granularity, which made
-    // staging (a byte store per value) cost as much as the MFMAs.  There a thread stages whole image rows instead: the
-    // 7 values of a row and the value before them (or, for the first row of a plane, the value behind them, shifted
-    // in registers) are one unaligned 16-byte (gradient) or 8-byte (input) global load, the value before the row
-    // becomes the pad, and a padded row goes to LDS as one aligned 8-byte store per byte plane.
-    constexpr bool ROWG = P == 7 && STRIDE == 1, ROWX = ROWG;   // (at stride 2 the row tasks cost registers and gained nothing)
+    // Staging by image rows: a 16-byte piece of the contiguous tile covers parts of several image rows at byte (7x7) or
+    // 2-byte (14x14) granularity, which made staging (a narrow LDS store per value or pair) cost as much as the MFMAs.
+    // Here a thread stages whole image rows instead: the P values of a row and the LEADC values before them (for the
+    // first row of a plane: the values behind them, shifted in registers) are one or two unaligned global loads of a
+    // padded row's size, the values before the row become the pads, and a padded row goes to LDS as one aligned 8- or
+    // 16-byte store per byte plane.
+    constexpr bool ROWG = kRowG<P, STRIDE>, ROWX = STRIDE == 1;
     constexpr int GROWS = KT * P * NIMG, XROWS = CT * P * NIMG;
     constexpr int GT = ROWG ? (GROWS + kThreads - 1) / kThreads : 1, XT = ROWX ? (XROWS + kThreads - 1) / kThreads : 1;
-    static_assert(!ROWG || (GT <= NIMG * GS && XT <= NIMG * XS), "the row tasks reuse the registers of the pieces");
+    constexpr int GW = PT / 8;      // 16-byte pieces of a padded gradient row (2 * PT bytes), = of a padded input row times two
+    static_assert(!ROWG || GT * GW <= NIMG * GS, "the row tasks reuse the registers of the pieces");
+    static_assert(!ROWX || XT <= NIMG * XS, "the row tasks reuse the registers of the pieces");
     int rg_off[GT], rg_lds[GT], rx_off[XT], rx_lds[XT];   // byte offset in the image's tile (-1: no task) / in the LDS region
     int rg_img[GT], rx_img[XT];
     bool rg_first[GT], rx_first[XT];
@@ -191,7 +199,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
         const int m = tt / (KT * P), rr = tt - m * (KT * P), k = rr / P, r = rr - k * P;
         rg_img[s2] = m;
         rg_first[s2] = r == 0;
-        rg_off[s2] = ROWG && t < GROWS ? (k * PP + r * P) * 2 - (r ? 2 : 0) : -1;
+        rg_off[s2] = ROWG && t < GROWS ? (k * PP + r * P - (r ? SH::LEADC : 0)) * 2 : -1;
         rg_lds[s2] = m * PL + k * ROWP + LEFT + r * PT;
     }
 #pragma unroll
@@ -200,7 +208,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
         const int m = tt / (CT * P), rr = tt - m * (CT * P), c = rr / P, r = rr - c * P;
         rx_img[s2] = m;
         rx_first[s2] = r == 0;
-        rx_off[s2] = ROWX && t < XROWS ? c * WW + r * P - (r ? 1 : 0) : -1;
+        rx_off[s2] = ROWX && t < XROWS ? c * WW + r * P - (r ? SH::LEADC : 0) : -1;
         rx_lds[s2] = m * PL + c * ROWP + LEFT + r * PT;
     }
     const bool g_last = tid + kThreads * (GS - 1) < G_U4, x_last = tid + kThreads * (XS - 1) < X_U4;
@@ -234,10 +242,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
             for (int i = 0; i < GT; ++i)
                 if (i % NPART == part) {
                     const bool have = rg_off[i] >= 0 && (rg_img[i] == 0 || l_img + rg_img[i] < img1);
-                    uint4 v = make_uint4(a_pad, a_pad, a_pad, a_pad);
-                    if (have)
-                        __builtin_memcpy(&v, reinterpret_cast<const uint8_t *>(gsrc) + rg_img[i] * gstep * 16 + rg_off[i], 16);
-                    rgr[i] = v;
+                    const uint8_t *src = reinterpret_cast<const uint8_t *>(gsrc) + rg_img[i] * gstep * 16 + (have ? rg_off[i] : 0);
+#pragma unroll
+                    for (int w = 0; w < GW; ++w) {
+                        uint4 v = make_uint4(a_pad, a_pad, a_pad, a_pad);
+                        if (have) __builtin_memcpy(&v, src + 16 * w, 16);
+                        rgr[i * GW + w] = v;
+                    }
                 }
         }
         if constexpr (ROWX) {
@@ -245,10 +256,19 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
             for (int i = 0; i < XT; ++i)
                 if ((i + 2) % NPART == part) {
                     const bool have = rx_off[i] >= 0 && (rx_img[i] == 0 || l_img + rx_img[i] < img1);
-                    uint2 v = make_uint2(b_pad, b_pad);
-                    if (have)
-                        __builtin_memcpy(&v, reinterpret_cast<const uint8_t *>(xsrc) + rx_img[i] * xstep * 16 + rx_off[i], 8);
-                    rxr[i] = make_uint4(v.x, v.y, 0u, 0u);
+                    const uint8_t *src = reinterpret_cast<const uint8_t *>(xsrc) + rx_img[i] * xstep * 16 + (have ? rx_off[i] : 0);
+                    uint4 v = make_uint4(b_pad, b_pad, b_pad, b_pad);
+                    if (have) {
+                        if (PT == 16) {
+                            __builtin_memcpy(&v, src, 16);
+                        } else {
+                            uint2 h;
+                            __builtin_memcpy(&h, src, 8);
+                            v.x = h.x;
+                            v.y = h.y;
+                        }
+                    }
+                    rxr[i] = v;
                 }
         }
 #pragma unroll
@@ -327,24 +347,50 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
 #pragma unroll
             for (int i = 0; i < GT; ++i)
                 if (i % NPART == part && rg_off[i] >= 0) {
-                    uint4 w = rgr[i];
-                    if (rg_first[i]) w = make_uint4(w.x << 16, abu(w.y, w.x, 2), abu(w.z, w.y, 2), abu(w.w, w.z, 2));
-                    w.x = (w.x & 0xFFFF0000u) | (a_pad & 0xFFFFu);          // the value before the row is the pad
-                    const uint32_t d0 = w.x ^ 0x00800080u, d1 = w.y ^ 0x00800080u, d2 = w.z ^ 0x00800080u, d3 = w.w ^ 0x00800080u;
-                    *reinterpret_cast<uint2 *>(A + rg_lds[i]) =
-                        make_uint2(__builtin_amdgcn_perm(d1, d0, 0x07050301u), __builtin_amdgcn_perm(d3, d2, 0x07050301u));
-                    *reinterpret_cast<uint2 *>(A + rg_lds[i] + KT * ROWP) =
-                        make_uint2(__builtin_amdgcn_perm(d1, d0, 0x06040200u), __builtin_amdgcn_perm(d3, d2, 0x06040200u));
+                    uint32_t w[4 * GW];   // a padded row: LEADC pad values, then the P values of the row
+#pragma unroll
+                    for (int q = 0; q < GW; ++q) {
+                        w[4 * q] = rgr[i * GW + q].x;
+                        w[4 * q + 1] = rgr[i * GW + q].y;
+                        w[4 * q + 2] = rgr[i * GW + q].z;
+                        w[4 * q + 3] = rgr[i * GW + q].w;
+                    }
+                    if (rg_first[i]) {   // loaded from the row's own start: move up by LEADC values
+#pragma unroll
+                        for (int q = 4 * GW - 1; q > 0; --q) w[q] = SH::LEADC == 2 ? w[q - 1] : abu(w[q], w[q - 1], 2);
+                        if (SH::LEADC == 1) w[0] = w[0] << 16;
+                    }
+                    w[0] = SH::LEADC == 2 ? a_pad : (w[0] & 0xFFFF0000u) | (a_pad & 0xFFFFu);
+                    uint32_t hi[2 * GW], lo[2 * GW];
+#pragma unroll
+                    for (int q = 0; q < 2 * GW; ++q) {
+                        const uint32_t d0 = w[2 * q] ^ 0x00800080u, d1 = w[2 * q + 1] ^ 0x00800080u;
+                        hi[q] = __builtin_amdgcn_perm(d1, d0, 0x07050301u);
+                        lo[q] = __builtin_amdgcn_perm(d1, d0, 0x06040200u);
+                    }
+                    if (GW == 2) {
+                        *reinterpret_cast<uint4 *>(A + rg_lds[i]) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+                        *reinterpret_cast<uint4 *>(A + rg_lds[i] + KT * ROWP) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                    } else {
+                        *reinterpret_cast<uint2 *>(A + rg_lds[i]) = make_uint2(hi[0], hi[1]);
+                        *reinterpret_cast<uint2 *>(A + rg_lds[i] + KT * ROWP) = make_uint2(lo[0], lo[1]);
+                    }
                 }
         }
         if constexpr (ROWX) {
 #pragma unroll
             for (int i = 0; i < XT; ++i)
                 if ((i + 2) % NPART == part && rx_off[i] >= 0) {
-                    uint2 w = make_uint2(rxr[i].x, rxr[i].y);
-                    if (rx_first[i]) w = make_uint2(w.x << 8, abu(w.y, w.x, 3));
-                    w.x = (w.x & 0xFFFFFF00u) | (b_pad & 0xFFu);
-                    *reinterpret_cast<uint2 *>(B + rx_lds[i]) = w;
+                    uint32_t w[4] = {rxr[i].x, rxr[i].y, rxr[i].z, rxr[i].w};
+                    constexpr int NW = PT / 4;   // dwords of a padded input row
+                    if (rx_first[i]) {   // move up by LEADC bytes
+#pragma unroll
+                        for (int q = NW - 1; q > 0; --q) w[q] = abu(w[q], w[q - 1], 4 - SH::LEADC);
+                        w[0] = w[0] << (8 * SH::LEADC);
+                    }
+                    w[0] = SH::LEADC == 2 ? (w[0] & 0xFFFF0000u) | (b_pad & 0xFFFFu) : (w[0] & 0xFFFFFF00u) | (b_pad & 0xFFu);
+                    if (NW == 4) *reinterpret_cast<uint4 *>(B + rx_lds[i]) = make_uint4(w[0], w[1], w[2], w[3]);
+                    else *reinterpret_cast<uint2 *>(B + rx_lds[i]) = make_uint2(w[0], w[1]);
                 }
         }
 #pragma unroll
