@@ -333,6 +333,11 @@ def _conv(fn, name, d, a, pa, b, pb, out_shape, which, acc_dtype, want_acc, out,
     return y, acc
 
 
+def qconv_workspace_size(d, which):
+    """Bytes of workspace q8t_qconv_fwd (0) / dgrad (1) / wgrad (2) need for this layer."""
+    return int(_lib.q8t_qconv_workspace_size(C.byref(d), int(which)))
+
+
 def qconv_fwd(d, qx, px, qw, pw, want_acc=False, out=None, ws=None):
     _dev(qx), _dev(qw)
     assert tuple(qx.shape) == (d.N, d.C, d.H, d.W) and tuple(qw.shape) == (d.K, d.C, d.R, d.S)

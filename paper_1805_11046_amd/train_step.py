@@ -100,6 +100,42 @@ def _bn_bwd(fn, name, ny, *args):
     return r
 
 
+_overlap = False     # weight gradients on a second stream (see _wgrad)
+_side = {}           # device index -> [stream, workspace]
+
+
+def _wgrad(d, qa, pa, g16, pg16, ops, nx, ny):
+    """The weight gradient of a layer.  Nothing downstream of it is needed before the optimizer, so with
+    `_overlap` it is issued on a second stream (default priority) with a workspace of its own and runs beside the
+    Range BN passes and layer gradients of the layers below it, which are bound by memory and vector arithmetic where
+    this product is bound by the matrix units and LDS; step() joins the stream at its end."""
+    if not _overlap:
+        return _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))[0]
+    dev = g16.device
+    main = torch.cuda.current_stream(dev)
+    ent = _side.get(dev.index)
+    if ent is None:
+        ent = _side[dev.index] = [torch.cuda.Stream(dev), None]
+    side = ent[0]
+    side.wait_stream(main)          # the codes were written on the main stream
+    need = q8t.qconv_workspace_size(d, 2)
+    with torch.cuda.stream(side):
+        if ent[1] is None or ent[1].numel() < need:
+            ent[1] = torch.empty(max(int(need), 256), dtype=torch.uint8, device=dev)
+        dw, _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, ws=ent[1], tag=_tag(d))
+    _keep.append((qa, pa, g16, pg16))   # their memory must not be handed out again before the side stream is done with it
+    return dw
+
+
+_keep = []
+
+
+def _join_side():
+    for idx, (side, _) in _side.items():
+        torch.cuda.current_stream(idx).wait_stream(side)
+    del _keep[:]   # freed on the main stream, which is now behind the side stream
+
+
 _pending = []
 _layer = [0]   # layers are numbered in forward order; a layer's backward draws its two roundings with seeds 2 id + 1, + 2
 
@@ -141,7 +177,7 @@ def _convbn_bwd(saved, dbn, need_dx, lattice=False):
         dx, _ = _call("qconv_dgrad", ops, ny + 4 * (nx // (d.stride * d.stride)), q8t.qconv_dgrad, ds, g8, pg8, qw, pw, tag=_tag(d))
     elif need_dx:
         dx, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d))
-    dw, _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
+    dw = _wgrad(d, qa, pa, g16, pg16, ops, nx, ny)
     return dx, dw
 
 
@@ -196,7 +232,7 @@ class StemConvBNPool(torch.autograd.Function):
             dy = _call("maxpool_relu_bwd", 0, 5 * (ny // 4) + 4 * ny, q8t.maxpool_relu_bwd, gp.contiguous(), idx, d.P, d.Q)
             _, _, _, g8, pg8, g16, pg16 = _bn_bwd(q8t.range_bn_bwd_bifurcate, "range_bn_bwd_bifurcate", ny, y, dy, stats, None,
                                                   1e-5, 2 * lid + 1, 2 * lid + 2)
-        dw, _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
+        dw = _wgrad(d, qa, pa, g16, pg16, ops, nx, ny)
         return None, dw, None, None
 
 
@@ -250,7 +286,7 @@ def _chain_bwd(saved, g, need_dx, block_end=None):
                       qw, pw, other, act, tag=_tag(d))
         elif i > 0 or need_dx:
             g, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d))
-        dws[i], _ = _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))
+        dws[i] = _wgrad(d, qa, pa, g16, pg16, ops, nx, ny)
     return g, dws
 
 
@@ -293,7 +329,9 @@ class ResBlock(torch.autograd.Function):
                                y2, st2, ysc, other_stats=stsc, eps=1e-5, quantized=quantized)
         if quantized:
             _qcache[out.data_ptr()] = (q, qp)
-        ctx.saved = (chain, scs, a if mask_input else None, out, grad_is_masked)
+        # (a detached alias of the output: the output itself would point back at this node and keep the whole step's
+        # saved tensors alive until the cycle collector runs)
+        ctx.saved = (chain, scs, a if mask_input else None, out.detach(), grad_is_masked)
         return out
 
     @staticmethod
@@ -395,6 +433,7 @@ def step(x, labels, ws):
     a = F.adaptive_avg_pool2d(a, 1).flatten(1)
     loss = F.cross_entropy(Linear.apply(a, ws["fc"]), labels)
     loss.backward()
+    _join_side()
     return loss
 
 

@@ -34,3 +34,32 @@ def test_fused_and_plain_resnet18_steps_agree():
     assert lf == lp
     for i, (a, b) in enumerate(zip(gf, gp)):
         assert torch.equal(a, b), "gradient of parameter %d differs: max |diff| %g" % (i, float((a - b).abs().max()))
+
+
+def test_steps_leave_no_memory_behind():
+    # the nodes of a step must not keep each other alive (a node that saves its own output would, until the cycle
+    # collector happens to run): allocated device memory is the same after every step
+    require_gpu()
+    import gc
+    import torch
+    from paper_1805_11046_amd import train_step as ts
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(6)
+    ws = ts.make_weights(dev, gen)
+    x = torch.randn((2, 3, 224, 224), device=dev, generator=gen)
+    labels = torch.randint(0, 1000, (2,), device=dev, generator=gen)
+    params = [ws["conv1"], ws["fc"]] + [w for b in ws["blocks"] for w in b.values()]
+    gc.collect()
+    gc.disable()
+    try:
+        seen = []
+        for _ in range(4):
+            for p in params:
+                p.grad = None
+            ts.step(x, labels, ws)
+            torch.cuda.synchronize()
+            seen.append(torch.cuda.memory_allocated())
+    finally:
+        gc.enable()
+    assert seen[1] == seen[2] == seen[3], seen
