@@ -109,7 +109,7 @@ def _wgrad(d, qa, pa, g16, pg16, ops, nx, ny):
     `_overlap` it is issued on a second stream (default priority) with a workspace of its own and runs beside the
     Range BN passes and layer gradients of the layers below it, which are bound by memory and vector arithmetic where
     this product is bound by the matrix units and LDS; step() joins the stream at its end."""
-    if not _overlap:
+    if not _overlap or _breakdown or _bracket:    # calls that are being timed one by one stay on one stream
         return _call("qconv_wgrad", ops, nx + 2 * ny, q8t.qconv_wgrad, d, qa, pa, g16, pg16, tag=_tag(d))[0]
     dev = g16.device
     main = torch.cuda.current_stream(dev)
