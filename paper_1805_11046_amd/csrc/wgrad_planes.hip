@@ -93,11 +93,6 @@ struct Shape {
 
 __device__ __forceinline__ int dot4_ones(int v, int acc) { return __builtin_amdgcn_sdot4(v, 0x01010101, acc, false); }
 
-// gradient staged by image rows (see the kernel): everywhere but on 7x7 planes at stride 2, where the row tasks cost
-// registers and gained nothing
-template <int P, int STRIDE>
-constexpr bool kRowG = !(P == 7 && STRIDE == 2);
-
 template <class SH>
 __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restrict__ g16, const int8_t *__restrict__ x,
                                                          const q8t_qparams *__restrict__ qpg,
@@ -108,12 +103,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
     constexpr int P = SH::P, PT = SH::PT, PL = SH::PL, NIMG = SH::NIMG, TAPS = SH::TAPS;
     constexpr int NBV = SH::NBV, NAS = SH::NAS, WIN = SH::WIN, STRIDE = SH::STRIDE;
     constexpr int PP = P * P, WW = WIN * WIN;
-    constexpr int G_U4 = KT * PP * 2 / 16, X_U4 = CT * WW / 16;            // 16-byte pieces of one image's tiles
-    constexpr int GS = (G_U4 + kThreads - 1) / kThreads, XS = (X_U4 + kThreads - 1) / kThreads;
-    constexpr int GPC = P == 14 ? 4 : 8;                                    // LDS pieces per 16 bytes of gradient
-    constexpr int XPC = STRIDE == 1 ? (P == 14 ? 8 : 16) : (P == 14 ? 4 : 8);
     constexpr int NPART = 4;                                                // staging is spread over 4 of the 8 K-steps
-    static_assert(G_U4 * 16 == KT * PP * 2 && X_U4 * 16 == CT * WW, "tiles are whole 16-byte pieces");
 
     // XCD-aware decode (workgroup b runs on XCD b % 8): every XCD gets a contiguous run of the
     // (image range, tile pair) list, so workgroups that share an image range, and with it their
@@ -143,75 +133,40 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
         }
     }
 
-    // ---- per-thread staging plan: LDS byte offsets of the pieces of its 16-byte loads (per image) ----
-    // gradient: offset of the high byte plane inside the A region; the low plane is KT rows further
-    uint32_t ga[GS][GPC / 2];
-#pragma unroll
-    for (int s = 0; s < GS; ++s)
-#pragma unroll
-        for (int q = 0; q < GPC; q += 2) {
-            uint32_t pk = 0;
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int e = 8 * (tid + kThreads * s) + (P == 14 ? 2 : 1) * (q + h);   // value index in [KT][PP]
-                const int row = e / PP, pos = e - row * PP, y = pos / P, xq = pos - y * P;
-                pk |= (uint32_t)((row * ROWP + LEFT + y * PT + SH::LEADC + xq) & 0xFFFF) << (16 * h);
-            }
-            ga[s][q / 2] = pk;
-        }
-    // input: offset inside the B region (stride 2: of the even-column class of the piece's row parity)
-    uint32_t xa[XS][XPC / 2];
-#pragma unroll
-    for (int s = 0; s < XS; ++s)
-#pragma unroll
-        for (int q = 0; q < XPC; q += 2) {
-            uint32_t pk = 0;
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int e = 16 * (tid + kThreads * s) + (16 / XPC) * (q + h);         // byte index in [CT][WW]
-                const int c = e / WW, pos = e - c * WW, y = pos / WIN, xq = pos - y * WIN;
-                int o;
-                if (STRIDE == 1) o = c * ROWP + LEFT + y * PT + SH::LEADC + xq;
-                else o = c * ROWP + LEFT + (y >> 1) * PT + SH::LEADC + (xq >> 1) + ((y & 1) << 15);   // bit 15: odd input row
-                pk |= (uint32_t)(o & 0xFFFF) << (16 * h);
-            }
-            xa[s][q / 2] = pk;
-        }
-    static_assert(CT * ROWP <= 32768, "bit 15 of a packed input offset is the row parity");
-    // Staging by image rows: a 16-byte piece of the contiguous tile covers parts of several image rows at byte (7x7) or
-    // 2-byte (14x14) granularity, which made staging (a narrow LDS store per value or pair) cost as much as the MFMAs.
-    // Here a thread stages whole image rows instead: the P values of a row and the LEADC values before them (for the
+    // ---- staging plan ----
+    // Staging goes by image rows.  (A 16-byte piece of the contiguous tile covers parts of several image rows at byte (7x7)
+    // or 2-byte (14x14) granularity; staging by pieces, a narrow LDS store per value or pair, cost as much as the MFMAs.)
+    // A thread stages whole image rows: the P values of a row and the LEADC values before them (for the
     // first row of a plane: the values behind them, shifted in registers) are one or two unaligned global loads of a
     // padded row's size, the values before the row become the pads, and a padded row goes to LDS as one aligned 8- or
     // 16-byte store per byte plane.
-    constexpr bool ROWG = kRowG<P, STRIDE>, ROWX = STRIDE == 1;
-    constexpr int GROWS = KT * P * NIMG, XROWS = CT * P * NIMG;
-    constexpr int GT = ROWG ? (GROWS + kThreads - 1) / kThreads : 1, XT = ROWX ? (XROWS + kThreads - 1) / kThreads : 1;
-    constexpr int GW = PT / 8;      // 16-byte pieces of a padded gradient row (2 * PT bytes), = of a padded input row times two
-    static_assert(!ROWG || GT * GW <= NIMG * GS, "the row tasks reuse the registers of the pieces");
-    static_assert(!ROWX || XT <= NIMG * XS, "the row tasks reuse the registers of the pieces");
-    int rg_off[GT], rg_lds[GT], rx_off[XT], rx_lds[XT];   // byte offset in the image's tile (-1: no task) / in the LDS region
-    int rg_img[GT], rx_img[XT];
-    bool rg_first[GT], rx_first[XT];
-#pragma unroll
-    for (int s2 = 0; s2 < GT; ++s2) {
-        const int t = tid + s2 * kThreads, tt = t < GROWS ? t : 0;
-        const int m = tt / (KT * P), rr = tt - m * (KT * P), k = rr / P, r = rr - k * P;
-        rg_img[s2] = m;
-        rg_first[s2] = r == 0;
-        rg_off[s2] = ROWG && t < GROWS ? (k * PP + r * P - (r ? SH::LEADC : 0)) * 2 : -1;
-        rg_lds[s2] = m * PL + k * ROWP + LEFT + r * PT;
-    }
-#pragma unroll
-    for (int s2 = 0; s2 < XT; ++s2) {
-        const int t = tid + s2 * kThreads, tt = t < XROWS ? t : 0;
-        const int m = tt / (CT * P), rr = tt - m * (CT * P), c = rr / P, r = rr - c * P;
-        rx_img[s2] = m;
-        rx_first[s2] = r == 0;
-        rx_off[s2] = ROWX && t < XROWS ? c * WW + r * P - (r ? SH::LEADC : 0) : -1;
-        rx_lds[s2] = m * PL + c * ROWP + LEFT + r * PT;
-    }
-    const bool g_last = tid + kThreads * (GS - 1) < G_U4, x_last = tid + kThreads * (XS - 1) < X_U4;
+    // An input row at stride 2 is 2 * PT bytes (2 * LEADC of them before the row) that fall apart into the padded rows
+    // of the even-column and the odd-column class of the row's parity: two byte permutes per pair of dwords.
+    // Row tasks are dealt out so that a thread's tasks differ by constants only: 448 = 64 * 7 = 32 * 14 = 16 * 28 rows
+    // (the rows of 64, 32 or 16 channels of one image) go to threads 0..447 per slot, and the slots walk the channel
+    // groups of an image, then the images of the chunk.  One offset pair per operand describes all of a thread's tasks
+    // (a table per slot cost enough registers to spill, and a reload from scratch waits for every global load in flight).
+    constexpr int kRowThreads = 448;
+    constexpr int G_CPS = kRowThreads / P, G_SPI = KT / G_CPS;        // gradient: channels per slot, slots per image
+    constexpr int X_CPS = kRowThreads / WIN, X_SPI = CT / X_CPS;      // input
+    static_assert(G_CPS * P == kRowThreads && X_CPS * WIN == kRowThreads && G_SPI * G_CPS == KT && X_SPI * X_CPS == CT, "whole groups");
+    constexpr int GT = NIMG * G_SPI, XT = NIMG * X_SPI;   // row tasks per thread and chunk
+    constexpr int GW = PT / 8;      // 16-byte pieces of a padded gradient row (2 * PT bytes)
+    constexpr int XWB = STRIDE * PT, XW = (XWB + 15) / 16, XSB = STRIDE * SH::LEADC;   // bytes / 16-byte pieces of an input row task, bytes before the row
+    const int rt = tid < kRowThreads ? tid : tid - kRowThreads;   // the last 64 threads repeat the first 64 tasks: no thread-dependent branch
+    const int gk0 = rt / P, gr0 = rt - gk0 * P, xc0 = rt / WIN, xr0 = rt - xc0 * WIN;
+    const bool rg_first = gr0 == 0, rx_first = xr0 == 0;
+    // byte offset in the image's tile / in the LDS region, of slot 0
+    const int rg_off0 = (gk0 * PP + gr0 * P - (gr0 ? SH::LEADC : 0)) * 2, rg_lds0 = gk0 * ROWP + LEFT + gr0 * PT;
+    const int rx_off0 = xc0 * WW + xr0 * WIN - (xr0 ? XSB : 0);
+    const int rx_lds0 = STRIDE == 1 ? xc0 * ROWP + LEFT + xr0 * PT
+                                    : ((xr0 & 1) ? 2 * SH::CLSB : 0) + xc0 * ROWP + LEFT + (xr0 >> 1) * PT;   // even-column class of the row's parity
+    auto rg_img = [](int i) { return i / G_SPI; };
+    auto rg_off = [&](int i) { return rg_off0 + (i % G_SPI) * G_CPS * PP * 2; };
+    auto rg_lds = [&](int i) { return rg_lds0 + (i / G_SPI) * PL + (i % G_SPI) * G_CPS * ROWP; };
+    auto rx_img = [](int i) { return i / X_SPI; };
+    auto rx_off = [&](int i) { return rx_off0 + (i % X_SPI) * X_CPS * WW; };
+    auto rx_lds = [&](int i) { return rx_lds0 + (i / X_SPI) * PL + (i % X_SPI) * X_CPS * ROWP; };
 
     const int img0 = kr * g.ipr, img1 = min(g.N, img0 + g.ipr);
     const int units = (img1 - img0 + NIMG - 1) / NIMG;
@@ -225,68 +180,51 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
 #pragma unroll
     for (int i = 0; i < SH::CSW; ++i) csum[i] = 0;
 
-    uint4 rgr[NIMG * GS], rxr[NIMG * XS];
+    uint4 rgr[GT * GW], rxr[XT * XW];
     const uint4 *gsrc = reinterpret_cast<const uint4 *>(g16 + ((int64_t)img0 * g.K + rg * KT) * PP);
     const uint4 *xsrc = reinterpret_cast<const uint4 *>(x + ((int64_t)img0 * g.C + cg * CT) * WW);
     const int64_t gstep = (int64_t)g.K * PP * 2 / 16, xstep = (int64_t)g.C * WW / 16;   // 16-byte pieces per image
     int l_img = img0;                      // first image of the chunk that is being loaded
-    // The 16-byte pieces that write_part(., part) puts into LDS, for the chunk starting at image l_img.
-    // Every load is issued unconditionally (straight-line code lets the compiler wait for exactly the
-    // loads it needs instead of for all of them): a thread without a piece in its last slot reads
-    // piece 0 of the tile, an image past the range re-reads the chunk's first image, and neither is
-    // used.  Every index stays inside the tile of an image of the range.
-    const int g_lastoff = g_last ? tid + (GS - 1) * kThreads : 0, x_lastoff = x_last ? tid + (XS - 1) * kThreads : 0;
+    // The rows that write_part(., part) puts into LDS, for the chunk starting at image l_img.  Every load is issued
+    // unconditionally (straight-line code lets the compiler wait for exactly the loads it needs instead of for all of
+    // them): an image past the range re-reads the chunk's first image and is replaced by zero codes.  Every address
+    // stays inside the tile of an image of the range.
     auto load_part = [&](int part) {
-        if constexpr (ROWG) {
+        {
 #pragma unroll
             for (int i = 0; i < GT; ++i)
                 if (i % NPART == part) {
-                    const bool have = rg_off[i] >= 0 && (rg_img[i] == 0 || l_img + rg_img[i] < img1);
-                    const uint8_t *src = reinterpret_cast<const uint8_t *>(gsrc) + rg_img[i] * gstep * 16 + (have ? rg_off[i] : 0);
+                    const bool have = rg_img(i) == 0 || l_img + rg_img(i) < img1;
+                    const uint8_t *src = reinterpret_cast<const uint8_t *>(gsrc) + (have ? rg_img(i) * gstep * 16 : 0) + rg_off(i);
 #pragma unroll
                     for (int w = 0; w < GW; ++w) {
-                        uint4 v = make_uint4(a_pad, a_pad, a_pad, a_pad);
-                        if (have) __builtin_memcpy(&v, src + 16 * w, 16);
-                        rgr[i * GW + w] = v;
+                        uint4 v;
+                        __builtin_memcpy(&v, src + 16 * w, 16);
+                        rgr[i * GW + w] = have ? v : make_uint4(a_pad, a_pad, a_pad, a_pad);
                     }
                 }
         }
-        if constexpr (ROWX) {
+        {
 #pragma unroll
             for (int i = 0; i < XT; ++i)
                 if ((i + 2) % NPART == part) {
-                    const bool have = rx_off[i] >= 0 && (rx_img[i] == 0 || l_img + rx_img[i] < img1);
-                    const uint8_t *src = reinterpret_cast<const uint8_t *>(xsrc) + rx_img[i] * xstep * 16 + (have ? rx_off[i] : 0);
-                    uint4 v = make_uint4(b_pad, b_pad, b_pad, b_pad);
-                    if (have) {
-                        if (PT == 16) {
-                            __builtin_memcpy(&v, src, 16);
+                    const bool have = rx_img(i) == 0 || l_img + rx_img(i) < img1;
+                    const uint8_t *src = reinterpret_cast<const uint8_t *>(xsrc) + (have ? rx_img(i) * xstep * 16 : 0) + rx_off(i);
+#pragma unroll
+                    for (int w = 0; w < XW; ++w) {
+                        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+                        if (XWB >= 16) {
+                            __builtin_memcpy(&v, src + 16 * w, 16);
                         } else {
                             uint2 h;
                             __builtin_memcpy(&h, src, 8);
                             v.x = h.x;
                             v.y = h.y;
                         }
+                        rxr[i * XW + w] = have ? v : make_uint4(b_pad, b_pad, b_pad, b_pad);
                     }
-                    rxr[i] = v;
                 }
         }
-#pragma unroll
-        for (int i = 0; i < (ROWG ? 0 : NIMG * GS); ++i)
-            if (i % NPART == part) {
-                const int m = i / GS, sl = i % GS;
-                const bool have = m == 0 || l_img + m < img1;
-                const uint4 v = gsrc[(have ? m * gstep : 0) + (sl < GS - 1 ? tid + sl * kThreads : g_lastoff)];
-                rgr[i] = have ? v : make_uint4(a_pad, a_pad, a_pad, a_pad);
-            }
-#pragma unroll
-        for (int i = 0; i < (ROWX ? 0 : NIMG * XS); ++i)
-            if ((i + 2) % NPART == part) {
-                const int m = i / XS, sl = i % XS;
-                const bool have = m == 0 || l_img + m < img1;
-                const uint4 v = xsrc[(have ? m * xstep : 0) + (sl < XS - 1 ? tid + sl * kThreads : x_lastoff)];
-                rxr[i] = have ? v : make_uint4(b_pad, b_pad, b_pad, b_pad);
-            }
     };
     // the chunk after this one, or this one again when it is the last (its reload is never used)
     auto next_chunk = [&]() {
@@ -295,58 +233,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
         xsrc += more ? NIMG * xstep : 0;
         l_img += more ? NIMG : 0;
     };
-    auto comp = [](const uint4 &v, int i) -> uint32_t { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; };
-    // one staged 16-byte piece of the gradient -> the two byte planes in LDS
-    auto write_g = [&](uint8_t *A, int m, int s) {
-        if (!(s < GS - 1 || g_last)) return;
-        const uint4 v = rgr[m * GS + s];
-        uint8_t *Am = A + m * PL;
-#pragma unroll
-        for (int q = 0; q < GPC; ++q) {
-            const uint32_t o = (ga[s][q / 2] >> (16 * (q & 1))) & 0xFFFFu;
-            if (P == 14) {     // two values: both high bytes, both low bytes (flipped: lo - 128)
-                const uint32_t d = comp(v, q) ^ 0x00800080u;
-                *reinterpret_cast<uint16_t *>(Am + o) = (uint16_t)__builtin_amdgcn_perm(0u, d, 0x0C0C0301u);
-                *reinterpret_cast<uint16_t *>(Am + o + KT * ROWP) = (uint16_t)__builtin_amdgcn_perm(0u, d, 0x0C0C0200u);
-            } else {
-                const uint32_t d = (comp(v, q >> 1) ^ 0x00800080u) >> (16 * (q & 1));
-                Am[o] = (uint8_t)(d >> 8);
-                Am[o + KT * ROWP] = (uint8_t)d;
-            }
-        }
-    };
-    auto write_x = [&](uint8_t *B, int m, int s) {
-        if (!(s < XS - 1 || x_last)) return;
-        const uint4 v = rxr[m * XS + s];
-        uint8_t *Bm = B + m * PL;
-#pragma unroll
-        for (int q = 0; q < XPC; ++q) {
-            const uint32_t pk = (xa[s][q / 2] >> (16 * (q & 1))) & 0xFFFFu;
-            if (STRIDE == 1 && P == 14) {
-                *reinterpret_cast<uint16_t *>(Bm + pk) = (uint16_t)(comp(v, q >> 1) >> (16 * (q & 1)));
-            } else if (STRIDE == 1) {
-                Bm[pk] = (uint8_t)(comp(v, q >> 2) >> (8 * (q & 3)));
-            } else {
-                const uint32_t o = (pk & 0x7FFFu) + (pk >> 15) * (2 * SH::CLSB);   // classes of odd input rows come third and fourth
-                if (P == 14) {      // 4 bytes of one input row: even columns -> class b = 0, odd -> b = 1
-                    const uint32_t d = comp(v, q);
-                    *reinterpret_cast<uint16_t *>(Bm + o) = (uint16_t)__builtin_amdgcn_perm(0u, d, 0x0C0C0200u);
-                    *reinterpret_cast<uint16_t *>(Bm + o + SH::CLSB) = (uint16_t)__builtin_amdgcn_perm(0u, d, 0x0C0C0301u);
-                } else {
-                    const uint32_t d = comp(v, q >> 1) >> (16 * (q & 1));
-                    Bm[o] = (uint8_t)d;
-                    Bm[o + SH::CLSB] = (uint8_t)(d >> 8);
-                }
-            }
-        }
-    };
     auto abu = [](uint32_t hi, uint32_t lo, int n) { return __builtin_amdgcn_alignbyte(hi, lo, n); };
     auto write_part = [&](int buf, int part) {
         uint8_t *A = smem + buf * SH::BUF, *B = A + SH::A_BYTES;
-        if constexpr (ROWG) {
+        {
 #pragma unroll
             for (int i = 0; i < GT; ++i)
-                if (i % NPART == part && rg_off[i] >= 0) {
+                if (i % NPART == part) {
                     uint32_t w[4 * GW];   // a padded row: LEADC pad values, then the P values of the row
 #pragma unroll
                     for (int q = 0; q < GW; ++q) {
@@ -355,7 +248,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
                         w[4 * q + 2] = rgr[i * GW + q].z;
                         w[4 * q + 3] = rgr[i * GW + q].w;
                     }
-                    if (rg_first[i]) {   // loaded from the row's own start: move up by LEADC values
+                    if (rg_first) {   // loaded from the row's own start: move up by LEADC values
 #pragma unroll
                         for (int q = 4 * GW - 1; q > 0; --q) w[q] = SH::LEADC == 2 ? w[q - 1] : abu(w[q], w[q - 1], 2);
                         if (SH::LEADC == 1) w[0] = w[0] << 16;
@@ -369,36 +262,57 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
                         lo[q] = __builtin_amdgcn_perm(d1, d0, 0x06040200u);
                     }
                     if (GW == 2) {
-                        *reinterpret_cast<uint4 *>(A + rg_lds[i]) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-                        *reinterpret_cast<uint4 *>(A + rg_lds[i] + KT * ROWP) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                        *reinterpret_cast<uint4 *>(A + rg_lds(i)) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+                        *reinterpret_cast<uint4 *>(A + rg_lds(i) + KT * ROWP) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
                     } else {
-                        *reinterpret_cast<uint2 *>(A + rg_lds[i]) = make_uint2(hi[0], hi[1]);
-                        *reinterpret_cast<uint2 *>(A + rg_lds[i] + KT * ROWP) = make_uint2(lo[0], lo[1]);
+                        *reinterpret_cast<uint2 *>(A + rg_lds(i)) = make_uint2(hi[0], hi[1]);
+                        *reinterpret_cast<uint2 *>(A + rg_lds(i) + KT * ROWP) = make_uint2(lo[0], lo[1]);
                     }
                 }
         }
-        if constexpr (ROWX) {
+        {
 #pragma unroll
             for (int i = 0; i < XT; ++i)
-                if ((i + 2) % NPART == part && rx_off[i] >= 0) {
-                    uint32_t w[4] = {rxr[i].x, rxr[i].y, rxr[i].z, rxr[i].w};
-                    constexpr int NW = PT / 4;   // dwords of a padded input row
-                    if (rx_first[i]) {   // move up by LEADC bytes
+                if ((i + 2) % NPART == part) {
+                    uint32_t w[4 * XW];
 #pragma unroll
-                        for (int q = NW - 1; q > 0; --q) w[q] = abu(w[q], w[q - 1], 4 - SH::LEADC);
-                        w[0] = w[0] << (8 * SH::LEADC);
+                    for (int q = 0; q < XW; ++q) {
+                        w[4 * q] = rxr[i * XW + q].x;
+                        w[4 * q + 1] = rxr[i * XW + q].y;
+                        w[4 * q + 2] = rxr[i * XW + q].z;
+                        w[4 * q + 3] = rxr[i * XW + q].w;
                     }
-                    w[0] = SH::LEADC == 2 ? (w[0] & 0xFFFF0000u) | (b_pad & 0xFFFFu) : (w[0] & 0xFFFFFF00u) | (b_pad & 0xFFu);
-                    if (NW == 4) *reinterpret_cast<uint4 *>(B + rx_lds[i]) = make_uint4(w[0], w[1], w[2], w[3]);
-                    else *reinterpret_cast<uint2 *>(B + rx_lds[i]) = make_uint2(w[0], w[1]);
+                    constexpr int LW = XWB / 4;  // dwords loaded for the row
+                    constexpr int NW = PT / 4;   // dwords of a padded row in LDS
+                    if (rx_first) {   // loaded from the row's own start: move up by the bytes before a row
+#pragma unroll
+                        for (int q = LW - 1; q > 0; --q) w[q] = XSB == 4 ? w[q - 1] : abu(w[q], w[q - 1], 4 - XSB);
+                        w[0] = XSB == 4 ? 0u : w[0] << (8 * XSB);
+                    }
+                    constexpr uint32_t keep = SH::LEADC == 2 ? 0xFFFF0000u : 0xFFFFFF00u;
+                    if (STRIDE == 1) {
+                        w[0] = (w[0] & keep) | (b_pad & ~keep);
+                        if (NW == 4) *reinterpret_cast<uint4 *>(B + rx_lds(i)) = make_uint4(w[0], w[1], w[2], w[3]);
+                        else *reinterpret_cast<uint2 *>(B + rx_lds(i)) = make_uint2(w[0], w[1]);
+                    } else {
+                        uint32_t ev[NW], od[NW];
+#pragma unroll
+                        for (int q = 0; q < NW; ++q) {
+                            ev[q] = __builtin_amdgcn_perm(w[2 * q + 1], w[2 * q], 0x06040200u);
+                            od[q] = __builtin_amdgcn_perm(w[2 * q + 1], w[2 * q], 0x07050301u);
+                        }
+                        ev[0] = (ev[0] & keep) | (b_pad & ~keep);
+                        od[0] = (od[0] & keep) | (b_pad & ~keep);
+                        if (NW == 4) {
+                            *reinterpret_cast<uint4 *>(B + rx_lds(i)) = make_uint4(ev[0], ev[1], ev[2], ev[3]);
+                            *reinterpret_cast<uint4 *>(B + rx_lds(i) + SH::CLSB) = make_uint4(od[0], od[1], od[2], od[3]);
+                        } else {
+                            *reinterpret_cast<uint2 *>(B + rx_lds(i)) = make_uint2(ev[0], ev[1]);
+                            *reinterpret_cast<uint2 *>(B + rx_lds(i) + SH::CLSB) = make_uint2(od[0], od[1]);
+                        }
+                    }
                 }
         }
-#pragma unroll
-        for (int i = 0; i < (ROWG ? 0 : NIMG * GS); ++i)
-            if (i % NPART == part) write_g(A, i / GS, i % GS);
-#pragma unroll
-        for (int i = 0; i < (ROWX ? 0 : NIMG * XS); ++i)
-            if ((i + 2) % NPART == part) write_x(B, i / XS, i % XS);
     };
     auto ab = [](int hi, int lo, int n) { return (int)__builtin_amdgcn_alignbyte((uint32_t)hi, (uint32_t)lo, n); };
 
@@ -434,8 +348,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
     auto compute = [&](int buf, auto stage_tag) {
         constexpr bool stage = decltype(stage_tag)::value;
         const uint8_t *A = smem + buf * SH::BUF, *B = A + SH::A_BYTES;
-        const uint8_t *Ar = A + (pl * KT + kt * 32 + r32) * ROWP + LEFT + kh * 16;
-        const uint8_t *Br = B + (ch * 32 + r32) * ROWP + LEFT + kh * 16;
+        // the fragment addresses are rebuilt from the lane index in every chunk: held across the loop they were the
+        // registers that spilled, and a reload from scratch waits for the global loads in flight
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        const uint8_t *Ar = A + (pl * KT + kt * 32 + (ln & 31)) * ROWP + LEFT + (ln >> 5) * 16;
+        const uint8_t *Br = B + (ch * 32 + (ln & 31)) * ROWP + LEFT + (ln >> 5) * 16;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             v4i fa[NAS];
@@ -455,18 +373,20 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
                 write_part(buf ^ 1, ks >> 1);
                 load_part(ks >> 1);
             }
+            {
 #pragma unroll
-            for (int i = 0; i < SH::CSW; ++i) {
-                const v4i fb = read_b(Br + cs_off[i] + ks * 32, PT == 16);
-                csum[i] = dot4_ones(fb[0], dot4_ones(fb[1], dot4_ones(fb[2], dot4_ones(fb[3], csum[i]))));
-            }
+                for (int i = 0; i < SH::CSW; ++i) {
+                    const v4i fb = read_b(Br + cs_off[i] + ks * 32, PT == 16);
+                    csum[i] = dot4_ones(fb[0], dot4_ones(fb[1], dot4_ones(fb[2], dot4_ones(fb[3], csum[i]))));
+                }
 #pragma unroll
-            for (int v = 0; v < NBV; ++v) {
-                const v4i fb = read_b(Br + SH::bcls(v) * SH::CLSB + ks * 32 + SH::boff(v), PT == 16 || SH::boff(v) == 0);
+                for (int v = 0; v < NBV; ++v) {
+                    const v4i fb = read_b(Br + SH::bcls(v) * SH::CLSB + ks * 32 + SH::boff(v), PT == 16 || SH::boff(v) == 0);
 #pragma unroll
-                for (int t = 0; t < TAPS; ++t)
-                    if (SH::bvar(t) == v)
-                        acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[SH::ashift(t)], fb, acc[t], 0, 0, 0);
+                    for (int t = 0; t < TAPS; ++t)
+                        if (SH::bvar(t) == v)
+                            acc[t] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[SH::ashift(t)], fb, acc[t], 0, 0, 0);
+                }
             }
         }
     };
