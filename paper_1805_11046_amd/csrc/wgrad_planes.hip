@@ -58,37 +58,41 @@ struct PGeom {
     int nrg, ncg;    // row groups (K/64), channel groups (C/64)
 };
 
-template <int P_, int STRIDE_>
+// KS_ = 3: 3x3 filter, pad 1.  KS_ = 1: the 1x1 filter at stride 2 without padding (the projection shortcut of a
+// down-sampling block): one tap, which reads the (even row, even column) class of the input plane only.
+template <int P_, int STRIDE_, int KS_ = 3>
 struct Shape {
-    static constexpr int P = P_, STRIDE = STRIDE_;
+    static constexpr int P = P_, STRIDE = STRIDE_, KS = KS_;
+    static_assert(KS == 3 || (KS == 1 && STRIDE == 2), "filters served: 3x3 at stride 1 or 2, 1x1 at stride 2");
     static constexpr int PT = P == 14 ? 16 : 8;          // padded row pitch
     static constexpr int LEADC = PT - P;                 // pad columns, at the start of a row (so that position 0 is a pad)
     static constexpr int PL = PT * PT;                   // padded positions per plane
     static constexpr int NIMG = KC / PL;                 // planes per chunk
-    static constexpr int TAPS = 9;
-    static constexpr int NCLS = STRIDE == 1 ? 1 : 4;     // parity classes of the input plane
-    static constexpr int NBV = STRIDE == 1 ? 3 : 6;      // distinct input fragments per K-step
-    static constexpr int NAS = STRIDE == 1 ? 3 : 2;      // distinct shifts of the gradient fragment
+    static constexpr int TAPS = KS * KS;
+    static constexpr int NCLS = STRIDE == 1 || KS == 1 ? 1 : 4;     // parity classes of the input plane that are staged
+    static constexpr int NBV = KS == 1 ? 1 : (STRIDE == 1 ? 3 : 6); // distinct input fragments per K-step
+    static constexpr int NAS = KS == 1 ? 1 : (STRIDE == 1 ? 3 : 2); // distinct shifts of the gradient fragment
     static constexpr int WIN = P * STRIDE;               // input plane edge
     static constexpr int A_BYTES = 2 * KT * ROWP;
     static constexpr int CLSB = CT * ROWP;               // bytes of one parity class
     static constexpr int B_BYTES = NCLS * CLSB;
     static constexpr int BUF = A_BYTES + B_BYTES;
-    static constexpr bool DB = STRIDE == 1;              // two LDS buffers (stride 2: the four classes leave room for one)
+    static constexpr bool DB = NCLS == 1;                // two LDS buffers (four classes leave room for one)
     static constexpr int SMEM = (DB ? 2 : 1) * BUF;
     static constexpr int HALF_INTS = 4 * TAPS * 16 * 64;     // accumulators of one byte plane: [row half][channel half][tap][reg][lane]
     static constexpr int TILE_INTS = 2 * HALF_INTS;
     static constexpr int PART_INTS = TILE_INTS + NBV * CT + 2 * KT;   // + column sums [variant][ch] + row sums [plane][row]
     static constexpr int CSW = (NBV + 3) / 4;            // column sums gathered per wavefront (variants 4i + its index among the four that share a channel half)
 
-    // tap t = 3r + s -> variant of the input fragment, shift index of the gradient fragment
+    // tap t = 3r + s -> variant of the input fragment, shift index of the gradient fragment (0: g[p' + 1], 1: g[p'], 2: g[p' - 1])
     //   stride 1: variant r (offset (r-1)*PT), gradient g[p' - (s-1)]: shift index s = {+1, 0, -1}
     //   stride 2: input row 2p+r-1 -> (parity, offset) r=0:(1,-PT) r=1:(0,0) r=2:(1,0); column likewise
     //             s=0:(1,-1) s=1:(0,0) s=2:(1,0); the -1 moves to the gradient as g[p'+1]: shift index {+1, 0}
-    static __host__ __device__ constexpr int bvar(int t) { return STRIDE == 1 ? t / 3 : (t / 3) * 2 + (((t % 3) & 1) ? 0 : 1); }
-    static __host__ __device__ constexpr int ashift(int t) { return STRIDE == 1 ? t % 3 : ((t % 3) == 0 ? 0 : 1); }
-    static __host__ __device__ constexpr int bcls(int v) { return STRIDE == 1 ? 0 : ((v >> 1) == 1 ? 0 : 2) + (v & 1); }
-    static __host__ __device__ constexpr int boff(int v) { return STRIDE == 1 ? (v - 1) * PT : ((v >> 1) == 0 ? -PT : 0); }
+    //   1x1: the one tap reads class (0, 0) at offset 0 against the unshifted gradient
+    static __host__ __device__ constexpr int bvar(int t) { return KS == 1 ? 0 : (STRIDE == 1 ? t / 3 : (t / 3) * 2 + (((t % 3) & 1) ? 0 : 1)); }
+    static __host__ __device__ constexpr int ashift(int t) { return KS == 1 ? 1 : (STRIDE == 1 ? t % 3 : ((t % 3) == 0 ? 0 : 1)); }
+    static __host__ __device__ constexpr int bcls(int v) { return STRIDE == 1 || KS == 1 ? 0 : ((v >> 1) == 1 ? 0 : 2) + (v & 1); }
+    static __host__ __device__ constexpr int boff(int v) { return KS == 1 ? 0 : (STRIDE == 1 ? (v - 1) * PT : ((v >> 1) == 0 ? -PT : 0)); }
 };
 
 __device__ __forceinline__ int dot4_ones(int v, int acc) { return __builtin_amdgcn_sdot4(v, 0x01010101, acc, false); }
@@ -101,7 +105,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     constexpr int P = SH::P, PT = SH::PT, PL = SH::PL, NIMG = SH::NIMG, TAPS = SH::TAPS;
-    constexpr int NBV = SH::NBV, NAS = SH::NAS, WIN = SH::WIN, STRIDE = SH::STRIDE;
+    constexpr int NBV = SH::NBV, NAS = SH::NAS, WIN = SH::WIN, STRIDE = SH::STRIDE, KS = SH::KS;
     constexpr int PP = P * P, WW = WIN * WIN;
     constexpr int NPART = 4;                                                // staging is spread over 4 of the 8 K-steps
 
@@ -148,19 +152,21 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
     // (a table per slot cost enough registers to spill, and a reload from scratch waits for every global load in flight).
     constexpr int kRowThreads = 448;
     constexpr int G_CPS = kRowThreads / P, G_SPI = KT / G_CPS;        // gradient: channels per slot, slots per image
-    constexpr int X_CPS = kRowThreads / WIN, X_SPI = CT / X_CPS;      // input
-    static_assert(G_CPS * P == kRowThreads && X_CPS * WIN == kRowThreads && G_SPI * G_CPS == KT && X_SPI * X_CPS == CT, "whole groups");
+    constexpr int XR = KS == 1 ? P : WIN;                             // input rows staged per channel (1x1: the even ones)
+    constexpr int X_CPS = kRowThreads / XR, X_SPI = CT / X_CPS;       // input
+    static_assert(G_CPS * P == kRowThreads && X_CPS * XR == kRowThreads && G_SPI * G_CPS == KT && X_SPI * X_CPS == CT, "whole groups");
     constexpr int GT = NIMG * G_SPI, XT = NIMG * X_SPI;   // row tasks per thread and chunk
     constexpr int GW = PT / 8;      // 16-byte pieces of a padded gradient row (2 * PT bytes)
     constexpr int XWB = STRIDE * PT, XW = (XWB + 15) / 16, XSB = STRIDE * SH::LEADC;   // bytes / 16-byte pieces of an input row task, bytes before the row
     const int rt = tid < kRowThreads ? tid : tid - kRowThreads;   // the last 64 threads repeat the first 64 tasks: no thread-dependent branch
-    const int gk0 = rt / P, gr0 = rt - gk0 * P, xc0 = rt / WIN, xr0 = rt - xc0 * WIN;
+    const int gk0 = rt / P, gr0 = rt - gk0 * P, xc0 = rt / XR, xr0 = rt - xc0 * XR;
     const bool rg_first = gr0 == 0, rx_first = xr0 == 0;
     // byte offset in the image's tile / in the LDS region, of slot 0
     const int rg_off0 = (gk0 * PP + gr0 * P - (gr0 ? SH::LEADC : 0)) * 2, rg_lds0 = gk0 * ROWP + LEFT + gr0 * PT;
-    const int rx_off0 = xc0 * WW + xr0 * WIN - (xr0 ? XSB : 0);
-    const int rx_lds0 = STRIDE == 1 ? xc0 * ROWP + LEFT + xr0 * PT
-                                    : ((xr0 & 1) ? 2 * SH::CLSB : 0) + xc0 * ROWP + LEFT + (xr0 >> 1) * PT;   // even-column class of the row's parity
+    const int rx_off0 = xc0 * WW + xr0 * (KS == 1 ? 2 * WIN : WIN) - (xr0 ? XSB : 0);
+    const int rx_lds0 = STRIDE == 1 || KS == 1
+                            ? xc0 * ROWP + LEFT + xr0 * PT
+                            : ((xr0 & 1) ? 2 * SH::CLSB : 0) + xc0 * ROWP + LEFT + (xr0 >> 1) * PT;   // even-column class of the row's parity
     auto rg_img = [](int i) { return i / G_SPI; };
     auto rg_off = [&](int i) { return rg_off0 + (i % G_SPI) * G_CPS * PP * 2; };
     auto rg_lds = [&](int i) { return rg_lds0 + (i / G_SPI) * PL + (i % G_SPI) * G_CPS * ROWP; };
@@ -305,10 +311,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
                         od[0] = (od[0] & keep) | (b_pad & ~keep);
                         if (NW == 4) {
                             *reinterpret_cast<uint4 *>(B + rx_lds(i)) = make_uint4(ev[0], ev[1], ev[2], ev[3]);
-                            *reinterpret_cast<uint4 *>(B + rx_lds(i) + SH::CLSB) = make_uint4(od[0], od[1], od[2], od[3]);
+                            if (KS != 1) *reinterpret_cast<uint4 *>(B + rx_lds(i) + SH::CLSB) = make_uint4(od[0], od[1], od[2], od[3]);
                         } else {
                             *reinterpret_cast<uint2 *>(B + rx_lds(i)) = make_uint2(ev[0], ev[1]);
-                            *reinterpret_cast<uint2 *>(B + rx_lds(i) + SH::CLSB) = make_uint2(od[0], od[1]);
+                            if (KS != 1) *reinterpret_cast<uint2 *>(B + rx_lds(i) + SH::CLSB) = make_uint2(od[0], od[1]);
                         }
                     }
                 }
@@ -326,7 +332,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
         int v = 4 * i + (wave & 3);
         if (v >= NBV) v = 0;
         int cls, off;
-        if (STRIDE == 1) { cls = 0; off = (v - 1) * PT; }
+        if (KS == 1) { cls = 0; off = 0; }
+        else if (STRIDE == 1) { cls = 0; off = (v - 1) * PT; }
         else { cls = ((v >> 1) == 1 ? 0 : 2) + (v & 1); off = (v >> 1) == 0 ? -PT : 0; }
         cs_off[i] = __builtin_amdgcn_readfirstlane(cls * SH::CLSB + off);
     }
@@ -356,16 +363,18 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
         const uint8_t *Br = B + (ch * 32 + (ln & 31)) * ROWP + LEFT + (ln >> 5) * 16;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            v4i fa[NAS];
+            v4i fa[3];   // by shift index: g[p' + 1], g[p'], g[p' - 1] (as many as the filter needs)
             {
                 const uint8_t *ap = Ar + ks * 32;
                 const v4i c = *reinterpret_cast<const v4i *>(ap);
-                const int dp1 = *reinterpret_cast<const int *>(ap + 16);
-                fa[0] = (v4i){ab(c[1], c[0], 1), ab(c[2], c[1], 1), ab(c[3], c[2], 1), ab(dp1, c[3], 1)};   // g[p' + 1]
                 fa[1] = c;
+                if (NAS >= 2) {
+                    const int dp1 = *reinterpret_cast<const int *>(ap + 16);
+                    fa[0] = (v4i){ab(c[1], c[0], 1), ab(c[2], c[1], 1), ab(c[3], c[2], 1), ab(dp1, c[3], 1)};
+                }
                 if (NAS == 3) {
                     const int dm1 = *reinterpret_cast<const int *>(ap - 4);
-                    fa[NAS - 1] = (v4i){ab(c[0], dm1, 3), ab(c[1], c[0], 3), ab(c[2], c[1], 3), ab(c[3], c[2], 3)};   // g[p' - 1]
+                    fa[2] = (v4i){ab(c[0], dm1, 3), ab(c[1], c[0], 3), ab(c[2], c[1], 3), ab(c[3], c[2], 3)};
                 }
                 rsum = dot4_ones(c[0], dot4_ones(c[1], dot4_ones(c[2], dot4_ones(c[3], rsum))));
             }
@@ -512,9 +521,11 @@ __global__ __launch_bounds__(64 * kFinishMaxQ) void wgrad_planes_finish(const in
 // 0 = not served; else the result plane edge (14 or 7)
 int planes_edge(const q8t_conv_desc *d)
 {
-    if (d->R != 3 || d->S != 3 || d->pad != 1 || (d->stride != 1 && d->stride != 2)) return 0;
+    const bool k3 = d->R == 3 && d->S == 3 && d->pad == 1 && (d->stride == 1 || d->stride == 2);
+    const bool k1 = d->R == 1 && d->S == 1 && d->pad == 0 && d->stride == 2;
+    if (!k3 && !k1) return 0;
     if (d->H != d->W || d->K % KT || d->C % CT) return 0;
-    const int P = (d->H + 2 - 3) / d->stride + 1;
+    const int P = (d->H + 2 * d->pad - d->R) / d->stride + 1;
     if ((P != 14 && P != 7) || d->H != P * d->stride) return 0;
     return P;
 }
@@ -577,6 +588,7 @@ size_t q8t_planes_wgrad_ws(const q8t_conv_desc *d)
 {
     const int P = planes_edge(d);
     if (!P) return 0;
+    if (d->R == 1) return P == 14 ? planes_ws<Shape<14, 2, 1>>(d) : planes_ws<Shape<7, 2, 1>>(d);
     if (d->stride == 1) return P == 14 ? planes_ws<Shape<14, 1>>(d) : planes_ws<Shape<7, 1>>(d);
     return P == 14 ? planes_ws<Shape<14, 2>>(d) : planes_ws<Shape<7, 2>>(d);
 }
@@ -586,6 +598,10 @@ int q8t_planes_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qpara
 {
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
     const int P = planes_edge(d);
+    if (!P) return Q8T_ERR_SHAPE;
+    if (d->R == 1)
+        return P == 14 ? launch_planes<Shape<14, 2, 1>>(d, g16, qg, x, qx, dw, acc_out, ws, st)
+                       : launch_planes<Shape<7, 2, 1>>(d, g16, qg, x, qx, dw, acc_out, ws, st);
     if (d->stride == 1)
         return P == 14 ? launch_planes<Shape<14, 1>>(d, g16, qg, x, qx, dw, acc_out, ws, st)
                        : launch_planes<Shape<7, 1>>(d, g16, qg, x, qx, dw, acc_out, ws, st);

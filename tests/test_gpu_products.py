@@ -162,6 +162,9 @@ CONV_CASES = [
     (40, 64, 28, 28, 64, 3, 3, 2, 1),    # one image range per image
     (37, 64, 7, 7, 64, 3, 3, 1, 1),      # ten image ranges, the last chunk incomplete
     (19, 64, 14, 14, 128, 3, 3, 1, 1),   # two row groups
+    (3, 64, 28, 28, 128, 1, 1, 2, 0),    # 1x1 at stride 2 -> 14x14: one tap on the (even row, even column) class
+    (6, 128, 14, 14, 64, 1, 1, 2, 0),    # 1x1 at stride 2 -> 7x7: chunks of four planes, the last one with two images
+    (33, 64, 14, 14, 64, 1, 1, 2, 0),    # ... nine image ranges
     # forward with few input channels: explicit im2col rows + GEMM
     (4, 16, 20, 20, 128, 3, 3, 1, 1),    # 144 columns -> 192, 128-wide tiles
     (8, 5, 30, 17, 64, 5, 3, 2, 2),      # non-square filter, stride 2, 75 columns -> 128
