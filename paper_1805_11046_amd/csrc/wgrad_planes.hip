@@ -46,7 +46,6 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 512;
 constexpr int KC = 256;                 // padded positions per chunk (8 K-steps of 32)
-constexpr int LEFT = 16;                // bytes before the chunk in an LDS row (margin / halo)
 constexpr int ROWP = 336;               // LDS bytes per operand row: 16 + 256 + 16 and a spare 48, so that the pitch is
                                         // 84 dwords = 20 mod 64: 16 rows of 16-byte fragments fall into 16 distinct bank groups
 constexpr int KT = 64;                  // output channels per workgroup
@@ -64,10 +63,13 @@ template <int P_, int STRIDE_, int KS_ = 3>
 struct Shape {
     static constexpr int P = P_, STRIDE = STRIDE_, KS = KS_;
     static_assert(KS == 3 || (KS == 1 && STRIDE == 2), "filters served: 3x3 at stride 1 or 2, 1x1 at stride 2");
-    static constexpr int PT = P == 14 ? 16 : 8;          // padded row pitch
+    static_assert(P == 7 || P == 14 || (P == 28 && STRIDE == 2), "result planes served: 7x7, 14x14, and 28x28 at stride 2");
+    static constexpr int PT = P == 28 ? 32 : (P == 14 ? 16 : 8);   // padded row pitch
     static constexpr int LEADC = PT - P;                 // pad columns, at the start of a row (so that position 0 is a pad)
     static constexpr int PL = PT * PT;                   // padded positions per plane
-    static constexpr int NIMG = KC / PL;                 // planes per chunk
+    static constexpr int NBAND = PL > KC ? PL / KC : 1;  // chunks per plane: a 28x28 plane goes in four bands of 8 padded rows
+    static constexpr int NIMG = NBAND > 1 ? 1 : KC / PL; // planes per chunk
+    static constexpr int LEFT = PT > 16 ? PT : 16;       // bytes before the chunk in an LDS row: margin, and the row above a band
     static constexpr int TAPS = KS * KS;
     static constexpr int NCLS = STRIDE == 1 || KS == 1 ? 1 : 4;     // parity classes of the input plane that are staged
     static constexpr int NBV = KS == 1 ? 1 : (STRIDE == 1 ? 3 : 6); // distinct input fragments per K-step
@@ -77,7 +79,7 @@ struct Shape {
     static constexpr int CLSB = CT * ROWP;               // bytes of one parity class
     static constexpr int B_BYTES = NCLS * CLSB;
     static constexpr int BUF = A_BYTES + B_BYTES;
-    static constexpr bool DB = NCLS == 1;                // two LDS buffers (four classes leave room for one)
+    static constexpr bool DB = NCLS == 1 && NBAND == 1;  // two LDS buffers (four classes leave room for one; bands keep to one)
     static constexpr int SMEM = (DB ? 2 : 1) * BUF;
     static constexpr int HALF_INTS = 4 * TAPS * 16 * 64;     // accumulators of one byte plane: [row half][channel half][tap][reg][lane]
     static constexpr int TILE_INTS = 2 * HALF_INTS;
@@ -106,6 +108,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     constexpr int P = SH::P, PT = SH::PT, PL = SH::PL, NIMG = SH::NIMG, TAPS = SH::TAPS;
     constexpr int NBV = SH::NBV, NAS = SH::NAS, WIN = SH::WIN, STRIDE = SH::STRIDE, KS = SH::KS;
+    constexpr int LEFT = SH::LEFT, NBAND = SH::NBAND, LEADC = SH::LEADC;
     constexpr int PP = P * P, WW = WIN * WIN;
     constexpr int NPART = 4;                                                // staging is spread over 4 of the 8 K-steps
 
@@ -150,32 +153,47 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
     // (the rows of 64, 32 or 16 channels of one image) go to threads 0..447 per slot, and the slots walk the channel
     // groups of an image, then the images of the chunk.  One offset pair per operand describes all of a thread's tasks
     // (a table per slot cost enough registers to spill, and a reload from scratch waits for every global load in flight).
-    constexpr int kRowThreads = 448;
-    constexpr int G_CPS = kRowThreads / P, G_SPI = KT / G_CPS;        // gradient: channels per slot, slots per image
-    constexpr int XR = KS == 1 ? P : WIN;                             // input rows staged per channel (1x1: the even ones)
-    constexpr int X_CPS = kRowThreads / XR, X_SPI = CT / X_CPS;       // input
-    static_assert(G_CPS * P == kRowThreads && X_CPS * XR == kRowThreads && G_SPI * G_CPS == KT && X_SPI * X_CPS == CT, "whole groups");
+    // A 28x28 plane goes in four bands of 8 padded rows (a chunk each): 8 gradient rows x 64 channels and 16 input
+    // rows x 32 channels are 512 tasks, one per thread; rows past the plane (the last band) are staged as zero codes.
+    constexpr int kRowThreads = NBAND > 1 ? kThreads : 448;
+    constexpr int GRB = NBAND > 1 ? KC / PT : P;                      // gradient rows per channel and chunk
+    constexpr int XRB = KS == 1 ? GRB : GRB * STRIDE;                 // input rows staged per channel and chunk (1x1: the even ones)
+    constexpr int G_CPS = kRowThreads / GRB, G_SPI = KT / G_CPS;      // gradient: channels per slot, slots per image
+    constexpr int X_CPS = kRowThreads / XRB, X_SPI = CT / X_CPS;      // input
+    static_assert(G_CPS * GRB == kRowThreads && X_CPS * XRB == kRowThreads && G_SPI * G_CPS == KT && X_SPI * X_CPS == CT, "whole groups");
     constexpr int GT = NIMG * G_SPI, XT = NIMG * X_SPI;   // row tasks per thread and chunk
     constexpr int GW = PT / 8;      // 16-byte pieces of a padded gradient row (2 * PT bytes)
-    constexpr int XWB = STRIDE * PT, XW = (XWB + 15) / 16, XSB = STRIDE * SH::LEADC;   // bytes / 16-byte pieces of an input row task, bytes before the row
+    constexpr int XWB = STRIDE * PT, XW = (XWB + 15) / 16, XSB = STRIDE * LEADC;   // bytes / 16-byte pieces of an input row task, bytes before the row
     const int rt = tid < kRowThreads ? tid : tid - kRowThreads;   // the last 64 threads repeat the first 64 tasks: no thread-dependent branch
-    const int gk0 = rt / P, gr0 = rt - gk0 * P, xc0 = rt / XR, xr0 = rt - xc0 * XR;
-    const bool rg_first = gr0 == 0, rx_first = xr0 == 0;
-    // byte offset in the image's tile / in the LDS region, of slot 0
-    const int rg_off0 = (gk0 * PP + gr0 * P - (gr0 ? SH::LEADC : 0)) * 2, rg_lds0 = gk0 * ROWP + LEFT + gr0 * PT;
-    const int rx_off0 = xc0 * WW + xr0 * (KS == 1 ? 2 * WIN : WIN) - (xr0 ? XSB : 0);
+    const int gk0 = rt / GRB, gr0 = rt - gk0 * GRB, xc0 = rt / XRB, xr0 = rt - xc0 * XRB;
+    // LDS byte offset of slot 0's row (the same in every band)
+    const int rg_lds0 = gk0 * ROWP + LEFT + gr0 * PT;
     const int rx_lds0 = STRIDE == 1 || KS == 1
                             ? xc0 * ROWP + LEFT + xr0 * PT
                             : ((xr0 & 1) ? 2 * SH::CLSB : 0) + xc0 * ROWP + LEFT + (xr0 >> 1) * PT;   // even-column class of the row's parity
     auto rg_img = [](int i) { return i / G_SPI; };
-    auto rg_off = [&](int i) { return rg_off0 + (i % G_SPI) * G_CPS * PP * 2; };
     auto rg_lds = [&](int i) { return rg_lds0 + (i / G_SPI) * PL + (i % G_SPI) * G_CPS * ROWP; };
     auto rx_img = [](int i) { return i / X_SPI; };
-    auto rx_off = [&](int i) { return rx_off0 + (i % X_SPI) * X_CPS * WW; };
     auto rx_lds = [&](int i) { return rx_lds0 + (i / X_SPI) * PL + (i % X_SPI) * X_CPS * ROWP; };
+    // plane row of a task in band b (gradient) / input row; a row past the plane has nothing to load
+    auto g_row = [&](int b) { return b * GRB + gr0; };
+    auto x_row = [&](int b) { return (KS == 1 ? 2 : 1) * (b * XRB + xr0); };
+    // byte offset in the image's tile: LEADC values (XSB bytes) before the row, but for the first row of a plane
+    const int rg_off0 = (gk0 * PP + gr0 * P - (gr0 ? LEADC : 0)) * 2;                       // band 0, slot 0
+    const int rx_off0 = xc0 * WW + x_row(0) * WIN - (xr0 ? XSB : 0);
+    auto rg_off = [&](int i, int b) {
+        if (NBAND == 1) return rg_off0 + (i % G_SPI) * G_CPS * PP * 2;
+        const int r = g_row(b) < P ? g_row(b) : 0;
+        return ((gk0 + (i % G_SPI) * G_CPS) * PP + r * P - (r ? LEADC : 0)) * 2;
+    };
+    auto rx_off = [&](int i, int b) {
+        if (NBAND == 1) return rx_off0 + (i % X_SPI) * X_CPS * WW;
+        const int r = x_row(b) < WIN ? x_row(b) : 0;
+        return (xc0 + (i % X_SPI) * X_CPS) * WW + r * WIN - (r ? XSB : 0);
+    };
 
     const int img0 = kr * g.ipr, img1 = min(g.N, img0 + g.ipr);
-    const int units = (img1 - img0 + NIMG - 1) / NIMG;
+    const int units = NBAND > 1 ? (img1 - img0) * NBAND : (img1 - img0 + NIMG - 1) / NIMG;
 
     v16i acc[TAPS];
 #pragma unroll
@@ -190,7 +208,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
     const uint4 *gsrc = reinterpret_cast<const uint4 *>(g16 + ((int64_t)img0 * g.K + rg * KT) * PP);
     const uint4 *xsrc = reinterpret_cast<const uint4 *>(x + ((int64_t)img0 * g.C + cg * CT) * WW);
     const int64_t gstep = (int64_t)g.K * PP * 2 / 16, xstep = (int64_t)g.C * WW / 16;   // 16-byte pieces per image
-    int l_img = img0;                      // first image of the chunk that is being loaded
+    int l_img = img0, l_band = 0;          // first image of the chunk that is being loaded, its band
     // The rows that write_part(., part) puts into LDS, for the chunk starting at image l_img.  Every load is issued
     // unconditionally (straight-line code lets the compiler wait for exactly the loads it needs instead of for all of
     // them): an image past the range re-reads the chunk's first image and is replaced by zero codes.  Every address
@@ -200,8 +218,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
 #pragma unroll
             for (int i = 0; i < GT; ++i)
                 if (i % NPART == part) {
-                    const bool have = rg_img(i) == 0 || l_img + rg_img(i) < img1;
-                    const uint8_t *src = reinterpret_cast<const uint8_t *>(gsrc) + (have ? rg_img(i) * gstep * 16 : 0) + rg_off(i);
+                    const bool img_ok = rg_img(i) == 0 || l_img + rg_img(i) < img1;
+                    const bool have = img_ok && g_row(l_band) < P;
+                    const uint8_t *src = reinterpret_cast<const uint8_t *>(gsrc) + (img_ok ? rg_img(i) * gstep * 16 : 0) + rg_off(i, l_band);
 #pragma unroll
                     for (int w = 0; w < GW; ++w) {
                         uint4 v;
@@ -214,8 +233,9 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
 #pragma unroll
             for (int i = 0; i < XT; ++i)
                 if ((i + 2) % NPART == part) {
-                    const bool have = rx_img(i) == 0 || l_img + rx_img(i) < img1;
-                    const uint8_t *src = reinterpret_cast<const uint8_t *>(xsrc) + (have ? rx_img(i) * xstep * 16 : 0) + rx_off(i);
+                    const bool img_ok = rx_img(i) == 0 || l_img + rx_img(i) < img1;
+                    const bool have = img_ok && x_row(l_band) < WIN;
+                    const uint8_t *src = reinterpret_cast<const uint8_t *>(xsrc) + (img_ok ? rx_img(i) * xstep * 16 : 0) + rx_off(i, l_band);
 #pragma unroll
                     for (int w = 0; w < XW; ++w) {
                         uint4 v = make_uint4(0u, 0u, 0u, 0u);
@@ -234,14 +254,25 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
     };
     // the chunk after this one, or this one again when it is the last (its reload is never used)
     auto next_chunk = [&]() {
-        const bool more = l_img + NIMG < img1;
-        gsrc += more ? NIMG * gstep : 0;
-        xsrc += more ? NIMG * xstep : 0;
-        l_img += more ? NIMG : 0;
+        if (NBAND > 1) {
+            const bool last_band = l_band + 1 == NBAND;
+            const bool more = !last_band || l_img + 1 < img1;
+            const bool step_img = more && last_band;
+            l_band = more ? (last_band ? 0 : l_band + 1) : l_band;
+            gsrc += step_img ? gstep : 0;
+            xsrc += step_img ? xstep : 0;
+            l_img += step_img ? 1 : 0;
+        } else {
+            const bool more = l_img + NIMG < img1;
+            gsrc += more ? NIMG * gstep : 0;
+            xsrc += more ? NIMG * xstep : 0;
+            l_img += more ? NIMG : 0;
+        }
     };
     auto abu = [](uint32_t hi, uint32_t lo, int n) { return __builtin_amdgcn_alignbyte(hi, lo, n); };
-    auto write_part = [&](int buf, int part) {
+    auto write_part = [&](int buf, int part, int band) {
         uint8_t *A = smem + buf * SH::BUF, *B = A + SH::A_BYTES;
+        const bool rg_first = g_row(band) == 0, rx_first = x_row(band) == 0;
         {
 #pragma unroll
             for (int i = 0; i < GT; ++i)
@@ -255,11 +286,14 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
                         w[4 * q + 3] = rgr[i * GW + q].w;
                     }
                     if (rg_first) {   // loaded from the row's own start: move up by LEADC values
+                        constexpr int D = LEADC / 2;   // whole dwords (LEADC = 1: half a dword)
 #pragma unroll
-                        for (int q = 4 * GW - 1; q > 0; --q) w[q] = SH::LEADC == 2 ? w[q - 1] : abu(w[q], w[q - 1], 2);
-                        if (SH::LEADC == 1) w[0] = w[0] << 16;
+                        for (int q = 4 * GW - 1; q > 0; --q) w[q] = LEADC == 1 ? abu(w[q], w[q - 1], 2) : (q >= D ? w[q - D] : w[q]);
+                        if (LEADC == 1) w[0] = w[0] << 16;
                     }
-                    w[0] = SH::LEADC == 2 ? a_pad : (w[0] & 0xFFFF0000u) | (a_pad & 0xFFFFu);
+                    if (LEADC == 1) w[0] = (w[0] & 0xFFFF0000u) | (a_pad & 0xFFFFu);
+#pragma unroll
+                    for (int q = 0; q < LEADC / 2; ++q) w[q] = a_pad;
                     uint32_t hi[2 * GW], lo[2 * GW];
 #pragma unroll
                     for (int q = 0; q < 2 * GW; ++q) {
@@ -267,9 +301,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
                         hi[q] = __builtin_amdgcn_perm(d1, d0, 0x07050301u);
                         lo[q] = __builtin_amdgcn_perm(d1, d0, 0x06040200u);
                     }
-                    if (GW == 2) {
-                        *reinterpret_cast<uint4 *>(A + rg_lds(i)) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-                        *reinterpret_cast<uint4 *>(A + rg_lds(i) + KT * ROWP) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+                    if (GW >= 2) {
+#pragma unroll
+                        for (int h = 0; h < GW / 2; ++h) {
+                            *reinterpret_cast<uint4 *>(A + rg_lds(i) + 16 * h) = make_uint4(hi[4 * h], hi[4 * h + 1], hi[4 * h + 2], hi[4 * h + 3]);
+                            *reinterpret_cast<uint4 *>(A + rg_lds(i) + KT * ROWP + 16 * h) = make_uint4(lo[4 * h], lo[4 * h + 1], lo[4 * h + 2], lo[4 * h + 3]);
+                        }
                     } else {
                         *reinterpret_cast<uint2 *>(A + rg_lds(i)) = make_uint2(hi[0], hi[1]);
                         *reinterpret_cast<uint2 *>(A + rg_lds(i) + KT * ROWP) = make_uint2(lo[0], lo[1]);
@@ -291,11 +328,12 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
                     constexpr int LW = XWB / 4;  // dwords loaded for the row
                     constexpr int NW = PT / 4;   // dwords of a padded row in LDS
                     if (rx_first) {   // loaded from the row's own start: move up by the bytes before a row
+                        constexpr int D = XSB / 4;     // whole dwords (XSB = 1, 2: part of one)
 #pragma unroll
-                        for (int q = LW - 1; q > 0; --q) w[q] = XSB == 4 ? w[q - 1] : abu(w[q], w[q - 1], 4 - XSB);
-                        w[0] = XSB == 4 ? 0u : w[0] << (8 * XSB);
+                        for (int q = LW - 1; q > 0; --q) w[q] = XSB % 4 ? abu(w[q], w[q - 1], 4 - XSB % 4) : (q >= D ? w[q - D] : w[q]);
+                        w[0] = XSB % 4 ? w[0] << (8 * (XSB % 4)) : w[0];
                     }
-                    constexpr uint32_t keep = SH::LEADC == 2 ? 0xFFFF0000u : 0xFFFFFF00u;
+                    constexpr uint32_t keep = LEADC == 4 ? 0u : (LEADC == 2 ? 0xFFFF0000u : 0xFFFFFF00u);   // bytes of the first dword that are data
                     if (STRIDE == 1) {
                         w[0] = (w[0] & keep) | (b_pad & ~keep);
                         if (NW == 4) *reinterpret_cast<uint4 *>(B + rx_lds(i)) = make_uint4(w[0], w[1], w[2], w[3]);
@@ -309,9 +347,24 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
                         }
                         ev[0] = (ev[0] & keep) | (b_pad & ~keep);
                         od[0] = (od[0] & keep) | (b_pad & ~keep);
-                        if (NW == 4) {
-                            *reinterpret_cast<uint4 *>(B + rx_lds(i)) = make_uint4(ev[0], ev[1], ev[2], ev[3]);
-                            if (KS != 1) *reinterpret_cast<uint4 *>(B + rx_lds(i) + SH::CLSB) = make_uint4(od[0], od[1], od[2], od[3]);
+                        if (NBAND > 1 && KS != 1 && xr0 == XRB - 1) {
+                            // the last odd input row of a band is the row above the next band: before it is overwritten, its
+                            // two class rows move to the margin in front of the chunk (first band of a plane: they hold the
+                            // zero codes of a row past the previous plane, or of the initial fill)
+#pragma unroll
+                            for (int h = 0; h < 2 * (NW / 4); ++h) {
+                                const int o = rx_lds(i) + (h & 1) * SH::CLSB + 16 * (h >> 1);
+                                *reinterpret_cast<uint4 *>(B + o - GRB * PT) = *reinterpret_cast<const uint4 *>(B + o);
+                            }
+                        }
+                        if (NW >= 4) {
+#pragma unroll
+                            for (int h = 0; h < NW / 4; ++h) {
+                                *reinterpret_cast<uint4 *>(B + rx_lds(i) + 16 * h) = make_uint4(ev[4 * h], ev[4 * h + 1], ev[4 * h + 2], ev[4 * h + 3]);
+                                if (KS != 1)
+                                    *reinterpret_cast<uint4 *>(B + rx_lds(i) + SH::CLSB + 16 * h) =
+                                        make_uint4(od[4 * h], od[4 * h + 1], od[4 * h + 2], od[4 * h + 3]);
+                            }
                         } else {
                             *reinterpret_cast<uint2 *>(B + rx_lds(i)) = make_uint2(ev[0], ev[1]);
                             if (KS != 1) *reinterpret_cast<uint2 *>(B + rx_lds(i) + SH::CLSB) = make_uint2(od[0], od[1]);
@@ -379,18 +432,18 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
                 rsum = dot4_ones(c[0], dot4_ones(c[1], dot4_ones(c[2], dot4_ones(c[3], rsum))));
             }
             if (stage && (ks & 1) == 0) {
-                write_part(buf ^ 1, ks >> 1);
+                write_part(buf ^ 1, ks >> 1, 0);
                 load_part(ks >> 1);
             }
             {
 #pragma unroll
                 for (int i = 0; i < SH::CSW; ++i) {
-                    const v4i fb = read_b(Br + cs_off[i] + ks * 32, PT == 16);
+                    const v4i fb = read_b(Br + cs_off[i] + ks * 32, PT >= 16);
                     csum[i] = dot4_ones(fb[0], dot4_ones(fb[1], dot4_ones(fb[2], dot4_ones(fb[3], csum[i]))));
                 }
 #pragma unroll
                 for (int v = 0; v < NBV; ++v) {
-                    const v4i fb = read_b(Br + SH::bcls(v) * SH::CLSB + ks * 32 + SH::boff(v), PT == 16 || SH::boff(v) == 0);
+                    const v4i fb = read_b(Br + SH::bcls(v) * SH::CLSB + ks * 32 + SH::boff(v), PT >= 16 || SH::boff(v) == 0);
 #pragma unroll
                     for (int t = 0; t < TAPS; ++t)
                         if (SH::bvar(t) == v)
@@ -407,7 +460,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
             for (int part = 0; part < NPART; ++part) load_part(part);
             next_chunk();
 #pragma unroll
-            for (int part = 0; part < NPART; ++part) write_part(0, part);
+            for (int part = 0; part < NPART; ++part) write_part(0, part, 0);
 #pragma unroll
             for (int part = 0; part < NPART; ++part) load_part(part);
             next_chunk();
@@ -428,7 +481,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_planes(const int16_t *__restri
         }
         for (int u = 0; u < units; ++u) {
 #pragma unroll
-            for (int part = 0; part < NPART; ++part) write_part(0, part);
+            for (int part = 0; part < NPART; ++part) write_part(0, part, u & (NBAND - 1));   // a range is whole planes: chunk u is band u % NBAND
 #pragma unroll
             for (int part = 0; part < NPART; ++part) load_part(part);
             next_chunk();
@@ -490,7 +543,7 @@ __global__ __launch_bounds__(64 * kFinishMaxQ) void wgrad_planes_finish(const in
     for (int kr = quarter; kr < g.S; kr += nq) {
         const int *p = partial + ((int64_t)(kr * g.nrg + rg) * g.ncg + cg) * SH::PART_INTS;
         const int nimg = min(g.N, (kr + 1) * g.ipr) - kr * g.ipr;
-        const int64_t Kp = (int64_t)((nimg + SH::NIMG - 1) / SH::NIMG) * KC;
+        const int64_t Kp = (int64_t)((nimg + SH::NIMG - 1) / SH::NIMG) * SH::NBAND * KC;
         const v4i hi = *reinterpret_cast<const v4i *>(p + idx), lo = *reinterpret_cast<const v4i *>(p + SH::HALF_INTS + idx);
         const v4i csv = *reinterpret_cast<const v4i *>(p + SH::TILE_INTS + bv * CT + ch_l);
         const int64_t rsh = p[SH::TILE_INTS + NBV * CT + row_l], rsl = p[SH::TILE_INTS + NBV * CT + KT + row_l];
@@ -526,7 +579,7 @@ int planes_edge(const q8t_conv_desc *d)
     if (!k3 && !k1) return 0;
     if (d->H != d->W || d->K % KT || d->C % CT) return 0;
     const int P = (d->H + 2 * d->pad - d->R) / d->stride + 1;
-    if ((P != 14 && P != 7) || d->H != P * d->stride) return 0;
+    if ((P != 14 && P != 7 && !(P == 28 && d->stride == 2)) || d->H != P * d->stride) return 0;
     return P;
 }
 
@@ -542,7 +595,7 @@ PGeom planes_geom(const q8t_conv_desc *d)
     if (want < 1) want = 1;
     if (want > chunks) want = chunks;
     int cpr = (chunks + want - 1) / want;      // chunks per range
-    if (cpr > 511) cpr = 511;                  // 2^14 * 256 * 511 < 2^31: the 32-bit partial sums cannot overflow
+    if (cpr > 511 / SH::NBAND) cpr = 511 / SH::NBAND;   // 2^14 * 256 * 511 < 2^31: the 32-bit partial sums cannot overflow
     g.ipr = cpr * SH::NIMG;
     g.S = (d->N + g.ipr - 1) / g.ipr;
     return g;
@@ -588,6 +641,7 @@ size_t q8t_planes_wgrad_ws(const q8t_conv_desc *d)
 {
     const int P = planes_edge(d);
     if (!P) return 0;
+    if (P == 28) return d->R == 1 ? planes_ws<Shape<28, 2, 1>>(d) : planes_ws<Shape<28, 2>>(d);
     if (d->R == 1) return P == 14 ? planes_ws<Shape<14, 2, 1>>(d) : planes_ws<Shape<7, 2, 1>>(d);
     if (d->stride == 1) return P == 14 ? planes_ws<Shape<14, 1>>(d) : planes_ws<Shape<7, 1>>(d);
     return P == 14 ? planes_ws<Shape<14, 2>>(d) : planes_ws<Shape<7, 2>>(d);
@@ -599,6 +653,9 @@ int q8t_planes_wgrad(const q8t_conv_desc *d, const int16_t *g16, const q8t_qpara
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
     const int P = planes_edge(d);
     if (!P) return Q8T_ERR_SHAPE;
+    if (P == 28)
+        return d->R == 1 ? launch_planes<Shape<28, 2, 1>>(d, g16, qg, x, qx, dw, acc_out, ws, st)
+                         : launch_planes<Shape<28, 2>>(d, g16, qg, x, qx, dw, acc_out, ws, st);
     if (d->R == 1)
         return P == 14 ? launch_planes<Shape<14, 2, 1>>(d, g16, qg, x, qx, dw, acc_out, ws, st)
                        : launch_planes<Shape<7, 2, 1>>(d, g16, qg, x, qx, dw, acc_out, ws, st);

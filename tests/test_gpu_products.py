@@ -165,6 +165,9 @@ CONV_CASES = [
     (3, 64, 28, 28, 128, 1, 1, 2, 0),    # 1x1 at stride 2 -> 14x14: one tap on the (even row, even column) class
     (6, 128, 14, 14, 64, 1, 1, 2, 0),    # 1x1 at stride 2 -> 7x7: chunks of four planes, the last one with two images
     (33, 64, 14, 14, 64, 1, 1, 2, 0),    # ... nine image ranges
+    (2, 64, 56, 56, 128, 3, 3, 2, 1),    # stride 2 -> 28x28: four bands of 8 rows per plane, the last one half empty
+    (5, 128, 56, 56, 64, 3, 3, 2, 1),    # ... two channel groups, image ranges of unequal length
+    (3, 128, 56, 56, 64, 1, 1, 2, 0),    # ... one tap
     # forward with few input channels: explicit im2col rows + GEMM
     (4, 16, 20, 20, 128, 3, 3, 1, 1),    # 144 columns -> 192, 128-wide tiles
     (8, 5, 30, 17, 64, 5, 3, 2, 2),      # non-square filter, stride 2, 75 columns -> 128
