@@ -1,6 +1,7 @@
-// Weight gradient of 3x3 convolutions whose result planes are 14x14 or 7x7 (stride 1 or 2, pad 1):
+// Weight gradient of 3x3 convolutions whose result planes are 14x14 or 7x7 (stride 1 or 2, pad 1) or 28x28 (stride 2):
 //   dW[k,c,r,s] = sum_{n,p,q} g16[n,k,p,q] * x8[n,c,p*st+r-1,q*st+s-1]      (Section 4, eq. (grad_weight))
-// with the 16-bit copy of the gradient (Sections 1, 7) and the 8-bit layer input, exact in integers.
+// with the 16-bit copy of the gradient (Sections 1, 7) and the 8-bit layer input, exact in integers; and of the 1x1
+// convolution at stride 2 without padding on the same result planes (one tap, x8[n,c,2p,2q]).
 //
 // GEMM view: rows = output channel k (two byte planes: s = 256*hi + lo + 128), cols = (input
 // channel c, tap), reduction = (image, position).  Both operands are contiguous along the
@@ -11,7 +12,9 @@
 // zero point.  A chunk of the reduction is 256 such padded positions (one 14x14 plane or four 7x7
 // planes) = 8 MFMA K-steps of 32.  In these coordinates a filter tap is a byte offset; the pad
 // before one row is the pad after the previous one, and the pad rows of one plane separate it from
-// the next one.  Staging writes data positions only, the pads are set once per workgroup.
+// the next one.  Staging writes data positions only, the pads are set once per workgroup.  A 28x28 plane (32x32
+// padded) is four chunks: a chunk is a band of 8 padded rows, the rows of the last band that lie past the plane are
+// staged as zero codes, and the input row above a band is carried over from the previous band inside LDS.
 //   * the vertical tap is an offset of +-pitch on the input operand (aligned 16-byte LDS reads for
 //     pitch 16, 8-byte reads for pitch 8);
 //   * the horizontal tap is moved to the gradient operand (p' = p + s - 1), whose fragment is
