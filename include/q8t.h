@@ -206,6 +206,36 @@ int q8t_qconv_dgrad_relu_sum(const q8t_conv_desc *desc /* host */, const int8_t 
                              const int8_t *qw, const q8t_qparams *pw, const float *other, const float *act,
                              float *dx, void *ws, void *stream);
 
+/* Filters packed ahead of the products.  The forward and the layer-gradient product (Section 4, eqs. (forward),
+ * (grad_layer)) of most layer shapes read the 8-bit filter in a kernel-specific order and need the sum of every
+ * output channel's codes for the zero-point correction; by default each product call makes both in a small launch of
+ * its own in front of the product.  The weights of a training step are quantized once, so a caller can have the
+ * filters of all its layers packed by ONE launch, right after the weights are quantized, and hand each product its
+ * packed filter.  Results are bit-identical with and without.
+ *   q8t_qconv_pack_size(desc, which): bytes of the packed filter for the forward (which = 0) or layer-gradient (1)
+ *     product of this shape; 0 where the kernel that serves the shape packs nothing ahead (then pass packed = NULL).
+ *   q8t_qconv_pack_multi: n jobs; descs / which: host arrays; qw[i]: device, the layer's codes [K,C,R,S]; packed[i]:
+ *     device buffer of q8t_qconv_pack_size(&descs[i], which[i]) bytes, 16-byte aligned, owned by the caller and left
+ *     alone by the library after the call; jobs with a size of 0 or packed[i] = NULL are skipped.
+ *   the _packed products: as their namesakes, with packed = the buffer made for the same desc, which and codes (or
+ *     NULL: behave exactly like the namesake).  Where the operands' alignment sends a call down another kernel than the
+ *     shape alone would, the buffer is ignored and the filter is packed in the workspace as usual.  ws as for the
+ *     namesake.  A buffer made from other codes or another shape gives wrong results without an error.
+ * Errors: Q8T_ERR_NULL, Q8T_ERR_WORKSPACE (misaligned packed buffer), and those of the namesakes. */
+size_t q8t_qconv_pack_size(const q8t_conv_desc *desc /* host */, int which);
+int q8t_qconv_pack_multi(int n, const q8t_conv_desc *descs /* host */, const int *which /* host */,
+                         const int8_t *const *qw /* host array of device pointers */,
+                         void *const *packed /* host array of device pointers */, void *stream);
+int q8t_qconv_fwd_bn_stats_packed(const q8t_conv_desc *desc /* host */, const int8_t *qx, const q8t_qparams *px,
+                                  const int8_t *qw, const q8t_qparams *pw, const void *packed, float *y,
+                                  int32_t *acc_out, float *stats_out, void *ws, void *stream);
+int q8t_qconv_dgrad_packed(const q8t_conv_desc *desc /* host */, const int8_t *qdy, const q8t_qparams *pg,
+                           const int8_t *qw, const q8t_qparams *pw, const void *packed, float *dx,
+                           int32_t *acc_out, void *ws, void *stream);
+int q8t_qconv_dgrad_relu_sum_packed(const q8t_conv_desc *desc /* host */, const int8_t *qdy, const q8t_qparams *pg,
+                                    const int8_t *qw, const q8t_qparams *pw, const void *packed, const float *other,
+                                    const float *act, float *dx, void *ws, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Range Batch-Norm over NCHW (Section 3, eq. (range); FC activations: H = W = 1).
  * Per channel c over its n = N*H*W values:

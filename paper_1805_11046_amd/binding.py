@@ -64,6 +64,11 @@ _SIGS = {
     "q8t_qconv_dgrad": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "q8t_qconv_dgrad_relu_sum": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "q8t_qconv_wgrad": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_qconv_pack_size": (_sz, [C.POINTER(ConvDesc), _i]),
+    "q8t_qconv_pack_multi": (_i, [_i, C.POINTER(ConvDesc), C.POINTER(C.c_int), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), _vp]),
+    "q8t_qconv_fwd_bn_stats_packed": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_qconv_dgrad_packed": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "q8t_qconv_dgrad_relu_sum_packed": (_i, [C.POINTER(ConvDesc), _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "q8t_range_bn_workspace_size": (_sz, [_i, _i, _i, _i]),
     "q8t_range_bn_fwd": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp, _vp, _vp, _vp]),
     "q8t_range_bn_bwd": (_i, [_vp, _vp, _vp, _i, _i, _i, _i, _vp, _f, _vp, _vp, _vp, _vp, _vp]),
@@ -345,8 +350,40 @@ def qconv_fwd(d, qx, px, qw, pw, want_acc=False, out=None, ws=None):
                  want_acc, out, ws)
 
 
-def qconv_fwd_bn_stats(d, qx, px, qw, pw, want_acc=False, out=None, stats_out=None, ws=None):
-    """Forward convolution + Range BN statistics of its result.  Returns (y, acc or None, stats[3,K])."""
+def qconv_pack_size(d, which):
+    """Bytes of the packed filter for the forward (0) / layer-gradient (1) product of this shape; 0: nothing to pack."""
+    return int(_lib.q8t_qconv_pack_size(C.byref(d), int(which)))
+
+
+def qconv_pack_multi(jobs, out=None):
+    """jobs: list of (desc, which, qw).  Packs the filters of all of them in one launch and returns one buffer per job
+    (None where the shape packs nothing ahead) for the packed= argument of the products.  out: buffers to reuse."""
+    n = len(jobs)
+    if n == 0:
+        return []
+    descs = (ConvDesc * n)(*[j[0] for j in jobs])
+    which = (C.c_int * n)(*[int(j[1]) for j in jobs])
+    bufs = []
+    for i, (d, w, qw) in enumerate(jobs):
+        _dev(qw)
+        assert tuple(qw.shape) == (d.K, d.C, d.R, d.S) and qw.dtype == torch.int8
+        size = qconv_pack_size(d, w)
+        if size == 0:
+            bufs.append(None)
+        elif out is not None and out[i] is not None:
+            assert out[i].numel() >= size and out[i].dtype == torch.uint8
+            bufs.append(out[i])
+        else:
+            bufs.append(torch.empty(size, dtype=torch.uint8, device=qw.device))
+    qws = (C.c_void_p * n)(*[_ptr(j[2]) for j in jobs])
+    pks = (C.c_void_p * n)(*[_ptr(b) for b in bufs])
+    _check(_lib.q8t_qconv_pack_multi(n, descs, which, qws, pks, _stream()), "q8t_qconv_pack_multi")
+    return bufs
+
+
+def qconv_fwd_bn_stats(d, qx, px, qw, pw, want_acc=False, out=None, stats_out=None, ws=None, packed=None):
+    """Forward convolution + Range BN statistics of its result.  Returns (y, acc or None, stats[3,K]).
+    packed: the layer's filter from qconv_pack_multi (same desc, which = 0, same codes)."""
     _dev(qx), _dev(qw)
     assert tuple(qx.shape) == (d.N, d.C, d.H, d.W) and tuple(qw.shape) == (d.K, d.C, d.R, d.S)
     dev = qx.device
@@ -355,19 +392,33 @@ def qconv_fwd_bn_stats(d, qx, px, qw, pw, want_acc=False, out=None, stats_out=No
     acc = torch.empty(shape, dtype=torch.int32, device=dev) if want_acc else None
     stats = stats_out if stats_out is not None else torch.empty((3, d.K), dtype=torch.float32, device=dev)
     ws = ws if ws is not None else workspace(_lib.q8t_qconv_fwd_bn_stats_workspace_size(C.byref(d)), dev)
-    _check(_lib.q8t_qconv_fwd_bn_stats(C.byref(d), _ptr(qx), _ptr(px), _ptr(qw), _ptr(pw), _ptr(y), _ptr(acc),
-                                       _ptr(stats), _ptr(ws), _stream()), "q8t_qconv_fwd_bn_stats")
+    if packed is not None:
+        _check(_lib.q8t_qconv_fwd_bn_stats_packed(C.byref(d), _ptr(qx), _ptr(px), _ptr(qw), _ptr(pw), _ptr(packed), _ptr(y),
+                                                  _ptr(acc), _ptr(stats), _ptr(ws), _stream()), "q8t_qconv_fwd_bn_stats_packed")
+    else:
+        _check(_lib.q8t_qconv_fwd_bn_stats(C.byref(d), _ptr(qx), _ptr(px), _ptr(qw), _ptr(pw), _ptr(y), _ptr(acc),
+                                           _ptr(stats), _ptr(ws), _stream()), "q8t_qconv_fwd_bn_stats")
     return y, acc, stats
 
 
-def qconv_dgrad(d, qdy, pg, qw, pw, want_acc=False, out=None, ws=None):
+def qconv_dgrad(d, qdy, pg, qw, pw, want_acc=False, out=None, ws=None, packed=None):
+    """packed: the layer's filter from qconv_pack_multi (same desc, which = 1, same codes)."""
     _dev(qdy), _dev(qw)
     assert tuple(qdy.shape) == (d.N, d.K, d.P, d.Q) and tuple(qw.shape) == (d.K, d.C, d.R, d.S)
+    if packed is not None:
+        dev = qdy.device
+        shape = (d.N, d.C, d.H, d.W)
+        dx = out if out is not None else torch.empty(shape, dtype=torch.float32, device=dev)
+        acc = torch.empty(shape, dtype=torch.int32, device=dev) if want_acc else None
+        ws = ws if ws is not None else workspace(_lib.q8t_qconv_workspace_size(C.byref(d), 1), dev)
+        _check(_lib.q8t_qconv_dgrad_packed(C.byref(d), _ptr(qdy), _ptr(pg), _ptr(qw), _ptr(pw), _ptr(packed), _ptr(dx), _ptr(acc),
+                                           _ptr(ws), _stream()), "q8t_qconv_dgrad_packed")
+        return dx, acc
     return _conv(_lib.q8t_qconv_dgrad, "q8t_qconv_dgrad", d, qdy, pg, qw, pw, (d.N, d.C, d.H, d.W), 1,
                  torch.int32, want_acc, out, ws)
 
 
-def qconv_dgrad_relu_sum(d, qdy, pg, qw, pw, other, act, out=None, ws=None):
+def qconv_dgrad_relu_sum(d, qdy, pg, qw, pw, other, act, out=None, ws=None, packed=None):
     """act > 0 ? dgrad + other : 0 (other may be None): the layer gradient of a residual block's first convolution
     with the end of the block's backward pass in its epilogue.  Returns dx."""
     _dev(qdy), _dev(qw), _dev(act)
@@ -379,8 +430,12 @@ def qconv_dgrad_relu_sum(d, qdy, pg, qw, pw, other, act, out=None, ws=None):
         assert tuple(other.shape) == shape and other.dtype == torch.float32 and other.is_contiguous()
     dx = out if out is not None else torch.empty(shape, dtype=torch.float32, device=qdy.device)
     ws = ws if ws is not None else workspace(_lib.q8t_qconv_workspace_size(C.byref(d), 1), qdy.device)
-    _check(_lib.q8t_qconv_dgrad_relu_sum(C.byref(d), _ptr(qdy), _ptr(pg), _ptr(qw), _ptr(pw), _ptr(other), _ptr(act), _ptr(dx),
-                                         _ptr(ws), _stream()), "q8t_qconv_dgrad_relu_sum")
+    if packed is not None:
+        _check(_lib.q8t_qconv_dgrad_relu_sum_packed(C.byref(d), _ptr(qdy), _ptr(pg), _ptr(qw), _ptr(pw), _ptr(packed), _ptr(other),
+                                                    _ptr(act), _ptr(dx), _ptr(ws), _stream()), "q8t_qconv_dgrad_relu_sum_packed")
+    else:
+        _check(_lib.q8t_qconv_dgrad_relu_sum(C.byref(d), _ptr(qdy), _ptr(pg), _ptr(qw), _ptr(pw), _ptr(other), _ptr(act), _ptr(dx),
+                                             _ptr(ws), _stream()), "q8t_qconv_dgrad_relu_sum")
     return dx
 
 

@@ -1,7 +1,10 @@
 // C-ABI entry points of the product calls: argument checks on the host, then dispatch to the
 // specialised kernel for the shape if there is one, else to the general kernel.
 #include "q8t_common.h"
+#include <vector>
+
 #include "q8t_internal.h"
+#include "repack.h"
 
 namespace {
 
@@ -57,6 +60,30 @@ bool lattice_forward(const q8t_conv_desc *d, q8t_conv_desc *sub)
     return q8t_fast_conv_ws(0, sub) != 0;   // the shape is one the register-tile kernel takes
 }
 size_t lattice_codes_bytes(const q8t_conv_desc *sub) { return ((size_t)sub->N * sub->C * sub->H * sub->W + 255) & ~(size_t)255; }
+
+// The layout (repack.h) in which the forward (which = 0) or layer-gradient (1) product of this shape reads its filter
+// when its operands are aligned, decided by the shape alone and in the order the products route; Q8T_PACK_NONE: the
+// path that serves the shape has no filter pre-pass to take out.
+int pack_layout(const q8t_conv_desc *d, int which)
+{
+    if (!d || which < 0 || which > 1 || q8t_conv_reduction_check(which, d)) return Q8T_PACK_NONE;
+    q8t_conv_desc sub;
+    if (which == 0 && lattice_forward(d, &sub)) return Q8T_PACK_TILE64;   // the same filter layout as on the full shape
+    const int w = q8t_wide_conv_pack_layout(which, d);
+    if (w != Q8T_PACK_NONE) return w;
+    return q8t_fast_conv_ws(which, d) ? Q8T_PACK_TILE64 : Q8T_PACK_NONE;
+}
+// the packed filter for a branch that reads layout `want`, if the caller's buffer holds that one
+// the caller's packed filter for the register-tile kernel / for the wide-tile kernel, if it holds that layout
+const void *packed_tile64(const void *packed, const q8t_conv_desc *d, int which)
+{
+    return packed && pack_layout(d, which) == Q8T_PACK_TILE64 ? packed : nullptr;
+}
+const void *packed_wide(const void *packed, const q8t_conv_desc *d, int which)
+{
+    const int l = packed ? pack_layout(d, which) : Q8T_PACK_NONE;
+    return l == Q8T_PACK_WIDE256 || l == Q8T_PACK_WIDE128 ? packed : nullptr;
+}
 
 }  // namespace
 
@@ -122,8 +149,8 @@ size_t q8t_qconv_workspace_size(const q8t_conv_desc *desc, int which)
     return g > f ? g : f;
 }
 
-int q8t_qconv_fwd(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams *px, const int8_t *qw,
-                  const q8t_qparams *pw, float *y, int32_t *acc_out, void *ws, void *stream)
+static int qconv_fwd_impl(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams *px, const int8_t *qw,
+                          const q8t_qparams *pw, float *y, int32_t *acc_out, void *ws, void *stream, const void *packed)
 {
     if (!desc || !qx || !px || !qw || !pw || (!y && !acc_out)) return Q8T_ERR_NULL;
     const int rc = q8t_conv_reduction_check(0, desc);
@@ -135,19 +162,27 @@ int q8t_qconv_fwd(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams
         if (q8t_fast_conv_supported(0, &sub, codes, qw, y, acc_out)) {
             const int rs = q8t_subsample_codes(qx, desc->N, desc->C, desc->H, desc->W, desc->stride, codes, (hipStream_t)stream);
             if (rs) return rs;
-            return q8t_fast_conv(0, &sub, codes, px, qw, pw, y, acc_out, nullptr, ws2, (hipStream_t)stream);
+            return q8t_fast_conv(0, &sub, codes, px, qw, pw, y, acc_out, nullptr, ws2, (hipStream_t)stream, nullptr,
+                                 packed_tile64(packed, desc, 0));
         }
     }
     if (q8t_wide_conv_supported(0, desc, qx, y, acc_out))
-        return q8t_wide_conv(0, desc, qx, px, qw, pw, y, acc_out, nullptr, ws, (hipStream_t)stream);
+        return q8t_wide_conv(0, desc, qx, px, qw, pw, y, acc_out, nullptr, ws, (hipStream_t)stream, packed_wide(packed, desc, 0));
     if (q8t_fast_conv_supported(0, desc, qx, qw, y, acc_out))
-        return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, nullptr, ws, (hipStream_t)stream);
+        return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, nullptr, ws, (hipStream_t)stream, nullptr,
+                             packed_tile64(packed, desc, 0));
     if (q8t_nhwc_conv_supported(0, desc))
         return q8t_nhwc_conv(0, desc, qx, px, qw, pw, y, acc_out, nullptr, nullptr, ws, (hipStream_t)stream);
     if (q8t_first_conv_supported(desc, qx, y, acc_out))
         return q8t_first_conv(desc, qx, px, qw, pw, y, acc_out, nullptr, nullptr, ws, (hipStream_t)stream);
     if (smallc_wanted(0, desc)) return q8t_smallc_conv(desc, qx, px, qw, pw, y, acc_out, nullptr, nullptr, ws, (hipStream_t)stream);
     return q8t_generic_conv(0, desc, qx, px, qw, pw, y, acc_out, ws, (hipStream_t)stream);
+}
+
+int q8t_qconv_fwd(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams *px, const int8_t *qw,
+                  const q8t_qparams *pw, float *y, int32_t *acc_out, void *ws, void *stream)
+{
+    return qconv_fwd_impl(desc, qx, px, qw, pw, y, acc_out, ws, stream, nullptr);
 }
 
 size_t q8t_qconv_fwd_bn_stats_workspace_size(const q8t_conv_desc *desc)
@@ -163,8 +198,9 @@ size_t q8t_qconv_fwd_bn_stats_workspace_size(const q8t_conv_desc *desc)
     return c + s;
 }
 
-int q8t_qconv_fwd_bn_stats(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams *px, const int8_t *qw,
-                           const q8t_qparams *pw, float *y, int32_t *acc_out, float *stats_out, void *ws, void *stream)
+static int qconv_fwd_bn_stats_impl(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams *px, const int8_t *qw,
+                                   const q8t_qparams *pw, float *y, int32_t *acc_out, float *stats_out, void *ws, void *stream,
+                                   const void *packed)
 {
     if (!desc || !qx || !px || !qw || !pw || !y || !stats_out) return Q8T_ERR_NULL;
     const int rc = q8t_conv_reduction_check(0, desc);
@@ -177,15 +213,17 @@ int q8t_qconv_fwd_bn_stats(const q8t_conv_desc *desc, const int8_t *qx, const q8
         if (q8t_fast_conv_supported(0, &sub, codes, qw, y, acc_out)) {
             const int rs = q8t_subsample_codes(qx, desc->N, desc->C, desc->H, desc->W, desc->stride, codes, (hipStream_t)stream);
             if (rs) return rs;
-            return q8t_fast_conv(0, &sub, codes, px, qw, pw, y, acc_out, stats_out, ws2, (hipStream_t)stream);
+            return q8t_fast_conv(0, &sub, codes, px, qw, pw, y, acc_out, stats_out, ws2, (hipStream_t)stream, nullptr,
+                                 packed_tile64(packed, desc, 0));
         }
     }
     // the specialised kernel gathers the statistics in its epilogue; other shapes run the product
     // and then the statistics pass of the Range BN over its result
     if (q8t_wide_conv_supported(0, desc, qx, y, acc_out))
-        return q8t_wide_conv(0, desc, qx, px, qw, pw, y, acc_out, stats_out, ws, (hipStream_t)stream);
+        return q8t_wide_conv(0, desc, qx, px, qw, pw, y, acc_out, stats_out, ws, (hipStream_t)stream, packed_wide(packed, desc, 0));
     if (q8t_fast_conv_supported(0, desc, qx, qw, y, acc_out))
-        return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, stats_out, ws, (hipStream_t)stream);
+        return q8t_fast_conv(0, desc, qx, px, qw, pw, y, acc_out, stats_out, ws, (hipStream_t)stream, nullptr,
+                             packed_tile64(packed, desc, 0));
     void *sws = (char *)ws + ((q8t_qconv_workspace_size(desc, 0) + 255) & ~(size_t)255);
     if (q8t_nhwc_conv_supported(0, desc))
         return q8t_nhwc_conv(0, desc, qx, px, qw, pw, y, acc_out, stats_out, sws, ws, (hipStream_t)stream);
@@ -193,30 +231,44 @@ int q8t_qconv_fwd_bn_stats(const q8t_conv_desc *desc, const int8_t *qx, const q8
         return q8t_first_conv(desc, qx, px, qw, pw, y, acc_out, stats_out, sws, ws, (hipStream_t)stream);
     if (smallc_wanted(0, desc) && q8t_smallc_conv_stats_ws(desc))
         return q8t_smallc_conv(desc, qx, px, qw, pw, y, acc_out, stats_out, sws, ws, (hipStream_t)stream);
-    const int rc2 = q8t_qconv_fwd(desc, qx, px, qw, pw, y, acc_out, ws, stream);
+    const int rc2 = qconv_fwd_impl(desc, qx, px, qw, pw, y, acc_out, ws, stream, packed);
     if (rc2) return rc2;
     const int P = (desc->H + 2 * desc->pad - desc->R) / desc->stride + 1, Q = (desc->W + 2 * desc->pad - desc->S) / desc->stride + 1;
     void *bnws = (char *)ws + ((q8t_qconv_workspace_size(desc, 0) + 255) & ~(size_t)255);
     return q8t_range_bn_stats(y, desc->N, desc->K, P, Q, stats_out, bnws, (hipStream_t)stream);
 }
 
-int q8t_qconv_dgrad(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qparams *pg, const int8_t *qw,
-                    const q8t_qparams *pw, float *dx, int32_t *acc_out, void *ws, void *stream)
+int q8t_qconv_fwd_bn_stats(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams *px, const int8_t *qw,
+                           const q8t_qparams *pw, float *y, int32_t *acc_out, float *stats_out, void *ws, void *stream)
+{
+    return qconv_fwd_bn_stats_impl(desc, qx, px, qw, pw, y, acc_out, stats_out, ws, stream, nullptr);
+}
+
+static int qconv_dgrad_impl(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qparams *pg, const int8_t *qw,
+                            const q8t_qparams *pw, float *dx, int32_t *acc_out, void *ws, void *stream, const void *packed)
 {
     if (!desc || !qdy || !pg || !qw || !pw || (!dx && !acc_out)) return Q8T_ERR_NULL;
     const int rc = q8t_conv_reduction_check(1, desc);
     if (rc) return rc;
     if (q8t_wide_conv_supported(1, desc, qdy, dx, acc_out))
-        return q8t_wide_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, nullptr, ws, (hipStream_t)stream);
+        return q8t_wide_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, nullptr, ws, (hipStream_t)stream, packed_wide(packed, desc, 1));
     if (q8t_fast_conv_supported(1, desc, qdy, qw, dx, acc_out))
-        return q8t_fast_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, nullptr, ws, (hipStream_t)stream);
+        return q8t_fast_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, nullptr, ws, (hipStream_t)stream, nullptr,
+                             packed_tile64(packed, desc, 1));
     if (q8t_nhwc_conv_supported(1, desc))
         return q8t_nhwc_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, nullptr, nullptr, ws, (hipStream_t)stream);
     return q8t_generic_conv(1, desc, qdy, pg, qw, pw, dx, acc_out, ws, (hipStream_t)stream);
 }
 
-int q8t_qconv_dgrad_relu_sum(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qparams *pg, const int8_t *qw,
-                             const q8t_qparams *pw, const float *other, const float *act, float *dx, void *ws, void *stream)
+int q8t_qconv_dgrad(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qparams *pg, const int8_t *qw,
+                    const q8t_qparams *pw, float *dx, int32_t *acc_out, void *ws, void *stream)
+{
+    return qconv_dgrad_impl(desc, qdy, pg, qw, pw, dx, acc_out, ws, stream, nullptr);
+}
+
+static int qconv_dgrad_relu_sum_impl(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qparams *pg, const int8_t *qw,
+                                     const q8t_qparams *pw, const float *other, const float *act, float *dx, void *ws,
+                                     void *stream, const void *packed)
 {
     if (!desc || !qdy || !pg || !qw || !pw || !act || !dx) return Q8T_ERR_NULL;
     const int rc = q8t_conv_reduction_check(1, desc);
@@ -229,10 +281,69 @@ int q8t_qconv_dgrad_relu_sum(const q8t_conv_desc *desc, const int8_t *qdy, const
     // write-out more than the separate pass does, so those shapes, like every other one, run the product and then
     // the plumbing pass in place.
     if (al && !q8t_wide_conv_supported(1, desc, qdy, dx, nullptr) && q8t_fast_conv_supported(1, desc, qdy, qw, dx, nullptr))
-        return q8t_fast_conv(1, desc, qdy, pg, qw, pw, dx, nullptr, nullptr, ws, st, &rs);
-    const int r2 = q8t_qconv_dgrad(desc, qdy, pg, qw, pw, dx, nullptr, ws, stream);
+        return q8t_fast_conv(1, desc, qdy, pg, qw, pw, dx, nullptr, nullptr, ws, st, &rs, packed_tile64(packed, desc, 1));
+    const int r2 = qconv_dgrad_impl(desc, qdy, pg, qw, pw, dx, nullptr, ws, stream, packed);
     if (r2) return r2;
     return q8t_relu_bwd_sum(dx, other, act, (int64_t)desc->N * desc->C * desc->H * desc->W, dx, stream);
+}
+
+int q8t_qconv_dgrad_relu_sum(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qparams *pg, const int8_t *qw,
+                             const q8t_qparams *pw, const float *other, const float *act, float *dx, void *ws, void *stream)
+{
+    return qconv_dgrad_relu_sum_impl(desc, qdy, pg, qw, pw, other, act, dx, ws, stream, nullptr);
+}
+
+// ---- filters packed ahead of the products ----
+size_t q8t_qconv_pack_size(const q8t_conv_desc *desc, int which)
+{
+    return pack_layout(desc, which) == Q8T_PACK_NONE ? 0 : q8t_pack_bytes(which, desc);
+}
+
+int q8t_qconv_pack_multi(int n, const q8t_conv_desc *descs, const int *which, const int8_t *const *qw, void *const *packed,
+                         void *stream)
+{
+    if (n < 0 || (n > 0 && (!descs || !which || !qw || !packed))) return Q8T_ERR_NULL;
+    std::vector<Q8tPackJob> jobs;
+    jobs.reserve((size_t)n);
+    for (int i = 0; i < n; ++i) {
+        const int lay = pack_layout(&descs[i], which[i]);
+        if (lay == Q8T_PACK_NONE || !packed[i]) continue;   // nothing to pack ahead for this product
+        if (!qw[i]) return Q8T_ERR_NULL;
+        if (!q8t_aligned(packed[i], 16)) return Q8T_ERR_WORKSPACE;
+        Q8tPackJob j;
+        j.w = qw[i];
+        j.out = (int8_t *)packed[i];
+        j.colsum = (int *)((char *)packed[i] + q8t_pack_colsum_offset(&descs[i]));
+        j.Kf = descs[i].K;
+        j.Cf = descs[i].C;
+        j.R = descs[i].R;
+        j.S = descs[i].S;
+        j.dgrad = which[i];
+        j.layout = lay;
+        j.first_block = 0;
+        jobs.push_back(j);
+    }
+    return q8t_pack_launch(jobs.data(), (int)jobs.size(), (hipStream_t)stream);
+}
+
+int q8t_qconv_fwd_bn_stats_packed(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams *px, const int8_t *qw,
+                                  const q8t_qparams *pw, const void *packed, float *y, int32_t *acc_out, float *stats_out,
+                                  void *ws, void *stream)
+{
+    return qconv_fwd_bn_stats_impl(desc, qx, px, qw, pw, y, acc_out, stats_out, ws, stream, packed);
+}
+
+int q8t_qconv_dgrad_packed(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qparams *pg, const int8_t *qw,
+                           const q8t_qparams *pw, const void *packed, float *dx, int32_t *acc_out, void *ws, void *stream)
+{
+    return qconv_dgrad_impl(desc, qdy, pg, qw, pw, dx, acc_out, ws, stream, packed);
+}
+
+int q8t_qconv_dgrad_relu_sum_packed(const q8t_conv_desc *desc, const int8_t *qdy, const q8t_qparams *pg, const int8_t *qw,
+                                    const q8t_qparams *pw, const void *packed, const float *other, const float *act, float *dx,
+                                    void *ws, void *stream)
+{
+    return qconv_dgrad_relu_sum_impl(desc, qdy, pg, qw, pw, other, act, dx, ws, stream, packed);
 }
 
 int q8t_qconv_wgrad(const q8t_conv_desc *desc, const int8_t *qx, const q8t_qparams *px, const int16_t *qdy16,

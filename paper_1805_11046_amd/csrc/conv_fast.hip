@@ -27,6 +27,7 @@
 
 #include "q8t_common.h"
 #include "q8t_internal.h"
+#include "repack.h"
 
 namespace {
 
@@ -75,36 +76,13 @@ __device__ __forceinline__ uint32_t divc(uint32_t n, const FastDiv fd)
     return fdiv(n, fd);
 }
 
-// ---- weight pre-pass: repack + per-output-channel sums -----------------------------------------
-// out[(oc/64)][cc][tap][oc%64][ch%64] = W'(oc, ch, tap);  forward: W'(oc,ch,r,s) = W[oc][ch][r][s];
-// layer gradient: W'(oc,ch,r,s) = W[ch][oc][R-1-r][S-1-s]  (oc = input channel of the layer).
-constexpr int kRepackThreads = 256;
+// ---- weight pre-pass: repack + per-output-channel sums (layout and body: repack.h) --------------
 __global__ __launch_bounds__(kRepackThreads) void repack_weights(const int8_t *__restrict__ w, int Kf, int Cf, int R,
                                                            int S, int dgrad, int8_t *__restrict__ out,
                                                            int *__restrict__ colsum)
 {
     __shared__ int red[kRepackThreads / 64];
-    const int OC = dgrad ? Cf : Kf, CHN = dgrad ? Kf : Cf;
-    const int oc = blockIdx.x;
-    const int taps = R * S, CC = CHN / CH;
-    int sum = 0;
-    for (int e = threadIdx.x; e < taps * CHN; e += kRepackThreads) {
-        const int tap = e / CHN, ch = e - tap * CHN;
-        const int r = tap / S, s = tap - r * S;
-        int v;
-        if (!dgrad)
-            v = w[(((int64_t)oc * Cf + ch) * R + r) * S + s];
-        else
-            v = w[(((int64_t)ch * Cf + oc) * R + (R - 1 - r)) * S + (S - 1 - s)];
-        sum += v;
-        const int64_t o = ((((int64_t)(oc / CH) * CC + ch / CH) * taps + tap) * CH + (oc % CH)) * CH + (ch % CH);
-        out[o] = (int8_t)v;
-    }
-    sum = wave_reduce(sum, [](int a, int b) { return a + b; });
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sum;
-    __syncthreads();
-    if (threadIdx.x == 0) colsum[oc] = red[0] + red[1] + red[2] + red[3];
-    (void)OC;
+    q8t_repack_tile64(w, Kf, Cf, R, S, dgrad, out, colsum, (int)blockIdx.x, red);
 }
 
 // 4x4 byte transpose: in[j] = 4 consecutive positions of channel j; out[i] = 4 channels of position i
@@ -632,9 +610,10 @@ int launch_conv(dim3 grid, hipStream_t st, const int8_t *a, const int8_t *wpk, c
 
 int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
                   const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *ws, hipStream_t st,
-                  const Q8tReluSum *relu_sum)
+                  const Q8tReluSum *relu_sum, const void *packed)
 {
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    if (packed && !q8t_aligned(packed, 16)) return Q8T_ERR_WORKSPACE;
     Q8tReluSum fuse = {nullptr, nullptr};
     if (relu_sum) {
         if (bn_stats || which != 1) return Q8T_ERR_SHAPE;
@@ -644,9 +623,11 @@ int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
     const int taps = d->R * d->S;
     const size_t wbytes = (size_t)d->K * d->C * taps;
     const int oc_all = which == 0 ? d->K : d->C;
-    int8_t *wpk = (int8_t *)ws;
-    int *colsum = (int *)((char *)ws + ((wbytes + 255) & ~(size_t)255));
-    ConvStat *bnpart = bn_stats ? (ConvStat *)((char *)colsum + (((size_t)oc_all * sizeof(int) + 255) & ~(size_t)255))
+    // the packed filter and its column sums: made here in the workspace, or handed in (q8t_qconv_pack_multi)
+    int8_t *wpk = packed ? (int8_t *)packed : (int8_t *)ws;
+    int *colsum = (int *)((char *)wpk + ((wbytes + 255) & ~(size_t)255));
+    ConvStat *bnpart = bn_stats ? (ConvStat *)((char *)ws + ((wbytes + 255) & ~(size_t)255) +
+                                               (((size_t)oc_all * sizeof(int) + 255) & ~(size_t)255))
                                 : (ConvStat *)nullptr;
     int rc = 0;
     FastGeom g;
@@ -662,9 +643,11 @@ int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qp
     g.dW = mkdiv(g.W);
     g.dW1 = mkdiv(W1);
     g.dIMG = mkdiv(taps == 9 ? (d->H + 1) * W1 : g.PQ);
-    hipLaunchKernelGGL(repack_weights, dim3(g.K), dim3(kRepackThreads), 0, st, (const int8_t *)b, d->K, d->C, d->R, d->S,
-                       which, wpk, colsum);
-    Q8T_LAUNCH_CHECK();
+    if (!packed) {
+        hipLaunchKernelGGL(repack_weights, dim3(g.K), dim3(kRepackThreads), 0, st, (const int8_t *)b, d->K, d->C, d->R, d->S,
+                           which, wpk, colsum);
+        Q8T_LAUNCH_CHECK();
+    }
     Sched sch;
     const int occs = g.K / CH;
     int nbx = 512 / occs;                       // two workgroups (16 wavefronts) per compute unit in total

@@ -25,6 +25,7 @@
 
 #include "q8t_common.h"
 #include "q8t_internal.h"
+#include "repack.h"
 
 namespace {
 
@@ -52,47 +53,12 @@ struct WideGeom {
     int last_dword;      // index of the last aligned dword of the operand
 };
 
-// Packed filter, BN = 256 or 128 columns per workgroup: block (oc / BN, chunk, tap) of BN x 64 bytes =
-// [32-column tile = oc % BN / 32 (a wavefront owns BN / 128 consecutive ones)][K half = ch % 64 / 32]
-// [lane = (ch % 32 / 16) * 32 + oc % 32][16 bytes = ch % 16]: every MFMA operand of a wavefront is one 16-byte
-// load per lane, 1 KB contiguous per instruction.  forward: W'(oc,ch,r,s) =
-// W[oc][ch][r][s]; layer gradient: W'(oc,ch,r,s) = W[ch][oc][2-r][2-s] (oc = input channel of the layer);
-// colsum[oc] = sum of W'(oc,.,.)
-constexpr int kRepackThreads = 256;
+// Packed filter (layout and body: repack.h, q8t_repack_wide)
 __global__ __launch_bounds__(kRepackThreads) void repack_wide(const int8_t *__restrict__ w, int Kf, int Cf, int dgrad, int BN,
                                                               int8_t *__restrict__ out, int *__restrict__ colsum)
 {
     __shared__ int red[kRepackThreads / 64];
-    const int CHN = dgrad ? Kf : Cf;
-    const int oc = blockIdx.x, CC = CHN / CH;
-    const int o256 = oc % BN, WN = BN / 4;   // columns of one wavefront: 64 or 32
-    int sum = 0;
-    // a thread gathers the 16 reduction channels of one (tap, 16-channel group) and writes them as one piece
-    for (int e = threadIdx.x; e < 9 * (CHN / 16); e += kRepackThreads) {
-        const int tap = e / (CHN / 16), c16 = e - tap * (CHN / 16);
-        const int r = tap / 3, t = tap - r * 3;
-        const int ch0 = c16 * 16, c64 = ch0 % CH;
-        uint32_t pk[4] = {0, 0, 0, 0};
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int ch = ch0 + i;
-            int v;
-            if (!dgrad)
-                v = w[(((int64_t)oc * Cf + ch) * 3 + r) * 3 + t];
-            else
-                v = w[(((int64_t)ch * Cf + oc) * 3 + (2 - r)) * 3 + (2 - t)];
-            sum += v;
-            pk[i >> 2] |= (uint32_t)(v & 255) << (8 * (i & 3));
-        }
-        const int64_t blk = ((int64_t)(oc / BN) * CC + ch0 / CH) * 9 + tap;
-        const int frag = (o256 / 32) * 2 + c64 / 32;   // (wavefront, column tile) = o256 / WN, (o256 % WN) / 32 in one index
-        *reinterpret_cast<uint4 *>(out + blk * (BN * CH) + frag * 1024 + (((c64 % 32) / 16) * 32 + oc % 32) * 16) =
-            make_uint4(pk[0], pk[1], pk[2], pk[3]);
-    }
-    sum = wave_reduce(sum, [](int a, int b) { return a + b; });
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = sum;
-    __syncthreads();
-    if (threadIdx.x == 0) colsum[oc] = red[0] + red[1] + red[2] + red[3];
+    q8t_repack_wide(w, Kf, Cf, dgrad, BN, out, colsum, (int)blockIdx.x, red);
 }
 
 // in[j] = 4 consecutive positions of channel j; out[i] = 4 channels of position i
@@ -550,6 +516,14 @@ bool q8t_wide_conv_supported(int which, const q8t_conv_desc *d, const void *a, c
     return q8t_aligned(a, 4) && q8t_aligned(out_f, 16) && q8t_aligned(out_acc, 16);
 }
 
+int q8t_wide_conv_pack_layout(int which, const q8t_conv_desc *d)
+{
+    WideGeom g;
+    if (!make_geom(which, d, &g)) return Q8T_PACK_NONE;
+    if (g.K % 256 != 0 && g.PQ % 4 == 0) return Q8T_PACK_NONE;   // as q8t_wide_conv_supported
+    return g.K % 256 == 0 ? Q8T_PACK_WIDE256 : Q8T_PACK_WIDE128;
+}
+
 size_t q8t_wide_conv_ws(int which, const q8t_conv_desc *d)
 {
     WideGeom g;
@@ -560,21 +534,27 @@ size_t q8t_wide_conv_ws(int which, const q8t_conv_desc *d)
 }
 
 int q8t_wide_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
-                  const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *ws, hipStream_t st)
+                  const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *ws, hipStream_t st,
+                  const void *packed)
 {
     WideGeom g;
     if (!make_geom(which, d, &g)) return Q8T_ERR_SHAPE;
     if (!ws || !q8t_aligned(ws, 16)) return Q8T_ERR_WORKSPACE;
+    if (packed && !q8t_aligned(packed, 16)) return Q8T_ERR_WORKSPACE;
     if (lds_bytes(g) > 96 * 1024) return Q8T_ERR_SHAPE;
     const size_t wbytes = (size_t)d->K * d->C * 9;
-    int8_t *wpk = (int8_t *)ws;
-    int *colsum = (int *)((char *)ws + ((wbytes + 255) & ~(size_t)255));
-    Q8tConvStat *bnpart = bn_stats ? (Q8tConvStat *)((char *)colsum + (((size_t)g.K * sizeof(int) + 255) & ~(size_t)255))
+    // the packed filter and its column sums: made here in the workspace, or handed in (q8t_qconv_pack_multi)
+    int8_t *wpk = packed ? (int8_t *)packed : (int8_t *)ws;
+    int *colsum = (int *)((char *)wpk + ((wbytes + 255) & ~(size_t)255));
+    Q8tConvStat *bnpart = bn_stats ? (Q8tConvStat *)((char *)ws + ((wbytes + 255) & ~(size_t)255) +
+                                                     (((size_t)g.K * sizeof(int) + 255) & ~(size_t)255))
                                    : (Q8tConvStat *)nullptr;
     const int ntw = g.K % 256 == 0 ? 2 : 1;
-    hipLaunchKernelGGL(repack_wide, dim3((unsigned)g.K), dim3(kRepackThreads), 0, st, (const int8_t *)b, d->K, d->C, which,
-                       128 * ntw, wpk, colsum);
-    Q8T_LAUNCH_CHECK();
+    if (!packed) {
+        hipLaunchKernelGGL(repack_wide, dim3((unsigned)g.K), dim3(kRepackThreads), 0, st, (const int8_t *)b, d->K, d->C, which,
+                           128 * ntw, wpk, colsum);
+        Q8T_LAUNCH_CHECK();
+    }
     const int8_t *pa = (const int8_t *)a;
     int32_t *pacc = (int32_t *)out_acc;
     const bool al = g.PQ % 4 == 0;

@@ -36,14 +36,19 @@ size_t q8t_fast_conv_ws(int which, const q8t_conv_desc *d);
 // (relu_sum.h); act and other 16-byte aligned
 int q8t_fast_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
                   const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *ws, hipStream_t st,
-                  const Q8tReluSum *relu_sum = nullptr);
+                  const Q8tReluSum *relu_sum = nullptr, const void *packed = nullptr);
+// packed (nullable, both kernels): the filter already in the kernel's layout with its column sums (repack.h); the
+// pre-pass is skipped and that part of the workspace stays unused
 
 // 3x3 stride-1 layers with many channels on small planes: 128 x 256 tiles, activations staged once per
 // 64-channel chunk, weights streamed (conv_wide.hip).  Same contract as q8t_fast_conv.
 bool q8t_wide_conv_supported(int which, const q8t_conv_desc *d, const void *a, const void *out_f, const void *out_acc);
 size_t q8t_wide_conv_ws(int which, const q8t_conv_desc *d);
 int q8t_wide_conv(int which, const q8t_conv_desc *d, const void *a, const q8t_qparams *qa, const void *b,
-                  const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *ws, hipStream_t st);
+                  const q8t_qparams *qb, float *out_f, void *out_acc, float *bn_stats, void *ws, hipStream_t st,
+                  const void *packed = nullptr);
+// Q8T_PACK_* layout the wide-tile kernel takes for this product, by shape alone (Q8T_PACK_NONE: not its shape)
+int q8t_wide_conv_pack_layout(int which, const q8t_conv_desc *d);
 
 // Range BN statistics of an NCHW tensor alone (range_bn.hip); ws as for q8t_range_bn_fwd
 int q8t_range_bn_stats(const float *x, int N, int C, int H, int W, float *stats_out, void *ws, hipStream_t st);

@@ -73,6 +73,17 @@ def _angle(kind, t, q, qp):
 
 
 _qcache = {}   # data_ptr of an activation -> (codes, parameters) left behind by the kernel that wrote it
+_pcache = {}   # (data_ptr of a layer's weight codes, 0 forward / 1 layer gradient) -> its packed filter for this step
+_pbufs = {}    # the same keys by weight tensor: buffers kept from step to step
+# Pack all filters in one launch after the weights are quantized (off: every product packs its own, a small launch in
+# front of each).  Off: in a warmed process the step gains 0.06 ms of 8.5 with it, but the first process on a fresh
+# machine measured 0.6 - 1.5 ms slower in every trial, with unchanged per-call times; until that is understood the
+# step keeps the per-call pre-pass.  tests/test_gpu_train_step.py runs both ways.
+_pack = False
+
+
+def _packed(qw, which):
+    return _pcache.get((qw.data_ptr(), which))
 
 
 def _quantize(name, t):
@@ -156,7 +167,8 @@ def _convbn_fwd(a, w, stride, pad, apply=True):
     qw, pw = _quantize("quantize (weights)", w)
     ops = 2.0 * n * d.P * d.Q * k * c * r * s
     nx, ny = a.numel(), n * k * d.P * d.Q
-    y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw, tag=_tag(d))
+    y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw, tag=_tag(d),
+                        packed=_packed(qw, 0))
     saved = (d, qa, pa, qw, pw, y, stats, ops, nx, ny, _next_layer())
     if not apply:
         return (y, stats), saved
@@ -174,9 +186,10 @@ def _convbn_bwd(saved, dbn, need_dx, lattice=False):
     dx = None
     if need_dx and lattice:
         ds = q8t.conv_desc(d.N, d.C, d.P, d.Q, d.K, 1, 1, 1, 0)
-        dx, _ = _call("qconv_dgrad", ops, ny + 4 * (nx // (d.stride * d.stride)), q8t.qconv_dgrad, ds, g8, pg8, qw, pw, tag=_tag(d))
+        dx, _ = _call("qconv_dgrad", ops, ny + 4 * (nx // (d.stride * d.stride)), q8t.qconv_dgrad, ds, g8, pg8, qw, pw, tag=_tag(d),
+                      packed=_packed(qw, 1))
     elif need_dx:
-        dx, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d))
+        dx, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d), packed=_packed(qw, 1))
     dw = _wgrad(d, qa, pa, g16, pg16, ops, nx, ny)
     return dx, dw
 
@@ -251,7 +264,8 @@ def _chain_fwd(a, specs, ws, apply_last=True):
         qw, pw = _quantize("quantize (weights)", w)
         ops = 2.0 * n * d.P * d.Q * k * c * r * s
         nx, ny = n * c * h * wd, n * k * d.P * d.Q
-        y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw, tag=_tag(d))
+        y, _, stats = _call("qconv_fwd_bn_stats", ops, nx + 4 * ny, q8t.qconv_fwd_bn_stats, d, qa, pa, qw, pw, tag=_tag(d),
+                            packed=_packed(qw, 0))
         saved.append((d, qa, pa, qw, pw, y, stats, ops, nx, ny, _next_layer()))
         if i + 1 < len(ws):
             _, qa, pa = _call("range_bn_relu_fwd_apply (int8 out)", 0, 5 * ny, q8t.range_bn_relu_fwd_apply, y, stats,
@@ -283,9 +297,9 @@ def _chain_bwd(saved, g, need_dx, block_end=None):
         if i == 0 and block_end is not None:
             other, act = block_end
             g = _call("qconv_dgrad", ops, ny + (12 if other is not None else 8) * nx, q8t.qconv_dgrad_relu_sum, d, g8, pg8,
-                      qw, pw, other, act, tag=_tag(d))
+                      qw, pw, other, act, tag=_tag(d), packed=_packed(qw, 1))
         elif i > 0 or need_dx:
-            g, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d))
+            g, _ = _call("qconv_dgrad", ops, ny + 4 * nx, q8t.qconv_dgrad, d, g8, pg8, qw, pw, tag=_tag(d), packed=_packed(qw, 1))
         dws[i] = _wgrad(d, qa, pa, g16, pg16, ops, nx, ny)
     return g, dws
 
@@ -409,11 +423,47 @@ def _quantize_weights(tensors):
         _qcache[t.data_ptr()] = (q, qp)
 
 
+def _pack_filters(x, ws):
+    """The filters of every convolution of the network, in the layouts its forward and layer-gradient kernels read,
+    by one launch (the products then skip their own small pre-pass)."""
+    n = x.shape[0]
+    h = (x.shape[2] + 2 * 3 - 7) // 2 + 1      # first layer 7x7 / 2, pad 3
+    h = (h + 2 * 1 - 3) // 2 + 1               # pooling 3x3 / 2, pad 1
+    jobs, keys = [], []
+
+    def add(w, d, which):
+        qw, _ = _quantize("quantize (weights)", w)
+        jobs.append((d, which, qw))
+        keys.append(((w.data_ptr(), which), (qw.data_ptr(), which)))
+
+    for (cin, cout, stride), b in zip(STAGES, ws["blocks"]):
+        h2 = (h + 2 - 3) // stride + 1
+        d1 = q8t.conv_desc(n, cin, h, h, cout, 3, 3, stride, 1)
+        d2 = q8t.conv_desc(n, cout, h2, h2, cout, 3, 3, 1, 1)
+        for w, d in ((b["c1"], d1), (b["c2"], d2)):
+            add(w, d, 0)
+            add(w, d, 1)
+        if "sc" in b:
+            add(b["sc"], q8t.conv_desc(n, cin, h, h, cout, 1, 1, stride, 0), 0)
+            # its layer gradient runs as the stride-1 product on the positions the layer read (_convbn_bwd)
+            add(b["sc"], q8t.conv_desc(n, cin, h2, h2, cout, 1, 1, 1, 0), 1)
+        h = h2
+    nbytes = 2 * sum(j[2].numel() for j in jobs)
+    bufs = _call("qconv_pack_multi", 0, nbytes, q8t.qconv_pack_multi, jobs, [_pbufs.get(k[0]) for k in keys])
+    for (kw, kq), b in zip(keys, bufs):
+        if b is not None:
+            _pbufs[kw] = b
+            _pcache[kq] = b
+
+
 def step(x, labels, ws):
     _qcache.clear()
+    _pcache.clear()
     _layer[0] = 0
     if _fuse:
         _quantize_weights([ws["conv1"], ws["fc"]] + [w for b in ws["blocks"] for w in b.values()])
+        if _pack:
+            _pack_filters(x, ws)
     if _fuse:
         a = StemConvBNPool.apply(x, ws["conv1"], 2, 3)
     else:

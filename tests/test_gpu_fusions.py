@@ -188,3 +188,50 @@ def test_layer_gradient_with_the_end_of_the_block_in_its_epilogue(case, with_oth
     ores = oracle.relu_bwd_sum(odx, other, act)
     close(host(dx), ores)
     same_ints(host(dx) == 0, ores == 0)
+
+
+PACK_CASES = [
+    (3, 256, 14, 14, 256, 3, 3, 1, 1),   # wide tiles, 256 columns, both products
+    (5, 256, 7, 7, 512, 3, 3, 1, 1),     # ... forward 512 -> two column tiles; layer gradient 256 columns
+    (7, 128, 7, 7, 128, 3, 3, 1, 1),     # wide tiles, 128 columns
+    (2, 64, 56, 56, 64, 3, 3, 1, 1),     # 64-column register tiles
+    (2, 64, 28, 28, 128, 1, 1, 1, 0),    # ... 1x1
+    (3, 64, 28, 28, 128, 1, 1, 2, 0),    # 1x1 at stride 2: forward on the gathered positions; layer gradient packs nothing
+    (2, 64, 16, 16, 128, 3, 3, 2, 1),    # strided 3x3: nothing to pack ahead
+    (2, 3, 32, 32, 64, 7, 7, 2, 3),      # first layer: nothing to pack ahead
+]
+
+
+def test_products_with_filters_packed_ahead():
+    # every filter packed by ONE launch, then handed to the products: bit-identical to the calls that pack on their own
+    q8t = require_gpu()
+    g = synth.rng(77)
+    layers, jobs = [], []
+    for case in PACK_CASES:
+        N, C, H, W, K, R, S, st, pad = case
+        d = q8t.conv_desc(*case)
+        sx, px = _rand_q(g, (N, C, H, W))
+        sw, pw = _rand_q(g, (K, C, R, S))
+        sg, pg = _rand_q(g, (N, K, d.P, d.Q))
+        ops = dict(d=d, qx=dev(sx), px=qp_dev_from(px), qw=dev(sw), pw=qp_dev_from(pw), qg=dev(sg), pg=qp_dev_from(pg),
+                   other=dev(synth.normal(g, (N, C, H, W), std=1.0)),
+                   act=dev(np.maximum(synth.normal(g, (N, C, H, W), std=1.0), 0).astype(np.float32)))
+        layers.append(ops)
+        jobs.append((d, 0, ops["qw"]))
+        jobs.append((d, 1, ops["qw"]))
+    packed = q8t.qconv_pack_multi(jobs)
+    sizes = [q8t.qconv_pack_size(j[0], j[1]) for j in jobs]
+    assert [b is None for b in packed] == [s == 0 for s in sizes]
+    assert sizes[0] > 0 and sizes[1] > 0 and sizes[6] > 0 and sizes[10] > 0     # wide, register tile, gathered 1x1
+    assert sizes[11] == 0 and sizes[12] == 0 and sizes[13] == 0 and sizes[14] == 0 and sizes[15] == 0
+    for i, o in enumerate(layers):
+        pf, pd = packed[2 * i], packed[2 * i + 1]
+        y0, a0, s0 = q8t.qconv_fwd_bn_stats(o["d"], o["qx"], o["px"], o["qw"], o["pw"], want_acc=True)
+        y1, a1, s1 = q8t.qconv_fwd_bn_stats(o["d"], o["qx"], o["px"], o["qw"], o["pw"], want_acc=True, packed=pf)
+        assert np.array_equal(host(a0), host(a1)) and np.array_equal(host(y0), host(y1)) and np.array_equal(host(s0), host(s1))
+        dx0, c0 = q8t.qconv_dgrad(o["d"], o["qg"], o["pg"], o["qw"], o["pw"], want_acc=True)
+        dx1, c1 = q8t.qconv_dgrad(o["d"], o["qg"], o["pg"], o["qw"], o["pw"], want_acc=True, packed=pd)
+        assert np.array_equal(host(c0), host(c1)) and np.array_equal(host(dx0), host(dx1))
+        r0 = q8t.qconv_dgrad_relu_sum(o["d"], o["qg"], o["pg"], o["qw"], o["pw"], o["other"], o["act"])
+        r1 = q8t.qconv_dgrad_relu_sum(o["d"], o["qg"], o["pg"], o["qw"], o["pw"], o["other"], o["act"], packed=pd)
+        assert np.array_equal(host(r0).view(np.int32), host(r1).view(np.int32))

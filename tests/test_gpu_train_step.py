@@ -91,3 +91,36 @@ def test_weight_gradients_on_a_second_stream_change_nothing():
         assert lo == results[0][0]
         for i, (a, b) in enumerate(zip(results[0][1], go)):
             assert torch.equal(a, b), "gradient of parameter %d differs" % i
+
+
+def test_filters_packed_in_one_launch_change_nothing():
+    # the step with every filter packed ahead by one launch against the step whose products pack their own
+    require_gpu()
+    import torch
+    from paper_1805_11046_amd import train_step as ts
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(11)
+    ws = ts.make_weights(dev, gen)
+    x = torch.randn((4, 3, 224, 224), device=dev, generator=gen)
+    labels = torch.randint(0, 1000, (4,), device=dev, generator=gen)
+    params = [ws["conv1"], ws["fc"]] + [w for b in ws["blocks"] for w in b.values()]
+    results = []
+    try:
+        for pack in (False, True, True):
+            ts._pack = pack
+            for p in params:
+                p.grad = None
+            loss = ts.step(x, labels, ws)
+            torch.cuda.synchronize()
+            results.append((float(loss.detach()), [p.grad.clone() for p in params]))
+            if pack:
+                assert len(ts._pcache) >= 30      # most layers have a packed form in both directions
+            else:
+                assert len(ts._pcache) == 0
+    finally:
+        ts._pack = False
+    for lo, go in results[1:]:
+        assert lo == results[0][0]
+        for i, (a, b) in enumerate(zip(results[0][1], go)):
+            assert torch.equal(a, b), "gradient of parameter %d differs" % i
