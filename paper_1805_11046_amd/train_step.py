@@ -41,7 +41,8 @@ def _call(name, ops, nbytes, fn, *a, tag="", **k):
     `name` (and `tag`, the layer it belongs to)."""
     if not (_breakdown or _bracket == name):
         return fn(*a, **k)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0 = _evpool.pop() if _evpool else torch.cuda.Event(enable_timing=True)
+    e1 = _evpool.pop() if _evpool else torch.cuda.Event(enable_timing=True)
     e0.record()
     r = fn(*a, **k)
     e1.record()
@@ -59,6 +60,8 @@ def drain():
     """The (name, tag, ops, bytes, microseconds) records collected since the last drain (synchronizes)."""
     torch.cuda.synchronize()
     out = [(n, t, o, b, e0.elapsed_time(e1) * 1e3) for n, t, o, b, e0, e1 in _pending]
+    for rec in _pending:   # the events go back to the pool: creating a pair per call costs the host more than recording it
+        _evpool.extend(rec[4:6])
     del _pending[:]
     return out
 
@@ -76,9 +79,9 @@ _qcache = {}   # data_ptr of an activation -> (codes, parameters) left behind by
 _pcache = {}   # (data_ptr of a layer's weight codes, 0 forward / 1 layer gradient) -> its packed filter for this step
 _pbufs = {}    # the same keys by weight tensor: buffers kept from step to step
 # Pack all filters in one launch after the weights are quantized (off: every product packs its own, a small launch in
-# front of each).  Off: in a warmed process the step gains 0.06 ms of 8.5 with it, but the first process on a fresh
-# machine measured 0.6 - 1.5 ms slower in every trial, with unchanged per-call times; until that is understood the
-# step keeps the per-call pre-pass.  tests/test_gpu_train_step.py runs both ways.
+# front of each).  Off: the best runs gain 0.06 ms of 8.5 with it, but the timed single-stream loop came out 0.3 - 1.5
+# ms slower in most trials (first processes on a fresh machine above all), with unchanged per-call times; until that is
+# understood the step keeps the per-call pre-pass.  tests/test_gpu_train_step.py runs both ways.
 _pack = False
 
 
@@ -148,6 +151,7 @@ def _join_side():
 
 
 _pending = []
+_evpool = []
 _layer = [0]   # layers are numbered in forward order; a layer's backward draws its two roundings with seeds 2 id + 1, + 2
 
 
