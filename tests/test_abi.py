@@ -69,3 +69,31 @@ def test_argument_errors_are_reported_before_any_launch():
     assert L.q8t_quantize_noalloc(None, 16, 8, 0, 0, None, None, None) == -1
     assert L.q8t_qgemm_fwd(None, None, None, None, 0, 1, 1, None, None, None, None) == -2
     assert L.q8t_range_bn_fwd(None, 1, 1, 1, 1, None, None, 0.0, None, None, None, None, None, None) == -2
+
+
+def test_packed_filter_sizes_follow_the_kernel_that_serves_the_shape():
+    # host logic of the packed filters: codes rounded up to 256 bytes + one column sum per output channel of the product,
+    # for the shapes the register-tile and wide-tile kernels take; nothing for the others
+    _lib_path()
+    from paper_1805_11046_amd import binding
+
+    def size(case, which):
+        return binding.qconv_pack_size(binding.conv_desc(*case), which)
+
+    def expect(case, which):
+        n, c, h, w, k, r, s, st, pad = case
+        up = lambda v: (v + 255) // 256 * 256
+        return up(k * c * r * s) + up(4 * (k if which == 0 else c))
+
+    for case in ((256, 256, 14, 14, 256, 3, 3, 1, 1), (256, 512, 7, 7, 512, 3, 3, 1, 1), (256, 64, 56, 56, 64, 3, 3, 1, 1),
+                 (8, 64, 28, 28, 128, 1, 1, 1, 0)):
+        for which in (0, 1):
+            assert size(case, which) == expect(case, which)
+    lattice = (256, 64, 56, 56, 128, 1, 1, 2, 0)       # forward on the gathered positions; its layer gradient packs nothing
+    assert size(lattice, 0) == expect(lattice, 0) and size(lattice, 1) == 0
+    for case in ((256, 64, 56, 56, 128, 3, 3, 2, 1), (256, 3, 224, 224, 64, 7, 7, 2, 3), (2, 3, 7, 6, 4, 3, 3, 1, 1)):
+        assert size(case, 0) == 0 and size(case, 1) == 0
+    assert size(lattice, 2) == 0                       # the weight gradient reads no filter
+    L = binding._lib
+    assert L.q8t_qconv_pack_multi(1, None, None, None, None, None) == -1
+    assert L.q8t_qconv_pack_multi(0, None, None, None, None, None) == 0
